@@ -1,0 +1,260 @@
+"""CPU oracle for relay-boundary KV compression: headwise attention-mass eviction
+followed by Orthogonal BackFill (OBF).
+
+THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, fp64 numpy restatement of the
+method, one (layer, KV head) at a time, written to be checked against the paper
+by eye.  Only tests, the smoke check and the benchmark's cpu_baseline leg may use
+it; the product path never does.  It shares no code with the HIP path.
+
+Every input value is taken as the exact real number its bf16 / fp32 bit pattern
+denotes; all arithmetic is float64; outputs are rounded once to the I/O dtype.
+
+Steps follow Sec. 4.3.2 (Eq. 1, TopK_B), Sec. 4.4 (Eq. 2-7), Alg. 2 and Alg. 3.
+Readings taken where the paper leaves a choice (each is listed in the design notes):
+  * Eq. 1's attention rows come from observation-window queries; the softmax is
+    over the N prompt keys only, scale 1/sqrt(d) (App. L setup), no mask; the
+    rows of all query heads that share a KV head are summed (GQA).
+  * TopK_B ties go to the lowest index; index lists are ascending (Sec. 3.1).
+  * orth() spans the numerical row space: singular values above
+    sigma_max * max(rows, d) * 2^-23 (Eq. 2 only bounds r by min(B, d)).
+  * rank(R) in k = min(pca_rank, rank R) uses the same rule.
+  * "||R||_F negligible" (footnote of Eq. 7): ||R||_F^2 <= 1e-6 ||V_del||_F^2.
+  * epsilon = 1e-12 exactly where Eq. 4 and Eq. 6 place it.
+Pinned by tests/test_oracle_pins.py (closed forms, brute force, invariants).
+Parity unpinned: absolute values on realistic caches (the paper prints no worked
+numeric example); those rest on invariants only.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+EPS = 1e-12                 # Eq. 4, Eq. 6, footnote of Eq. 7
+RANK_EPS = 2.0 ** -23       # single-precision epsilon, used on purpose in the rank rule
+RCR_SKIP = 1e-6             # reading of "||R||_F negligible"
+
+
+# ----------------------------------------------------------------------------- dtype
+def decode(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact float64 value of fp32 values or bf16 bit patterns (uint16)."""
+    if dtype == "f32":
+        return np.asarray(x, dtype=np.float32).astype(np.float64)
+    if dtype == "bf16":
+        bits = np.asarray(x, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+        return bits.view(np.float32).astype(np.float64)
+    raise ValueError(dtype)
+
+
+def round_to_io(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float64 to the I/O dtype: fp32 (RNE) or bf16 bits (RNE, via one fp32 rounding).
+
+    The device adds delta to V in fp32 and rounds that sum to bf16; the fp64 sum
+    rounded to fp32 first and then to bf16 follows the same two roundings.
+    """
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    if dtype == "f32":
+        return f
+    if dtype == "bf16":
+        u = f.view(np.uint32)
+        lsb = (u >> np.uint32(16)) & np.uint32(1)
+        return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------- Eq. 1
+def attention_mass(K: np.ndarray, Qrows: np.ndarray) -> np.ndarray:
+    """A_j = sum over window-query rows of softmax_j(q . k_j / sqrt(d))   (Eq. 1).
+
+    K [N, d] float64, Qrows [R, d] float64 (all window queries of all query heads
+    of the KV group).  Returns A [N] float64; sum(A) == R.
+    """
+    N, d = K.shape
+    if Qrows.shape[0] == 0 or N == 0:
+        return np.zeros(N, dtype=np.float64)
+    S = (Qrows @ K.T) / np.sqrt(float(d))
+    S = S - S.max(axis=1, keepdims=True)
+    P = np.exp(S)
+    P /= P.sum(axis=1, keepdims=True)
+    return P.sum(axis=0)
+
+
+# ----------------------------------------------------------------------------- TopK_B
+def select_topk(A: np.ndarray, budget: int) -> np.ndarray:
+    """Indices of the `budget` largest A_j, ties to the lowest index, ascending (Sec. 4.3.2)."""
+    N = A.shape[0]
+    b = int(min(max(budget, 0), N))
+    order = np.argsort(-A, kind="stable")      # stable: equal values keep index order
+    return np.sort(order[:b]).astype(np.int64)
+
+
+def complement(idx: np.ndarray, N: int) -> np.ndarray:
+    m = np.ones(N, dtype=bool)
+    m[idx] = False
+    return np.nonzero(m)[0]
+
+
+# ----------------------------------------------------------------------------- Eq. 2
+def numerical_rank(sigma: np.ndarray, rows: int, cols: int) -> int:
+    if sigma.size == 0 or sigma[0] <= 0.0:
+        return 0
+    return int(np.count_nonzero(sigma > sigma[0] * max(rows, cols) * RANK_EPS))
+
+
+def orth_rowspace(V_keep: np.ndarray):
+    """Q [d, r] with orthonormal columns spanning span(V_keep rows)   (Eq. 2).
+
+    Returns (Q, sigma) where sigma are V_keep's singular values.
+    """
+    B, d = V_keep.shape
+    if B == 0:
+        return np.zeros((d, 0)), np.zeros(0)
+    _, s, Vt = np.linalg.svd(V_keep, full_matrices=False)
+    r = numerical_rank(s, B, d)
+    return Vt[:r].T.copy(), s
+
+
+# ----------------------------------------------------------------------------- Eq. 3-7
+@dataclass
+class HeadDiag:
+    n_keep: int = 0
+    r_keep: int = 0              # dim span(V_keep)
+    k_used: int = 0              # residual principal directions used
+    skipped: int = 1             # 1: V* = V_keep (no injection)
+    a_keep: float = 0.0
+    a_del: float = 0.0
+    rcr: float = 0.0             # ||R||^2 / ||V_del||^2            (App. K.2)
+    pcr: float = 0.0
+    pc: float = 0.0              # projection cosine                 (App. K.2)
+    revr: float = 0.0            # residual explained variance ratio (App. K.2)
+    dr: float = 0.0              # demand ratio                      (App. K.2)
+    ivn: float = 0.0             # ||delta||                         (App. K.2)
+    gap: float = np.inf          # sigma_k / sigma_{k+1} of R (subspace conditioning)
+    keep_sigma_margin: float = np.inf   # min over sigma of |log10(sigma / rank threshold)|
+    res_sigma_margin: float = np.inf
+    delta: Optional[np.ndarray] = field(default=None, repr=False)
+
+
+def _margin(sigma: np.ndarray, rows: int, cols: int) -> float:
+    if sigma.size == 0 or sigma[0] <= 0:
+        return np.inf
+    thr = sigma[0] * max(rows, cols) * RANK_EPS
+    with np.errstate(divide="ignore"):
+        m = np.abs(np.log10(np.maximum(sigma, 1e-300) / thr))
+    return float(m.min())
+
+
+def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int):
+    """OBF for one head (Eq. 2-7, Alg. 3).  V [N, d] float64, A [N], idx ascending.
+
+    Returns (V_star [B, d] float64 before output rounding, HeadDiag).
+    """
+    N, d = V.shape
+    idx = np.asarray(idx, dtype=np.int64)
+    dele = complement(idx, N)
+    V_keep = V[idx]
+    diag = HeadDiag(n_keep=int(idx.size))
+    diag.a_keep = float(A[idx].sum())
+    diag.a_del = float(A[dele].sum())
+    diag.dr = diag.a_del / (diag.a_keep + EPS)
+    diag.delta = np.zeros(d)
+    if rank <= 0 or dele.size == 0 or idx.size == 0:
+        # rank 0 is the plain selector (App. G); empty P_del is skipped (Alg. 3)
+        return V_keep.copy(), diag
+
+    Q, s_keep = orth_rowspace(V_keep)                      # Eq. 2
+    diag.r_keep = Q.shape[1]
+    diag.keep_sigma_margin = _margin(s_keep, idx.size, d)
+    V_del = V[dele]
+    if diag.r_keep == d:
+        # retained span is all of R^d: the residual is identically zero
+        diag.pcr = 1.0
+        return V_keep.copy(), diag
+    V_par = (V_del @ Q) @ Q.T
+    R = V_del - V_par                                      # Eq. 3
+    vd2 = float((V_del * V_del).sum())
+    r2 = float((R * R).sum())
+    diag.rcr = r2 / (vd2 + EPS)
+    diag.pcr = float((V_par * V_par).sum()) / (vd2 + EPS)
+    sd, sp = V_del.sum(axis=0), V_par.sum(axis=0)
+    den = np.linalg.norm(sd) * np.linalg.norm(sp)
+    diag.pc = float(sd @ sp / den) if den > 0 else 0.0
+    if r2 <= RCR_SKIP * vd2:
+        return V_keep.copy(), diag
+
+    _, sR, VtR = np.linalg.svd(R, full_matrices=False)     # rows of VtR: right singular vectors
+    rankR = numerical_rank(sR, R.shape[0], d)
+    k = min(int(rank), rankR)
+    diag.res_sigma_margin = _margin(sR, R.shape[0], d)
+    if k == 0:
+        return V_keep.copy(), diag
+    C = VtR[:k]                                            # [k, d]
+    diag.k_used = k
+    diag.revr = float((sR[:k] ** 2).sum() / ((sR ** 2).sum() + EPS))
+    if k < sR.size and sR[k] > 0:
+        diag.gap = float(sR[k - 1] / sR[k])
+
+    w = A[dele] / (diag.a_del + EPS)                       # Eq. 4
+    rbar = w @ R
+    Delta = (rbar @ C.T) @ C                               # Eq. 5
+    delta = diag.a_del / (diag.a_keep + EPS) * Delta       # Eq. 6
+    diag.delta = delta
+    diag.ivn = float(np.linalg.norm(delta))
+    diag.skipped = 0
+    return V_keep + delta[None, :], diag                   # Eq. 7
+
+
+# ----------------------------------------------------------------------------- one head, whole relay
+@dataclass
+class HeadResult:
+    A: np.ndarray
+    idx: np.ndarray
+    K_keep: np.ndarray        # I/O dtype (bit copy of the selected rows)
+    V_out: np.ndarray         # I/O dtype (rounded V*)
+    V_star: np.ndarray        # float64 V* before rounding
+    diag: HeadDiag
+
+
+def compress_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, rank: int,
+                  dtype: str) -> HeadResult:
+    """score -> TopK_B -> gather -> OBF for one (layer, KV head).
+
+    K_io, V_io [N, d]; Q_io [group, window, d] (or [rows, d]); all in the I/O dtype.
+    """
+    K = decode(K_io, dtype)
+    V = decode(V_io, dtype)
+    Qr = decode(Q_io, dtype).reshape(-1, K.shape[1])
+    A = attention_mass(K, Qr)
+    idx = select_topk(A, budget)
+    V_star, diag = backfill(V, A, idx, rank)
+    if diag.skipped:
+        V_out = np.asarray(V_io)[idx].copy()               # identity: a bit copy, not a re-rounding
+    else:
+        V_out = round_to_io(V_star, dtype)
+    return HeadResult(A=A, idx=idx, K_keep=np.asarray(K_io)[idx].copy(), V_out=V_out, V_star=V_star, diag=diag)
+
+
+def compress_relay(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budgets: np.ndarray, rank: int,
+                   group: int, dtype: str, heads=None):
+    """All (layer, KV head) pairs of a cache in the canonical layout.
+
+    K_io, V_io [L, H, N, d]; Q_io [L, H*group, W, d]; budgets int [L, H].
+    Returns {(l, h): HeadResult}.
+    """
+    L, H = K_io.shape[:2]
+    out = {}
+    todo = heads if heads is not None else [(l, h) for l in range(L) for h in range(H)]
+    for (l, h) in todo:
+        out[(l, h)] = compress_head(K_io[l, h], V_io[l, h], Q_io[l, h * group:(h + 1) * group],
+                                    int(budgets[l, h]), rank, dtype)
+    return out
+
+
+# ----------------------------------------------------------------------------- App. H route (used by pins and as a second CPU timing)
+def top_subspace_gram(R: np.ndarray, k: int) -> np.ndarray:
+    """Top-k right singular vectors of R from the d x d Gram matrix R^T R (App. H)."""
+    G = R.T @ R
+    w, U = np.linalg.eigh(G)
+    order = np.argsort(-w, kind="stable")[:k]
+    return U[:, order].T

@@ -1,0 +1,387 @@
+"""Pins for the CPU oracle: closed forms, brute force, invariants and special
+cases fixed by the paper or by the mathematics, none of which re-use the
+oracle's own formulas.  A dropped term, wrong sign, wrong axis or transposed
+operand in oracle/obf_oracle.py fails at least one of these."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp
+
+from oracle import obf_oracle as O
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# --------------------------------------------------------------------------- S1: Eq. 1
+def test_mass_sums_to_number_of_query_rows():
+    r = rng(1)
+    K = r.standard_normal((300, 64)); Q = r.standard_normal((24, 64))
+    A = O.attention_mass(K, Q)
+    assert A.shape == (300,)
+    assert abs(A.sum() - 24.0) < 1e-11          # each softmax row sums to one over the tokens
+
+
+def test_zero_queries_give_uniform_mass():
+    K = rng(2).standard_normal((50, 64))
+    A = O.attention_mass(K, np.zeros((6, 64)))
+    assert np.allclose(A, 6.0 / 50.0, rtol=0, atol=1e-15)
+
+
+def test_rank_one_keys_closed_form_pins_scale_and_axis():
+    # k_j = c_j u, q = u  =>  logits c_j |u|^2 / sqrt(d); A_j = exp(.) / sum exp(.)
+    r = rng(3)
+    d, N = 64, 40
+    u = r.standard_normal(d)
+    c = r.standard_normal(N)
+    K = c[:, None] * u[None, :]
+    A = O.attention_mass(K, u[None, :])
+    z = c * (u @ u) / math.sqrt(d)
+    ref = np.exp(z - z.max()); ref /= ref.sum()
+    assert np.allclose(A, ref, rtol=1e-12, atol=0)
+    # a wrong scale (1/d, or none) would not match
+    bad = np.exp(c * (u @ u) / d); bad /= bad.sum()
+    assert not np.allclose(A, bad, rtol=1e-3)
+
+
+def test_mass_matches_independent_logsumexp_formulation_loopwise():
+    r = rng(4)
+    N, d, R = 37, 64, 5
+    K = r.standard_normal((N, d)) * 3.0; Q = r.standard_normal((R, d)) * 3.0
+    A = O.attention_mass(K, Q)
+    ref = np.zeros(N)
+    for t in range(R):
+        s = np.array([sum(Q[t, c] * K[j, c] for c in range(d)) for j in range(N)]) / math.sqrt(d)
+        ref += np.exp(s - logsumexp(s))
+    assert np.allclose(A, ref, rtol=1e-11, atol=1e-300)
+
+
+def test_mass_survives_huge_logits():
+    K = np.zeros((4, 64)); K[0, 0] = 1e4; K[1, 0] = 1e4 - 8.0 * math.log(3.0)
+    q = np.zeros((1, 64)); q[0, 0] = 1.0
+    A = O.attention_mass(K, q)           # logits differ by log 3 after the 1/8 scale
+    assert np.all(np.isfinite(A)) and abs(A[0] / A[1] - 3.0) < 1e-9
+
+
+# --------------------------------------------------------------------------- S2: TopK_B
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_brute_force_tiny(seed):
+    r = rng(100 + seed)
+    N = int(r.integers(5, 12)); B = int(r.integers(1, N))
+    A = r.random(N)
+    idx = O.select_topk(A, B)
+    assert len(idx) == B and np.all(np.diff(idx) > 0)
+    best = max(itertools.combinations(range(N), B), key=lambda s: A[list(s)].sum())
+    assert tuple(idx) == best
+
+
+def test_topk_all_ties_keeps_lowest_indices():
+    idx = O.select_topk(np.full(20, 0.25), 7)
+    assert idx.tolist() == list(range(7))
+
+
+def test_topk_partial_ties_lowest_index_wins():
+    A = np.array([1.0, 5.0, 2.0, 2.0, 9.0, 2.0, 0.5])
+    assert O.select_topk(A, 3).tolist() == [1, 2, 4]      # of the three 2.0s only index 2 fits
+    assert O.select_topk(A, 4).tolist() == [1, 2, 3, 4]
+
+
+def test_topk_budget_edges():
+    A = rng(5).random(9)
+    assert O.select_topk(A, 0).size == 0
+    assert O.select_topk(A, 9).tolist() == list(range(9))
+    assert O.select_topk(A, 50).tolist() == list(range(9))
+
+
+def test_topk_permutation_equivariance():
+    r = rng(6)
+    A = r.random(64)
+    perm = r.permutation(64)
+    idx = O.select_topk(A, 10)
+    idx_p = O.select_topk(A[perm], 10)
+    assert sorted(perm[idx_p].tolist()) == idx.tolist()
+
+
+# --------------------------------------------------------------------------- S3 + dtype plumbing
+def test_bf16_decode_and_round_roundtrip_all_finite_patterns():
+    bits = np.arange(0, 1 << 16, dtype=np.uint32).astype(np.uint16)
+    exp = (bits >> 7) & 0xFF
+    finite = bits[exp != 0xFF]
+    x = O.decode(finite, "bf16")
+    assert np.array_equal(O.round_to_io(x, "bf16"), finite)
+    # 1.0 = 0x3F80, -2.0 = 0xC000, 0.15625 = 0x3E20
+    assert O.decode(np.array([0x3F80, 0xC000, 0x3E20], np.uint16), "bf16").tolist() == [1.0, -2.0, 0.15625]
+
+
+def test_bf16_rounding_is_nearest_even():
+    # 1 + 2^-8 is halfway between 1.0 (even mantissa) and 1 + 2^-7: ties to even -> 1.0
+    assert O.round_to_io(np.array([1.0 + 2.0 ** -8]), "bf16")[0] == 0x3F80
+    assert O.round_to_io(np.array([1.0 + 2.0 ** -8 + 2.0 ** -12]), "bf16")[0] == 0x3F81
+    assert O.round_to_io(np.array([1.0 + 3 * 2.0 ** -8]), "bf16")[0] == 0x3F82   # tie -> even (0x82)
+
+
+def test_gather_is_bit_copy():
+    r = rng(7)
+    K = r.integers(0, 1 << 16, size=(64, 64)).astype(np.uint16)
+    K[(K >> 7) & 0xFF == 0xFF] = 0
+    V = K[::-1].copy()
+    Q = O.round_to_io(r.standard_normal((2, 4, 64)), "bf16")
+    res = O.compress_head(K, V, Q, 9, 0, "bf16")
+    assert np.array_equal(res.K_keep, K[res.idx]) and np.array_equal(res.V_out, V[res.idx])
+
+
+# --------------------------------------------------------------------------- S4-S5: Eq. 2-3
+def test_orth_is_orthonormal_basis_of_retained_span():
+    V = rng(8).standard_normal((20, 64))
+    Q, _ = O.orth_rowspace(V)
+    assert Q.shape == (64, 20)
+    assert np.allclose(Q.T @ Q, np.eye(20), atol=1e-12)
+    assert np.allclose(V - (V @ Q) @ Q.T, 0, atol=1e-11)
+    # same projector as the pseudo-inverse route
+    assert np.allclose(Q @ Q.T, np.linalg.pinv(V) @ V, atol=1e-10)
+
+
+def test_orth_drops_dependent_rows():
+    r = rng(9)
+    base = r.standard_normal((5, 64))
+    V = np.vstack([base, base[0] + base[1], 2.0 * base[3]])
+    Q, _ = O.orth_rowspace(V)
+    assert Q.shape[1] == 5
+
+
+def test_pcr_plus_rcr_is_one_and_residual_orthogonal():
+    r = rng(10)
+    V = r.standard_normal((200, 64)); A = r.random(200)
+    idx = O.select_topk(A, 24)
+    _, dg = O.backfill(V, A, idx, 4)
+    assert abs(dg.pcr + dg.rcr - 1.0) < 1e-12
+    assert dg.r_keep == 24 and dg.k_used == 4 and dg.skipped == 0
+
+
+def test_full_rank_retained_span_makes_backfill_identity():
+    r = rng(11)
+    V = r.standard_normal((300, 64)); A = r.random(300)
+    idx = O.select_topk(A, 64)                       # B = d, generic => span = R^d
+    Vs, dg = O.backfill(V, A, idx, 4)
+    assert dg.skipped == 1 and dg.r_keep == 64 and np.array_equal(Vs, V[idx])
+    idx = O.select_topk(A, 100)                      # B > d
+    Vs, dg = O.backfill(V, A, idx, 4)
+    assert dg.skipped == 1 and np.array_equal(Vs, V[idx])
+
+
+def test_deleted_rows_inside_retained_span_are_skipped():
+    r = rng(12)
+    keep_rows = r.standard_normal((10, 64))
+    mix = r.standard_normal((50, 10))
+    V = np.vstack([keep_rows, mix @ keep_rows])
+    A = np.concatenate([np.full(10, 5.0), r.random(50)])
+    idx = O.select_topk(A, 10)
+    assert idx.tolist() == list(range(10))
+    Vs, dg = O.backfill(V, A, idx, 3)
+    assert dg.skipped == 1 and dg.rcr < 1e-20 and np.array_equal(Vs, V[idx])
+
+
+# --------------------------------------------------------------------------- S6: rank-k subspace
+def _power_subspace(G, k, iters=4000):
+    C = np.linalg.qr(np.random.default_rng(0).standard_normal((G.shape[0], k)))[0]
+    for _ in range(iters):
+        C = np.linalg.qr(G @ C)[0]
+    return C.T
+
+
+def test_svd_gram_eigh_and_subspace_iteration_agree():
+    r = rng(13)
+    R = r.standard_normal((400, 32)) * np.linspace(3.0, 0.2, 32)[None, :] @ np.linalg.qr(r.standard_normal((32, 32)))[0]
+    k = 4
+    C_svd = np.linalg.svd(R, full_matrices=False)[2][:k]
+    C_gram = O.top_subspace_gram(R, k)
+    C_pow = _power_subspace(R.T @ R, k)
+    P = C_svd.T @ C_svd
+    assert np.allclose(P, C_gram.T @ C_gram, atol=1e-9)
+    assert np.allclose(P, C_pow.T @ C_pow, atol=1e-7)
+
+
+def test_revr_monotone_in_rank():
+    r = rng(14)
+    V = r.standard_normal((256, 64)); A = r.random(256)
+    idx = O.select_topk(A, 16)
+    vals = [O.backfill(V, A, idx, k)[1].revr for k in (1, 2, 4, 8, 16, 32)]
+    assert all(b > a for a, b in zip(vals, vals[1:])) and vals[-1] < 1.0
+
+
+# --------------------------------------------------------------------------- S7-S9: Eq. 4-6 closed forms
+def test_closed_form_full_rank_budget_needs_no_svd():
+    # pca_rank >= rank(R)  =>  Delta = rbar = P_perp sum_j w_j V_j
+    r = rng(15)
+    N, d, B = 120, 64, 40
+    V = r.standard_normal((N, d)); A = r.random(N) + 0.01
+    idx = O.select_topk(A, B)
+    dele = np.setdiff1d(np.arange(N), idx)
+    Vs, dg = O.backfill(V, A, idx, d)
+    Pperp = np.eye(d) - np.linalg.pinv(V[idx]) @ V[idx]
+    a_del, a_keep = A[dele].sum(), A[idx].sum()
+    rbar = Pperp @ (A[dele] @ V[dele]) / (a_del + 1e-12)
+    delta = a_del / (a_keep + 1e-12) * rbar
+    assert dg.k_used == d - B
+    assert np.allclose(Vs - V[idx], delta[None, :], rtol=1e-9, atol=1e-12)
+
+
+def test_closed_form_planted_single_direction():
+    # retained rows live on coordinates 0..B-1, every deleted row is c_j e_{d-1}
+    r = rng(16)
+    d, B, nd = 64, 12, 30
+    Vk = np.zeros((B, d)); Vk[:, :B] = r.standard_normal((B, B))
+    c = r.standard_normal(nd)
+    Vd = np.zeros((nd, d)); Vd[:, d - 1] = c
+    V = np.vstack([Vk, Vd])
+    A = np.concatenate([2.0 + r.random(B), r.random(nd)])
+    idx = O.select_topk(A, B)
+    assert idx.tolist() == list(range(B))
+    Vs, dg = O.backfill(V, A, idx, 3)
+    a_keep, a_del = A[:B].sum(), A[B:].sum()
+    expect = np.zeros(d)
+    expect[d - 1] = (a_del / (a_keep + 1e-12)) * ((A[B:] @ c) / (a_del + 1e-12))
+    assert dg.k_used == 1 and dg.r_keep == B and abs(dg.rcr - 1.0) < 1e-12
+    assert np.allclose(Vs - Vk, expect[None, :], rtol=1e-10, atol=1e-14)
+
+
+def test_rank_one_injection_by_hand():
+    # hand computation on a 3-d example: keep = e0 ; deleted rows (1,2,0),(1,-2,0.1)
+    V = np.array([[1.0, 0, 0], [1.0, 2.0, 0.0], [1.0, -2.0, 0.1]])
+    A = np.array([3.0, 1.0, 0.5])
+    idx = np.array([0])
+    Vs, dg = O.backfill(V, A, idx, 1)
+    R = np.array([[0, 2.0, 0.0], [0, -2.0, 0.1]])
+    G = R.T @ R
+    w, U = np.linalg.eigh(G)
+    c = U[:, -1]
+    rbar = (1.0 * R[0] + 0.5 * R[1]) / (1.5 + 1e-12)
+    delta = 1.5 / (3.0 + 1e-12) * (rbar @ c) * c
+    assert np.allclose(Vs[0] - V[0], delta, rtol=1e-12, atol=1e-15)
+
+
+def test_homogeneity_and_token_permutation():
+    r = rng(17)
+    N, d, B = 90, 64, 20
+    V = r.standard_normal((N, d)); A = r.random(N)
+    idx = O.select_topk(A, B)
+    d1 = O.backfill(V, A, idx, 3)[1].delta
+    d2 = O.backfill(2.5 * V, A, idx, 3)[1].delta
+    assert np.allclose(d2, 2.5 * d1, rtol=1e-10)
+    d3 = O.backfill(V, 7.0 * A, idx, 3)[1].delta          # mass scale only meets epsilon
+    assert np.allclose(d3, d1, rtol=1e-9)
+    perm = r.permutation(N)
+    inv = np.argsort(perm)
+    idx_p = np.sort(inv[idx])
+    d4 = O.backfill(V[perm], A[perm], idx_p, 3)[1].delta
+    assert np.allclose(d4, d1, rtol=1e-9, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- S10: Eq. 7 and the whole head
+def _head(seed, N=160, d=64, rows=6, scale=1.0):
+    r = rng(seed)
+    K = r.standard_normal((N, d)).astype(np.float32) * scale
+    V = r.standard_normal((N, d)).astype(np.float32)
+    Q = r.standard_normal((rows, d)).astype(np.float32)
+    return K, V, Q
+
+
+def test_injection_orthogonal_to_retained_values():
+    K, V, Q = _head(18)
+    res = O.compress_head(K, V, Q, 24, 4, "f32")
+    delta = res.diag.delta
+    Vk = V[res.idx].astype(np.float64)
+    assert res.diag.skipped == 0 and res.diag.ivn > 0
+    assert np.abs(Vk @ delta).max() <= 1e-5 * np.linalg.norm(Vk, axis=1).max() * np.linalg.norm(delta)
+    assert np.allclose(res.V_star - Vk, delta[None, :], atol=1e-14)   # same vector on every retained row
+
+
+def test_indices_and_keys_unchanged_by_backfill_and_rank_zero_is_eviction():
+    K, V, Q = _head(19)
+    a = O.compress_head(K, V, Q, 24, 0, "f32")
+    b = O.compress_head(K, V, Q, 24, 4, "f32")
+    assert np.array_equal(a.idx, b.idx) and np.array_equal(a.K_keep, b.K_keep)
+    assert a.idx.size == 24
+    assert np.array_equal(a.V_out, V[a.idx]) and a.diag.skipped == 1
+    assert not np.array_equal(b.V_out, V[b.idx])
+
+
+def test_budget_at_least_n_keeps_everything_untouched():
+    K, V, Q = _head(20, N=40)
+    res = O.compress_head(K, V, Q, 40, 4, "f32")
+    assert res.idx.tolist() == list(range(40)) and np.array_equal(res.V_out, V) and res.diag.skipped == 1
+
+
+def test_single_query_attention_output_identities():
+    # App. L: with one query, o_evict is the retained conditional mean, and attending the
+    # compressed cache gives o_OBF - o_evict = delta exactly.
+    K, V, Q = _head(21, rows=1)
+    res = O.compress_head(K, V, Q, 20, 3, "f32")
+    Kd, Vd, q = K.astype(np.float64), V.astype(np.float64), Q.astype(np.float64)[0]
+    s = Kd @ q / math.sqrt(64)
+    alpha = np.exp(s - logsumexp(s))
+    assert np.allclose(alpha, res.A, rtol=1e-12)
+    keep = res.idx
+    dele = np.setdiff1d(np.arange(len(s)), keep)
+    sk = s[keep]; at = np.exp(sk - logsumexp(sk))
+    o_evict = at @ Vd[keep]
+    vbar_keep = (alpha[keep] @ Vd[keep]) / alpha[keep].sum()
+    assert np.allclose(o_evict, vbar_keep, rtol=1e-12, atol=1e-14)
+    o_obf = at @ res.V_star
+    assert np.allclose(o_obf - o_evict, res.diag.delta, rtol=1e-10, atol=1e-14)
+    # error decomposition with Eq. 6 taken literally (injection = Pi_U tau_perp / A_keep)
+    o_full = alpha @ Vd
+    A_keep, A_del = alpha[keep].sum(), alpha[dele].sum()
+    tau = A_del * ((alpha[dele] @ Vd[dele]) / A_del - vbar_keep)
+    assert np.allclose(o_full - o_evict, tau, rtol=1e-10, atol=1e-14)
+    Pk = np.linalg.pinv(Vd[keep]) @ Vd[keep]
+    tau_perp = tau - Pk @ tau
+    R = Vd[dele] - Vd[dele] @ Pk
+    C = np.linalg.svd(R, full_matrices=False)[2][:3]
+    PU = C.T @ C
+    lhs = np.linalg.norm(o_full - o_obf) ** 2
+    rhs = (np.linalg.norm(Pk @ tau) ** 2 + np.linalg.norm(tau_perp - PU @ tau_perp) ** 2
+           + (1.0 - 1.0 / A_keep) ** 2 * np.linalg.norm(PU @ tau_perp) ** 2)
+    assert abs(lhs - rhs) <= 1e-9 * max(lhs, 1e-30)
+
+
+def test_whole_head_against_loop_implementation_tiny():
+    # an independent, loop-level restatement on a tiny head
+    r = rng(22)
+    N, d, B, p = 10, 4, 2, 1
+    K = r.standard_normal((N, d)).astype(np.float32); V = r.standard_normal((N, d)).astype(np.float32)
+    Q = r.standard_normal((3, d)).astype(np.float32)
+    res = O.compress_head(K, V, Q, B, p, "f32")
+    A = [0.0] * N
+    for t in range(3):
+        s = [sum(float(Q[t, c]) * float(K[j, c]) for c in range(d)) / math.sqrt(d) for j in range(N)]
+        m = max(s); e = [math.exp(x - m) for x in s]; z = sum(e)
+        for j in range(N):
+            A[j] += e[j] / z
+    order = sorted(range(N), key=lambda j: (-A[j], j))
+    keep = sorted(order[:B]); dele = [j for j in range(N) if j not in keep]
+    assert res.idx.tolist() == keep
+    Vd = V.astype(np.float64)
+    # Gram-Schmidt on the two retained rows
+    q1 = Vd[keep[0]] / np.linalg.norm(Vd[keep[0]])
+    u2 = Vd[keep[1]] - (Vd[keep[1]] @ q1) * q1; q2 = u2 / np.linalg.norm(u2)
+    R = np.array([Vd[j] - (Vd[j] @ q1) * q1 - (Vd[j] @ q2) * q2 for j in dele])
+    w, U = np.linalg.eigh(R.T @ R); c = U[:, -1]
+    a_del = sum(A[j] for j in dele); a_keep = sum(A[j] for j in keep)
+    rbar = sum((A[j] / (a_del + 1e-12)) * R[i] for i, j in enumerate(dele))
+    delta = a_del / (a_keep + 1e-12) * (rbar @ c) * c
+    assert np.allclose(res.V_star, Vd[keep] + delta[None, :], rtol=1e-10, atol=1e-13)
+
+
+def test_relay_layout_maps_query_heads_to_kv_heads():
+    r = rng(23)
+    L, H, g, W, N, d = 2, 2, 3, 2, 30, 64
+    K = r.standard_normal((L, H, N, d)).astype(np.float32); V = r.standard_normal((L, H, N, d)).astype(np.float32)
+    Q = r.standard_normal((L, H * g, W, d)).astype(np.float32)
+    out = O.compress_relay(K, V, Q, np.full((L, H), 5), 2, g, "f32")
+    for (l, h), res in out.items():
+        ref = O.attention_mass(K[l, h].astype(np.float64), Q[l, h * g:(h + 1) * g].reshape(-1, d).astype(np.float64))
+        assert np.allclose(res.A, ref) and abs(res.A.sum() - g * W) < 1e-10
