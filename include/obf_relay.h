@@ -1,0 +1,136 @@
+/*
+ * obf_relay.h -- C ABI of the relay-boundary KV compression library for MI355X (gfx950).
+ *
+ * One call compresses the prompt block of an agent's KV cache before it is relayed to the
+ * next agent: per (layer, KV head) it scores the prompt tokens by the attention mass they
+ * receive from a window of observation queries (Eq. 1), keeps the top-B tokens (TopK_B,
+ * Sec. 4.3.2 / Alg. 2), gathers their keys and values, and applies Orthogonal BackFill
+ * (Sec. 4.4, Eq. 2-7 / Alg. 3): one low-rank correction vector, orthogonal to the span of
+ * the retained values, is added to every retained value; keys and the retained index set
+ * are left untouched.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer unless its name ends in `_host`.
+ *   - The caller owns all buffers.  The library never allocates, frees or keeps device
+ *     memory; scratch space is the caller's workspace `ws` of at least
+ *     obf_workspace_bytes() bytes, 256-byte aligned.  Its contents are undefined after a call.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*); nothing is
+ *     synchronised.  Inputs are never modified.
+ *   - Argument errors are found on the host before anything is enqueued and reported as
+ *     a status code; obf_last_error() gives a thread-local message.  No exceptions, no abort.
+ *   - Layouts are contiguous, row-major, head-major:
+ *       K, V        [n_layers][n_kv_heads][n_tokens][head_dim]          dtype
+ *       Qwin        [n_layers][n_kv_heads*group][window][head_dim]      dtype
+ *                   query head i belongs to KV head i / group; Q and K are taken as given
+ *                   (position encoding already applied)
+ *       scores      [n_layers][n_kv_heads][n_tokens]                    float
+ *       row_lse     [n_layers][n_kv_heads][group*window]                double
+ *       idx         [n_layers][n_kv_heads][max_budget]                  int32, ascending,
+ *                                                                       entries >= n_keep are -1
+ *       n_keep      [n_layers][n_kv_heads]                              int32
+ *       K_out,V_out [n_layers][n_kv_heads][max_budget][head_dim]        dtype, rows >= n_keep zero
+ *       delta_out   [n_layers][n_kv_heads][head_dim]                    float (optional)
+ *       diag        [n_layers][n_kv_heads]                              obf_diag_t (optional)
+ *   - Limits: head_dim in {64, 128}; 1 <= n_tokens <= 32768; group*window >= 1;
+ *     0 <= budget <= max_budget.  Anything else is OBF_ERR_UNSUPPORTED / OBF_ERR_INVALID_ARG.
+ */
+#ifndef OBF_RELAY_H
+#define OBF_RELAY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OBF_OK = 0,
+  OBF_ERR_INVALID_ARG = 1,
+  OBF_ERR_UNSUPPORTED = 2,
+  OBF_ERR_WORKSPACE_TOO_SMALL = 3,
+  OBF_ERR_HIP = 4
+} obf_status_t;
+
+typedef enum { OBF_F32 = 0, OBF_BF16 = 1 } obf_dtype_t;
+
+typedef struct {
+  int32_t n_layers;
+  int32_t n_kv_heads;
+  int32_t group;      /* query heads per KV head (GQA) */
+  int32_t head_dim;   /* d */
+  int32_t n_tokens;   /* N prompt tokens per head */
+  int32_t window;     /* W observation queries per query head */
+  int32_t dtype;      /* obf_dtype_t of K, V, Qwin, K_out, V_out */
+} obf_shape_t;
+
+/* Per-head diagnostics (App. K.2 quantities that fall out of the computation). */
+typedef struct {
+  int32_t n_keep;   /* retained tokens */
+  int32_t r_keep;   /* dimension of the retained value span (Eq. 2); 0 if not computed */
+  int32_t k_used;   /* residual principal directions used (Sec. 4.4, k = min(pca_rank, rank R)) */
+  int32_t skipped;  /* 1: no injection (empty P_del, rank 0, span = R^d, negligible residual) */
+  float a_keep;     /* sum of attention mass over retained tokens (Eq. 6) */
+  float a_del;      /* sum over deleted tokens */
+  float rcr;        /* ||R||_F^2 / ||V_del||_F^2 */
+  float ivn;        /* ||delta||_2 */
+} obf_diag_t;
+
+/* Bytes of workspace any entry point needs for this shape (host function, no device work).
+ * Returns 0 if the shape is unsupported. */
+size_t obf_workspace_bytes(const obf_shape_t* shape, int32_t max_budget, int32_t rank);
+
+/* Eq. 1 / Alg. 2 line 1: scores[l][h][j] = sum over the group*window query rows of
+ * softmax_j(q . k_j / sqrt(d)), softmax over the n_tokens keys of the head.
+ * row_lse (nullable) receives log(sum_j exp(logit)) of every query row in double; the
+ * boundary refinement needs it. */
+obf_status_t obf_score(const obf_shape_t* shape, const void* K, const void* Qwin, float* scores,
+                       double* row_lse, void* ws, size_t ws_bytes, void* stream);
+
+/* TopK_B (Sec. 4.3.2, Alg. 2 line 3) on the float scores as given: the B largest, ties to the
+ * lowest index, written ascending.  Pure integer/compare work on the fp32 bit patterns.
+ * budgets_host (nullable, host memory, [n_layers*n_kv_heads]) gives per-head budgets;
+ * otherwise `budget` is used for every head.  Budgets above n_tokens keep everything. */
+obf_status_t obf_select_topk(const obf_shape_t* shape, const float* scores, const int32_t* budgets_host,
+                             int32_t budget, int32_t max_budget, int32_t* idx, int32_t* n_keep,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* Re-decides, in double precision, the membership of the tokens whose float score lies within
+ * a relative band of the selection threshold, so that the retained set is the one exact
+ * arithmetic on the given K / Qwin bits would give (ties still to the lowest index).
+ * idx / n_keep are updated in place; n_keep does not change. */
+obf_status_t obf_refine_boundary(const obf_shape_t* shape, const void* K, const void* Qwin, const float* scores,
+                                 const double* row_lse, int32_t max_budget, int32_t* idx, const int32_t* n_keep,
+                                 void* ws, size_t ws_bytes, void* stream);
+
+/* Alg. 2 line 7: K_out = K[idx], V_out = V[idx] as bit copies; rows >= n_keep are zeroed.
+ * Either output may be NULL to skip it. */
+obf_status_t obf_gather(const obf_shape_t* shape, const void* K, const void* V, const int32_t* idx,
+                        const int32_t* n_keep, int32_t max_budget, void* K_out, void* V_out, void* stream);
+
+/* Orthogonal BackFill (Eq. 2-7, Alg. 3 lines 3-10) on already gathered values: V_out holds
+ * V[idx] on entry and V[idx] + delta on exit (rounded to dtype); untouched where OBF is
+ * skipped.  `rank` is pca_rank (0 = plain eviction).  delta_out, diag nullable. */
+obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* scores, const int32_t* idx,
+                          const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
+                          float* delta_out, obf_diag_t* diag, void* ws, size_t ws_bytes, void* stream);
+
+/* The whole relay compression Phi_OBF (Alg. 3) in one enqueue: score, select, refine, gather,
+ * back-fill.  Outputs equal those of the five stage calls run in that order.
+ * scores_out, delta_out, diag nullable. */
+obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                float* scores_out, float* delta_out, obf_diag_t* diag,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* Message for the calling thread's last non-OK status (static storage, never NULL). */
+const char* obf_last_error(void);
+
+/* Library version string (static storage). */
+const char* obf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OBF_RELAY_H */

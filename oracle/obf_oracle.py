@@ -133,15 +133,19 @@ class HeadDiag:
     gap: float = np.inf          # sigma_k / sigma_{k+1} of R (subspace conditioning)
     keep_sigma_margin: float = np.inf   # min over sigma of |log10(sigma / rank threshold)|
     res_sigma_margin: float = np.inf
+    res_sigma_rel: Optional[np.ndarray] = field(default=None, repr=False)   # sigma_i/sigma_1 of R, i < pca_rank
+    res_thr_rel: float = 0.0            # rank threshold of R relative to sigma_1
     delta: Optional[np.ndarray] = field(default=None, repr=False)
 
 
-def _margin(sigma: np.ndarray, rows: int, cols: int) -> float:
+def _margin(sigma: np.ndarray, rows: int, cols: int, first: Optional[int] = None) -> float:
+    """Decades between the rank threshold and the nearest of the (first `first`) singular values."""
     if sigma.size == 0 or sigma[0] <= 0:
         return np.inf
     thr = sigma[0] * max(rows, cols) * RANK_EPS
+    sel = sigma if first is None else sigma[:first]
     with np.errstate(divide="ignore"):
-        m = np.abs(np.log10(np.maximum(sigma, 1e-300) / thr))
+        m = np.abs(np.log10(np.maximum(sel, 1e-300) / thr))
     return float(m.min())
 
 
@@ -186,7 +190,9 @@ def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int):
     _, sR, VtR = np.linalg.svd(R, full_matrices=False)     # rows of VtR: right singular vectors
     rankR = numerical_rank(sR, R.shape[0], d)
     k = min(int(rank), rankR)
-    diag.res_sigma_margin = _margin(sR, R.shape[0], d)
+    diag.res_sigma_margin = _margin(sR, R.shape[0], d, first=int(rank))   # only these decide k
+    diag.res_sigma_rel = sR[:int(rank)] / sR[0] if sR[0] > 0 else None
+    diag.res_thr_rel = max(R.shape[0], d) * RANK_EPS
     if k == 0:
         return V_keep.copy(), diag
     C = VtR[:k]                                            # [k, d]

@@ -1,0 +1,228 @@
+"""ctypes binding of include/obf_relay.h: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libobf_relay.so"
+_lib = None
+
+OBF_F32, OBF_BF16 = 0, 1
+_STATUS = {1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP"}
+
+DIAG_DTYPE = np.dtype([("n_keep", "<i4"), ("r_keep", "<i4"), ("k_used", "<i4"), ("skipped", "<i4"),
+                       ("a_keep", "<f4"), ("a_del", "<f4"), ("rcr", "<f4"), ("ivn", "<f4")])
+
+
+class ObfError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"obf_relay status {status} ({_STATUS.get(status, '?')}): {msg}")
+        self.status = status
+
+
+class _Shape(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
+                ("n_tokens", C.c_int32), ("window", C.c_int32), ("dtype", C.c_int32)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Loads the built library (torch first, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          f"or `python paper_2604_13349_amd/build.py` (there is no CPU fallback)")
+    lib = C.CDLL(path)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    sp = C.POINTER(_Shape)
+    lib.obf_workspace_bytes.restype = sz
+    lib.obf_workspace_bytes.argtypes = [sp, i32, i32]
+    lib.obf_score.restype = C.c_int
+    lib.obf_score.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
+    lib.obf_select_topk.restype = C.c_int
+    lib.obf_select_topk.argtypes = [sp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.obf_refine_boundary.restype = C.c_int
+    lib.obf_refine_boundary.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.obf_gather.restype = C.c_int
+    lib.obf_gather.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.obf_backfill.restype = C.c_int
+    lib.obf_backfill.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.obf_compress_relay.restype = C.c_int
+    lib.obf_compress_relay.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.obf_last_error.restype = C.c_char_p
+    lib.obf_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise ObfError(status, load_library().obf_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def shape_of(K: torch.Tensor, Qwin: torch.Tensor) -> _Shape:
+    """Shape descriptor from K [L,H,N,d] and Qwin [L,H*group,W,d]."""
+    L, H, N, d = K.shape
+    Lq, Hq, W, dq = Qwin.shape
+    if Lq != L or dq != d or Hq % H != 0:
+        raise ValueError("Qwin does not match K")
+    if K.dtype == torch.float32:
+        dt = OBF_F32
+    elif K.dtype == torch.bfloat16:
+        dt = OBF_BF16
+    else:
+        raise ValueError("K must be float32 or bfloat16")
+    if Qwin.dtype != K.dtype:
+        raise ValueError("Qwin dtype differs from K")
+    return _Shape(L, H, Hq // H, d, N, W, dt)
+
+
+def make_shape(n_layers, n_kv_heads, group, head_dim, n_tokens, window, dtype) -> _Shape:
+    """Shape descriptor from plain numbers; dtype is "bf16"/"f32" or a torch dtype."""
+    if dtype in ("bf16", torch.bfloat16):
+        dt = OBF_BF16
+    elif dtype in ("f32", torch.float32):
+        dt = OBF_F32
+    else:
+        raise ValueError("dtype must be bf16 or f32")
+    return _Shape(n_layers, n_kv_heads, group, head_dim, n_tokens, window, dt)
+
+
+def workspace_bytes(shape: _Shape, max_budget: int, rank: int) -> int:
+    return int(load_library().obf_workspace_bytes(C.byref(shape), max_budget, rank))
+
+
+def _ws(shape: _Shape, max_budget: int, rank: int, ws: Optional[torch.Tensor], device) -> torch.Tensor:
+    need = workspace_bytes(shape, max_budget, rank)
+    if need == 0:
+        raise ObfError(2, "unsupported shape")
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return ws
+
+
+def _budgets_arg(budgets: Optional[Sequence[int]]):
+    if budgets is None:
+        return None, None
+    arr = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
+    return arr, arr.ctypes.data_as(C.c_void_p)
+
+
+def score(K, Qwin, scores=None, row_lse=None, ws=None):
+    sh = shape_of(K, Qwin)
+    L, H, N = sh.n_layers, sh.n_kv_heads, sh.n_tokens
+    if scores is None:
+        scores = torch.empty((L, H, N), dtype=torch.float32, device=K.device)
+    if row_lse is None:
+        row_lse = torch.empty((L, H, sh.group * sh.window), dtype=torch.float64, device=K.device)
+    ws = _ws(sh, 0, 0, ws, K.device)
+    _check(load_library().obf_score(C.byref(sh), _ptr(K), _ptr(Qwin), _ptr(scores), _ptr(row_lse), _ptr(ws),
+                                    ws.numel(), _stream()))
+    return scores, row_lse
+
+
+def select_topk(shape: _Shape, scores, budget: int = 0, budgets=None, max_budget: Optional[int] = None,
+                idx=None, n_keep=None):
+    L, H = shape.n_layers, shape.n_kv_heads
+    keep, bptr = _budgets_arg(budgets)
+    if max_budget is None:
+        max_budget = int(min(shape.n_tokens, max(keep) if keep is not None else budget))
+    if idx is None:
+        idx = torch.empty((L, H, max_budget), dtype=torch.int32, device=scores.device)
+    if n_keep is None:
+        n_keep = torch.empty((L, H), dtype=torch.int32, device=scores.device)
+    _check(load_library().obf_select_topk(C.byref(shape), _ptr(scores), bptr, budget, max_budget, _ptr(idx), _ptr(n_keep),
+                                          None, 0, _stream()))
+    return idx, n_keep
+
+
+def refine_boundary(K, Qwin, scores, row_lse, idx, n_keep, ws=None):
+    sh = shape_of(K, Qwin)
+    max_budget = idx.shape[-1]
+    ws = _ws(sh, max_budget, 0, ws, K.device)
+    _check(load_library().obf_refine_boundary(C.byref(sh), _ptr(K), _ptr(Qwin), _ptr(scores), _ptr(row_lse), max_budget,
+                                              _ptr(idx), _ptr(n_keep), _ptr(ws), ws.numel(), _stream()))
+    return idx
+
+
+def gather(shape: _Shape, K, V, idx, n_keep, K_out=None, V_out=None):
+    L, H, d = shape.n_layers, shape.n_kv_heads, shape.head_dim
+    max_budget = idx.shape[-1]
+    src = K if K is not None else V
+    if K is not None and K_out is None:
+        K_out = torch.empty((L, H, max_budget, d), dtype=src.dtype, device=src.device)
+    if V is not None and V_out is None:
+        V_out = torch.empty((L, H, max_budget, d), dtype=src.dtype, device=src.device)
+    _check(load_library().obf_gather(C.byref(shape), _ptr(K), _ptr(V), _ptr(idx), _ptr(n_keep), max_budget, _ptr(K_out),
+                                     _ptr(V_out), _stream()))
+    return K_out, V_out
+
+
+def backfill(shape: _Shape, V, scores, idx, n_keep, rank: int, V_out, delta_out=None, diag=None, ws=None):
+    max_budget = idx.shape[-1]
+    ws = _ws(shape, max_budget, rank, ws, V.device)
+    _check(load_library().obf_backfill(C.byref(shape), _ptr(V), _ptr(scores), _ptr(idx), _ptr(n_keep), max_budget, rank,
+                                       _ptr(V_out), _ptr(delta_out), _ptr(diag), _ptr(ws), ws.numel(), _stream()))
+    return V_out
+
+
+def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max_budget: Optional[int] = None,
+                   out=None, ws=None, want_scores=False, want_delta=False, want_diag=False):
+    """Fused relay compression.  Returns a dict of output tensors (device)."""
+    sh = shape_of(K, Qwin)
+    L, H, d, N = sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.n_tokens
+    keep, bptr = _budgets_arg(budgets)
+    if max_budget is None:
+        max_budget = int(min(N, max(keep) if keep is not None else budget))
+    dev = K.device
+    o = out if out is not None else {}
+    if "K_out" not in o:
+        o["K_out"] = torch.empty((L, H, max_budget, d), dtype=K.dtype, device=dev)
+    if "V_out" not in o:
+        o["V_out"] = torch.empty((L, H, max_budget, d), dtype=K.dtype, device=dev)
+    if "idx" not in o:
+        o["idx"] = torch.empty((L, H, max_budget), dtype=torch.int32, device=dev)
+    if "n_keep" not in o:
+        o["n_keep"] = torch.empty((L, H), dtype=torch.int32, device=dev)
+    if want_scores and "scores" not in o:
+        o["scores"] = torch.empty((L, H, N), dtype=torch.float32, device=dev)
+    if want_delta and "delta" not in o:
+        o["delta"] = torch.empty((L, H, d), dtype=torch.float32, device=dev)
+    if want_diag and "diag" not in o:
+        o["diag"] = torch.empty((L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
+    ws = _ws(sh, max_budget, rank, ws, dev)
+    _check(load_library().obf_compress_relay(
+        C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]),
+        _ptr(o["idx"]), _ptr(o["n_keep"]), _ptr(o.get("scores")), _ptr(o.get("delta")), _ptr(o.get("diag")),
+        _ptr(ws), ws.numel(), _stream()))
+    o["ws"] = ws
+    return o
+
+
+def diag_to_numpy(diag: torch.Tensor) -> np.ndarray:
+    """Device diag bytes [L,H,32] -> structured numpy array [L,H]."""
+    a = diag.cpu().numpy()
+    return a.view(DIAG_DTYPE).reshape(a.shape[0], a.shape[1])

@@ -1,0 +1,173 @@
+// Host side of the C ABI: argument validation, workspace carving, stage sequencing.
+// Nothing here touches device memory; every entry point only enqueues kernels.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include "common.hpp"
+
+namespace obf {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+obf_status_t check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return OBF_ERR_HIP;
+  }
+  return OBF_OK;
+}
+
+static obf_status_t check_shape(const obf_shape_t* s) {
+  if (!s) { set_error("shape is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (s->n_layers < 1 || s->n_kv_heads < 1 || s->group < 1 || s->window < 1 || s->n_tokens < 1) {
+    set_error("shape: n_layers, n_kv_heads, group, window, n_tokens must all be >= 1");
+    return OBF_ERR_INVALID_ARG;
+  }
+  if (s->dtype != OBF_F32 && s->dtype != OBF_BF16) { set_error("shape: unknown dtype %d", s->dtype); return OBF_ERR_INVALID_ARG; }
+  if (s->head_dim != 64 && s->head_dim != 128) { set_error("head_dim %d unsupported (64 or 128)", s->head_dim); return OBF_ERR_UNSUPPORTED; }
+  if (s->n_tokens > kMaxTokens) { set_error("n_tokens %d above the supported %d", s->n_tokens, kMaxTokens); return OBF_ERR_UNSUPPORTED; }
+  if ((int64_t)s->n_layers * s->n_kv_heads > 65535) { set_error("more than 65535 heads in one call"); return OBF_ERR_UNSUPPORTED; }
+  if ((int64_t)s->group * s->window > 4096) { set_error("group*window above 4096"); return OBF_ERR_UNSUPPORTED; }
+  return OBF_OK;
+}
+
+static obf_status_t check_ws(const Dims& m, const Workspace& w, const void* ws, size_t ws_bytes) {
+  (void)m;
+  if (!ws) { set_error("workspace is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (((uintptr_t)ws & 255) != 0) { set_error("workspace must be 256-byte aligned"); return OBF_ERR_INVALID_ARG; }
+  if (ws_bytes < w.total) { set_error("workspace too small: %zu bytes given, %zu needed", ws_bytes, w.total); return OBF_ERR_WORKSPACE_TOO_SMALL; }
+  return OBF_OK;
+}
+
+static obf_status_t check_budget(const Dims& m, const int32_t* budgets_host, int32_t budget, int32_t max_budget) {
+  if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }
+  if (budgets_host) {
+    for (int h = 0; h < m.heads; ++h) {
+      int32_t b = budgets_host[h];
+      if (b < 0) { set_error("budgets_host[%d] = %d < 0", h, b); return OBF_ERR_INVALID_ARG; }
+      if ((b < m.N ? b : m.N) > max_budget) { set_error("budgets_host[%d] = %d exceeds max_budget %d", h, b, max_budget); return OBF_ERR_INVALID_ARG; }
+    }
+  } else {
+    if (budget < 0) { set_error("budget < 0"); return OBF_ERR_INVALID_ARG; }
+    if ((budget < m.N ? budget : m.N) > max_budget) { set_error("budget %d exceeds max_budget %d", budget, max_budget); return OBF_ERR_INVALID_ARG; }
+  }
+  return OBF_OK;
+}
+
+static obf_status_t run_score(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
+                              float* scores, double* row_lse, hipStream_t st) {
+  if (mfma_score_supported(m)) return launch_score_mfma(m, w, ws, K, Q, scores, row_lse, st);
+  return launch_score_generic(m, w, ws, K, Q, scores, row_lse, st);
+}
+
+}  // namespace obf
+
+using namespace obf;
+
+#define OBF_TRY(expr) do { obf_status_t _s = (expr); if (_s != OBF_OK) return _s; } while (0)
+#define OBF_NONNULL(p) do { if (!(p)) { set_error(#p " is NULL"); return OBF_ERR_INVALID_ARG; } } while (0)
+
+extern "C" {
+
+const char* obf_last_error(void) { return g_err; }
+const char* obf_version(void) { return "obf_relay 0.1 (gfx950)"; }
+
+size_t obf_workspace_bytes(const obf_shape_t* shape, int32_t max_budget, int32_t rank) {
+  if (check_shape(shape) != OBF_OK || max_budget < 0 || rank < 0) return 0;
+  Dims m = make_dims(shape);
+  return carve(m, max_budget, rank).total;
+}
+
+obf_status_t obf_score(const obf_shape_t* shape, const void* K, const void* Qwin, float* scores,
+                       double* row_lse, void* ws, size_t ws_bytes, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(K); OBF_NONNULL(Qwin); OBF_NONNULL(scores);
+  Dims m = make_dims(shape);
+  Workspace w = carve(m, 0, 0);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  if (!row_lse) row_lse = (double*)((char*)ws + w.row_lse);
+  return run_score(m, w, (char*)ws, K, Qwin, scores, row_lse, (hipStream_t)stream);
+}
+
+obf_status_t obf_select_topk(const obf_shape_t* shape, const float* scores, const int32_t* budgets_host,
+                             int32_t budget, int32_t max_budget, int32_t* idx, int32_t* n_keep,
+                             void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(scores); OBF_NONNULL(idx); OBF_NONNULL(n_keep);
+  Dims m = make_dims(shape);
+  OBF_TRY(check_budget(m, budgets_host, budget, max_budget));
+  return launch_select(m, scores, budgets_host, budget, max_budget, idx, n_keep, (hipStream_t)stream);
+}
+
+obf_status_t obf_refine_boundary(const obf_shape_t* shape, const void* K, const void* Qwin, const float* scores,
+                                 const double* row_lse, int32_t max_budget, int32_t* idx, const int32_t* n_keep,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(K); OBF_NONNULL(Qwin); OBF_NONNULL(scores); OBF_NONNULL(row_lse); OBF_NONNULL(idx); OBF_NONNULL(n_keep);
+  if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }
+  Dims m = make_dims(shape);
+  Workspace w = carve(m, max_budget, 0);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  return launch_refine(m, w, (char*)ws, K, Qwin, scores, row_lse, max_budget, idx, n_keep, (hipStream_t)stream);
+}
+
+obf_status_t obf_gather(const obf_shape_t* shape, const void* K, const void* V, const int32_t* idx,
+                        const int32_t* n_keep, int32_t max_budget, void* K_out, void* V_out, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(idx); OBF_NONNULL(n_keep);
+  if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }
+  if (K_out && !K) { set_error("K_out given but K is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (V_out && !V) { set_error("V_out given but V is NULL"); return OBF_ERR_INVALID_ARG; }
+  Dims m = make_dims(shape);
+  return launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, (hipStream_t)stream);
+}
+
+obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* scores, const int32_t* idx,
+                          const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
+                          float* delta_out, obf_diag_t* diag, void* ws, size_t ws_bytes, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(V); OBF_NONNULL(scores); OBF_NONNULL(idx); OBF_NONNULL(n_keep); OBF_NONNULL(V_out);
+  if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }
+  if (rank < 0) { set_error("rank < 0"); return OBF_ERR_INVALID_ARG; }
+  Dims m = make_dims(shape);
+  Workspace w = carve(m, max_budget, rank);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  return launch_backfill(m, w, (char*)ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag,
+                         (hipStream_t)stream);
+}
+
+obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                float* scores_out, float* delta_out, obf_diag_t* diag,
+                                void* ws, size_t ws_bytes, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(Qwin); OBF_NONNULL(K_out); OBF_NONNULL(V_out);
+  OBF_NONNULL(idx); OBF_NONNULL(n_keep);
+  if (rank < 0) { set_error("rank < 0"); return OBF_ERR_INVALID_ARG; }
+  Dims m = make_dims(shape);
+  OBF_TRY(check_budget(m, budgets_host, budget, max_budget));
+  Workspace w = carve(m, max_budget, rank);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  char* base = (char*)ws;
+  hipStream_t st = (hipStream_t)stream;
+  float* scores = scores_out ? scores_out : (float*)(base + w.scores);
+  double* row_lse = (double*)(base + w.row_lse);
+  OBF_TRY(run_score(m, w, base, K, Qwin, scores, row_lse, st));
+  OBF_TRY(launch_select(m, scores, budgets_host, budget, max_budget, idx, n_keep, st));
+  OBF_TRY(launch_refine(m, w, base, K, Qwin, scores, row_lse, max_budget, idx, n_keep, st));
+  OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st));
+  OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st));
+  return OBF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,642 @@
+// Orthogonal BackFill (Sec. 4.4, Eq. 2-7; Alg. 3 lines 3-10) on one GPU.
+//
+//   keep_basis : per head, demand sums (Eq. 6), dimension r and an orthonormal basis Q of the span of
+//                the retained values (Eq. 2).  r == d means the orthogonal complement is {0}: the
+//                residual of Eq. 3 vanishes identically and the head is left as plain eviction.
+//   del_stats  : for heads that still need it, one streaming pass over V accumulating the Gram
+//                matrix V_del^T V_del, the mass-weighted sum of deleted values and ||V_del||_F^2.
+//                R itself (Eq. 3) is never materialised: R^T R = P (V_del^T V_del) P and
+//                sum_j w_j R_j = P sum_j w_j V_j with P = I - Q Q^T.
+//   finalize   : per head, P G P, its leading eigenvectors C (the top right singular vectors of R,
+//                App. H: same subspace as the SVD of R), rbar (Eq. 4), Delta (Eq. 5), delta (Eq. 6).
+//   inject     : V* = V_keep + delta on every retained row (Eq. 7), rounded once to the I/O dtype.
+#include "common.hpp"
+
+namespace obf {
+
+constexpr int KB_THREADS = 256;
+constexpr int KB_WAVES = KB_THREADS / 64;
+constexpr double kRankEps = 1.1920928955078125e-07;   // 2^-23, the rank rule's epsilon
+constexpr float kRcrSkip = 1.0e-6f;                   // "||R||_F negligible": ||R||^2 <= 1e-6 ||V_del||^2
+constexpr float kEigFloor = 1.0e-6f;                  // resolution of the fp32 residual Gram (relative)
+
+// ------------------------------------------------------------------------------------------------
+// small block helpers (KB_THREADS threads)
+__device__ __forceinline__ double wave_sum(double v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+__device__ __forceinline__ double block_sum(double v, double* red /*[KB_WAVES]*/) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  double s = 0.0;
+  for (int i = 0; i < KB_WAVES; ++i) s += red[i];
+  return s;
+}
+
+// Pivoted modified Gram-Schmidt on the m rows (dimension d) of W in LDS, double precision.
+// Rows are orthonormalised in place in pivot order; returns the number of rows whose remaining
+// norm exceeded thr_abs.  rows 0..r-1 of W are the basis on exit.
+__device__ int pivoted_mgs(double* W, int m, int d, double thr_abs, double* red, int* ired) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ double nrm2[128];
+  int r = 0;
+  for (int k = 0; k < m; ++k) {
+    // remaining squared norms, recomputed every step (no downdating drift)
+    for (int i = k + wave; i < m; i += KB_WAVES) {
+      double s = 0.0;
+      for (int c = lane; c < d; c += 64) { const double x = W[i * d + c]; s += x * x; }
+      s = wave_sum(s);
+      if (lane == 0) nrm2[i] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int p = k; double best = nrm2[k];
+      for (int i = k + 1; i < m; ++i) if (nrm2[i] > best) { best = nrm2[i]; p = i; }   // first maximum
+      ired[0] = p; red[0] = best;
+    }
+    __syncthreads();
+    const int p = ired[0];
+    const double best = red[0];
+    if (!(sqrt(best) > thr_abs)) break;
+    const double inv = 1.0 / sqrt(best);
+    // swap rows p and k, normalise row k
+    for (int c = threadIdx.x; c < d; c += KB_THREADS) {
+      const double a = W[p * d + c], b = W[k * d + c];
+      W[p * d + c] = b; W[k * d + c] = a * inv;
+    }
+    __syncthreads();
+    // remove the new direction from the remaining rows (twice: keeps orthogonality at double precision)
+    for (int pass = 0; pass < 2; ++pass) {
+      for (int i = k + 1 + wave; i < m; i += KB_WAVES) {
+        double s = 0.0;
+        for (int c = lane; c < d; c += 64) s += W[i * d + c] * W[k * d + c];
+        s = wave_sum(s);
+        for (int c = lane; c < d; c += 64) W[i * d + c] -= s * W[k * d + c];
+      }
+      __syncthreads();
+    }
+    r = k + 1;
+  }
+  __syncthreads();
+  return r;
+}
+
+// Largest singular value of the m x d matrix W (LDS, double) by power iteration on W^T W.
+__device__ double sigma_max_est(const double* W, int m, int d, double* x /*[d]*/, double* y /*[m]*/, double* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int c = threadIdx.x; c < d; c += KB_THREADS) x[c] = 1.0 / sqrt((double)d) * (1.0 + 0.01 * (c % 7));
+  __syncthreads();
+  double lam = 0.0;
+  for (int it = 0; it < 24; ++it) {
+    for (int i = wave; i < m; i += KB_WAVES) {
+      double s = 0.0;
+      for (int c = lane; c < d; c += 64) s += W[i * d + c] * x[c];
+      s = wave_sum(s);
+      if (lane == 0) y[i] = s;
+    }
+    __syncthreads();
+    double part = 0.0;
+    for (int c = threadIdx.x; c < d; c += KB_THREADS) {
+      double s = 0.0;
+      for (int i = 0; i < m; ++i) s += W[i * d + c] * y[i];
+      x[c] = s;
+      part += s * s;
+    }
+    const double n2 = block_sum(part, red);     // ||W^T W x||^2 with ||x|| = 1
+    lam = sqrt(n2);                             // -> lambda_max(W^T W)
+    if (!(lam > 0.0)) break;
+    const double inv = 1.0 / lam;
+    for (int c = threadIdx.x; c < d; c += KB_THREADS) x[c] *= inv;
+    __syncthreads();
+  }
+  return sqrt(lam);
+}
+
+// ------------------------------------------------------------------------------------------------
+// keep_basis
+template <typename T>
+__global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restrict__ V, const float* __restrict__ scores,
+                                                              const int32_t* __restrict__ idx,
+                                                              const int32_t* __restrict__ n_keep, int N, int d,
+                                                              int max_budget, int rank, HeadState* __restrict__ state,
+                                                              float* __restrict__ basis) {
+  extern __shared__ double W[];            // [d][d] doubles (rows: vectors being orthonormalised / Gram)
+  __shared__ double red[KB_WAVES];
+  __shared__ int ired[2];
+  __shared__ double xv[128], yv[128];
+  __shared__ int perm[128];
+  const int head = blockIdx.x;
+  const int n = n_keep[head];
+  const int n_del = N - n;
+  const float* sc = scores + (size_t)head * N;
+  const int32_t* id = idx + (size_t)head * max_budget;
+  const T* Vh = V + (size_t)head * N * d;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // demand sums of Eq. 6, in double, fixed summation order
+  double pk = 0.0, pt = 0.0;
+  for (int i = threadIdx.x; i < n; i += KB_THREADS) pk += (double)sc[id[i]];
+  for (int i = threadIdx.x; i < N; i += KB_THREADS) pt += (double)sc[i];
+  const double a_keep = block_sum(pk, red);
+  const double a_tot = block_sum(pt, red);
+  double a_del = a_tot - a_keep;
+  if (a_del < 0.0) a_del = 0.0;
+
+  int r_keep = 0, active = 0;
+  if (rank > 0 && n > 0 && n_del > 0) {
+    if (n <= d) {
+      // rows of V_keep straight into LDS
+      for (int e = threadIdx.x; e < n * d; e += KB_THREADS) {
+        const int i = e / d, c = e - i * d;
+        W[e] = (double)Elem<T>::load(Vh + (size_t)id[i] * d + c);
+      }
+      __syncthreads();
+      const double smax = sigma_max_est(W, n, d, xv, yv, red);
+      const double thr = smax * (double)max(n, d) * kRankEps;
+      r_keep = pivoted_mgs(W, n, d, thr, red, ired);
+    } else {
+      // n > d: Gram matrix of the retained rows in double (inputs are exact, products exact),
+      // diagonally pivoted Cholesky for the rank, then the rows of the factor span the row space.
+      const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;     // 16 x 16 threads, (d/16)^2 outputs each
+      const int bs = d / 16;
+      double acc[8][8];
+      for (int a = 0; a < 8; ++a) for (int b = 0; b < 8; ++b) acc[a][b] = 0.0;
+      float* rowbuf = (float*)W;                                   // [16][d] staging (W is free until the end)
+      for (int i0 = 0; i0 < n; i0 += 16) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < 16 * d; e += KB_THREADS) {
+          const int i = e / d, c = e - i * d;
+          rowbuf[e] = (i0 + i < n) ? Elem<T>::load(Vh + (size_t)id[i0 + i] * d + c) : 0.0f;
+        }
+        __syncthreads();
+        for (int i = 0; i < 16; ++i) {
+          double av[8], bv[8];
+          for (int a = 0; a < bs; ++a) av[a] = (double)rowbuf[i * d + ty * bs + a];
+          for (int b = 0; b < bs; ++b) bv[b] = (double)rowbuf[i * d + tx * bs + b];
+          for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
+        }
+      }
+      __syncthreads();
+      for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) W[(ty * bs + a) * d + tx * bs + b] = acc[a][b];
+      __syncthreads();
+      // sigma_max^2 = lambda_max(G): power iteration on G
+      for (int c = threadIdx.x; c < d; c += KB_THREADS) xv[c] = 1.0 / sqrt((double)d) * (1.0 + 0.01 * (c % 7));
+      __syncthreads();
+      double lam = 0.0;
+      for (int it = 0; it < 24; ++it) {
+        double part = 0.0;
+        for (int a = threadIdx.x; a < d; a += KB_THREADS) {
+          double s = 0.0;
+          for (int c = 0; c < d; ++c) s += W[a * d + c] * xv[c];
+          yv[a] = s; part += s * s;
+        }
+        const double n2 = block_sum(part, red);
+        lam = sqrt(n2);
+        if (!(lam > 0.0)) break;
+        for (int a = threadIdx.x; a < d; a += KB_THREADS) xv[a] = yv[a] / lam;
+        __syncthreads();
+      }
+      const double smax = sqrt(lam);
+      const double thr = smax * (double)max(n, d) * kRankEps;     // on singular values
+      // diagonally pivoted Cholesky, upper factor kept in the upper triangle (row k, columns >= k)
+      for (int c = threadIdx.x; c < d; c += KB_THREADS) perm[c] = c;
+      __syncthreads();
+      int r = 0;
+      for (int k = 0; k < d; ++k) {
+        if (threadIdx.x == 0) {
+          int p = k; double best = W[k * d + k];
+          for (int i = k + 1; i < d; ++i) if (W[i * d + i] > best) { best = W[i * d + i]; p = i; }
+          ired[0] = p; red[0] = best;
+        }
+        __syncthreads();
+        const int p = ired[0];
+        const double piv = red[0];
+        if (!(piv > 0.0) || !(sqrt(piv) > thr)) break;
+        if (p != k) {   // symmetric swap of rows/columns p and k
+          for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[k * d + c]; W[k * d + c] = W[p * d + c]; W[p * d + c] = t; }
+          __syncthreads();
+          for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[c * d + k]; W[c * d + k] = W[c * d + p]; W[c * d + p] = t; }
+          if (threadIdx.x == 0) { const int t = perm[k]; perm[k] = perm[p]; perm[p] = t; }
+          __syncthreads();
+        }
+        const double rkk = sqrt(piv);
+        for (int c = k + threadIdx.x; c < d; c += KB_THREADS) W[k * d + c] = W[k * d + c] / rkk;   // row k of the factor
+        __syncthreads();
+        // trailing update: G[i][j] -= R[k][i] R[k][j] for i, j > k
+        const int rem = d - k - 1;
+        for (int e = threadIdx.x; e < rem * rem; e += KB_THREADS) {
+          const int i = k + 1 + e / rem, j = k + 1 + e % rem;
+          W[i * d + j] -= W[k * d + i] * W[k * d + j];
+        }
+        __syncthreads();
+        r = k + 1;
+      }
+      __syncthreads();
+      r_keep = r;
+      if (r_keep < d) {
+        // rows 0..r-1 of the factor (zero left of the diagonal), columns back in original order
+        for (int e = threadIdx.x; e < d * d; e += KB_THREADS) {
+          const int i = e / d, c = e - i * d;
+          if (i >= r_keep || c < i) W[e] = 0.0;
+        }
+        __syncthreads();
+        // un-permute columns: out[:, perm[c]] = in[:, c]; done row by row through yv
+        for (int i = 0; i < r_keep; ++i) {
+          for (int c = threadIdx.x; c < d; c += KB_THREADS) yv[perm[c]] = W[i * d + c];
+          __syncthreads();
+          for (int c = threadIdx.x; c < d; c += KB_THREADS) W[i * d + c] = yv[c];
+          __syncthreads();
+        }
+        r_keep = pivoted_mgs(W, r_keep, d, thr, red, ired);
+      }
+    }
+    active = (r_keep < d) ? 1 : 0;
+    if (active) {
+      float* bh = basis + (size_t)head * d * d;
+      for (int e = threadIdx.x; e < r_keep * d; e += KB_THREADS) bh[e] = (float)W[e];
+    }
+  }
+  (void)lane; (void)wave;
+  if (threadIdx.x == 0) {
+    HeadState s;
+    s.a_keep = a_keep; s.a_del = a_del; s.n_keep = n; s.n_del = n_del; s.r_keep = r_keep; s.active = active;
+    s.k_used = 0; s.pad = 0; s.rcr = 0.f; s.ivn = 0.f;
+    state[head] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// del_stats: partial V_del^T V_del, sum_j A_j v_j and ||V_del||^2 over one chunk of tokens
+constexpr int DS_THREADS = 256;
+constexpr int DS_TOK = 32;
+
+template <typename T>
+__global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict__ V, const float* __restrict__ scores,
+                                                             const int32_t* __restrict__ idx, int N, int d,
+                                                             int max_budget, int nstat,
+                                                             const HeadState* __restrict__ state,
+                                                             float* __restrict__ gram_part) {
+  const int head = blockIdx.y, chunk = blockIdx.x;
+  if (!state[head].active) return;
+  extern __shared__ float Vs[];              // [DS_TOK][d], retained rows zeroed
+  __shared__ float wt[DS_TOK];               // score of the token (0 for rows that are not deleted)
+  __shared__ int isdel[DS_TOK];              // 1: deleted row of this chunk
+  const int n = state[head].n_keep;
+  const int32_t* id = idx + (size_t)head * max_budget;
+  const T* Vh = V + (size_t)head * N * d;
+  const float* sc = scores + (size_t)head * N;
+  const int t0 = chunk * kStatChunk, t1 = min(N, t0 + kStatChunk);
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int bs = d / 16;
+  float acc[8][8];
+  for (int a = 0; a < 8; ++a) for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
+  float u = 0.f, nn = 0.f;                   // threads < d: weighted column sum; all: squared norm share
+
+  for (int tt = t0; tt < t1; tt += DS_TOK) {
+    __syncthreads();
+    if (threadIdx.x < DS_TOK) {
+      const int j = tt + threadIdx.x;
+      float wgt = 0.f;
+      int del = 0;
+      if (j < t1) {
+        int lo = 0, hi = n;                  // is j in the ascending retained list?
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (id[mid] < j) lo = mid + 1; else hi = mid; }
+        del = !(lo < n && id[lo] == j);
+        wgt = del ? sc[j] : 0.f;
+      }
+      wt[threadIdx.x] = wgt;
+      isdel[threadIdx.x] = del;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < DS_TOK * d; e += DS_THREADS) {
+      const int i = e / d, c = e - i * d;
+      Vs[e] = isdel[i] ? Elem<T>::load(Vh + (size_t)(tt + i) * d + c) : 0.f;
+    }
+    __syncthreads();
+    for (int i = 0; i < DS_TOK; ++i) {
+      float av[8], bv[8];
+      for (int a = 0; a < bs; ++a) av[a] = Vs[i * d + ty * bs + a];
+      for (int b = 0; b < bs; ++b) bv[b] = Vs[i * d + tx * bs + b];
+      for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) acc[a][b] = fmaf(av[a], bv[b], acc[a][b]);
+    }
+    if ((int)threadIdx.x < d) {
+      for (int i = 0; i < DS_TOK; ++i) {
+        const float x = Vs[i * d + threadIdx.x];
+        const float wgt = wt[i];
+        u = fmaf(wgt, x, u);
+        nn = fmaf(x, x, nn);
+      }
+    }
+  }
+  float* out = gram_part + ((size_t)head * nstat + chunk) * ((size_t)d * d + d + 4);
+  for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) out[(ty * bs + a) * d + tx * bs + b] = acc[a][b];
+  if ((int)threadIdx.x < d) { out[d * d + threadIdx.x] = u; }
+  // ||V_del||^2 of the chunk: sum over the d column shares, fixed order
+  __shared__ float nsh[128];
+  __syncthreads();
+  if ((int)threadIdx.x < d) nsh[threadIdx.x] = nn;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int c = 0; c < d; ++c) s += (double)nsh[c];
+    out[d * d + d] = (float)s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// finalize: per head, everything after the streaming pass
+constexpr int FN_THREADS = 1024;
+constexpr int FN_WAVES = FN_THREADS / 64;
+constexpr int FN_SWEEPS = 12;
+
+__global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int nstat, int rank,
+                                                            HeadState* __restrict__ state,
+                                                            const float* __restrict__ basis,
+                                                            const float* __restrict__ gram_part,
+                                                            float* __restrict__ mats, float* __restrict__ delta,
+                                                            float* __restrict__ delta_out, obf_diag_t* __restrict__ diag) {
+  extern __shared__ float sm[];
+  const int head = blockIdx.x;
+  const int ld = d + 1;
+  float* M = sm;                    // [d][ld]   P G P, then its diagonal form
+  float* U = sm + d * ld;           // [d][ld]   accumulated rotations (columns = eigenvectors)
+  __shared__ float cs[64], sn[64];
+  __shared__ int pp[64], qq[64];
+  __shared__ float uvec[128], rbar[128], dvec[128], lamv[128];
+  __shared__ int order[128];
+  __shared__ float fred[FN_WAVES];
+  __shared__ int s_k;
+  __shared__ float s_off;
+  HeadState st = state[head];
+  int skipped = 1;
+  float rcr = 0.f, ivn = 0.f;
+  int k_used = 0;
+  const int tid = threadIdx.x;
+
+  if (st.active) {
+    const int r = st.r_keep;
+    const float* Qb = basis + (size_t)head * d * d;            // [r][d] orthonormal rows
+    const size_t pstride = (size_t)d * d + d + 4;
+    const float* gp = gram_part + (size_t)head * nstat * pstride;
+    float* T1 = mats + (size_t)head * 3 * d * d;               // [d][r] scratch in global memory
+
+    // G = sum of chunk partials (fixed order), u, ||V_del||^2
+    for (int e = tid; e < d * d; e += FN_THREADS) {
+      float s = 0.f;
+      for (int c = 0; c < nstat; ++c) s += gp[c * pstride + e];
+      M[(e / d) * ld + (e % d)] = s;
+    }
+    if (tid < d) {
+      float s = 0.f;
+      for (int c = 0; c < nstat; ++c) s += gp[c * pstride + d * d + tid];
+      uvec[tid] = s;
+    }
+    float vd2 = 0.f;
+    for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + d];
+    __syncthreads();
+
+    // M <- G P  with P = I - Q^T Q (Q rows orthonormal):  T1 = G Q^T (d x r);  M -= T1 Q
+    for (int e = tid; e < d * r; e += FN_THREADS) {
+      const int a = e / r, i = e - a * r;
+      float s = 0.f;
+      for (int c = 0; c < d; ++c) s = fmaf(M[a * ld + c], Qb[i * d + c], s);
+      T1[e] = s;
+    }
+    __syncthreads();
+    for (int e = tid; e < d * d; e += FN_THREADS) {
+      const int a = e / d, b = e - a * d;
+      float s = 0.f;
+      for (int i = 0; i < r; ++i) s = fmaf(T1[a * r + i], Qb[i * d + b], s);
+      M[a * ld + b] -= s;
+    }
+    __syncthreads();
+    // M <- P M:  T2 = Q M (r x d);  M -= Q^T T2
+    for (int e = tid; e < r * d; e += FN_THREADS) {
+      const int i = e / d, b = e - i * d;
+      float s = 0.f;
+      for (int a = 0; a < d; ++a) s = fmaf(Qb[i * d + a], M[a * ld + b], s);
+      T1[e] = s;
+    }
+    __syncthreads();
+    for (int e = tid; e < d * d; e += FN_THREADS) {
+      const int a = e / d, b = e - a * d;
+      float s = 0.f;
+      for (int i = 0; i < r; ++i) s = fmaf(Qb[i * d + a], T1[i * d + b], s);
+      M[a * ld + b] -= s;
+    }
+    __syncthreads();
+    // symmetrise, U = I, trace
+    for (int e = tid; e < d * d; e += FN_THREADS) {
+      const int a = e / d, b = e - a * d;
+      if (a < b) { const float v = 0.5f * (M[a * ld + b] + M[b * ld + a]); M[a * ld + b] = v; M[b * ld + a] = v; }
+      U[a * ld + b] = (a == b) ? 1.f : 0.f;
+    }
+    __syncthreads();
+    if (tid == 0) { double tr = 0.0; for (int a = 0; a < d; ++a) tr += (double)M[a * ld + a]; s_off = (float)tr; }
+    __syncthreads();
+    const float res2 = s_off;
+    rcr = res2 / (vd2 + 1e-12f);
+    const bool negligible = !(res2 > kRcrSkip * vd2);
+
+    if (!negligible) {
+      // cyclic Jacobi with a round-robin ordering: d/2 disjoint rotations per round
+      const int half = d / 2;
+      for (int sweep = 0; sweep < FN_SWEEPS; ++sweep) {
+        for (int round = 0; round < d - 1; ++round) {
+          if (tid < half) {
+            int p, q;
+            if (tid == 0) { p = d - 1; q = round; }
+            else { p = (round + tid) % (d - 1); q = (round - tid + (d - 1)) % (d - 1); }
+            if (p > q) { const int t = p; p = q; q = t; }
+            const float app = M[p * ld + p], aqq = M[q * ld + q], apq = M[p * ld + q];
+            float c = 1.f, s = 0.f;
+            if (fabsf(apq) > 1e-30f && fabsf(apq) > 1e-9f * sqrtf(fabsf(app * aqq)) ) {
+              const float tau = (aqq - app) / (2.f * apq);
+              const float t = ((tau >= 0.f) ? 1.f : -1.f) / (fabsf(tau) + sqrtf(1.f + tau * tau));
+              c = 1.f / sqrtf(1.f + t * t);
+              s = t * c;
+            }
+            pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
+          }
+          __syncthreads();
+          // columns: M <- M J, U <- U J
+          for (int e = tid; e < half * d; e += FN_THREADS) {
+            const int i = e / d, k = e - i * d;
+            const int p = pp[i], q = qq[i];
+            const float c = cs[i], s = sn[i];
+            const float mp = M[k * ld + p], mq = M[k * ld + q];
+            M[k * ld + p] = c * mp - s * mq;
+            M[k * ld + q] = s * mp + c * mq;
+            const float up = U[k * ld + p], uq = U[k * ld + q];
+            U[k * ld + p] = c * up - s * uq;
+            U[k * ld + q] = s * up + c * uq;
+          }
+          __syncthreads();
+          // rows: M <- J^T M
+          for (int e = tid; e < half * d; e += FN_THREADS) {
+            const int i = e / d, k = e - i * d;
+            const int p = pp[i], q = qq[i];
+            const float c = cs[i], s = sn[i];
+            const float mp = M[p * ld + k], mq = M[q * ld + k];
+            M[p * ld + k] = c * mp - s * mq;
+            M[q * ld + k] = s * mp + c * mq;
+          }
+          __syncthreads();
+        }
+        // off-diagonal energy; stop when it is below single-precision noise of the trace
+        float off = 0.f;
+        for (int e = tid; e < d * d; e += FN_THREADS) {
+          const int a = e / d, b = e - a * d;
+          if (a != b) { const float v = M[a * ld + b]; off = fmaf(v, v, off); }
+        }
+        for (int o = 32; o > 0; o >>= 1) off += __shfl_xor(off, o);
+        if ((tid & 63) == 0) fred[tid >> 6] = off;
+        __syncthreads();
+        if (tid == 0) { float s = 0.f; for (int i = 0; i < FN_WAVES; ++i) s += fred[i]; s_off = s; }
+        __syncthreads();
+        const float offn = s_off;
+        __syncthreads();
+        if (offn <= 1e-13f * res2 * res2) break;
+      }
+      // eigenvalues, descending order (ties: lower index first), numerical rank of R
+      if (tid < d) lamv[tid] = M[tid * ld + tid];
+      __syncthreads();
+      if (tid < d) {
+        const float mine = lamv[tid];
+        int rk = 0;
+        for (int j = 0; j < d; ++j) { const float o = lamv[j]; rk += (o > mine) || (o == mine && j < tid); }
+        order[rk] = tid;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        const float lmax = lamv[order[0]];
+        const float srel = (float)max(st.n_del, d) * (float)kRankEps;
+        const float floor_rel = fmaxf(srel * srel, kEigFloor);
+        int rankR = 0;
+        for (int j = 0; j < d; ++j) if (lamv[order[j]] > lmax * floor_rel) ++rankR;
+        const int cap = min(min(st.n_del, d - r), d);
+        if (rankR > cap) rankR = cap;
+        s_k = min(rank, rankR);
+      }
+      __syncthreads();
+      k_used = s_k;
+      if (k_used > 0) {
+        // rbar = P u / (a_del + eps)   (Eq. 4 with R_j = P v_j)
+        if (tid < r) {
+          float s = 0.f;
+          for (int c = 0; c < d; ++c) s = fmaf(Qb[tid * d + c], uvec[c], s);
+          lamv[tid] = s;                                   // reuse: coefficients q_i . u   (r <= d-1 entries)
+        }
+        __syncthreads();
+        if (tid < d) {
+          float s = uvec[tid];
+          for (int i = 0; i < r; ++i) s = fmaf(-lamv[i], Qb[i * d + tid], s);
+          rbar[tid] = (float)((double)s / (st.a_del + kEps));
+        }
+        __syncthreads();
+        // Delta = sum_i (rbar . c_i) c_i   (Eq. 5), c_i = column order[i] of U
+        if (tid < k_used) {
+          const int col = order[tid];
+          float s = 0.f;
+          for (int c = 0; c < d; ++c) s = fmaf(rbar[c], U[c * ld + col], s);
+          dvec[tid] = s;                                   // coefficient
+        }
+        __syncthreads();
+        if (tid < d) {
+          float s = 0.f;
+          for (int i = 0; i < k_used; ++i) s = fmaf(dvec[i], U[tid * ld + order[i]], s);
+          const double alpha = st.a_del / (st.a_keep + kEps);          // Eq. 6
+          uvec[tid] = (float)(alpha * (double)s);
+        }
+        __syncthreads();
+        if (tid == 0) { double s = 0.0; for (int c = 0; c < d; ++c) s += (double)uvec[c] * uvec[c]; s_off = (float)sqrt(s); }
+        __syncthreads();
+        ivn = s_off;
+        skipped = 0;
+      }
+    }
+  }
+  // outputs for every head
+  if (tid < d) {
+    const float v = skipped ? 0.f : uvec[tid];
+    delta[(size_t)head * d + tid] = v;
+    if (delta_out) delta_out[(size_t)head * d + tid] = v;
+  }
+  if (tid == 0) {
+    st.active = skipped ? 0 : 1;
+    st.k_used = k_used; st.rcr = rcr; st.ivn = ivn;
+    state[head] = st;
+    if (diag) {
+      obf_diag_t dg;
+      dg.n_keep = st.n_keep; dg.r_keep = st.r_keep; dg.k_used = k_used; dg.skipped = skipped;
+      dg.a_keep = (float)st.a_keep; dg.a_del = (float)st.a_del; dg.rcr = rcr; dg.ivn = ivn;
+      diag[head] = dg;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// inject: V_out[row] += delta for the retained rows of heads that were not skipped (Eq. 7)
+template <typename T>
+__global__ void k_bf_inject(T* __restrict__ V_out, const float* __restrict__ delta, const HeadState* __restrict__ state,
+                            int d, int max_budget) {
+  const int head = blockIdx.y;
+  const HeadState* s = state + head;
+  if (!s->active) return;
+  const int n = s->n_keep;
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n * d) return;
+  const int c = e % d;
+  T* p = V_out + (size_t)head * max_budget * d + e;
+  Elem<T>::store(p, Elem<T>::load(p) + delta[(size_t)head * d + c]);
+}
+
+template <typename T>
+static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
+                        const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
+                        float* delta_out, obf_diag_t* diag, hipStream_t st) {
+  HeadState* state = (HeadState*)(ws + w.head_state);
+  float* basis = (float*)(ws + w.basis);
+  float* gram_part = (float*)(ws + w.gram_part);
+  float* mats = (float*)(ws + w.mats);
+  float* delta = (float*)(ws + w.delta);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
+    (void)hipFuncSetAttribute((const void*)k_bf_finalize, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
+    attr_done = true;
+  }
+  const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
+  hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
+                     m.N, m.d, max_budget, rank, state, basis);
+  if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
+  if (rank > 0) {
+    hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
+                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part);
+    if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
+  }
+  hipLaunchKernelGGL(k_bf_finalize, dim3(m.heads), dim3(FN_THREADS), sizeof(float) * 2 * m.d * (m.d + 1), st, m.N, m.d,
+                     w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag);
+  if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
+  if (rank > 0 && max_budget > 0) {
+    const int per = max_budget * m.d;
+    hipLaunchKernelGGL(k_bf_inject<T>, dim3((per + 255) / 256, m.heads), dim3(256), 0, st, (T*)V_out, delta, state, m.d,
+                       max_budget);
+    if (check_launch("backfill inject") != OBF_OK) return OBF_ERR_HIP;
+  }
+  return OBF_OK;
+}
+
+obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
+                             const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st) {
+  if (m.dtype == OBF_BF16)
+    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st);
+  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st);
+}
+
+}  // namespace obf

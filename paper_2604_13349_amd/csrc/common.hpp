@@ -1,0 +1,125 @@
+// Internal declarations shared by the translation units of libobf_relay.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "obf_relay.h"
+
+namespace obf {
+
+constexpr int kMaxTokens = 32768;
+constexpr int kScoreChunk = 512;        // tokens per score workgroup
+constexpr int kStatChunk = 1024;        // tokens per deleted-value statistics workgroup
+constexpr int kBandCap = 256;           // most boundary candidates re-scored per head
+constexpr double kEps = 1e-12;          // epsilon of Eq. 4 / Eq. 6
+constexpr float kBandRel = 1.0e-4f;     // relative half-width of the refinement band
+
+struct Dims {
+  int heads;      // n_layers * n_kv_heads
+  int L, H, g, d, N, W;
+  int R;          // query rows per KV head = g * W
+  int dtype;
+  int esize;      // bytes per element of K/V/Q
+};
+
+inline Dims make_dims(const obf_shape_t* s) {
+  Dims m;
+  m.L = s->n_layers; m.H = s->n_kv_heads; m.g = s->group; m.d = s->head_dim; m.N = s->n_tokens; m.W = s->window;
+  m.heads = m.L * m.H; m.R = m.g * m.W; m.dtype = s->dtype; m.esize = (s->dtype == OBF_BF16) ? 2 : 4;
+  return m;
+}
+
+// Workspace carving.  Every region is 256-byte aligned; offsets are from the workspace base.
+struct Workspace {
+  size_t stats_part;   // double2 [heads][nchunk][R]      partial (max, sum-exp) per score chunk
+  size_t row_lse;      // double  [heads][R]
+  size_t lse_corr;     // int64   [heads][R]              fixed-point corrections of sum-exp (MFMA path)
+  size_t scores;       // float   [heads][N]              (fused call without scores_out)
+  size_t budgets;      // unused placeholder kept for alignment
+  size_t head_state;   // HeadState [heads]
+  size_t basis;        // float   [heads][d][d]           orthonormal basis of the retained span (columns)
+  size_t gram_part;    // float   [heads][nstat][d*d+d+4] partial Gram / weighted sum / norms of V_del
+  size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
+  size_t delta;        // float   [heads][d]
+  size_t band;         // BandEntry [heads][kBandCap]
+  size_t total;
+  int nchunk;          // score chunks per head
+  int nstat;           // statistics chunks per head
+};
+
+struct HeadState {
+  double a_keep, a_del;
+  int32_t n_keep, n_del;
+  int32_t r_keep;       // dimension of the retained span, -1 = not computed
+  int32_t active;       // 1: residual statistics and injection are needed
+  int32_t k_used;
+  int32_t pad;
+  float rcr, ivn;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+inline Workspace carve(const Dims& m, int max_budget, int rank) {
+  (void)max_budget; (void)rank;
+  Workspace w;
+  w.nchunk = (m.N + kScoreChunk - 1) / kScoreChunk;
+  w.nstat = (m.N + kStatChunk - 1) / kStatChunk;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  w.stats_part = take(sizeof(double) * 2 * (size_t)m.heads * w.nchunk * m.R);
+  w.row_lse = take(sizeof(double) * (size_t)m.heads * m.R);
+  w.lse_corr = take(sizeof(int64_t) * (size_t)m.heads * m.R);
+  w.scores = take(sizeof(float) * (size_t)m.heads * m.N);
+  w.budgets = take(256);
+  w.head_state = take(sizeof(HeadState) * (size_t)m.heads);
+  w.basis = take(sizeof(float) * (size_t)m.heads * m.d * m.d);
+  w.gram_part = take(sizeof(float) * (size_t)m.heads * w.nstat * ((size_t)m.d * m.d + m.d + 4));
+  w.mats = take(sizeof(float) * (size_t)m.heads * 3 * m.d * m.d);
+  w.delta = take(sizeof(float) * (size_t)m.heads * m.d);
+  w.band = take(16 * (size_t)m.heads * kBandCap);
+  w.total = off;
+  return w;
+}
+
+void set_error(const char* fmt, ...);
+obf_status_t check_launch(const char* what);
+
+// ---- device helpers -------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even float -> bf16 bits; NaN stays NaN
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  uint32_t lsb = (u >> 16) & 1u;
+  return (uint16_t)((u + 0x7fffu + lsb) >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {
+  static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
+  static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
+};
+
+// ---- stage launchers (each enqueues on `st`, returns OBF_OK or OBF_ERR_HIP) --------------
+obf_status_t launch_score_generic(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
+                                  float* scores, double* row_lse, hipStream_t st);
+bool mfma_score_supported(const Dims& m);
+obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
+                               float* scores, double* row_lse, hipStream_t st);
+obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
+                           int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st);
+obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
+                           const float* scores, const double* row_lse, int32_t max_budget, int32_t* idx,
+                           const int32_t* n_keep, hipStream_t st);
+obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const int32_t* idx, const int32_t* n_keep,
+                           int32_t max_budget, void* K_out, void* V_out, hipStream_t st);
+obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
+                             const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st);
+
+}  // namespace obf

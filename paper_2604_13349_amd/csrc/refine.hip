@@ -1,0 +1,153 @@
+// Boundary refinement of TopK_B.  The fast score path works in fp32; two tokens whose exact
+// attention masses (Eq. 1) differ by less than its error can come out in the wrong order at
+// the selection threshold.  Here the few tokens whose float score lies within a relative band
+// of the threshold are re-scored in double from the K / Qwin bits and the per-row
+// log-sum-exp, and the retained slots inside the band are re-assigned by that exact order
+// (ties to the lowest index).  Tokens outside the band keep their decision.
+#include "common.hpp"
+
+namespace obf {
+
+constexpr int RF_THREADS = 256;
+constexpr int RF_WAVES = RF_THREADS / 64;
+
+__device__ __forceinline__ int rf_block_exscan(int v, int& total, int* wsum) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+  for (int off = 1; off < 64; off <<= 1) {
+    const int x = __shfl_up(inc, off);
+    if (lane >= off) inc += x;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int pre = 0; total = 0;
+  for (int wv = 0; wv < RF_WAVES; ++wv) { if (wv < wave) pre += wsum[wv]; total += wsum[wv]; }
+  __syncthreads();
+  return pre + inc - v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, const T* __restrict__ Q,
+                                                       const float* __restrict__ scores,
+                                                       const double* __restrict__ row_lse, int N, int d, int R,
+                                                       int max_budget, int32_t* __restrict__ idx,
+                                                       const int32_t* __restrict__ n_keep) {
+  __shared__ uint32_t bitmap[kMaxTokens / 32];
+  __shared__ int band[kBandCap];
+  __shared__ double band_score[kBandCap];
+  __shared__ int keep_new[kBandCap];
+  __shared__ int wsum[RF_WAVES];
+  __shared__ float wred[RF_WAVES];
+  __shared__ int s_changed;
+  const int head = blockIdx.x;
+  const int n = n_keep[head];
+  if (n <= 0 || n >= N) return;
+  const float* sc = scores + (size_t)head * N;
+  int32_t* out = idx + (size_t)head * max_budget;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // 1. threshold = smallest retained score
+  float tmin = INFINITY;
+  for (int i = threadIdx.x; i < n; i += RF_THREADS) tmin = fminf(tmin, sc[out[i]]);
+  for (int off = 32; off > 0; off >>= 1) tmin = fminf(tmin, __shfl_xor(tmin, off));
+  if (lane == 0) wred[wave] = tmin;
+  if (threadIdx.x == 0) s_changed = 0;
+  __syncthreads();
+  float tau = wred[0];
+  for (int wv = 1; wv < RF_WAVES; ++wv) tau = fminf(tau, wred[wv]);
+  const float half = kBandRel * fabsf(tau);
+  const float lo = tau - half, hi = tau + half;
+
+  // 2. band tokens in index order
+  const int seg = (N + RF_THREADS - 1) / RF_THREADS;
+  const int b0 = min(N, (int)threadIdx.x * seg), b1 = min(N, b0 + seg);
+  int cnt = 0;
+  for (int i = b0; i < b1; ++i) { const float s = sc[i]; cnt += (s >= lo && s <= hi); }
+  int nband;
+  int pos = rf_block_exscan(cnt, nband, wsum);
+  if (nband <= 1 || nband > kBandCap) return;
+  for (int i = b0; i < b1; ++i) { const float s = sc[i]; if (s >= lo && s <= hi) band[pos++] = i; }
+
+  // 3. membership bitmap of the current retained set
+  const int words = (N + 31) / 32;
+  for (int i = threadIdx.x; i < words; i += RF_THREADS) bitmap[i] = 0u;
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += RF_THREADS) { const int j = out[i]; atomicOr(&bitmap[j >> 5], 1u << (j & 31)); }
+  __syncthreads();
+  int kb = 0;
+  if (threadIdx.x < nband) { const int j = band[threadIdx.x]; kb = (bitmap[j >> 5] >> (j & 31)) & 1u; }
+  int nkb;
+  rf_block_exscan(kb, nkb, wsum);
+  if (nkb == 0 || nkb == nband) return;
+
+  // 4. exact scores of the band tokens: one wave per token, lanes over query rows
+  const T* Kh = K + (size_t)head * N * d;
+  const T* Qh = Q + (size_t)head * R * d;
+  const double* lse = row_lse + (size_t)head * R;
+  const double scale = 1.0 / sqrt((double)d);
+  for (int b = wave; b < nband; b += RF_WAVES) {
+    const T* kr = Kh + (size_t)band[b] * d;
+    double part = 0.0;
+    for (int r = lane; r < R; r += 64) {
+      const T* qr = Qh + (size_t)r * d;
+      double acc = 0.0;
+      for (int c = 0; c < d; ++c) acc = fma((double)Elem<T>::load(qr + c), (double)Elem<T>::load(kr + c), acc);
+      part += exp(acc * scale - lse[r]);
+    }
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+    if (lane == 0) band_score[b] = part;
+  }
+  __syncthreads();
+
+  // 5. the nkb best band tokens (exact score descending, index ascending) are retained
+  if (threadIdx.x < nband) {
+    const double mine = band_score[threadIdx.x];
+    int rank = 0;
+    for (int u = 0; u < nband; ++u) {
+      const double o = band_score[u];
+      rank += (o > mine) || (o == mine && u < (int)threadIdx.x);     // band[] is ascending in index
+    }
+    const int keep = rank < nkb;
+    keep_new[threadIdx.x] = keep;
+    if (keep != kb) s_changed = 1;
+  }
+  __syncthreads();
+  if (!s_changed) return;
+  if (threadIdx.x < nband) {
+    const int j = band[threadIdx.x];
+    if (keep_new[threadIdx.x]) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+    else atomicAnd(&bitmap[j >> 5], ~(1u << (j & 31)));
+  }
+  __syncthreads();
+
+  // 6. rewrite the ascending index list from the bitmap
+  const int wseg = (words + RF_THREADS - 1) / RF_THREADS;
+  const int w0 = min(words, (int)threadIdx.x * wseg), w1 = min(words, w0 + wseg);
+  int pc = 0;
+  for (int wi = w0; wi < w1; ++wi) pc += __popc(bitmap[wi]);
+  int total;
+  int o = rf_block_exscan(pc, total, wsum);
+  for (int wi = w0; wi < w1; ++wi) {
+    uint32_t bits = bitmap[wi];
+    while (bits) {
+      const int bpos = __ffs(bits) - 1;
+      bits &= bits - 1;
+      out[o++] = wi * 32 + bpos;
+    }
+  }
+}
+
+obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
+                           const float* scores, const double* row_lse, int32_t max_budget, int32_t* idx,
+                           const int32_t* n_keep, hipStream_t st) {
+  (void)w; (void)ws;
+  if (m.dtype == OBF_BF16)
+    hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                       scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
+  else
+    hipLaunchKernelGGL(k_refine<float>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
+                       row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
+  return check_launch("refine");
+}
+
+}  // namespace obf

@@ -1,0 +1,167 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import obf_oracle as O
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_util
+    from paper_2604_13349_amd import binding
+    binding.load_library()          # no fallback: a missing library is an error, not a skip
+    return gpu_util
+
+
+def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None):
+    K, V, Q = si.make_cache(cfg, seed, threads=8)
+    bud = si.budgets(cfg, seed) if budgets is None else np.asarray(budgets, dtype=np.int32).reshape(cfg.n_layers, cfg.n_kv_heads)
+    rank = cfg.rank if rank is None else rank
+    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=max_budget)
+    reps = []
+    for l in range(cfg.n_layers):
+        for h in range(cfg.n_kv_heads):
+            ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), rank, cfg.dtype)
+            rep = parity.check_head(f"{cfg.name}[{l},{h}]", ref, K[l, h], V[l, h], cfg.dtype, int(bud[l, h]),
+                                    out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
+                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
+            reps.append(rep)
+    checked = [r for r in reps if r.v_checked]
+    assert len(checked) >= max(1, len(reps) // 2), "too few heads reached the value check"
+    if expect_active is True:
+        assert any(r.skipped == 0 for r in checked), "no head exercised the back-fill"
+    if expect_active is False:
+        assert all(r.skipped == 1 for r in checked)
+    return reps
+
+
+def test_config1_tiny_fp32(gpu):
+    _check_cfg(gpu, si.CONFIGS["1"], expect_active=False)       # B = d: retained span is R^d
+
+
+def test_config1_shadow_fp32(gpu):
+    _check_cfg(gpu, si.CONFIGS["1s"], expect_active=True)
+
+
+def test_config2_shape_one_layer(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["2"], n_layers=1), expect_active=False)
+
+
+def test_config2_shadow_one_layer(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["2s"], n_layers=1), expect_active=True)
+
+
+def test_config3_shape_four_heads(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["3"], n_layers=1, n_kv_heads=4), expect_active=False)
+
+
+def test_config3_shadow_four_heads(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["3s"], n_layers=1, n_kv_heads=4), expect_active=True)
+
+
+def test_config4_shape_two_heads(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["4"], n_layers=1, n_kv_heads=2), expect_active=False)
+
+
+def test_config4_shadow_two_heads(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["4s"], n_layers=1, n_kv_heads=2), expect_active=True)
+
+
+def test_config5_shape_ragged_budgets(gpu):
+    cfg = si.shrink(si.CONFIGS["5"], n_layers=1, n_kv_heads=3)
+    _check_cfg(gpu, cfg, seed=1, expect_active=False)
+
+
+def test_config5_shadow_ragged_budgets(gpu):
+    cfg = si.shrink(si.CONFIGS["5s"], n_layers=1, n_kv_heads=3)
+    _check_cfg(gpu, cfg, seed=2, expect_active=True)
+
+
+def test_paper_shape(gpu):
+    _check_cfg(gpu, si.shrink(si.CONFIGS["paper"], n_layers=2), expect_active=True)
+
+
+@pytest.mark.parametrize("N,d,dtype,g,W,B,rank", [
+    (1000, 64, "bf16", 3, 8, 40, 3),        # ragged tail, odd group, d = 64
+    (777, 128, "f32", 1, 5, 100, 2),        # fp32 at d = 128, rows not a multiple of anything
+    (1, 64, "f32", 1, 1, 1, 2),             # a single token
+    (513, 128, "bf16", 2, 16, 20, 40),      # rank above the complement's dimension is capped
+    (4099, 128, "bf16", 4, 32, 130, 4),     # budget just above head_dim
+])
+def test_ragged_shapes(gpu, N, d, dtype, g, W, B, rank):
+    cfg = si.RelayConfig("ragged", 7, 1, 2, g, d, N, W, B, rank, dtype, "structured", outlier_frac=0.01)
+    _check_cfg(gpu, cfg)
+
+
+def test_budget_edges_and_rank_zero(gpu):
+    cfg = si.RelayConfig("edge", 8, 1, 4, 2, 64, 300, 8, 0, 2, "bf16", "structured")
+    _check_cfg(gpu, cfg, budgets=[0, 300, 1000, 17], max_budget=300)
+    reps = _check_cfg(gpu, cfg, budgets=[5, 30, 63, 17], rank=0)
+    assert all(r.skipped == 1 for r in reps)
+
+
+def test_all_ties_keep_lowest_indices(gpu):
+    cfg = si.RelayConfig("ties", 9, 1, 2, 2, 64, 640, 4, 50, 2, "bf16", "structured")
+    K, V, Q = si.make_cache(cfg, 0)
+    Q[:] = 0                                   # every logit is zero: all scores equal
+    out = gpu.run_fused(cfg, K, V, Q, budget=50)
+    for h in range(2):
+        assert out["idx"][0, h].tolist() == list(range(50))
+
+
+def test_fused_equals_staged_and_is_deterministic(gpu):
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    cfg = si.shrink(si.CONFIGS["2s"], n_layers=1, n_kv_heads=4)
+    K, V, Q = si.make_cache(cfg, 3)
+    Kd, Vd, Qd = (gpu.to_dev(x, cfg.dtype) for x in (K, V, Q))
+    a = Bd.compress_relay(Kd, Vd, Qd, budget=cfg.budget, rank=cfg.rank, want_scores=True, want_delta=True)
+    b = Bd.compress_relay(Kd, Vd, Qd, budget=cfg.budget, rank=cfg.rank, want_scores=True, want_delta=True)
+    for k in ("K_out", "V_out", "idx", "n_keep", "scores", "delta"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), f"run-to-run difference in {k}"
+    sh = Bd.shape_of(Kd, Qd)
+    scores, lse = Bd.score(Kd, Qd)
+    idx, n_keep = Bd.select_topk(sh, scores, budget=cfg.budget)
+    Bd.refine_boundary(Kd, Qd, scores, lse, idx, n_keep)
+    K_out, V_out = Bd.gather(sh, Kd, Vd, idx, n_keep)
+    delta = torch.empty((1, 4, cfg.head_dim), dtype=torch.float32, device="cuda")
+    Bd.backfill(sh, Vd, scores, idx, n_keep, cfg.rank, V_out, delta_out=delta)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, a["scores"]) and torch.equal(idx, a["idx"]) and torch.equal(n_keep, a["n_keep"])
+    assert torch.equal(K_out.view(torch.int16), a["K_out"].view(torch.int16))
+    assert torch.equal(V_out.view(torch.int16), a["V_out"].view(torch.int16))
+    assert torch.equal(delta, a["delta"])
+
+
+def test_select_stage_is_exact_on_given_scores(gpu):
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    rng = np.random.default_rng(5)
+    N = 5000
+    s = np.empty((1, 4, N), dtype=np.float32)
+    s[0, 0] = rng.random(N).astype(np.float32)
+    s[0, 1] = np.round(rng.random(N) * 8).astype(np.float32) / 8           # many exact ties
+    s[0, 2] = rng.standard_normal(N).astype(np.float32)                    # negatives
+    s[0, 2, ::7] = 0.0
+    s[0, 2, 3::7] = -0.0
+    s[0, 3] = 1.0
+    sh = Bd.make_shape(1, 4, 1, 64, N, 1, "bf16")
+    for budgets in ([1, 77, 2500, 4999], [5000, 0, 13, 700]):
+        idx, n_keep = Bd.select_topk(sh, torch.from_numpy(s).cuda(), budgets=budgets, max_budget=5000)
+        torch.cuda.synchronize()
+        idx, n_keep = idx.cpu().numpy(), n_keep.cpu().numpy()
+        for h in range(4):
+            b = budgets[h]
+            # the decision is taken on the fp32 values by both sides; -0 orders below +0 as bit patterns
+            key = s[0, h].astype(np.float64)
+            key = np.where((s[0, h] == 0) & np.signbit(s[0, h]), -1e-300, key)
+            ref = O.select_topk(key, b)
+            assert n_keep[0, h] == b and np.array_equal(idx[0, h, :b], ref), f"head {h} budget {b}"
+            assert np.all(idx[0, h, b:] == -1)
