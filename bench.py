@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused relay compression (score -> TopK_B -> refine -> gather -> OBF) on one MI355X.
+
+A step is one obf_compress_relay call over a whole synthetic cache that is already resident in
+HBM.  Prints ONE JSON line: head-tokens/s, the HBM roofline of the dominant kernel (timed with
+HIP events inside the library, on the launch stream), and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "compressed KV-head-tokens/s + achieved HBM GB/s, Qwen3-8B-shape 8K cache"
+
+
+def stage_bytes(stage: str, cfg, budgets, active_heads: int) -> float:
+    """Algorithmic HBM bytes one launch of a stage must move (inputs read once, outputs written once)."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    heads, N, d, R = cfg.n_heads, cfg.n_tokens, cfg.head_dim, cfg.rows
+    kept = float(sum(min(int(b), N) for b in budgets.reshape(-1)))
+    k_bytes = heads * N * d * es
+    q_bytes = heads * R * d * es
+    if stage == "score_stats":
+        return k_bytes + q_bytes
+    if stage == "score_mass":
+        return k_bytes + q_bytes + heads * N * 4
+    if stage == "score_fused":
+        return k_bytes + q_bytes + heads * N * 4
+    if stage == "gather":
+        return 4 * kept * d * es
+    if stage == "del_stats":
+        return active_heads * N * d * es
+    if stage == "keep_basis":
+        return kept * d * es + heads * N * 4
+    if stage == "select":
+        return heads * N * 4 + kept * 4
+    return 0.0
+
+
+def path_bytes(cfg, budgets, active_heads: int) -> float:
+    """Algorithmic bytes of the whole path: K and Q once, kept rows read and written, V only where OBF is active."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    heads, N, d, R = cfg.n_heads, cfg.n_tokens, cfg.head_dim, cfg.rows
+    kept = float(sum(min(int(b), N) for b in budgets.reshape(-1)))
+    return heads * N * d * es + heads * R * d * es + 4 * kept * d * es + active_heads * N * d * es
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="3", help="config name from synth_inputs.CONFIGS (default: config 3)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline (0: skip)")
+    ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (0: all)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    from paper_2604_13349_amd import binding as B
+
+    B.load_library()                      # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = si.CONFIGS[args.workload]
+    if args.layers:
+        cfg = si.shrink(cfg, n_layers=args.layers, name=cfg.name)
+    threads = min(16, os.cpu_count() or 1)
+    t0 = time.time()
+    calls = []
+    for a in range(cfg.agents):           # config 5: sequential, independent agent hand-offs
+        K, V, Q = si.make_cache(cfg, args.seed + a, threads=threads)
+        bud = si.budgets(cfg, args.seed + a)
+        def dev(x):
+            if cfg.dtype == "bf16":
+                return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+            return torch.from_numpy(x).cuda()
+        calls.append({"K": dev(K), "V": dev(V), "Q": dev(Q), "bud": bud, "host": (K, V, Q) if a == 0 else None})
+        if a > 0:
+            del K, V, Q
+    gen_s = time.time() - t0
+    uniform = cfg.budget_range is None and cfg.budget_int_range is None
+    max_budget = int(max(int(min(c["bud"].max(), cfg.n_tokens)) for c in calls))
+    outs = [None] * len(calls)
+
+    def step():
+        for i, c in enumerate(calls):
+            kw = dict(rank=cfg.rank, max_budget=max_budget, out=outs[i], ws=(outs[i] or {}).get("ws"),
+                      want_diag=True)
+            if uniform:
+                outs[i] = B.compress_relay(c["K"], c["V"], c["Q"], budget=int(c["bud"].flat[0]), **kw)
+            else:
+                outs[i] = B.compress_relay(c["K"], c["V"], c["Q"], budgets=c["bud"].reshape(-1), **kw)
+
+    stages = B.profile_stages()
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
+    # survey: one untimed step per stage to find the dominant kernel
+    stage_ms = {}
+    for sid, name in enumerate(stages):
+        B.profile_enable(sid)
+        step()
+        ms, n = B.profile_read()
+        stage_ms[name] = ms
+    B.profile_enable(-1)
+    dominant = max(stage_ms, key=stage_ms.get)
+    diag = B.diag_to_numpy(outs[0]["diag"])
+    active_heads = int((diag["skipped"] == 0).sum())
+
+    B.profile_enable(stages.index(dominant))
+    B.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_n = B.profile_read()
+    B.profile_enable(-1)
+    elapsed = t1 - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    head_tokens = cfg.n_heads * cfg.n_tokens * len(calls)
+    value = head_tokens / (elapsed / args.steps)
+
+    launches_per_step = max(1, dom_n // max(1, args.steps))
+    dom_avg_ms = dom_ms / max(1, dom_n)
+    dom_bytes = sum(stage_bytes(dominant, cfg, c["bud"], active_heads) for c in calls) / launches_per_step
+    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_avg_ms > 0 else 0.0
+    pbytes = sum(path_bytes(cfg, c["bud"], active_heads) for c in calls)
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"traffic_config{cfg.name}.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            traffic = json.load(f).get(dominant)
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "kernel_ms": round(dom_avg_ms, 4), "kernel_bytes": dom_bytes,
+                "path_bytes": pbytes, "path_GBps": round(pbytes / (elapsed / args.steps) / 1e9, 2),
+                "path_frac": round(pbytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        from oracle import obf_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        Kh, Vh, Qh = calls[0]["host"]
+        bud = calls[0]["bud"]
+        done, tc0 = 0, time.perf_counter()
+        order = [(l, h) for l in range(cfg.n_layers) for h in range(cfg.n_kv_heads)]
+        idx_host = outs[0]["idx"].cpu().numpy()
+        mismatched = 0
+        for (l, h) in order:
+            ref = O.compress_head(Kh[l, h], Vh[l, h], Qh[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), cfg.rank, cfg.dtype)
+            done += 1
+            mismatched += int(not np.array_equal(idx_host[l, h, :len(ref.idx)], ref.idx))
+            if time.perf_counter() - tc0 >= args.cpu_seconds:
+                break
+        tc = time.perf_counter() - tc0
+        cpu = {"value": round(done * cfg.n_tokens / tc, 1), "unit": "head-tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {done} of {cfg.n_heads} heads of call 0, {tc:.1f} s, fp64 numpy with exact SVD",
+               "heads_index_mismatch": mismatched}
+
+    line = {
+        "metric": METRIC, "value": round(value, 1), "unit": "head-tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.name}: {cfg.n_layers} layers x {cfg.n_kv_heads} KV heads, group {cfg.group}, "
+                               f"head_dim {cfg.head_dim}, N={cfg.n_tokens}, window {cfg.window}, rank {cfg.rank}, "
+                               f"budget {'per-head' if not uniform else cfg.budget}, {cfg.agents} call(s) per step",
+                   "heads": cfg.n_heads, "active_obf_heads": active_heads, "input_gen_s": round(gen_s, 1)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

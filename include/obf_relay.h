@@ -124,6 +124,17 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
                                 float* scores_out, float* delta_out, obf_diag_t* diag,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/* Profiling aid (tracing of the path's own kernels with HIP events on the caller's stream).
+ * obf_profile_enable(stage) makes every later call on this thread bracket the launch of that
+ * internal stage's kernel with a pair of events; stage -1 switches it off.  obf_profile_read
+ * waits for the recorded events, returns the summed elapsed milliseconds and the number of
+ * launches since the last read, and resets both.  Stage ids run 0 .. obf_profile_stage_count()-1;
+ * obf_profile_stage_name gives the kernel family each one covers. */
+obf_status_t obf_profile_enable(int32_t stage);
+obf_status_t obf_profile_read(double* total_ms, int32_t* launches);
+int32_t obf_profile_stage_count(void);
+const char* obf_profile_stage_name(int32_t stage);
+
 /* Message for the calling thread's last non-OK status (static storage, never NULL). */
 const char* obf_last_error(void);
 

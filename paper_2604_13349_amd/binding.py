@@ -60,6 +60,13 @@ def load_library():
     lib.obf_backfill.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.obf_compress_relay.restype = C.c_int
     lib.obf_compress_relay.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.obf_profile_enable.restype = C.c_int
+    lib.obf_profile_enable.argtypes = [i32]
+    lib.obf_profile_read.restype = C.c_int
+    lib.obf_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.obf_profile_stage_count.restype = i32
+    lib.obf_profile_stage_name.restype = C.c_char_p
+    lib.obf_profile_stage_name.argtypes = [i32]
     lib.obf_last_error.restype = C.c_char_p
     lib.obf_version.restype = C.c_char_p
     _lib = lib
@@ -226,3 +233,19 @@ def diag_to_numpy(diag: torch.Tensor) -> np.ndarray:
     """Device diag bytes [L,H,32] -> structured numpy array [L,H]."""
     a = diag.cpu().numpy()
     return a.view(DIAG_DTYPE).reshape(a.shape[0], a.shape[1])
+
+
+def profile_enable(stage: int) -> None:
+    _check(load_library().obf_profile_enable(stage))
+
+
+def profile_read():
+    """(total milliseconds, launches) of the profiled stage since the last read."""
+    ms, n = C.c_double(0.0), C.c_int32(0)
+    _check(load_library().obf_profile_read(C.byref(ms), C.byref(n)))
+    return ms.value, n.value
+
+
+def profile_stages():
+    lib = load_library()
+    return [lib.obf_profile_stage_name(i).decode() for i in range(lib.obf_profile_stage_count())]

@@ -3,6 +3,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <vector>
 #include "common.hpp"
 
 namespace obf {
@@ -24,6 +25,32 @@ obf_status_t check_launch(const char* what) {
   }
   return OBF_OK;
 }
+
+// ---- stage profiling ---------------------------------------------------------------------------
+struct ProfRec { hipEvent_t a, b; };
+static thread_local int g_prof_stage = -1;
+static thread_local std::vector<ProfRec>* g_prof_used = nullptr;
+static thread_local std::vector<ProfRec>* g_prof_free = nullptr;
+
+ProfScope::ProfScope(int stage, hipStream_t s) : rec(nullptr), st(s) {
+  if (stage != g_prof_stage || g_prof_stage < 0) return;
+  if (!g_prof_used) { g_prof_used = new std::vector<ProfRec>(); g_prof_free = new std::vector<ProfRec>(); }
+  ProfRec r;
+  if (!g_prof_free->empty()) { r = g_prof_free->back(); g_prof_free->pop_back(); }
+  else {
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+  }
+  g_prof_used->push_back(r);
+  rec = &g_prof_used->back();
+  (void)hipEventRecord(r.a, st);
+}
+
+ProfScope::~ProfScope() {
+  if (rec) (void)hipEventRecord(((ProfRec*)rec)->b, st);
+}
+
+static const char* kStageNames[ST_COUNT] = {"score_stats", "score_lse", "score_mass", "select", "refine", "gather",
+                                            "keep_basis", "del_stats", "finalize", "inject"};
 
 static obf_status_t check_shape(const obf_shape_t* s) {
   if (!s) { set_error("shape is NULL"); return OBF_ERR_INVALID_ARG; }
@@ -78,6 +105,35 @@ using namespace obf;
 extern "C" {
 
 const char* obf_last_error(void) { return g_err; }
+
+obf_status_t obf_profile_enable(int32_t stage) {
+  if (stage >= ST_COUNT) { set_error("profile stage %d out of range", stage); return OBF_ERR_INVALID_ARG; }
+  g_prof_stage = stage < 0 ? -1 : stage;
+  return OBF_OK;
+}
+
+obf_status_t obf_profile_read(double* total_ms, int32_t* launches) {
+  double ms = 0.0;
+  int32_t n = 0;
+  if (g_prof_used) {
+    for (ProfRec& r : *g_prof_used) {
+      float t = 0.f;
+      if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) {
+        set_error("profile: event read failed");
+        return OBF_ERR_HIP;
+      }
+      ms += t; ++n;
+      g_prof_free->push_back(r);
+    }
+    g_prof_used->clear();
+  }
+  if (total_ms) *total_ms = ms;
+  if (launches) *launches = n;
+  return OBF_OK;
+}
+
+int32_t obf_profile_stage_count(void) { return ST_COUNT; }
+const char* obf_profile_stage_name(int32_t stage) { return (stage >= 0 && stage < ST_COUNT) ? kStageNames[stage] : ""; }
 const char* obf_version(void) { return "obf_relay 0.1 (gfx950)"; }
 
 size_t obf_workspace_bytes(const obf_shape_t* shape, int32_t max_budget, int32_t rank) {

@@ -611,21 +611,21 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     attr_done = true;
   }
   const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
-  hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
-                     m.N, m.d, max_budget, rank, state, basis);
+  { ProfScope prof_(ST_KEEP_BASIS, st); hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
+                     m.N, m.d, max_budget, rank, state, basis); }
   if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
   if (rank > 0) {
-    hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
-                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part);
+    { ProfScope prof_(ST_DEL_STATS, st); hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
+                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
-  hipLaunchKernelGGL(k_bf_finalize, dim3(m.heads), dim3(FN_THREADS), sizeof(float) * 2 * m.d * (m.d + 1), st, m.N, m.d,
-                     w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag);
+  { ProfScope prof_(ST_FINALIZE, st); hipLaunchKernelGGL(k_bf_finalize, dim3(m.heads), dim3(FN_THREADS), sizeof(float) * 2 * m.d * (m.d + 1), st, m.N, m.d,
+                     w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag); }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
   if (rank > 0 && max_budget > 0) {
     const int per = max_budget * m.d;
-    hipLaunchKernelGGL(k_bf_inject<T>, dim3((per + 255) / 256, m.heads), dim3(256), 0, st, (T*)V_out, delta, state, m.d,
-                       max_budget);
+    { ProfScope prof_(ST_INJECT, st); hipLaunchKernelGGL(k_bf_inject<T>, dim3((per + 255) / 256, m.heads), dim3(256), 0, st, (T*)V_out, delta, state, m.d,
+                       max_budget); }
     if (check_launch("backfill inject") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;

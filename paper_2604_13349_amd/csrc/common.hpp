@@ -81,6 +81,19 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   return w;
 }
 
+enum Stage {
+  ST_SCORE_STATS = 0, ST_SCORE_LSE, ST_SCORE_MASS, ST_SELECT, ST_REFINE, ST_GATHER, ST_KEEP_BASIS, ST_DEL_STATS,
+  ST_FINALIZE, ST_INJECT, ST_COUNT
+};
+
+// Brackets one kernel launch with HIP events when profiling of that stage is enabled.
+struct ProfScope {
+  ProfScope(int stage, hipStream_t st);
+  ~ProfScope();
+  void* rec;
+  hipStream_t st;
+};
+
 void set_error(const char* fmt, ...);
 obf_status_t check_launch(const char* what);
 

@@ -34,8 +34,8 @@ obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const in
   const int row_vec = m.d * m.esize / 16;            // 8, 16 or 32
   const int rows_per_block = GA_THREADS / row_vec;
   dim3 grid((max_budget + rows_per_block - 1) / rows_per_block, m.heads);
-  hipLaunchKernelGGL(k_gather, grid, dim3(GA_THREADS), 0, st, (const uint4*)K, (const uint4*)V, idx, n_keep, m.N, row_vec,
-                     max_budget, (uint4*)K_out, (uint4*)V_out);
+  { ProfScope prof_(ST_GATHER, st); hipLaunchKernelGGL(k_gather, grid, dim3(GA_THREADS), 0, st, (const uint4*)K, (const uint4*)V, idx, n_keep, m.N, row_vec,
+                     max_budget, (uint4*)K_out, (uint4*)V_out); }
   return check_launch("gather");
 }
 

@@ -142,11 +142,11 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
                            const int32_t* n_keep, hipStream_t st) {
   (void)w; (void)ws;
   if (m.dtype == OBF_BF16)
-    hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
+    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                       scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep); }
   else
-    hipLaunchKernelGGL(k_refine<float>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
-                       row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
+    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL(k_refine<float>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
+                       row_lse, m.N, m.d, m.R, max_budget, idx, n_keep); }
   return check_launch("refine");
 }
 

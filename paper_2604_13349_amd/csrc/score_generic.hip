@@ -152,15 +152,15 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   const size_t smemA = sizeof(float) * (GS_ROWS + GS_TOK) * ld;
   const size_t smemB = smemA + 8 + sizeof(double) * GS_ROWS * GS_TOK;
   dim3 grid(w.nchunk, m.heads);
-  hipLaunchKernelGGL(k_score_stats_generic<T>, grid, dim3(GS_THREADS), smemA, st, (const T*)K, (const T*)Q, stats_part,
-                     m.N, m.d, m.R, w.nchunk);
+  { ProfScope prof_(ST_SCORE_STATS, st); hipLaunchKernelGGL(k_score_stats_generic<T>, grid, dim3(GS_THREADS), smemA, st, (const T*)K, (const T*)Q, stats_part,
+                     m.N, m.d, m.R, w.nchunk); }
   if (check_launch("score stats (generic)") != OBF_OK) return OBF_ERR_HIP;
   const int total_rows = m.heads * m.R;
-  hipLaunchKernelGGL(k_score_lse, dim3((total_rows + 255) / 256), dim3(256), 0, st, stats_part, row_lse, m.R, w.nchunk,
-                     total_rows);
+  { ProfScope prof_(ST_SCORE_LSE, st); hipLaunchKernelGGL(k_score_lse, dim3((total_rows + 255) / 256), dim3(256), 0, st, stats_part, row_lse, m.R, w.nchunk,
+                     total_rows); }
   if (check_launch("score lse") != OBF_OK) return OBF_ERR_HIP;
-  hipLaunchKernelGGL(k_score_mass_generic<T>, grid, dim3(GS_THREADS), smemB, st, (const T*)K, (const T*)Q, row_lse, scores,
-                     m.N, m.d, m.R);
+  { ProfScope prof_(ST_SCORE_MASS, st); hipLaunchKernelGGL(k_score_mass_generic<T>, grid, dim3(GS_THREADS), smemB, st, (const T*)K, (const T*)Q, row_lse, scores,
+                     m.N, m.d, m.R); }
   return check_launch("score mass (generic)");
 }
 

@@ -115,14 +115,14 @@ obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* bu
   }
   BudgetBatch bb;
   if (!budgets_host) {
-    hipLaunchKernelGGL(k_select, dim3(m.heads), dim3(SEL_THREADS), smem, st, scores, m.N, 0, budget, bb, 0, max_budget,
-                       idx, n_keep);
+    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL(k_select, dim3(m.heads), dim3(SEL_THREADS), smem, st, scores, m.N, 0, budget, bb, 0, max_budget,
+                       idx, n_keep); }
     return check_launch("select");
   }
   for (int h0 = 0; h0 < m.heads; h0 += SEL_BATCH) {
     const int nb = (m.heads - h0 < SEL_BATCH) ? (m.heads - h0) : SEL_BATCH;
     for (int i = 0; i < nb; ++i) bb.b[i] = budgets_host[h0 + i];
-    hipLaunchKernelGGL(k_select, dim3(nb), dim3(SEL_THREADS), smem, st, scores, m.N, h0, 0, bb, 1, max_budget, idx, n_keep);
+    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL(k_select, dim3(nb), dim3(SEL_THREADS), smem, st, scores, m.N, h0, 0, bb, 1, max_budget, idx, n_keep); }
     if (check_launch("select") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;
