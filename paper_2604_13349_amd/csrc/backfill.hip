@@ -123,7 +123,9 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
                                                               const int32_t* __restrict__ idx,
                                                               const int32_t* __restrict__ n_keep, int N, int d,
                                                               int max_budget, int rank, HeadState* __restrict__ state,
-                                                              float* __restrict__ basis) {
+                                                              float* __restrict__ basis,
+                                                              const int32_t* __restrict__ decided) {
+  if (decided && decided[blockIdx.x]) return;        // settled by the fast full-rank test
   extern __shared__ double W[];            // [d][d] doubles (rows: vectors being orthonormalised / Gram)
   __shared__ double red[KB_WAVES];
   __shared__ int ired[2];
@@ -611,8 +613,13 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     attr_done = true;
   }
   const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
+  int32_t* decided = nullptr;
+  if (keep_cert_supported(m)) {
+    decided = (int32_t*)(ws + w.decided);
+    if (launch_keep_cert(m, V, scores, idx, n_keep, max_budget, rank, state, decided, st) != OBF_OK) return OBF_ERR_HIP;
+  }
   { ProfScope prof_(ST_KEEP_BASIS, st); hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
-                     m.N, m.d, max_budget, rank, state, basis); }
+                     m.N, m.d, max_budget, rank, state, basis, decided); }
   if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
   if (rank > 0) {
     { ProfScope prof_(ST_DEL_STATS, st); hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,

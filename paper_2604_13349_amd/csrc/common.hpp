@@ -35,8 +35,10 @@ struct Workspace {
   size_t row_lse;      // double  [heads][R]
   size_t lse_corr;     // int64   [heads][R]              fixed-point corrections of sum-exp (MFMA path)
   size_t scores;       // float   [heads][N]              (fused call without scores_out)
+  size_t score_part;   // float   [RG][heads][N]          per-row-group column sums when group*window > 128
   size_t budgets;      // unused placeholder kept for alignment
   size_t head_state;   // HeadState [heads]
+  size_t decided;      // int32   [heads]                 1: the fast full-rank test settled the head
   size_t basis;        // float   [heads][d][d]           orthonormal basis of the retained span (columns)
   size_t gram_part;    // float   [heads][nstat][d*d+d+4] partial Gram / weighted sum / norms of V_del
   size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
@@ -70,8 +72,13 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.row_lse = take(sizeof(double) * (size_t)m.heads * m.R);
   w.lse_corr = take(sizeof(int64_t) * (size_t)m.heads * m.R);
   w.scores = take(sizeof(float) * (size_t)m.heads * m.N);
+  {
+    const int rgroups = (m.R + 127) / 128;
+    w.score_part = take(rgroups > 1 ? sizeof(float) * (size_t)rgroups * m.heads * m.N : 0);
+  }
   w.budgets = take(256);
   w.head_state = take(sizeof(HeadState) * (size_t)m.heads);
+  w.decided = take(sizeof(int32_t) * (size_t)m.heads);
   w.basis = take(sizeof(float) * (size_t)m.heads * m.d * m.d);
   w.gram_part = take(sizeof(float) * (size_t)m.heads * w.nstat * ((size_t)m.d * m.d + m.d + 4));
   w.mats = take(sizeof(float) * (size_t)m.heads * 3 * m.d * m.d);
@@ -82,7 +89,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
 }
 
 enum Stage {
-  ST_SCORE_STATS = 0, ST_SCORE_LSE, ST_SCORE_MASS, ST_SELECT, ST_REFINE, ST_GATHER, ST_KEEP_BASIS, ST_DEL_STATS,
+  ST_SCORE_STATS = 0, ST_SCORE_LSE, ST_SCORE_MASS, ST_SELECT, ST_REFINE, ST_GATHER, ST_KEEP_CERT, ST_KEEP_BASIS, ST_DEL_STATS,
   ST_FINALIZE, ST_INJECT, ST_COUNT
 };
 
@@ -131,6 +138,10 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
                            const int32_t* n_keep, hipStream_t st);
 obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const int32_t* idx, const int32_t* n_keep,
                            int32_t max_budget, void* K_out, void* V_out, hipStream_t st);
+bool keep_cert_supported(const Dims& m);
+obf_status_t launch_keep_cert(const Dims& m, const void* V, const float* scores, const int32_t* idx,
+                              const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
+                              int32_t* decided, hipStream_t st);
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
                              void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st);
