@@ -8,7 +8,7 @@
 namespace obf {
 
 constexpr int kMaxTokens = 32768;
-constexpr int kScoreChunk = 512;        // tokens per score workgroup
+constexpr int kNumCU = 256;             // compute units of the target (MI355X)
 constexpr int kStatChunk = 1024;        // tokens per deleted-value statistics workgroup
 constexpr int kBandCap = 256;           // most boundary candidates re-scored per head
 constexpr double kEps = 1e-12;          // epsilon of Eq. 4 / Eq. 6
@@ -46,6 +46,8 @@ struct Workspace {
   size_t band;         // BandEntry [heads][kBandCap]
   size_t total;
   int nchunk;          // score chunks per head
+  int chunk_tokens;    // tokens per score chunk
+  int rgroups, tiles_per_head, tiles_per_range, nranges, nslot;   // matrix-core score partition
   int nstat;           // statistics chunks per head
 };
 
@@ -64,18 +66,31 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 inline Workspace carve(const Dims& m, int max_budget, int rank) {
   (void)max_budget; (void)rank;
   Workspace w;
-  w.nchunk = (m.N + kScoreChunk - 1) / kScoreChunk;
+  // reference-precision score path: fixed chunks of 512 tokens
+  w.chunk_tokens = 512;
+  w.nchunk = (m.N + w.chunk_tokens - 1) / w.chunk_tokens;
   w.nstat = (m.N + kStatChunk - 1) / kStatChunk;
+  // matrix-core score path: the flattened (head, 32-token tile) space is cut into one range per
+  // persistent workgroup; a head is covered by at most nslot ranges
+  w.rgroups = (m.R + 127) / 128;
+  w.tiles_per_head = (m.N + 31) / 32;
+  {
+    const long TT = (long)m.heads * w.tiles_per_head;
+    const int G = kNumCU / w.rgroups > 0 ? kNumCU / w.rgroups : 1;
+    long T = (TT + G - 1) / G;
+    T = ((T + 3) / 4) * 4;
+    if (T < 4) T = 4;
+    w.tiles_per_range = (int)T;
+    w.nranges = (int)((TT + T - 1) / T);
+    w.nslot = (int)((w.tiles_per_head + T - 1) / T) + 1;
+  }
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
-  w.stats_part = take(sizeof(double) * 2 * (size_t)m.heads * w.nchunk * m.R);
+  w.stats_part = take(sizeof(double) * 2 * (size_t)m.heads * (w.nchunk > w.nslot ? w.nchunk : w.nslot) * m.R);
   w.row_lse = take(sizeof(double) * (size_t)m.heads * m.R);
   w.lse_corr = take(sizeof(int64_t) * (size_t)m.heads * m.R);
   w.scores = take(sizeof(float) * (size_t)m.heads * m.N);
-  {
-    const int rgroups = (m.R + 127) / 128;
-    w.score_part = take(rgroups > 1 ? sizeof(float) * (size_t)rgroups * m.heads * m.N : 0);
-  }
+  w.score_part = take(w.rgroups > 1 ? sizeof(float) * (size_t)w.rgroups * m.heads * m.N : 0);
   w.budgets = take(256);
   w.head_state = take(sizeof(HeadState) * (size_t)m.heads);
   w.decided = take(sizeof(int32_t) * (size_t)m.heads);

@@ -31,214 +31,326 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 union Frag { uint4 u; bf16x8 v; };
 
+// Rows past R and tokens past t_end are clamped to the last valid one instead of being predicated: their
+// results are never used (padded rows get lse = +inf in pass B and are not written in pass A; tokens past the
+// end are masked by index), and branch-free loads keep the fragments in registers.
 __device__ __forceinline__ void load_q(Frag (&qf)[SM_RB][SM_KK], const uint16_t* __restrict__ Qh, int row0, int R, int lane) {
   const int r = lane & 31, kh = (lane >> 5) * 8;
 #pragma unroll
   for (int rb = 0; rb < SM_RB; ++rb) {
-    const int row = row0 + rb * 32 + r;
+    const int row = min(row0 + rb * 32 + r, R - 1);
+    const uint4* p = (const uint4*)(Qh + (size_t)row * SM_D + kh);
 #pragma unroll
-    for (int kk = 0; kk < SM_KK; ++kk) {
-      if (row < R) qf[rb][kk].u = *(const uint4*)(Qh + (size_t)row * SM_D + kk * 16 + kh);
-      else qf[rb][kk].u = make_uint4(0, 0, 0, 0);
-    }
+    for (int kk = 0; kk < SM_KK; ++kk) qf[rb][kk].u = p[kk * 2];
   }
 }
 
 __device__ __forceinline__ void load_k(Frag (&kf)[SM_KK], const uint16_t* __restrict__ Kh, int tok0, int t_end, int lane) {
-  const int t = tok0 + (lane & 31), kh = (lane >> 5) * 8;
-  if (t < t_end) {
-    const uint4* p = (const uint4*)(Kh + (size_t)t * SM_D + kh);
+  const int t = min(tok0 + (lane & 31), t_end - 1), kh = (lane >> 5) * 8;
+  const uint4* p = (const uint4*)(Kh + (size_t)t * SM_D + kh);
 #pragma unroll
-    for (int kk = 0; kk < SM_KK; ++kk) kf[kk].u = p[kk * 2];
-  } else {
-#pragma unroll
-    for (int kk = 0; kk < SM_KK; ++kk) kf[kk].u = make_uint4(0, 0, 0, 0);
-  }
+  for (int kk = 0; kk < SM_KK; ++kk) kf[kk].u = p[kk * 2];
 }
 
 // ------------------------------------------------------------------------------------------------
-// Pass A.  grid (nchunk * RG, heads); workgroup = 4 waves, each takes every 4th 32-token tile.
+// Shared tile machinery.  A wave walks the 32-token tiles wave, wave+4, ... of its chunk.  The MFMAs of
+// tile i+1 are issued in the same basic block as the vector-ALU epilogue of tile i (two accumulator
+// sets, two K fragment buffers), so that the matrix pipe and the vector ALU overlap within the one
+// wave a SIMD holds.
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32, denormal results flush to 0
+
+// MFMA chain of one 32-row block against one 32-token tile (8 k-steps of 16).
+template <bool TOKENS_BY_ROWS>
+__device__ __forceinline__ void block_mfma(f32x16& acc, const Frag (&kf)[SM_KK], const Frag (&qf)[SM_KK]) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < SM_KK; ++kk) {
+    if (TOKENS_BY_ROWS) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk].v, qf[kk].v, acc, 0, 0, 0);
+    else acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk].v, kf[kk].v, acc, 0, 0, 0);
+  }
+}
+
+// Pass A epilogue of one row block of a tile whose 32 tokens are all valid.  acc[i] is the raw dot product
+// of token tok + (i/4)*8 + (lane/32)*4 + (i%4) with query row row0 + rb*32 + lane%32.  m is the running
+// maximum in raw units, l the running sum of exp2((raw - m) a2) in double.
+struct StatsEp {
+  float (&m)[SM_RB];
+  double (&l)[SM_RB];
+  float a2;
+  template <int RB>
+  __device__ __forceinline__ void block(const f32x16& acc, int) {
+    float mx = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, acc[i]), acc[i + 1]);
+    mx = fmaxf(mx, acc[15]);
+    const float mo = m[RB];
+    const float mn = fmaxf(mo, mx);
+    const float off = mn * a2;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+      s0 += fast_exp2(fmaf(acc[i], a2, -off));
+      s1 += fast_exp2(fmaf(acc[i + 1], a2, -off));
+      s2 += fast_exp2(fmaf(acc[i + 2], a2, -off));
+      s3 += fast_exp2(fmaf(acc[i + 3], a2, -off));
+    }
+    const float ts = (s0 + s1) + (s2 + s3);
+    const float sc = fast_exp2((mo - mn) * a2);          // 0 on the first tile (mo = -inf), 1 when the maximum stands
+    l[RB] = fma(l[RB], (double)sc, (double)ts);
+    m[RB] = mn;
+  }
+};
+
+// Same for a ragged tile: tokens at or past t_end are left out.
+__device__ __forceinline__ void stats_block_ragged(const f32x16& acc, float& m, double& l, float a2, int tok, int t_end,
+                                                   int lane) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int t = tok + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+    if (t < t_end) mx = fmaxf(mx, acc[i]);
+  }
+  const float mo = m;
+  const float mn = fmaxf(mo, mx);
+  if (mn > -INFINITY) {
+    const float off = mn * a2;
+    float ts = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int t = tok + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+      if (t < t_end) ts += fast_exp2(fmaf(acc[i], a2, -off));
+    }
+    const float sc = (mo > -INFINITY) ? fast_exp2((mo - mn) * a2) : 0.f;
+    l = fma(l, (double)sc, (double)ts);
+    m = mn;
+  }
+}
+
+// Pass B epilogue: acc[i] is the raw dot product of query row row0 + rb*32 + (i/4)*8 + (lane/32)*4 + (i%4) with
+// token tok + lane%32; b2 holds lse[row] * log2(e) for the same (rb, i).  The column sum of a tile is
+// complete after its last row block.
+struct MassEp {
+  const float (&b2)[SM_RB][16];
+  float a2;
+  float* __restrict__ dst;
+  int t_end, lane;
+  float c0, c1, c2, c3;
+  template <int RB>
+  __device__ __forceinline__ void block(const f32x16& acc, int tok) {
+    if (RB == 0) { c0 = 0.f; c1 = 0.f; c2 = 0.f; c3 = 0.f; }
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+      c0 += fast_exp2(fmaf(acc[i], a2, -b2[RB][i]));
+      c1 += fast_exp2(fmaf(acc[i + 1], a2, -b2[RB][i + 1]));
+      c2 += fast_exp2(fmaf(acc[i + 2], a2, -b2[RB][i + 2]));
+      c3 += fast_exp2(fmaf(acc[i + 3], a2, -b2[RB][i + 3]));
+    }
+    if (RB == SM_RB - 1) {
+      float col = (c0 + c1) + (c2 + c3);
+      const float other = __shfl_xor(col, 32);
+      col = (lane < 32) ? (col + other) : (other + col);
+      const int t = tok + (lane & 31);
+      if (lane < 32 && t < t_end) dst[t] = col;
+    }
+  }
+};
+
+// Software pipeline over the tiles first, first + STEP, ... of one wave, at row-block granularity: micro-stage
+// (tile t, row block rb) issues the MFMA chain of the NEXT (tile, row block) and, in the same basic block,
+// runs the vector-ALU epilogue of the current one, so the matrix pipe and the vector ALU overlap within the
+// one wave a SIMD holds.  Two 16-register accumulators and two K fragment buffers alternate; the load of
+// tile t+2 is issued once the last chain of tile t has been issued.
+template <bool TOKENS_BY_ROWS, int U, class Ep>
+__device__ __forceinline__ void micro_stage(const uint16_t* __restrict__ Kh, int first, int n, int t_end, int lane, int i,
+                                            const Frag (&qf)[SM_RB][SM_KK], Frag (&kb)[2][SM_KK], f32x16 (&acc)[2], Ep& ep,
+                                            bool guarded) {
+  constexpr int STEP = SM_WAVES * SM_TILE;
+  constexpr int rb = U % 4, tl = U / 4;                 // current row block, tile offset within the group of 2
+  constexpr int rbn = (U + 1) % 4, tln = (U + 1) / 4;   // next
+  const int tile = i + tl, tilen = i + tln;
+  if (guarded && tile >= n) return;
+  if (!guarded || tilen < n) block_mfma<TOKENS_BY_ROWS>(acc[(U + 1) & 1], kb[tln % 2], qf[rbn]);
+  ep.template block<rb>(acc[U & 1], first + tile * STEP);
+  if (rb == 3 && tile + 2 < n) load_k(kb[tl % 2], Kh, first + (tile + 2) * STEP, t_end, lane);
+  __builtin_amdgcn_sched_barrier(0);      // keep the scheduler from merging micro-stages (register pressure)
+}
+
+template <bool TOKENS_BY_ROWS, class Ep>
+__device__ __forceinline__ void run_tiles(const uint16_t* __restrict__ Kh, int first, int n, int t_end, int lane,
+                                          const Frag (&qf)[SM_RB][SM_KK], Ep& ep) {
+  constexpr int STEP = SM_WAVES * SM_TILE;
+  if (n <= 0) return;
+  Frag kb[2][SM_KK];
+  f32x16 acc[2];
+  load_k(kb[0], Kh, first, t_end, lane);
+  if (n > 1) load_k(kb[1], Kh, first + STEP, t_end, lane);
+  block_mfma<TOKENS_BY_ROWS>(acc[0], kb[0], qf[0]);
+  int i = 0;
+#define OBF_STAGES(G)                                                                                      \
+  micro_stage<TOKENS_BY_ROWS, 0>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 1>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 2>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 3>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 4>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 5>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 6>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 7>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);
+  for (; i + 2 < n; i += 2) { OBF_STAGES(false) }      // two whole tiles and the first chain of the next exist
+  { OBF_STAGES(true) }
+#undef OBF_STAGES
+}
+
+// Static partition of the flattened (head, tile) space over the persistent workgroups.
+struct Part {
+  int TH;        // 32-token tiles per head
+  int T;         // tiles per workgroup range
+  long TT;       // heads * TH
+};
+
+// ------------------------------------------------------------------------------------------------
+// Pass A.  grid = G ranges x RG row groups, one workgroup per compute unit; a workgroup walks its range of
+// tiles segment by segment (a segment = the part of one head inside the range) and leaves one partial
+// (max, sum-exp) per query row and segment.
 __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16_t* __restrict__ K,
                                                                     const uint16_t* __restrict__ Q,
                                                                     double* __restrict__ stats_part, int N, int R,
-                                                                    int nchunk, int RG) {
+                                                                    int RG, Part pt, int nslot) {
   __shared__ double s_m[SM_WAVES][SM_ROWS], s_l[SM_WAVES][SM_ROWS];
-  const int head = blockIdx.y;
-  const int chunk = blockIdx.x / RG, rg = blockIdx.x - chunk * RG;
+  const int range = blockIdx.x / RG, rg = blockIdx.x - range * RG;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int t0 = chunk * kScoreChunk, t1 = min(N, t0 + kScoreChunk);
-  const uint16_t* Kh = K + (size_t)head * N * SM_D;
-  const uint16_t* Qh = Q + (size_t)head * R * SM_D;
   const int row0 = rg * SM_ROWS;
   const float a2 = kLog2e / sqrtf((float)SM_D);
+  constexpr int STEP = SM_WAVES * SM_TILE;
+  const long gs = (long)range * pt.T;
+  const long ge = min(pt.TT, gs + pt.T);
 
-  Frag qf[SM_RB][SM_KK];
-  load_q(qf, Qh, row0, R, lane);
-  float m[SM_RB];
-  double l[SM_RB];
-#pragma unroll
-  for (int rb = 0; rb < SM_RB; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0; }
+  for (long cur = gs; cur < ge;) {
+    const int head = (int)(cur / pt.TH);
+    const long hs = (long)head * pt.TH;
+    const long se = min(ge, hs + pt.TH);
+    const int ta = (int)(cur - hs) * SM_TILE, tb = min(N, (int)(se - hs) * SM_TILE);
+    const int slot = range - (int)(hs / pt.T);
+    const uint16_t* Kh = K + (size_t)head * N * SM_D;
+    const uint16_t* Qh = Q + (size_t)head * R * SM_D;
 
-  Frag kf[SM_KK], kn[SM_KK];
-  int tok = t0 + wave * SM_TILE;
-  if (tok < t1) load_k(kf, Kh, tok, t1, lane);
-  for (; tok < t1; tok += SM_WAVES * SM_TILE) {
-    const int nxt = tok + SM_WAVES * SM_TILE;
-    if (nxt < t1) load_k(kn, Kh, nxt, t1, lane);
-    f32x16 acc[SM_RB];
+    Frag qf[SM_RB][SM_KK];
+    load_q(qf, Qh, row0, R, lane);
+    float m[SM_RB];
+    double l[SM_RB];
 #pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb) {
+    for (int rb = 0; rb < SM_RB; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0; }
+    const int first = ta + wave * SM_TILE;
+    const int nfull = (tb - first >= SM_TILE) ? ((tb - first - SM_TILE) / STEP + 1) : 0;
+    StatsEp ep{m, l, a2};
+    run_tiles<true>(Kh, first, nfull, tb, lane, qf, ep);
+    {
+      const int tok = first + nfull * STEP;          // a ragged last tile, if any
+      if (tok < tb) {
+        Frag kr[SM_KK];
+        load_k(kr, Kh, tok, tb, lane);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < SM_KK; ++kk)
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk].v, qf[rb][kk].v, acc[rb], 0, 0, 0);
-    }
-    // acc[rb][i]: token tok + (i/4)*8 + (lane/32)*4 + (i%4), query row row0 + rb*32 + lane%32
-    const bool ragged = tok + SM_TILE > t1;
-#pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb) {
-      float tv[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        tv[i] = acc[rb][i] * a2;
-        if (ragged) {
-          const int t = tok + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-          if (t >= t1) tv[i] = -INFINITY;
+        for (int rb = 0; rb < SM_RB; ++rb) {
+          f32x16 accr;
+          block_mfma<true>(accr, kr, qf[rb]);
+          stats_block_ragged(accr, m[rb], l[rb], a2, tok, tb, lane);
         }
       }
-      float mx = tv[0];
+    }
+    // fold the two lane halves (same query row, different tokens), then the four waves
 #pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, tv[i]);
-      const float mo = m[rb];
-      const float mn = fmaxf(mo, mx);
-      if (mn > -INFINITY) {
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; i += 4) {
-          s0 += exp2f(tv[i] - mn); s1 += exp2f(tv[i + 1] - mn); s2 += exp2f(tv[i + 2] - mn); s3 += exp2f(tv[i + 3] - mn);
-        }
-        const float ts = (s0 + s1) + (s2 + s3);
-        const double scale = (mo == mn) ? 1.0 : (double)exp2f(mo - mn);
-        l[rb] = l[rb] * scale + (double)ts;
-        m[rb] = mn;
+    for (int rb = 0; rb < SM_RB; ++rb) {
+      const float mo = __shfl_xor(m[rb], 32);
+      const double lo = __shfl_xor(l[rb], 32);
+      const float mn = fmaxf(m[rb], mo);
+      double a = 0.0, b = 0.0;
+      if (m[rb] > -INFINITY) a = l[rb] * exp2((double)((m[rb] - mn) * a2));
+      if (mo > -INFINITY) b = lo * exp2((double)((mo - mn) * a2));
+      if (lane < 32) { s_m[wave][rb * 32 + lane] = (double)mn * (double)a2; s_l[wave][rb * 32 + lane] = a + b; }
+    }
+    __syncthreads();
+    if (threadIdx.x < SM_ROWS) {
+      const int row = row0 + threadIdx.x;
+      if (row < R) {
+        double M = -INFINITY;
+        for (int w = 0; w < SM_WAVES; ++w) M = fmax(M, s_m[w][threadIdx.x]);
+        double L = 0.0;
+        for (int w = 0; w < SM_WAVES; ++w)
+          if (s_m[w][threadIdx.x] > -INFINITY) L += s_l[w][threadIdx.x] * exp2(s_m[w][threadIdx.x] - M);
+        double* o = stats_part + (((size_t)head * nslot + slot) * R + row) * 2;
+        o[0] = M * 0.6931471805599453;     // log2 units -> natural log
+        o[1] = L;
       }
     }
-    if (nxt < t1) {
-#pragma unroll
-      for (int kk = 0; kk < SM_KK; ++kk) kf[kk] = kn[kk];
-    }
+    __syncthreads();
+    cur = se;
   }
-  // fold the two lane halves (same query row, different tokens), then the four waves
-#pragma unroll
-  for (int rb = 0; rb < SM_RB; ++rb) {
-    const float mo = __shfl_xor(m[rb], 32);
-    const double lo = __shfl_xor(l[rb], 32);
-    const float mn = fmaxf(m[rb], mo);
-    double a = 0.0, b = 0.0;
-    if (m[rb] > -INFINITY) a = l[rb] * exp2((double)(m[rb] - mn));
-    if (mo > -INFINITY) b = lo * exp2((double)(mo - mn));
-    // both halves compute the same sum in the same operand order: a is always the lower half's term
-    const double sum = (lane < 32) ? (a + b) : (b + a);
-    if (lane < 32) { s_m[wave][rb * 32 + lane] = (double)mn; s_l[wave][rb * 32 + lane] = sum; }
-  }
-  __syncthreads();
-  if (threadIdx.x < SM_ROWS) {
-    const int row = row0 + threadIdx.x;
-    if (row < R) {
-      double M = -INFINITY;
-      for (int w = 0; w < SM_WAVES; ++w) M = fmax(M, s_m[w][threadIdx.x]);
-      double L = 0.0;
-      for (int w = 0; w < SM_WAVES; ++w)
-        if (s_m[w][threadIdx.x] > -INFINITY) L += s_l[w][threadIdx.x] * exp2(s_m[w][threadIdx.x] - M);
-      double* o = stats_part + (((size_t)head * nchunk + chunk) * R + row) * 2;
-      o[0] = M * 0.6931471805599453;     // log2 units -> natural log, as the fold kernel expects
-      o[1] = L;
-    }
-  }
-}
-
-// log-sum-exp of every query row from the chunk partials (same as the reference-precision path)
-__global__ void k_score_lse_mfma(const double* __restrict__ stats_part, double* __restrict__ row_lse, int R, int nchunk,
-                                 int total_rows) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= total_rows) return;
-  const int head = i / R, row = i - head * R;
-  double M = -INFINITY;
-  for (int c = 0; c < nchunk; ++c) M = fmax(M, stats_part[(((size_t)head * nchunk + c) * R + row) * 2]);
-  double L = 0.0;
-  for (int c = 0; c < nchunk; ++c) {
-    const double* p = stats_part + (((size_t)head * nchunk + c) * R + row) * 2;
-    if (p[0] != -INFINITY) L += p[1] * exp(p[0] - M);
-  }
-  row_lse[i] = M + log(L);
 }
 
 // ------------------------------------------------------------------------------------------------
-// Pass B.  Same grid.  out = scores (RG == 1) or the row group's partial column sums.
+// Pass B.  Same partition.  First folds the head's partials into log-sum-exp (every workgroup that touches
+// a head computes the same values; the one holding the head's first tile also writes row_lse), then
+// out = scores (RG == 1) or the row group's partial column sums.
 __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_t* __restrict__ K,
                                                                    const uint16_t* __restrict__ Q,
-                                                                   const double* __restrict__ row_lse,
+                                                                   const double* __restrict__ stats_part,
+                                                                   double* __restrict__ row_lse,
                                                                    float* __restrict__ out, int N, int R, int RG,
-                                                                   size_t rg_stride) {
-  const int head = blockIdx.y;
-  const int chunk = blockIdx.x / RG, rg = blockIdx.x - chunk * RG;
+                                                                   size_t rg_stride, Part pt, int nslot) {
+  __shared__ double s_lse[SM_ROWS];
+  const int range = blockIdx.x / RG, rg = blockIdx.x - range * RG;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int t0 = chunk * kScoreChunk, t1 = min(N, t0 + kScoreChunk);
-  const uint16_t* Kh = K + (size_t)head * N * SM_D;
-  const uint16_t* Qh = Q + (size_t)head * R * SM_D;
-  const double* lse = row_lse + (size_t)head * R;
-  float* dst = out + (size_t)rg * rg_stride + (size_t)head * N;
   const int row0 = rg * SM_ROWS;
   const float a2 = kLog2e / sqrtf((float)SM_D);
+  constexpr int STEP = SM_WAVES * SM_TILE;
+  const long gs = (long)range * pt.T;
+  const long ge = min(pt.TT, gs + pt.T);
 
-  Frag qf[SM_RB][SM_KK];
-  load_q(qf, Qh, row0, R, lane);
-  // per-lane row offsets: row of acc[rb][i] is row0 + rb*32 + (i/4)*8 + (lane/32)*4 + (i%4)
-  float b2[SM_RB][16];
-#pragma unroll
-  for (int rb = 0; rb < SM_RB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = row0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-      b2[rb][i] = (row < R) ? (float)(lse[row] * 1.4426950408889634) : INFINITY;   // padded rows contribute exp2(-inf) = 0
-    }
+  for (long cur = gs; cur < ge;) {
+    const int head = (int)(cur / pt.TH);
+    const long hs = (long)head * pt.TH;
+    const long se = min(ge, hs + pt.TH);
+    const int ta = (int)(cur - hs) * SM_TILE, tb = min(N, (int)(se - hs) * SM_TILE);
+    const uint16_t* Kh = K + (size_t)head * N * SM_D;
+    const uint16_t* Qh = Q + (size_t)head * R * SM_D;
+    float* dst = out + (size_t)rg * rg_stride + (size_t)head * N;
 
-  Frag kf[SM_KK], kn[SM_KK];
-  int tok = t0 + wave * SM_TILE;
-  if (tok < t1) load_k(kf, Kh, tok, t1, lane);
-  for (; tok < t1; tok += SM_WAVES * SM_TILE) {
-    const int nxt = tok + SM_WAVES * SM_TILE;
-    if (nxt < t1) load_k(kn, Kh, nxt, t1, lane);
-    f32x16 acc[SM_RB];
-#pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < SM_KK; ++kk)
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk].v, kf[kk].v, acc[rb], 0, 0, 0);
-    }
-    float c0 = 0.f, c1 = 0.f, c2 = 0.f, c3 = 0.f;
-#pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb) {
-#pragma unroll
-      for (int i = 0; i < 16; i += 4) {
-        c0 += exp2f(fmaf(acc[rb][i], a2, -b2[rb][i]));
-        c1 += exp2f(fmaf(acc[rb][i + 1], a2, -b2[rb][i + 1]));
-        c2 += exp2f(fmaf(acc[rb][i + 2], a2, -b2[rb][i + 2]));
-        c3 += exp2f(fmaf(acc[rb][i + 3], a2, -b2[rb][i + 3]));
+    __syncthreads();
+    if (threadIdx.x < SM_ROWS) {
+      const int row = row0 + threadIdx.x;
+      double lse = INFINITY;                                   // padded rows: exp2(-inf) = 0
+      if (row < R) {
+        const int s_first = (int)(hs / pt.T), s_last = (int)((hs + pt.TH - 1) / pt.T);
+        const double* p = stats_part + ((size_t)head * nslot * R + row) * 2;
+        double M = -INFINITY;
+        for (int sl = 0; sl <= s_last - s_first; ++sl) M = fmax(M, p[(size_t)sl * R * 2]);
+        double L = 0.0;
+        for (int sl = 0; sl <= s_last - s_first; ++sl) {
+          const double pm = p[(size_t)sl * R * 2], pl = p[(size_t)sl * R * 2 + 1];
+          if (pm != -INFINITY) L += pl * exp(pm - M);
+        }
+        lse = M + log(L);
+        if (cur == hs) row_lse[(size_t)head * R + row] = lse;
       }
+      s_lse[threadIdx.x] = lse;
     }
-    float col = (c0 + c1) + (c2 + c3);
-    const float other = __shfl_xor(col, 32);
-    col = (lane < 32) ? (col + other) : (other + col);
-    const int t = tok + (lane & 31);
-    if (lane < 32 && t < t1) dst[t] = col;
-    if (nxt < t1) {
+    __syncthreads();
+
+    Frag qf[SM_RB][SM_KK];
+    load_q(qf, Qh, row0, R, lane);
+    float b2[SM_RB][16];
 #pragma unroll
-      for (int kk = 0; kk < SM_KK; ++kk) kf[kk] = kn[kk];
-    }
+    for (int rb = 0; rb < SM_RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        b2[rb][i] = (float)(s_lse[rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3)] * 1.4426950408889634);
+
+    const int first = ta + wave * SM_TILE;
+    const int nt = (first < tb) ? ((tb - first - 1) / STEP + 1) : 0;      // tiles of this wave, the last may be ragged
+    MassEp ep{b2, a2, dst, tb, lane, 0.f, 0.f, 0.f, 0.f};
+    run_tiles<false>(Kh, first, nt, tb, lane, qf, ep);
+    cur = se;
   }
 }
 
@@ -259,22 +371,19 @@ bool mfma_score_supported(const Dims& m) {
 obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
                                float* scores, double* row_lse, hipStream_t st) {
   double* stats_part = (double*)(ws + w.stats_part);
-  const int RG = (m.R + SM_ROWS - 1) / SM_ROWS;
+  const int RG = w.rgroups;
   const size_t rg_stride = (size_t)m.heads * m.N;
   float* part = (RG > 1) ? (float*)(ws + w.score_part) : scores;
-  dim3 grid(w.nchunk * RG, m.heads);
+  Part pt;
+  pt.TH = w.tiles_per_head; pt.T = w.tiles_per_range; pt.TT = (long)m.heads * w.tiles_per_head;
+  dim3 grid(w.nranges * RG);
   { ProfScope prof_(ST_SCORE_STATS, st);
     hipLaunchKernelGGL(k_score_stats_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       stats_part, m.N, m.R, w.nchunk, RG); }
+                       stats_part, m.N, m.R, RG, pt, w.nslot); }
   if (check_launch("score stats (mfma)") != OBF_OK) return OBF_ERR_HIP;
-  const int total_rows = m.heads * m.R;
-  { ProfScope prof_(ST_SCORE_LSE, st);
-    hipLaunchKernelGGL(k_score_lse_mfma, dim3((total_rows + 255) / 256), dim3(256), 0, st, stats_part, row_lse, m.R,
-                       w.nchunk, total_rows); }
-  if (check_launch("score lse (mfma)") != OBF_OK) return OBF_ERR_HIP;
   { ProfScope prof_(ST_SCORE_MASS, st);
-    hipLaunchKernelGGL(k_score_mass_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q, row_lse,
-                       part, m.N, m.R, RG, rg_stride); }
+    hipLaunchKernelGGL(k_score_mass_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                       (const double*)stats_part, row_lse, part, m.N, m.R, RG, rg_stride, pt, w.nslot); }
   if (check_launch("score mass (mfma)") != OBF_OK) return OBF_ERR_HIP;
   if (RG > 1) {
     const size_t n = (size_t)m.heads * m.N;
