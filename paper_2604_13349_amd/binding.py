@@ -31,7 +31,7 @@ class _Shape(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, _LIB_NAME)
+    return os.environ.get("OBF_RELAY_LIB") or os.path.join(_HERE, _LIB_NAME)
 
 
 def load_library():

@@ -14,7 +14,7 @@ SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "select.hip", "refi
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + os.environ.get("OBF_EXTRA_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:

@@ -616,7 +616,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   int32_t* decided = nullptr;
   if (keep_cert_supported(m)) {
     decided = (int32_t*)(ws + w.decided);
-    if (launch_keep_cert(m, V, scores, idx, n_keep, max_budget, rank, state, decided, st) != OBF_OK) return OBF_ERR_HIP;
+    if (launch_keep_cert(m, V_out, scores, idx, n_keep, max_budget, rank, state, decided, st) != OBF_OK) return OBF_ERR_HIP;
   }
   { ProfScope prof_(ST_KEEP_BASIS, st); hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
                      m.N, m.d, max_budget, rank, state, basis, decided); }

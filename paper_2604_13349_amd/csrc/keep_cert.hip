@@ -7,7 +7,7 @@
 //         cores: products of bf16 values are exact in fp32, accumulation is fp32;
 //   mu  = (max(n, d) 2^-23)^2 ||V_keep||_F^2  +  allowance for the fp32 error of G and of the
 //         factorisation;
-//   if the Cholesky factorisation of G - mu I runs through with positive pivots, then
+//   if the LDL^T factorisation of G - mu I runs through with positive pivots (G - mu I positive definite), then
 //   sigma_min(V_keep)^2 >= lambda_min(G) > (max(n, d) 2^-23)^2 sigma_max(V_keep)^2, i.e. every singular
 //   value is above the rank rule's threshold: r = d.
 #include "common.hpp"
@@ -21,87 +21,139 @@ constexpr int KC_THREADS = 256;
 constexpr int KC_D = 128;
 constexpr int KC_TILE = 64;              // rows staged per iteration
 constexpr int KC_LDT = 132;              // staging row stride in bf16 (264 bytes: the two lane halves, 8 rows apart, use different banks)
-constexpr int KC_LDG = 129;              // Gram row stride in floats
 constexpr int KC_MAXROWS = 1536;
-constexpr float kCertErr = 4.0e-6f;      // allowance for fp32 Gram + Cholesky error, relative to trace(G)
+constexpr float kCertErr = 4.0e-6f;      // allowance for fp32 Gram + factorisation error, relative to trace(G)
 
 union FragU { uint32_t w[4]; bf16x8 v; };
 
-__global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __restrict__ V,
+// The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb).  A tile stays live in the
+// factorisation until its column block is finished, i.e. for 32 (cb + 1) steps; the assignment below gives each
+// wave the same total lifetime (5 units).  Each tile lives in one wave's MFMA accumulator registers from the
+// Gram phase to the end: entry i of lane l is G[rb*32 + (i/4)*8 + (l/32)*4 + (i%4)][cb*32 + l%32].
+__device__ __forceinline__ void wave_tiles(int wave, int (&rb)[4], int (&cb)[4], int& nt) {
+  if (wave == 0) { rb[0] = 3; cb[0] = 3; rb[1] = 0; cb[1] = 0; rb[2] = 0; cb[2] = 0; rb[3] = 0; cb[3] = 0; nt = 2; }
+  else if (wave == 1) { rb[0] = 3; cb[0] = 2; rb[1] = 3; cb[1] = 1; rb[2] = 0; cb[2] = 0; rb[3] = 0; cb[3] = 0; nt = 2; }
+  else if (wave == 2) { rb[0] = 2; cb[0] = 2; rb[1] = 2; cb[1] = 1; rb[2] = 0; cb[2] = 0; rb[3] = 0; cb[3] = 0; nt = 2; }
+  else { rb[0] = 1; cb[0] = 1; rb[1] = 1; cb[1] = 0; rb[2] = 2; cb[2] = 0; rb[3] = 3; cb[3] = 0; nt = 4; }
+}
+
+__global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __restrict__ Vkeep /*gathered rows [heads][max_budget][d]*/,
                                                              const float* __restrict__ scores,
                                                              const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ n_keep, int N, int max_budget,
                                                              int rank, HeadState* __restrict__ state,
                                                              int32_t* __restrict__ decided) {
-  __shared__ float G[KC_D * KC_LDG];                 // also the staging tile during the Gram phase
-  __shared__ double red[KC_THREADS / 64];
-  __shared__ int s_fail;
-  uint16_t* stage = (uint16_t*)G;                    // [KC_TILE][KC_LDT]
+  __shared__ uint16_t stage[2][KC_TILE * KC_LDT];
+  __shared__ __attribute__((aligned(16))) float col[2][KC_D];
+  __shared__ double red[KC_THREADS / 64], red2[KC_THREADS / 64];
   const int head = blockIdx.x;
   const int n = n_keep[head];
   const int n_del = N - n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, lh = lane >> 5;
   if (tid == 0) decided[head] = 0;
   if (!(rank > 0 && n > KC_D && n_del > 0)) return;
   const float* sc = scores + (size_t)head * N;
   const int32_t* id = idx + (size_t)head * max_budget;
-  const uint16_t* Vh = V + (size_t)head * N * KC_D;
+  const uint16_t* Vh = Vkeep + (size_t)head * max_budget * KC_D;      // row r of the head = V[idx[r]]
 
   const int stride = (n + KC_MAXROWS - 1) / KC_MAXROWS;
   const int rows = (n + stride - 1) / stride;
+  int trb[4], tcb[4], nt;
+  wave_tiles(wave, trb, tcb, nt);
 
   f32x16 acc[4];
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
+  for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-  for (int r0 = 0; r0 < rows; r0 += KC_TILE) {
-    __syncthreads();
-    // stage 64 rows: thread -> (row, 8-byte piece); 64 rows * 32 pieces = 2048 pieces
-    for (int e = tid; e < KC_TILE * 32; e += KC_THREADS) {
+  // ---- Gram phase: rows staged 64 at a time through LDS (double buffered); the loads run two tiles ahead in
+  // registers so that their latency is covered by the MFMAs and the transposing LDS reads of two tiles
+  uint2 pre[2][8];
+  auto fetch = [&](uint2 (&dst)[8], int r0) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int e = tid + q * KC_THREADS;
       const int r = e >> 5, c = e & 31;
-      uint2 val = make_uint2(0u, 0u);
-      if (r0 + r < rows) val = *(const uint2*)(Vh + (size_t)id[(size_t)(r0 + r) * stride] * KC_D + c * 4);
-      *(uint2*)(stage + r * KC_LDT + c * 4) = val;
+      dst[q] = make_uint2(0u, 0u);
+      if (r0 + r < rows) dst[q] = *(const uint2*)(Vh + (size_t)(r0 + r) * stride * KC_D + c * 4);
     }
-    __syncthreads();
+  };
+  auto put = [&](const uint2 (&src)[8], int buf) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int e = tid + q * KC_THREADS;
+      const int r = e >> 5, c = e & 31;
+      *(uint2*)(&stage[buf][r * KC_LDT + c * 4]) = src[q];
+    }
+  };
+  auto compute = [&](const uint16_t* st) {
 #pragma unroll
     for (int ks = 0; ks < KC_TILE / 16; ++ks) {
       FragU f[4];
-      const int tb = ks * 16 + (lane >> 5) * 8;
+      const int tb = ks * 16 + lh * 8;
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        const uint16_t* p = stage + tb * KC_LDT + cb * 32 + (lane & 31);
+      for (int c = 0; c < 4; ++c) {
+        const uint16_t* p = st + tb * KC_LDT + c * 32 + lr;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const uint32_t lo = p[(2 * i) * KC_LDT], hi = p[(2 * i + 1) * KC_LDT];
-          f[cb].w[i] = lo | (hi << 16);
+          f[c].w[i] = lo | (hi << 16);
         }
       }
-      // wave w owns output rows (channels) w*32..w*32+31 and all four column blocks
-      FragU own = f[0];
-      if (wave == 1) own = f[1];
-      if (wave == 2) own = f[2];
-      if (wave == 3) own = f[3];
+      if (wave == 0) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[3].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].v, f[0].v, acc[1], 0, 0, 0);
+      } else if (wave == 1) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[2].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[1].v, acc[1], 0, 0, 0);
+      } else if (wave == 2) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[2].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[1].v, acc[1], 0, 0, 0);
+      } else {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[1].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[0].v, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[0].v, acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[0].v, acc[3], 0, 0, 0);
+      }
+    }
+  };
+  fetch(pre[0], 0);
+  fetch(pre[1], KC_TILE);
+  put(pre[0], 0);
+  fetch(pre[0], 2 * KC_TILE);
+  __syncthreads();
+#ifdef KC_SKIP_GRAM
+  for (int r0 = 0; r0 < 0; r0 += 2 * KC_TILE) {
+#else
+  for (int r0 = 0; r0 < rows; r0 += 2 * KC_TILE) {
+#endif
+    // even tile: in stage[0]; pre[1] holds tile r0+64, pre[0] holds tile r0+128
+    compute(stage[0]);
+    put(pre[1], 1);
+    fetch(pre[1], r0 + 3 * KC_TILE);
+    __syncthreads();
+    if (r0 + KC_TILE < rows) compute(stage[1]);
+    put(pre[0], 0);
+    fetch(pre[0], r0 + 4 * KC_TILE);
+    __syncthreads();
+  }
+
+  // ---- trace(G), ||V_keep||_F^2, shift
+  // a lane holds a diagonal entry of a diagonal tile iff (lr % 8) / 4 == lh, at i = (lr / 8) * 4 + lr % 4
+  const bool has_diag = ((lr & 7) >> 2) == lh;
+  const int di = (lr >> 3) * 4 + (lr & 3);
+  double part = 0.0;
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb) acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(own.v, f[cb].v, acc[cb], 0, 0, 0);
+  for (int t = 0; t < 4; ++t) {
+    if (t < nt && trb[t] == tcb[t] && has_diag) {
+      float v = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) if (i == di) v = acc[t][i];
+      part += (double)v;
     }
   }
-  __syncthreads();
-#pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = wave * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-      const int col = cb * 32 + (lane & 31);
-      G[row * KC_LDG + col] = acc[cb][i];
-    }
-  __syncthreads();
-
-  // trace(G) and ||V_keep||_F^2 (equal when every retained row entered G)
-  double part = 0.0;
-  if (tid < KC_D) part = (double)G[tid * KC_LDG + tid];
   for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
   if (lane == 0) red[wave] = part;
   __syncthreads();
@@ -109,11 +161,10 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
   __syncthreads();
   double f2 = tr;
   if (stride > 1) {
-    // squared norms of all retained rows: 16 lanes per row, 8 bf16 each
     double p2 = 0.0;
     const int sub = tid >> 4, piece = tid & 15;
     for (int r = sub; r < n; r += KC_THREADS / 16) {
-      const uint4 q = *(const uint4*)(Vh + (size_t)id[r] * KC_D + piece * 8);
+      const uint4 q = *(const uint4*)(Vh + (size_t)r * KC_D + piece * 8);
       const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
       float s = 0.f;
 #pragma unroll
@@ -131,36 +182,67 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
   }
   const double thr_rel = (double)max(n, KC_D) * 1.1920928955078125e-07;
   const float mu = (float)(thr_rel * thr_rel * f2 + (double)kCertErr * tr);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    if (t < nt && trb[t] == tcb[t] && has_diag) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) if (i == di) acc[t][i] -= mu;
+    }
+  }
 
-  // right-looking Cholesky of G - mu I on the lower triangle; any non-positive pivot -> not certified
-  if (tid == 0) s_fail = 0;
-  if (tid < KC_D) G[tid * KC_LDG + tid] -= mu;
-  __syncthreads();
-  const int ty = tid >> 4, tx = tid & 15;
+  // ---- LDL^T of G - mu I in registers: step k publishes column k, everyone applies the rank-one update.
+  // A non-positive pivot only sets a flag (no early exit: the steps stay free of divergent control flow).
+  float g[4][16];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) g[t][i] = acc[t][i];
+  int cbuf = 0;
+  bool ok = true;
+#ifdef KC_SKIP_LDL
+  for (int k = 0; k < 0; ++k) {
+#else
   for (int k = 0; k < KC_D; ++k) {
-    const float piv = G[k * KC_LDG + k];
-    if (!(piv > 0.f)) { if (tid == 0) s_fail = 1; break; }           // uniform: every thread reads the same pivot
-    const float rinv = rsqrtf(piv);
-    __syncthreads();
-    for (int i = k + 1 + tid; i < KC_D; i += KC_THREADS) G[i * KC_LDG + k] *= rinv;
-    __syncthreads();
-    // trailing update on 16 x 16 interleaved blocks: rows i = ty + 16a, cols j = tx + 16b, k < j <= i
-    for (int i = ty + ((k + 1 - ty + 15) >> 4) * 16; i < KC_D; i += 16) {
-      const float lik = G[i * KC_LDG + k];
-      for (int j = tx + ((k + 1 - tx + 15) >> 4) * 16; j <= i; j += 16) G[i * KC_LDG + j] -= lik * G[j * KC_LDG + k];
+#endif
+    const int kb = k >> 5, kc = k & 31;
+    float* cw = col[cbuf];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (t < nt && tcb[t] == kb && lr == kc) {
+        float4* o = (float4*)(cw + trb[t] * 32 + lh * 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o[q * 2] = make_float4(g[t][q * 4], g[t][q * 4 + 1], g[t][q * 4 + 2], g[t][q * 4 + 3]);
+      }
     }
     __syncthreads();
+    const float piv = cw[k];
+    ok = ok && (piv > 0.f);
+    const float inv = __builtin_amdgcn_rcpf(piv);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (t < nt && tcb[t] >= kb) {
+        const float lj = cw[tcb[t] * 32 + lr] * inv;
+        const float4* lp = (const float4*)(cw + trb[t] * 32 + lh * 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 li = lp[q * 2];
+          g[t][q * 4 + 0] = fmaf(-li.x, lj, g[t][q * 4 + 0]);
+          g[t][q * 4 + 1] = fmaf(-li.y, lj, g[t][q * 4 + 1]);
+          g[t][q * 4 + 2] = fmaf(-li.z, lj, g[t][q * 4 + 2]);
+          g[t][q * 4 + 3] = fmaf(-li.w, lj, g[t][q * 4 + 3]);
+        }
+      }
+    }
+    cbuf ^= 1;
   }
-  __syncthreads();
-  if (s_fail) return;
+  if (!ok) return;
 
   // certified: r = d, OBF is the identity on this head; fill in the demand sums (Eq. 6) for the diagnostics
-  double pk = 0.0, pt = 0.0;
+  double pk = 0.0, ptot = 0.0;
   for (int i = tid; i < n; i += KC_THREADS) pk += (double)sc[id[i]];
-  for (int i = tid; i < N; i += KC_THREADS) pt += (double)sc[i];
-  for (int off = 32; off > 0; off >>= 1) { pk += __shfl_xor(pk, off); pt += __shfl_xor(pt, off); }
-  __shared__ double red2[KC_THREADS / 64];
-  if (lane == 0) { red[wave] = pk; red2[wave] = pt; }
+  for (int i = tid; i < N; i += KC_THREADS) ptot += (double)sc[i];
+  for (int off = 32; off > 0; off >>= 1) { pk += __shfl_xor(pk, off); ptot += __shfl_xor(ptot, off); }
+  if (lane == 0) { red[wave] = pk; red2[wave] = ptot; }
   __syncthreads();
   if (tid == 0) {
     const double a_keep = ((red[0] + red[1]) + red[2]) + red[3];
@@ -175,11 +257,11 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
 
 bool keep_cert_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == KC_D; }
 
-obf_status_t launch_keep_cert(const Dims& m, const void* V, const float* scores, const int32_t* idx,
+obf_status_t launch_keep_cert(const Dims& m, const void* Vkeep, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
                               int32_t* decided, hipStream_t st) {
   { ProfScope prof_(ST_KEEP_CERT, st);
-    hipLaunchKernelGGL(k_bf_keep_cert, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)V, scores, idx, n_keep,
+    hipLaunchKernelGGL(k_bf_keep_cert, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vkeep, scores, idx, n_keep,
                        m.N, max_budget, rank, state, decided); }
   return check_launch("backfill keep_cert");
 }
