@@ -39,7 +39,7 @@ def stage_bytes(stage: str, cfg, budgets, active_heads: int) -> float:
         return 4 * kept * d * es
     if stage == "del_stats":
         return active_heads * N * d * es
-    if stage == "keep_basis":
+    if stage in ("keep_basis", "keep_cert"):
         return kept * d * es + heads * N * 4
     if stage == "select":
         return heads * N * 4 + kept * 4

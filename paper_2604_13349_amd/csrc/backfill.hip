@@ -583,18 +583,20 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
 
 // ------------------------------------------------------------------------------------------------
 // inject: V_out[row] += delta for the retained rows of heads that were not skipped (Eq. 7)
+constexpr int INJ_BLOCKS = 8;
 template <typename T>
 __global__ void k_bf_inject(T* __restrict__ V_out, const float* __restrict__ delta, const HeadState* __restrict__ state,
                             int d, int max_budget) {
   const int head = blockIdx.y;
   const HeadState* s = state + head;
   if (!s->active) return;
-  const int n = s->n_keep;
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= n * d) return;
-  const int c = e % d;
-  T* p = V_out + (size_t)head * max_budget * d + e;
-  Elem<T>::store(p, Elem<T>::load(p) + delta[(size_t)head * d + c]);
+  const int total = s->n_keep * d;
+  T* base = V_out + (size_t)head * max_budget * d;
+  const float* dl = delta + (size_t)head * d;
+  for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += INJ_BLOCKS * blockDim.x) {
+    T* p = base + e;
+    Elem<T>::store(p, Elem<T>::load(p) + dl[e % d]);
+  }
 }
 
 template <typename T>
@@ -630,8 +632,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
                      w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag); }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
   if (rank > 0 && max_budget > 0) {
-    const int per = max_budget * m.d;
-    { ProfScope prof_(ST_INJECT, st); hipLaunchKernelGGL(k_bf_inject<T>, dim3((per + 255) / 256, m.heads), dim3(256), 0, st, (T*)V_out, delta, state, m.d,
+    { ProfScope prof_(ST_INJECT, st); hipLaunchKernelGGL(k_bf_inject<T>, dim3(INJ_BLOCKS, m.heads), dim3(256), 0, st, (T*)V_out, delta, state, m.d,
                        max_budget); }
     if (check_launch("backfill inject") != OBF_OK) return OBF_ERR_HIP;
   }

@@ -48,7 +48,13 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
 
   // 1. threshold = smallest retained score
   float tmin = INFINITY;
-  for (int i = threadIdx.x; i < n; i += RF_THREADS) tmin = fminf(tmin, sc[out[i]]);
+  for (int i0 = threadIdx.x; i0 < n; i0 += 8 * RF_THREADS) {      // batches of 8 independent index -> score loads
+    int j[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { const int i = i0 + q * RF_THREADS; j[q] = (i < n) ? out[i] : -1; }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) if (j[q] >= 0 && j[q] < N) tmin = fminf(tmin, sc[j[q]]);
+  }
   for (int off = 32; off > 0; off >>= 1) tmin = fminf(tmin, __shfl_xor(tmin, off));
   if (lane == 0) wred[wave] = tmin;
   if (threadIdx.x == 0) s_changed = 0;
@@ -58,15 +64,26 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   const float half = kBandRel * fabsf(tau);
   const float lo = tau - half, hi = tau + half;
 
-  // 2. band tokens in index order
-  const int seg = (N + RF_THREADS - 1) / RF_THREADS;
+  // 2. band tokens in index order (thread t owns a contiguous run of tokens; 16-byte loads when aligned)
+  int seg = (N + RF_THREADS - 1) / RF_THREADS;
+  seg = (seg + 3) & ~3;
   const int b0 = min(N, (int)threadIdx.x * seg), b1 = min(N, b0 + seg);
+  const bool vec = (N & 3) == 0;
   int cnt = 0;
-  for (int i = b0; i < b1; ++i) { const float s = sc[i]; cnt += (s >= lo && s <= hi); }
+  if (vec) {
+    for (int i = b0; i < b1; i += 4) {
+      const float4 v = *(const float4*)(sc + i);
+      cnt += (v.x >= lo && v.x <= hi) + (v.y >= lo && v.y <= hi) + (v.z >= lo && v.z <= hi) + (v.w >= lo && v.w <= hi);
+    }
+  } else {
+    for (int i = b0; i < b1; ++i) { const float s = sc[i]; cnt += (s >= lo && s <= hi); }
+  }
   int nband;
   int pos = rf_block_exscan(cnt, nband, wsum);
   if (nband <= 1 || nband > kBandCap) return;
-  for (int i = b0; i < b1; ++i) { const float s = sc[i]; if (s >= lo && s <= hi) band[pos++] = i; }
+  if (cnt > 0) {
+    for (int i = b0; i < b1; ++i) { const float s = sc[i]; if (s >= lo && s <= hi) band[pos++] = i; }
+  }
 
   // 3. membership bitmap of the current retained set
   const int words = (N + 31) / 32;

@@ -1,12 +1,10 @@
 // TopK_B (Sec. 4.3.2): the B largest scores of a head, ties to the lowest index, written as an
-// ascending index list.  One workgroup per head; the N keys live in LDS.  All comparisons are
+// ascending index list.  One workgroup per head; the N keys live in registers.  All comparisons are
 // on an order-preserving integer image of the fp32 bit patterns, so the result is exact.
 #include "common.hpp"
 
 namespace obf {
 
-constexpr int SEL_THREADS = 1024;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int SEL_BATCH = 256;   // heads per launch when budgets differ per head
 
 struct BudgetBatch { int32_t b[SEL_BATCH]; };
@@ -18,6 +16,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 }
 
 // exclusive prefix sums of (a, b) over the workgroup, in thread order
+template <int SEL_WAVES>
 __device__ __forceinline__ void block_exscan2(int a, int b, int& ea, int& eb, int& ta, int& tb, int* wsum /*[2*SEL_WAVES]*/) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int ia = a, ib = b;
@@ -38,94 +37,119 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int& ea, int& eb, in
   __syncthreads();
 }
 
+// Thread t owns the SEG consecutive tokens starting at t*SEG (keys stay in registers).  The key of rank B is
+// found by bisection on the 32 key bits, most significant first: T is the largest value with
+// count(key >= T) >= B.  Counting is one ballot + population count per owned token and one workgroup sum per bit.
+template <int SEG, int SEL_THREADS>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict__ scores, int N, int head0,
                                                         int uniform_budget, BudgetBatch per_head, int use_per_head,
                                                         int max_budget, int32_t* __restrict__ idx,
                                                         int32_t* __restrict__ n_keep) {
-  extern __shared__ uint32_t keys[];           // [N]
-  __shared__ int hist[256];
+  constexpr int SEL_WAVES = SEL_THREADS / 64;
+  __shared__ int wcnt[2][SEL_WAVES];
   __shared__ int wsum[2 * SEL_WAVES];
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_remaining;
   const int head = head0 + blockIdx.x;
   const float* sc = scores + (size_t)head * N;
   int32_t* out = idx + (size_t)head * max_budget;
   int B = use_per_head ? per_head.b[blockIdx.x] : uniform_budget;
   if (B > N) B = N;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   if (B == 0 || B == N) {
-    for (int i = threadIdx.x; i < max_budget; i += SEL_THREADS) out[i] = (i < B) ? i : -1;
-    if (threadIdx.x == 0) n_keep[head] = B;
+    for (int i = tid; i < max_budget; i += SEL_THREADS) out[i] = (i < B) ? i : -1;
+    if (tid == 0) n_keep[head] = B;
     return;
   }
-  for (int i = threadIdx.x; i < N; i += SEL_THREADS) keys[i] = order_key(sc[i]);
-  if (threadIdx.x == 0) { s_prefix = 0u; s_remaining = B; }
-  __syncthreads();
-
-  // radix select, most significant byte first: find the key T of rank B (1-based, descending)
-  uint32_t mask = 0u;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int i = threadIdx.x; i < 256; i += SEL_THREADS) hist[i] = 0;
-    __syncthreads();
-    const uint32_t prefix = s_prefix;
-    for (int i = threadIdx.x; i < N; i += SEL_THREADS) {
-      const uint32_t k = keys[i];
-      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+  const int base = tid * SEG;
+  uint32_t key[SEG];
+  int nvalid = min(SEG, max(0, N - base));                     // tokens of this thread inside the head
+  if (nvalid == SEG && ((N & 3) == 0)) {
+#pragma unroll
+    for (int i = 0; i < SEG; i += 4) {
+      const float4 v = *(const float4*)(sc + base + i);
+      key[i] = order_key(v.x); key[i + 1] = order_key(v.y); key[i + 2] = order_key(v.z); key[i + 3] = order_key(v.w);
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int rem = s_remaining, bin = 255;
-      for (; bin > 0; --bin) {
-        const int c = hist[bin];
-        if (c >= rem) break;
-        rem -= c;
-      }
-      s_remaining = rem;
-      s_prefix = prefix | ((uint32_t)bin << shift);
-    }
-    mask |= 255u << shift;
-    __syncthreads();
+  } else {
+#pragma unroll
+    for (int i = 0; i < SEG; ++i) key[i] = (i < nvalid) ? order_key(sc[base + i]) : 0u;
   }
-  const uint32_t T = s_prefix;
-  const int need_eq = s_remaining;     // how many keys equal to T are kept (the lowest indices)
 
-  // ordered compaction: thread t owns tokens [t*seg, (t+1)*seg)
-  const int seg = (N + SEL_THREADS - 1) / SEL_THREADS;
-  const int b0 = min(N, (int)threadIdx.x * seg), b1 = min(N, b0 + seg);
+  auto count_ge = [&](uint32_t cand, int buf) -> int {
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(i < nvalid && key[i] >= cand));
+    if (lane == 0) wcnt[buf][wave] = c;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < SEL_WAVES; ++w) tot += wcnt[buf][w];
+    return tot;
+  };
+
+  uint32_t T = 0u;
+  int buf = 0;
+#ifndef SEL_BITS
+#define SEL_BITS 32
+#endif
+  for (int bit = 31; bit >= 32 - SEL_BITS; --bit) {
+    const uint32_t cand = T | (1u << bit);
+    if (count_ge(cand, buf) >= B) T = cand;
+    buf ^= 1;
+  }
+  // keys greater than T are all kept; of the keys equal to T the lowest indices fill the rest
+  int n_gt = 0;
+  if (T != 0xffffffffu) n_gt = count_ge(T + 1u, buf);
+  buf ^= 1;
+  const int need_eq = B - n_gt;
+
+#ifdef SEL_SKIP_COMPACT
+  if (tid == 0) n_keep[head] = B + (int)T + need_eq;
+  return;
+#endif
   int cg = 0, ce = 0;
-  for (int i = b0; i < b1; ++i) { const uint32_t k = keys[i]; cg += (k > T); ce += (k == T); }
+#pragma unroll
+  for (int i = 0; i < SEG; ++i) { if (i < nvalid) { cg += (key[i] > T); ce += (key[i] == T); } }
   int eg, ee, tg, te;
-  block_exscan2(cg, ce, eg, ee, tg, te, wsum);
-  for (int i = b0; i < b1; ++i) {
-    const uint32_t k = keys[i];
-    if (k > T) { out[eg + min(ee, need_eq)] = i; ++eg; }
-    else if (k == T) { if (ee < need_eq) out[eg + ee] = i; ++ee; }
+  block_exscan2<SEL_WAVES>(cg, ce, eg, ee, tg, te, wsum);
+#pragma unroll
+  for (int i = 0; i < SEG; ++i) {
+    if (i < nvalid) {
+      const uint32_t k = key[i];
+      if (k > T) { out[eg + min(ee, need_eq)] = base + i; ++eg; }
+      else if (k == T) { if (ee < need_eq) out[eg + ee] = base + i; ++ee; }
+    }
   }
-  for (int i = B + threadIdx.x; i < max_budget; i += SEL_THREADS) out[i] = -1;
-  if (threadIdx.x == 0) n_keep[head] = B;
+  for (int i = B + tid; i < max_budget; i += SEL_THREADS) out[i] = -1;
+  if (tid == 0) n_keep[head] = B;
 }
 
-obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
-                           int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st) {
-  const size_t smem = sizeof(uint32_t) * (size_t)m.N;
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_select, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxTokens * 4);
-    attr_done = true;
-  }
+template <int SEG, int SEL_THREADS>
+static obf_status_t launch_select_seg(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
+                                      int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st) {
   BudgetBatch bb;
   if (!budgets_host) {
-    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL(k_select, dim3(m.heads), dim3(SEL_THREADS), smem, st, scores, m.N, 0, budget, bb, 0, max_budget,
+    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL((k_select<SEG, SEL_THREADS>), dim3(m.heads), dim3(SEL_THREADS), 0, st, scores, m.N, 0, budget, bb, 0, max_budget,
                        idx, n_keep); }
     return check_launch("select");
   }
   for (int h0 = 0; h0 < m.heads; h0 += SEL_BATCH) {
     const int nb = (m.heads - h0 < SEL_BATCH) ? (m.heads - h0) : SEL_BATCH;
     for (int i = 0; i < nb; ++i) bb.b[i] = budgets_host[h0 + i];
-    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL(k_select, dim3(nb), dim3(SEL_THREADS), smem, st, scores, m.N, h0, 0, bb, 1, max_budget, idx, n_keep); }
+    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL((k_select<SEG, SEL_THREADS>), dim3(nb), dim3(SEL_THREADS), 0, st, scores, m.N, h0, 0, bb, 1, max_budget, idx, n_keep); }
     if (check_launch("select") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;
+}
+
+obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
+                           int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st) {
+  // few waves per head keep the per-bit workgroup sum cheap; 32 keys per thread is the register budget
+  if (m.N <= 4 * 256) return launch_select_seg<4, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
+  if (m.N <= 8 * 256) return launch_select_seg<8, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
+  if (m.N <= 16 * 256) return launch_select_seg<16, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
+  if (m.N <= 32 * 256) return launch_select_seg<32, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
+  if (m.N <= 32 * 512) return launch_select_seg<32, 512>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
+  return launch_select_seg<32, 1024>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
 }
 
 }  // namespace obf

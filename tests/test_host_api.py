@@ -1,0 +1,93 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header
+declares, sizes its workspace, and rejects bad arguments before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_13349_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.lib_path()):
+        from paper_2604_13349_amd import build
+        build.build(verbose=False)
+    return B.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "obf_relay.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(obf_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"obf_score", "obf_select_topk", "obf_refine_boundary", "obf_gather", "obf_backfill",
+            "obf_compress_relay", "obf_workspace_bytes", "obf_last_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in obf_relay.h but not exported"
+
+
+def test_version_and_stage_names(lib):
+    assert b"gfx950" in lib.obf_version()
+    stages = B.profile_stages()
+    assert stages[0] == "score_stats" and "gather" in stages and len(stages) == lib.obf_profile_stage_count()
+
+
+def test_workspace_bytes_and_unsupported_shapes(lib):
+    ok = B.make_shape(36, 8, 4, 128, 8192, 32, "bf16")
+    need = B.workspace_bytes(ok, 1229, 8)
+    assert need > 0 and need % 256 == 0
+    assert B.workspace_bytes(B.make_shape(1, 1, 1, 100, 64, 1, "bf16"), 8, 1) == 0     # head_dim
+    assert B.workspace_bytes(B.make_shape(1, 1, 1, 128, 40000, 1, "bf16"), 8, 1) == 0  # too many tokens
+    assert B.workspace_bytes(B.make_shape(0, 1, 1, 128, 64, 1, "bf16"), 8, 1) == 0
+    assert B.workspace_bytes(ok, -1, 1) == 0 and B.workspace_bytes(ok, 8, -1) == 0
+
+
+def _status(lib, fn, *args):
+    rc = fn(*args)
+    return rc, lib.obf_last_error().decode()
+
+
+def test_argument_errors_are_reported_before_any_device_work(lib):
+    sh = B.make_shape(2, 2, 2, 64, 100, 4, "f32")
+    fake = C.c_void_p(256 * 7)          # never dereferenced: every call below must fail on the host
+    rc, msg = _status(lib, lib.obf_score, C.byref(sh), None, fake, fake, None, fake, 1 << 30, None)
+    assert rc == 1 and "K" in msg
+    rc, msg = _status(lib, lib.obf_score, C.byref(sh), fake, fake, fake, None, None, 0, None)
+    assert rc == 1 and "workspace" in msg
+    rc, msg = _status(lib, lib.obf_score, C.byref(sh), fake, fake, fake, None, C.c_void_p(257), 1 << 30, None)
+    assert rc == 1 and "aligned" in msg
+    rc, msg = _status(lib, lib.obf_score, C.byref(sh), fake, fake, fake, None, fake, 16, None)
+    assert rc == 3 and "too small" in msg
+    rc, msg = _status(lib, lib.obf_select_topk, C.byref(sh), fake, None, -1, 10, fake, fake, None, 0, None)
+    assert rc == 1 and "budget" in msg
+    rc, msg = _status(lib, lib.obf_select_topk, C.byref(sh), fake, None, 50, 10, fake, fake, None, 0, None)
+    assert rc == 1 and "max_budget" in msg
+    budgets = (C.c_int32 * 4)(1, 2, 300, 4)     # 300 > n_tokens clamps to 100 > max_budget 10
+    rc, msg = _status(lib, lib.obf_select_topk, C.byref(sh), fake, C.cast(budgets, C.c_void_p), 0, 10, fake, fake, None, 0, None)
+    assert rc == 1 and "budgets_host[2]" in msg
+    rc, msg = _status(lib, lib.obf_gather, C.byref(sh), None, fake, fake, fake, 10, fake, None, None)
+    assert rc == 1 and "K_out" in msg
+    rc, msg = _status(lib, lib.obf_backfill, C.byref(sh), fake, fake, fake, fake, 10, -2, fake, None, None, fake, 1 << 30, None)
+    assert rc == 1 and "rank" in msg
+    bad = B.make_shape(2, 2, 2, 96, 100, 4, "f32")
+    rc, msg = _status(lib, lib.obf_compress_relay, C.byref(bad), fake, fake, fake, None, 5, 5, 1, fake, fake, fake, fake,
+                      None, None, None, fake, 1 << 30, None)
+    assert rc == 2 and "head_dim" in msg
+    rc, msg = _status(lib, lib.obf_compress_relay, None, fake, fake, fake, None, 5, 5, 1, fake, fake, fake, fake,
+                      None, None, None, fake, 1 << 30, None)
+    assert rc == 1 and "shape" in msg
+    assert lib.obf_profile_enable(999) == 1
+
+
+def test_binding_raises_without_library(monkeypatch, tmp_path):
+    monkeypatch.setenv("OBF_RELAY_LIB", str(tmp_path / "missing.so"))
+    monkeypatch.setattr(B, "_lib", None)
+    with pytest.raises(ImportError):
+        B.load_library()
