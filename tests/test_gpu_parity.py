@@ -165,3 +165,60 @@ def test_select_stage_is_exact_on_given_scores(gpu):
             ref = O.select_topk(key, b)
             assert n_keep[0, h] == b and np.array_equal(idx[0, h, :b], ref), f"head {h} budget {b}"
             assert np.all(idx[0, h, b:] == -1)
+
+
+# --------------------------------------------------------------------------- full sizes, sampled heads
+def _full_size(gpu, name, seed, sample, expect_active):
+    """The whole named config through the fused call (the launch configuration bench.py times);
+    the oracle checks a sample of heads one by one, every head is checked for structure."""
+    cfg = si.CONFIGS[name]
+    K, V, Q = si.make_cache(cfg, seed, threads=16)
+    bud = si.budgets(cfg, seed)
+    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=cfg.rank)
+    L, H, N = cfg.n_layers, cfg.n_kv_heads, cfg.n_tokens
+    nk = np.minimum(bud, N)
+    assert np.array_equal(out["n_keep"], nk)
+    for l in range(L):
+        for h in range(H):
+            b = int(nk[l, h])
+            ix = out["idx"][l, h]
+            assert np.all(np.diff(ix[:b]) > 0) and ix[0] >= 0 and ix[b - 1] < N and np.all(ix[b:] == -1)
+            assert abs(float(out["scores"][l, h].sum(dtype=np.float64)) - cfg.rows) < 1e-3 * cfg.rows   # Eq. 1: rows sum to one
+    rng = np.random.default_rng(1234 + seed)
+    heads = [(int(l), int(h)) for l, h in zip(rng.integers(0, L, sample), rng.integers(0, H, sample))]
+    heads += [(0, 0), (L - 1, H - 1)]
+    active = 0
+    for (l, h) in heads:
+        ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), cfg.rank, cfg.dtype)
+        rep = parity.check_head(f"{name}[{l},{h}]", ref, K[l, h], V[l, h], cfg.dtype, int(bud[l, h]),
+                                out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
+                                gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
+        active += int(rep.skipped == 0)
+    if expect_active:
+        assert active > 0
+    else:
+        assert active == 0 and int((out["diag"]["skipped"] == 0).sum()) == 0
+
+
+def test_full_config2(gpu):
+    _full_size(gpu, "2", 0, 10, False)
+
+
+def test_full_config3(gpu):
+    _full_size(gpu, "3", 0, 8, False)
+
+
+def test_full_config3_shadow(gpu):
+    _full_size(gpu, "3s", 0, 6, True)
+
+
+def test_full_config4(gpu):
+    _full_size(gpu, "4", 0, 4, False)
+
+
+def test_full_config5_agent1(gpu):
+    _full_size(gpu, "5", 1, 3, False)
+
+
+def test_full_paper_shape(gpu):
+    _full_size(gpu, "paper", 0, 16, True)
