@@ -154,11 +154,11 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
 obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const int32_t* idx, const int32_t* n_keep,
                            int32_t max_budget, void* K_out, void* V_out, hipStream_t st);
 bool keep_cert_supported(const Dims& m);
-obf_status_t launch_keep_cert(const Dims& m, const void* Vkeep, const float* scores, const int32_t* idx,
+obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
                               int32_t* decided, hipStream_t st);
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st);
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, bool cert_done = false);
 
 }  // namespace obf

@@ -21,23 +21,23 @@ constexpr int KC_THREADS = 256;
 constexpr int KC_D = 128;
 constexpr int KC_TILE = 64;              // rows staged per iteration
 constexpr int KC_LDT = 132;              // staging row stride in bf16 (264 bytes: the two lane halves, 8 rows apart, use different banks)
-constexpr int KC_MAXROWS = 1536;
+constexpr int KC_MINROWS = 1536;         // rows entering G: all up to 1536, else about max(1536, n/4) at a constant stride
 constexpr float kCertErr = 4.0e-6f;      // allowance for fp32 Gram + factorisation error, relative to trace(G)
 
 union FragU { uint32_t w[4]; bf16x8 v; };
 
-// The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb).  A tile stays live in the
-// factorisation until its column block is finished, i.e. for 32 (cb + 1) steps; the assignment below gives each
-// wave the same total lifetime (5 units).  Each tile lives in one wave's MFMA accumulator registers from the
-// Gram phase to the end: entry i of lane l is G[rb*32 + (i/4)*8 + (l/32)*4 + (i%4)][cb*32 + l%32].
-__device__ __forceinline__ void wave_tiles(int wave, int (&rb)[4], int (&cb)[4], int& nt) {
-  if (wave == 0) { rb[0] = 3; cb[0] = 3; rb[1] = 0; cb[1] = 0; rb[2] = 0; cb[2] = 0; rb[3] = 0; cb[3] = 0; nt = 2; }
-  else if (wave == 1) { rb[0] = 3; cb[0] = 2; rb[1] = 3; cb[1] = 1; rb[2] = 0; cb[2] = 0; rb[3] = 0; cb[3] = 0; nt = 2; }
-  else if (wave == 2) { rb[0] = 2; cb[0] = 2; rb[1] = 2; cb[1] = 1; rb[2] = 0; cb[2] = 0; rb[3] = 0; cb[3] = 0; nt = 2; }
-  else { rb[0] = 1; cb[0] = 1; rb[1] = 1; cb[1] = 0; rb[2] = 2; cb[2] = 0; rb[3] = 3; cb[3] = 0; nt = 4; }
+// The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb).  Each tile lives in one wave's
+// registers from the Gram phase to the end of the factorisation: entry i of lane l is
+// G[rb*32 + (i/4)*8 + (l/32)*4 + (i%4)][cb*32 + l%32].  No wave holds two tiles of the same column block, so the
+// part of a step that the next pivot column waits for is at most one tile update per wave.
+__device__ __forceinline__ void wave_tiles(int wave, int (&rb)[3], int (&cb)[3], int& nt) {
+  if (wave == 0) { rb[0] = 0; cb[0] = 0; rb[1] = 1; cb[1] = 1; rb[2] = 3; cb[2] = 2; nt = 3; }
+  else if (wave == 1) { rb[0] = 1; cb[0] = 0; rb[1] = 2; cb[1] = 1; rb[2] = 3; cb[2] = 3; nt = 3; }
+  else if (wave == 2) { rb[0] = 2; cb[0] = 0; rb[1] = 3; cb[1] = 1; rb[2] = 0; cb[2] = 0; nt = 2; }
+  else { rb[0] = 3; cb[0] = 0; rb[1] = 2; cb[1] = 2; rb[2] = 0; cb[2] = 0; nt = 2; }
 }
 
-__global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __restrict__ Vkeep /*gathered rows [heads][max_budget][d]*/,
+__global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* __restrict__ Vsrc /*via_idx ? V [heads][N][d] : gathered rows [heads][max_budget][d]*/, int via_idx,
                                                              const float* __restrict__ scores,
                                                              const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ n_keep, int N, int max_budget,
@@ -49,22 +49,25 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
   const int head = blockIdx.x;
   const int n = n_keep[head];
   const int n_del = N - n;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept in a scalar register
   const int lr = lane & 31, lh = lane >> 5;
   if (tid == 0) decided[head] = 0;
   if (!(rank > 0 && n > KC_D && n_del > 0)) return;
   const float* sc = scores + (size_t)head * N;
   const int32_t* id = idx + (size_t)head * max_budget;
-  const uint16_t* Vh = Vkeep + (size_t)head * max_budget * KC_D;      // row r of the head = V[idx[r]]
+  const uint16_t* Vh = Vsrc + (size_t)head * (via_idx ? N : max_budget) * KC_D;
+  auto row_of = [&](int r) -> size_t { return via_idx ? (size_t)id[r] : (size_t)r; };    // retained row r of the head
 
-  const int stride = (n + KC_MAXROWS - 1) / KC_MAXROWS;
+  const int cap = max(KC_MINROWS, n >> 2);
+  const int stride = (n + cap - 1) / cap;
   const int rows = (n + stride - 1) / stride;
-  int trb[4], tcb[4], nt;
+  int trb[3], tcb[3], nt;
   wave_tiles(wave, trb, tcb, nt);
 
-  f32x16 acc[4];
+  f32x16 acc[3];
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < 3; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
       const int e = tid + q * KC_THREADS;
       const int r = e >> 5, c = e & 31;
       dst[q] = make_uint2(0u, 0u);
-      if (r0 + r < rows) dst[q] = *(const uint2*)(Vh + (size_t)(r0 + r) * stride * KC_D + c * 4);
+      if (r0 + r < rows) dst[q] = *(const uint2*)(Vh + row_of((r0 + r) * stride) * KC_D + c * 4);
     }
   };
   auto put = [&](const uint2 (&src)[8], int buf) {
@@ -103,19 +106,19 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
         }
       }
       if (wave == 0) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[3].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].v, f[0].v, acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].v, f[0].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[1].v, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[2].v, acc[2], 0, 0, 0);
       } else if (wave == 1) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[2].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[1].v, acc[1], 0, 0, 0);
-      } else if (wave == 2) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[2].v, acc[0], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[0].v, acc[0], 0, 0, 0);
         acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[1].v, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[3].v, acc[2], 0, 0, 0);
+      } else if (wave == 2) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[0].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[1].v, acc[1], 0, 0, 0);
       } else {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[1].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[0].v, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[0].v, acc[2], 0, 0, 0);
-        acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[0].v, acc[3], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[0].v, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[2].v, acc[1], 0, 0, 0);
       }
     }
   };
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
   const int di = (lr >> 3) * 4 + (lr & 3);
   double part = 0.0;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < 3; ++t) {
     if (t < nt && trb[t] == tcb[t] && has_diag) {
       float v = 0.f;
 #pragma unroll
@@ -163,16 +166,24 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
   if (stride > 1) {
     double p2 = 0.0;
     const int sub = tid >> 4, piece = tid & 15;
-    for (int r = sub; r < n; r += KC_THREADS / 16) {
-      const uint4 q = *(const uint4*)(Vh + (size_t)r * KC_D + piece * 8);
-      const uint32_t w4[4] = {q.x, q.y, q.z, q.w};
-      float s = 0.f;
+    for (int r0 = sub; r0 < n; r0 += 8 * (KC_THREADS / 16)) {          // 8 independent row pieces in flight per lane
+      uint4 q[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float a = __uint_as_float(w4[i] << 16), b = __uint_as_float(w4[i] & 0xffff0000u);
-        s = fmaf(a, a, s); s = fmaf(b, b, s);
+      for (int u = 0; u < 8; ++u) {
+        const int r = r0 + u * (KC_THREADS / 16);
+        q[u] = (r < n) ? *(const uint4*)(Vh + row_of(r) * KC_D + piece * 8) : make_uint4(0u, 0u, 0u, 0u);
       }
-      p2 += (double)s;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t w4[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float a = __uint_as_float(w4[i] << 16), b = __uint_as_float(w4[i] & 0xffff0000u);
+          s = fmaf(a, a, s); s = fmaf(b, b, s);
+        }
+        p2 += (double)s;
+      }
     }
     for (int off = 32; off > 0; off >>= 1) p2 += __shfl_xor(p2, off);
     if (lane == 0) red[wave] = p2;
@@ -183,64 +194,95 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
   const double thr_rel = (double)max(n, KC_D) * 1.1920928955078125e-07;
   const float mu = (float)(thr_rel * thr_rel * f2 + (double)kCertErr * tr);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < 3; ++t) {
     if (t < nt && trb[t] == tcb[t] && has_diag) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) if (i == di) acc[t][i] -= mu;
     }
   }
 
-  // ---- LDL^T of G - mu I in registers: step k publishes column k, everyone applies the rank-one update.
-  // A non-positive pivot only sets a flag (no early exit: the steps stay free of divergent control flow).
-  float g[4][16];
+  // ---- LDL^T of G - mu I in registers with one column of look-ahead.  Column k is in col[k & 1] when step k
+  // starts.  A step first updates the one tile (per wave) that holds column k+1 and publishes that column, then
+  // updates the rest, so the chain pivot -> next pivot only contains one tile update.  A non-positive pivot sets a
+  // flag (no early exit: the steps stay free of divergent control flow).
+  float g[3][16];
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < 3; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) g[t][i] = acc[t][i];
-  int cbuf = 0;
-  bool ok = true;
-#ifdef KC_SKIP_LDL
-  for (int k = 0; k < 0; ++k) {
-#else
-  for (int k = 0; k < KC_D; ++k) {
-#endif
+  auto publish = [&](int k) {
     const int kb = k >> 5, kc = k & 31;
-    float* cw = col[cbuf];
+    float* cw = col[k & 1];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < 3; ++t) {
       if (t < nt && tcb[t] == kb && lr == kc) {
         float4* o = (float4*)(cw + trb[t] * 32 + lh * 4);
 #pragma unroll
         for (int q = 0; q < 4; ++q) o[q * 2] = make_float4(g[t][q * 4], g[t][q * 4 + 1], g[t][q * 4 + 2], g[t][q * 4 + 3]);
       }
     }
-    __syncthreads();
+  };
+  auto update = [&](int t, const float* cw, float inv) {
+    const float lj = cw[tcb[t] * 32 + lr] * inv;
+    const float4* lp = (const float4*)(cw + trb[t] * 32 + lh * 4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 li = lp[q * 2];
+      g[t][q * 4 + 0] = fmaf(-li.x, lj, g[t][q * 4 + 0]);
+      g[t][q * 4 + 1] = fmaf(-li.y, lj, g[t][q * 4 + 1]);
+      g[t][q * 4 + 2] = fmaf(-li.z, lj, g[t][q * 4 + 2]);
+      g[t][q * 4 + 3] = fmaf(-li.w, lj, g[t][q * 4 + 3]);
+    }
+  };
+  bool ok = true;
+  publish(0);
+#ifdef KC_SKIP_LDL
+  for (int k = 0; k < 0; ++k) {
+#else
+  for (int k = 0; k < KC_D; ++k) {
+#endif
+    __syncthreads();                                   // column k visible; column k-1's buffer free again
+    const float* cw = col[k & 1];
+    const int kb = k >> 5;
+    const int kbn = (k + 1) >> 5;                      // column block of the next pivot column
     const float piv = cw[k];
     ok = ok && (piv > 0.f);
     const float inv = __builtin_amdgcn_rcpf(piv);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      if (t < nt && tcb[t] >= kb) {
-        const float lj = cw[tcb[t] * 32 + lr] * inv;
-        const float4* lp = (const float4*)(cw + trb[t] * 32 + lh * 4);
+    for (int t = 0; t < 3; ++t)
+      if (t < nt && tcb[t] == kbn && tcb[t] >= kb) update(t, cw, inv);
+    if (k + 1 < KC_D) publish(k + 1);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float4 li = lp[q * 2];
-          g[t][q * 4 + 0] = fmaf(-li.x, lj, g[t][q * 4 + 0]);
-          g[t][q * 4 + 1] = fmaf(-li.y, lj, g[t][q * 4 + 1]);
-          g[t][q * 4 + 2] = fmaf(-li.z, lj, g[t][q * 4 + 2]);
-          g[t][q * 4 + 3] = fmaf(-li.w, lj, g[t][q * 4 + 3]);
-        }
-      }
-    }
-    cbuf ^= 1;
+    for (int t = 0; t < 3; ++t)
+      if (t < nt && tcb[t] != kbn && tcb[t] >= kb) update(t, cw, inv);
   }
   if (!ok) return;
 
   // certified: r = d, OBF is the identity on this head; fill in the demand sums (Eq. 6) for the diagnostics
   double pk = 0.0, ptot = 0.0;
-  for (int i = tid; i < n; i += KC_THREADS) pk += (double)sc[id[i]];
-  for (int i = tid; i < N; i += KC_THREADS) ptot += (double)sc[i];
+  for (int i0 = tid; i0 < n; i0 += 8 * KC_THREADS) {              // batches of independent index -> score loads
+    int j[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { const int i = i0 + u * KC_THREADS; j[u] = (i < n) ? id[i] : -1; }
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (j[u] >= 0) ? sc[j[u]] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) pk += (double)v[u];
+  }
+  if ((N & 3) == 0) {
+    const float4* sc4 = (const float4*)sc;
+    const int n4 = N >> 2;
+    for (int i0 = tid; i0 < n4; i0 += 8 * KC_THREADS) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { const int i = i0 + u * KC_THREADS; v[u] = (i < n4) ? sc4[i] : make_float4(0.f, 0.f, 0.f, 0.f); }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) ptot += ((double)v[u].x + (double)v[u].y) + ((double)v[u].z + (double)v[u].w);
+    }
+  } else {
+    for (int i = tid; i < N; i += KC_THREADS) ptot += (double)sc[i];
+  }
   for (int off = 32; off > 0; off >>= 1) { pk += __shfl_xor(pk, off); ptot += __shfl_xor(ptot, off); }
   if (lane == 0) { red[wave] = pk; red2[wave] = ptot; }
   __syncthreads();
@@ -257,11 +299,11 @@ __global__ __launch_bounds__(KC_THREADS) void k_bf_keep_cert(const uint16_t* __r
 
 bool keep_cert_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == KC_D; }
 
-obf_status_t launch_keep_cert(const Dims& m, const void* Vkeep, const float* scores, const int32_t* idx,
+obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
                               int32_t* decided, hipStream_t st) {
   { ProfScope prof_(ST_KEEP_CERT, st);
-    hipLaunchKernelGGL(k_bf_keep_cert, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vkeep, scores, idx, n_keep,
+    hipLaunchKernelGGL(k_bf_keep_cert, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, via_idx, scores, idx, n_keep,
                        m.N, max_budget, rank, state, decided); }
   return check_launch("backfill keep_cert");
 }

@@ -71,6 +71,7 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   const bool vec = (N & 3) == 0;
   int cnt = 0;
   if (vec) {
+#pragma unroll 8
     for (int i = b0; i < b1; i += 4) {
       const float4 v = *(const float4*)(sc + i);
       cnt += (v.x >= lo && v.x <= hi) + (v.y >= lo && v.y <= hi) + (v.z >= lo && v.z <= hi) + (v.w >= lo && v.w <= hi);

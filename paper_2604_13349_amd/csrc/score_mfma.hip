@@ -46,7 +46,11 @@ __device__ __forceinline__ void load_q(Frag (&qf)[SM_RB][SM_KK], const uint16_t*
 }
 
 __device__ __forceinline__ void load_k(Frag (&kf)[SM_KK], const uint16_t* __restrict__ Kh, int tok0, int t_end, int lane) {
+#ifdef SM_NO_LOAD
+  const int t = min((tok0 & 127) + (lane & 31), t_end - 1), kh = (lane >> 5) * 8;   // experiment: stay in cache
+#else
   const int t = min(tok0 + (lane & 31), t_end - 1), kh = (lane >> 5) * 8;
+#endif
   const uint4* p = (const uint4*)(Kh + (size_t)t * SM_D + kh);
 #pragma unroll
   for (int kk = 0; kk < SM_KK; ++kk) kf[kk].u = p[kk * 2];
@@ -139,6 +143,12 @@ struct MassEp {
   float c0, c1, c2, c3;
   template <int RB>
   __device__ __forceinline__ void block(const f32x16& acc, int tok) {
+#ifdef SM_NO_EPILOGUE
+    if (RB == 0) { c0 = 0.f; c1 = 0.f; c2 = 0.f; c3 = 0.f; }
+    c0 += acc[0] + acc[5] + acc[10] + acc[15];
+    if (RB == SM_RB - 1) { const int t = tok + (lane & 31); if (lane < 32 && t < t_end) dst[t] = c0; }
+    return;
+#endif
     if (RB == 0) { c0 = 0.f; c1 = 0.f; c2 = 0.f; c3 = 0.f; }
 #pragma unroll
     for (int i = 0; i < 16; i += 4) {
