@@ -37,7 +37,8 @@ __device__ __forceinline__ void wave_tiles(int wave, int (&rb)[3], int (&cb)[3],
   else { rb[0] = 3; cb[0] = 0; rb[1] = 2; cb[1] = 2; rb[2] = 0; cb[2] = 0; nt = 2; }
 }
 
-__global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* __restrict__ Vsrc /*via_idx ? V [heads][N][d] : gathered rows [heads][max_budget][d]*/, int via_idx,
+template <bool via_idx>
+__global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* __restrict__ Vsrc /*via_idx ? V [heads][N][d] : gathered rows [heads][max_budget][d]*/,
                                                              const float* __restrict__ scores,
                                                              const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ n_keep, int N, int max_budget,
@@ -303,8 +304,12 @@ obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, cons
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
                               int32_t* decided, hipStream_t st) {
   { ProfScope prof_(ST_KEEP_CERT, st);
-    hipLaunchKernelGGL(k_bf_keep_cert, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, via_idx, scores, idx, n_keep,
-                       m.N, max_budget, rank, state, decided); }
+    if (via_idx)
+      hipLaunchKernelGGL(k_bf_keep_cert<true>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
+                         n_keep, m.N, max_budget, rank, state, decided);
+    else
+      hipLaunchKernelGGL(k_bf_keep_cert<false>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
+                         n_keep, m.N, max_budget, rank, state, decided); }
   return check_launch("backfill keep_cert");
 }
 
