@@ -219,8 +219,8 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
   float* scores = scores_out ? scores_out : (float*)(base + w.scores);
   double* row_lse = (double*)(base + w.row_lse);
   OBF_TRY(run_score(m, w, base, K, Qwin, scores, row_lse, st));
-  OBF_TRY(launch_select(m, scores, budgets_host, budget, max_budget, idx, n_keep, st));
-  OBF_TRY(launch_refine(m, w, base, K, Qwin, scores, row_lse, max_budget, idx, n_keep, st));
+  // selection and boundary refinement in one kernel (same decisions as the two stage calls)
+  OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
   OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st));
   OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st));
   return OBF_OK;

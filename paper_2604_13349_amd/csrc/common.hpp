@@ -148,6 +148,9 @@ obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, cons
                                float* scores, double* row_lse, hipStream_t st);
 obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                            int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st);
+obf_status_t launch_select_refine(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
+                                  int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
+                                  const double* row_lse, hipStream_t st);
 obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
                            const float* scores, const double* row_lse, int32_t max_budget, int32_t* idx,
                            const int32_t* n_keep, hipStream_t st);

@@ -4,7 +4,7 @@
 // of the threshold are re-scored in double from the K / Qwin bits and the per-row
 // log-sum-exp, and the retained slots inside the band are re-assigned by that exact order
 // (ties to the lowest index).  Tokens outside the band keep their decision.
-#include "common.hpp"
+#include "boundary.hpp"
 
 namespace obf {
 
@@ -98,34 +98,14 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   rf_block_exscan(kb, nkb, wsum);
   if (nkb == 0 || nkb == nband) return;
 
-  // 4. exact scores of the band tokens: one wave per token, lanes over query rows
-  const T* Kh = K + (size_t)head * N * d;
-  const T* Qh = Q + (size_t)head * R * d;
-  const double* lse = row_lse + (size_t)head * R;
-  const double scale = 1.0 / sqrt((double)d);
-  for (int b = wave; b < nband; b += RF_WAVES) {
-    const T* kr = Kh + (size_t)band[b] * d;
-    double part = 0.0;
-    for (int r = lane; r < R; r += 64) {
-      const T* qr = Qh + (size_t)r * d;
-      double acc = 0.0;
-      for (int c = 0; c < d; ++c) acc = fma((double)Elem<T>::load(qr + c), (double)Elem<T>::load(kr + c), acc);
-      part += exp(acc * scale - lse[r]);
-    }
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-    if (lane == 0) band_score[b] = part;
-  }
+  // 4. exact scores of the band tokens
+  rescore_band<T, RF_WAVES>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, band,
+                            nband, band_score);
   __syncthreads();
 
-  // 5. the nkb best band tokens (exact score descending, index ascending) are retained
+  // 5. the nkb best band tokens are retained
   if (threadIdx.x < nband) {
-    const double mine = band_score[threadIdx.x];
-    int rank = 0;
-    for (int u = 0; u < nband; ++u) {
-      const double o = band_score[u];
-      rank += (o > mine) || (o == mine && u < (int)threadIdx.x);     // band[] is ascending in index
-    }
-    const int keep = rank < nkb;
+    const int keep = band_keeps(band_score, nband, nkb, threadIdx.x);
     keep_new[threadIdx.x] = keep;
     if (keep != kb) s_changed = 1;
   }

@@ -1,7 +1,7 @@
 // TopK_B (Sec. 4.3.2): the B largest scores of a head, ties to the lowest index, written as an
 // ascending index list.  One workgroup per head; the N keys live in registers.  All comparisons are
 // on an order-preserving integer image of the fp32 bit patterns, so the result is exact.
-#include "common.hpp"
+#include "boundary.hpp"
 
 namespace obf {
 
@@ -13,6 +13,10 @@ struct BudgetBatch { int32_t b[SEL_BATCH]; };
 __device__ __forceinline__ uint32_t order_key(float f) {
   const uint32_t u = __float_as_uint(f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
 // exclusive prefix sums of (a, b) over the workgroup, in thread order
@@ -40,12 +44,20 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int& ea, int& eb, in
 // Thread t owns the SEG consecutive tokens starting at t*SEG (keys stay in registers).  The key of rank B is
 // found by bisection on the 32 key bits, most significant first: T is the largest value with
 // count(key >= T) >= B.  Counting is one ballot + population count per owned token and one workgroup sum per bit.
-template <int SEG, int SEL_THREADS>
+// With REFINE the tokens whose score lies in the relative band around the threshold are re-decided in double from K, Q
+// and the row log-sum-exp before the list is written (same decisions as select followed by the refinement kernel).
+template <int SEG, int SEL_THREADS, bool REFINE, typename ET>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict__ scores, int N, int head0,
                                                         int uniform_budget, BudgetBatch per_head, int use_per_head,
                                                         int max_budget, int32_t* __restrict__ idx,
-                                                        int32_t* __restrict__ n_keep) {
+                                                        int32_t* __restrict__ n_keep, const ET* __restrict__ K,
+                                                        const ET* __restrict__ Q, const double* __restrict__ row_lse,
+                                                        int d, int R) {
   constexpr int SEL_WAVES = SEL_THREADS / 64;
+  __shared__ int band[REFINE ? kBandCap : 1];
+  __shared__ double band_score[REFINE ? kBandCap : 1];
+  __shared__ int keep_new[REFINE ? kBandCap : 1];
+  __shared__ int s_changed;
   __shared__ int wcnt[2][SEL_WAVES];
   __shared__ int wsum[2 * SEL_WAVES];
   const int head = head0 + blockIdx.x;
@@ -111,45 +123,141 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   for (int i = 0; i < SEG; ++i) { if (i < nvalid) { cg += (key[i] > T); ce += (key[i] == T); } }
   int eg, ee, tg, te;
   block_exscan2<SEL_WAVES>(cg, ce, eg, ee, tg, te, wsum);
+
+  bool refined = false;
+  int bpos0 = 0;
+  float lo = 0.f, hi = 0.f;
+  if (REFINE) {
+    // band around the threshold score, in the same float arithmetic as the standalone refinement
+    const float tau = key_to_float(T);
+    const float half = kBandRel * fabsf(tau);
+    lo = tau - half; hi = tau + half;
+    int cb = 0, ckb = 0;
+    {
+      int er = ee;                                      // running count of keys equal to T before this token
 #pragma unroll
-  for (int i = 0; i < SEG; ++i) {
-    if (i < nvalid) {
-      const uint32_t k = key[i];
-      if (k > T) { out[eg + min(ee, need_eq)] = base + i; ++eg; }
-      else if (k == T) { if (ee < need_eq) out[eg + ee] = base + i; ++ee; }
+      for (int i = 0; i < SEG; ++i) {
+        if (i < nvalid) {
+          const uint32_t k = key[i];
+          const float s = key_to_float(k);
+          const bool kept = (k > T) || (k == T && er < need_eq);
+          er += (k == T);
+          if (s >= lo && s <= hi) { ++cb; ckb += kept; }
+        }
+      }
     }
+    int ebk, nband, nkb;
+    block_exscan2<SEL_WAVES>(cb, ckb, bpos0, ebk, nband, nkb, wsum);
+    if (tid == 0) s_changed = 0;
+    if (nband > 1 && nband <= kBandCap && nkb > 0 && nkb < nband) {       // uniform
+      int bp = bpos0, er = ee;
+#pragma unroll
+      for (int i = 0; i < SEG; ++i) {
+        if (i < nvalid) {
+          const uint32_t k = key[i];
+          const float s = key_to_float(k);
+          const bool kept = (k > T) || (k == T && er < need_eq);
+          er += (k == T);
+          if (s >= lo && s <= hi) { band[bp] = base + i; keep_new[bp] = kept; ++bp; }
+        }
+      }
+      __syncthreads();
+      rescore_band<ET, SEL_WAVES>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R,
+                                 band, nband, band_score);
+      __syncthreads();
+      int keep = 0, was = 0;
+      if (tid < nband) { was = keep_new[tid]; keep = band_keeps(band_score, nband, nkb, tid); if (keep != was) s_changed = 1; }
+      __syncthreads();
+      if (tid < nband) keep_new[tid] = keep;
+      __syncthreads();
+      refined = s_changed != 0;
+    }
+  }
+
+  if (!refined) {
+#pragma unroll
+    for (int i = 0; i < SEG; ++i) {
+      if (i < nvalid) {
+        const uint32_t k = key[i];
+        if (k > T) { out[eg + min(ee, need_eq)] = base + i; ++eg; }
+        else if (k == T) { if (ee < need_eq) out[eg + ee] = base + i; ++ee; }
+      }
+    }
+  } else {
+    // membership changed inside the band: recount positions from the final flags
+    uint32_t flags = 0u;
+    int cnt = 0;
+    {
+      int bp = bpos0, er = ee;
+#pragma unroll
+      for (int i = 0; i < SEG; ++i) {
+        if (i < nvalid) {
+          const uint32_t k = key[i];
+          const float s = key_to_float(k);
+          bool kept = (k > T) || (k == T && er < need_eq);
+          er += (k == T);
+          if (s >= lo && s <= hi) { kept = keep_new[bp] != 0; ++bp; }
+          if (kept) { flags |= 1u << i; ++cnt; }
+        }
+      }
+    }
+    int e0, e1, t0, t1;
+    block_exscan2<SEL_WAVES>(cnt, 0, e0, e1, t0, t1, wsum);
+#pragma unroll
+    for (int i = 0; i < SEG; ++i) if (flags & (1u << i)) out[e0++] = base + i;
   }
   for (int i = B + tid; i < max_budget; i += SEL_THREADS) out[i] = -1;
   if (tid == 0) n_keep[head] = B;
 }
 
-template <int SEG, int SEL_THREADS>
+template <int SEG, int SEL_THREADS, bool REFINE, typename T>
 static obf_status_t launch_select_seg(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
-                                      int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st) {
+                                      int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
+                                      const double* row_lse, hipStream_t st) {
   BudgetBatch bb;
   if (!budgets_host) {
-    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL((k_select<SEG, SEL_THREADS>), dim3(m.heads), dim3(SEL_THREADS), 0, st, scores, m.N, 0, budget, bb, 0, max_budget,
-                       idx, n_keep); }
+    { ProfScope prof_(ST_SELECT, st);
+      hipLaunchKernelGGL((k_select<SEG, SEL_THREADS, REFINE, T>), dim3(m.heads), dim3(SEL_THREADS), 0, st, scores, m.N, 0,
+                         budget, bb, 0, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R); }
     return check_launch("select");
   }
   for (int h0 = 0; h0 < m.heads; h0 += SEL_BATCH) {
     const int nb = (m.heads - h0 < SEL_BATCH) ? (m.heads - h0) : SEL_BATCH;
     for (int i = 0; i < nb; ++i) bb.b[i] = budgets_host[h0 + i];
-    { ProfScope prof_(ST_SELECT, st); hipLaunchKernelGGL((k_select<SEG, SEL_THREADS>), dim3(nb), dim3(SEL_THREADS), 0, st, scores, m.N, h0, 0, bb, 1, max_budget, idx, n_keep); }
+    { ProfScope prof_(ST_SELECT, st);
+      hipLaunchKernelGGL((k_select<SEG, SEL_THREADS, REFINE, T>), dim3(nb), dim3(SEL_THREADS), 0, st, scores, m.N, h0, 0, bb,
+                         1, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R); }
     if (check_launch("select") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;
 }
 
+template <bool REFINE, typename T>
+static obf_status_t dispatch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
+                                    int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
+                                    const double* row_lse, hipStream_t st) {
+  // few waves per head keep the per-bit workgroup sum cheap; 32 keys per thread is the register budget
+#define OBF_SEL(SEG, THR) launch_select_seg<SEG, THR, REFINE, T>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st)
+  if (m.N <= 4 * 256) return OBF_SEL(4, 256);
+  if (m.N <= 8 * 256) return OBF_SEL(8, 256);
+  if (m.N <= 16 * 256) return OBF_SEL(16, 256);
+  if (m.N <= 32 * 256) return OBF_SEL(32, 256);
+  if (m.N <= 32 * 512) return OBF_SEL(32, 512);
+  return OBF_SEL(32, 1024);
+#undef OBF_SEL
+}
+
 obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                            int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st) {
-  // few waves per head keep the per-bit workgroup sum cheap; 32 keys per thread is the register budget
-  if (m.N <= 4 * 256) return launch_select_seg<4, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
-  if (m.N <= 8 * 256) return launch_select_seg<8, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
-  if (m.N <= 16 * 256) return launch_select_seg<16, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
-  if (m.N <= 32 * 256) return launch_select_seg<32, 256>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
-  if (m.N <= 32 * 512) return launch_select_seg<32, 512>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
-  return launch_select_seg<32, 1024>(m, scores, budgets_host, budget, max_budget, idx, n_keep, st);
+  return dispatch_select<false, float>(m, scores, budgets_host, budget, max_budget, idx, n_keep, nullptr, nullptr, nullptr, st);
+}
+
+obf_status_t launch_select_refine(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
+                                  int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
+                                  const double* row_lse, hipStream_t st) {
+  if (m.dtype == OBF_BF16)
+    return dispatch_select<true, uint16_t>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st);
+  return dispatch_select<true, float>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st);
 }
 
 }  // namespace obf

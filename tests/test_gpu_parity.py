@@ -222,3 +222,57 @@ def test_full_config5_agent1(gpu):
 
 def test_full_paper_shape(gpu):
     _full_size(gpu, "paper", 0, 16, True)
+
+
+# --------------------------------------------------------------------------- boundary refinement really decides
+def _bf16_next_toward_zero(bits):
+    """The neighbouring bf16 value with smaller magnitude (bit pattern arithmetic on the magnitude)."""
+    return np.uint16(bits - 1) if (bits & 0x7FFF) != 0 else bits
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_near_tie_at_threshold_is_decided_exactly(gpu, dtype, d):
+    """Two tokens whose exact masses differ by less than fp32 can resolve straddle the budget boundary; the
+    lower index is the (slightly) lighter one, so an fp32 tie-break would keep the wrong token."""
+    cfg = si.RelayConfig("neartie", 11, 1, 1, 2, d, 1536, 16, 150, 0, dtype, "structured")
+    K, V, Q = si.make_cache(cfg, 0)
+    Kh = K[0, 0]
+    ref0 = O.compress_head(Kh, V[0, 0], Q[0, 0:cfg.group], cfg.budget, 0, dtype)
+    order = np.argsort(-ref0.A, kind="stable")
+    a = int(order[cfg.budget - 1])                     # the last retained token
+    dropped = [int(j) for j in order[cfg.budget + 20:] if j < a]
+    assert dropped, "need a dropped token at a lower index"
+    p = dropped[0]
+    found = False
+    for c in np.argsort(np.abs(O.decode(Kh[a], dtype))):       # smallest components first: smallest nudges
+        row = Kh[a].copy()
+        if dtype == "bf16":
+            row[c] = _bf16_next_toward_zero(row[c])
+        else:
+            row[c] = np.nextafter(row[c], np.float32(0.0))
+        Kt = Kh.copy(); Kt[p] = row
+        A = O.attention_mass(O.decode(Kt, dtype), O.decode(Q[0, 0:cfg.group], dtype).reshape(-1, d))
+        rel = (A[a] - A[p]) / A[a]
+        if 1e-9 < rel < 2e-7:                          # lighter by less than an fp32 ulp of the score
+            srt = np.sort(A)[::-1]
+            if srt[cfg.budget - 2] > A[a] * (1 + 1e-5) and srt[cfg.budget + 1] < A[p] * (1 - 1e-5):
+                found = True
+                break
+    assert found, "could not build a near tie"
+    K2 = K.copy(); K2[0, 0] = Kt
+    ref = O.compress_head(Kt, V[0, 0], Q[0, 0:cfg.group], cfg.budget, 0, dtype)
+    assert a in ref.idx and p not in ref.idx
+    out = gpu.run_fused(cfg, K2, V, Q, budget=cfg.budget, rank=0)
+    assert np.array_equal(out["idx"][0, 0], ref.idx), "fused call: near tie decided differently from exact arithmetic"
+    # the staged calls give the same list
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    Kd, Qd = gpu.to_dev(K2, dtype), gpu.to_dev(Q, dtype)
+    sh = Bd.shape_of(Kd, Qd)
+    scores, lse = Bd.score(Kd, Qd)
+    idx, n_keep = Bd.select_topk(sh, scores, budget=cfg.budget)
+    plain = idx.cpu().numpy()[0, 0].copy()
+    Bd.refine_boundary(Kd, Qd, scores, lse, idx, n_keep)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy()[0, 0], ref.idx)
+    print("fp32 selection alone agreed with exact arithmetic:", bool(np.array_equal(plain, ref.idx)))
