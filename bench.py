@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline (0: skip)")
     ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (0: all)")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the timed region (a kernel of known "
+                         "traffic that calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -106,6 +109,13 @@ def main() -> int:
             else:
                 outs[i] = B.compress_relay(c["K"], c["V"], c["Q"], budgets=c["bud"].reshape(-1), **kw)
 
+    if args.copy_mib > 0:
+        src = torch.empty(args.copy_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                    # reads and writes copy_mib MiB once each
+        torch.cuda.synchronize()
+        del src, dst
     stages = B.profile_stages()
     for _ in range(max(1, args.warmup)):
         step()
