@@ -45,7 +45,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
                                                              int rank, HeadState* __restrict__ state,
                                                              int32_t* __restrict__ decided) {
   __shared__ uint16_t stage[2][KC_TILE * KC_LDT];
-  __shared__ __attribute__((aligned(16))) float col[2][KC_D];
+  __shared__ __attribute__((aligned(16))) float panel[2][KC_D][4];
   __shared__ double red[KC_THREADS / 64], red2[KC_THREADS / 64];
   const int head = blockIdx.x;
   const int n = n_keep[head];
@@ -202,60 +202,83 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     }
   }
 
-  // ---- LDL^T of G - mu I in registers with one column of look-ahead.  Column k is in col[k & 1] when step k
-  // starts.  A step first updates the one tile (per wave) that holds column k+1 and publishes that column, then
-  // updates the rest, so the chain pivot -> next pivot only contains one tile update.  A non-positive pivot sets a
-  // flag (no early exit: the steps stay free of divergent control flow).
+  // ---- LDL^T of G - mu I in registers, four columns per step.  panel[s & 1][row] holds columns 4s .. 4s+3 of
+  // the current matrix when step s starts.  Every thread factors the 4x4 diagonal block itself (the same
+  // arithmetic everywhere, so no broadcast), turns the panel rows it needs into L d (a 4-term forward
+  // substitution per row) and applies the rank-4 update to its tiles: first to the one tile (per wave) that holds
+  // the next four columns, which are then published, then to the rest, so the chain block -> next block only
+  // contains one tile update.  A non-positive pivot sets a flag (no early exit: the steps stay free of
+  // divergent control flow); entries above the diagonal are carried along and never read.
   float g[3][16];
 #pragma unroll
   for (int t = 0; t < 3; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) g[t][i] = acc[t][i];
-  auto publish = [&](int k) {
+  auto publish = [&](int k) {                         // columns k .. k+3 (k % 4 == 0) -> panel[(k / 4) & 1]
     const int kb = k >> 5, kc = k & 31;
-    float* cw = col[k & 1];
+    float* pw = &panel[(k >> 2) & 1][0][0];
 #pragma unroll
     for (int t = 0; t < 3; ++t) {
-      if (t < nt && tcb[t] == kb && lr == kc) {
-        float4* o = (float4*)(cw + trb[t] * 32 + lh * 4);
+      if (t < nt && tcb[t] == kb && (lr & ~3) == kc) {
+        const int c = lr & 3;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) o[q * 2] = make_float4(g[t][q * 4], g[t][q * 4 + 1], g[t][q * 4 + 2], g[t][q * 4 + 3]);
+        for (int i = 0; i < 16; ++i) pw[(trb[t] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)) * 4 + c] = g[t][i];
       }
-    }
-  };
-  auto update = [&](int t, const float* cw, float inv) {
-    const float lj = cw[tcb[t] * 32 + lr] * inv;
-    const float4* lp = (const float4*)(cw + trb[t] * 32 + lh * 4);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float4 li = lp[q * 2];
-      g[t][q * 4 + 0] = fmaf(-li.x, lj, g[t][q * 4 + 0]);
-      g[t][q * 4 + 1] = fmaf(-li.y, lj, g[t][q * 4 + 1]);
-      g[t][q * 4 + 2] = fmaf(-li.z, lj, g[t][q * 4 + 2]);
-      g[t][q * 4 + 3] = fmaf(-li.w, lj, g[t][q * 4 + 3]);
     }
   };
   bool ok = true;
   publish(0);
 #ifdef KC_SKIP_LDL
-  for (int k = 0; k < 0; ++k) {
+  for (int k = 0; k < 0; k += 4) {
 #else
-  for (int k = 0; k < KC_D; ++k) {
+  for (int k = 0; k < KC_D; k += 4) {
 #endif
-    __syncthreads();                                   // column k visible; column k-1's buffer free again
-    const float* cw = col[k & 1];
+    __syncthreads();                                   // this panel visible; the previous one free again
+    const float4* pr = (const float4*)&panel[(k >> 2) & 1][0][0];
     const int kb = k >> 5;
-    const int kbn = (k + 1) >> 5;                      // column block of the next pivot column
-    const float piv = cw[k];
-    ok = ok && (piv > 0.f);
-    const float inv = __builtin_amdgcn_rcpf(piv);
+    const int kbn = (k + 4) >> 5;                      // column block of the next four columns
+    // 4x4 diagonal block: rows k .. k+3, lower triangle
+    const float4 r0 = pr[k], r1 = pr[k + 1], r2 = pr[k + 2], r3 = pr[k + 3];
+    const float d0 = r0.x;
+    const float i0 = __builtin_amdgcn_rcpf(d0);
+    const float l10 = r1.x * i0, l20 = r2.x * i0, l30 = r3.x * i0;
+    const float d1 = fmaf(-l10, r1.x, r1.y);
+    const float i1 = __builtin_amdgcn_rcpf(d1);
+    const float l21 = fmaf(-l20, r1.x, r2.y) * i1, l31 = fmaf(-l30, r1.x, r3.y) * i1;
+    const float y21 = l21 * d1, y31 = l31 * d1;
+    const float d2 = fmaf(-l21, y21, fmaf(-l20, r2.x, r2.z));
+    const float i2 = __builtin_amdgcn_rcpf(d2);
+    const float l32 = fmaf(-l31, y21, fmaf(-l30, r2.x, r3.z)) * i2;
+    const float y32 = l32 * d2;
+    const float d3 = fmaf(-l32, y32, fmaf(-l31, y31, fmaf(-l30, r3.x, r3.w)));
+    ok = ok && (d0 > 0.f) && (d1 > 0.f) && (d2 > 0.f) && (d3 > 0.f);
+    const float i3 = __builtin_amdgcn_rcpf(d3);
+    // y = L d of a panel row x: y0 = x0, y1 = x1 - y0 l10, y2 = x2 - y0 l20 - y1 l21, y3 = x3 - y0 l30 - y1 l31 - y2 l32
+    auto solve = [&](const float4 x, float& y0, float& y1, float& y2, float& y3) {
+      y0 = x.x;
+      y1 = fmaf(-y0, l10, x.y);
+      y2 = fmaf(-y1, l21, fmaf(-y0, l20, x.z));
+      y3 = fmaf(-y2, l32, fmaf(-y1, l31, fmaf(-y0, l30, x.w)));
+    };
+    auto update = [&](int t) {
+      float a0, a1, a2, a3;
+      solve(pr[tcb[t] * 32 + lr], a0, a1, a2, a3);     // the lane's column j, as row j of the panel
+      const float c0 = a0 * i0, c1 = a1 * i1, c2 = a2 * i2, c3 = a3 * i3;      // L[j][k .. k+3]
+      const float4* rp = pr + trb[t] * 32 + lh * 4;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float y0, y1, y2, y3;
+        solve(rp[(i >> 2) * 8 + (i & 3)], y0, y1, y2, y3);
+        g[t][i] = fmaf(-y3, c3, fmaf(-y2, c2, fmaf(-y1, c1, fmaf(-y0, c0, g[t][i]))));
+      }
+    };
 #pragma unroll
     for (int t = 0; t < 3; ++t)
-      if (t < nt && tcb[t] == kbn && tcb[t] >= kb) update(t, cw, inv);
-    if (k + 1 < KC_D) publish(k + 1);
+      if (t < nt && tcb[t] == kbn && tcb[t] >= kb) update(t);
+    if (k + 4 < KC_D) publish(k + 4);
 #pragma unroll
     for (int t = 0; t < 3; ++t)
-      if (t < nt && tcb[t] != kbn && tcb[t] >= kb) update(t, cw, inv);
+      if (t < nt && tcb[t] != kbn && tcb[t] >= kb) update(t);
   }
   if (!ok) return;
 
