@@ -602,7 +602,7 @@ __global__ void k_bf_inject(T* __restrict__ V_out, const float* __restrict__ del
 template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
-                        float* delta_out, obf_diag_t* diag, hipStream_t st, bool cert_done) {
+                        float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part) {
   HeadState* state = (HeadState*)(ws + w.head_state);
   float* basis = (float*)(ws + w.basis);
   float* gram_part = (float*)(ws + w.gram_part);
@@ -618,7 +618,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   int32_t* decided = nullptr;
   if (keep_cert_supported(m)) {
     decided = (int32_t*)(ws + w.decided);
-    if (!cert_done && launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st) != OBF_OK)
+    if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part) != OBF_OK)
       return OBF_ERR_HIP;
   }
   { ProfScope prof_(ST_KEEP_BASIS, st); hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
@@ -642,10 +642,10 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
 
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, bool cert_done) {
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part) {
   if (m.dtype == OBF_BF16)
-    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, cert_done);
-  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, cert_done);
+    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part);
+  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part);
 }
 
 }  // namespace obf

@@ -10,6 +10,7 @@ namespace obf {
 constexpr int kMaxTokens = 32768;
 constexpr int kNumCU = 256;             // compute units of the target (MI355X)
 constexpr int kStatChunk = 1024;        // tokens per deleted-value statistics workgroup
+constexpr int kGatherRows = 16;         // rows per gather workgroup when a row is 256 bytes (bf16, head_dim 128)
 constexpr int kBandCap = 256;           // most boundary candidates re-scored per head
 constexpr double kEps = 1e-12;          // epsilon of Eq. 4 / Eq. 6
 constexpr float kBandRel = 1.0e-4f;     // relative half-width of the refinement band
@@ -44,6 +45,7 @@ struct Workspace {
   size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
   size_t delta;        // float   [heads][d]
   size_t band;         // BandEntry [heads][kBandCap]
+  size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
   size_t total;
   int nchunk;          // score chunks per head
   int chunk_tokens;    // tokens per score chunk
@@ -64,7 +66,7 @@ struct HeadState {
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 inline Workspace carve(const Dims& m, int max_budget, int rank) {
-  (void)max_budget; (void)rank;
+  (void)rank;
   Workspace w;
   // reference-precision score path: fixed chunks of 512 tokens
   w.chunk_tokens = 512;
@@ -99,6 +101,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.mats = take(sizeof(float) * (size_t)m.heads * 3 * m.d * m.d);
   w.delta = take(sizeof(float) * (size_t)m.heads * m.d);
   w.band = take(16 * (size_t)m.heads * kBandCap);
+  w.fro_part = take(sizeof(double) * (size_t)m.heads * ((max_budget > 0 ? max_budget : 0) / kGatherRows + 1));
   w.total = off;
   return w;
 }
@@ -155,13 +158,14 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
                            const float* scores, const double* row_lse, int32_t max_budget, int32_t* idx,
                            const int32_t* n_keep, hipStream_t st);
 obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const int32_t* idx, const int32_t* n_keep,
-                           int32_t max_budget, void* K_out, void* V_out, hipStream_t st);
+                           int32_t max_budget, void* K_out, void* V_out, hipStream_t st, double* fro_part = nullptr);
 bool keep_cert_supported(const Dims& m);
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
-                              int32_t* decided, hipStream_t st);
+                              int32_t* decided, hipStream_t st, const double* fro_part = nullptr);
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, bool cert_done = false);
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st,
+                             const double* fro_part = nullptr);
 
 }  // namespace obf

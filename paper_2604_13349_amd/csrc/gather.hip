@@ -9,33 +9,53 @@ constexpr int GA_THREADS = 256;
 __global__ __launch_bounds__(GA_THREADS) void k_gather(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                        const int32_t* __restrict__ idx,
                                                        const int32_t* __restrict__ n_keep, int N, int row_vec /*uint4 per row*/,
-                                                       int max_budget, uint4* __restrict__ K_out, uint4* __restrict__ V_out) {
+                                                       int max_budget, uint4* __restrict__ K_out, uint4* __restrict__ V_out,
+                                                       double* __restrict__ fro_part /*bf16 rows of 256 bytes only*/) {
+  __shared__ float s_red[GA_THREADS / 64];
   const int head = blockIdx.y;
   const int rows_per_block = GA_THREADS / row_vec;
   const int r = blockIdx.x * rows_per_block + threadIdx.x / row_vec;
   const int c = threadIdx.x % row_vec;
-  if (r >= max_budget) return;
+  if (r >= max_budget && !fro_part) return;
   const int n = n_keep[head];
   const size_t o = ((size_t)head * max_budget + r) * row_vec + c;
   uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-  if (r < n) {
+  if (r < n && r < max_budget) {
     const int j = idx[(size_t)head * max_budget + r];
     const size_t s = ((size_t)head * N + j) * row_vec + c;
     if (K_out) kv = K[s];
     if (V_out) vv = V[s];
   }
-  if (K_out) K_out[o] = kv;
-  if (V_out) V_out[o] = vv;
+  if (r < max_budget) {
+    if (K_out) K_out[o] = kv;
+    if (V_out) V_out[o] = vv;
+  }
+  if (fro_part) {
+    // sum of squares of this workgroup's V rows (zero for the padding), in a fixed order
+    const uint32_t w4[4] = {vv.x, vv.y, vv.z, vv.w};
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float a = __uint_as_float(w4[i] << 16), b = __uint_as_float(w4[i] & 0xffff0000u);
+      sq = fmaf(a, a, sq); sq = fmaf(b, b, sq);
+    }
+    for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      fro_part[(size_t)head * gridDim.x + blockIdx.x] = ((double)s_red[0] + (double)s_red[1]) + ((double)s_red[2] + (double)s_red[3]);
+  }
 }
 
 obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const int32_t* idx, const int32_t* n_keep,
-                           int32_t max_budget, void* K_out, void* V_out, hipStream_t st) {
+                           int32_t max_budget, void* K_out, void* V_out, hipStream_t st, double* fro_part) {
   if (max_budget == 0 || (!K_out && !V_out)) return OBF_OK;
+  if (!(m.dtype == OBF_BF16 && m.d * m.esize == 256 && V_out)) fro_part = nullptr;
   const int row_vec = m.d * m.esize / 16;            // 8, 16 or 32
   const int rows_per_block = GA_THREADS / row_vec;
   dim3 grid((max_budget + rows_per_block - 1) / rows_per_block, m.heads);
   { ProfScope prof_(ST_GATHER, st); hipLaunchKernelGGL(k_gather, grid, dim3(GA_THREADS), 0, st, (const uint4*)K, (const uint4*)V, idx, n_keep, m.N, row_vec,
-                     max_budget, (uint4*)K_out, (uint4*)V_out); }
+                     max_budget, (uint4*)K_out, (uint4*)V_out, fro_part); }
   return check_launch("gather");
 }
 

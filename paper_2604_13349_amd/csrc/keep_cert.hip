@@ -3,7 +3,7 @@
 // head_dim.  It is a sufficient test only: heads it cannot certify go to the reference-precision
 // basis kernel.
 //
-//   G   = V_s^T V_s over a strided subset V_s of the retained rows (all rows up to 1536), on the matrix
+//   G   = V_s^T V_s over a strided subset V_s of the retained rows (all rows up to 768), on the matrix
 //         cores: products of bf16 values are exact in fp32, accumulation is fp32;
 //   mu  = (max(n, d) 2^-23)^2 ||V_keep||_F^2  +  allowance for the fp32 error of G and of the
 //         factorisation;
@@ -20,8 +20,8 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 constexpr int KC_THREADS = 256;
 constexpr int KC_D = 128;
 constexpr int KC_TILE = 64;              // rows staged per iteration
-constexpr int KC_LDT = 132;              // staging row stride in bf16 (264 bytes: the two lane halves, 8 rows apart, use different banks)
-constexpr int KC_MINROWS = 1536;         // rows entering G: all up to 1536, else about max(1536, n/4) at a constant stride
+constexpr int KC_LDW = 136;              // staging stride in 32-bit words per token PAIR (the two lane halves, 4 pairs apart, use different banks)
+constexpr int KC_MINROWS = 768;          // rows entering G: all up to 768, else about max(768, n/4) at a constant stride
 constexpr float kCertErr = 4.0e-6f;      // allowance for fp32 Gram + factorisation error, relative to trace(G)
 
 union FragU { uint32_t w[4]; bf16x8 v; };
@@ -37,15 +37,26 @@ __device__ __forceinline__ void wave_tiles(int wave, int (&rb)[3], int (&cb)[3],
   else { rb[0] = 3; cb[0] = 0; rb[1] = 2; cb[1] = 2; rb[2] = 0; cb[2] = 0; nt = 2; }
 }
 
+#ifdef KC_TRACE
+__device__ uint64_t g_kc_trace[512 * 8];
+#define KC_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_kc_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define KC_STAMP(k) do { } while (0)
+#endif
+
 template <bool via_idx>
 __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* __restrict__ Vsrc /*via_idx ? V [heads][N][d] : gathered rows [heads][max_budget][d]*/,
                                                              const float* __restrict__ scores,
                                                              const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ n_keep, int N, int max_budget,
                                                              int rank, HeadState* __restrict__ state,
-                                                             int32_t* __restrict__ decided) {
-  __shared__ uint16_t stage[2][KC_TILE * KC_LDT];
+                                                             int32_t* __restrict__ decided,
+                                                             const double* __restrict__ fro_part /*optional: sums of squares of the retained rows, per gather block*/,
+                                                             int fro_blocks) {
+  __shared__ uint32_t stage[2][(KC_TILE / 2) * KC_LDW];
   __shared__ __attribute__((aligned(16))) float panel[2][KC_D][4];
+  __shared__ float4 ypan[KC_D], lpan[KC_D];
+  __shared__ int s_bad;
   __shared__ double red[KC_THREADS / 64], red2[KC_THREADS / 64];
   const int head = blockIdx.x;
   const int n = n_keep[head];
@@ -60,6 +71,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   const uint16_t* Vh = Vsrc + (size_t)head * (via_idx ? N : max_budget) * KC_D;
   auto row_of = [&](int r) -> size_t { return via_idx ? (size_t)id[r] : (size_t)r; };    // retained row r of the head
 
+  KC_STAMP(0);
   const int cap = max(KC_MINROWS, n >> 2);
   const int stride = (n + cap - 1) / cap;
   const int rows = (n + stride - 1) / stride;
@@ -84,27 +96,36 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
       if (r0 + r < rows) dst[q] = *(const uint2*)(Vh + row_of((r0 + r) * stride) * KC_D + c * 4);
     }
   };
+  // Staging layout: word [p][j] holds column j of tokens 2p and 2p+1 (low / high half), so that an operand
+  // fragment (8 tokens of one column) is four 32-bit reads; the order of the tokens inside a fragment does not
+  // matter for V^T V as long as both operands use the same one.  Lanes l and l+32 of a wave hold rows 2p and 2p+1
+  // of the same four columns; the lower lane writes the words of the first two, the upper lane of the last two.
   auto put = [&](const uint2 (&src)[8], int buf) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const int e = tid + q * KC_THREADS;
-      const int r = e >> 5, c = e & 31;
-      *(uint2*)(&stage[buf][r * KC_LDT + c * 4]) = src[q];
+      const int pr = e >> 6, c = e & 31;
+      const uint32_t mine = lh ? src[q].y : src[q].x;            // the dword this lane combines: columns 4c+2*lh, +1
+      const uint32_t other = lh ? src[q].x : src[q].y;           // the dword the partner lane combines
+      // partner's copy of "my" dword: it is the partner's "other" seen from its side
+      const auto sw = __builtin_amdgcn_permlane32_swap(other, other, false, false);
+      const uint32_t theirs = lh ? sw[0] : sw[1];                // lower lanes get the upper half's value and vice versa
+      const uint32_t even = lh ? theirs : mine, odd = lh ? mine : theirs;     // rows 2p and 2p+1
+      uint2 w;
+      w.x = (even & 0xffffu) | (odd << 16);
+      w.y = (even >> 16) | (odd & 0xffff0000u);
+      *(uint2*)(&stage[buf][pr * KC_LDW + c * 4 + lh * 2]) = w;
     }
   };
-  auto compute = [&](const uint16_t* st) {
+  auto compute = [&](const uint32_t* st) {
 #pragma unroll
     for (int ks = 0; ks < KC_TILE / 16; ++ks) {
       FragU f[4];
-      const int tb = ks * 16 + lh * 8;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint16_t* p = st + tb * KC_LDT + c * 32 + lr;
+        const uint32_t* p = st + (ks * 8 + lh * 4) * KC_LDW + c * 32 + lr;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const uint32_t lo = p[(2 * i) * KC_LDT], hi = p[(2 * i + 1) * KC_LDT];
-          f[c].w[i] = lo | (hi << 16);
-        }
+        for (int i = 0; i < 4; ++i) f[c].w[i] = p[i * KC_LDW];
       }
       if (wave == 0) {
         acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].v, f[0].v, acc[0], 0, 0, 0);
@@ -123,6 +144,14 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
       }
     }
   };
+  // The demand sums of Eq. 6 (diagnostics of a certified head) need sum(scores[idx]) and sum(scores): their first
+  // batch of loads is issued here and consumed after the factorisation, so that its latency is hidden.
+  int ej[8];
+  const bool vec_scores = (N & 3) == 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) { const int i = tid + u * KC_THREADS; ej[u] = (i < n) ? id[i] : -1; }
+  // tile j is staged in stage[j % 2]; the loads run two tiles ahead in registers
+  KC_STAMP(1);
   fetch(pre[0], 0);
   fetch(pre[1], KC_TILE);
   put(pre[0], 0);
@@ -143,7 +172,11 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     fetch(pre[0], r0 + 4 * KC_TILE);
     __syncthreads();
   }
+  float ev[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) ev[u] = (ej[u] >= 0) ? sc[ej[u]] : 0.f;
 
+  KC_STAMP(2);
   // ---- trace(G), ||V_keep||_F^2, shift
   // a lane holds a diagonal entry of a diagonal tile iff (lr % 8) / 4 == lh, at i = (lr / 8) * 4 + lr % 4
   const bool has_diag = ((lr & 7) >> 2) == lh;
@@ -164,7 +197,15 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   const double tr = (red[0] + red[1]) + (red[2] + red[3]);
   __syncthreads();
   double f2 = tr;
-  if (stride > 1) {
+  if (stride > 1 && fro_part) {
+    double p2 = 0.0;
+    for (int b = tid; b < fro_blocks; b += KC_THREADS) p2 += fro_part[(size_t)head * fro_blocks + b];
+    for (int off = 32; off > 0; off >>= 1) p2 += __shfl_xor(p2, off);
+    if (lane == 0) red[wave] = p2;
+    __syncthreads();
+    f2 = (red[0] + red[1]) + (red[2] + red[3]);
+    __syncthreads();
+  } else if (stride > 1) {
     double p2 = 0.0;
     const int sub = tid >> 4, piece = tid & 15;
     for (int r0 = sub; r0 < n; r0 += 8 * (KC_THREADS / 16)) {          // 8 independent row pieces in flight per lane
@@ -203,17 +244,13 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   }
 
   // ---- LDL^T of G - mu I in registers, four columns per step.  panel[s & 1][row] holds columns 4s .. 4s+3 of
-  // the current matrix when step s starts.  Every thread factors the 4x4 diagonal block itself (the same
-  // arithmetic everywhere, so no broadcast), turns the panel rows it needs into L d (a 4-term forward
-  // substitution per row) and applies the rank-4 update to its tiles: first to the one tile (per wave) that holds
+  // the current matrix when step s starts.  Thread r < 128 factors the 4x4 diagonal block (the same arithmetic in
+  // every thread, so no broadcast) and turns panel row r into y = L d (a 4-term forward substitution) and L; after a
+  // second barrier every wave applies the rank-4 update to its tiles: first to the one tile (per wave) that holds
   // the next four columns, which are then published, then to the rest, so the chain block -> next block only
   // contains one tile update.  A non-positive pivot sets a flag (no early exit: the steps stay free of
   // divergent control flow); entries above the diagonal are carried along and never read.
-  float g[3][16];
-#pragma unroll
-  for (int t = 0; t < 3; ++t)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) g[t][i] = acc[t][i];
+  f32x16 (&g)[3] = acc;
   auto publish = [&](int k) {                         // columns k .. k+3 (k % 4 == 0) -> panel[(k / 4) & 1]
     const int kb = k >> 5, kc = k & 31;
     float* pw = &panel[(k >> 2) & 1][0][0];
@@ -226,51 +263,53 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
       }
     }
   };
-  bool ok = true;
+  KC_STAMP(3);
+  if (tid == 0) s_bad = 0;
   publish(0);
 #ifdef KC_SKIP_LDL
   for (int k = 0; k < 0; k += 4) {
 #else
   for (int k = 0; k < KC_D; k += 4) {
 #endif
-    __syncthreads();                                   // this panel visible; the previous one free again
-    const float4* pr = (const float4*)&panel[(k >> 2) & 1][0][0];
+    __syncthreads();                                   // this panel visible; ypan / lpan free again
+    if (tid < KC_D) {
+      const float4* pr = (const float4*)&panel[(k >> 2) & 1][0][0];
+      // 4x4 diagonal block: rows k .. k+3, lower triangle
+      const float4 r0 = pr[k], r1 = pr[k + 1], r2 = pr[k + 2], r3 = pr[k + 3];
+      const float4 x = pr[tid];
+      const float d0 = r0.x;
+      const float i0 = __builtin_amdgcn_rcpf(d0);
+      const float l10 = r1.x * i0, l20 = r2.x * i0, l30 = r3.x * i0;
+      const float d1 = fmaf(-l10, r1.x, r1.y);
+      const float i1 = __builtin_amdgcn_rcpf(d1);
+      const float l21 = fmaf(-l20, r1.x, r2.y) * i1, l31 = fmaf(-l30, r1.x, r3.y) * i1;
+      const float y21 = l21 * d1, y31 = l31 * d1;
+      const float d2 = fmaf(-l21, y21, fmaf(-l20, r2.x, r2.z));
+      const float i2 = __builtin_amdgcn_rcpf(d2);
+      const float l32 = fmaf(-l31, y21, fmaf(-l30, r2.x, r3.z)) * i2;
+      const float y32 = l32 * d2;
+      const float d3 = fmaf(-l32, y32, fmaf(-l31, y31, fmaf(-l30, r3.x, r3.w)));
+      const float i3 = __builtin_amdgcn_rcpf(d3);
+      if (!((d0 > 0.f) && (d1 > 0.f) && (d2 > 0.f) && (d3 > 0.f))) s_bad = 1;
+      // y = L d of panel row x: y0 = x0, y1 = x1 - y0 l10, y2 = x2 - y0 l20 - y1 l21, y3 = x3 - y0 l30 - y1 l31 - y2 l32
+      const float y0 = x.x;
+      const float y1 = fmaf(-y0, l10, x.y);
+      const float y2 = fmaf(-y1, l21, fmaf(-y0, l20, x.z));
+      const float y3 = fmaf(-y2, l32, fmaf(-y1, l31, fmaf(-y0, l30, x.w)));
+      ypan[tid] = make_float4(y0, y1, y2, y3);
+      lpan[tid] = make_float4(y0 * i0, y1 * i1, y2 * i2, y3 * i3);
+    }
+    __syncthreads();
     const int kb = k >> 5;
     const int kbn = (k + 4) >> 5;                      // column block of the next four columns
-    // 4x4 diagonal block: rows k .. k+3, lower triangle
-    const float4 r0 = pr[k], r1 = pr[k + 1], r2 = pr[k + 2], r3 = pr[k + 3];
-    const float d0 = r0.x;
-    const float i0 = __builtin_amdgcn_rcpf(d0);
-    const float l10 = r1.x * i0, l20 = r2.x * i0, l30 = r3.x * i0;
-    const float d1 = fmaf(-l10, r1.x, r1.y);
-    const float i1 = __builtin_amdgcn_rcpf(d1);
-    const float l21 = fmaf(-l20, r1.x, r2.y) * i1, l31 = fmaf(-l30, r1.x, r3.y) * i1;
-    const float y21 = l21 * d1, y31 = l31 * d1;
-    const float d2 = fmaf(-l21, y21, fmaf(-l20, r2.x, r2.z));
-    const float i2 = __builtin_amdgcn_rcpf(d2);
-    const float l32 = fmaf(-l31, y21, fmaf(-l30, r2.x, r3.z)) * i2;
-    const float y32 = l32 * d2;
-    const float d3 = fmaf(-l32, y32, fmaf(-l31, y31, fmaf(-l30, r3.x, r3.w)));
-    ok = ok && (d0 > 0.f) && (d1 > 0.f) && (d2 > 0.f) && (d3 > 0.f);
-    const float i3 = __builtin_amdgcn_rcpf(d3);
-    // y = L d of a panel row x: y0 = x0, y1 = x1 - y0 l10, y2 = x2 - y0 l20 - y1 l21, y3 = x3 - y0 l30 - y1 l31 - y2 l32
-    auto solve = [&](const float4 x, float& y0, float& y1, float& y2, float& y3) {
-      y0 = x.x;
-      y1 = fmaf(-y0, l10, x.y);
-      y2 = fmaf(-y1, l21, fmaf(-y0, l20, x.z));
-      y3 = fmaf(-y2, l32, fmaf(-y1, l31, fmaf(-y0, l30, x.w)));
-    };
+    // rank-4 update of a tile on the matrix cores in fp32: G_tile -= Y_rows (32 x 4) * L_cols^T (4 x 32), two
+    // v_mfma_f32_32x32x2_f32 (A: lane l holds row l%32, k = l/32; B: k = l/32, column l%32)
     auto update = [&](int t) {
-      float a0, a1, a2, a3;
-      solve(pr[tcb[t] * 32 + lr], a0, a1, a2, a3);     // the lane's column j, as row j of the panel
-      const float c0 = a0 * i0, c1 = a1 * i1, c2 = a2 * i2, c3 = a3 * i3;      // L[j][k .. k+3]
-      const float4* rp = pr + trb[t] * 32 + lh * 4;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float y0, y1, y2, y3;
-        solve(rp[(i >> 2) * 8 + (i & 3)], y0, y1, y2, y3);
-        g[t][i] = fmaf(-y3, c3, fmaf(-y2, c2, fmaf(-y1, c1, fmaf(-y0, c0, g[t][i]))));
-      }
+      const float* yp = (const float*)ypan + (trb[t] * 32 + lr) * 4 + lh;
+      const float* lp = (const float*)lpan + (tcb[t] * 32 + lr) * 4 + lh;
+      const float y0 = -yp[0], y1 = -yp[2], l0 = lp[0], l1 = lp[2];
+      g[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(y0, l0, g[t], 0, 0, 0);
+      g[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(y1, l1, g[t], 0, 0, 0);
     };
 #pragma unroll
     for (int t = 0; t < 3; ++t)
@@ -280,11 +319,16 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     for (int t = 0; t < 3; ++t)
       if (t < nt && tcb[t] != kbn && tcb[t] >= kb) update(t);
   }
+  __syncthreads();
+  KC_STAMP(4);
+  const bool ok = (s_bad == 0);
   if (!ok) return;
 
   // certified: r = d, OBF is the identity on this head; fill in the demand sums (Eq. 6) for the diagnostics
   double pk = 0.0, ptot = 0.0;
-  for (int i0 = tid; i0 < n; i0 += 8 * KC_THREADS) {              // batches of independent index -> score loads
+#pragma unroll
+  for (int u = 0; u < 8; ++u) pk += (double)ev[u];
+  for (int i0 = tid + 8 * KC_THREADS; i0 < n; i0 += 8 * KC_THREADS) {       // further batches of index -> score loads
     int j[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) { const int i = i0 + u * KC_THREADS; j[u] = (i < n) ? id[i] : -1; }
@@ -294,7 +338,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
 #pragma unroll
     for (int u = 0; u < 8; ++u) pk += (double)v[u];
   }
-  if ((N & 3) == 0) {
+  if (vec_scores) {
     const float4* sc4 = (const float4*)sc;
     const int n4 = N >> 2;
     for (int i0 = tid; i0 < n4; i0 += 8 * KC_THREADS) {
@@ -319,21 +363,29 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     state[head] = s;
     decided[head] = 1;
   }
+  KC_STAMP(5);
 }
 
 bool keep_cert_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == KC_D; }
 
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
-                              int32_t* decided, hipStream_t st) {
+                              int32_t* decided, hipStream_t st, const double* fro_part) {
+  const int fro_blocks = (max_budget + kGatherRows - 1) / kGatherRows;
   { ProfScope prof_(ST_KEEP_CERT, st);
     if (via_idx)
       hipLaunchKernelGGL(k_bf_keep_cert<true>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
-                         n_keep, m.N, max_budget, rank, state, decided);
+                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks);
     else
       hipLaunchKernelGGL(k_bf_keep_cert<false>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
-                         n_keep, m.N, max_budget, rank, state, decided); }
+                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks); }
   return check_launch("backfill keep_cert");
 }
 
 }  // namespace obf
+
+#ifdef KC_TRACE
+extern "C" int obf_debug_copy_kc_trace(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_kc_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
