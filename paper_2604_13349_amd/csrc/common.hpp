@@ -78,7 +78,9 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.tiles_per_head = (m.N + 31) / 32;
   {
     const long TT = (long)m.heads * w.tiles_per_head;
-    const int G = kNumCU / w.rgroups > 0 ? kNumCU / w.rgroups : 1;
+    // ranges: a multiple of 8 (one share per XCD) such that an XCD's ranges x row groups fit its 32 compute units
+    const int per_xcd = (kNumCU / 8) / w.rgroups > 0 ? (kNumCU / 8) / w.rgroups : 1;
+    const int G = 8 * per_xcd;
     long T = (TT + G - 1) / G;
     T = ((T + 3) / 4) * 4;
     if (T < 4) T = 4;

@@ -228,7 +228,11 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
                                                                     double* __restrict__ stats_part, int N, int R,
                                                                     int RG, Part pt, int nslot) {
   __shared__ double s_m[SM_WAVES][SM_ROWS], s_l[SM_WAVES][SM_ROWS];
-  const int range = blockIdx.x / RG, rg = blockIdx.x - range * RG;
+  // Workgroups are dealt to the 8 XCDs round-robin.  The RG workgroups that stream the same K range (one per row
+  // group) get block indices 8 apart, so they run on one XCD side by side and share its L2.
+  const int blk_group = blockIdx.x / (8 * RG), blk_in = blockIdx.x - blk_group * (8 * RG);
+  const int range = blk_group * 8 + (blk_in & 7), rg = blk_in >> 3;
+  if ((long)range * pt.T >= pt.TT) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row0 = rg * SM_ROWS;
   const float a2 = kLog2e / sqrtf((float)SM_D);
@@ -309,7 +313,11 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
                                                                    float* __restrict__ out, int N, int R, int RG,
                                                                    size_t rg_stride, Part pt, int nslot) {
   __shared__ double s_lse[SM_ROWS];
-  const int range = blockIdx.x / RG, rg = blockIdx.x - range * RG;
+  // Workgroups are dealt to the 8 XCDs round-robin.  The RG workgroups that stream the same K range (one per row
+  // group) get block indices 8 apart, so they run on one XCD side by side and share its L2.
+  const int blk_group = blockIdx.x / (8 * RG), blk_in = blockIdx.x - blk_group * (8 * RG);
+  const int range = blk_group * 8 + (blk_in & 7), rg = blk_in >> 3;
+  if ((long)range * pt.T >= pt.TT) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row0 = rg * SM_ROWS;
   const float a2 = kLog2e / sqrtf((float)SM_D);
@@ -386,7 +394,7 @@ obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, cons
   float* part = (RG > 1) ? (float*)(ws + w.score_part) : scores;
   Part pt;
   pt.TH = w.tiles_per_head; pt.T = w.tiles_per_range; pt.TT = (long)m.heads * w.tiles_per_head;
-  dim3 grid(w.nranges * RG);
+  dim3 grid(((w.nranges + 7) / 8) * 8 * RG);
   { ProfScope prof_(ST_SCORE_STATS, st);
     hipLaunchKernelGGL(k_score_stats_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
                        stats_part, m.N, m.R, RG, pt, w.nslot); }

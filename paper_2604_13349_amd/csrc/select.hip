@@ -46,6 +46,12 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int& ea, int& eb, in
 // count(key >= T) >= B.  Counting is one ballot + population count per owned token and one workgroup sum per bit.
 // With REFINE the tokens whose score lies in the relative band around the threshold are re-decided in double from K, Q
 // and the row log-sum-exp before the list is written (same decisions as select followed by the refinement kernel).
+#ifdef SEL_TRACE
+__device__ uint64_t g_sel_trace[512 * 8];
+#define SEL_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_sel_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define SEL_STAMP(k) do { } while (0)
+#endif
 template <int SEG, int SEL_THREADS, bool REFINE, typename ET>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict__ scores, int N, int head0,
                                                         int uniform_budget, BudgetBatch per_head, int use_per_head,
@@ -72,6 +78,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     if (tid == 0) n_keep[head] = B;
     return;
   }
+  SEL_STAMP(0);
   const int base = tid * SEG;
   uint32_t key[SEG];
   int nvalid = min(SEG, max(0, N - base));                     // tokens of this thread inside the head
@@ -86,10 +93,16 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     for (int i = 0; i < SEG; ++i) key[i] = (i < nvalid) ? order_key(sc[base + i]) : 0u;
   }
 
+  const bool full = __builtin_amdgcn_readfirstlane(N) == SEG * SEL_THREADS;     // every thread owns SEG tokens
   auto count_ge = [&](uint32_t cand, int buf) -> int {
     int c = 0;
+    if (full) {
 #pragma unroll
-    for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(i < nvalid && key[i] >= cand));
+      for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(key[i] >= cand));
+    } else {
+#pragma unroll
+      for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(i < nvalid && key[i] >= cand));
+    }
     if (lane == 0) wcnt[buf][wave] = c;
     __syncthreads();
     int tot = 0;
@@ -98,14 +111,32 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     return tot;
   };
 
+  // Bisection, most significant bit first.  As soon as exactly B keys are >= the candidate, the retained set is
+  // known and the rank-B key is the smallest of them (one more workgroup reduction) - the remaining bits are skipped.
   uint32_t T = 0u;
   int buf = 0;
+  bool exact = false;
 #ifndef SEL_BITS
 #define SEL_BITS 32
 #endif
   for (int bit = 31; bit >= 32 - SEL_BITS; --bit) {
     const uint32_t cand = T | (1u << bit);
-    if (count_ge(cand, buf) >= B) T = cand;
+    const int c = count_ge(cand, buf);
+    buf ^= 1;
+    if (c >= B) T = cand;
+    if (c == B) { exact = true; break; }
+  }
+  if (exact) {
+    uint32_t mn = 0xffffffffu;
+#pragma unroll
+    for (int i = 0; i < SEG; ++i) if (i < nvalid && key[i] >= T) mn = min(mn, key[i]);
+    for (int off = 32; off > 0; off >>= 1) mn = min(mn, (uint32_t)__shfl_xor((int)mn, off));
+    if (lane == 0) wcnt[buf][wave] = (int)mn;
+    __syncthreads();
+    uint32_t t = 0xffffffffu;
+#pragma unroll
+    for (int w = 0; w < SEL_WAVES; ++w) t = min(t, (uint32_t)wcnt[buf][w]);
+    T = t;
     buf ^= 1;
   }
   // keys greater than T are all kept; of the keys equal to T the lowest indices fill the rest
@@ -118,12 +149,14 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   if (tid == 0) n_keep[head] = B + (int)T + need_eq;
   return;
 #endif
+  SEL_STAMP(2);
   int cg = 0, ce = 0;
 #pragma unroll
   for (int i = 0; i < SEG; ++i) { if (i < nvalid) { cg += (key[i] > T); ce += (key[i] == T); } }
   int eg, ee, tg, te;
   block_exscan2<SEL_WAVES>(cg, ce, eg, ee, tg, te, wsum);
 
+  SEL_STAMP(3);
   bool refined = false;
   int bpos0 = 0;
   float lo = 0.f, hi = 0.f;
@@ -162,6 +195,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
         }
       }
       __syncthreads();
+      SEL_STAMP(4);
       rescore_band<ET, SEL_WAVES>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R,
                                  band, nband, band_score);
       __syncthreads();
@@ -174,6 +208,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     }
   }
 
+  SEL_STAMP(5);
   if (!refined) {
 #pragma unroll
     for (int i = 0; i < SEG; ++i) {
@@ -208,6 +243,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   }
   for (int i = B + tid; i < max_budget; i += SEL_THREADS) out[i] = -1;
   if (tid == 0) n_keep[head] = B;
+  SEL_STAMP(6);
 }
 
 template <int SEG, int SEL_THREADS, bool REFINE, typename T>
@@ -261,3 +297,9 @@ obf_status_t launch_select_refine(const Dims& m, const float* scores, const int3
 }
 
 }  // namespace obf
+
+#ifdef SEL_TRACE
+extern "C" int obf_debug_copy_sel_trace(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_sel_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
