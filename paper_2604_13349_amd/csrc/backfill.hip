@@ -355,12 +355,14 @@ constexpr int FN_THREADS = 1024;
 constexpr int FN_WAVES = FN_THREADS / 64;
 constexpr int FN_SWEEPS = 12;
 
+template <typename T>
 __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int nstat, int rank,
                                                             HeadState* __restrict__ state,
                                                             const float* __restrict__ basis,
                                                             const float* __restrict__ gram_part,
                                                             float* __restrict__ mats, float* __restrict__ delta,
-                                                            float* __restrict__ delta_out, obf_diag_t* __restrict__ diag) {
+                                                            float* __restrict__ delta_out, obf_diag_t* __restrict__ diag,
+                                                            T* __restrict__ V_out, int max_budget) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
@@ -579,26 +581,19 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       diag[head] = dg;
     }
   }
+  // Eq. 7: the one offset is added to every retained value row (rounded once to the storage type)
+  if (!skipped && V_out) {
+    const int total = st.n_keep * d;
+    T* base = V_out + (size_t)head * max_budget * d;
+    for (int e = tid; e < total; e += FN_THREADS) {
+      T* p = base + e;
+      Elem<T>::store(p, Elem<T>::load(p) + uvec[e % d]);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
 // inject: V_out[row] += delta for the retained rows of heads that were not skipped (Eq. 7)
-constexpr int INJ_BLOCKS = 8;
-template <typename T>
-__global__ void k_bf_inject(T* __restrict__ V_out, const float* __restrict__ delta, const HeadState* __restrict__ state,
-                            int d, int max_budget) {
-  const int head = blockIdx.y;
-  const HeadState* s = state + head;
-  if (!s->active) return;
-  const int total = s->n_keep * d;
-  T* base = V_out + (size_t)head * max_budget * d;
-  const float* dl = delta + (size_t)head * d;
-  for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += INJ_BLOCKS * blockDim.x) {
-    T* p = base + e;
-    Elem<T>::store(p, Elem<T>::load(p) + dl[e % d]);
-  }
-}
-
 template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
@@ -611,7 +606,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
-    (void)hipFuncSetAttribute((const void*)k_bf_finalize, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
+    (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     attr_done = true;
   }
   const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
@@ -629,14 +624,10 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
                        (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
-  { ProfScope prof_(ST_FINALIZE, st); hipLaunchKernelGGL(k_bf_finalize, dim3(m.heads), dim3(FN_THREADS), sizeof(float) * 2 * m.d * (m.d + 1), st, m.N, m.d,
-                     w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag); }
+  { ProfScope prof_(ST_FINALIZE, st); hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), sizeof(float) * 2 * m.d * (m.d + 1), st, m.N, m.d,
+                     w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
+                     (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget); }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
-  if (rank > 0 && max_budget > 0) {
-    { ProfScope prof_(ST_INJECT, st); hipLaunchKernelGGL(k_bf_inject<T>, dim3(INJ_BLOCKS, m.heads), dim3(256), 0, st, (T*)V_out, delta, state, m.d,
-                       max_budget); }
-    if (check_launch("backfill inject") != OBF_OK) return OBF_ERR_HIP;
-  }
   return OBF_OK;
 }
 
