@@ -173,40 +173,38 @@ struct MassEp {
 // one wave a SIMD holds.  Two 16-register accumulators and two K fragment buffers alternate; the load of
 // tile t+2 is issued once the last chain of tile t has been issued.
 template <bool TOKENS_BY_ROWS, int U, class Ep>
-__device__ __forceinline__ void micro_stage(const uint16_t* __restrict__ Kh, int first, int n, int t_end, int lane, int i,
+__device__ __forceinline__ void micro_stage(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane, int i,
                                             const Frag (&qf)[SM_RB][SM_KK], Frag (&kb)[2][SM_KK], f32x16 (&acc)[2], Ep& ep,
                                             bool guarded) {
-  constexpr int STEP = SM_WAVES * SM_TILE;
   constexpr int rb = U % 4, tl = U / 4;                 // current row block, tile offset within the group of 2
   constexpr int rbn = (U + 1) % 4, tln = (U + 1) / 4;   // next
   const int tile = i + tl, tilen = i + tln;
   if (guarded && tile >= n) return;
   if (!guarded || tilen < n) block_mfma<TOKENS_BY_ROWS>(acc[(U + 1) & 1], kb[tln % 2], qf[rbn]);
-  ep.template block<rb>(acc[U & 1], first + tile * STEP);
-  if (rb == 3 && tile + 2 < n) load_k(kb[tl % 2], Kh, first + (tile + 2) * STEP, t_end, lane);
+  ep.template block<rb>(acc[U & 1], first + tile * step);
+  if (rb == 3 && tile + 2 < n) load_k(kb[tl % 2], Kh, first + (tile + 2) * step, t_end, lane);
   __builtin_amdgcn_sched_barrier(0);      // keep the scheduler from merging micro-stages (register pressure)
 }
 
 template <bool TOKENS_BY_ROWS, class Ep>
-__device__ __forceinline__ void run_tiles(const uint16_t* __restrict__ Kh, int first, int n, int t_end, int lane,
+__device__ __forceinline__ void run_tiles(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane,
                                           const Frag (&qf)[SM_RB][SM_KK], Ep& ep) {
-  constexpr int STEP = SM_WAVES * SM_TILE;
   if (n <= 0) return;
   Frag kb[2][SM_KK];
   f32x16 acc[2];
   load_k(kb[0], Kh, first, t_end, lane);
-  if (n > 1) load_k(kb[1], Kh, first + STEP, t_end, lane);
+  if (n > 1) load_k(kb[1], Kh, first + step, t_end, lane);
   block_mfma<TOKENS_BY_ROWS>(acc[0], kb[0], qf[0]);
   int i = 0;
 #define OBF_STAGES(G)                                                                                      \
-  micro_stage<TOKENS_BY_ROWS, 0>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 1>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 2>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 3>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 4>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 5>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 6>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 7>(Kh, first, n, t_end, lane, i, qf, kb, acc, ep, G);
+  micro_stage<TOKENS_BY_ROWS, 0>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 1>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 2>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 3>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 4>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 5>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 6>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
+  micro_stage<TOKENS_BY_ROWS, 7>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);
   for (; i + 2 < n; i += 2) { OBF_STAGES(false) }      // two whole tiles and the first chain of the next exist
   { OBF_STAGES(true) }
 #undef OBF_STAGES
@@ -258,7 +256,7 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
     const int first = ta + wave * SM_TILE;
     const int nfull = (tb - first >= SM_TILE) ? ((tb - first - SM_TILE) / STEP + 1) : 0;
     StatsEp ep{m, l, a2};
-    run_tiles<true>(Kh, first, nfull, tb, lane, qf, ep);
+    run_tiles<true>(Kh, first, STEP, nfull, tb, lane, qf, ep);
     {
       const int tok = first + nfull * STEP;          // a ragged last tile, if any
       if (tok < tb) {
@@ -325,10 +323,12 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
   const long gs = (long)range * pt.T;
   const long ge = min(pt.TT, gs + pt.T);
 
-  for (long cur = gs; cur < ge;) {
-    const int head = (int)(cur / pt.TH);
+  // The range is walked BACKWARDS (last segment first, last tile first): the first pass has just streamed it
+  // forwards, so its end is what the memory-side cache still holds.
+  for (long se = ge; se > gs;) {
+    const int head = (int)((se - 1) / pt.TH);
     const long hs = (long)head * pt.TH;
-    const long se = min(ge, hs + pt.TH);
+    const long cur = max(gs, hs);
     const int ta = (int)(cur - hs) * SM_TILE, tb = min(N, (int)(se - hs) * SM_TILE);
     const uint16_t* Kh = K + (size_t)head * N * SM_D;
     const uint16_t* Qh = Q + (size_t)head * R * SM_D;
@@ -367,8 +367,8 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
     const int first = ta + wave * SM_TILE;
     const int nt = (first < tb) ? ((tb - first - 1) / STEP + 1) : 0;      // tiles of this wave, the last may be ragged
     MassEp ep{b2, a2, dst, tb, lane, 0.f, 0.f, 0.f, 0.f};
-    run_tiles<false>(Kh, first, nt, tb, lane, qf, ep);
-    cur = se;
+    run_tiles<false>(Kh, first + (nt - 1) * STEP, -STEP, nt, tb, lane, qf, ep);
+    se = cur;
   }
 }
 
