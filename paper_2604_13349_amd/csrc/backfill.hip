@@ -619,7 +619,9 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   { ProfScope prof_(ST_KEEP_BASIS, st); hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
                      m.N, m.d, max_budget, rank, state, basis, decided); }
   if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
-  if (rank > 0) {
+  if (rank > 0 && del_stats_mfma_supported(m)) {
+    if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
+  } else if (rank > 0) {
     { ProfScope prof_(ST_DEL_STATS, st); hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
                        (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
