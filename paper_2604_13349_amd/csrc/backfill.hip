@@ -354,6 +354,7 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
 constexpr int FN_THREADS = 1024;
 constexpr int FN_WAVES = FN_THREADS / 64;
 constexpr int FN_SWEEPS = 12;
+constexpr int FN_TPT = (128 * 128) / FN_THREADS;   // entries of the reduced Gram matrix per thread, at most
 
 template <typename T>
 __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int nstat, int rank,
@@ -375,6 +376,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
   __shared__ float fred[FN_WAVES];
   __shared__ int s_k;
   __shared__ float s_off;
+  __shared__ float pdiag[128], wmax[2];
+  __shared__ int piv[128], warg[2];
   HeadState st = state[head];
   int skipped = 1;
   float rcr = 0.f, ivn = 0.f;
@@ -383,10 +386,12 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
 
   if (st.active) {
     const int r = st.r_keep;
+    int m = d - r;                                             // dimension of the orthogonal complement
     const float* Qb = basis + (size_t)head * d * d;            // [r][d] orthonormal rows
     const size_t pstride = (size_t)d * d + d + 4;
     const float* gp = gram_part + (size_t)head * nstat * pstride;
-    float* T1 = mats + (size_t)head * 3 * d * d;               // [d][r] scratch in global memory
+    float* Zg = mats + (size_t)head * 3 * d * d;               // [m][d] basis of the complement (global scratch)
+    float* Yg = Zg + (size_t)d * d;                            // [m][d] Z G
 
     // G = sum of chunk partials (fixed order), u, ||V_del||^2
     for (int e = tid; e < d * d; e += FN_THREADS) {
@@ -401,62 +406,132 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
     }
     float vd2 = 0.f;
     for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + d];
+
+    // P = I - Q^T Q (projector onto the complement of the retained span, Eq. 3), 4 x 4 tiles per thread
+    const int q4 = d >> 2;
+    for (int e = tid; e < q4 * q4; e += FN_THREADS) {
+      const int a0 = (e / q4) << 2, b0 = (e % q4) << 2;
+      float acc[4][4];
+      for (int x = 0; x < 4; ++x) for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
+      for (int i = 0; i < r; ++i) {
+        const float4 qa = *(const float4*)(Qb + (size_t)i * d + a0);
+        const float4 qb = *(const float4*)(Qb + (size_t)i * d + b0);
+        const float av[4] = {qa.x, qa.y, qa.z, qa.w}, bv[4] = {qb.x, qb.y, qb.z, qb.w};
+        for (int x = 0; x < 4; ++x) for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(av[x], bv[y], acc[x][y]);
+      }
+      for (int x = 0; x < 4; ++x)
+        for (int y = 0; y < 4; ++y) U[(a0 + x) * ld + b0 + y] = ((a0 + x == b0 + y) ? 1.f : 0.f) - acc[x][y];
+    }
     __syncthreads();
 
-    // M <- G P  with P = I - Q^T Q (Q rows orthonormal):  T1 = G Q^T (d x r);  M -= T1 Q
-    for (int e = tid; e < d * r; e += FN_THREADS) {
-      const int a = e / r, i = e - a * r;
-      float s = 0.f;
-      for (int c = 0; c < d; ++c) s = fmaf(M[a * ld + c], Qb[i * d + c], s);
-      T1[e] = s;
+    // Diagonally pivoted Cholesky of P, left-looking: a projector of rank m factors as P = Z^T Z with the
+    // m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  Row s of Z overwrites
+    // row piv[s] of P, which is never read again (only rows of pivots still to come are).
+    float dg = -1.f;
+    bool used = false;
+    if (tid < d) { dg = U[tid * ld + tid]; pdiag[tid] = dg; }
+    __syncthreads();
+    for (int s = 0; s < m; ++s) {
+      if (tid < d) {
+        float v = dg; int ix = tid;
+        for (int off = 32; off > 0; off >>= 1) {
+          const float ov = __shfl_xor(v, off);
+          const int oi = __shfl_xor(ix, off);
+          if (ov > v || (ov == v && oi < ix)) { v = ov; ix = oi; }
+        }
+        if ((tid & 63) == 0) { wmax[tid >> 6] = v; warg[tid >> 6] = ix; }
+      }
+      __syncthreads();
+      int j = warg[0];
+      float pv = wmax[0];
+      if (d > 64 && wmax[1] > pv) { j = warg[1]; pv = wmax[1]; }
+      if (!(pv > 1e-5f)) { m = s; break; }                       // cannot happen for an exact projector of rank m
+      if (tid < d) {
+        float x = U[j * ld + tid], xj = pdiag[j];
+        for (int t = 0; t < s; ++t) {
+          const float* zt = U + piv[t] * ld;
+          const float zj = zt[j];
+          x = fmaf(-zt[tid], zj, x);
+          xj = fmaf(-zj, zj, xj);                                // the pivot itself, same arithmetic in every thread
+        }
+        const float l = used ? 0.f : x * rsqrtf(fmaxf(xj, 1e-12f));
+        U[j * ld + tid] = l;
+        if (tid == j) used = true;
+        dg = used ? -1.f : dg - l * l;
+        if (tid == 0) piv[s] = j;
+      }
+      __syncthreads();
     }
     __syncthreads();
-    for (int e = tid; e < d * d; e += FN_THREADS) {
-      const int a = e / d, b = e - a * d;
-      float s = 0.f;
-      for (int i = 0; i < r; ++i) s = fmaf(T1[a * r + i], Qb[i * d + b], s);
-      M[a * ld + b] -= s;
+
+    // Z to global scratch (compact rows), Y = Z G
+    for (int e = tid; e < m * d; e += FN_THREADS) Zg[e] = U[piv[e / d] * ld + (e % d)];
+    const int sg = (m + 3) >> 2;
+    for (int e = tid; e < sg * d; e += FN_THREADS) {
+      const int s0 = (e / d) << 2, b = e % d;
+      const float* z0 = U + piv[min(s0, m - 1)] * ld;
+      const float* z1 = U + piv[min(s0 + 1, m - 1)] * ld;
+      const float* z2 = U + piv[min(s0 + 2, m - 1)] * ld;
+      const float* z3 = U + piv[min(s0 + 3, m - 1)] * ld;
+      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+      for (int c = 0; c < d; ++c) {
+        const float g = M[c * ld + b];
+        a0 = fmaf(z0[c], g, a0); a1 = fmaf(z1[c], g, a1); a2 = fmaf(z2[c], g, a2); a3 = fmaf(z3[c], g, a3);
+      }
+      Yg[(size_t)s0 * d + b] = a0;
+      if (s0 + 1 < m) Yg[(size_t)(s0 + 1) * d + b] = a1;
+      if (s0 + 2 < m) Yg[(size_t)(s0 + 2) * d + b] = a2;
+      if (s0 + 3 < m) Yg[(size_t)(s0 + 3) * d + b] = a3;
     }
     __syncthreads();
-    // M <- P M:  T2 = Q M (r x d);  M -= Q^T T2
-    for (int e = tid; e < r * d; e += FN_THREADS) {
-      const int i = e / d, b = e - i * d;
-      float s = 0.f;
-      for (int a = 0; a < d; ++a) s = fmaf(Qb[i * d + a], M[a * ld + b], s);
-      T1[e] = s;
+    // T = Y Z^T = Z G Z^T (m x m): the residual Gram matrix R^T R = P G P restricted to the complement,
+    // whose eigenpairs (lambda, w) give those of P G P as (lambda, Z^T w).  Stored over G, padded to even size.
+    const int mm = m + (m & 1);
+    const int lt = mm + 1;
+    float tacc[FN_TPT];
+    for (int k = 0, e = tid; k < FN_TPT; ++k, e += FN_THREADS) {
+      float acc = 0.f;
+      if (e < m * m) {
+        const int s = e / m, t = e - s * m;
+        const float* zt = U + piv[t] * ld;
+        const float* yr = Yg + (size_t)s * d;
+        for (int c = 0; c < d; c += 4) {
+          const float4 y4 = *(const float4*)(yr + c);
+          acc = fmaf(y4.x, zt[c], acc); acc = fmaf(y4.y, zt[c + 1], acc);
+          acc = fmaf(y4.z, zt[c + 2], acc); acc = fmaf(y4.w, zt[c + 3], acc);
+        }
+      }
+      tacc[k] = acc;
+    }
+    __syncthreads();                                             // G and Z (in LDS) are dead from here on
+    for (int k = 0, e = tid; k < FN_TPT; ++k, e += FN_THREADS)
+      if (e < m * m) M[(e / m) * lt + (e % m)] = tacc[k];
+    if (mm > m) for (int e = tid; e < mm; e += FN_THREADS) { M[m * lt + e] = 0.f; M[e * lt + m] = 0.f; }
+    __syncthreads();
+    // symmetrise, W = I, trace
+    for (int e = tid; e < mm * mm; e += FN_THREADS) {
+      const int a = e / mm, b = e - a * mm;
+      if (a < b) { const float v = 0.5f * (M[a * lt + b] + M[b * lt + a]); M[a * lt + b] = v; M[b * lt + a] = v; }
+      U[a * lt + b] = (a == b) ? 1.f : 0.f;
     }
     __syncthreads();
-    for (int e = tid; e < d * d; e += FN_THREADS) {
-      const int a = e / d, b = e - a * d;
-      float s = 0.f;
-      for (int i = 0; i < r; ++i) s = fmaf(Qb[i * d + a], T1[i * d + b], s);
-      M[a * ld + b] -= s;
-    }
-    __syncthreads();
-    // symmetrise, U = I, trace
-    for (int e = tid; e < d * d; e += FN_THREADS) {
-      const int a = e / d, b = e - a * d;
-      if (a < b) { const float v = 0.5f * (M[a * ld + b] + M[b * ld + a]); M[a * ld + b] = v; M[b * ld + a] = v; }
-      U[a * ld + b] = (a == b) ? 1.f : 0.f;
-    }
-    __syncthreads();
-    if (tid == 0) { double tr = 0.0; for (int a = 0; a < d; ++a) tr += (double)M[a * ld + a]; s_off = (float)tr; }
+    if (tid == 0) { double tr = 0.0; for (int a = 0; a < m; ++a) tr += (double)M[a * lt + a]; s_off = (float)tr; }
     __syncthreads();
     const float res2 = s_off;
     rcr = res2 / (vd2 + 1e-12f);
-    const bool negligible = !(res2 > kRcrSkip * vd2);
+    const bool negligible = !(res2 > kRcrSkip * vd2) || m <= 0;
 
     if (!negligible) {
-      // cyclic Jacobi with a round-robin ordering: d/2 disjoint rotations per round
-      const int half = d / 2;
-      for (int sweep = 0; sweep < FN_SWEEPS; ++sweep) {
-        for (int round = 0; round < d - 1; ++round) {
+      // cyclic Jacobi with a round-robin ordering: mm/2 disjoint rotations per round
+      const int half = mm / 2;
+      for (int sweep = 0; sweep < FN_SWEEPS && mm > 1; ++sweep) {
+        for (int round = 0; round < mm - 1; ++round) {
           if (tid < half) {
             int p, q;
-            if (tid == 0) { p = d - 1; q = round; }
-            else { p = (round + tid) % (d - 1); q = (round - tid + (d - 1)) % (d - 1); }
+            if (tid == 0) { p = mm - 1; q = round; }
+            else { p = (round + tid) % (mm - 1); q = (round - tid + (mm - 1)) % (mm - 1); }
             if (p > q) { const int t = p; p = q; q = t; }
-            const float app = M[p * ld + p], aqq = M[q * ld + q], apq = M[p * ld + q];
+            const float app = M[p * lt + p], aqq = M[q * lt + q], apq = M[p * lt + q];
             float c = 1.f, s = 0.f;
             if (fabsf(apq) > 1e-30f && fabsf(apq) > 1e-9f * sqrtf(fabsf(app * aqq)) ) {
               const float tau = (aqq - app) / (2.f * apq);
@@ -467,35 +542,35 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
             pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
           }
           __syncthreads();
-          // columns: M <- M J, U <- U J
-          for (int e = tid; e < half * d; e += FN_THREADS) {
-            const int i = e / d, k = e - i * d;
+          // columns: T <- T J, W <- W J  (the two matrices on different threads)
+          for (int e = tid; e < 2 * half * mm; e += FN_THREADS) {
+            const int w = e >= half * mm;
+            const int e2 = e - w * half * mm;
+            const int i = e2 / mm, k = e2 - i * mm;
             const int p = pp[i], q = qq[i];
             const float c = cs[i], s = sn[i];
-            const float mp = M[k * ld + p], mq = M[k * ld + q];
-            M[k * ld + p] = c * mp - s * mq;
-            M[k * ld + q] = s * mp + c * mq;
-            const float up = U[k * ld + p], uq = U[k * ld + q];
-            U[k * ld + p] = c * up - s * uq;
-            U[k * ld + q] = s * up + c * uq;
+            float* A = w ? U : M;
+            const float mp = A[k * lt + p], mq = A[k * lt + q];
+            A[k * lt + p] = c * mp - s * mq;
+            A[k * lt + q] = s * mp + c * mq;
           }
           __syncthreads();
-          // rows: M <- J^T M
-          for (int e = tid; e < half * d; e += FN_THREADS) {
-            const int i = e / d, k = e - i * d;
+          // rows: T <- J^T T
+          for (int e = tid; e < half * mm; e += FN_THREADS) {
+            const int i = e / mm, k = e - i * mm;
             const int p = pp[i], q = qq[i];
             const float c = cs[i], s = sn[i];
-            const float mp = M[p * ld + k], mq = M[q * ld + k];
-            M[p * ld + k] = c * mp - s * mq;
-            M[q * ld + k] = s * mp + c * mq;
+            const float mp = M[p * lt + k], mq = M[q * lt + k];
+            M[p * lt + k] = c * mp - s * mq;
+            M[q * lt + k] = s * mp + c * mq;
           }
           __syncthreads();
         }
         // off-diagonal energy; stop when it is below single-precision noise of the trace
         float off = 0.f;
-        for (int e = tid; e < d * d; e += FN_THREADS) {
-          const int a = e / d, b = e - a * d;
-          if (a != b) { const float v = M[a * ld + b]; off = fmaf(v, v, off); }
+        for (int e = tid; e < mm * mm; e += FN_THREADS) {
+          const int a = e / mm, b = e - a * mm;
+          if (a != b) { const float v = M[a * lt + b]; off = fmaf(v, v, off); }
         }
         for (int o = 32; o > 0; o >>= 1) off += __shfl_xor(off, o);
         if ((tid & 63) == 0) fred[tid >> 6] = off;
@@ -507,12 +582,12 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
         if (offn <= 1e-13f * res2 * res2) break;
       }
       // eigenvalues, descending order (ties: lower index first), numerical rank of R
-      if (tid < d) lamv[tid] = M[tid * ld + tid];
+      if (tid < m) lamv[tid] = M[tid * lt + tid];
       __syncthreads();
-      if (tid < d) {
+      if (tid < m) {
         const float mine = lamv[tid];
         int rk = 0;
-        for (int j = 0; j < d; ++j) { const float o = lamv[j]; rk += (o > mine) || (o == mine && j < tid); }
+        for (int j = 0; j < m; ++j) { const float o = lamv[j]; rk += (o > mine) || (o == mine && j < tid); }
         order[rk] = tid;
       }
       __syncthreads();
@@ -521,7 +596,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
         const float srel = (float)max(st.n_del, d) * (float)kRankEps;
         const float floor_rel = fmaxf(srel * srel, kEigFloor);
         int rankR = 0;
-        for (int j = 0; j < d; ++j) if (lamv[order[j]] > lmax * floor_rel) ++rankR;
+        for (int j = 0; j < m; ++j) if (lamv[order[j]] > lmax * floor_rel) ++rankR;
         const int cap = min(min(st.n_del, d - r), d);
         if (rankR > cap) rankR = cap;
         s_k = min(rank, rankR);
@@ -529,32 +604,32 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       __syncthreads();
       k_used = s_k;
       if (k_used > 0) {
-        // rbar = P u / (a_del + eps)   (Eq. 4 with R_j = P v_j)
-        if (tid < r) {
+        // In complement coordinates: y = Z u, so that rbar = Z^T y / (a_del + eps)  (Eq. 4 with R_j = P v_j)
+        if (tid < m) {
           float s = 0.f;
-          for (int c = 0; c < d; ++c) s = fmaf(Qb[tid * d + c], uvec[c], s);
-          lamv[tid] = s;                                   // reuse: coefficients q_i . u   (r <= d-1 entries)
+          for (int c = 0; c < d; ++c) s = fmaf(Zg[(size_t)tid * d + c], uvec[c], s);
+          rbar[tid] = s;
         }
         __syncthreads();
-        if (tid < d) {
-          float s = uvec[tid];
-          for (int i = 0; i < r; ++i) s = fmaf(-lamv[i], Qb[i * d + tid], s);
-          rbar[tid] = (float)((double)s / (st.a_del + kEps));
-        }
-        __syncthreads();
-        // Delta = sum_i (rbar . c_i) c_i   (Eq. 5), c_i = column order[i] of U
+        // Delta = sum_i (rbar . c_i) c_i  (Eq. 5) with c_i = Z^T w_i, w_i = column order[i] of W
         if (tid < k_used) {
           const int col = order[tid];
           float s = 0.f;
-          for (int c = 0; c < d; ++c) s = fmaf(rbar[c], U[c * ld + col], s);
+          for (int t = 0; t < m; ++t) s = fmaf(rbar[t], U[t * lt + col], s);
           dvec[tid] = s;                                   // coefficient
+        }
+        __syncthreads();
+        if (tid < m) {
+          float s = 0.f;
+          for (int i = 0; i < k_used; ++i) s = fmaf(dvec[i], U[tid * lt + order[i]], s);
+          lamv[tid] = s;                                   // Delta in complement coordinates (times a_del + eps)
         }
         __syncthreads();
         if (tid < d) {
           float s = 0.f;
-          for (int i = 0; i < k_used; ++i) s = fmaf(dvec[i], U[tid * ld + order[i]], s);
+          for (int t = 0; t < m; ++t) s = fmaf(Zg[(size_t)t * d + tid], lamv[t], s);
           const double alpha = st.a_del / (st.a_keep + kEps);          // Eq. 6
-          uvec[tid] = (float)(alpha * (double)s);
+          uvec[tid] = (float)(alpha * ((double)s / (st.a_del + kEps)));
         }
         __syncthreads();
         if (tid == 0) { double s = 0.0; for (int c = 0; c < d; ++c) s += (double)uvec[c] * uvec[c]; s_off = (float)sqrt(s); }
