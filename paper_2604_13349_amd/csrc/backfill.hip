@@ -126,6 +126,7 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
                                                               float* __restrict__ basis,
                                                               const int32_t* __restrict__ decided) {
   if (decided && decided[blockIdx.x]) return;        // settled by the fast full-rank test
+  if (n_keep[blockIdx.x] <= d) return;               // heads of k_bf_keep_basis_small
   extern __shared__ double W[];            // [d][d] doubles (rows: vectors being orthonormalised / Gram)
   __shared__ double red[KB_WAVES];
   __shared__ int ired[2];
@@ -264,6 +265,193 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
   }
   (void)lane; (void)wave;
   if (threadIdx.x == 0) {
+    HeadState s;
+    s.a_keep = a_keep; s.a_del = a_del; s.n_keep = n; s.n_del = n_del; s.r_keep = r_keep; s.active = active;
+    s.k_used = 0; s.pad = 0; s.rcr = 0.f; s.ivn = 0.f;
+    state[head] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// keep_basis for heads with at most d retained rows (budget below the head dimension: Eq. 2 always
+// leaves a complement).  Everything in double precision on the n x n Gram matrix C = A A^T of the
+// retained rows A (entries of A are exact in float, products and sums are taken in double):
+//   sigma_max^2 = lambda_max(C) by power iteration (rank rule threshold),
+//   diagonally pivoted Cholesky C = L L^T; a pivot is the squared distance of a row from the span of
+//   the rows chosen before it, exactly the quantity pivoted Gram-Schmidt tests, so the rank is the same,
+//   Q = L^-1 A (rows orthonormal) through the explicit inverse of the r x r triangular factor.
+// Storage: row piv[s] of C is dead once s is chosen; it then holds column s of L (at positions piv[k],
+// k > s) and row s of L^-1 (at positions piv[k], k <= s).
+constexpr int KS_THREADS = 256;
+constexpr int KS_CH = 32;                  // columns of A staged per Gram step
+constexpr int KS_QROWS = 64;               // rows of Q per thread in the final product, at most
+
+template <typename T, int TI>
+__device__ void ks_gram(const T* __restrict__ Vh, const int32_t* __restrict__ id, int n, int d, float* stg, double* C) {
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  double acc[TI][TI];
+  for (int a = 0; a < TI; ++a) for (int b = 0; b < TI; ++b) acc[a][b] = 0.0;
+  for (int c0 = 0; c0 < d; c0 += KS_CH) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < n * KS_CH; e += KS_THREADS) {
+      const int i = e / KS_CH, c = e - i * KS_CH;
+      stg[i * (KS_CH + 1) + c] = Elem<T>::load(Vh + (size_t)id[i] * d + c0 + c);
+    }
+    __syncthreads();
+    for (int c = 0; c < KS_CH; ++c) {
+      double av[TI], bv[TI];
+      for (int a = 0; a < TI; ++a) av[a] = (double)stg[min(ty + 16 * a, n - 1) * (KS_CH + 1) + c];
+      for (int b = 0; b < TI; ++b) bv[b] = (double)stg[min(tx + 16 * b, n - 1) * (KS_CH + 1) + c];
+      for (int a = 0; a < TI; ++a) for (int b = 0; b < TI; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
+    }
+  }
+  __syncthreads();                           // the staging area aliases C
+  for (int a = 0; a < TI; ++a)
+    for (int b = 0; b < TI; ++b) {
+      const int i = ty + 16 * a, j = tx + 16 * b;
+      if (i < n && j < n) C[i * n + j] = acc[a][b];
+    }
+  __syncthreads();
+}
+
+template <typename T>
+__global__ __launch_bounds__(KS_THREADS, 2) void k_bf_keep_basis_small(const T* __restrict__ V, const float* __restrict__ scores,
+                                                                    const int32_t* __restrict__ idx,
+                                                                    const int32_t* __restrict__ n_keep, int N, int d,
+                                                                    int max_budget, int rank, HeadState* __restrict__ state,
+                                                                    float* __restrict__ basis) {
+  const int head = blockIdx.x;
+  const int n = n_keep[head];
+  if (n > d) return;                         // heads of the general kernel
+  extern __shared__ double C[];              // [n][n]; first the float staging area of the Gram phase
+  __shared__ double red[KB_WAVES];
+  __shared__ double xv[128], pdiag[128], invd[128], wmax[2];
+  __shared__ int piv[128], rowoff[128], warg[2];
+  const int n_del = N - n;
+  const float* sc = scores + (size_t)head * N;
+  const int32_t* id = idx + (size_t)head * max_budget;
+  const T* Vh = V + (size_t)head * N * d;
+  const int tid = threadIdx.x;
+
+  // demand sums of Eq. 6, in double, fixed summation order
+  double pk = 0.0, pt = 0.0;
+  for (int i = tid; i < n; i += KS_THREADS) pk += (double)sc[id[i]];
+  for (int i = tid; i < N; i += KS_THREADS) pt += (double)sc[i];
+  const double a_keep = block_sum(pk, red);
+  const double a_tot = block_sum(pt, red);
+  double a_del = a_tot - a_keep;
+  if (a_del < 0.0) a_del = 0.0;
+
+  int r_keep = 0, active = 0;
+  if (rank > 0 && n > 0 && n_del > 0) {
+    float* stg = (float*)C;
+    if (n <= 32) ks_gram<T, 2>(Vh, id, n, d, stg, C);
+    else if (n <= 64) ks_gram<T, 4>(Vh, id, n, d, stg, C);
+    else if (n <= 96) ks_gram<T, 6>(Vh, id, n, d, stg, C);
+    else ks_gram<T, 8>(Vh, id, n, d, stg, C);
+
+    // sigma_max^2 = lambda_max(C): power iteration (C symmetric: column reads are row reads)
+    if (tid < n) xv[tid] = 1.0 / sqrt((double)n) * (1.0 + 0.01 * (tid % 7));
+    __syncthreads();
+    double lam = 0.0;
+    for (int it = 0; it < 24; ++it) {
+      double y = 0.0;
+      if (tid < n) for (int t = 0; t < n; ++t) y = fma(C[t * n + tid], xv[t], y);
+      const double n2 = block_sum(y * y, red);             // barriers inside: every xv read is done
+      lam = sqrt(n2);
+      if (!(lam > 0.0)) break;
+      if (tid < n) xv[tid] = y / lam;
+      __syncthreads();
+    }
+    const double thr = sqrt(lam) * (double)max(n, d) * kRankEps;
+
+    // diagonally pivoted Cholesky, left-looking
+    double dg = -1.0;
+    bool used = false;
+    if (tid < n) { dg = C[tid * n + tid]; pdiag[tid] = dg; }
+    __syncthreads();
+    int r = 0;
+    for (int s = 0; s < n; ++s) {
+      if (tid < 128) {
+        double v = dg; int ix = tid;
+        for (int off = 32; off > 0; off >>= 1) {
+          const double ov = __shfl_xor(v, off);
+          const int oi = __shfl_xor(ix, off);
+          if (ov > v || (ov == v && oi < ix)) { v = ov; ix = oi; }
+        }
+        if ((tid & 63) == 0) { wmax[tid >> 6] = v; warg[tid >> 6] = ix; }
+      }
+      __syncthreads();
+      int j = warg[0];
+      double pv = wmax[0];
+      if (wmax[1] > pv) { j = warg[1]; pv = wmax[1]; }
+      if (!(pv > 0.0) || !(sqrt(pv) > thr)) break;
+      if (tid < n) {
+        double x = C[j * n + tid], xj = pdiag[j];
+        for (int t = 0; t < s; ++t) {
+          const double* zt = C + piv[t] * n;
+          const double zj = zt[j];
+          x = fma(-zt[tid], zj, x);
+          xj = fma(-zj, zj, xj);                           // the pivot itself, same arithmetic in every thread
+        }
+        const double ljj = sqrt(fmax(xj, 1e-300));
+        const double l = used ? 0.0 : x / ljj;
+        C[j * n + tid] = l;
+        if (tid == j) used = true;
+        dg = used ? -1.0 : dg - l * l;
+        if (tid == 0) { piv[s] = j; invd[s] = 1.0 / ljj; rowoff[s] = id[j]; }
+      }
+      __syncthreads();
+      r = s + 1;
+    }
+    __syncthreads();
+    r_keep = r;
+    active = (r_keep < d) ? 1 : 0;
+    if (active && r > 0) {
+      // inverse of the triangular factor in pivot order, one column per thread:
+      //   Minv[c][c] = 1 / L[c][c];  Minv[k][c] = -(sum_{c <= t < k} L[k][t] Minv[t][c]) / L[k][k]
+      // with L[k][t] at C[piv[t]][piv[k]] and Minv[k][c] going to C[piv[k]][piv[c]] (c < k).
+      if (tid < r) {
+        const int c = tid;
+        const int pc = piv[c];
+        const double mcc = invd[c];
+        for (int k = c + 1; k < r; ++k) {
+          const int pkk = piv[k];
+          double sum = C[pc * n + pkk] * mcc;
+          for (int t = c + 1; t < k; ++t) {
+            const double* rt = C + piv[t] * n;
+            sum = fma(rt[pkk], rt[pc], sum);
+          }
+          C[pkk * n + pc] = -sum * invd[k];
+        }
+      }
+      __syncthreads();
+      if (tid < r) C[piv[tid] * n + piv[tid]] = invd[tid];   // the factor itself is no longer needed
+      __syncthreads();
+      // Q = Minv A_piv:  Q[s][col] = sum_{k <= s} Minv[s][k] A[piv[k]][col]
+      const int groups = KS_THREADS / d;                     // 2 (d = 128) or 4 (d = 64): wave-uniform
+      const int g = tid / d, col = tid - g * d;
+      double acc[KS_QROWS];
+#pragma unroll
+      for (int i = 0; i < KS_QROWS; ++i) acc[i] = 0.0;
+      for (int k = 0; k < r; ++k) {
+        const double a = (double)Elem<T>::load(Vh + (size_t)rowoff[k] * d + col);
+        const int pkk = piv[k];
+#pragma unroll
+        for (int i = 0; i < KS_QROWS; ++i) {
+          const int srow = g + groups * i;
+          if (srow >= k && srow < r) acc[i] = fma(C[piv[srow] * n + pkk], a, acc[i]);
+        }
+      }
+      float* bh = basis + (size_t)head * d * d;
+#pragma unroll
+      for (int i = 0; i < KS_QROWS; ++i) {
+        const int srow = g + groups * i;
+        if (srow < r) bh[(size_t)srow * d + col] = (float)acc[i];
+      }
+    }
+  }
+  if (tid == 0) {
     HeadState s;
     s.a_keep = a_keep; s.a_del = a_del; s.n_keep = n; s.n_del = n_del; s.r_keep = r_keep; s.active = active;
     s.k_used = 0; s.pad = 0; s.rcr = 0.f; s.ivn = 0.f;
@@ -681,6 +869,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
+    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     attr_done = true;
   }
@@ -691,9 +880,19 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part) != OBF_OK)
       return OBF_ERR_HIP;
   }
-  { ProfScope prof_(ST_KEEP_BASIS, st); hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
-                     m.N, m.d, max_budget, rank, state, basis, decided); }
-  if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
+  {
+    ProfScope prof_(ST_KEEP_BASIS, st);
+    const size_t nmax = (size_t)min(max_budget, m.d);
+    const size_t smem_ks = max(nmax * nmax * sizeof(double), nmax * (KS_CH + 1) * sizeof(float));
+    hipLaunchKernelGGL(k_bf_keep_basis_small<T>, dim3(m.heads), dim3(KS_THREADS), smem_ks, st, (const T*)V, scores, idx,
+                       n_keep, m.N, m.d, max_budget, rank, state, basis);
+    if (check_launch("backfill keep_basis_small") != OBF_OK) return OBF_ERR_HIP;
+    if (max_budget > m.d) {
+      hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
+                         m.N, m.d, max_budget, rank, state, basis, decided);
+      if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
+    }
+  }
   if (rank > 0 && del_stats_mfma_supported(m)) {
     if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
   } else if (rank > 0) {
