@@ -11,6 +11,7 @@
 //                App. H: same subspace as the SVD of R), rbar (Eq. 4), Delta (Eq. 5), delta (Eq. 6).
 //   inject     : V* = V_keep + delta on every retained row (Eq. 7), rounded once to the I/O dtype.
 #include "common.hpp"
+#include "wave_ops.hpp"
 
 namespace obf {
 
@@ -19,6 +20,13 @@ constexpr int KB_WAVES = KB_THREADS / 64;
 constexpr double kRankEps = 1.1920928955078125e-07;   // 2^-23, the rank rule's epsilon
 constexpr float kRcrSkip = 1.0e-6f;                   // "||R||_F negligible": ||R||^2 <= 1e-6 ||V_del||^2
 constexpr float kEigFloor = 1.0e-6f;                  // resolution of the fp32 residual Gram (relative)
+
+#ifdef BF_TRACE
+__device__ uint64_t g_bf_trace[512 * 12];
+#define BF_STAMP(w, k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_bf_trace[blockIdx.x * 12 + (k)] = wall_clock64(); } while (0)
+#else
+#define BF_STAMP(w, k) do { } while (0)
+#endif
 
 // ------------------------------------------------------------------------------------------------
 // small block helpers (KB_THREADS threads)
@@ -273,193 +281,6 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
 }
 
 // ------------------------------------------------------------------------------------------------
-// keep_basis for heads with at most d retained rows (budget below the head dimension: Eq. 2 always
-// leaves a complement).  Everything in double precision on the n x n Gram matrix C = A A^T of the
-// retained rows A (entries of A are exact in float, products and sums are taken in double):
-//   sigma_max^2 = lambda_max(C) by power iteration (rank rule threshold),
-//   diagonally pivoted Cholesky C = L L^T; a pivot is the squared distance of a row from the span of
-//   the rows chosen before it, exactly the quantity pivoted Gram-Schmidt tests, so the rank is the same,
-//   Q = L^-1 A (rows orthonormal) through the explicit inverse of the r x r triangular factor.
-// Storage: row piv[s] of C is dead once s is chosen; it then holds column s of L (at positions piv[k],
-// k > s) and row s of L^-1 (at positions piv[k], k <= s).
-constexpr int KS_THREADS = 256;
-constexpr int KS_CH = 32;                  // columns of A staged per Gram step
-constexpr int KS_QROWS = 64;               // rows of Q per thread in the final product, at most
-
-template <typename T, int TI>
-__device__ void ks_gram(const T* __restrict__ Vh, const int32_t* __restrict__ id, int n, int d, float* stg, double* C) {
-  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-  double acc[TI][TI];
-  for (int a = 0; a < TI; ++a) for (int b = 0; b < TI; ++b) acc[a][b] = 0.0;
-  for (int c0 = 0; c0 < d; c0 += KS_CH) {
-    __syncthreads();
-    for (int e = threadIdx.x; e < n * KS_CH; e += KS_THREADS) {
-      const int i = e / KS_CH, c = e - i * KS_CH;
-      stg[i * (KS_CH + 1) + c] = Elem<T>::load(Vh + (size_t)id[i] * d + c0 + c);
-    }
-    __syncthreads();
-    for (int c = 0; c < KS_CH; ++c) {
-      double av[TI], bv[TI];
-      for (int a = 0; a < TI; ++a) av[a] = (double)stg[min(ty + 16 * a, n - 1) * (KS_CH + 1) + c];
-      for (int b = 0; b < TI; ++b) bv[b] = (double)stg[min(tx + 16 * b, n - 1) * (KS_CH + 1) + c];
-      for (int a = 0; a < TI; ++a) for (int b = 0; b < TI; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
-    }
-  }
-  __syncthreads();                           // the staging area aliases C
-  for (int a = 0; a < TI; ++a)
-    for (int b = 0; b < TI; ++b) {
-      const int i = ty + 16 * a, j = tx + 16 * b;
-      if (i < n && j < n) C[i * n + j] = acc[a][b];
-    }
-  __syncthreads();
-}
-
-template <typename T>
-__global__ __launch_bounds__(KS_THREADS, 2) void k_bf_keep_basis_small(const T* __restrict__ V, const float* __restrict__ scores,
-                                                                    const int32_t* __restrict__ idx,
-                                                                    const int32_t* __restrict__ n_keep, int N, int d,
-                                                                    int max_budget, int rank, HeadState* __restrict__ state,
-                                                                    float* __restrict__ basis) {
-  const int head = blockIdx.x;
-  const int n = n_keep[head];
-  if (n > d) return;                         // heads of the general kernel
-  extern __shared__ double C[];              // [n][n]; first the float staging area of the Gram phase
-  __shared__ double red[KB_WAVES];
-  __shared__ double xv[128], pdiag[128], invd[128], wmax[2];
-  __shared__ int piv[128], rowoff[128], warg[2];
-  const int n_del = N - n;
-  const float* sc = scores + (size_t)head * N;
-  const int32_t* id = idx + (size_t)head * max_budget;
-  const T* Vh = V + (size_t)head * N * d;
-  const int tid = threadIdx.x;
-
-  // demand sums of Eq. 6, in double, fixed summation order
-  double pk = 0.0, pt = 0.0;
-  for (int i = tid; i < n; i += KS_THREADS) pk += (double)sc[id[i]];
-  for (int i = tid; i < N; i += KS_THREADS) pt += (double)sc[i];
-  const double a_keep = block_sum(pk, red);
-  const double a_tot = block_sum(pt, red);
-  double a_del = a_tot - a_keep;
-  if (a_del < 0.0) a_del = 0.0;
-
-  int r_keep = 0, active = 0;
-  if (rank > 0 && n > 0 && n_del > 0) {
-    float* stg = (float*)C;
-    if (n <= 32) ks_gram<T, 2>(Vh, id, n, d, stg, C);
-    else if (n <= 64) ks_gram<T, 4>(Vh, id, n, d, stg, C);
-    else if (n <= 96) ks_gram<T, 6>(Vh, id, n, d, stg, C);
-    else ks_gram<T, 8>(Vh, id, n, d, stg, C);
-
-    // sigma_max^2 = lambda_max(C): power iteration (C symmetric: column reads are row reads)
-    if (tid < n) xv[tid] = 1.0 / sqrt((double)n) * (1.0 + 0.01 * (tid % 7));
-    __syncthreads();
-    double lam = 0.0;
-    for (int it = 0; it < 24; ++it) {
-      double y = 0.0;
-      if (tid < n) for (int t = 0; t < n; ++t) y = fma(C[t * n + tid], xv[t], y);
-      const double n2 = block_sum(y * y, red);             // barriers inside: every xv read is done
-      lam = sqrt(n2);
-      if (!(lam > 0.0)) break;
-      if (tid < n) xv[tid] = y / lam;
-      __syncthreads();
-    }
-    const double thr = sqrt(lam) * (double)max(n, d) * kRankEps;
-
-    // diagonally pivoted Cholesky, left-looking
-    double dg = -1.0;
-    bool used = false;
-    if (tid < n) { dg = C[tid * n + tid]; pdiag[tid] = dg; }
-    __syncthreads();
-    int r = 0;
-    for (int s = 0; s < n; ++s) {
-      if (tid < 128) {
-        double v = dg; int ix = tid;
-        for (int off = 32; off > 0; off >>= 1) {
-          const double ov = __shfl_xor(v, off);
-          const int oi = __shfl_xor(ix, off);
-          if (ov > v || (ov == v && oi < ix)) { v = ov; ix = oi; }
-        }
-        if ((tid & 63) == 0) { wmax[tid >> 6] = v; warg[tid >> 6] = ix; }
-      }
-      __syncthreads();
-      int j = warg[0];
-      double pv = wmax[0];
-      if (wmax[1] > pv) { j = warg[1]; pv = wmax[1]; }
-      if (!(pv > 0.0) || !(sqrt(pv) > thr)) break;
-      if (tid < n) {
-        double x = C[j * n + tid], xj = pdiag[j];
-        for (int t = 0; t < s; ++t) {
-          const double* zt = C + piv[t] * n;
-          const double zj = zt[j];
-          x = fma(-zt[tid], zj, x);
-          xj = fma(-zj, zj, xj);                           // the pivot itself, same arithmetic in every thread
-        }
-        const double ljj = sqrt(fmax(xj, 1e-300));
-        const double l = used ? 0.0 : x / ljj;
-        C[j * n + tid] = l;
-        if (tid == j) used = true;
-        dg = used ? -1.0 : dg - l * l;
-        if (tid == 0) { piv[s] = j; invd[s] = 1.0 / ljj; rowoff[s] = id[j]; }
-      }
-      __syncthreads();
-      r = s + 1;
-    }
-    __syncthreads();
-    r_keep = r;
-    active = (r_keep < d) ? 1 : 0;
-    if (active && r > 0) {
-      // inverse of the triangular factor in pivot order, one column per thread:
-      //   Minv[c][c] = 1 / L[c][c];  Minv[k][c] = -(sum_{c <= t < k} L[k][t] Minv[t][c]) / L[k][k]
-      // with L[k][t] at C[piv[t]][piv[k]] and Minv[k][c] going to C[piv[k]][piv[c]] (c < k).
-      if (tid < r) {
-        const int c = tid;
-        const int pc = piv[c];
-        const double mcc = invd[c];
-        for (int k = c + 1; k < r; ++k) {
-          const int pkk = piv[k];
-          double sum = C[pc * n + pkk] * mcc;
-          for (int t = c + 1; t < k; ++t) {
-            const double* rt = C + piv[t] * n;
-            sum = fma(rt[pkk], rt[pc], sum);
-          }
-          C[pkk * n + pc] = -sum * invd[k];
-        }
-      }
-      __syncthreads();
-      if (tid < r) C[piv[tid] * n + piv[tid]] = invd[tid];   // the factor itself is no longer needed
-      __syncthreads();
-      // Q = Minv A_piv:  Q[s][col] = sum_{k <= s} Minv[s][k] A[piv[k]][col]
-      const int groups = KS_THREADS / d;                     // 2 (d = 128) or 4 (d = 64): wave-uniform
-      const int g = tid / d, col = tid - g * d;
-      double acc[KS_QROWS];
-#pragma unroll
-      for (int i = 0; i < KS_QROWS; ++i) acc[i] = 0.0;
-      for (int k = 0; k < r; ++k) {
-        const double a = (double)Elem<T>::load(Vh + (size_t)rowoff[k] * d + col);
-        const int pkk = piv[k];
-#pragma unroll
-        for (int i = 0; i < KS_QROWS; ++i) {
-          const int srow = g + groups * i;
-          if (srow >= k && srow < r) acc[i] = fma(C[piv[srow] * n + pkk], a, acc[i]);
-        }
-      }
-      float* bh = basis + (size_t)head * d * d;
-#pragma unroll
-      for (int i = 0; i < KS_QROWS; ++i) {
-        const int srow = g + groups * i;
-        if (srow < r) bh[(size_t)srow * d + col] = (float)acc[i];
-      }
-    }
-  }
-  if (tid == 0) {
-    HeadState s;
-    s.a_keep = a_keep; s.a_del = a_del; s.n_keep = n; s.n_del = n_del; s.r_keep = r_keep; s.active = active;
-    s.k_used = 0; s.pad = 0; s.rcr = 0.f; s.ivn = 0.f;
-    state[head] = s;
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // del_stats: partial V_del^T V_del, sum_j A_j v_j and ||V_del||^2 over one chunk of tokens
 constexpr int DS_THREADS = 256;
 constexpr int DS_TOK = 32;
@@ -564,14 +385,16 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
   __shared__ float fred[FN_WAVES];
   __shared__ int s_k;
   __shared__ float s_off;
-  __shared__ float pdiag[128], wmax[2];
-  __shared__ int piv[128], warg[2];
+  __shared__ float pdiag[128];
+  __shared__ uint32_t wkey[2][2];
+  __shared__ int piv[128];
   HeadState st = state[head];
   int skipped = 1;
   float rcr = 0.f, ivn = 0.f;
   int k_used = 0;
   const int tid = threadIdx.x;
 
+  BF_STAMP(1, 0);
   if (st.active) {
     const int r = st.r_keep;
     int m = d - r;                                             // dimension of the orthogonal complement
@@ -582,25 +405,34 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
     float* Yg = Zg + (size_t)d * d;                            // [m][d] Z G
 
     // G = sum of chunk partials (fixed order), u, ||V_del||^2
-    for (int e = tid; e < d * d; e += FN_THREADS) {
-      float s = 0.f;
-      for (int c = 0; c < nstat; ++c) s += gp[c * pstride + e];
-      M[(e / d) * ld + (e % d)] = s;
+    for (int e = tid * 4; e < d * d; e += FN_THREADS * 4) {
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+      for (int c = 0; c < nstat; ++c) {
+        const float4 q = *(const float4*)(gp + c * pstride + e);
+        s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
+      }
+      float* o = M + (e / d) * ld + (e % d);
+      o[0] = s.x; o[1] = s.y; o[2] = s.z; o[3] = s.w;
     }
     if (tid < d) {
       float s = 0.f;
+#pragma unroll 8
       for (int c = 0; c < nstat; ++c) s += gp[c * pstride + d * d + tid];
       uvec[tid] = s;
     }
     float vd2 = 0.f;
+#pragma unroll 8
     for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + d];
 
+    BF_STAMP(1, 1);
     // P = I - Q^T Q (projector onto the complement of the retained span, Eq. 3), 4 x 4 tiles per thread
     const int q4 = d >> 2;
     for (int e = tid; e < q4 * q4; e += FN_THREADS) {
       const int a0 = (e / q4) << 2, b0 = (e % q4) << 2;
       float acc[4][4];
       for (int x = 0; x < 4; ++x) for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
+#pragma unroll 8
       for (int i = 0; i < r; ++i) {
         const float4 qa = *(const float4*)(Qb + (size_t)i * d + a0);
         const float4 qb = *(const float4*)(Qb + (size_t)i * d + b0);
@@ -612,46 +444,62 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
     }
     __syncthreads();
 
+    BF_STAMP(1, 2);
     // Diagonally pivoted Cholesky of P, left-looking: a projector of rank m factors as P = Z^T Z with the
     // m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  Row s of Z overwrites
     // row piv[s] of P, which is never read again (only rows of pivots still to come are).
     float dg = -1.f;
     bool used = false;
+    const int lane = tid & 63;
+    int pivlo = 0, pivhi = 0;                                  // lane t holds piv[t] / piv[64 + t]
     if (tid < d) { dg = U[tid * ld + tid]; pdiag[tid] = dg; }
+    auto publish = [&](int buf) {                              // wave maxima of (remaining diagonal, lowest index first)
+      if (tid < 128) {
+        uint32_t key = (!used && tid < d && dg > 0.f) ? ((__float_as_uint(dg) & ~0x7Fu) | (uint32_t)(127 - tid)) : 0u;
+        key = wave_max_u32(key);
+        if (lane == 0) wkey[buf][tid >> 6] = key;
+      }
+    };
+    auto pivot_of = [&](const int t) {
+      return t < 64 ? __builtin_amdgcn_readlane(pivlo, t) : __builtin_amdgcn_readlane(pivhi, t - 64);
+    };
+    publish(0);
     __syncthreads();
     for (int s = 0; s < m; ++s) {
-      if (tid < d) {
-        float v = dg; int ix = tid;
-        for (int off = 32; off > 0; off >>= 1) {
-          const float ov = __shfl_xor(v, off);
-          const int oi = __shfl_xor(ix, off);
-          if (ov > v || (ov == v && oi < ix)) { v = ov; ix = oi; }
-        }
-        if ((tid & 63) == 0) { wmax[tid >> 6] = v; warg[tid >> 6] = ix; }
-      }
-      __syncthreads();
-      int j = warg[0];
-      float pv = wmax[0];
-      if (d > 64 && wmax[1] > pv) { j = warg[1]; pv = wmax[1]; }
+      const uint32_t key = max(wkey[s & 1][0], wkey[s & 1][1]);
+      const int j = 127 - (int)(key & 0x7Fu);
+      const float pv = __uint_as_float(key & ~0x7Fu);
       if (!(pv > 1e-5f)) { m = s; break; }                       // cannot happen for an exact projector of rank m
       if (tid < d) {
         float x = U[j * ld + tid], xj = pdiag[j];
-        for (int t = 0; t < s; ++t) {
-          const float* zt = U + piv[t] * ld;
-          const float zj = zt[j];
-          x = fmaf(-zt[tid], zj, x);
-          xj = fmaf(-zj, zj, xj);                                // the pivot itself, same arithmetic in every thread
+        int t = 0;
+        for (; t + 8 <= s; t += 8) {
+          float zj[8], v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) { const float* zt = U + pivot_of(t + u) * ld; zj[u] = zt[j]; v[u] = zt[tid]; }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) { x = fmaf(-v[u], zj[u], x); xj = fmaf(-zj[u], zj[u], xj); }
+        }
+        {
+          float zj[8], v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) { const float* zt = U + pivot_of(min(t + u, max(s - 1, 0))) * ld; zj[u] = zt[j]; v[u] = zt[tid]; }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) if (t + u < s) { x = fmaf(-v[u], zj[u], x); xj = fmaf(-zj[u], zj[u], xj); }   // xj: the pivot, same arithmetic in every thread
         }
         const float l = used ? 0.f : x * rsqrtf(fmaxf(xj, 1e-12f));
         U[j * ld + tid] = l;
         if (tid == j) used = true;
-        dg = used ? -1.f : dg - l * l;
+        if (!used) dg -= l * l;
         if (tid == 0) piv[s] = j;
       }
+      if (s < 64) { if (lane == s) pivlo = j; } else { if (lane == s - 64) pivhi = j; }
+      publish((s + 1) & 1);
       __syncthreads();
     }
     __syncthreads();
 
+    BF_STAMP(1, 3);
     // Z to global scratch (compact rows), Y = Z G
     for (int e = tid; e < m * d; e += FN_THREADS) Zg[e] = U[piv[e / d] * ld + (e % d)];
     const int sg = (m + 3) >> 2;
@@ -672,6 +520,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       if (s0 + 3 < m) Yg[(size_t)(s0 + 3) * d + b] = a3;
     }
     __syncthreads();
+    BF_STAMP(1, 4);
     // T = Y Z^T = Z G Z^T (m x m): the residual Gram matrix R^T R = P G P restricted to the complement,
     // whose eigenpairs (lambda, w) give those of P G P as (lambda, Z^T w).  Stored over G, padded to even size.
     const int mm = m + (m & 1);
@@ -709,6 +558,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
     rcr = res2 / (vd2 + 1e-12f);
     const bool negligible = !(res2 > kRcrSkip * vd2) || m <= 0;
 
+    BF_STAMP(1, 5);
     if (!negligible) {
       // cyclic Jacobi with a round-robin ordering: mm/2 disjoint rotations per round
       const int half = mm / 2;
@@ -730,27 +580,35 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
             pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
           }
           __syncthreads();
-          // columns: T <- T J, W <- W J  (the two matrices on different threads)
-          for (int e = tid; e < 2 * half * mm; e += FN_THREADS) {
-            const int w = e >= half * mm;
-            const int e2 = e - w * half * mm;
-            const int i = e2 / mm, k = e2 - i * mm;
-            const int p = pp[i], q = qq[i];
-            const float c = cs[i], s = sn[i];
-            float* A = w ? U : M;
-            const float mp = A[k * lt + p], mq = A[k * lt + q];
-            A[k * lt + p] = c * mp - s * mq;
-            A[k * lt + q] = s * mp + c * mq;
-          }
-          __syncthreads();
-          // rows: T <- J^T T
-          for (int e = tid; e < half * mm; e += FN_THREADS) {
-            const int i = e / mm, k = e - i * mm;
-            const int p = pp[i], q = qq[i];
-            const float c = cs[i], s = sn[i];
-            const float mp = M[p * lt + k], mq = M[q * lt + k];
-            M[p * lt + k] = c * mp - s * mq;
-            M[q * lt + k] = s * mp + c * mq;
+          // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j, mirrored: the blocks are
+          // disjoint, so one pass does both sides), and W <- W J by columns
+          const int nb = half * half;
+          for (int e = tid; e < nb + half * mm; e += FN_THREADS) {
+            if (e < nb) {
+              const int i = e / half, jb = e - i * half;
+              if (i <= jb) {
+                const int p = pp[i], q = qq[i], p2 = pp[jb], q2 = qq[jb];
+                const float ci = cs[i], si = sn[i], cj = cs[jb], sj = sn[jb];
+                const float a = M[p * lt + p2], b = M[p * lt + q2], c = M[q * lt + p2], dd = M[q * lt + q2];
+                const float a1 = cj * a - sj * b, b1 = sj * a + cj * b, c1 = cj * c - sj * dd, d1 = sj * c + cj * dd;
+                const float a2 = ci * a1 - si * c1, c2 = si * a1 + ci * c1, b2 = ci * b1 - si * d1, d2 = si * b1 + ci * d1;
+                if (i == jb) {
+                  const float od = 0.5f * (b2 + c2);
+                  M[p * lt + p] = a2; M[q * lt + q] = d2; M[p * lt + q] = od; M[q * lt + p] = od;
+                } else {
+                  M[p * lt + p2] = a2; M[p * lt + q2] = b2; M[q * lt + p2] = c2; M[q * lt + q2] = d2;
+                  M[p2 * lt + p] = a2; M[q2 * lt + p] = b2; M[p2 * lt + q] = c2; M[q2 * lt + q] = d2;
+                }
+              }
+            } else {
+              const int e2 = e - nb;
+              const int i = e2 / mm, k = e2 - i * mm;
+              const int p = pp[i], q = qq[i];
+              const float c = cs[i], s = sn[i];
+              const float wp = U[k * lt + p], wq = U[k * lt + q];
+              U[k * lt + p] = c * wp - s * wq;
+              U[k * lt + q] = s * wp + c * wq;
+            }
           }
           __syncthreads();
         }
@@ -769,6 +627,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
         __syncthreads();
         if (offn <= 1e-13f * res2 * res2) break;
       }
+      BF_STAMP(1, 6);
       // eigenvalues, descending order (ties: lower index first), numerical rank of R
       if (tid < m) lamv[tid] = M[tid * lt + tid];
       __syncthreads();
@@ -827,6 +686,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       }
     }
   }
+  BF_STAMP(1, 7);
   // outputs for every head
   if (tid < d) {
     const float v = skipped ? 0.f : uvec[tid];
@@ -853,6 +713,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       Elem<T>::store(p, Elem<T>::load(p) + uvec[e % d]);
     }
   }
+  BF_STAMP(1, 8);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -869,7 +730,6 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
-    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     attr_done = true;
   }
@@ -882,11 +742,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   }
   {
     ProfScope prof_(ST_KEEP_BASIS, st);
-    const size_t nmax = (size_t)min(max_budget, m.d);
-    const size_t smem_ks = max(nmax * nmax * sizeof(double), nmax * (KS_CH + 1) * sizeof(float));
-    hipLaunchKernelGGL(k_bf_keep_basis_small<T>, dim3(m.heads), dim3(KS_THREADS), smem_ks, st, (const T*)V, scores, idx,
-                       n_keep, m.N, m.d, max_budget, rank, state, basis);
-    if (check_launch("backfill keep_basis_small") != OBF_OK) return OBF_ERR_HIP;
+    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
     if (max_budget > m.d) {
       hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
                          m.N, m.d, max_budget, rank, state, basis, decided);
@@ -916,3 +772,9 @@ obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const 
 }
 
 }  // namespace obf
+
+#ifdef BF_TRACE
+extern "C" int obf_debug_copy_bf_trace(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_bf_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif

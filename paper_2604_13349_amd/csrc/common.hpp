@@ -161,6 +161,10 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
                            const int32_t* n_keep, hipStream_t st);
 obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const int32_t* idx, const int32_t* n_keep,
                            int32_t max_budget, void* K_out, void* V_out, hipStream_t st, double* fro_part = nullptr);
+// Retained-span basis for the heads with at most head_dim retained rows (the others are left untouched).
+obf_status_t launch_keep_basis_small(const Dims& m, const void* V, const float* scores, const int32_t* idx,
+                                     const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
+                                     float* basis, hipStream_t st);
 bool del_stats_mfma_supported(const Dims& m);
 obf_status_t launch_del_stats_mfma(const Dims& m, const Workspace& w, const void* V, const float* scores,
                                    const int32_t* idx, int32_t max_budget, const HeadState* state, float* gram_part,
