@@ -366,18 +366,18 @@ constexpr int FN_SWEEPS = 12;
 constexpr int FN_TPT = (128 * 128) / FN_THREADS;   // entries of the reduced Gram matrix per thread, at most
 
 template <typename T>
-__global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int nstat, int rank,
+__global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int nstat, int rank,
                                                             HeadState* __restrict__ state,
                                                             const float* __restrict__ basis,
                                                             const float* __restrict__ gram_part,
                                                             float* __restrict__ mats, float* __restrict__ delta,
                                                             float* __restrict__ delta_out, obf_diag_t* __restrict__ diag,
-                                                            T* __restrict__ V_out, int max_budget) {
+                                                            T* __restrict__ V_out, int max_budget, int cls) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
-  float* M = sm;                    // [d][ld]   P G P, then its diagonal form
-  float* U = sm + d * ld;           // [d][ld]   accumulated rotations (columns = eigenvectors)
+  float* U = sm;                    // [d][ld]   projector P, then the rows of Z; later T and (if they both fit) W
+  float* M = sm;                    // T = Z G Z^T and its diagonal form, set below
   __shared__ float cs[64], sn[64];
   __shared__ int pp[64], qq[64];
   __shared__ float uvec[128], rbar[128], dvec[128], lamv[128];
@@ -393,6 +393,14 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
   float rcr = 0.f, ivn = 0.f;
   int k_used = 0;
   const int tid = threadIdx.x;
+  {
+    // Two launches share the heads: the first has LDS for one d x d matrix (two workgroups per CU) and takes
+    // every head whose complement is small enough for T and W to fit there, the second takes the rest.
+    const int m0 = st.active ? d - st.r_keep : 0;
+    const int mm0 = m0 + (m0 & 1);
+    const int big = 2 * mm0 * (mm0 + 1) > d * ld;
+    if (big != cls) return;
+  }
 
   BF_STAMP(1, 0);
   if (st.active) {
@@ -403,6 +411,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
     const float* gp = gram_part + (size_t)head * nstat * pstride;
     float* Zg = mats + (size_t)head * 3 * d * d;               // [m][d] basis of the complement (global scratch)
     float* Yg = Zg + (size_t)d * d;                            // [m][d] Z G
+    float* Gg = Yg + (size_t)d * d;                            // [d][d] G summed over the chunk partials
 
     // G = sum of chunk partials (fixed order), u, ||V_del||^2
     for (int e = tid * 4; e < d * d; e += FN_THREADS * 4) {
@@ -412,8 +421,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
         const float4 q = *(const float4*)(gp + c * pstride + e);
         s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
       }
-      float* o = M + (e / d) * ld + (e % d);
-      o[0] = s.x; o[1] = s.y; o[2] = s.z; o[3] = s.w;
+      *(float4*)(Gg + e) = s;                                  // read back (through L2) when Y = Z G is formed
     }
     if (tid < d) {
       float s = 0.f;
@@ -510,8 +518,9 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       const float* z2 = U + piv[min(s0 + 2, m - 1)] * ld;
       const float* z3 = U + piv[min(s0 + 3, m - 1)] * ld;
       float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 8
       for (int c = 0; c < d; ++c) {
-        const float g = M[c * ld + b];
+        const float g = Gg[c * d + b];
         a0 = fmaf(z0[c], g, a0); a1 = fmaf(z1[c], g, a1); a2 = fmaf(z2[c], g, a2); a3 = fmaf(z3[c], g, a3);
       }
       Yg[(size_t)s0 * d + b] = a0;
@@ -522,7 +531,7 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
     __syncthreads();
     BF_STAMP(1, 4);
     // T = Y Z^T = Z G Z^T (m x m): the residual Gram matrix R^T R = P G P restricted to the complement,
-    // whose eigenpairs (lambda, w) give those of P G P as (lambda, Z^T w).  Stored over G, padded to even size.
+    // whose eigenpairs (lambda, w) give those of P G P as (lambda, Z^T w).  Stored over Z, padded to even size.
     const int mm = m + (m & 1);
     const int lt = mm + 1;
     float tacc[FN_TPT];
@@ -540,7 +549,8 @@ __global__ __launch_bounds__(FN_THREADS) void k_bf_finalize(int N, int d, int ns
       }
       tacc[k] = acc;
     }
-    __syncthreads();                                             // G and Z (in LDS) are dead from here on
+    __syncthreads();                                             // Z (in LDS) is dead from here on
+    U = (2 * mm * lt <= d * ld) ? sm + mm * lt : sm + d * ld;    // W next to T, or in the second buffer of the large launch
     for (int k = 0, e = tid; k < FN_TPT; ++k, e += FN_THREADS)
       if (e < m * m) M[(e / m) * lt + (e % m)] = tacc[k];
     if (mm > m) for (int e = tid; e < mm; e += FN_THREADS) { M[m * lt + e] = 0.f; M[e * lt + m] = 0.f; }
@@ -756,9 +766,15 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
                        (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
-  { ProfScope prof_(ST_FINALIZE, st); hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), sizeof(float) * 2 * m.d * (m.d + 1), st, m.N, m.d,
-                     w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
-                     (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget); }
+  {
+    ProfScope prof_(ST_FINALIZE, st);
+    const size_t one = sizeof(float) * m.d * (m.d + 1);
+    for (int cls = 0; cls < 2; ++cls) {
+      hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), one * (cls + 1), st, m.N, m.d,
+                         w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
+                         (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls);
+    }
+  }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
   return OBF_OK;
 }
