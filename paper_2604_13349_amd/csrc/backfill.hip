@@ -290,13 +290,14 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
                                                              const int32_t* __restrict__ idx, int N, int d,
                                                              int max_budget, int nstat,
                                                              const HeadState* __restrict__ state,
+                                                             const int32_t* __restrict__ n_keep /*non-null: do not read the head states*/,
                                                              float* __restrict__ gram_part) {
   const int head = blockIdx.y, chunk = blockIdx.x;
-  if (!state[head].active) return;
+  const int n = n_keep ? n_keep[head] : state[head].n_keep;
+  if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
   extern __shared__ float Vs[];              // [DS_TOK][d], retained rows zeroed
   __shared__ float wt[DS_TOK];               // score of the token (0 for rows that are not deleted)
   __shared__ int isdel[DS_TOK];              // 1: deleted row of this chunk
-  const int n = state[head].n_keep;
   const int32_t* id = idx + (size_t)head * max_budget;
   const T* Vh = V + (size_t)head * N * d;
   const float* sc = scores + (size_t)head * N;
@@ -728,6 +729,25 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
 
 // ------------------------------------------------------------------------------------------------
 // inject: V_out[row] += delta for the retained rows of heads that were not skipped (Eq. 7)
+// A second stream (default priority) per host thread and device, with the two events of a fork / join.
+struct SideStream { hipStream_t stream; hipEvent_t fork, join; int dev; };
+
+static SideStream* side_stream() {
+  static thread_local SideStream ctx[16];
+  static thread_local int nctx = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  for (int i = 0; i < nctx; ++i) if (ctx[i].dev == dev) return &ctx[i];
+  if (nctx == 16) return nullptr;
+  SideStream c;
+  c.dev = dev;
+  if (hipStreamCreateWithFlags(&c.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+  if (hipEventCreateWithFlags(&c.fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+  ctx[nctx] = c;
+  return &ctx[nctx++];
+}
+
 template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
@@ -750,22 +770,37 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part) != OBF_OK)
       return OBF_ERR_HIP;
   }
+  // With every budget below the head dimension each head with deleted rows is active whatever its basis turns
+  // out to be, so the streaming statistics pass does not wait for the basis: the two run side by side, the
+  // basis on a second stream that forks from and joins back into the caller's stream.
+  SideStream* side = (rank > 0 && max_budget < m.d) ? side_stream() : nullptr;
+  hipStream_t sb = st;
+  if (side) {
+    if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
+      set_error("backfill: forking the side stream failed");
+      return OBF_ERR_HIP;
+    }
+    sb = side->stream;
+  }
   {
-    ProfScope prof_(ST_KEEP_BASIS, st);
-    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
+    ProfScope prof_(ST_KEEP_BASIS, sb);
+    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, sb) != OBF_OK) return OBF_ERR_HIP;
     if (max_budget > m.d) {
-      hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
+      hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, sb, (const T*)V, scores, idx, n_keep,
                          m.N, m.d, max_budget, rank, state, basis, decided);
       if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
     }
   }
+  if (side && hipEventRecord(side->join, sb) != hipSuccess) { set_error("backfill: side stream record failed"); return OBF_ERR_HIP; }
+  const int32_t* nk_stats = side ? n_keep : nullptr;
   if (rank > 0 && del_stats_mfma_supported(m)) {
-    if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
+    if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, nk_stats, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
   } else if (rank > 0) {
     { ProfScope prof_(ST_DEL_STATS, st); hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
-                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, gram_part); }
+                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, nk_stats, gram_part); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
+  if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) { set_error("backfill: joining the side stream failed"); return OBF_ERR_HIP; }
   {
     ProfScope prof_(ST_FINALIZE, st);
     const size_t one = sizeof(float) * m.d * (m.d + 1);

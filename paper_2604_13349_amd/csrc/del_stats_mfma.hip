@@ -32,9 +32,11 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
                                                                      const int32_t* __restrict__ idx, int N,
                                                                      int max_budget, int nstat,
                                                                      const HeadState* __restrict__ state,
+                                                                     const int32_t* __restrict__ n_keep /*non-null: the head states are still being written; every head with deleted rows is active*/,
                                                                      float* __restrict__ gram_part) {
   const int head = blockIdx.y, chunk = blockIdx.x;
-  if (!state[head].active) return;
+  const int n = n_keep ? n_keep[head] : state[head].n_keep;
+  if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
   __shared__ uint32_t stage[2][(DM_TILE / 2) * DM_LDW];
   __shared__ float wt[kStatChunk];                     // score of a deleted token of the chunk, 0 for a retained one
   __shared__ uint32_t kept[kStatChunk / 32];           // bitmap of the retained tokens of the chunk
@@ -42,7 +44,6 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 31, lh = lane >> 5;
-  const int n = state[head].n_keep;
   const int32_t* id = idx + (size_t)head * max_budget;
   const uint16_t* Vh = V + (size_t)head * N * DM_D;
   const float* sc = scores + (size_t)head * N;
@@ -194,11 +195,11 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
 bool del_stats_mfma_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == DM_D; }
 
 obf_status_t launch_del_stats_mfma(const Dims& m, const Workspace& w, const void* V, const float* scores,
-                                   const int32_t* idx, int32_t max_budget, const HeadState* state, float* gram_part,
-                                   hipStream_t st) {
+                                   const int32_t* idx, int32_t max_budget, const HeadState* state,
+                                   const int32_t* n_keep, float* gram_part, hipStream_t st) {
   { ProfScope prof_(ST_DEL_STATS, st);
     hipLaunchKernelGGL(k_bf_del_stats_mfma, dim3(w.nstat, m.heads), dim3(DM_THREADS), 0, st, (const uint16_t*)V, scores,
-                       idx, m.N, max_budget, w.nstat, state, gram_part); }
+                       idx, m.N, max_budget, w.nstat, state, n_keep, gram_part); }
   return check_launch("backfill del_stats (mfma)");
 }
 
