@@ -71,10 +71,9 @@ template <> struct RowLoad<float, 2> {
 
 struct KsShared {
   double red[KS_WAVES];
-  double xv[128], yv[128];           // power iteration vectors
-  double xcol[128];                  // column j of C at a step (unscaled)
+  double xv[128], yp[4][128];        // power iteration: iterate, partial products
   double qrow[128];                  // row j of A at a step (unscaled)
-  uint64_t wkey[2][2];
+  uint32_t wkey[2][2];
 };
 
 // Stages 16-byte pieces of the retained rows into LDS as float, row stride d + 1.
@@ -149,12 +148,13 @@ __device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id,
   }
   KS_STAMP(2);
 
-  // ---- sigma_max^2 = lambda_max(C): power iteration, four threads per row.  The iterate is scaled by the first
+  // ---- sigma_max^2 = lambda_max(C): power iteration.  Each quarter of the workgroup (a wave pair) takes every
+  // fourth row of C for all columns, the partial products meet in LDS.  The iterate is scaled by the first
   // step's estimate only; the last step takes the true ratio.
   if (tid < 128) sh.xv[tid] = (tid < n) ? 1.0 / sqrt((double)n) * (1.0 + 0.01 * (tid % 7)) : 0.0;
   __syncthreads();
   double lam = 0.0, scale = 1.0;
-  const int prow = tid >> 2, ppart = tid & 3;
+  const int prow = tid & 127, ppart = tid >> 7;                // ppart is uniform over a wave
   const bool pact = prow < NP;
   const double* cp = C + ppart * NP + (pact ? prow : 0);       // C symmetric: column reads are row reads
   const double* xp = sh.xv + ppart;
@@ -165,21 +165,19 @@ __device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id,
       y0 = fma(cp[(4 * u) * NP], xp[4 * u], y0);
       y1 = fma(cp[(4 * u + 4) * NP], xp[4 * u + 4], y1);
     }
-    double y = y0 + y1;
-    y += __longlong_as_double((long long)obf_dpp_mov64((uint64_t)__double_as_longlong(y), 0));
-    y += __longlong_as_double((long long)obf_dpp_mov64((uint64_t)__double_as_longlong(y), 1));
-    if (!pact || ppart != 0) y = 0.0;
+    sh.yp[ppart][prow] = pact ? y0 + y1 : 0.0;
+    lds_barrier();
+    double y = 0.0;
+    if (tid < 128) y = (sh.yp[0][tid] + sh.yp[1][tid]) + (sh.yp[2][tid] + sh.yp[3][tid]);
     if (it == 0 || it == 23) {
-      const double x0 = (tid < n) ? sh.xv[tid] : 0.0;
-      const double n2 = ks_block_sum(y * y, sh.red);           // barriers inside: every read of xv is done
+      const double x0 = (tid < 128) ? sh.xv[tid] : 0.0;
+      const double n2 = ks_block_sum(y * y, sh.red);
       const double d2 = ks_block_sum(x0 * x0, sh.red);
       lam = sqrt(n2 / fmax(d2, 1e-300));
       if (!(lam > 0.0)) break;
       scale = 1.0 / lam;
-    } else {
-      lds_barrier();
     }
-    if (pact && ppart == 0) sh.xv[prow] = y * scale;
+    if (tid < 128) sh.xv[tid] = y * scale;
     lds_barrier();
   }
   const double thr = sqrt(lam) * (double)max(n, d) * kRankEpsKs;
@@ -205,10 +203,12 @@ __device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id,
   // ---- pivoted Gram-Schmidt driven by C
   double dg = (tid < n) ? C[tid * NP + tid] : -1.0;            // threads < n: remaining squared norm of row tid
   bool used = false;
-  auto publish = [&](int buf) {                                // wave maxima of (remaining norm, lowest index first)
+  // Pivot search key: the high word of the (positive) double, low 7 bits replaced by 127 - row, so that the
+  // maximum over the keys is the largest remaining norm (to 13 mantissa bits), lowest row first among equals.
+  auto publish = [&](int buf) {
     if (tid < 128) {
-      uint64_t key = (!used && dg > 0.0) ? ((((uint64_t)__double_as_longlong(dg)) & ~0x7FULL) | (uint64_t)(127 - tid)) : 0ULL;
-      key = wave_max_u64(key);
+      uint32_t key = (!used && dg > 0.0) ? ((((uint32_t)(((uint64_t)__double_as_longlong(dg)) >> 32)) & ~0x7Fu) | (uint32_t)(127 - tid)) : 0u;
+      key = wave_max_u32(key);
       if (lane == 0) sh.wkey[buf][tid >> 6] = key;
     }
   };
@@ -217,25 +217,30 @@ __device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id,
   double* cown = C + ty * NP + tx;                             // element (a, b) of this thread: cown[16a * NP + 32b]
   int r = 0;
   for (int s = 0; s < n; ++s) {
-    const uint64_t k0 = sh.wkey[s & 1][0], k1 = sh.wkey[s & 1][1];
-    const uint64_t key = k0 > k1 ? k0 : k1;
-    const int j = 127 - (int)(key & 0x7F);
-    const double pv = __longlong_as_double((long long)(key & ~0x7FULL));
-    if (!(pv > thr2)) break;
-    if (s == 2) KS_STAMP(5);
-    if (tid < NP) sh.xcol[tid] = C[j * NP + tid];              // row j of C (= column j), before anyone updates it
+    const uint32_t key = max(sh.wkey[s & 1][0], sh.wkey[s & 1][1]);
+    if (key == 0u) break;
+    const int j = 127 - (int)(key & 0x7Fu);
+    // row j of C (= column j) straight into registers: final since the last barrier, and every thread has its
+    // values before the next barrier lets anyone update them
+    const double* crow = C + j * NP;
+    const double xjj = crow[j];
+    double la[TI], lb[TJ];
+#pragma unroll
+    for (int a = 0; a < TI; ++a) la[a] = crow[ty + 16 * a];
+#pragma unroll
+    for (int b = 0; b < TJ; ++b) lb[b] = crow[tx + 32 * b];
+    const double lmine = crow[min(tid, NP - 1)];             // threads < 128: their own row's coefficient
     if (ty == (j & 15)) {                                      // row j of A sits in these threads, register j / 16
       double* qr = sh.qrow + tx * CW;
 #define KS_ROW(k) case k: if constexpr (k < TI) { _Pragma("unroll") for (int c = 0; c < CW; ++c) qr[c] = areg[k][c]; } break;
       switch (j >> 4) { KS_ROW(0) KS_ROW(1) KS_ROW(2) KS_ROW(3) KS_ROW(4) KS_ROW(5) KS_ROW(6) KS_ROW(7) default: break; }
 #undef KS_ROW
     }
+    if (!(xjj > thr2)) break;                                  // the largest remaining norm is at the rank threshold
     lds_barrier();
-    if (s == 2) KS_STAMP(6);
-    const double inv = rsqrt(fmax(sh.xcol[j], 1e-300));        // 1 / remaining norm of row j
-    double la[TI];
+    const double inv = rsqrt(xjj);                             // 1 / remaining norm of row j
 #pragma unroll
-    for (int a = 0; a < TI; ++a) la[a] = sh.xcol[ty + 16 * a] * inv;      // <row, new direction>
+    for (int a = 0; a < TI; ++a) la[a] *= inv;                 // <row, new direction>
     {
       double q[CW];
 #pragma unroll
@@ -250,23 +255,19 @@ __device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id,
         else *(float2*)o = make_float2((float)q[0], (float)q[1]);
       }
     }
-    if (s == 2) KS_STAMP(7);
 #pragma unroll
     for (int b = 0; b < TJ; ++b) {
-      const double lb = sh.xcol[tx + 32 * b] * inv;
+      const double lbs = lb[b] * inv;
 #pragma unroll
-      for (int a = 0; a < TI; ++a) cown[16 * a * NP + 32 * b] = fma(-la[a], lb, cown[16 * a * NP + 32 * b]);
+      for (int a = 0; a < TI; ++a) cown[16 * a * NP + 32 * b] = fma(-la[a], lbs, cown[16 * a * NP + 32 * b]);
     }
-    if (s == 2) KS_STAMP(8);
     if (tid < 128) {
-      const double l = sh.xcol[tid] * inv;
+      const double l = lmine * inv;
       if (tid == j) used = true;
       if (!used) dg -= l * l;
     }
     publish((s + 1) & 1);
-    if (s == 2) KS_STAMP(9);
     lds_barrier();
-    if (s == 2) KS_STAMP(10);
     r = s + 1;
   }
   __syncthreads();
