@@ -223,8 +223,12 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
   OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
   // the gather also leaves the sums of squares of the retained V rows for the full-rank certificate
   double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
+  // small budgets: the bases of the retained spans start now on a second stream, beside the gather
+  bool basis_started = false;
+  OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
   OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part));
-  OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part));
+  OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
+                          basis_started));
   return OBF_OK;
 }
 

@@ -748,10 +748,38 @@ static SideStream* side_stream() {
   return &ctx[nctx++];
 }
 
+// True when the basis of the retained span may be computed beside the gather and the statistics pass: with every
+// budget below the head dimension each head with deleted rows is active whatever its basis turns out to be.
+static bool basis_overlaps(const Dims& m, int32_t max_budget, int32_t rank) { return rank > 0 && max_budget < m.d; }
+
+// Forks a second stream off `st` and computes the bases there.  *started tells the caller to pass basis_started
+// to launch_backfill, which joins the second stream back before the finalisation.
+obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
+                                   const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
+                                   hipStream_t st, bool* started) {
+  *started = false;
+  if (!basis_overlaps(m, max_budget, rank)) return OBF_OK;
+  SideStream* side = side_stream();
+  if (!side) return OBF_OK;                                      // no second stream: the caller's stream does it all
+  HeadState* state = (HeadState*)(ws + w.head_state);
+  float* basis = (float*)(ws + w.basis);
+  if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
+    set_error("backfill: forking the side stream failed");
+    return OBF_ERR_HIP;
+  }
+  {
+    ProfScope prof_(ST_KEEP_BASIS, side->stream);
+    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, side->stream) != OBF_OK) return OBF_ERR_HIP;
+  }
+  if (hipEventRecord(side->join, side->stream) != hipSuccess) { set_error("backfill: side stream record failed"); return OBF_ERR_HIP; }
+  *started = true;
+  return OBF_OK;
+}
+
 template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
-                        float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part) {
+                        float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part, bool basis_started) {
   HeadState* state = (HeadState*)(ws + w.head_state);
   float* basis = (float*)(ws + w.basis);
   float* gram_part = (float*)(ws + w.gram_part);
@@ -763,36 +791,28 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     attr_done = true;
   }
-  const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
-  int32_t* decided = nullptr;
-  if (keep_cert_supported(m)) {
-    decided = (int32_t*)(ws + w.decided);
-    if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part) != OBF_OK)
-      return OBF_ERR_HIP;
+  if (!basis_started) {
+    // the caller did not start the bases earlier: try here (beside the statistics pass only)
+    if (launch_backfill_basis(m, w, ws, V, scores, idx, n_keep, max_budget, rank, st, &basis_started) != OBF_OK) return OBF_ERR_HIP;
   }
-  // With every budget below the head dimension each head with deleted rows is active whatever its basis turns
-  // out to be, so the streaming statistics pass does not wait for the basis: the two run side by side, the
-  // basis on a second stream that forks from and joins back into the caller's stream.
-  SideStream* side = (rank > 0 && max_budget < m.d) ? side_stream() : nullptr;
-  hipStream_t sb = st;
-  if (side) {
-    if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
-      set_error("backfill: forking the side stream failed");
-      return OBF_ERR_HIP;
+  if (!basis_started) {
+    const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
+    int32_t* decided = nullptr;
+    if (keep_cert_supported(m)) {
+      decided = (int32_t*)(ws + w.decided);
+      if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part) != OBF_OK)
+        return OBF_ERR_HIP;
     }
-    sb = side->stream;
-  }
-  {
-    ProfScope prof_(ST_KEEP_BASIS, sb);
-    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, sb) != OBF_OK) return OBF_ERR_HIP;
+    ProfScope prof_(ST_KEEP_BASIS, st);
+    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
     if (max_budget > m.d) {
-      hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, sb, (const T*)V, scores, idx, n_keep,
+      hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
                          m.N, m.d, max_budget, rank, state, basis, decided);
       if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
     }
   }
-  if (side && hipEventRecord(side->join, sb) != hipSuccess) { set_error("backfill: side stream record failed"); return OBF_ERR_HIP; }
-  const int32_t* nk_stats = side ? n_keep : nullptr;
+  // while the bases are still being written on the second stream the statistics pass must not read the head states
+  const int32_t* nk_stats = basis_started ? n_keep : nullptr;
   if (rank > 0 && del_stats_mfma_supported(m)) {
     if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, nk_stats, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
   } else if (rank > 0) {
@@ -800,7 +820,10 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
                        (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, nk_stats, gram_part); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
-  if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) { set_error("backfill: joining the side stream failed"); return OBF_ERR_HIP; }
+  if (basis_started) {
+    SideStream* side = side_stream();
+    if (!side || hipStreamWaitEvent(st, side->join, 0) != hipSuccess) { set_error("backfill: joining the side stream failed"); return OBF_ERR_HIP; }
+  }
   {
     ProfScope prof_(ST_FINALIZE, st);
     const size_t one = sizeof(float) * m.d * (m.d + 1);
@@ -816,10 +839,11 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
 
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part) {
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part,
+                             bool basis_started) {
   if (m.dtype == OBF_BF16)
-    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part);
-  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part);
+    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started);
+  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started);
 }
 
 }  // namespace obf

@@ -174,9 +174,15 @@ bool keep_cert_supported(const Dims& m);
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
                               int32_t* decided, hipStream_t st, const double* fro_part = nullptr);
+// Optional early start of the retained-span bases on a second stream (forked from st), for shapes where they
+// do not depend on the gather; *started is then passed on to launch_backfill as basis_started.
+obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
+                                   const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
+                                   hipStream_t st, bool* started);
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
                              void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st,
-                             const double* fro_part = nullptr);
+                             const double* fro_part = nullptr,
+                             bool basis_started = false);
 
 }  // namespace obf
