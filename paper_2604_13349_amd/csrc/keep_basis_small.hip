@@ -99,7 +99,7 @@ __device__ __forceinline__ void ks_stage_rows(const T* __restrict__ Vh, const in
 // One head.  TI = ceil(n / 16) rounded up to even, CW = d / 32.  Returns r.
 // C is stored padded to NP = 16 TI rows and columns (zero beyond n), so that every index below is an immediate.
 template <typename T, int TI, int CW>
-__device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id, int n, float* __restrict__ bh,
+__device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id, int n, float* __restrict__ bh,
                        double* C, KsShared& sh) {
   constexpr int d = 32 * CW;
   constexpr int TJ = TI / 2;                                   // column blocks of 32 of a thread's C elements
@@ -274,16 +274,16 @@ __device__ int ks_head(const T* __restrict__ Vh, const int32_t* __restrict__ id,
   return r;
 }
 
-template <typename T>
-__global__ __launch_bounds__(KS_THREADS, 4) void k_bf_keep_basis_small(const T* __restrict__ V, const float* __restrict__ scores,
+template <typename T, bool BIG>
+__global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small(const T* __restrict__ V, const float* __restrict__ scores,
                                                                     const int32_t* __restrict__ idx,
                                                                     const int32_t* __restrict__ n_keep, int N, int d,
                                                                     int max_budget, int rank, HeadState* __restrict__ state,
-                                                                    float* __restrict__ basis, int big) {
+                                                                    float* __restrict__ basis) {
   const int head = blockIdx.x;
   const int n = n_keep[head];
   if (n > d) return;                         // heads of the general kernel
-  if ((n > 96) != (big != 0)) return;        // the launch for n > 96 carries the larger LDS buffer
+  if ((n > 96) != BIG) return;               // n > 96: larger LDS buffer and register budget, a launch of its own
   extern __shared__ double Cs[];             // [n][n] Gram matrix (first the staging area of its accumulation)
   __shared__ KsShared sh;
   const int n_del = N - n;
@@ -306,11 +306,12 @@ __global__ __launch_bounds__(KS_THREADS, 4) void k_bf_keep_basis_small(const T* 
   int r_keep = 0, active = 0;
   if (rank > 0 && n > 0 && n_del > 0) {
     float* bh = basis + (size_t)head * d * d;
-    if (d == 128) {
+    if constexpr (BIG) {
+      r_keep = ks_head<T, 8, 4>(Vh, id, n, bh, Cs, sh);        // n > 96 implies d = 128
+    } else if (d == 128) {
       if (n <= 32) r_keep = ks_head<T, 2, 4>(Vh, id, n, bh, Cs, sh);
       else if (n <= 64) r_keep = ks_head<T, 4, 4>(Vh, id, n, bh, Cs, sh);
-      else if (n <= 96) r_keep = ks_head<T, 6, 4>(Vh, id, n, bh, Cs, sh);
-      else r_keep = ks_head<T, 8, 4>(Vh, id, n, bh, Cs, sh);
+      else r_keep = ks_head<T, 6, 4>(Vh, id, n, bh, Cs, sh);
     } else {
       if (n <= 32) r_keep = ks_head<T, 2, 2>(Vh, id, n, bh, Cs, sh);
       else r_keep = ks_head<T, 4, 2>(Vh, id, n, bh, Cs, sh);
@@ -338,16 +339,17 @@ static obf_status_t run_small(const Dims& m, const void* V, const float* scores,
                               hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
+    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 129 * 4);
+    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     attr_done = true;
   }
   const size_t nmax = (size_t)min(max_budget, m.d);
-  hipLaunchKernelGGL(k_bf_keep_basis_small<T>, dim3(m.heads), dim3(KS_THREADS), ks_smem(min(nmax, (size_t)96), m.d), st,
-                     (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis, 0);
+  hipLaunchKernelGGL((k_bf_keep_basis_small<T, false>), dim3(m.heads), dim3(KS_THREADS), ks_smem(min(nmax, (size_t)96), m.d), st,
+                     (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis);
   if (check_launch("backfill keep_basis_small") != OBF_OK) return OBF_ERR_HIP;
   if (nmax > 96) {
-    hipLaunchKernelGGL(k_bf_keep_basis_small<T>, dim3(m.heads), dim3(KS_THREADS), ks_smem(nmax, m.d), st,
-                       (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis, 1);
+    hipLaunchKernelGGL((k_bf_keep_basis_small<T, true>), dim3(m.heads), dim3(KS_THREADS), ks_smem(nmax, m.d), st,
+                       (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis);
     if (check_launch("backfill keep_basis_small (wide)") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;
