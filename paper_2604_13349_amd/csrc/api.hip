@@ -227,8 +227,10 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
   bool basis_started = false;
   OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
   OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part));
+  int32_t min_budget = budget;
+  if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < m.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
   OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
-                          basis_started));
+                          basis_started, min_budget));
   return OBF_OK;
 }
 

@@ -15,6 +15,11 @@
 
 namespace obf {
 
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// Workgroup barrier that orders LDS traffic only (global stores still in flight are not waited for).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 constexpr int KB_THREADS = 256;
 constexpr int KB_WAVES = KB_THREADS / 64;
 constexpr double kRankEps = 1.1920928955078125e-07;   // 2^-23, the rank rule's epsilon
@@ -364,7 +369,6 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
 constexpr int FN_THREADS = 1024;
 constexpr int FN_WAVES = FN_THREADS / 64;
 constexpr int FN_SWEEPS = 12;
-constexpr int FN_TPT = (128 * 128) / FN_THREADS;   // entries of the reduced Gram matrix per thread, at most
 
 template <typename T>
 __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int nstat, int rank,
@@ -386,9 +390,8 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   __shared__ float fred[FN_WAVES];
   __shared__ int s_k;
   __shared__ float s_off;
-  __shared__ float pdiag[128];
+  __shared__ __attribute__((aligned(16))) float xcol[128];
   __shared__ uint32_t wkey[2][2];
-  __shared__ int piv[128];
   HeadState st = state[head];
   int skipped = 1;
   float rcr = 0.f, ivn = 0.f;
@@ -434,126 +437,156 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
 #pragma unroll 8
     for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + d];
 
+    __syncthreads();                                           // G is in global scratch for every thread of the workgroup
     BF_STAMP(1, 1);
-    // P = I - Q^T Q (projector onto the complement of the retained span, Eq. 3), 4 x 4 tiles per thread
-    const int q4 = d >> 2;
-    for (int e = tid; e < q4 * q4; e += FN_THREADS) {
-      const int a0 = (e / q4) << 2, b0 = (e % q4) << 2;
-      float acc[4][4];
-      for (int x = 0; x < 4; ++x) for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
-#pragma unroll 8
-      for (int i = 0; i < r; ++i) {
-        const float4 qa = *(const float4*)(Qb + (size_t)i * d + a0);
-        const float4 qb = *(const float4*)(Qb + (size_t)i * d + b0);
-        const float av[4] = {qa.x, qa.y, qa.z, qa.w}, bv[4] = {qb.x, qb.y, qb.z, qb.w};
-        for (int x = 0; x < 4; ++x) for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(av[x], bv[y], acc[x][y]);
+    // P = I - Q^T Q (projector onto the complement of the retained span, Eq. 3) on the matrix cores: wave (rb, cb)
+    // holds the 32 x 32 tile of P in 16 registers per lane, entry i of lane l being
+    // P[rb*32 + (i/4)*8 + (l/32)*4 + i%4][cb*32 + l%32].
+    const int lane = tid & 63, l31 = lane & 31, lh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int TD = d >> 5;
+    const bool ptile = wave < TD * TD;
+    const int rb = wave / TD, cb = wave % TD;
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    if (ptile) {
+      const float* qa = Qb + rb * 32 + l31;
+      const float* qb = Qb + cb * 32 + l31;
+      for (int k0 = 0; k0 < r; k0 += 16) {                      // eight operand pairs in flight per group
+        float av[8], bv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int k = k0 + 2 * u + lh;
+          const size_t o = (size_t)min(k, r - 1) * d;
+          av[u] = qa[o]; bv[u] = qb[o];
+          if (k >= r) { av[u] = 0.f; bv[u] = 0.f; }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], acc, 0, 0, 0);
       }
-      for (int x = 0; x < 4; ++x)
-        for (int y = 0; y < 4; ++y) U[(a0 + x) * ld + b0 + y] = ((a0 + x == b0 + y) ? 1.f : 0.f) - acc[x][y];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), col = cb * 32 + l31;
+        acc[i] = ((row == col) ? 1.f : 0.f) - acc[i];
+        if (row == col) xcol[row] = acc[i];
+      }
     }
     __syncthreads();
 
     BF_STAMP(1, 2);
-    // Diagonally pivoted Cholesky of P, left-looking: a projector of rank m factors as P = Z^T Z with the
-    // m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  Row s of Z overwrites
-    // row piv[s] of P, which is never read again (only rows of pivots still to come are).
-    float dg = -1.f;
+    // Diagonally pivoted Cholesky of P, right-looking on the register tiles: a projector of rank m factors as
+    // P = Z^T Z with the m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  Step s takes
+    // the column with the largest remaining diagonal, scales it into row s of Z (LDS) and deflates P by it.
+    float dg = (tid < d) ? xcol[tid] : -1.f;
     bool used = false;
-    const int lane = tid & 63;
-    int pivlo = 0, pivhi = 0;                                  // lane t holds piv[t] / piv[64 + t]
-    if (tid < d) { dg = U[tid * ld + tid]; pdiag[tid] = dg; }
     auto publish = [&](int buf) {                              // wave maxima of (remaining diagonal, lowest index first)
       if (tid < 128) {
-        uint32_t key = (!used && tid < d && dg > 0.f) ? ((__float_as_uint(dg) & ~0x7Fu) | (uint32_t)(127 - tid)) : 0u;
+        uint32_t key = (!used && dg > 0.f) ? ((__float_as_uint(dg) & ~0x7Fu) | (uint32_t)(127 - tid)) : 0u;
         key = wave_max_u32(key);
         if (lane == 0) wkey[buf][tid >> 6] = key;
       }
     };
-    auto pivot_of = [&](const int t) {
-      return t < 64 ? __builtin_amdgcn_readlane(pivlo, t) : __builtin_amdgcn_readlane(pivhi, t - 64);
-    };
+    __syncthreads();
     publish(0);
     __syncthreads();
     for (int s = 0; s < m; ++s) {
       const uint32_t key = max(wkey[s & 1][0], wkey[s & 1][1]);
+      if (key == 0u) { m = s; break; }
       const int j = 127 - (int)(key & 0x7Fu);
-      const float pv = __uint_as_float(key & ~0x7Fu);
-      if (!(pv > 1e-5f)) { m = s; break; }                       // cannot happen for an exact projector of rank m
+      if (ptile && cb == (j >> 5) && l31 == (j & 31)) {         // column j of P sits in these lanes
+#pragma unroll
+        for (int i = 0; i < 16; ++i) xcol[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
+      }
+      lds_barrier();
+      const float xjj = xcol[j];
+      if (!(xjj > 1e-5f)) { m = s; break; }                      // cannot happen for an exact projector of rank m
+      const float inv = rsqrtf(xjj);
+      if (ptile) {
+        const float lc = xcol[cb * 32 + l31] * inv;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 lr = *(const float4*)&xcol[rb * 32 + i4 * 8 + lh * 4];
+          acc[4 * i4 + 0] = fmaf(-lr.x * inv, lc, acc[4 * i4 + 0]);
+          acc[4 * i4 + 1] = fmaf(-lr.y * inv, lc, acc[4 * i4 + 1]);
+          acc[4 * i4 + 2] = fmaf(-lr.z * inv, lc, acc[4 * i4 + 2]);
+          acc[4 * i4 + 3] = fmaf(-lr.w * inv, lc, acc[4 * i4 + 3]);
+        }
+      }
       if (tid < d) {
-        float x = U[j * ld + tid], xj = pdiag[j];
-        int t = 0;
-        for (; t + 8 <= s; t += 8) {
-          float zj[8], v[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) { const float* zt = U + pivot_of(t + u) * ld; zj[u] = zt[j]; v[u] = zt[tid]; }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) { x = fmaf(-v[u], zj[u], x); xj = fmaf(-zj[u], zj[u], xj); }
-        }
-        {
-          float zj[8], v[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) { const float* zt = U + pivot_of(min(t + u, max(s - 1, 0))) * ld; zj[u] = zt[j]; v[u] = zt[tid]; }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) if (t + u < s) { x = fmaf(-v[u], zj[u], x); xj = fmaf(-zj[u], zj[u], xj); }   // xj: the pivot, same arithmetic in every thread
-        }
-        const float l = used ? 0.f : x * rsqrtf(fmaxf(xj, 1e-12f));
-        U[j * ld + tid] = l;
+        const float l = used ? 0.f : xcol[tid] * inv;            // rows already taken are zero in exact arithmetic
+        U[s * ld + tid] = l;                                     // row s of Z
         if (tid == j) used = true;
         if (!used) dg -= l * l;
-        if (tid == 0) piv[s] = j;
       }
-      if (s < 64) { if (lane == s) pivlo = j; } else { if (lane == s - 64) pivhi = j; }
       publish((s + 1) & 1);
-      __syncthreads();
+      lds_barrier();
     }
     __syncthreads();
 
     BF_STAMP(1, 3);
-    // Z to global scratch (compact rows), Y = Z G
-    for (int e = tid; e < m * d; e += FN_THREADS) Zg[e] = U[piv[e / d] * ld + (e % d)];
-    const int sg = (m + 3) >> 2;
-    for (int e = tid; e < sg * d; e += FN_THREADS) {
-      const int s0 = (e / d) << 2, b = e % d;
-      const float* z0 = U + piv[min(s0, m - 1)] * ld;
-      const float* z1 = U + piv[min(s0 + 1, m - 1)] * ld;
-      const float* z2 = U + piv[min(s0 + 2, m - 1)] * ld;
-      const float* z3 = U + piv[min(s0 + 3, m - 1)] * ld;
-      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 8
-      for (int c = 0; c < d; ++c) {
-        const float g = Gg[c * d + b];
-        a0 = fmaf(z0[c], g, a0); a1 = fmaf(z1[c], g, a1); a2 = fmaf(z2[c], g, a2); a3 = fmaf(z3[c], g, a3);
+    // Z to global scratch (for the last phase), X = G Z^T (d x m) and T = Z X (m x m) on the matrix cores.
+    // T is the residual Gram matrix R^T R = P G P restricted to the complement; its eigenpairs (lambda, w) give
+    // those of P G P as (lambda, Z^T w).
+    for (int e = tid; e < m * d; e += FN_THREADS) Zg[e] = U[(e / d) * ld + (e % d)];
+    const int MB = (m + 31) >> 5, MP = MB << 5;
+    float* Xg = Yg;                                              // [d][MP]
+    if (wave < TD * MB) {
+      const int cblk = wave / MB, tblk = wave % MB;
+      const int t = tblk * 32 + l31;
+      const float* ga = Gg + cblk * 32 + l31;                    // G symmetric: G[c][b] read as G[b][c], coalesced
+      const float* zb = U + min(t, m - 1) * ld;
+      f32x16 xa;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) xa[i] = 0.f;
+      for (int k0 = 0; k0 < d; k0 += 16) {
+        float av[8], bv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int k = k0 + 2 * u + lh;
+          av[u] = ga[(size_t)k * d];
+          bv[u] = (t < m) ? zb[k] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) xa = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], xa, 0, 0, 0);
       }
-      Yg[(size_t)s0 * d + b] = a0;
-      if (s0 + 1 < m) Yg[(size_t)(s0 + 1) * d + b] = a1;
-      if (s0 + 2 < m) Yg[(size_t)(s0 + 2) * d + b] = a2;
-      if (s0 + 3 < m) Yg[(size_t)(s0 + 3) * d + b] = a3;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) Xg[(size_t)(cblk * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)) * MP + t] = xa[i];
     }
     __syncthreads();
     BF_STAMP(1, 4);
-    // T = Y Z^T = Z G Z^T (m x m): the residual Gram matrix R^T R = P G P restricted to the complement,
-    // whose eigenpairs (lambda, w) give those of P G P as (lambda, Z^T w).  Stored over Z, padded to even size.
     const int mm = m + (m & 1);
     const int lt = mm + 1;
-    float tacc[FN_TPT];
-    for (int k = 0, e = tid; k < FN_TPT; ++k, e += FN_THREADS) {
-      float acc = 0.f;
-      if (e < m * m) {
-        const int s = e / m, t = e - s * m;
-        const float* zt = U + piv[t] * ld;
-        const float* yr = Yg + (size_t)s * d;
-        for (int c = 0; c < d; c += 4) {
-          const float4 y4 = *(const float4*)(yr + c);
-          acc = fmaf(y4.x, zt[c], acc); acc = fmaf(y4.y, zt[c + 1], acc);
-          acc = fmaf(y4.z, zt[c + 2], acc); acc = fmaf(y4.w, zt[c + 3], acc);
+    f32x16 ta;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ta[i] = 0.f;
+    const bool ttile = wave < MB * MB;
+    const int sblk = wave / max(MB, 1), tblk2 = wave % max(MB, 1);
+    if (ttile) {
+      const int srow = sblk * 32 + l31;
+      const float* za = U + min(srow, m - 1) * ld;
+      const float* xb = Xg + tblk2 * 32 + l31;
+      for (int k0 = 0; k0 < d; k0 += 16) {
+        float av[8], bv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int k = k0 + 2 * u + lh;
+          av[u] = (srow < m) ? za[k] : 0.f;
+          bv[u] = xb[(size_t)k * MP];
         }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ta = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], ta, 0, 0, 0);
       }
-      tacc[k] = acc;
     }
     __syncthreads();                                             // Z (in LDS) is dead from here on
     U = (2 * mm * lt <= d * ld) ? sm + mm * lt : sm + d * ld;    // W next to T, or in the second buffer of the large launch
-    for (int k = 0, e = tid; k < FN_TPT; ++k, e += FN_THREADS)
-      if (e < m * m) M[(e / m) * lt + (e % m)] = tacc[k];
+    if (ttile) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int srow = sblk * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), t = tblk2 * 32 + l31;
+        if (srow < m && t < m) M[srow * lt + t] = ta[i];
+      }
+    }
     if (mm > m) for (int e = tid; e < mm; e += FN_THREADS) { M[m * lt + e] = 0.f; M[e * lt + m] = 0.f; }
     __syncthreads();
     // symmetrise, W = I, trace
@@ -573,6 +606,17 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     if (!negligible) {
       // cyclic Jacobi with a round-robin ordering: mm/2 disjoint rotations per round
       const int half = mm / 2;
+      auto rot_of = [&](const float* A, const int p, const int q, float& c, float& s) {
+        const float app = A[p * lt + p], aqq = A[q * lt + q], apq = A[p * lt + q];
+        c = 1.f; s = 0.f;
+        // single-instruction reciprocal / square roots (1 ulp): the rotation only has to be orthogonal to rounding
+        if (fabsf(apq) > 1e-30f && fabsf(apq) > 1e-9f * __builtin_amdgcn_sqrtf(fabsf(app * aqq)) ) {
+          const float tau = (aqq - app) * __builtin_amdgcn_rcpf(2.f * apq);
+          const float t = copysignf(__builtin_amdgcn_rcpf(fabsf(tau) + __builtin_amdgcn_sqrtf(fmaf(tau, tau, 1.f))), tau);
+          c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f));
+          s = t * c;
+        }
+      };
       for (int sweep = 0; sweep < FN_SWEEPS && mm > 1; ++sweep) {
         for (int round = 0; round < mm - 1; ++round) {
           if (tid < half) {
@@ -580,14 +624,8 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             if (tid == 0) { p = mm - 1; q = round; }
             else { p = (round + tid) % (mm - 1); q = (round - tid + (mm - 1)) % (mm - 1); }
             if (p > q) { const int t = p; p = q; q = t; }
-            const float app = M[p * lt + p], aqq = M[q * lt + q], apq = M[p * lt + q];
-            float c = 1.f, s = 0.f;
-            if (fabsf(apq) > 1e-30f && fabsf(apq) > 1e-9f * sqrtf(fabsf(app * aqq)) ) {
-              const float tau = (aqq - app) / (2.f * apq);
-              const float t = ((tau >= 0.f) ? 1.f : -1.f) / (fabsf(tau) + sqrtf(1.f + tau * tau));
-              c = 1.f / sqrtf(1.f + t * t);
-              s = t * c;
-            }
+            float c, s;
+            rot_of(M, p, q, c, s);
             pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
           }
           __syncthreads();
@@ -779,7 +817,8 @@ obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, 
 template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
-                        float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part, bool basis_started) {
+                        float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part, bool basis_started,
+                        int32_t min_budget) {
   HeadState* state = (HeadState*)(ws + w.head_state);
   float* basis = (float*)(ws + w.basis);
   float* gram_part = (float*)(ws + w.gram_part);
@@ -804,7 +843,9 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
         return OBF_ERR_HIP;
     }
     ProfScope prof_(ST_KEEP_BASIS, st);
-    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
+    // heads with at most d retained rows (none when the caller states that every budget is above d)
+    if (!(min_budget > m.d && m.N > m.d) &&
+        launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
     if (max_budget > m.d) {
       hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
                          m.N, m.d, max_budget, rank, state, basis, decided);
@@ -840,10 +881,10 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
                              void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part,
-                             bool basis_started) {
+                             bool basis_started, int32_t min_budget) {
   if (m.dtype == OBF_BF16)
-    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started);
-  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started);
+    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget);
+  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget);
 }
 
 }  // namespace obf

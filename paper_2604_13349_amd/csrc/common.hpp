@@ -183,6 +183,6 @@ obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const 
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
                              void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st,
                              const double* fro_part = nullptr,
-                             bool basis_started = false);
+                             bool basis_started = false, int32_t min_budget = -1 /*smallest per-head budget if known*/);
 
 }  // namespace obf
