@@ -3,13 +3,19 @@
 //   keep_basis : per head, demand sums (Eq. 6), dimension r and an orthonormal basis Q of the span of
 //                the retained values (Eq. 2).  r == d means the orthogonal complement is {0}: the
 //                residual of Eq. 3 vanishes identically and the head is left as plain eviction.
+//                Three kernels share the heads: the full-rank certificate (keep_cert.hip, n > d), the
+//                small-budget kernel (keep_basis_small.hip, n <= d) and k_bf_keep_basis below (n > d, not
+//                certified).
 //   del_stats  : for heads that still need it, one streaming pass over V accumulating the Gram
-//                matrix V_del^T V_del, the mass-weighted sum of deleted values and ||V_del||_F^2.
+//                matrix V_del^T V_del, the mass-weighted sum of deleted values and ||V_del||_F^2
+//                (del_stats_mfma.hip for bf16 head_dim-128 caches, k_bf_del_stats below otherwise).
 //                R itself (Eq. 3) is never materialised: R^T R = P (V_del^T V_del) P and
 //                sum_j w_j R_j = P sum_j w_j V_j with P = I - Q Q^T.
-//   finalize   : per head, P G P, its leading eigenvectors C (the top right singular vectors of R,
-//                App. H: same subspace as the SVD of R), rbar (Eq. 4), Delta (Eq. 5), delta (Eq. 6).
-//   inject     : V* = V_keep + delta on every retained row (Eq. 7), rounded once to the I/O dtype.
+//   finalize   : per head, an orthonormal basis Z of the complement of the retained span, the eigenpairs of
+//                Z G Z^T (those of P G P, i.e. the top right singular vectors of R; App. H: same subspace as
+//                the SVD of R), rbar (Eq. 4), Delta (Eq. 5), delta (Eq. 6), and V* = V_keep + delta on every
+//                retained row (Eq. 7), rounded once to the I/O dtype.
+// The basis kernels may run on a second stream beside the gather and the statistics pass (small budgets).
 #include "common.hpp"
 #include "wave_ops.hpp"
 

@@ -157,11 +157,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   put(pre[0], 0);
   fetch(pre[0], 2 * KC_TILE);
   __syncthreads();
-#ifdef KC_SKIP_GRAM
-  for (int r0 = 0; r0 < 0; r0 += 2 * KC_TILE) {
-#else
   for (int r0 = 0; r0 < rows; r0 += 2 * KC_TILE) {
-#endif
     // even tile: in stage[0]; pre[1] holds tile r0+64, pre[0] holds tile r0+128
     compute(stage[0]);
     put(pre[1], 1);
@@ -266,11 +262,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   KC_STAMP(3);
   if (tid == 0) s_bad = 0;
   publish(0);
-#ifdef KC_SKIP_LDL
-  for (int k = 0; k < 0; k += 4) {
-#else
   for (int k = 0; k < KC_D; k += 4) {
-#endif
     __syncthreads();                                   // this panel visible; ypan / lpan free again
     if (tid < KC_D) {
       const float4* pr = (const float4*)&panel[(k >> 2) & 1][0][0];

@@ -2,9 +2,9 @@
 // (v_mfma_f32_32x32x16_bf16), head_dim 128.
 //
 // A column sum of softmax rows needs every row's normaliser before any column can be summed, so
-// K is streamed twice: pass A gives each query row's (max, sum-exp) over a chunk of tokens, a
-// small kernel folds the chunks into log-sum-exp, pass B recomputes the logits and sums
-// exp(logit - lse[row]) over the rows.  Both passes use the same register fragments of Q and K:
+// K is streamed twice: pass A gives each query row's (max, sum-exp) over each contiguous range of
+// tokens a workgroup walks, pass B first folds the ranges of its head into the rows' log-sum-exp
+// (in its prologue), then recomputes the logits and sums exp(logit - lse[row]) over the rows.  Both passes use the same register fragments of Q and K:
 // an MFMA operand fragment holds, for lane l, 8 consecutive head_dim entries (l/32)*8.. of
 // row l%32, for either operand, so swapping the two operands transposes the 32x32 output tile.
 //   pass A computes (tokens x query rows): a lane then owns ONE query row per row block, and the
@@ -46,11 +46,7 @@ __device__ __forceinline__ void load_q(Frag (&qf)[SM_RB][SM_KK], const uint16_t*
 }
 
 __device__ __forceinline__ void load_k(Frag (&kf)[SM_KK], const uint16_t* __restrict__ Kh, int tok0, int t_end, int lane) {
-#ifdef SM_NO_LOAD
-  const int t = min((tok0 & 127) + (lane & 31), t_end - 1), kh = (lane >> 5) * 8;   // experiment: stay in cache
-#else
   const int t = min(tok0 + (lane & 31), t_end - 1), kh = (lane >> 5) * 8;
-#endif
   const uint4* p = (const uint4*)(Kh + (size_t)t * SM_D + kh);
 #pragma unroll
   for (int kk = 0; kk < SM_KK; ++kk) kf[kk].u = p[kk * 2];
@@ -143,12 +139,6 @@ struct MassEp {
   float c0, c1, c2, c3;
   template <int RB>
   __device__ __forceinline__ void block(const f32x16& acc, int tok) {
-#ifdef SM_NO_EPILOGUE
-    if (RB == 0) { c0 = 0.f; c1 = 0.f; c2 = 0.f; c3 = 0.f; }
-    c0 += acc[0] + acc[5] + acc[10] + acc[15];
-    if (RB == SM_RB - 1) { const int t = tok + (lane & 31); if (lane < 32 && t < t_end) dst[t] = c0; }
-    return;
-#endif
     if (RB == 0) { c0 = 0.f; c1 = 0.f; c2 = 0.f; c3 = 0.f; }
 #pragma unroll
     for (int i = 0; i < 16; i += 4) {
