@@ -35,8 +35,11 @@ constexpr float kEigFloor = 1.0e-6f;                  // resolution of the fp32 
 #ifdef BF_TRACE
 __device__ uint64_t g_bf_trace[512 * 12];
 #define BF_STAMP(w, k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_bf_trace[blockIdx.x * 12 + (k)] = wall_clock64(); } while (0)
+__device__ uint64_t g_kb_trace[512 * 12];
+#define KB_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_kb_trace[blockIdx.x * 12 + (k)] = wall_clock64(); } while (0)
 #else
 #define BF_STAMP(w, k) do { } while (0)
+#define KB_STAMP(k) do { } while (0)
 #endif
 
 // ------------------------------------------------------------------------------------------------
@@ -135,6 +138,66 @@ __device__ double sigma_max_est(const double* W, int m, int d, double* x /*[d]*/
   return sqrt(lam);
 }
 
+// Gram matrix V_keep^T V_keep (d x d, double) of the n retained rows into W (LDS, [d][d]); W doubles as the
+// staging area while the sums are in registers.  16 x 16 threads, BS x BS outputs each (d = 16 BS): thread (ty, tx) owns G[ty + 16a][tx + 16b].
+template <typename T, int BS>
+__device__ void gram_rows_f64(const T* __restrict__ Vh, const int32_t* __restrict__ id, int n, double* W) {
+  constexpr int D = 16 * BS;
+  constexpr int EPP = 16 / (int)sizeof(T);                     // elements per 16-byte piece
+  constexpr int PPR = D / EPP;                                 // pieces per row
+  constexpr int TR = KB_THREADS / PPR;                         // rows staged per step
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  double acc[BS][BS];
+#pragma unroll
+  for (int a = 0; a < BS; ++a)
+#pragma unroll
+    for (int b = 0; b < BS; ++b) acc[a][b] = 0.0;
+  float* rowbuf = (float*)W;                                   // [2][TR][D + 1]
+  const int pr = threadIdx.x / PPR, pc = threadIdx.x - pr * PPR;
+  auto fetch = [&](int i0) -> uint4 {
+    const int i = i0 + pr;
+    return (i < n) ? *(const uint4*)(Vh + (size_t)id[i] * D + pc * EPP) : make_uint4(0u, 0u, 0u, 0u);
+  };
+  auto put = [&](const uint4 q, int buf) {
+    float* o = rowbuf + (buf * TR + pr) * (D + 1) + pc * EPP;
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { o[2 * k] = __uint_as_float(w[k] << 16); o[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u); }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = __uint_as_float(w[k]);
+    }
+  };
+  uint4 nxt = fetch(0);
+  int buf = 0;
+  for (int i0 = 0; i0 < n; i0 += TR) {
+    put(nxt, buf);
+    nxt = fetch(i0 + TR);                                      // next rows are in flight during this step's sums
+    __syncthreads();
+    const float* rb = rowbuf + buf * TR * (D + 1);
+#pragma unroll 2
+    for (int i = 0; i < TR; ++i) {
+      double av[BS], bv[BS];
+#pragma unroll
+      for (int a = 0; a < BS; ++a) av[a] = (double)rb[i * (D + 1) + ty + 16 * a];
+#pragma unroll
+      for (int b = 0; b < BS; ++b) bv[b] = (double)rb[i * (D + 1) + tx + 16 * b];
+#pragma unroll
+      for (int a = 0; a < BS; ++a)
+#pragma unroll
+        for (int b = 0; b < BS; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
+    }
+    buf ^= 1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < BS; ++a)
+#pragma unroll
+    for (int b = 0; b < BS; ++b) W[(ty + 16 * a) * D + tx + 16 * b] = acc[a][b];
+  __syncthreads();
+}
+
 // ------------------------------------------------------------------------------------------------
 // keep_basis
 template <typename T>
@@ -181,30 +244,12 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       const double thr = smax * (double)max(n, d) * kRankEps;
       r_keep = pivoted_mgs(W, n, d, thr, red, ired);
     } else {
+      KB_STAMP(0);
       // n > d: Gram matrix of the retained rows in double (inputs are exact, products exact),
       // diagonally pivoted Cholesky for the rank, then the rows of the factor span the row space.
-      const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;     // 16 x 16 threads, (d/16)^2 outputs each
-      const int bs = d / 16;
-      double acc[8][8];
-      for (int a = 0; a < 8; ++a) for (int b = 0; b < 8; ++b) acc[a][b] = 0.0;
-      float* rowbuf = (float*)W;                                   // [16][d] staging (W is free until the end)
-      for (int i0 = 0; i0 < n; i0 += 16) {
-        __syncthreads();
-        for (int e = threadIdx.x; e < 16 * d; e += KB_THREADS) {
-          const int i = e / d, c = e - i * d;
-          rowbuf[e] = (i0 + i < n) ? Elem<T>::load(Vh + (size_t)id[i0 + i] * d + c) : 0.0f;
-        }
-        __syncthreads();
-        for (int i = 0; i < 16; ++i) {
-          double av[8], bv[8];
-          for (int a = 0; a < bs; ++a) av[a] = (double)rowbuf[i * d + ty * bs + a];
-          for (int b = 0; b < bs; ++b) bv[b] = (double)rowbuf[i * d + tx * bs + b];
-          for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
-        }
-      }
-      __syncthreads();
-      for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) W[(ty * bs + a) * d + tx * bs + b] = acc[a][b];
-      __syncthreads();
+      if (d == 128) gram_rows_f64<T, 8>(Vh, id, n, W);
+      else gram_rows_f64<T, 4>(Vh, id, n, W);
+      KB_STAMP(1);
       // sigma_max^2 = lambda_max(G): power iteration on G
       for (int c = threadIdx.x; c < d; c += KB_THREADS) xv[c] = 1.0 / sqrt((double)d) * (1.0 + 0.01 * (c % 7));
       __syncthreads();
@@ -224,6 +269,7 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       }
       const double smax = sqrt(lam);
       const double thr = smax * (double)max(n, d) * kRankEps;     // on singular values
+      KB_STAMP(2);
       // diagonally pivoted Cholesky, upper factor kept in the upper triangle (row k, columns >= k)
       for (int c = threadIdx.x; c < d; c += KB_THREADS) perm[c] = c;
       __syncthreads();
@@ -259,6 +305,7 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       }
       __syncthreads();
       r_keep = r;
+      KB_STAMP(3);
       if (r_keep < d) {
         // rows 0..r-1 of the factor (zero left of the diagonal), columns back in original order
         for (int e = threadIdx.x; e < d * d; e += KB_THREADS) {
@@ -896,6 +943,9 @@ obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const 
 }  // namespace obf
 
 #ifdef BF_TRACE
+extern "C" int obf_debug_copy_kb_trace(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_kb_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
 extern "C" int obf_debug_copy_bf_trace(void* host, size_t bytes) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_bf_trace), bytes, 0, hipMemcpyDeviceToHost);
 }
