@@ -214,6 +214,7 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
   __shared__ int ired[2];
   __shared__ double xv[128], yv[128];
   __shared__ int perm[128];
+  __shared__ uint64_t pkey[2];
   const int head = blockIdx.x;
   const int n = n_keep[head];
   const int n_del = N - n;
@@ -256,10 +257,16 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       double lam = 0.0;
       for (int it = 0; it < 24; ++it) {
         double part = 0.0;
-        for (int a = threadIdx.x; a < d; a += KB_THREADS) {
-          double s = 0.0;
-          for (int c = 0; c < d; ++c) s += W[a * d + c] * xv[c];
-          yv[a] = s; part += s * s;
+        if ((int)threadIdx.x < d) {                                // G symmetric: column reads, no bank conflicts
+          const double* col = W + threadIdx.x;
+          double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll 4
+          for (int c = 0; c < d; c += 4) {
+            s0 = fma(col[(c + 0) * d], xv[c + 0], s0); s1 = fma(col[(c + 1) * d], xv[c + 1], s1);
+            s2 = fma(col[(c + 2) * d], xv[c + 2], s2); s3 = fma(col[(c + 3) * d], xv[c + 3], s3);
+          }
+          const double s = (s0 + s1) + (s2 + s3);
+          yv[threadIdx.x] = s; part = s * s;
         }
         const double n2 = block_sum(part, red);
         lam = sqrt(n2);
@@ -275,14 +282,18 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       __syncthreads();
       int r = 0;
       for (int k = 0; k < d; ++k) {
-        if (threadIdx.x == 0) {
-          int p = k; double best = W[k * d + k];
-          for (int i = k + 1; i < d; ++i) if (W[i * d + i] > best) { best = W[i * d + i]; p = i; }
-          ired[0] = p; red[0] = best;
+        if (threadIdx.x < 128) {                                   // largest remaining diagonal entry, lowest index first
+          const int i = threadIdx.x;
+          const double dv = (i >= k && i < d) ? W[i * d + i] : 0.0;
+          uint64_t key = (dv > 0.0) ? ((((uint64_t)__double_as_longlong(dv)) & ~0x7FULL) | (uint64_t)(127 - i)) : 0ULL;
+          key = wave_max_u64(key);
+          if ((threadIdx.x & 63) == 0) pkey[threadIdx.x >> 6] = key;
         }
         __syncthreads();
-        const int p = ired[0];
-        const double piv = red[0];
+        const uint64_t key = pkey[0] > pkey[1] ? pkey[0] : pkey[1];
+        const int p = key ? 127 - (int)(key & 0x7F) : k;
+        const double piv = W[p * d + p];
+        __syncthreads();                                             // pkey is rewritten in the next step
         if (!(piv > 0.0) || !(sqrt(piv) > thr)) break;
         if (p != k) {   // symmetric swap of rows/columns p and k
           for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[k * d + c]; W[k * d + c] = W[p * d + c]; W[p * d + c] = t; }
