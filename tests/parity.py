@@ -40,6 +40,7 @@ class HeadReport:
         self.delta_err = 0.0
         self.ambiguous = False
         self.skipped = None
+        self.r_keep = None
 
 
 def gap_factor(diag) -> float:
@@ -89,6 +90,7 @@ def check_head(tag, ref: O.HeadResult, K_io, V_io, dtype, budget, gpu_idx, gpu_n
         rel = dg.res_sigma_rel
         rep.ambiguous |= bool(np.any((rel > dg.res_thr_rel / 10) & (rel < GPU_RES_FLOOR * 10)))
     rep.skipped = dg.skipped
+    rep.r_keep = dg.r_keep
     if gpu_diag is not None and not rep.ambiguous:
         assert int(gpu_diag["skipped"]) == dg.skipped, f"{tag}: skipped {gpu_diag['skipped']} vs oracle {dg.skipped}"
         if dg.r_keep > 0:

@@ -20,8 +20,10 @@ def gpu():
     return gpu_util
 
 
-def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None):
+def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None, edit=None):
     K, V, Q = si.make_cache(cfg, seed, threads=8)
+    if edit is not None:
+        edit(K, V, Q)                     # in-place change of the synthetic cache (still seeded, still no oracle data)
     bud = si.budgets(cfg, seed) if budgets is None else np.asarray(budgets, dtype=np.int32).reshape(cfg.n_layers, cfg.n_kv_heads)
     rank = cfg.rank if rank is None else rank
     out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=max_budget)
@@ -98,6 +100,36 @@ def test_paper_shape(gpu):
 def test_ragged_shapes(gpu, N, d, dtype, g, W, B, rank):
     cfg = si.RelayConfig("ragged", 7, 1, 2, g, d, N, W, B, rank, dtype, "structured", outlier_frac=0.01)
     _check_cfg(gpu, cfg)
+
+
+@pytest.mark.parametrize("d,dtype,budgets", [
+    (128, "bf16", [16, 33, 64, 96, 97, 112, 127, 128]),     # every tile width of the small-budget basis kernel, n == d,
+                                                            # complements wider than 90 (second finalisation launch)
+    (64, "f32", [8, 31, 33, 64]),                           # head_dim 64, fp32 I/O
+    (128, "f32", [20, 100, 120, 129]),                      # fp32 at head_dim 128, one head just above d
+])
+def test_small_budget_basis_variants(gpu, d, dtype, budgets):
+    cfg = si.RelayConfig("smallb", 11, 1, len(budgets), 2, d, 1500, 8, 0, 4, dtype, "structured", outlier_frac=0.01)
+    reps = _check_cfg(gpu, cfg, budgets=budgets, max_budget=max(budgets))
+    assert sum(r.skipped == 0 for r in reps) >= len(budgets) // 2
+
+
+@pytest.mark.parametrize("budget", [48, 300])
+def test_rank_deficient_retained_rows(gpu, budget):
+    """Values that repeat 24 distinct rows (plus a few free tokens): the retained span has rank far below both the
+    budget and head_dim, on the small-budget kernel (48 rows) and on the general one (300 rows)."""
+    cfg = si.RelayConfig("rankdef", 12, 1, 4, 2, 128, 1200, 8, budget, 4, "bf16", "structured")
+
+    def edit(K, V, Q):
+        N = V.shape[2]
+        free = np.arange(N) % 97 == 5                      # every 97th token keeps its own value row
+        for h in range(V.shape[1]):
+            rep = V[0, h, :24].copy()
+            tiled = rep[np.arange(N) % 24]
+            V[0, h] = np.where(free[:, None], V[0, h], tiled)
+
+    reps = _check_cfg(gpu, cfg, edit=edit)
+    assert all(r.r_keep < 128 for r in reps)
 
 
 def test_budget_edges_and_rank_zero(gpu):
