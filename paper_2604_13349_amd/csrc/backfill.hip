@@ -482,14 +482,21 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     float* Gg = Yg + (size_t)d * d;                            // [d][d] G summed over the chunk partials
 
     // G = sum of chunk partials (fixed order), u, ||V_del||^2
+    // only the 32 x 32 tiles on and below the diagonal of a partial are defined; the sum is mirrored
     for (int e = tid * 4; e < d * d; e += FN_THREADS * 4) {
+      const int row = e / d, col = e - row * d;
+      if ((row >> 5) < (col >> 5)) continue;
       float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 8
       for (int c = 0; c < nstat; ++c) {
         const float4 q = *(const float4*)(gp + c * pstride + e);
         s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
       }
-      *(float4*)(Gg + e) = s;                                  // read back (through L2) when Y = Z G is formed
+      *(float4*)(Gg + e) = s;                                  // read back (through L2) when X = G Z^T is formed
+      if ((row >> 5) > (col >> 5)) {
+        Gg[(col + 0) * d + row] = s.x; Gg[(col + 1) * d + row] = s.y;
+        Gg[(col + 2) * d + row] = s.z; Gg[(col + 3) * d + row] = s.w;
+      }
     }
     if (tid < d) {
       float s = 0.f;

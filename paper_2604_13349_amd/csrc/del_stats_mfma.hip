@@ -159,7 +159,8 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
     __syncthreads();
   }
 
-  // ---- results: the Gram, both triangles
+  // ---- results: the 32 x 32 tiles of the Gram matrix on and below the diagonal (row-major in the d x d partial, so
+  // the stores are row segments; the tiles above the diagonal are left unwritten, the reader mirrors)
   float* out = gram_part + ((size_t)head * nstat + chunk) * ((size_t)DM_D * DM_D + DM_D + 4);
 #pragma unroll
   for (int t = 0; t < 3; ++t) {
@@ -168,7 +169,6 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
       for (int i = 0; i < 16; ++i) {
         const int row = trb[t] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), col = tcb[t] * 32 + lr;
         out[row * DM_D + col] = acc[t][i];
-        if (trb[t] != tcb[t]) out[col * DM_D + row] = acc[t][i];
       }
     }
   }
