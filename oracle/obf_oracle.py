@@ -20,6 +20,8 @@ Readings taken where the paper leaves a choice (each is listed in the design not
   * rank(R) in k = min(pca_rank, rank R) uses the same rule.
   * "||R||_F negligible" (footnote of Eq. 7): ||R||_F^2 <= 1e-6 ||V_del||_F^2.
   * epsilon = 1e-12 exactly where Eq. 4 and Eq. 6 place it.
+The layerwise granularity of the same retention rule (one index set per layer) is
+compress_layer.
 Pinned by tests/test_oracle_pins.py (closed forms, brute force, invariants).
 Parity unpinned: absolute values on realistic caches (the paper prints no worked
 numeric example); those rest on invariants only.
@@ -255,6 +257,43 @@ def compress_relay(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budgets
         out[(l, h)] = compress_head(K_io[l, h], V_io[l, h], Q_io[l, h * group:(h + 1) * group],
                                     int(budgets[l, h]), rank, dtype)
     return out
+
+
+# ----------------------------------------------------------------------------- layerwise selector (Sec. 4.3.2)
+def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, rank: int,
+                   group: int, dtype: str):
+    """Layerwise granularity of the retention rule (Sec. 4.3.2; the "L" and "L-OBF" methods of Sec. 5):
+    one index set per layer, TopK_B of the attention mass summed over the layer's heads, shared by
+    all of them; Orthogonal BackFill then runs per head exactly as in the headwise case, with that
+    head's own attention mass in Eq. 4 and Eq. 6 and the shared index set.
+
+    K_io, V_io [H, N, d]; Q_io [H*group, W, d].  Returns (idx, [HeadResult per head]).
+    Reading: Eq. 1 is stated per attention head and the sum of the retention rule runs over all
+    heads of the layer; with grouped queries the per-KV-head mass already is the sum over the
+    group's query heads, so the layer sum is the sum of the per-KV-head masses.
+    """
+    H = K_io.shape[0]
+    d = K_io.shape[2]
+    masses = []
+    for h in range(H):
+        K = decode(K_io[h], dtype)
+        Qr = decode(Q_io[h * group:(h + 1) * group], dtype).reshape(-1, d)
+        masses.append(attention_mass(K, Qr))
+    layer_mass = np.zeros_like(masses[0])
+    for A in masses:                                        # plain left-to-right sum over the heads
+        layer_mass = layer_mass + A
+    idx = select_topk(layer_mass, budget)
+    heads = []
+    for h in range(H):
+        V = decode(V_io[h], dtype)
+        V_star, diag = backfill(V, masses[h], idx, rank)
+        if diag.skipped:
+            V_out = np.asarray(V_io[h])[idx].copy()
+        else:
+            V_out = round_to_io(V_star, dtype)
+        heads.append(HeadResult(A=masses[h], idx=idx, K_keep=np.asarray(K_io[h])[idx].copy(), V_out=V_out,
+                                V_star=V_star, diag=diag))
+    return idx, heads
 
 
 # ----------------------------------------------------------------------------- App. H route (used by pins and as a second CPU timing)

@@ -385,3 +385,75 @@ def test_relay_layout_maps_query_heads_to_kv_heads():
     for (l, h), res in out.items():
         ref = O.attention_mass(K[l, h].astype(np.float64), Q[l, h * g:(h + 1) * g].reshape(-1, d).astype(np.float64))
         assert np.allclose(res.A, ref) and abs(res.A.sum() - g * W) < 1e-10
+
+
+# --------------------------------------------------------------------------- layerwise granularity (Sec. 4.3.2)
+def test_layerwise_with_one_head_is_headwise():
+    r = rng(31)
+    N, d, g, W = 40, 16, 2, 3
+    K = r.standard_normal((1, N, d)).astype(np.float32); V = r.standard_normal((1, N, d)).astype(np.float32)
+    Q = r.standard_normal((g, W, d)).astype(np.float32)
+    idx, heads = O.compress_layer(K, V, Q, 7, 2, g, "f32")
+    ref = O.compress_head(K[0], V[0], Q, 7, 2, "f32")
+    assert idx.tolist() == ref.idx.tolist()
+    assert np.array_equal(heads[0].V_out, ref.V_out) and np.array_equal(heads[0].K_keep, ref.K_keep)
+
+
+def test_layerwise_index_set_against_loop_sum_tiny():
+    # the shared set is TopK_B of the loop-level sum of every head's mass; every head gathers exactly those rows
+    r = rng(32)
+    H, N, d, g, W, B = 3, 12, 4, 2, 2, 4
+    K = r.standard_normal((H, N, d)).astype(np.float32); V = r.standard_normal((H, N, d)).astype(np.float32)
+    Q = r.standard_normal((H * g, W, d)).astype(np.float32)
+    idx, heads = O.compress_layer(K, V, Q, B, 1, g, "f32")
+    tot = [0.0] * N
+    for h in range(H):
+        for qh in range(g):
+            for t in range(W):
+                q = Q[h * g + qh, t]
+                s = [sum(float(q[c]) * float(K[h, j, c]) for c in range(d)) / math.sqrt(d) for j in range(N)]
+                m = max(s); e = [math.exp(x - m) for x in s]; z = sum(e)
+                for j in range(N):
+                    tot[j] += e[j] / z
+    keep = sorted(sorted(range(N), key=lambda j: (-tot[j], j))[:B])
+    assert idx.tolist() == keep
+    assert abs(sum(tot) - H * g * W) < 1e-9
+    for h in range(H):
+        assert np.array_equal(heads[h].K_keep, K[h][keep])
+        assert heads[h].idx.tolist() == keep
+
+
+def test_layerwise_is_invariant_to_head_order_and_differs_from_headwise_when_heads_disagree():
+    r = rng(33)
+    H, N, d, g, W, B = 4, 50, 8, 1, 4, 6
+    K = r.standard_normal((H, N, d)).astype(np.float32); V = r.standard_normal((H, N, d)).astype(np.float32)
+    Q = (3.0 * r.standard_normal((H * g, W, d))).astype(np.float32)
+    idx, heads = O.compress_layer(K, V, Q, B, 2, g, "f32")
+    perm = [2, 0, 3, 1]
+    idx_p, heads_p = O.compress_layer(K[perm], V[perm], Q[perm], B, 2, g, "f32")
+    assert idx_p.tolist() == idx.tolist()
+    for a, h in enumerate(perm):
+        assert np.array_equal(heads_p[a].V_out, heads[h].V_out)
+    # a head whose own mass is concentrated elsewhere keeps the layer's set, not its own
+    own = [O.compress_head(K[h], V[h], Q[h * g:(h + 1) * g], B, 2, "f32").idx.tolist() for h in range(H)]
+    assert any(o != idx.tolist() for o in own)
+
+
+def test_layerwise_backfill_uses_each_heads_own_mass():
+    # Eq. 4 and Eq. 6 weigh with the head's own attention mass: recompute one head by hand from the shared set
+    r = rng(34)
+    H, N, d, g, W, B = 2, 14, 5, 1, 3, 3
+    K = r.standard_normal((H, N, d)).astype(np.float32); V = r.standard_normal((H, N, d)).astype(np.float32)
+    Q = r.standard_normal((H * g, W, d)).astype(np.float32)
+    idx, heads = O.compress_layer(K, V, Q, B, 1, g, "f32")
+    h = 1
+    A = O.attention_mass(K[h].astype(np.float64), Q[h * g:(h + 1) * g].reshape(-1, d).astype(np.float64))
+    keep = idx.tolist(); dele = [j for j in range(N) if j not in keep]
+    Vd = V[h].astype(np.float64)
+    Qb, _ = np.linalg.qr(Vd[keep].T)                      # orthonormal basis of the retained span (columns)
+    R = Vd[dele] - (Vd[dele] @ Qb) @ Qb.T
+    w, U = np.linalg.eigh(R.T @ R); c = U[:, -1]
+    a_del = A[dele].sum(); a_keep = A[keep].sum()
+    rbar = (A[dele] / (a_del + 1e-12)) @ R
+    delta = a_del / (a_keep + 1e-12) * (rbar @ c) * c
+    assert np.allclose(heads[h].V_star, Vd[keep] + delta[None, :], rtol=1e-9, atol=1e-12)
