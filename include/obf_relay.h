@@ -124,6 +124,19 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
                                 float* scores_out, float* delta_out, obf_diag_t* diag,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/* The same relay compression with the layerwise granularity of the retention rule (Sec. 4.3.2, the "L" selector
+ * and L-OBF of Sec. 5): per layer, TopK_B of the attention mass summed over the layer's KV heads (ties to the
+ * lowest index, the threshold re-decided in double precision like the headwise rule); every head of the layer
+ * keeps that one index set, and Orthogonal BackFill runs per head with the head's own attention mass in
+ * Eq. 4 / Eq. 6.  budgets_host (nullable, host memory) holds one budget per LAYER ([n_layers]); all other
+ * arguments, layouts, ownership and error behaviour are those of obf_compress_relay (idx and n_keep are still
+ * written per head: the heads of a layer receive identical lists). */
+obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                          const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                          void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                          float* scores_out, float* delta_out, obf_diag_t* diag,
+                                          void* ws, size_t ws_bytes, void* stream);
+
 /* Profiling aid (tracing of the path's own kernels with HIP events on the caller's stream).
  * obf_profile_enable(stage) makes every later call on this thread bracket the launch of that
  * internal stage's kernel with a pair of events; stage -1 switches it off.  obf_profile_read

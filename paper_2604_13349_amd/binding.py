@@ -60,6 +60,8 @@ def load_library():
     lib.obf_backfill.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.obf_compress_relay.restype = C.c_int
     lib.obf_compress_relay.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.obf_compress_relay_layerwise.restype = C.c_int
+    lib.obf_compress_relay_layerwise.argtypes = lib.obf_compress_relay.argtypes
     lib.obf_profile_enable.restype = C.c_int
     lib.obf_profile_enable.argtypes = [i32]
     lib.obf_profile_read.restype = C.c_int
@@ -197,8 +199,9 @@ def backfill(shape: _Shape, V, scores, idx, n_keep, rank: int, V_out, delta_out=
 
 
 def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max_budget: Optional[int] = None,
-                   out=None, ws=None, want_scores=False, want_delta=False, want_diag=False):
-    """Fused relay compression.  Returns a dict of output tensors (device)."""
+                   out=None, ws=None, want_scores=False, want_delta=False, want_diag=False, layerwise=False):
+    """Fused relay compression.  Returns a dict of output tensors (device).  layerwise: one index set per layer
+    (budgets then holds one entry per layer)."""
     sh = shape_of(K, Qwin)
     L, H, d, N = sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.n_tokens
     keep, bptr = _budgets_arg(budgets)
@@ -221,7 +224,8 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
     if want_diag and "diag" not in o:
         o["diag"] = torch.empty((L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
     ws = _ws(sh, max_budget, rank, ws, dev)
-    _check(load_library().obf_compress_relay(
+    fn = load_library().obf_compress_relay_layerwise if layerwise else load_library().obf_compress_relay
+    _check(fn(
         C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]),
         _ptr(o["idx"]), _ptr(o["n_keep"]), _ptr(o.get("scores")), _ptr(o.get("delta")), _ptr(o.get("diag")),
         _ptr(ws), ws.numel(), _stream()))

@@ -201,17 +201,20 @@ obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* 
                          (hipStream_t)stream);
 }
 
-obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
-                                const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
-                                void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
-                                float* scores_out, float* delta_out, obf_diag_t* diag,
-                                void* ws, size_t ws_bytes, void* stream) {
+// Shared body of the two fused calls; layerwise != 0 selects the per-layer retention rule.
+static obf_status_t compress_relay_impl(int layerwise, const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                        const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                        void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                        float* scores_out, float* delta_out, obf_diag_t* diag,
+                                        void* ws, size_t ws_bytes, void* stream) {
   OBF_TRY(check_shape(shape));
   OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(Qwin); OBF_NONNULL(K_out); OBF_NONNULL(V_out);
   OBF_NONNULL(idx); OBF_NONNULL(n_keep);
   if (rank < 0) { set_error("rank < 0"); return OBF_ERR_INVALID_ARG; }
   Dims m = make_dims(shape);
-  OBF_TRY(check_budget(m, budgets_host, budget, max_budget));
+  Dims mb = m;                                          // the units that own a budget: heads, or layers
+  if (layerwise) mb.heads = m.L;
+  OBF_TRY(check_budget(mb, budgets_host, budget, max_budget));
   Workspace w = carve(m, max_budget, rank);
   OBF_TRY(check_ws(m, w, ws, ws_bytes));
   char* base = (char*)ws;
@@ -219,8 +222,12 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
   float* scores = scores_out ? scores_out : (float*)(base + w.scores);
   double* row_lse = (double*)(base + w.row_lse);
   OBF_TRY(run_score(m, w, base, K, Qwin, scores, row_lse, st));
-  // selection and boundary refinement in one kernel (same decisions as the two stage calls)
-  OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+  if (layerwise) {
+    OBF_TRY(launch_select_layerwise(m, w, base, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+  } else {
+    // selection and boundary refinement in one kernel (same decisions as the two stage calls)
+    OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+  }
   // the gather also leaves the sums of squares of the retained V rows for the full-rank certificate
   double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
   // small budgets: the bases of the retained spans start now on a second stream, beside the gather
@@ -228,10 +235,28 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
   OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
   OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part));
   int32_t min_budget = budget;
-  if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < m.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
+  if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < mb.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
   OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
                           basis_started, min_budget));
   return OBF_OK;
+}
+
+obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                float* scores_out, float* delta_out, obf_diag_t* diag,
+                                void* ws, size_t ws_bytes, void* stream) {
+  return compress_relay_impl(0, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+                             scores_out, delta_out, diag, ws, ws_bytes, stream);
+}
+
+obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                          const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                          void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                          float* scores_out, float* delta_out, obf_diag_t* diag,
+                                          void* ws, size_t ws_bytes, void* stream) {
+  return compress_relay_impl(1, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+                             scores_out, delta_out, diag, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

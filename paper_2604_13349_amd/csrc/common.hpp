@@ -45,6 +45,8 @@ struct Workspace {
   size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
   size_t delta;        // float   [heads][d]
   size_t band;         // BandEntry [heads][kBandCap]
+  size_t layer_scores; // float   [L][N]        attention mass summed over the heads of a layer (layerwise selector)
+  size_t layer_idx;    // int32   [L][max_budget], then int32 [L]: the shared index lists and their lengths
   size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
   size_t total;
   int nchunk;          // score chunks per head
@@ -103,6 +105,8 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.mats = take(sizeof(float) * (size_t)m.heads * 3 * m.d * m.d);
   w.delta = take(sizeof(float) * (size_t)m.heads * m.d);
   w.band = take(16 * (size_t)m.heads * kBandCap);
+  w.layer_scores = take(sizeof(float) * (size_t)m.L * m.N);
+  w.layer_idx = take(sizeof(int32_t) * ((size_t)m.L * (max_budget > 0 ? max_budget : 0) + m.L));
   w.fro_part = take(sizeof(double) * (size_t)m.heads * ((max_budget > 0 ? max_budget : 0) / kGatherRows + 1));
   w.total = off;
   return w;
@@ -174,6 +178,15 @@ bool keep_cert_supported(const Dims& m);
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
                               int32_t* decided, hipStream_t st, const double* fro_part = nullptr);
+obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, const float* layer_scores,
+                                  const double* row_lse, int32_t max_budget, int32_t* idx_layer,
+                                  const int32_t* n_keep_layer, hipStream_t st);
+// Layerwise retention rule: TopK_B of the head-summed scores of each layer (with the exact re-decision at the
+// threshold), copied to every head of the layer.  budgets_host: per layer (nullable).
+obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws, const float* scores,
+                                     const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t* idx,
+                                     int32_t* n_keep, const void* K, const void* Q, const double* row_lse,
+                                     hipStream_t st);
 // Optional early start of the retained-span bases on a second stream (forked from st), for shapes where they
 // do not depend on the gather; *started is then passed on to launch_backfill as basis_started.
 obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,

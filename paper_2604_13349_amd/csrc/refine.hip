@@ -31,7 +31,8 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
                                                        const float* __restrict__ scores,
                                                        const double* __restrict__ row_lse, int N, int d, int R,
                                                        int max_budget, int32_t* __restrict__ idx,
-                                                       const int32_t* __restrict__ n_keep) {
+                                                       const int32_t* __restrict__ n_keep,
+                                                       int hps /*heads that share one selection: 1 (headwise) or the layer's heads; scores, idx, n_keep are per selection, K, Q, row_lse per head*/) {
   __shared__ uint32_t bitmap[kMaxTokens / 32];
   __shared__ int band[kBandCap];
   __shared__ double band_score[kBandCap];
@@ -99,8 +100,12 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   if (nkb == 0 || nkb == nband) return;
 
   // 4. exact scores of the band tokens
-  rescore_band<T, RF_WAVES>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, band,
-                            nband, band_score);
+  rescore_band<T, RF_WAVES>(K + (size_t)head * hps * N * d, Q + (size_t)head * hps * R * d,
+                            row_lse + (size_t)head * hps * R, d, R, band, nband, band_score);
+  for (int h = 1; h < hps; ++h) {                      // layerwise: exact masses of the other heads, added in head order
+    const size_t hh = (size_t)head * hps + h;
+    rescore_band<T, RF_WAVES, true>(K + hh * N * d, Q + hh * R * d, row_lse + hh * R, d, R, band, nband, band_score);
+  }
   __syncthreads();
 
   // 5. the nkb best band tokens are retained
@@ -141,11 +146,25 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
   (void)w; (void)ws;
   if (m.dtype == OBF_BF16)
     { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep); }
+                       scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, 1); }
   else
     { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL(k_refine<float>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
-                       row_lse, m.N, m.d, m.R, max_budget, idx, n_keep); }
+                       row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, 1); }
   return check_launch("refine");
+}
+
+// The same re-decision for selections shared by the heads of a layer: scores, idx and n_keep are per layer.
+obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, const float* layer_scores,
+                                  const double* row_lse, int32_t max_budget, int32_t* idx_layer,
+                                  const int32_t* n_keep_layer, hipStream_t st) {
+  ProfScope prof_(ST_REFINE, st);
+  if (m.dtype == OBF_BF16)
+    hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.L), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                       layer_scores, row_lse, m.N, m.d, m.R, max_budget, idx_layer, n_keep_layer, m.H);
+  else
+    hipLaunchKernelGGL(k_refine<float>, dim3(m.L), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q,
+                       layer_scores, row_lse, m.N, m.d, m.R, max_budget, idx_layer, n_keep_layer, m.H);
+  return check_launch("refine (layerwise)");
 }
 
 }  // namespace obf

@@ -308,3 +308,101 @@ def test_near_tie_at_threshold_is_decided_exactly(gpu, dtype, d):
     torch.cuda.synchronize()
     assert np.array_equal(idx.cpu().numpy()[0, 0], ref.idx)
     print("fp32 selection alone agreed with exact arithmetic:", bool(np.array_equal(plain, ref.idx)))
+
+
+# --------------------------------------------------------------------------- layerwise granularity (Sec. 4.3.2)
+def _check_layerwise(gpu, cfg, seed=0, budgets=None, rank=None):
+    """obf_compress_relay_layerwise against oracle.compress_layer: the shared index set must be the oracle's (the exact
+    re-decision at the threshold is part of the call), every head then goes through the per-head checks."""
+    K, V, Q = si.make_cache(cfg, seed, threads=8)
+    L, H = cfg.n_layers, cfg.n_kv_heads
+    bud = np.full(L, cfg.budget, dtype=np.int32) if budgets is None else np.asarray(budgets, dtype=np.int32)
+    rank = cfg.rank if rank is None else rank
+    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=int(min(bud.max(), cfg.n_tokens)), layerwise=True)
+    active = 0
+    for l in range(L):
+        idx, heads = O.compress_layer(K[l], V[l], Q[l], int(bud[l]), rank, cfg.group, cfg.dtype)
+        n = len(idx)
+        for h in range(H):
+            assert int(out["n_keep"][l, h]) == n
+            assert out["idx"][l, h, :n].tolist() == idx.tolist(), f"layer {l} head {h}: shared index set differs"
+            rep = parity.check_head(f"{cfg.name}-L[{l},{h}]", heads[h], K[l, h], V[l, h], cfg.dtype, int(bud[l]),
+                                    out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
+                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
+            active += int(rep.skipped == 0)
+    return active
+
+
+def test_layerwise_config2_shape(gpu):
+    cfg = si.shrink(si.CONFIGS["2"], n_layers=2)
+    assert _check_layerwise(gpu, cfg) == 0                  # budget above head_dim: plain layerwise eviction
+
+
+def test_layerwise_shadow_budget_runs_backfill(gpu):
+    cfg = si.shrink(si.CONFIGS["2s"], n_layers=2)
+    assert _check_layerwise(gpu, cfg, rank=4) > 0           # L-OBF: pca_rank 4 (Sec. 5)
+
+
+def test_layerwise_paper_shape_and_ragged_layer_budgets(gpu):
+    cfg = si.shrink(si.CONFIGS["paper"], n_layers=3)
+    assert _check_layerwise(gpu, cfg, budgets=[32, 7, 200], rank=4) > 0
+
+
+def test_layerwise_fp32_head_dim_64(gpu):
+    cfg = si.RelayConfig("lw64", 13, 2, 3, 2, 64, 700, 8, 40, 4, "f32", "structured", outlier_frac=0.01)
+    assert _check_layerwise(gpu, cfg) > 0
+
+
+def test_layerwise_with_one_head_equals_headwise(gpu):
+    cfg = si.RelayConfig("lw1", 14, 3, 1, 4, 128, 900, 16, 60, 2, "bf16", "structured")
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    a = gpu.run_fused(cfg, K, V, Q, budget=60)
+    b = gpu.run_fused(cfg, K, V, Q, budget=60, layerwise=True)
+    for k in ("idx", "n_keep", "K_out", "V_out", "delta"):
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_layerwise_near_tie_at_threshold_is_decided_exactly(gpu):
+    """A near tie of the LAYER mass (sum over three heads) at the budget boundary, built by nudging one key row of one
+    head: the lower index is the lighter token by less than fp32 resolves, so only the exact multi-head
+    re-decision keeps the right one."""
+    dtype, d, H = "bf16", 128, 3
+    cfg = si.RelayConfig("lwtie", 15, 1, H, 2, d, 1536, 16, 150, 0, dtype, "structured")
+    K, V, Q = si.make_cache(cfg, 0)
+
+    def layer_mass(Kl):
+        tot = np.zeros(cfg.n_tokens)
+        for h in range(H):
+            tot = tot + O.attention_mass(O.decode(Kl[h], dtype), O.decode(Q[0, h * cfg.group:(h + 1) * cfg.group], dtype).reshape(-1, d))
+        return tot
+
+    A0 = layer_mass(K[0])
+    order = np.argsort(-A0, kind="stable")
+    a = int(order[150])                                # a token of middling mass; the budget is set below
+    found = False
+    budget = 0
+    for p in [int(j) for j in order[170:600] if j < a][:6]:
+        # make token p a copy of token a in every head, then nudge one component of one head's copy
+        Kt = K[0].copy()
+        Kt[:, p] = Kt[:, a]
+        for c in np.argsort(np.abs(O.decode(Kt[0, a], dtype)))[:60]:
+            Kn = Kt.copy()
+            Kn[0, p, c] = _bf16_next_toward_zero(Kn[0, p, c])
+            A = layer_mass(Kn)
+            rel = (A[a] - A[p]) / A[a]
+            if 1e-9 < rel < 2e-7:
+                srt = np.argsort(-A, kind="stable")
+                ra = int(np.nonzero(srt == a)[0][0])
+                if int(srt[ra + 1]) == p and A[srt[ra - 1]] > A[a] * (1 + 1e-5) and A[srt[ra + 2]] < A[p] * (1 - 1e-5):
+                    budget = ra + 1                    # a is the last retained token, p the first dropped one
+                    found = True
+                    break
+        if found:
+            break
+    assert found, "could not build a near tie of the layer mass"
+    K2 = K.copy(); K2[0] = Kn
+    idx, _ = O.compress_layer(K2[0], V[0], Q[0], budget, 0, cfg.group, dtype)
+    assert a in idx and p not in idx
+    out = gpu.run_fused(cfg, K2, V, Q, budget=budget, rank=0, layerwise=True)
+    for h in range(H):
+        assert np.array_equal(out["idx"][0, h], idx), "layerwise call: near tie decided differently from exact arithmetic"
