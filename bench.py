@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline (0: skip)")
     ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (0: all)")
+    ap.add_argument("--selector", choices=["head", "layer"], default="head",
+                    help="granularity of the retention rule: per KV head (the headline path) or one index set per layer")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the timed region (a kernel of known "
                          "traffic that calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -97,13 +99,17 @@ def main() -> int:
             del K, V, Q
     gen_s = time.time() - t0
     uniform = cfg.budget_range is None and cfg.budget_int_range is None
+    layerwise = args.selector == "layer"
+    if layerwise and not uniform:
+        for c in calls:                   # one budget per layer: the first head's draw
+            c["bud"] = c["bud"].reshape(cfg.n_layers, cfg.n_kv_heads)[:, :1].copy()
     max_budget = int(max(int(min(c["bud"].max(), cfg.n_tokens)) for c in calls))
     outs = [None] * len(calls)
 
     def step():
         for i, c in enumerate(calls):
             kw = dict(rank=cfg.rank, max_budget=max_budget, out=outs[i], ws=(outs[i] or {}).get("ws"),
-                      want_diag=True)
+                      want_diag=True, layerwise=layerwise)
             if uniform:
                 outs[i] = B.compress_relay(c["K"], c["V"], c["Q"], budget=int(c["bud"].flat[0]), **kw)
             else:
@@ -165,7 +171,28 @@ def main() -> int:
                 "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
 
     cpu = None
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and layerwise:
+        from oracle import obf_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        Kh, Vh, Qh = calls[0]["host"]
+        bud = calls[0]["bud"].reshape(cfg.n_layers, -1)
+        idx_host = outs[0]["idx"].cpu().numpy()
+        done, mismatched, tc0 = 0, 0, time.perf_counter()
+        for l in range(cfg.n_layers):
+            ref_idx, _ = O.compress_layer(Kh[l], Vh[l], Qh[l], int(bud[l, 0]), cfg.rank, cfg.group, cfg.dtype)
+            done += 1
+            mismatched += int(not np.array_equal(idx_host[l, 0, :len(ref_idx)], ref_idx))
+            if time.perf_counter() - tc0 >= args.cpu_seconds:
+                break
+        tc = time.perf_counter() - tc0
+        cpu = {"value": round(done * cfg.n_kv_heads * cfg.n_tokens / tc, 1), "unit": "head-tokens/s", "cores": int(cores),
+               "kind": "oracle", "sample": f"first {done} of {cfg.n_layers} layers of call 0, {tc:.1f} s, fp64 numpy with exact SVD",
+               "layers_index_mismatch": mismatched}
+    elif args.cpu_seconds > 0:
         from oracle import obf_oracle as O
         try:
             from threadpoolctl import threadpool_info
@@ -195,7 +222,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.name}: {cfg.n_layers} layers x {cfg.n_kv_heads} KV heads, group {cfg.group}, "
                                f"head_dim {cfg.head_dim}, N={cfg.n_tokens}, window {cfg.window}, rank {cfg.rank}, "
-                               f"budget {'per-head' if not uniform else cfg.budget}, {cfg.agents} call(s) per step",
+                               f"budget {'per-head' if not uniform else cfg.budget}, {cfg.agents} call(s) per step"
+                               + (", layerwise selector" if layerwise else ""),
                    "heads": cfg.n_heads, "active_obf_heads": active_heads, "input_gen_s": round(gen_s, 1)},
         "roofline": roofline, "cpu_baseline": cpu,
     }

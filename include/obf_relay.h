@@ -15,7 +15,11 @@
  *     memory; scratch space is the caller's workspace `ws` of at least
  *     obf_workspace_bytes() bytes, 256-byte aligned.  Its contents are undefined after a call.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*); nothing is
- *     synchronised.  Inputs are never modified.
+ *     synchronised.  Inputs are never modified.  obf_backfill and the fused calls may run part
+ *     of their work on a second stream that the library creates once per host thread and device
+ *     (default priority): it is forked from `stream` with an event and joined back into `stream`
+ *     before the call returns, so all results are ordered on `stream`; the pattern is legal under
+ *     stream capture.
  *   - Argument errors are found on the host before anything is enqueued and reported as
  *     a status code; obf_last_error() gives a thread-local message.  No exceptions, no abort.
  *   - Layouts are contiguous, row-major, head-major:

@@ -9,8 +9,9 @@
 namespace obf {
 
 constexpr int RF_THREADS = 256;
-constexpr int RF_WAVES = RF_THREADS / 64;
+constexpr int RF_LAYER_THREADS = 1024;   // layerwise: one workgroup per layer re-scores the band in every head of the layer
 
+template <int NW>
 __device__ __forceinline__ int rf_block_exscan(int v, int& total, int* wsum) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int inc = v;
@@ -21,13 +22,13 @@ __device__ __forceinline__ int rf_block_exscan(int v, int& total, int* wsum) {
   if (lane == 63) wsum[wave] = inc;
   __syncthreads();
   int pre = 0; total = 0;
-  for (int wv = 0; wv < RF_WAVES; ++wv) { if (wv < wave) pre += wsum[wv]; total += wsum[wv]; }
+  for (int wv = 0; wv < NW; ++wv) { if (wv < wave) pre += wsum[wv]; total += wsum[wv]; }
   __syncthreads();
   return pre + inc - v;
 }
 
-template <typename T>
-__global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, const T* __restrict__ Q,
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T* __restrict__ Q,
                                                        const float* __restrict__ scores,
                                                        const double* __restrict__ row_lse, int N, int d, int R,
                                                        int max_budget, int32_t* __restrict__ idx,
@@ -37,8 +38,8 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   __shared__ int band[kBandCap];
   __shared__ double band_score[kBandCap];
   __shared__ int keep_new[kBandCap];
-  __shared__ int wsum[RF_WAVES];
-  __shared__ float wred[RF_WAVES];
+  __shared__ int wsum[(NT / 64)];
+  __shared__ float wred[(NT / 64)];
   __shared__ int s_changed;
   const int head = blockIdx.x;
   const int n = n_keep[head];
@@ -49,10 +50,10 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
 
   // 1. threshold = smallest retained score
   float tmin = INFINITY;
-  for (int i0 = threadIdx.x; i0 < n; i0 += 8 * RF_THREADS) {      // batches of 8 independent index -> score loads
+  for (int i0 = threadIdx.x; i0 < n; i0 += 8 * NT) {      // batches of 8 independent index -> score loads
     int j[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) { const int i = i0 + q * RF_THREADS; j[q] = (i < n) ? out[i] : -1; }
+    for (int q = 0; q < 8; ++q) { const int i = i0 + q * NT; j[q] = (i < n) ? out[i] : -1; }
 #pragma unroll
     for (int q = 0; q < 8; ++q) if (j[q] >= 0 && j[q] < N) tmin = fminf(tmin, sc[j[q]]);
   }
@@ -61,12 +62,12 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   if (threadIdx.x == 0) s_changed = 0;
   __syncthreads();
   float tau = wred[0];
-  for (int wv = 1; wv < RF_WAVES; ++wv) tau = fminf(tau, wred[wv]);
+  for (int wv = 1; wv < (NT / 64); ++wv) tau = fminf(tau, wred[wv]);
   const float half = kBandRel * fabsf(tau);
   const float lo = tau - half, hi = tau + half;
 
   // 2. band tokens in index order (thread t owns a contiguous run of tokens; 16-byte loads when aligned)
-  int seg = (N + RF_THREADS - 1) / RF_THREADS;
+  int seg = (N + NT - 1) / NT;
   seg = (seg + 3) & ~3;
   const int b0 = min(N, (int)threadIdx.x * seg), b1 = min(N, b0 + seg);
   const bool vec = (N & 3) == 0;
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
     for (int i = b0; i < b1; ++i) { const float s = sc[i]; cnt += (s >= lo && s <= hi); }
   }
   int nband;
-  int pos = rf_block_exscan(cnt, nband, wsum);
+  int pos = rf_block_exscan<NT / 64>(cnt, nband, wsum);
   if (nband <= 1 || nband > kBandCap) return;
   if (cnt > 0) {
     for (int i = b0; i < b1; ++i) { const float s = sc[i]; if (s >= lo && s <= hi) band[pos++] = i; }
@@ -89,22 +90,22 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
 
   // 3. membership bitmap of the current retained set
   const int words = (N + 31) / 32;
-  for (int i = threadIdx.x; i < words; i += RF_THREADS) bitmap[i] = 0u;
+  for (int i = threadIdx.x; i < words; i += NT) bitmap[i] = 0u;
   __syncthreads();
-  for (int i = threadIdx.x; i < n; i += RF_THREADS) { const int j = out[i]; atomicOr(&bitmap[j >> 5], 1u << (j & 31)); }
+  for (int i = threadIdx.x; i < n; i += NT) { const int j = out[i]; atomicOr(&bitmap[j >> 5], 1u << (j & 31)); }
   __syncthreads();
   int kb = 0;
   if (threadIdx.x < nband) { const int j = band[threadIdx.x]; kb = (bitmap[j >> 5] >> (j & 31)) & 1u; }
   int nkb;
-  rf_block_exscan(kb, nkb, wsum);
+  rf_block_exscan<NT / 64>(kb, nkb, wsum);
   if (nkb == 0 || nkb == nband) return;
 
   // 4. exact scores of the band tokens
-  rescore_band<T, RF_WAVES>(K + (size_t)head * hps * N * d, Q + (size_t)head * hps * R * d,
+  rescore_band<T, (NT / 64)>(K + (size_t)head * hps * N * d, Q + (size_t)head * hps * R * d,
                             row_lse + (size_t)head * hps * R, d, R, band, nband, band_score);
   for (int h = 1; h < hps; ++h) {                      // layerwise: exact masses of the other heads, added in head order
     const size_t hh = (size_t)head * hps + h;
-    rescore_band<T, RF_WAVES, true>(K + hh * N * d, Q + hh * R * d, row_lse + hh * R, d, R, band, nband, band_score);
+    rescore_band<T, (NT / 64), true>(K + hh * N * d, Q + hh * R * d, row_lse + hh * R, d, R, band, nband, band_score);
   }
   __syncthreads();
 
@@ -124,12 +125,12 @@ __global__ __launch_bounds__(RF_THREADS) void k_refine(const T* __restrict__ K, 
   __syncthreads();
 
   // 6. rewrite the ascending index list from the bitmap
-  const int wseg = (words + RF_THREADS - 1) / RF_THREADS;
+  const int wseg = (words + NT - 1) / NT;
   const int w0 = min(words, (int)threadIdx.x * wseg), w1 = min(words, w0 + wseg);
   int pc = 0;
   for (int wi = w0; wi < w1; ++wi) pc += __popc(bitmap[wi]);
   int total;
-  int o = rf_block_exscan(pc, total, wsum);
+  int o = rf_block_exscan<NT / 64>(pc, total, wsum);
   for (int wi = w0; wi < w1; ++wi) {
     uint32_t bits = bitmap[wi];
     while (bits) {
@@ -145,10 +146,10 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
                            const int32_t* n_keep, hipStream_t st) {
   (void)w; (void)ws;
   if (m.dtype == OBF_BF16)
-    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL((k_refine<uint16_t, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
                        scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, 1); }
   else
-    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL(k_refine<float>, dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
+    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL((k_refine<float, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
                        row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, 1); }
   return check_launch("refine");
 }
@@ -159,10 +160,10 @@ obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, c
                                   const int32_t* n_keep_layer, hipStream_t st) {
   ProfScope prof_(ST_REFINE, st);
   if (m.dtype == OBF_BF16)
-    hipLaunchKernelGGL(k_refine<uint16_t>, dim3(m.L), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+    hipLaunchKernelGGL((k_refine<uint16_t, RF_LAYER_THREADS>), dim3(m.L), dim3(RF_LAYER_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
                        layer_scores, row_lse, m.N, m.d, m.R, max_budget, idx_layer, n_keep_layer, m.H);
   else
-    hipLaunchKernelGGL(k_refine<float>, dim3(m.L), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q,
+    hipLaunchKernelGGL((k_refine<float, RF_LAYER_THREADS>), dim3(m.L), dim3(RF_LAYER_THREADS), 0, st, (const float*)K, (const float*)Q,
                        layer_scores, row_lse, m.N, m.d, m.R, max_budget, idx_layer, n_keep_layer, m.H);
   return check_launch("refine (layerwise)");
 }
