@@ -406,3 +406,44 @@ def test_layerwise_near_tie_at_threshold_is_decided_exactly(gpu):
     out = gpu.run_fused(cfg, K2, V, Q, budget=budget, rank=0, layerwise=True)
     for h in range(H):
         assert np.array_equal(out["idx"][0, h], idx), "layerwise call: near tie decided differently from exact arithmetic"
+
+
+# --------------------------------------------------------------------------- HIP graph capture of the fused call
+@pytest.mark.parametrize("name,layerwise", [("2", False), ("2s", False), ("2s", True)])
+def test_graph_capture_replays_match_eager(gpu, name, layerwise):
+    """The fused call is captured into a HIP graph (the small-budget shape forks and joins the library's second
+    stream inside the capture) and replayed several times with eager calls and synchronisations in between; every
+    replay must reproduce the eager outputs bit for bit."""
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    cfg = si.shrink(si.CONFIGS[name], n_layers=3)
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    Kd, Vd, Qd = gpu.to_dev(K, cfg.dtype), gpu.to_dev(V, cfg.dtype), gpu.to_dev(Q, cfg.dtype)
+    out = None
+    for _ in range(2):
+        out = Bd.compress_relay(Kd, Vd, Qd, budget=cfg.budget, rank=cfg.rank, out=out, ws=(out or {}).get("ws"),
+                                want_diag=True, want_delta=True, layerwise=layerwise)
+    torch.cuda.synchronize()
+    keys = ("idx", "n_keep", "K_out", "V_out", "delta", "diag")
+    ref = {k: out[k].clone() for k in keys}
+
+    def call():
+        Bd.compress_relay(Kd, Vd, Qd, budget=cfg.budget, rank=cfg.rank, out=out, ws=out["ws"], want_diag=True,
+                          want_delta=True, layerwise=layerwise)
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for k in keys:
+            out[k].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in keys:
+            assert torch.equal(out[k], ref[k]), f"replay {rep}: {k} differs from the eager call"
+        call()
+        torch.cuda.synchronize()
+        for k in keys:
+            assert torch.equal(out[k], ref[k]), f"eager call after replay {rep}: {k} differs"
