@@ -23,9 +23,6 @@ namespace obf {
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-// Workgroup barrier that orders LDS traffic only (global stores still in flight are not waited for).
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 constexpr int KB_THREADS = 256;
 constexpr int KB_WAVES = KB_THREADS / 64;
 constexpr double kRankEps = 1.1920928955078125e-07;   // 2^-23, the rank rule's epsilon

@@ -27,10 +27,6 @@ __device__ uint64_t g_ks_trace[512 * 12];
 #define KS_STAMP(k) do { } while (0)
 #endif
 
-// Workgroup barrier that orders LDS traffic only: global stores still in flight (rows of the basis, which
-// nobody in the workgroup reads back) are not waited for.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 __device__ __forceinline__ double ks_block_sum(double v, double* red /*[KS_WAVES]*/) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   __syncthreads();

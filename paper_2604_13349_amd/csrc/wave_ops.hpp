@@ -1,4 +1,4 @@
-// Cross-lane reductions on one 64-wide wave through DPP and lane-swap moves (no LDS traffic).
+// Cross-lane reductions on one 64-wide wave through DPP and lane-swap moves (no LDS traffic), and an LDS-only barrier.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -7,6 +7,10 @@ namespace obf {
 
 // The four in-row steps: lane ^ 1, lane ^ 2, mirror within 8, mirror within 16.  After them every lane of a
 // 16-lane row holds the reduction over that row.
+// Workgroup barrier that orders LDS traffic only: global stores still in flight (which nobody in the workgroup
+// reads back) are not waited for, unlike with __syncthreads().
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 #define OBF_DPP_MOV(x, ctrl) ((uint32_t)__builtin_amdgcn_update_dpp(0, (int)(x), (ctrl), 0xF, 0xF, false))
 
 // maximum over the wave, result in every lane
