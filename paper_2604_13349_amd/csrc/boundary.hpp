@@ -19,8 +19,7 @@ __device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
 
 // Exact (double) attention mass of each band token: one wave per token, lanes over the query rows, fixed
 // summation order (row stride 64 per lane, then a butterfly over the lanes).
-// ACC: add to band_score instead of overwriting it (sum over the heads that share one selection).
-template <typename T, int WAVES, bool ACC = false>
+template <typename T, int WAVES>
 __device__ __forceinline__ void rescore_band(const T* __restrict__ Kh, const T* __restrict__ Qh,
                                              const double* __restrict__ lse, int d, int R, const int* band, int nband,
                                              double* band_score) {
@@ -43,7 +42,7 @@ __device__ __forceinline__ void rescore_band(const T* __restrict__ Kh, const T* 
       part += exp(acc * scale - lse[r]);
     }
     for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-    if (lane == 0) band_score[b] = ACC ? band_score[b] + part : part;
+    if (lane == 0) band_score[b] = part;
   }
 }
 

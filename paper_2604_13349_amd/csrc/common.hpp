@@ -44,7 +44,7 @@ struct Workspace {
   size_t gram_part;    // float   [heads][nstat][d*d+d+4] partial Gram / weighted sum / norms of V_del
   size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
   size_t delta;        // float   [heads][d]
-  size_t band;         // BandEntry [heads][kBandCap]
+  size_t band;         // 16 bytes [heads][kBandCap]: scratch of the threshold re-decision (layerwise: exact per-head masses of the band)
   size_t layer_scores; // float   [L][N]        attention mass summed over the heads of a layer (layerwise selector)
   size_t layer_idx;    // int32   [L][max_budget], then int32 [L]: the shared index lists and their lengths
   size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
@@ -180,7 +180,7 @@ obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, cons
                               int32_t* decided, hipStream_t st, const double* fro_part = nullptr);
 obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, const float* layer_scores,
                                   const double* row_lse, int32_t max_budget, int32_t* idx_layer,
-                                  const int32_t* n_keep_layer, hipStream_t st);
+                                  const int32_t* n_keep_layer, double* part /*[heads][kBandCap]*/, hipStream_t st);
 // Layerwise retention rule: TopK_B of the head-summed scores of each layer (with the exact re-decision at the
 // threshold), copied to every head of the layer.  budgets_host: per layer (nullable).
 obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws, const float* scores,

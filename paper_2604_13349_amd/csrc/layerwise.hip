@@ -46,7 +46,8 @@ obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws
   Dims ml = m;
   ml.heads = m.L;                                       // one selection per layer
   if (launch_select(ml, layer_scores, budgets_host, budget, max_budget, idx_layer, nk_layer, st) != OBF_OK) return OBF_ERR_HIP;
-  if (launch_refine_layers(m, K, Q, layer_scores, row_lse, max_budget, idx_layer, nk_layer, st) != OBF_OK) return OBF_ERR_HIP;
+  double* part = (double*)(ws + w.band);               // [heads][kBandCap] exact masses of the band tokens, per head
+  if (launch_refine_layers(m, K, Q, layer_scores, row_lse, max_budget, idx_layer, nk_layer, part, st) != OBF_OK) return OBF_ERR_HIP;
   {
     ProfScope prof_(ST_SELECT, st);
     hipLaunchKernelGGL(k_share_selection, dim3((max(max_budget, 1) + LW_THREADS - 1) / LW_THREADS, m.heads), dim3(LW_THREADS),

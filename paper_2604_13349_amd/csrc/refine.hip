@@ -9,7 +9,6 @@
 namespace obf {
 
 constexpr int RF_THREADS = 256;
-constexpr int RF_LAYER_THREADS = 1024;   // layerwise: one workgroup per layer re-scores the band in every head of the layer
 
 template <int NW>
 __device__ __forceinline__ int rf_block_exscan(int v, int& total, int* wsum) {
@@ -27,27 +26,24 @@ __device__ __forceinline__ int rf_block_exscan(int v, int& total, int* wsum) {
   return pre + inc - v;
 }
 
-template <typename T, int NT>
-__global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T* __restrict__ Q,
-                                                       const float* __restrict__ scores,
-                                                       const double* __restrict__ row_lse, int N, int d, int R,
-                                                       int max_budget, int32_t* __restrict__ idx,
-                                                       const int32_t* __restrict__ n_keep,
-                                                       int hps /*heads that share one selection: 1 (headwise) or the layer's heads; scores, idx, n_keep are per selection, K, Q, row_lse per head*/) {
-  __shared__ uint32_t bitmap[kMaxTokens / 32];
-  __shared__ int band[kBandCap];
-  __shared__ double band_score[kBandCap];
-  __shared__ int keep_new[kBandCap];
-  __shared__ int wsum[(NT / 64)];
-  __shared__ float wred[(NT / 64)];
-  __shared__ int s_changed;
-  const int head = blockIdx.x;
-  const int n = n_keep[head];
-  if (n <= 0 || n >= N) return;
-  const float* sc = scores + (size_t)head * N;
-  int32_t* out = idx + (size_t)head * max_budget;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+template <int NT>
+struct RfShared {
+  uint32_t bitmap[kMaxTokens / 32];
+  int band[kBandCap];
+  double band_score[kBandCap];
+  int keep_new[kBandCap];
+  int wsum[NT / 64];
+  float wred[NT / 64];
+  int s_changed;
+};
 
+// Steps 1-3: the threshold (smallest retained score), the band tokens in index order, the membership bitmap of
+// the current retained set.  Returns false when there is nothing to re-decide.  kb (threads < nband): is band
+// token threadIdx.x retained now; nkb: how many band tokens are.
+template <int NT>
+__device__ bool rf_find_band(RfShared<NT>& sh, const float* __restrict__ sc, const int32_t* __restrict__ out, int n,
+                             int N, int& nband, int& nkb, int& kb) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // 1. threshold = smallest retained score
   float tmin = INFINITY;
   for (int i0 = threadIdx.x; i0 < n; i0 += 8 * NT) {      // batches of 8 independent index -> score loads
@@ -58,11 +54,11 @@ __global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T*
     for (int q = 0; q < 8; ++q) if (j[q] >= 0 && j[q] < N) tmin = fminf(tmin, sc[j[q]]);
   }
   for (int off = 32; off > 0; off >>= 1) tmin = fminf(tmin, __shfl_xor(tmin, off));
-  if (lane == 0) wred[wave] = tmin;
-  if (threadIdx.x == 0) s_changed = 0;
+  if (lane == 0) sh.wred[wave] = tmin;
+  if (threadIdx.x == 0) sh.s_changed = 0;
   __syncthreads();
-  float tau = wred[0];
-  for (int wv = 1; wv < (NT / 64); ++wv) tau = fminf(tau, wred[wv]);
+  float tau = sh.wred[0];
+  for (int wv = 1; wv < NT / 64; ++wv) tau = fminf(tau, sh.wred[wv]);
   const float half = kBandRel * fabsf(tau);
   const float lo = tau - half, hi = tau + half;
 
@@ -81,58 +77,50 @@ __global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T*
   } else {
     for (int i = b0; i < b1; ++i) { const float s = sc[i]; cnt += (s >= lo && s <= hi); }
   }
-  int nband;
-  int pos = rf_block_exscan<NT / 64>(cnt, nband, wsum);
-  if (nband <= 1 || nband > kBandCap) return;
+  int pos = rf_block_exscan<NT / 64>(cnt, nband, sh.wsum);
+  if (nband <= 1 || nband > kBandCap) return false;
   if (cnt > 0) {
-    for (int i = b0; i < b1; ++i) { const float s = sc[i]; if (s >= lo && s <= hi) band[pos++] = i; }
+    for (int i = b0; i < b1; ++i) { const float s = sc[i]; if (s >= lo && s <= hi) sh.band[pos++] = i; }
   }
 
   // 3. membership bitmap of the current retained set
   const int words = (N + 31) / 32;
-  for (int i = threadIdx.x; i < words; i += NT) bitmap[i] = 0u;
+  for (int i = threadIdx.x; i < words; i += NT) sh.bitmap[i] = 0u;
   __syncthreads();
-  for (int i = threadIdx.x; i < n; i += NT) { const int j = out[i]; atomicOr(&bitmap[j >> 5], 1u << (j & 31)); }
+  for (int i = threadIdx.x; i < n; i += NT) { const int j = out[i]; atomicOr(&sh.bitmap[j >> 5], 1u << (j & 31)); }
   __syncthreads();
-  int kb = 0;
-  if (threadIdx.x < nband) { const int j = band[threadIdx.x]; kb = (bitmap[j >> 5] >> (j & 31)) & 1u; }
-  int nkb;
-  rf_block_exscan<NT / 64>(kb, nkb, wsum);
-  if (nkb == 0 || nkb == nband) return;
+  kb = 0;
+  if ((int)threadIdx.x < nband) { const int j = sh.band[threadIdx.x]; kb = (sh.bitmap[j >> 5] >> (j & 31)) & 1u; }
+  rf_block_exscan<NT / 64>(kb, nkb, sh.wsum);
+  return !(nkb == 0 || nkb == nband);
+}
 
-  // 4. exact scores of the band tokens
-  rescore_band<T, (NT / 64)>(K + (size_t)head * hps * N * d, Q + (size_t)head * hps * R * d,
-                            row_lse + (size_t)head * hps * R, d, R, band, nband, band_score);
-  for (int h = 1; h < hps; ++h) {                      // layerwise: exact masses of the other heads, added in head order
-    const size_t hh = (size_t)head * hps + h;
-    rescore_band<T, (NT / 64), true>(K + hh * N * d, Q + hh * R * d, row_lse + hh * R, d, R, band, nband, band_score);
+// Steps 5-6: the nkb band tokens with the best exact scores (sh.band_score) are retained; the ascending index list
+// is rewritten from the bitmap if anything changed.
+template <int NT>
+__device__ void rf_apply(RfShared<NT>& sh, int32_t* __restrict__ out, int N, int nband, int nkb, int kb) {
+  if ((int)threadIdx.x < nband) {
+    const int keep = band_keeps(sh.band_score, nband, nkb, threadIdx.x);
+    sh.keep_new[threadIdx.x] = keep;
+    if (keep != kb) sh.s_changed = 1;
   }
   __syncthreads();
-
-  // 5. the nkb best band tokens are retained
-  if (threadIdx.x < nband) {
-    const int keep = band_keeps(band_score, nband, nkb, threadIdx.x);
-    keep_new[threadIdx.x] = keep;
-    if (keep != kb) s_changed = 1;
+  if (!sh.s_changed) return;
+  if ((int)threadIdx.x < nband) {
+    const int j = sh.band[threadIdx.x];
+    if (sh.keep_new[threadIdx.x]) atomicOr(&sh.bitmap[j >> 5], 1u << (j & 31));
+    else atomicAnd(&sh.bitmap[j >> 5], ~(1u << (j & 31)));
   }
   __syncthreads();
-  if (!s_changed) return;
-  if (threadIdx.x < nband) {
-    const int j = band[threadIdx.x];
-    if (keep_new[threadIdx.x]) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
-    else atomicAnd(&bitmap[j >> 5], ~(1u << (j & 31)));
-  }
-  __syncthreads();
-
-  // 6. rewrite the ascending index list from the bitmap
+  const int words = (N + 31) / 32;
   const int wseg = (words + NT - 1) / NT;
   const int w0 = min(words, (int)threadIdx.x * wseg), w1 = min(words, w0 + wseg);
   int pc = 0;
-  for (int wi = w0; wi < w1; ++wi) pc += __popc(bitmap[wi]);
+  for (int wi = w0; wi < w1; ++wi) pc += __popc(sh.bitmap[wi]);
   int total;
-  int o = rf_block_exscan<NT / 64>(pc, total, wsum);
+  int o = rf_block_exscan<NT / 64>(pc, total, sh.wsum);
   for (int wi = w0; wi < w1; ++wi) {
-    uint32_t bits = bitmap[wi];
+    uint32_t bits = sh.bitmap[wi];
     while (bits) {
       const int bpos = __ffs(bits) - 1;
       bits &= bits - 1;
@@ -141,30 +129,101 @@ __global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T*
   }
 }
 
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T* __restrict__ Q,
+                                                const float* __restrict__ scores,
+                                                const double* __restrict__ row_lse, int N, int d, int R,
+                                                int max_budget, int32_t* __restrict__ idx,
+                                                const int32_t* __restrict__ n_keep) {
+  __shared__ RfShared<NT> sh;
+  const int head = blockIdx.x;
+  const int n = n_keep[head];
+  if (n <= 0 || n >= N) return;
+  const float* sc = scores + (size_t)head * N;
+  int32_t* out = idx + (size_t)head * max_budget;
+  int nband, nkb, kb;
+  if (!rf_find_band<NT>(sh, sc, out, n, N, nband, nkb, kb)) return;
+  // 4. exact scores of the band tokens
+  rescore_band<T, NT / 64>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, sh.band,
+                           nband, sh.band_score);
+  __syncthreads();
+  rf_apply<NT>(sh, out, N, nband, nkb, kb);
+}
+
+// Layerwise selections (scores, idx, n_keep per layer; K, Q, row_lse per head), in two launches so that the exact
+// scores of the band are computed by one workgroup per (layer, head): this one finds the layer's band (the same
+// deterministic steps in every workgroup of the layer) and writes the head's exact masses of the band tokens.
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void k_refine_layer_part(const T* __restrict__ K, const T* __restrict__ Q,
+                                                          const float* __restrict__ layer_scores,
+                                                          const double* __restrict__ row_lse, int N, int d, int R, int H,
+                                                          int max_budget, const int32_t* __restrict__ idx_layer,
+                                                          const int32_t* __restrict__ n_keep_layer,
+                                                          double* __restrict__ part /*[L*H][kBandCap]*/) {
+  __shared__ RfShared<NT> sh;
+  const int head = blockIdx.x, l = head / H;
+  const int n = n_keep_layer[l];
+  if (n <= 0 || n >= N) return;
+  int nband, nkb, kb;
+  if (!rf_find_band<NT>(sh, layer_scores + (size_t)l * N, idx_layer + (size_t)l * max_budget, n, N, nband, nkb, kb)) return;
+  rescore_band<T, NT / 64>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, sh.band,
+                           nband, part + (size_t)head * kBandCap);
+}
+
+// Second launch: one workgroup per layer finds the band again, adds the heads' exact masses in head order and
+// re-decides the band.
+template <int NT>
+__global__ __launch_bounds__(NT) void k_refine_layer_apply(const float* __restrict__ layer_scores, int N, int H,
+                                                           int max_budget, int32_t* __restrict__ idx_layer,
+                                                           const int32_t* __restrict__ n_keep_layer,
+                                                           const double* __restrict__ part) {
+  __shared__ RfShared<NT> sh;
+  const int l = blockIdx.x;
+  const int n = n_keep_layer[l];
+  if (n <= 0 || n >= N) return;
+  int32_t* out = idx_layer + (size_t)l * max_budget;
+  int nband, nkb, kb;
+  if (!rf_find_band<NT>(sh, layer_scores + (size_t)l * N, out, n, N, nband, nkb, kb)) return;
+  if ((int)threadIdx.x < nband) {
+    double s = 0.0;
+    for (int h = 0; h < H; ++h) s += part[((size_t)l * H + h) * kBandCap + threadIdx.x];
+    sh.band_score[threadIdx.x] = s;
+  }
+  __syncthreads();
+  rf_apply<NT>(sh, out, N, nband, nkb, kb);
+}
+
 obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
                            const float* scores, const double* row_lse, int32_t max_budget, int32_t* idx,
                            const int32_t* n_keep, hipStream_t st) {
   (void)w; (void)ws;
+  ProfScope prof_(ST_REFINE, st);
   if (m.dtype == OBF_BF16)
-    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL((k_refine<uint16_t, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, 1); }
+    hipLaunchKernelGGL((k_refine<uint16_t, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K,
+                       (const uint16_t*)Q, scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
   else
-    { ProfScope prof_(ST_REFINE, st); hipLaunchKernelGGL((k_refine<float, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K, (const float*)Q, scores,
-                       row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, 1); }
+    hipLaunchKernelGGL((k_refine<float, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K,
+                       (const float*)Q, scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
   return check_launch("refine");
 }
 
-// The same re-decision for selections shared by the heads of a layer: scores, idx and n_keep are per layer.
+// The same re-decision for selections shared by the heads of a layer: scores, idx and n_keep are per layer;
+// part is scratch for the heads' exact masses of the band tokens ([L*H][kBandCap] doubles).
 obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, const float* layer_scores,
                                   const double* row_lse, int32_t max_budget, int32_t* idx_layer,
-                                  const int32_t* n_keep_layer, hipStream_t st) {
+                                  const int32_t* n_keep_layer, double* part, hipStream_t st) {
   ProfScope prof_(ST_REFINE, st);
   if (m.dtype == OBF_BF16)
-    hipLaunchKernelGGL((k_refine<uint16_t, RF_LAYER_THREADS>), dim3(m.L), dim3(RF_LAYER_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       layer_scores, row_lse, m.N, m.d, m.R, max_budget, idx_layer, n_keep_layer, m.H);
+    hipLaunchKernelGGL((k_refine_layer_part<uint16_t, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st,
+                       (const uint16_t*)K, (const uint16_t*)Q, layer_scores, row_lse, m.N, m.d, m.R, m.H, max_budget,
+                       idx_layer, n_keep_layer, part);
   else
-    hipLaunchKernelGGL((k_refine<float, RF_LAYER_THREADS>), dim3(m.L), dim3(RF_LAYER_THREADS), 0, st, (const float*)K, (const float*)Q,
-                       layer_scores, row_lse, m.N, m.d, m.R, max_budget, idx_layer, n_keep_layer, m.H);
+    hipLaunchKernelGGL((k_refine_layer_part<float, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st,
+                       (const float*)K, (const float*)Q, layer_scores, row_lse, m.N, m.d, m.R, m.H, max_budget,
+                       idx_layer, n_keep_layer, part);
+  if (check_launch("refine (layerwise, exact masses)") != OBF_OK) return OBF_ERR_HIP;
+  hipLaunchKernelGGL((k_refine_layer_apply<RF_THREADS>), dim3(m.L), dim3(RF_THREADS), 0, st, layer_scores, m.N, m.H,
+                     max_budget, idx_layer, n_keep_layer, part);
   return check_launch("refine (layerwise)");
 }
 
