@@ -68,7 +68,7 @@ typedef struct {
   int32_t dtype;      /* obf_dtype_t of K, V, Qwin, K_out, V_out */
 } obf_shape_t;
 
-/* Per-head diagnostics (App. K.2 quantities that fall out of the computation). */
+/* Per-head diagnostics: the quantities of App. K.2 (PCR, RCR, PC, REVR, DR, IVN) and the decisions taken. */
 typedef struct {
   int32_t n_keep;   /* retained tokens */
   int32_t r_keep;   /* dimension of the retained value span (Eq. 2); 0 if not computed */
@@ -76,8 +76,12 @@ typedef struct {
   int32_t skipped;  /* 1: no injection (empty P_del, rank 0, span = R^d, negligible residual) */
   float a_keep;     /* sum of attention mass over retained tokens (Eq. 6) */
   float a_del;      /* sum over deleted tokens */
-  float rcr;        /* ||R||_F^2 / ||V_del||_F^2 */
-  float ivn;        /* ||delta||_2 */
+  float rcr;        /* residual content ratio ||R||_F^2 / (||V_del||_F^2 + eps) */
+  float ivn;        /* injection vector norm ||delta||_2 */
+  float pcr;        /* projected content ratio ||V_par||_F^2 / (||V_del||_F^2 + eps); 1 when the retained span is R^d */
+  float pc;         /* projection cosine between the column sums of V_del and of V_par; 0 when not computed */
+  float revr;       /* residual explained variance ratio of the k_used directions; 0 when none is used */
+  float dr;         /* demand ratio a_del / (a_keep + eps) */
 } obf_diag_t;
 
 /* Bytes of workspace any entry point needs for this shape (host function, no device work).

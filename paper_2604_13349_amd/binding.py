@@ -16,7 +16,8 @@ OBF_F32, OBF_BF16 = 0, 1
 _STATUS = {1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP"}
 
 DIAG_DTYPE = np.dtype([("n_keep", "<i4"), ("r_keep", "<i4"), ("k_used", "<i4"), ("skipped", "<i4"),
-                       ("a_keep", "<f4"), ("a_del", "<f4"), ("rcr", "<f4"), ("ivn", "<f4")])
+                       ("a_keep", "<f4"), ("a_del", "<f4"), ("rcr", "<f4"), ("ivn", "<f4"),
+                       ("pcr", "<f4"), ("pc", "<f4"), ("revr", "<f4"), ("dr", "<f4")])
 
 
 class ObfError(RuntimeError):

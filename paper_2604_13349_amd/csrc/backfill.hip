@@ -372,7 +372,7 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
   const int bs = d / 16;
   float acc[8][8];
   for (int a = 0; a < 8; ++a) for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
-  float u = 0.f, nn = 0.f;                   // threads < d: weighted column sum; all: squared norm share
+  float u = 0.f, su = 0.f, nn = 0.f;         // threads < d: weighted and plain column sums, squared norm share
 
   for (int tt = t0; tt < t1; tt += DS_TOK) {
     __syncthreads();
@@ -406,13 +406,14 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
         const float x = Vs[i * d + threadIdx.x];
         const float wgt = wt[i];
         u = fmaf(wgt, x, u);
+        su += x;
         nn = fmaf(x, x, nn);
       }
     }
   }
-  float* out = gram_part + ((size_t)head * nstat + chunk) * ((size_t)d * d + d + 4);
+  float* out = gram_part + ((size_t)head * nstat + chunk) * gram_stride(d);
   for (int a = 0; a < bs; ++a) for (int b = 0; b < bs; ++b) out[(ty * bs + a) * d + tx * bs + b] = acc[a][b];
-  if ((int)threadIdx.x < d) { out[d * d + threadIdx.x] = u; }
+  if ((int)threadIdx.x < d) { out[d * d + threadIdx.x] = u; out[d * d + d + threadIdx.x] = su; }
   // ||V_del||^2 of the chunk: sum over the d column shares, fixed order
   __shared__ float nsh[128];
   __syncthreads();
@@ -421,7 +422,7 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
   if (threadIdx.x == 0) {
     double s = 0.0;
     for (int c = 0; c < d; ++c) s += (double)nsh[c];
-    out[d * d + d] = (float)s;
+    out[d * d + 2 * d] = (float)s;
   }
 }
 
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   float* M = sm;                    // T = Z G Z^T and its diagonal form, set below
   __shared__ float cs[64], sn[64];
   __shared__ int pp[64], qq[64];
-  __shared__ float uvec[128], rbar[128], dvec[128], lamv[128];
+  __shared__ float uvec[128], svec[128], rbar[128], dvec[128], lamv[128];
   __shared__ int order[128];
   __shared__ float fred[FN_WAVES];
   __shared__ int s_k;
@@ -455,7 +456,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   __shared__ uint32_t wkey[2][2];
   HeadState st = state[head];
   int skipped = 1;
-  float rcr = 0.f, ivn = 0.f;
+  float rcr = 0.f, ivn = 0.f, pcr = 0.f, pc = 0.f, revr = 0.f;
   int k_used = 0;
   const int tid = threadIdx.x;
   {
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     const int r = st.r_keep;
     int m = d - r;                                             // dimension of the orthogonal complement
     const float* Qb = basis + (size_t)head * d * d;            // [r][d] orthonormal rows
-    const size_t pstride = (size_t)d * d + d + 4;
+    const size_t pstride = gram_stride(d);
     const float* gp = gram_part + (size_t)head * nstat * pstride;
     float* Zg = mats + (size_t)head * 3 * d * d;               // [m][d] basis of the complement (global scratch)
     float* Yg = Zg + (size_t)d * d;                            // [m][d] Z G
@@ -500,10 +501,14 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
 #pragma unroll 8
       for (int c = 0; c < nstat; ++c) s += gp[c * pstride + d * d + tid];
       uvec[tid] = s;
+      float s2 = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < nstat; ++c) s2 += gp[c * pstride + d * d + d + tid];
+      svec[tid] = s2;
     }
     float vd2 = 0.f;
 #pragma unroll 8
-    for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + d];
+    for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + 2 * d];
 
     __syncthreads();                                           // G is in global scratch for every thread of the workgroup
     BF_STAMP(1, 1);
@@ -592,6 +597,19 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     }
     __syncthreads();
 
+    // projection cosine (App. K.2): with s the column sum of V_del, the column sum of V_par is s - Z^T Z s, and
+    // their cosine is |s_par| / |s| = sqrt(1 - |Z s|^2 / |s|^2)
+    {
+      float zs2 = 0.f, sd2 = 0.f;
+      if (tid < m) { float z = 0.f; for (int c = 0; c < d; ++c) z = fmaf(U[tid * ld + c], svec[c], z); zs2 = z * z; }
+      if (tid < d) sd2 = svec[tid] * svec[tid];
+      for (int o = 32; o > 0; o >>= 1) { zs2 += __shfl_xor(zs2, o); sd2 += __shfl_xor(sd2, o); }
+      if (tid < 128 && lane == 0) { fred[tid >> 6] = zs2; fred[2 + (tid >> 6)] = sd2; }
+      __syncthreads();
+      const float z2 = fred[0] + fred[1], s2 = fred[2] + fred[3];
+      pc = (s2 > 0.f) ? sqrtf(fmaxf(s2 - z2, 0.f) / s2) : 0.f;
+      __syncthreads();
+    }
     BF_STAMP(1, 3);
     // Z to global scratch (for the last phase), X = G Z^T (d x m) and T = Z X (m x m) on the matrix cores.
     // T is the residual Gram matrix R^T R = P G P restricted to the complement; its eigenpairs (lambda, w) give
@@ -668,6 +686,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     __syncthreads();
     const float res2 = s_off;
     rcr = res2 / (vd2 + 1e-12f);
+    pcr = fmaxf(vd2 - res2, 0.f) / (vd2 + 1e-12f);
     const bool negligible = !(res2 > kRcrSkip * vd2) || m <= 0;
 
     BF_STAMP(1, 5);
@@ -764,9 +783,14 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         const int cap = min(min(st.n_del, d - r), d);
         if (rankR > cap) rankR = cap;
         s_k = min(rank, rankR);
+        double top = 0.0;                                        // explained variance of the directions used (App. K.2)
+        for (int j = 0; j < s_k; ++j) top += (double)lamv[order[j]];
+        s_off = (float)(top / ((double)res2 + 1e-12));
       }
       __syncthreads();
       k_used = s_k;
+      revr = (k_used > 0) ? s_off : 0.f;
+      __syncthreads();
       if (k_used > 0) {
         // In complement coordinates: y = Z u, so that rbar = Z^T y / (a_del + eps)  (Eq. 4 with R_j = P v_j)
         if (tid < m) {
@@ -818,6 +842,10 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       obf_diag_t dg;
       dg.n_keep = st.n_keep; dg.r_keep = st.r_keep; dg.k_used = k_used; dg.skipped = skipped;
       dg.a_keep = (float)st.a_keep; dg.a_del = (float)st.a_del; dg.rcr = rcr; dg.ivn = ivn;
+      // a head whose retained span is all of R^d has its deleted values entirely inside it
+      dg.pcr = (rank > 0 && st.n_keep > 0 && st.n_del > 0 && st.r_keep >= d) ? 1.f : pcr;
+      dg.pc = pc; dg.revr = revr;
+      dg.dr = (float)(st.a_del / (st.a_keep + kEps));
       diag[head] = dg;
     }
   }

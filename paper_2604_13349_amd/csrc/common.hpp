@@ -41,7 +41,7 @@ struct Workspace {
   size_t head_state;   // HeadState [heads]
   size_t decided;      // int32   [heads]                 1: the fast full-rank test settled the head
   size_t basis;        // float   [heads][d][d]           orthonormal basis of the retained span (columns)
-  size_t gram_part;    // float   [heads][nstat][d*d+d+4] partial Gram / weighted sum / norms of V_del
+  size_t gram_part;    // float   [heads][nstat][gram_stride(d)] partial Gram / weighted sum / plain sum / norm of V_del
   size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
   size_t delta;        // float   [heads][d]
   size_t band;         // 16 bytes [heads][kBandCap]: scratch of the threshold re-decision (layerwise: exact per-head masses of the band)
@@ -64,6 +64,10 @@ struct HeadState {
   int32_t pad;
   float rcr, ivn;
 };
+
+// One chunk's statistics of the deleted values: G [d][d] (tiles on and below the diagonal), u = sum_j A_j v_j [d],
+// s = sum_j v_j [d], ||V_del||_F^2, padding.
+__host__ __device__ inline size_t gram_stride(int d) { return (size_t)d * d + 2 * (size_t)d + 4; }
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -101,7 +105,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.head_state = take(sizeof(HeadState) * (size_t)m.heads);
   w.decided = take(sizeof(int32_t) * (size_t)m.heads);
   w.basis = take(sizeof(float) * (size_t)m.heads * m.d * m.d);
-  w.gram_part = take(sizeof(float) * (size_t)m.heads * w.nstat * ((size_t)m.d * m.d + m.d + 4));
+  w.gram_part = take(sizeof(float) * (size_t)m.heads * w.nstat * gram_stride(m.d));
   w.mats = take(sizeof(float) * (size_t)m.heads * 3 * m.d * m.d);
   w.delta = take(sizeof(float) * (size_t)m.heads * m.d);
   w.band = take(16 * (size_t)m.heads * kBandCap);

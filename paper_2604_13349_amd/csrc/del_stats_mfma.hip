@@ -72,6 +72,7 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
   float u4[4] = {0.f, 0.f, 0.f, 0.f};                  // weighted sums of this thread's four columns 4*(tid%32) ..
+  float s4[4] = {0.f, 0.f, 0.f, 0.f};                  // plain sums of the same columns (deleted rows only)
   float nn = 0.f;                                      // squared norms of the deleted entries this thread has seen
 
   uint2 pre[2][8];
@@ -101,6 +102,7 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
         const float v0 = __uint_as_float(sx << 16), v1 = __uint_as_float(sx & 0xffff0000u);
         const float v2 = __uint_as_float(sy << 16), v3 = __uint_as_float(sy & 0xffff0000u);
         u4[0] = fmaf(w, v0, u4[0]); u4[1] = fmaf(w, v1, u4[1]); u4[2] = fmaf(w, v2, u4[2]); u4[3] = fmaf(w, v3, u4[3]);
+        s4[0] += v0; s4[1] += v1; s4[2] += v2; s4[3] += v3;
         nn = fmaf(v0, v0, nn); nn = fmaf(v1, v1, nn); nn = fmaf(v2, v2, nn); nn = fmaf(v3, v3, nn);
       }
       const uint32_t mine = lh ? sy : sx;
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
 
   // ---- results: the 32 x 32 tiles of the Gram matrix on and below the diagonal (row-major in the d x d partial, so
   // the stores are row segments; the tiles above the diagonal are left unwritten, the reader mirrors)
-  float* out = gram_part + ((size_t)head * nstat + chunk) * ((size_t)DM_D * DM_D + DM_D + 4);
+  float* out = gram_part + ((size_t)head * nstat + chunk) * gram_stride(DM_D);
 #pragma unroll
   for (int t = 0; t < 3; ++t) {
     if (t < nt) {
@@ -189,7 +191,20 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
     for (int p = 0; p < 8; ++p) s += red[p][tid];
     out[DM_D * DM_D + tid] = s;
   }
-  if (tid == 0) out[DM_D * DM_D + DM_D] = (red[0][DM_D] + red[1][DM_D]) + (red[2][DM_D] + red[3][DM_D]);
+  if (tid == 0) out[DM_D * DM_D + 2 * DM_D] = (red[0][DM_D] + red[1][DM_D]) + (red[2][DM_D] + red[3][DM_D]);
+  __syncthreads();
+  {
+    const int c = tid & 31, part = tid >> 5;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[part][c * 4 + k] = s4[k];
+  }
+  __syncthreads();
+  if (tid < DM_D) {
+    float s = 0.f;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) s += red[p][tid];
+    out[DM_D * DM_D + DM_D + tid] = s;
+  }
 }
 
 bool del_stats_mfma_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == DM_D; }

@@ -99,6 +99,16 @@ def check_head(tag, ref: O.HeadResult, K_io, V_io, dtype, budget, gpu_idx, gpu_n
     if gpu_diag is not None:
         assert abs(float(gpu_diag["a_keep"]) - dg.a_keep) <= 1e-4 * max(dg.a_keep, 1e-30) + 1e-30
         assert abs(float(gpu_diag["a_del"]) - dg.a_del) <= 1e-4 * max(dg.a_del, 1e-30) + 1e-7 * dg.a_keep
+        if "dr" in gpu_diag.dtype.names:
+            # the remaining App. K.2 diagnostics (fp32 Gram arithmetic on the device: 1e-4 absolute on the ratios)
+            assert abs(float(gpu_diag["dr"]) - dg.dr) <= 2e-4 * dg.dr + 1e-7, f"{tag}: DR {gpu_diag['dr']} vs {dg.dr}"
+            if not rep.ambiguous:
+                assert abs(float(gpu_diag["pcr"]) - dg.pcr) <= 2e-4, f"{tag}: PCR {gpu_diag['pcr']} vs {dg.pcr}"
+                assert abs(float(gpu_diag["rcr"]) - dg.rcr) <= 2e-4, f"{tag}: RCR {gpu_diag['rcr']} vs {dg.rcr}"
+                assert abs(float(gpu_diag["pc"]) - abs(dg.pc)) <= 1e-3, f"{tag}: PC {gpu_diag['pc']} vs {dg.pc}"
+                assert abs(float(gpu_diag["revr"]) - dg.revr) <= 1e-3, f"{tag}: REVR {gpu_diag['revr']} vs {dg.revr}"
+                assert abs(float(gpu_diag["ivn"]) - dg.ivn) <= 2e-3 * gap_factor(dg) * dg.ivn + 1e-6 * max(dg.ivn, 1e-3), (
+                    f"{tag}: IVN {gpu_diag['ivn']} vs {dg.ivn}")
     if dg.skipped and not rep.ambiguous:
         assert np.array_equal(gpu_V[:B], V_io[gi]), f"{tag}: OBF skipped but V_out is not a bit copy"
         if gpu_delta is not None:
