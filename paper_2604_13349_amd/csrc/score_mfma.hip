@@ -100,6 +100,10 @@ struct StatsEp {
     const float sc = fast_exp2((mo - mn) * a2);          // 0 on the first tile (mo = -inf), 1 when the maximum stands
     l[RB] = fma(l[RB], (double)sc, (double)ts);
     m[RB] = mn;
+    // Pin the update here: its results are only read by the next tile, so the optimiser would otherwise sink all
+    // epilogues of a loop iteration behind the matrix instructions, and the two pipes would take turns instead of
+    // running side by side.
+    asm volatile("" : "+v"(l[RB]), "+v"(m[RB]));
   }
 };
 
