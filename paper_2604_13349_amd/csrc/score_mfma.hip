@@ -164,19 +164,22 @@ struct MassEp {
 // Software pipeline over the tiles first, first + STEP, ... of one wave, at row-block granularity: micro-stage
 // (tile t, row block rb) issues the MFMA chain of the NEXT (tile, row block) and, in the same basic block,
 // runs the vector-ALU epilogue of the current one, so the matrix pipe and the vector ALU overlap within the
-// one wave a SIMD holds.  Two 16-register accumulators and two K fragment buffers alternate; the load of
-// tile t+2 is issued once the last chain of tile t has been issued.
+// one wave a SIMD holds.  Two 16-register accumulators alternate; three K fragment buffers rotate, and the load
+// of tile t+3 is issued once the last chain of tile t has been issued (almost three tiles of work ahead of
+// its first use: the memory latency is covered by two tiles' worth of compute).
+constexpr int SM_KBUF = 3;
+
 template <bool TOKENS_BY_ROWS, int U, class Ep>
 __device__ __forceinline__ void micro_stage(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane, int i,
-                                            const Frag (&qf)[SM_RB][SM_KK], Frag (&kb)[2][SM_KK], f32x16 (&acc)[2], Ep& ep,
+                                            const Frag (&qf)[SM_RB][SM_KK], Frag (&kb)[SM_KBUF][SM_KK], f32x16 (&acc)[2], Ep& ep,
                                             bool guarded) {
-  constexpr int rb = U % 4, tl = U / 4;                 // current row block, tile offset within the group of 2
+  constexpr int rb = U % 4, tl = U / 4;                 // current row block, tile offset within the group of SM_KBUF
   constexpr int rbn = (U + 1) % 4, tln = (U + 1) / 4;   // next
   const int tile = i + tl, tilen = i + tln;
   if (guarded && tile >= n) return;
-  if (!guarded || tilen < n) block_mfma<TOKENS_BY_ROWS>(acc[(U + 1) & 1], kb[tln % 2], qf[rbn]);
+  if (!guarded || tilen < n) block_mfma<TOKENS_BY_ROWS>(acc[(U + 1) & 1], kb[tln % SM_KBUF], qf[rbn]);
   ep.template block<rb>(acc[U & 1], first + tile * step);
-  if (rb == 3 && tile + 2 < n) load_k(kb[tl % 2], Kh, first + (tile + 2) * step, t_end, lane);
+  if (rb == 3 && tile + SM_KBUF < n) load_k(kb[tl % SM_KBUF], Kh, first + (tile + SM_KBUF) * step, t_end, lane);
   __builtin_amdgcn_sched_barrier(0);      // keep the scheduler from merging micro-stages (register pressure)
 }
 
@@ -184,24 +187,21 @@ template <bool TOKENS_BY_ROWS, class Ep>
 __device__ __forceinline__ void run_tiles(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane,
                                           const Frag (&qf)[SM_RB][SM_KK], Ep& ep) {
   if (n <= 0) return;
-  Frag kb[2][SM_KK];
+  Frag kb[SM_KBUF][SM_KK];
   f32x16 acc[2];
   load_k(kb[0], Kh, first, t_end, lane);
   if (n > 1) load_k(kb[1], Kh, first + step, t_end, lane);
+  if (n > 2) load_k(kb[2], Kh, first + 2 * step, t_end, lane);
   block_mfma<TOKENS_BY_ROWS>(acc[0], kb[0], qf[0]);
   int i = 0;
+#define OBF_ST(U, G) micro_stage<TOKENS_BY_ROWS, U>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);
 #define OBF_STAGES(G)                                                                                      \
-  micro_stage<TOKENS_BY_ROWS, 0>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 1>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 2>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 3>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 4>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 5>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 6>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);                        \
-  micro_stage<TOKENS_BY_ROWS, 7>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);
-  for (; i + 2 < n; i += 2) { OBF_STAGES(false) }      // two whole tiles and the first chain of the next exist
+  OBF_ST(0, G) OBF_ST(1, G) OBF_ST(2, G) OBF_ST(3, G) OBF_ST(4, G) OBF_ST(5, G)                            \
+  OBF_ST(6, G) OBF_ST(7, G) OBF_ST(8, G) OBF_ST(9, G) OBF_ST(10, G) OBF_ST(11, G)
+  for (; i + SM_KBUF < n; i += SM_KBUF) { OBF_STAGES(false) }   // three whole tiles and the first chain of the next exist
   { OBF_STAGES(true) }
 #undef OBF_STAGES
+#undef OBF_ST
 }
 
 // Static partition of the flattened (head, tile) space over the persistent workgroups.
