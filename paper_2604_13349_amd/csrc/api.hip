@@ -233,11 +233,21 @@ static obf_status_t compress_relay_impl(int layerwise, const obf_shape_t* shape,
   // small budgets: the bases of the retained spans start now on a second stream, beside the gather
   bool basis_started = false;
   OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
-  OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part));
+  // Large budgets: nothing downstream reads K_out, so the retained K rows are copied on the second stream once the
+  // V rows (which the certificate waits for) are through, beside the latency-bound per-head kernels.
+  hipStream_t kside = nullptr;
+  if (!basis_started && (size_t)max_budget * m.heads >= 65536) {
+    OBF_TRY(launch_gather(m, nullptr, V, idx, n_keep, max_budget, nullptr, V_out, st, fro_part));
+    kside = side_fork(st);
+    OBF_TRY(launch_gather(m, K, nullptr, idx, n_keep, max_budget, K_out, nullptr, kside ? kside : st, nullptr));
+  } else {
+    OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part));
+  }
   int32_t min_budget = budget;
   if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < mb.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
   OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
                           basis_started, min_budget));
+  if (kside) OBF_TRY(side_join(st));
   return OBF_OK;
 }
 

@@ -882,6 +882,25 @@ static SideStream* side_stream() {
   return &ctx[nctx++];
 }
 
+hipStream_t side_fork(hipStream_t st) {
+  SideStream* side = side_stream();
+  if (!side) return nullptr;
+  if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  return side->stream;
+}
+
+obf_status_t side_join(hipStream_t st) {
+  SideStream* side = side_stream();
+  if (!side || hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess) {
+    set_error("joining the side stream failed");
+    return OBF_ERR_HIP;
+  }
+  return OBF_OK;
+}
+
 // True when the basis of the retained span may be computed beside the gather and the statistics pass: with every
 // budget below the head dimension each head with deleted rows is active whatever its basis turns out to be.
 static bool basis_overlaps(const Dims& m, int32_t max_budget, int32_t rank) { return rank > 0 && max_budget < m.d; }

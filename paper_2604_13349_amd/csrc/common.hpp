@@ -191,6 +191,11 @@ obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws
                                      const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t* idx,
                                      int32_t* n_keep, const void* K, const void* Q, const double* row_lse,
                                      hipStream_t st);
+// The library's second stream (one per host thread and device).  side_fork makes it wait for everything queued on st
+// so far and returns it (nullptr: none available, keep everything on st); side_join makes st wait for everything
+// queued on it since.  One fork/join pair may be open at a time.
+hipStream_t side_fork(hipStream_t st);
+obf_status_t side_join(hipStream_t st);
 // Optional early start of the retained-span bases on a second stream (forked from st), for shapes where they
 // do not depend on the gather; *started is then passed on to launch_backfill as basis_started.
 obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
