@@ -22,6 +22,18 @@ Readings taken where the paper leaves a choice (each is listed in the design not
   * epsilon = 1e-12 exactly where Eq. 4 and Eq. 6 place it.
 The layerwise granularity of the same retention rule (one index set per layer) is
 compress_layer.
+The ablations of App. D are the flags of Variant; readings taken there:
+  * No Projection: R = V_del, so neither the retained basis nor the "retained
+    span is everything" skip takes part; the rest of Eq. 4-7 is unchanged.
+  * Max-P: k = rank R (every direction of the residual's row space).
+  * No Scaling: delta = Delta (the demand ratio of Eq. 6 is left out).
+  * Naive Aggregation: delta = unweighted mean of the deleted value rows, no
+    projection, no subspace, no scaling.
+  * Attn-inject: V*_t = V_t + B w_t delta, w_t = A_t / (sum_keep A + eps), with
+    delta the Eq. 6 vector ("alpha delta" in Alg. 3's naming).
+  * EVR-adaptive: k* = smallest k whose leading squared singular values of R
+    reach the fraction tau of their total; never above rank R.
+  The per-token variant is not stated precisely enough to restate and is absent.
 Pinned by tests/test_oracle_pins.py (closed forms, brute force, invariants).
 Parity unpinned: absolute values on realistic caches (the paper prints no worked
 numeric example); those rest on invariants only.
@@ -118,6 +130,17 @@ def orth_rowspace(V_keep: np.ndarray):
 
 
 # ----------------------------------------------------------------------------- Eq. 3-7
+@dataclass(frozen=True)
+class Variant:
+    """One ablation of App. D per flag; the default is the method of Sec. 4.4."""
+    no_projection: bool = False      # component ablation "No Projection"
+    subspace: str = "rank"           # "rank": top pca_rank directions; "all": Max-P; "evr": EVR-adaptive rank
+    evr_tau: float = 0.35
+    no_scaling: bool = False         # component ablation "No Scaling"
+    naive: bool = False              # component ablation "Naive Aggregation"
+    attn_inject: bool = False        # alternative design "Attn-inject"
+
+
 @dataclass
 class HeadDiag:
     n_keep: int = 0
@@ -137,6 +160,7 @@ class HeadDiag:
     res_sigma_margin: float = np.inf
     res_sigma_rel: Optional[np.ndarray] = field(default=None, repr=False)   # sigma_i/sigma_1 of R, i < pca_rank
     res_thr_rel: float = 0.0            # rank threshold of R relative to sigma_1
+    evr_margin: float = np.inf          # EVR-adaptive rank: distance of the nearest cumulative ratio from tau
     delta: Optional[np.ndarray] = field(default=None, repr=False)
 
 
@@ -151,7 +175,15 @@ def _margin(sigma: np.ndarray, rows: int, cols: int, first: Optional[int] = None
     return float(m.min())
 
 
-def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int):
+def inject(V_keep: np.ndarray, A_keep: np.ndarray, a_keep: float, delta: np.ndarray, variant: Variant) -> np.ndarray:
+    """Eq. 7 (the same offset on every retained row), or the attention-weighted shares of App. D."""
+    if variant.attn_inject:
+        w = A_keep / (a_keep + EPS)
+        return V_keep + V_keep.shape[0] * w[:, None] * delta[None, :]
+    return V_keep + delta[None, :]
+
+
+def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int, variant: Variant = Variant()):
     """OBF for one head (Eq. 2-7, Alg. 3).  V [N, d] float64, A [N], idx ascending.
 
     Returns (V_star [B, d] float64 before output rounding, HeadDiag).
@@ -169,10 +201,19 @@ def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int):
         # rank 0 is the plain selector (App. G); empty P_del is skipped (Alg. 3)
         return V_keep.copy(), diag
 
-    Q, s_keep = orth_rowspace(V_keep)                      # Eq. 2
-    diag.r_keep = Q.shape[1]
-    diag.keep_sigma_margin = _margin(s_keep, idx.size, d)
     V_del = V[dele]
+    if variant.naive:
+        delta = V_del.mean(axis=0)
+        diag.delta = delta
+        diag.ivn = float(np.linalg.norm(delta))
+        diag.skipped = 0
+        return inject(V_keep, A[idx], diag.a_keep, delta, variant), diag
+    if variant.no_projection:
+        Q = np.zeros((d, 0))
+    else:
+        Q, s_keep = orth_rowspace(V_keep)                  # Eq. 2
+        diag.keep_sigma_margin = _margin(s_keep, idx.size, d)
+    diag.r_keep = Q.shape[1]
     if diag.r_keep == d:
         # retained span is all of R^d: the residual is identically zero
         diag.pcr = 1.0
@@ -191,9 +232,18 @@ def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int):
 
     _, sR, VtR = np.linalg.svd(R, full_matrices=False)     # rows of VtR: right singular vectors
     rankR = numerical_rank(sR, R.shape[0], d)
-    k = min(int(rank), rankR)
-    diag.res_sigma_margin = _margin(sR, R.shape[0], d, first=int(rank))   # only these decide k
-    diag.res_sigma_rel = sR[:int(rank)] / sR[0] if sR[0] > 0 else None
+    want = int(rank)
+    if variant.subspace == "all":
+        want = d
+    elif variant.subspace == "evr":
+        cum = np.cumsum(sR ** 2) / (sR ** 2).sum()
+        want = int(np.argmax(cum >= variant.evr_tau)) + 1 if cum[-1] >= variant.evr_tau else sR.size
+        diag.evr_margin = float(np.abs(cum - variant.evr_tau).min())
+    elif variant.subspace != "rank":
+        raise ValueError(variant.subspace)
+    k = min(want, rankR)
+    diag.res_sigma_margin = _margin(sR, R.shape[0], d, first=want)        # only these decide k
+    diag.res_sigma_rel = sR[:want] / sR[0] if sR[0] > 0 else None
     diag.res_thr_rel = max(R.shape[0], d) * RANK_EPS
     if k == 0:
         return V_keep.copy(), diag
@@ -206,11 +256,11 @@ def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int):
     w = A[dele] / (diag.a_del + EPS)                       # Eq. 4
     rbar = w @ R
     Delta = (rbar @ C.T) @ C                               # Eq. 5
-    delta = diag.a_del / (diag.a_keep + EPS) * Delta       # Eq. 6
+    delta = Delta if variant.no_scaling else diag.a_del / (diag.a_keep + EPS) * Delta       # Eq. 6
     diag.delta = delta
     diag.ivn = float(np.linalg.norm(delta))
     diag.skipped = 0
-    return V_keep + delta[None, :], diag                   # Eq. 7
+    return inject(V_keep, A[idx], diag.a_keep, delta, variant), diag                         # Eq. 7
 
 
 # ----------------------------------------------------------------------------- one head, whole relay
@@ -225,7 +275,7 @@ class HeadResult:
 
 
 def compress_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, rank: int,
-                  dtype: str) -> HeadResult:
+                  dtype: str, variant: Variant = Variant()) -> HeadResult:
     """score -> TopK_B -> gather -> OBF for one (layer, KV head).
 
     K_io, V_io [N, d]; Q_io [group, window, d] (or [rows, d]); all in the I/O dtype.
@@ -235,7 +285,7 @@ def compress_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: 
     Qr = decode(Q_io, dtype).reshape(-1, K.shape[1])
     A = attention_mass(K, Qr)
     idx = select_topk(A, budget)
-    V_star, diag = backfill(V, A, idx, rank)
+    V_star, diag = backfill(V, A, idx, rank, variant)
     if diag.skipped:
         V_out = np.asarray(V_io)[idx].copy()               # identity: a bit copy, not a re-rounding
     else:
@@ -244,7 +294,7 @@ def compress_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: 
 
 
 def compress_relay(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budgets: np.ndarray, rank: int,
-                   group: int, dtype: str, heads=None):
+                   group: int, dtype: str, heads=None, variant: Variant = Variant()):
     """All (layer, KV head) pairs of a cache in the canonical layout.
 
     K_io, V_io [L, H, N, d]; Q_io [L, H*group, W, d]; budgets int [L, H].
@@ -255,13 +305,13 @@ def compress_relay(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budgets
     todo = heads if heads is not None else [(l, h) for l in range(L) for h in range(H)]
     for (l, h) in todo:
         out[(l, h)] = compress_head(K_io[l, h], V_io[l, h], Q_io[l, h * group:(h + 1) * group],
-                                    int(budgets[l, h]), rank, dtype)
+                                    int(budgets[l, h]), rank, dtype, variant)
     return out
 
 
 # ----------------------------------------------------------------------------- layerwise selector (Sec. 4.3.2)
 def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, rank: int,
-                   group: int, dtype: str):
+                   group: int, dtype: str, variant: Variant = Variant()):
     """Layerwise granularity of the retention rule (Sec. 4.3.2; the "L" and "L-OBF" methods of Sec. 5):
     one index set per layer, TopK_B of the attention mass summed over the layer's heads, shared by
     all of them; Orthogonal BackFill then runs per head exactly as in the headwise case, with that
@@ -286,7 +336,7 @@ def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget:
     heads = []
     for h in range(H):
         V = decode(V_io[h], dtype)
-        V_star, diag = backfill(V, masses[h], idx, rank)
+        V_star, diag = backfill(V, masses[h], idx, rank, variant)
         if diag.skipped:
             V_out = np.asarray(V_io[h])[idx].copy()
         else:

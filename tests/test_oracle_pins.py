@@ -457,3 +457,135 @@ def test_layerwise_backfill_uses_each_heads_own_mass():
     rbar = (A[dele] / (a_del + 1e-12)) @ R
     delta = a_del / (a_keep + 1e-12) * (rbar @ c) * c
     assert np.allclose(heads[h].V_star, Vd[keep] + delta[None, :], rtol=1e-9, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- App. D: ablation variants
+def _variant_case(seed=41, N=60, d=16, B=6):
+    r = rng(seed)
+    V = r.standard_normal((N, d))
+    A = r.random(N) + 0.05
+    idx = np.sort(r.choice(N, B, replace=False))
+    return V, A, idx
+
+
+def test_no_projection_equals_default_when_deleted_rows_are_orthogonal_to_the_retained_span():
+    # retained rows live in the first 4 coordinates, deleted rows in the others: Eq. 3 removes nothing
+    r = rng(42)
+    N, d = 30, 12
+    idx = np.array([2, 9, 17, 25])
+    V = np.zeros((N, d))
+    V[:, 4:] = r.standard_normal((N, 8))
+    V[idx] = 0.0
+    V[idx, :4] = r.standard_normal((4, 4))
+    A = r.random(N) + 0.1
+    a, da = O.backfill(V, A, idx, 3)
+    b, db = O.backfill(V, A, idx, 3, O.Variant(no_projection=True))
+    assert da.skipped == 0 and db.skipped == 0 and db.r_keep == 0
+    assert np.allclose(a, b, rtol=0, atol=1e-13)
+
+
+def test_no_projection_by_hand_where_the_default_has_nothing_to_inject():
+    # every deleted row is a multiple of e0 and e0 is a retained row: R = 0 for the method, R = V_del without Eq. 3.
+    # Then C = e0, rbar = sum_j w_j c_j e0, Delta = rbar, delta = a_del / a_keep * rbar.
+    d = 4
+    V = np.zeros((5, d))
+    V[0, 0] = 1.0; V[1, 1] = 1.0                                   # retained
+    c = np.array([2.0, -1.0, 4.0])
+    V[2:, 0] = c                                                  # deleted
+    A = np.array([0.3, 0.2, 0.1, 0.15, 0.25])
+    idx = np.array([0, 1])
+    out, dg = O.backfill(V, A, idx, 1)
+    assert dg.skipped == 1 and np.array_equal(out, V[idx])
+    out, dg = O.backfill(V, A, idx, 1, O.Variant(no_projection=True))
+    a_del, a_keep = 0.5, 0.5
+    coef = (0.1 * 2.0 + 0.15 * -1.0 + 0.25 * 4.0) / a_del * (a_del / a_keep)
+    assert dg.skipped == 0 and dg.k_used == 1
+    assert np.allclose(out - V[idx], np.array([[coef, 0, 0, 0]] * 2), rtol=0, atol=1e-11)
+
+
+def test_max_p_injects_the_whole_weighted_residual_mean():
+    V, A, idx = _variant_case()
+    out, dg = O.backfill(V, A, idx, 2, O.Variant(subspace="all"))
+    dele = np.setdiff1d(np.arange(V.shape[0]), idx)
+    # residual through a least-squares fit instead of an orthonormal basis
+    coef, *_ = np.linalg.lstsq(V[idx].T, V[dele].T, rcond=None)
+    R = V[dele] - (V[idx].T @ coef).T
+    rbar = (A[dele] / A[dele].sum()) @ R
+    want = A[dele].sum() / A[idx].sum() * rbar
+    assert dg.k_used == V.shape[1] - idx.size
+    assert np.allclose(out - V[idx], np.broadcast_to(want, (idx.size, V.shape[1])), rtol=0, atol=1e-11)
+
+
+def test_no_scaling_differs_from_the_method_by_exactly_the_demand_ratio():
+    V, A, idx = _variant_case(43)
+    a, da = O.backfill(V, A, idx, 3)
+    b, db = O.backfill(V, A, idx, 3, O.Variant(no_scaling=True))
+    dele = np.setdiff1d(np.arange(V.shape[0]), idx)
+    ratio = A[dele].sum() / A[idx].sum()
+    assert abs(ratio - 1.0) > 0.5                                  # the flag matters on this case
+    assert np.allclose(a - V[idx], ratio * (b - V[idx]), rtol=0, atol=1e-12)
+    assert abs(da.ivn - ratio * db.ivn) < 1e-12
+
+
+def test_naive_aggregation_by_hand():
+    V = np.array([[1.0, 0.0, 0.0], [0.0, 2.0, 0.0], [3.0, 3.0, 3.0], [1.0, -1.0, 5.0], [-4.0, 4.0, 1.0]])
+    A = np.array([0.5, 0.1, 0.2, 0.1, 0.1])
+    idx = np.array([0, 1])
+    out, dg = O.backfill(V, A, idx, 1, O.Variant(naive=True))
+    mean = np.array([0.0, 2.0, 3.0])                               # plain average of rows 2, 3, 4; A plays no part
+    assert dg.skipped == 0 and dg.k_used == 0
+    assert np.allclose(out, V[idx] + mean, rtol=0, atol=1e-15)
+    assert abs(dg.ivn - math.sqrt(13.0)) < 1e-14
+
+
+def test_attn_inject_shares_the_same_total_in_proportion_to_mass():
+    V, A, idx = _variant_case(44)
+    A[idx[0]] = A[idx[1]]                                          # two retained rows with equal mass
+    a, da = O.backfill(V, A, idx, 2)
+    b, db = O.backfill(V, A, idx, 2, O.Variant(attn_inject=True))
+    assert np.allclose(da.delta, db.delta, rtol=0, atol=0)         # only Eq. 7 differs
+    add = b - V[idx]
+    assert np.allclose(add.sum(axis=0), idx.size * da.delta, rtol=1e-11, atol=1e-13)   # same total as B equal shares
+    assert np.allclose(add[0], add[1], rtol=0, atol=1e-15)
+    share = A[idx] / A[idx].sum()
+    for t in range(idx.size):
+        assert np.allclose(add[t], idx.size * share[t] * da.delta, rtol=1e-11, atol=1e-13)
+    # with equal mass on every retained row it is Eq. 7 again
+    A2 = A.copy(); A2[idx] = 0.125
+    a2, _ = O.backfill(V, A2, idx, 2)
+    b2, _ = O.backfill(V, A2, idx, 2, O.Variant(attn_inject=True))
+    assert np.allclose(a2, b2, rtol=0, atol=1e-10)              # eps of the share's denominator is all that differs
+
+
+@pytest.mark.parametrize("tau,k_want", [(0.35, 1), (0.5, 2), (0.7, 3), (0.9, 4), (0.96, 5)])
+def test_evr_adaptive_rank_on_known_singular_values(tau, k_want):
+    # deleted rows sigma_j e_{2+j}, retained rows e_0, e_1: R = V_del with squared singular values 4, 3, 2, 1, 0.5
+    # cumulative fractions of 10.5: 0.381, 0.667, 0.857, 0.952, 1
+    d = 8
+    V = np.zeros((7, d))
+    V[0, 0] = 1.0; V[1, 1] = 1.0
+    s2 = [4.0, 3.0, 2.0, 1.0, 0.5]
+    for j, v in enumerate(s2):
+        V[2 + j, 2 + j] = math.sqrt(v)
+    A = np.full(7, 1.0 / 7)
+    out, dg = O.backfill(V, A, np.array([0, 1]), 1, O.Variant(subspace="evr", evr_tau=tau))
+    assert dg.k_used == k_want
+    assert abs(dg.revr - sum(s2[:k_want]) / 10.5) < 1e-12
+    # Delta keeps exactly the first k_want coordinates of rbar = (1/5) sum_j sigma_j e_{2+j}; demand ratio 5/2
+    want = np.zeros(d)
+    for j in range(k_want):
+        want[2 + j] = 0.2 * math.sqrt(s2[j]) * 2.5
+    assert np.allclose(out[0], V[0] + want, rtol=0, atol=1e-10)   # the eps of Eq. 4 and Eq. 6 is of relative size 4e-12 here
+
+
+def test_variants_leave_the_default_untouched_and_combine():
+    V, A, idx = _variant_case(45)
+    a, _ = O.backfill(V, A, idx, 2)
+    b, _ = O.backfill(V, A, idx, 2, O.Variant())
+    assert np.array_equal(a, b)
+    # naive aggregation with attention-weighted shares: both replacements act
+    c, dg = O.backfill(V, A, idx, 2, O.Variant(naive=True, attn_inject=True))
+    dele = np.setdiff1d(np.arange(V.shape[0]), idx)
+    mean = V[dele].sum(axis=0) / dele.size
+    share = A[idx] / A[idx].sum()
+    assert np.allclose(c - V[idx], idx.size * share[:, None] * mean[None, :], rtol=1e-11, atol=1e-13)
