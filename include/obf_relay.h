@@ -145,6 +145,50 @@ obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* 
                                           float* scores_out, float* delta_out, obf_diag_t* diag,
                                           void* ws, size_t ws_bytes, void* stream);
 
+/* Ablation variants of App. D: every field switches one step of Orthogonal BackFill off or replaces it; all zero
+ * is the method of Sec. 4.4.  The fields combine freely (naive_aggregation makes the first four irrelevant).
+ *   no_projection      "No Projection": Eq. 3 is skipped, R = V_del; the basis of the retained span is not built and
+ *                      a head is processed whatever that span is (diag.r_keep = 0, pcr = pc = 0, rcr = 1).
+ *   subspace           OBF_SUBSPACE_RANK: the top `rank` right singular directions of R (the method);
+ *                      OBF_SUBSPACE_ALL: "Max-P", every direction of R's row space (k = rank R);
+ *                      OBF_SUBSPACE_EVR: "EVR-adaptive", the smallest k whose leading squared singular values
+ *                      reach the fraction evr_tau of their total (never above rank R); `rank` must still be > 0.
+ *   evr_tau            in (0, 1], read only with OBF_SUBSPACE_EVR.
+ *   no_scaling         "No Scaling": delta = Delta, without the demand ratio of Eq. 6.
+ *   naive_aggregation  "Naive Aggregation": delta = unweighted mean of the deleted value rows (no Eq. 3-6).
+ *   attn_inject        "Attn-inject": row t of V_out receives n_keep * A_t / (sum of A over the retained rows + eps)
+ *                      times delta instead of delta (Eq. 7 replaced); delta_out is still delta.
+ * `rank` = 0 is plain eviction under every variant.  The per-token alternative of App. D is not provided. */
+#define OBF_SUBSPACE_RANK 0
+#define OBF_SUBSPACE_ALL 1
+#define OBF_SUBSPACE_EVR 2
+typedef struct obf_variant_t {
+  int32_t no_projection;
+  int32_t subspace;
+  float evr_tau;
+  int32_t no_scaling;
+  int32_t naive_aggregation;
+  int32_t attn_inject;
+} obf_variant_t;
+
+/* obf_backfill with an ablation variant (App. D); variant == NULL is obf_backfill itself.  Arguments, layouts,
+ * ownership and error behaviour as obf_backfill; an unknown subspace value or evr_tau outside (0, 1] is
+ * OBF_ERR_INVALID_ARG. */
+obf_status_t obf_backfill_variant(const obf_shape_t* shape, const void* V, const float* scores, const int32_t* idx,
+                                  const int32_t* n_keep, int32_t max_budget, int32_t rank,
+                                  const obf_variant_t* variant, void* V_out, float* delta_out, obf_diag_t* diag,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/* The fused relay compression with an ablation variant (App. D ablates L-OBF: layerwise != 0 selects the per-layer
+ * retention rule of obf_compress_relay_layerwise, 0 the headwise one of obf_compress_relay; budgets_host is per
+ * layer or per head accordingly).  variant == NULL is the corresponding plain call. */
+obf_status_t obf_compress_relay_variant(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                        const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                        int32_t layerwise, const obf_variant_t* variant,
+                                        void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                        float* scores_out, float* delta_out, obf_diag_t* diag,
+                                        void* ws, size_t ws_bytes, void* stream);
+
 /* Profiling aid (tracing of the path's own kernels with HIP events on the caller's stream).
  * obf_profile_enable(stage) makes every later call on this thread bracket the launch of that
  * internal stage's kernel with a pair of events; stage -1 switches it off.  obf_profile_read

@@ -31,6 +31,22 @@ class _Shape(C.Structure):
                 ("n_tokens", C.c_int32), ("window", C.c_int32), ("dtype", C.c_int32)]
 
 
+class _Variant(C.Structure):
+    """obf_variant_t."""
+    _fields_ = [("no_projection", C.c_int32), ("subspace", C.c_int32), ("evr_tau", C.c_float),
+                ("no_scaling", C.c_int32), ("naive_aggregation", C.c_int32), ("attn_inject", C.c_int32)]
+
+
+SUBSPACE = {"rank": 0, "all": 1, "evr": 2}
+
+
+def make_variant(no_projection=False, subspace="rank", evr_tau=0.35, no_scaling=False, naive_aggregation=False,
+                 attn_inject=False) -> _Variant:
+    """obf_variant_t from keywords (subspace by its name or its number)."""
+    code = SUBSPACE[subspace] if isinstance(subspace, str) else int(subspace)
+    return _Variant(int(no_projection), code, float(evr_tau), int(no_scaling), int(naive_aggregation), int(attn_inject))
+
+
 def lib_path() -> str:
     return os.environ.get("OBF_RELAY_LIB") or os.path.join(_HERE, _LIB_NAME)
 
@@ -63,6 +79,11 @@ def load_library():
     lib.obf_compress_relay.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.obf_compress_relay_layerwise.restype = C.c_int
     lib.obf_compress_relay_layerwise.argtypes = lib.obf_compress_relay.argtypes
+    vr = C.POINTER(_Variant)
+    lib.obf_backfill_variant.restype = C.c_int
+    lib.obf_backfill_variant.argtypes = [sp, vp, vp, vp, vp, i32, i32, vr, vp, vp, vp, vp, sz, vp]
+    lib.obf_compress_relay_variant.restype = C.c_int
+    lib.obf_compress_relay_variant.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, i32, vr, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.obf_profile_enable.restype = C.c_int
     lib.obf_profile_enable.argtypes = [i32]
     lib.obf_profile_read.restype = C.c_int
@@ -191,18 +212,25 @@ def gather(shape: _Shape, K, V, idx, n_keep, K_out=None, V_out=None):
     return K_out, V_out
 
 
-def backfill(shape: _Shape, V, scores, idx, n_keep, rank: int, V_out, delta_out=None, diag=None, ws=None):
+def backfill(shape: _Shape, V, scores, idx, n_keep, rank: int, V_out, delta_out=None, diag=None, ws=None,
+             variant: Optional[_Variant] = None):
     max_budget = idx.shape[-1]
     ws = _ws(shape, max_budget, rank, ws, V.device)
+    if variant is not None:
+        _check(load_library().obf_backfill_variant(C.byref(shape), _ptr(V), _ptr(scores), _ptr(idx), _ptr(n_keep), max_budget,
+                                                   rank, C.byref(variant), _ptr(V_out), _ptr(delta_out), _ptr(diag),
+                                                   _ptr(ws), ws.numel(), _stream()))
+        return V_out
     _check(load_library().obf_backfill(C.byref(shape), _ptr(V), _ptr(scores), _ptr(idx), _ptr(n_keep), max_budget, rank,
                                        _ptr(V_out), _ptr(delta_out), _ptr(diag), _ptr(ws), ws.numel(), _stream()))
     return V_out
 
 
 def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max_budget: Optional[int] = None,
-                   out=None, ws=None, want_scores=False, want_delta=False, want_diag=False, layerwise=False):
+                   out=None, ws=None, want_scores=False, want_delta=False, want_diag=False, layerwise=False,
+                   variant: Optional[_Variant] = None):
     """Fused relay compression.  Returns a dict of output tensors (device).  layerwise: one index set per layer
-    (budgets then holds one entry per layer)."""
+    (budgets then holds one entry per layer).  variant: an obf_variant_t from make_variant (the variant entry point)."""
     sh = shape_of(K, Qwin)
     L, H, d, N = sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.n_tokens
     keep, bptr = _budgets_arg(budgets)
@@ -225,6 +253,13 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
     if want_diag and "diag" not in o:
         o["diag"] = torch.empty((L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
     ws = _ws(sh, max_budget, rank, ws, dev)
+    if variant is not None:
+        _check(load_library().obf_compress_relay_variant(
+            C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, int(bool(layerwise)), C.byref(variant),
+            _ptr(o["K_out"]), _ptr(o["V_out"]), _ptr(o["idx"]), _ptr(o["n_keep"]), _ptr(o.get("scores")), _ptr(o.get("delta")),
+            _ptr(o.get("diag")), _ptr(ws), ws.numel(), _stream()))
+        o["ws"] = ws
+        return o
     fn = load_library().obf_compress_relay_layerwise if layerwise else load_library().obf_compress_relay
     _check(fn(
         C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]),

@@ -201,8 +201,29 @@ obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* 
                          (hipStream_t)stream);
 }
 
-// Shared body of the two fused calls; layerwise != 0 selects the per-layer retention rule.
-static obf_status_t compress_relay_impl(int layerwise, const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+// obf_variant_t (nullable) checked and packed for the kernels.
+static obf_status_t make_variant(const obf_variant_t* v, Variant* out) {
+  *out = Variant();
+  if (!v) return OBF_OK;
+  if (v->subspace != OBF_SUBSPACE_RANK && v->subspace != OBF_SUBSPACE_ALL && v->subspace != OBF_SUBSPACE_EVR) {
+    set_error("variant: unknown subspace rule");
+    return OBF_ERR_INVALID_ARG;
+  }
+  if (v->subspace == OBF_SUBSPACE_EVR && !(v->evr_tau > 0.f && v->evr_tau <= 1.f)) {
+    set_error("variant: evr_tau must lie in (0, 1]");
+    return OBF_ERR_INVALID_ARG;
+  }
+  if (v->no_projection) out->flags |= VF_NO_PROJECTION;
+  if (v->subspace == OBF_SUBSPACE_ALL) out->flags |= VF_SUBSPACE_ALL;
+  if (v->subspace == OBF_SUBSPACE_EVR) { out->flags |= VF_SUBSPACE_EVR; out->evr_tau = v->evr_tau; }
+  if (v->no_scaling) out->flags |= VF_NO_SCALING;
+  if (v->naive_aggregation) out->flags |= VF_NAIVE;
+  if (v->attn_inject) out->flags |= VF_ATTN_INJECT;
+  return OBF_OK;
+}
+
+// Shared body of the fused calls; layerwise != 0 selects the per-layer retention rule.
+static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
                                         const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
                                         void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                         float* scores_out, float* delta_out, obf_diag_t* diag,
@@ -232,7 +253,8 @@ static obf_status_t compress_relay_impl(int layerwise, const obf_shape_t* shape,
   double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
   // small budgets: the bases of the retained spans start now on a second stream, beside the gather
   bool basis_started = false;
-  OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
+  if (!var.skips_basis())
+    OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
   // Large budgets: nothing downstream reads K_out, so the retained K rows are copied on the second stream once the
   // V rows (which the certificate waits for) are through, beside the latency-bound per-head kernels.
   hipStream_t kside = nullptr;
@@ -246,7 +268,7 @@ static obf_status_t compress_relay_impl(int layerwise, const obf_shape_t* shape,
   int32_t min_budget = budget;
   if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < mb.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
   OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
-                          basis_started, min_budget));
+                          basis_started, min_budget, var));
   if (kside) OBF_TRY(side_join(st));
   return OBF_OK;
 }
@@ -256,7 +278,7 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
                                 void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                 float* scores_out, float* delta_out, obf_diag_t* diag,
                                 void* ws, size_t ws_bytes, void* stream) {
-  return compress_relay_impl(0, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+  return compress_relay_impl(0, Variant(), shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
                              scores_out, delta_out, diag, ws, ws_bytes, stream);
 }
 
@@ -265,8 +287,37 @@ obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* 
                                           void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                           float* scores_out, float* delta_out, obf_diag_t* diag,
                                           void* ws, size_t ws_bytes, void* stream) {
-  return compress_relay_impl(1, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+  return compress_relay_impl(1, Variant(), shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
                              scores_out, delta_out, diag, ws, ws_bytes, stream);
+}
+
+obf_status_t obf_compress_relay_variant(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                        const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                        int32_t layerwise, const obf_variant_t* variant,
+                                        void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                        float* scores_out, float* delta_out, obf_diag_t* diag,
+                                        void* ws, size_t ws_bytes, void* stream) {
+  Variant var;
+  OBF_TRY(make_variant(variant, &var));
+  return compress_relay_impl(layerwise != 0, var, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx,
+                             n_keep, scores_out, delta_out, diag, ws, ws_bytes, stream);
+}
+
+obf_status_t obf_backfill_variant(const obf_shape_t* shape, const void* V, const float* scores, const int32_t* idx,
+                                  const int32_t* n_keep, int32_t max_budget, int32_t rank,
+                                  const obf_variant_t* variant, void* V_out, float* delta_out, obf_diag_t* diag,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  Variant var;
+  OBF_TRY(make_variant(variant, &var));
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(V); OBF_NONNULL(scores); OBF_NONNULL(idx); OBF_NONNULL(n_keep); OBF_NONNULL(V_out);
+  if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }
+  if (rank < 0) { set_error("rank < 0"); return OBF_ERR_INVALID_ARG; }
+  Dims m = make_dims(shape);
+  Workspace w = carve(m, max_budget, rank);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  return launch_backfill(m, w, (char*)ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag,
+                         (hipStream_t)stream, nullptr, false, -1, var);
 }
 
 }  // extern "C"

@@ -347,6 +347,31 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
 }
 
 // ------------------------------------------------------------------------------------------------
+// Head states for the variants of App. D that do not use the retained span (No Projection, Naive Aggregation): the
+// demand sums of Eq. 6, r_keep = 0, and every head with retained and deleted rows is active.
+__global__ __launch_bounds__(KB_THREADS) void k_bf_plain_state(const float* __restrict__ scores, const int32_t* __restrict__ idx,
+                                                               const int32_t* __restrict__ n_keep, int N, int max_budget,
+                                                               int rank, HeadState* __restrict__ state) {
+  __shared__ double red[KB_WAVES];
+  const int head = blockIdx.x;
+  const int n = n_keep[head];
+  const float* sc = scores + (size_t)head * N;
+  const int32_t* id = idx + (size_t)head * max_budget;
+  double pk = 0.0, pt = 0.0;
+  for (int i = threadIdx.x; i < n; i += KB_THREADS) pk += (double)sc[id[i]];
+  for (int i = threadIdx.x; i < N; i += KB_THREADS) pt += (double)sc[i];
+  const double a_keep = block_sum(pk, red);
+  const double a_tot = block_sum(pt, red);
+  if (threadIdx.x == 0) {
+    HeadState s;
+    s.a_keep = a_keep; s.a_del = fmax(a_tot - a_keep, 0.0); s.n_keep = n; s.n_del = N - n; s.r_keep = 0;
+    s.active = (rank > 0 && n > 0 && N - n > 0) ? 1 : 0;
+    s.k_used = 0; s.pad = 0; s.rcr = 0.f; s.ivn = 0.f;
+    state[head] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // del_stats: partial V_del^T V_del, sum_j A_j v_j and ||V_del||^2 over one chunk of tokens
 constexpr int DS_THREADS = 256;
 constexpr int DS_TOK = 32;
@@ -439,7 +464,9 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
                                                             const float* __restrict__ gram_part,
                                                             float* __restrict__ mats, float* __restrict__ delta,
                                                             float* __restrict__ delta_out, obf_diag_t* __restrict__ diag,
-                                                            T* __restrict__ V_out, int max_budget, int cls) {
+                                                            T* __restrict__ V_out, int max_budget, int cls,
+                                                            const float* __restrict__ scores,
+                                                            const int32_t* __restrict__ idx, int vflags, float evr_tau) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
@@ -459,17 +486,33 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   float rcr = 0.f, ivn = 0.f, pcr = 0.f, pc = 0.f, revr = 0.f;
   int k_used = 0;
   const int tid = threadIdx.x;
+  const bool naive = (vflags & VF_NAIVE) != 0;
   {
     // Two launches share the heads: the first has LDS for one d x d matrix (two workgroups per CU) and takes
     // every head whose complement is small enough for T and W to fit there, the second takes the rest.
-    const int m0 = st.active ? d - st.r_keep : 0;
+    const int m0 = (st.active && !naive) ? d - st.r_keep : 0;
     const int mm0 = m0 + (m0 & 1);
     const int big = 2 * mm0 * (mm0 + 1) > d * ld;
     if (big != cls) return;
   }
 
   BF_STAMP(1, 0);
-  if (st.active) {
+  if (st.active && naive) {
+    // Naive Aggregation (App. D): the plain mean of the deleted value rows, none of Eq. 3-6
+    const size_t pstride = gram_stride(d);
+    const float* gp = gram_part + (size_t)head * nstat * pstride;
+    if (tid < d) {
+      float s = 0.f;
+      for (int c = 0; c < nstat; ++c) s += gp[c * pstride + d * d + d + tid];
+      uvec[tid] = s / (float)st.n_del;
+    }
+    __syncthreads();
+    if (tid == 0) { double s = 0.0; for (int c = 0; c < d; ++c) s += (double)uvec[c] * uvec[c]; s_off = (float)sqrt(s); }
+    __syncthreads();
+    ivn = s_off;
+    skipped = 0;
+  }
+  if (st.active && !naive) {
     const int r = st.r_keep;
     int m = d - r;                                             // dimension of the orthogonal complement
     const float* Qb = basis + (size_t)head * d * d;            // [r][d] orthonormal rows
@@ -782,7 +825,18 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         for (int j = 0; j < m; ++j) if (lamv[order[j]] > lmax * floor_rel) ++rankR;
         const int cap = min(min(st.n_del, d - r), d);
         if (rankR > cap) rankR = cap;
-        s_k = min(rank, rankR);
+        int want = rank;
+        if (vflags & VF_SUBSPACE_ALL) want = d;                  // Max-P (App. D): every direction of R
+        if (vflags & VF_SUBSPACE_EVR) {                          // EVR-adaptive rank (App. D)
+          double tot = 0.0, cum = 0.0;
+          for (int j = 0; j < m; ++j) tot += (double)fmaxf(lamv[order[j]], 0.f);
+          want = m;
+          for (int j = 0; j < m; ++j) {
+            cum += (double)fmaxf(lamv[order[j]], 0.f);
+            if (cum >= (double)evr_tau * tot) { want = j + 1; break; }
+          }
+        }
+        s_k = min(want, rankR);
         double top = 0.0;                                        // explained variance of the directions used (App. K.2)
         for (int j = 0; j < s_k; ++j) top += (double)lamv[order[j]];
         s_off = (float)(top / ((double)res2 + 1e-12));
@@ -816,7 +870,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         if (tid < d) {
           float s = 0.f;
           for (int t = 0; t < m; ++t) s = fmaf(Zg[(size_t)t * d + tid], lamv[t], s);
-          const double alpha = st.a_del / (st.a_keep + kEps);          // Eq. 6
+          const double alpha = (vflags & VF_NO_SCALING) ? 1.0 : st.a_del / (st.a_keep + kEps);          // Eq. 6
           uvec[tid] = (float)(alpha * ((double)s / (st.a_del + kEps)));
         }
         __syncthreads();
@@ -849,13 +903,24 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       diag[head] = dg;
     }
   }
-  // Eq. 7: the one offset is added to every retained value row (rounded once to the storage type)
+  // Eq. 7: the one offset is added to every retained value row (rounded once to the storage type); under Attn-inject
+  // (App. D) row t receives n_keep A_t / (a_keep + eps) times the offset instead
   if (!skipped && V_out) {
     const int total = st.n_keep * d;
     T* base = V_out + (size_t)head * max_budget * d;
-    for (int e = tid; e < total; e += FN_THREADS) {
-      T* p = base + e;
-      Elem<T>::store(p, Elem<T>::load(p) + uvec[e % d]);
+    if (vflags & VF_ATTN_INJECT) {
+      const float per_mass = (float)((double)st.n_keep / (st.a_keep + kEps));
+      const float* sc = scores + (size_t)head * N;
+      const int32_t* id = idx + (size_t)head * max_budget;
+      for (int e = tid; e < total; e += FN_THREADS) {
+        T* p = base + e;
+        Elem<T>::store(p, fmaf(per_mass * sc[id[e / d]], uvec[e % d], Elem<T>::load(p)));
+      }
+    } else {
+      for (int e = tid; e < total; e += FN_THREADS) {
+        T* p = base + e;
+        Elem<T>::store(p, Elem<T>::load(p) + uvec[e % d]);
+      }
     }
   }
   BF_STAMP(1, 8);
@@ -933,7 +998,7 @@ template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
                         float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part, bool basis_started,
-                        int32_t min_budget) {
+                        int32_t min_budget, Variant var) {
   HeadState* state = (HeadState*)(ws + w.head_state);
   float* basis = (float*)(ws + w.basis);
   float* gram_part = (float*)(ws + w.gram_part);
@@ -945,11 +1010,16 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     attr_done = true;
   }
-  if (!basis_started) {
+  if (var.skips_basis()) {
+    if (basis_started) { set_error("backfill: a basis was started for a variant without one"); return OBF_ERR_INVALID_ARG; }
+    ProfScope prof_(ST_KEEP_BASIS, st);
+    hipLaunchKernelGGL(k_bf_plain_state, dim3(m.heads), dim3(KB_THREADS), 0, st, scores, idx, n_keep, m.N, max_budget, rank, state);
+    if (check_launch("backfill plain state") != OBF_OK) return OBF_ERR_HIP;
+  } else if (!basis_started) {
     // the caller did not start the bases earlier: try here (beside the statistics pass only)
     if (launch_backfill_basis(m, w, ws, V, scores, idx, n_keep, max_budget, rank, st, &basis_started) != OBF_OK) return OBF_ERR_HIP;
   }
-  if (!basis_started) {
+  if (!basis_started && !var.skips_basis()) {
     const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
     int32_t* decided = nullptr;
     if (keep_cert_supported(m)) {
@@ -986,7 +1056,8 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     for (int cls = 0; cls < 2; ++cls) {
       hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), one * (cls + 1), st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
-                         (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls);
+                         (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
+                         var.flags, var.evr_tau);
     }
   }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
@@ -996,10 +1067,10 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
                              void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part,
-                             bool basis_started, int32_t min_budget) {
+                             bool basis_started, int32_t min_budget, Variant var) {
   if (m.dtype == OBF_BF16)
-    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget);
-  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget);
+    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget, var);
+  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget, var);
 }
 
 }  // namespace obf

@@ -191,6 +191,14 @@ obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws
                                      const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t* idx,
                                      int32_t* n_keep, const void* K, const void* Q, const double* row_lse,
                                      hipStream_t st);
+// Ablation variants of App. D as the kernels see them (obf_variant_t checked and packed).
+enum : int { VF_NO_PROJECTION = 1, VF_SUBSPACE_ALL = 2, VF_SUBSPACE_EVR = 4, VF_NO_SCALING = 8, VF_NAIVE = 16, VF_ATTN_INJECT = 32 };
+struct Variant {
+  int flags = 0;
+  float evr_tau = 0.f;
+  bool skips_basis() const { return (flags & (VF_NO_PROJECTION | VF_NAIVE)) != 0; }
+};
+
 // The library's second stream (one per host thread and device).  side_fork makes it wait for everything queued on st
 // so far and returns it (nullptr: none available, keep everything on st); side_join makes st wait for everything
 // queued on it since.  One fork/join pair may be open at a time.
@@ -205,6 +213,7 @@ obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const 
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
                              void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st,
                              const double* fro_part = nullptr,
-                             bool basis_started = false, int32_t min_budget = -1 /*smallest per-head budget if known*/);
+                             bool basis_started = false, int32_t min_budget = -1 /*smallest per-head budget if known*/,
+                             Variant var = Variant());
 
 }  // namespace obf

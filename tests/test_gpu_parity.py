@@ -20,20 +20,30 @@ def gpu():
     return gpu_util
 
 
-def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None, edit=None):
+def _gpu_variant(v):
+    """The binding's obf_variant_t for an oracle Variant (field by field, no arithmetic)."""
+    from paper_2604_13349_amd import binding as B
+    return B.make_variant(no_projection=v.no_projection, subspace=v.subspace, evr_tau=v.evr_tau, no_scaling=v.no_scaling,
+                          naive_aggregation=v.naive, attn_inject=v.attn_inject)
+
+
+def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None, edit=None, variant=None):
     K, V, Q = si.make_cache(cfg, seed, threads=8)
     if edit is not None:
         edit(K, V, Q)                     # in-place change of the synthetic cache (still seeded, still no oracle data)
     bud = si.budgets(cfg, seed) if budgets is None else np.asarray(budgets, dtype=np.int32).reshape(cfg.n_layers, cfg.n_kv_heads)
     rank = cfg.rank if rank is None else rank
-    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=max_budget)
+    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=max_budget,
+                        variant=None if variant is None else _gpu_variant(variant))
     reps = []
     for l in range(cfg.n_layers):
         for h in range(cfg.n_kv_heads):
-            ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), rank, cfg.dtype)
+            ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), rank, cfg.dtype,
+                                  *(() if variant is None else (variant,)))
             rep = parity.check_head(f"{cfg.name}[{l},{h}]", ref, K[l, h], V[l, h], cfg.dtype, int(bud[l, h]),
                                     out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
-                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
+                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h],
+                                    variant=variant)
             reps.append(rep)
     checked = [r for r in reps if r.v_checked]
     assert len(checked) >= max(1, len(reps) // 2), "too few heads reached the value check"
@@ -311,24 +321,27 @@ def test_near_tie_at_threshold_is_decided_exactly(gpu, dtype, d):
 
 
 # --------------------------------------------------------------------------- layerwise granularity (Sec. 4.3.2)
-def _check_layerwise(gpu, cfg, seed=0, budgets=None, rank=None):
+def _check_layerwise(gpu, cfg, seed=0, budgets=None, rank=None, variant=None):
     """obf_compress_relay_layerwise against oracle.compress_layer: the shared index set must be the oracle's (the exact
     re-decision at the threshold is part of the call), every head then goes through the per-head checks."""
     K, V, Q = si.make_cache(cfg, seed, threads=8)
     L, H = cfg.n_layers, cfg.n_kv_heads
     bud = np.full(L, cfg.budget, dtype=np.int32) if budgets is None else np.asarray(budgets, dtype=np.int32)
     rank = cfg.rank if rank is None else rank
-    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=int(min(bud.max(), cfg.n_tokens)), layerwise=True)
+    out = gpu.run_fused(cfg, K, V, Q, budgets=bud, rank=rank, max_budget=int(min(bud.max(), cfg.n_tokens)), layerwise=True,
+                        variant=None if variant is None else _gpu_variant(variant))
     active = 0
     for l in range(L):
-        idx, heads = O.compress_layer(K[l], V[l], Q[l], int(bud[l]), rank, cfg.group, cfg.dtype)
+        idx, heads = O.compress_layer(K[l], V[l], Q[l], int(bud[l]), rank, cfg.group, cfg.dtype,
+                                      *(() if variant is None else (variant,)))
         n = len(idx)
         for h in range(H):
             assert int(out["n_keep"][l, h]) == n
             assert out["idx"][l, h, :n].tolist() == idx.tolist(), f"layer {l} head {h}: shared index set differs"
             rep = parity.check_head(f"{cfg.name}-L[{l},{h}]", heads[h], K[l, h], V[l, h], cfg.dtype, int(bud[l]),
                                     out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
-                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
+                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h],
+                                    variant=variant)
             active += int(rep.skipped == 0)
     return active
 
@@ -406,6 +419,63 @@ def test_layerwise_near_tie_at_threshold_is_decided_exactly(gpu):
     out = gpu.run_fused(cfg, K2, V, Q, budget=budget, rank=0, layerwise=True)
     for h in range(H):
         assert np.array_equal(out["idx"][0, h], idx), "layerwise call: near tie decided differently from exact arithmetic"
+
+
+# --------------------------------------------------------------------------- ablation variants (App. D)
+VARIANTS = {
+    "no_projection": O.Variant(no_projection=True),
+    "max_p": O.Variant(subspace="all"),
+    "no_scaling": O.Variant(no_scaling=True),
+    "naive": O.Variant(naive=True),
+    "attn_inject": O.Variant(attn_inject=True),
+    "evr_0.35": O.Variant(subspace="evr", evr_tau=0.35),
+    "evr_0.8": O.Variant(subspace="evr", evr_tau=0.8),
+    "no_projection+no_scaling+attn_inject": O.Variant(no_projection=True, no_scaling=True, attn_inject=True),
+}
+
+
+@pytest.mark.parametrize("name", list(VARIANTS))
+def test_variants_headwise_small_budget(gpu, name):
+    """Each ablation of App. D through obf_compress_relay_variant on the paper-shaped shadow cache (budget below head_dim:
+    every head runs the back-fill) against the oracle with the same flag."""
+    reps = _check_cfg(gpu, si.shrink(si.CONFIGS["paper"], n_layers=1), variant=VARIANTS[name])
+    assert sum(r.skipped == 0 for r in reps if r.v_checked) >= len(reps) // 2
+
+
+@pytest.mark.parametrize("name", ["no_projection", "naive", "attn_inject"])
+def test_variants_headwise_budget_above_head_dim(gpu, name):
+    """Budget above head_dim on 8K-token bf16 heads: the method itself skips every head here (the retained span is everything);
+    the two variants without Eq. 3 still inject, the third stays skipped."""
+    cfg = si.shrink(si.CONFIGS["3"], n_layers=1, n_kv_heads=2)
+    reps = _check_cfg(gpu, cfg, variant=VARIANTS[name])
+    want_active = name != "attn_inject"
+    assert all((r.skipped == 0) == want_active for r in reps if r.v_checked)
+
+
+@pytest.mark.parametrize("name", ["max_p", "evr_0.35", "no_scaling"])
+def test_variants_layerwise(gpu, name):
+    """App. D ablates L-OBF: the same flags under the layerwise retention rule."""
+    cfg = si.shrink(si.CONFIGS["2s"], n_layers=2)
+    assert _check_layerwise(gpu, cfg, rank=4, variant=VARIANTS[name]) > 0
+
+
+def test_variant_null_and_default_equal_the_plain_call(gpu):
+    cfg = si.shrink(si.CONFIGS["2s"], n_layers=1)
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    from paper_2604_13349_amd import binding as B
+    a = gpu.run_fused(cfg, K, V, Q, budget=cfg.budget)
+    b = gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, variant=B.make_variant())
+    for k in ("K_out", "V_out", "idx", "n_keep", "delta"):
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_variant_argument_errors(gpu):
+    cfg = si.shrink(si.CONFIGS["1s"], n_layers=1)
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    from paper_2604_13349_amd import binding as B
+    for bad in (B.make_variant(subspace=7), B.make_variant(subspace="evr", evr_tau=0.0), B.make_variant(subspace="evr", evr_tau=1.5)):
+        with pytest.raises(B.ObfError):
+            gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, variant=bad)
 
 
 # --------------------------------------------------------------------------- HIP graph capture of the fused call
