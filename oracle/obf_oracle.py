@@ -34,6 +34,12 @@ The ablations of App. D are the flags of Variant; readings taken there:
   * EVR-adaptive: k* = smallest k whose leading squared singular values of R
     reach the fraction tau of their total; never above rank R.
   The per-token variant is not stated precisely enough to restate and is absent.
+Relay assembly (Sec. 3.2-3.3, Sec. 4.3.2): the eligible set Omega leaves out padding
+and the shared sink.  Readings: the arrays handed to this module hold real tokens
+only (right padding is a storage matter); the first `sink` tokens stay keys of the
+softmax of Eq. 1 but are neither candidates of TopK_B nor deleted values of
+Eq. 3-6; index lists keep the head's own token numbers.  append_message is the
+row-wise concatenation M_i = [M_{i-1}; Phi(P; G); G] of Sec. 3.3.
 Pinned by tests/test_oracle_pins.py (closed forms, brute force, invariants).
 Parity unpinned: absolute values on realistic caches (the paper prints no worked
 numeric example); those rest on invariants only.
@@ -275,17 +281,18 @@ class HeadResult:
 
 
 def compress_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, rank: int,
-                  dtype: str, variant: Variant = Variant()) -> HeadResult:
+                  dtype: str, variant: Variant = Variant(), sink: int = 0) -> HeadResult:
     """score -> TopK_B -> gather -> OBF for one (layer, KV head).
 
     K_io, V_io [N, d]; Q_io [group, window, d] (or [rows, d]); all in the I/O dtype.
+    sink: the first `sink` tokens are the shared attention sink (Sec. 4.3.2: not in Omega).
     """
     K = decode(K_io, dtype)
     V = decode(V_io, dtype)
     Qr = decode(Q_io, dtype).reshape(-1, K.shape[1])
-    A = attention_mass(K, Qr)
-    idx = select_topk(A, budget)
-    V_star, diag = backfill(V, A, idx, rank, variant)
+    A = attention_mass(K, Qr)                               # the sink tokens are keys like any other
+    idx = sink + select_topk(A[sink:], budget)              # TopK_B over Omega
+    V_star, diag = backfill(V[sink:], A[sink:], idx - sink, rank, variant)
     if diag.skipped:
         V_out = np.asarray(V_io)[idx].copy()               # identity: a bit copy, not a re-rounding
     else:
@@ -311,7 +318,7 @@ def compress_relay(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budgets
 
 # ----------------------------------------------------------------------------- layerwise selector (Sec. 4.3.2)
 def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, rank: int,
-                   group: int, dtype: str, variant: Variant = Variant()):
+                   group: int, dtype: str, variant: Variant = Variant(), sink: int = 0):
     """Layerwise granularity of the retention rule (Sec. 4.3.2; the "L" and "L-OBF" methods of Sec. 5):
     one index set per layer, TopK_B of the attention mass summed over the layer's heads, shared by
     all of them; Orthogonal BackFill then runs per head exactly as in the headwise case, with that
@@ -332,11 +339,11 @@ def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget:
     layer_mass = np.zeros_like(masses[0])
     for A in masses:                                        # plain left-to-right sum over the heads
         layer_mass = layer_mass + A
-    idx = select_topk(layer_mass, budget)
+    idx = sink + select_topk(layer_mass[sink:], budget)    # Omega leaves out the shared sink (Sec. 4.3.2)
     heads = []
     for h in range(H):
         V = decode(V_io[h], dtype)
-        V_star, diag = backfill(V, masses[h], idx, rank, variant)
+        V_star, diag = backfill(V[sink:], masses[h][sink:], idx - sink, rank, variant)
         if diag.skipped:
             V_out = np.asarray(V_io[h])[idx].copy()
         else:
@@ -344,6 +351,13 @@ def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget:
         heads.append(HeadResult(A=masses[h], idx=idx, K_keep=np.asarray(K_io[h])[idx].copy(), V_out=V_out,
                                 V_star=V_star, diag=diag))
     return idx, heads
+
+
+# ----------------------------------------------------------------------------- message of Sec. 3.3
+def append_message(prev: np.ndarray, keep: np.ndarray, gen: np.ndarray) -> np.ndarray:
+    """M_i = [M_{i-1}; Phi(P; G); G] for one (layer, KV head) and one of K / V: rows of the inherited message,
+    then the retained prompt rows, then the rows of the reasoning states, each [rows, d] in the I/O dtype."""
+    return np.concatenate([prev, keep, gen], axis=0)
 
 
 # ----------------------------------------------------------------------------- App. H route (used by pins and as a second CPU timing)

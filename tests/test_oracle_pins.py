@@ -589,3 +589,77 @@ def test_variants_leave_the_default_untouched_and_combine():
     mean = V[dele].sum(axis=0) / dele.size
     share = A[idx] / A[idx].sum()
     assert np.allclose(c - V[idx], idx.size * share[:, None] * mean[None, :], rtol=1e-11, atol=1e-13)
+
+
+# --------------------------------------------------------------------------- Sec. 4.3.2 eligible set, Sec. 3.3 message
+def _sink_case(seed=51, N=40, d=8, rows=6):
+    r = rng(seed)
+    K = r.standard_normal((N, d)).astype(np.float32)
+    V = r.standard_normal((N, d)).astype(np.float32)
+    Q = r.standard_normal((rows, d)).astype(np.float32)
+    return K, V, Q
+
+
+def test_sink_tokens_are_never_candidates_but_stay_softmax_keys():
+    K, V, Q = _sink_case()
+    K[:3] *= 6.0                                                   # the sink keys attract most of the mass
+    full = O.compress_head(K, V, Q, 5, 0, "f32")
+    assert set(full.idx.tolist()) & {0, 1, 2}                      # without protection some of them are picked
+    res = O.compress_head(K, V, Q, 5, 0, "f32", sink=3)
+    assert res.idx.min() >= 3 and res.idx.size == 5 and np.all(np.diff(res.idx) > 0)
+    assert abs(res.A.sum() - Q.shape[0]) < 1e-12                   # every row still sums to one over all real tokens
+    # brute force: the 5 largest masses among tokens 3.., ties to the lowest index
+    order = sorted(range(3, K.shape[0]), key=lambda j: (-res.A[j], j))[:5]
+    assert sorted(order) == res.idx.tolist()
+    # the sink keys shape the masses: without them the candidates' masses are larger
+    A_cut = O.attention_mass(O.decode(K[3:], "f32"), O.decode(Q, "f32"))
+    assert np.all(A_cut > res.A[3:])
+
+
+def test_sink_values_take_no_part_in_backfill_and_sink_zero_is_the_plain_call():
+    K, V, Q = _sink_case(52, N=30, d=8)
+    a = O.compress_head(K, V, Q, 4, 2, "f32", sink=4)
+    V2 = V.copy(); V2[:4] = 99.0
+    b = O.compress_head(K, V2, Q, 4, 2, "f32", sink=4)
+    assert a.diag.skipped == 0
+    assert np.array_equal(a.idx, b.idx) and np.array_equal(a.V_out, b.V_out)
+    # deleted set = eligible minus kept: the demand masses of Eq. 6 leave the sink out
+    elig = np.arange(4, 30)
+    dele = np.setdiff1d(elig, a.idx)
+    assert abs(a.diag.a_del - a.A[dele].sum()) < 1e-14 and abs(a.diag.a_keep - a.A[a.idx].sum()) < 1e-14
+    # the injection is orthogonal to the retained value rows
+    Vd = O.decode(V, "f32")
+    assert np.abs(Vd[a.idx] @ a.diag.delta).max() < 1e-12 * np.abs(Vd).max() * max(np.abs(a.diag.delta).max(), 1.0) * 100
+    p = O.compress_head(K, V, Q, 4, 2, "f32")
+    q = O.compress_head(K, V, Q, 4, 2, "f32", sink=0)
+    assert np.array_equal(p.idx, q.idx) and np.array_equal(p.V_out, q.V_out)
+
+
+def test_budget_above_the_eligible_count_keeps_every_eligible_token():
+    K, V, Q = _sink_case(53, N=12)
+    res = O.compress_head(K, V, Q, 100, 2, "f32", sink=4)
+    assert res.idx.tolist() == list(range(4, 12)) and res.diag.skipped == 1
+
+
+def test_layerwise_sink_shares_one_eligible_index_set():
+    r = rng(54)
+    H, N, d = 3, 24, 8
+    K = r.standard_normal((H, N, d)).astype(np.float32)
+    V = r.standard_normal((H, N, d)).astype(np.float32)
+    Q = r.standard_normal((H, 4, d)).astype(np.float32)
+    K[:, :2] *= 5.0
+    idx, heads = O.compress_layer(K, V, Q, 6, 1, 1, "f32", sink=2)
+    assert idx.min() >= 2 and idx.size == 6
+    tot = sum(h.A for h in heads)
+    order = sorted(range(2, N), key=lambda j: (-tot[j], j))[:6]
+    assert sorted(order) == idx.tolist()
+    assert all(np.array_equal(h.idx, idx) for h in heads)
+
+
+def test_message_is_the_row_concatenation_in_the_order_of_sec_3_3():
+    prev = np.array([[1, 1], [2, 2]], dtype=np.float32)
+    keep = np.array([[3, 3]], dtype=np.float32)
+    gen = np.array([[4, 4], [5, 5], [6, 6]], dtype=np.float32)
+    M = O.append_message(prev, keep, gen)
+    assert M.tolist() == [[1, 1], [2, 2], [3, 3], [4, 4], [5, 5], [6, 6]]
+    assert O.append_message(prev[:0], keep, gen[:0]).tolist() == [[3, 3]]
