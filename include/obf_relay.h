@@ -189,6 +189,47 @@ obf_status_t obf_compress_relay_variant(const obf_shape_t* shape, const void* K,
                                         float* scores_out, float* delta_out, obf_diag_t* diag,
                                         void* ws, size_t ws_bytes, void* stream);
 
+/* Relay assembly around the compression (Sec. 3.2-3.3, Sec. 4.3.2, App. A.7).
+ *
+ * obf_window_t places the prompt of one sample inside a larger, right-padded cache and names the shared attention sink:
+ *   token_stride  tokens between consecutive heads of K and V in memory (>= shape.n_tokens; 0 means n_tokens).
+ *                 shape.n_tokens is the number of real prompt tokens; the rows behind them (padding) are never read.
+ *   sink          the first `sink` tokens are the attention sink S: they are keys of the softmax of Eq. 1 like every
+ *                 real token, but they are not in the eligible set Omega, i.e. neither candidates of TopK_B nor deleted
+ *                 values of Eq. 3-6 (the sink travels inside the inherited message, M_0 = S).  0 <= sink < n_tokens.
+ * obf_compress_relay_window is obf_compress_relay_variant on that window: budgets count eligible tokens (a budget
+ * above n_tokens - sink keeps every eligible token), idx holds token numbers of the head (>= sink), scores_out covers
+ * all n_tokens real tokens ([n_layers][n_kv_heads][n_tokens], dense).  window == NULL and variant == NULL are the
+ * plain calls.  Errors as obf_compress_relay, plus OBF_ERR_INVALID_ARG for a window outside the limits above. */
+typedef struct obf_window_t {
+  int32_t token_stride;
+  int32_t sink;
+} obf_window_t;
+
+obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_window_t* window,
+                                       const void* K, const void* V, const void* Qwin,
+                                       const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                       int32_t layerwise, const obf_variant_t* variant,
+                                       void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                       float* scores_out, float* delta_out, obf_diag_t* diag,
+                                       void* ws, size_t ws_bytes, void* stream);
+
+/* The message an agent hands on (Sec. 3.3): M_i = [M_{i-1}; Phi(P; G); G], row-wise per (layer, KV head), keys and
+ * values alike.  For head h the output rows are prev[h][0 .. prev_len[h]), then keep[h][0 .. n_keep[h]), then
+ * gen[h][0 .. n_gen), all bit copies; msg_len[h] receives their number and the rows behind them up to msg_stride are
+ * zeroed.  Every part is [n_heads][*_stride][head_dim] of `dtype` (n_heads = layers x KV heads); prev_len
+ * (nullable: every head has prev_len_all rows) and n_keep are device arrays [n_heads]; for the first agent prev is the
+ * prompt cache itself with prev_len_all = sink.  A part with zero rows may be NULL.  The host checks what it can see
+ * (negative sizes, NULL parts, n_gen > gen_stride, prev_len_all > prev_stride: OBF_ERR_INVALID_ARG, nothing enqueued);
+ * lengths that live on the device are checked there: a head whose parts exceed prev_stride, keep_stride or msg_stride
+ * gets msg_len[h] = -1 and all-zero rows. */
+obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype,
+                                const void* prev_K, const void* prev_V, const int32_t* prev_len, int32_t prev_len_all,
+                                int32_t prev_stride,
+                                const void* keep_K, const void* keep_V, const int32_t* n_keep, int32_t keep_stride,
+                                const void* gen_K, const void* gen_V, int32_t n_gen, int32_t gen_stride,
+                                void* msg_K, void* msg_V, int32_t* msg_len, int32_t msg_stride, void* stream);
+
 /* Profiling aid (tracing of the path's own kernels with HIP events on the caller's stream).
  * obf_profile_enable(stage) makes every later call on this thread bracket the launch of that
  * internal stage's kernel with a pair of events; stage -1 switches it off.  obf_profile_read

@@ -37,6 +37,11 @@ class _Variant(C.Structure):
                 ("no_scaling", C.c_int32), ("naive_aggregation", C.c_int32), ("attn_inject", C.c_int32)]
 
 
+class _Window(C.Structure):
+    """obf_window_t."""
+    _fields_ = [("token_stride", C.c_int32), ("sink", C.c_int32)]
+
+
 SUBSPACE = {"rank": 0, "all": 1, "evr": 2}
 
 
@@ -84,6 +89,11 @@ def load_library():
     lib.obf_backfill_variant.argtypes = [sp, vp, vp, vp, vp, i32, i32, vr, vp, vp, vp, vp, sz, vp]
     lib.obf_compress_relay_variant.restype = C.c_int
     lib.obf_compress_relay_variant.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, i32, vr, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.obf_compress_relay_window.restype = C.c_int
+    lib.obf_compress_relay_window.argtypes = [sp, C.POINTER(_Window), vp, vp, vp, vp, i32, i32, i32, i32, vr, vp, vp, vp, vp,
+                                              vp, vp, vp, vp, sz, vp]
+    lib.obf_append_message.restype = C.c_int
+    lib.obf_append_message.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, i32, vp]
     lib.obf_profile_enable.restype = C.c_int
     lib.obf_profile_enable.argtypes = [i32]
     lib.obf_profile_read.restype = C.c_int
@@ -228,10 +238,17 @@ def backfill(shape: _Shape, V, scores, idx, n_keep, rank: int, V_out, delta_out=
 
 def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max_budget: Optional[int] = None,
                    out=None, ws=None, want_scores=False, want_delta=False, want_diag=False, layerwise=False,
-                   variant: Optional[_Variant] = None):
+                   variant: Optional[_Variant] = None, n_tokens: Optional[int] = None, sink: Optional[int] = None):
     """Fused relay compression.  Returns a dict of output tensors (device).  layerwise: one index set per layer
-    (budgets then holds one entry per layer).  variant: an obf_variant_t from make_variant (the variant entry point)."""
+    (budgets then holds one entry per layer).  variant: an obf_variant_t from make_variant (the variant entry point).
+    n_tokens / sink: the window entry point; K and V are then right-padded storage [L,H,stride,d] of which the first
+    n_tokens rows per head are real, the first `sink` of them the protected sink."""
     sh = shape_of(K, Qwin)
+    window = None
+    if n_tokens is not None or sink is not None:
+        window = _Window(K.shape[2], int(sink or 0))
+        if n_tokens is not None:
+            sh.n_tokens = int(n_tokens)
     L, H, d, N = sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.n_tokens
     keep, bptr = _budgets_arg(budgets)
     if max_budget is None:
@@ -253,6 +270,14 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
     if want_diag and "diag" not in o:
         o["diag"] = torch.empty((L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
     ws = _ws(sh, max_budget, rank, ws, dev)
+    if window is not None:
+        _check(load_library().obf_compress_relay_window(
+            C.byref(sh), C.byref(window), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, int(bool(layerwise)),
+            C.byref(variant) if variant is not None else None,
+            _ptr(o["K_out"]), _ptr(o["V_out"]), _ptr(o["idx"]), _ptr(o["n_keep"]), _ptr(o.get("scores")), _ptr(o.get("delta")),
+            _ptr(o.get("diag")), _ptr(ws), ws.numel(), _stream()))
+        o["ws"] = ws
+        return o
     if variant is not None:
         _check(load_library().obf_compress_relay_variant(
             C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, int(bool(layerwise)), C.byref(variant),
@@ -267,6 +292,24 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
         _ptr(ws), ws.numel(), _stream()))
     o["ws"] = ws
     return o
+
+
+def append_message(prev_K, prev_V, prev_len, keep_K, keep_V, n_keep, gen_K, gen_V, msg_stride: int, prev_len_all: int = 0):
+    """M = [prev; keep; gen] per head (obf_append_message).  Parts are [..., rows, d] tensors (leading dims = heads) or None;
+    prev_len / n_keep int32 device tensors (prev_len None: every head has prev_len_all rows).  Returns (msg_K, msg_V, msg_len)."""
+    ref = next(t for t in (keep_K, prev_K, gen_K) if t is not None)
+    d = ref.shape[-1]
+    heads = int(np.prod(ref.shape[:-2]))
+    dt = OBF_BF16 if ref.dtype == torch.bfloat16 else OBF_F32
+    msg_K = torch.empty((heads, msg_stride, d), dtype=ref.dtype, device=ref.device)
+    msg_V = torch.empty_like(msg_K)
+    msg_len = torch.empty((heads,), dtype=torch.int32, device=ref.device)
+    rows = lambda t: 0 if t is None else t.shape[-2]
+    _check(load_library().obf_append_message(
+        heads, d, dt, _ptr(prev_K), _ptr(prev_V), _ptr(prev_len), prev_len_all, rows(prev_K),
+        _ptr(keep_K), _ptr(keep_V), _ptr(n_keep), rows(keep_K), _ptr(gen_K), _ptr(gen_V), rows(gen_K), rows(gen_K),
+        _ptr(msg_K), _ptr(msg_V), _ptr(msg_len), msg_stride, _stream()))
+    return msg_K, msg_V, msg_len
 
 
 def diag_to_numpy(diag: torch.Tensor) -> np.ndarray:

@@ -223,7 +223,8 @@ static obf_status_t make_variant(const obf_variant_t* v, Variant* out) {
 }
 
 // Shared body of the fused calls; layerwise != 0 selects the per-layer retention rule.
-static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_window_t* window, const obf_shape_t* shape,
+                                        const void* K, const void* V, const void* Qwin,
                                         const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
                                         void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                         float* scores_out, float* delta_out, obf_diag_t* diag,
@@ -232,17 +233,32 @@ static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_sh
   OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(Qwin); OBF_NONNULL(K_out); OBF_NONNULL(V_out);
   OBF_NONNULL(idx); OBF_NONNULL(n_keep);
   if (rank < 0) { set_error("rank < 0"); return OBF_ERR_INVALID_ARG; }
-  Dims m = make_dims(shape);
+  Dims mf = make_dims(shape);                           // all real tokens: the keys of Eq. 1
+  int sink = 0;
+  if (window) {
+    if (window->token_stride != 0 && window->token_stride < mf.N) { set_error("window: token_stride below n_tokens"); return OBF_ERR_INVALID_ARG; }
+    if (window->sink < 0 || window->sink >= mf.N) { set_error("window: sink must lie in [0, n_tokens)"); return OBF_ERR_INVALID_ARG; }
+    if (window->token_stride) mf.kvs = window->token_stride;
+    sink = window->sink;
+  }
+  // the eligible tokens (Sec. 4.3.2): a view behind the sink, same strides; selection, gather and back-fill run on it
+  Dims m = mf;
+  m.N = mf.N - sink;
+  m.scs = mf.N;
   Dims mb = m;                                          // the units that own a budget: heads, or layers
   if (layerwise) mb.heads = m.L;
   OBF_TRY(check_budget(mb, budgets_host, budget, max_budget));
-  Workspace w = carve(m, max_budget, rank);
-  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  Workspace w = carve(mf, max_budget, rank);
+  OBF_TRY(check_ws(mf, w, ws, ws_bytes));
   char* base = (char*)ws;
   hipStream_t st = (hipStream_t)stream;
   float* scores = scores_out ? scores_out : (float*)(base + w.scores);
   double* row_lse = (double*)(base + w.row_lse);
-  OBF_TRY(run_score(m, w, base, K, Qwin, scores, row_lse, st));
+  OBF_TRY(run_score(mf, w, base, K, Qwin, scores, row_lse, st));
+  w.nstat = (m.N + kStatChunk - 1) / kStatChunk;        // statistics chunks of the view
+  K = (const char*)K + (size_t)sink * m.d * m.esize;
+  V = (const char*)V + (size_t)sink * m.d * m.esize;
+  scores += sink;
   if (layerwise) {
     OBF_TRY(launch_select_layerwise(m, w, base, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
   } else {
@@ -270,6 +286,7 @@ static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_sh
   OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
                           basis_started, min_budget, var));
   if (kside) OBF_TRY(side_join(st));
+  OBF_TRY(launch_idx_offset(idx, (size_t)m.heads * max_budget, sink, st));   // back to the head's own token numbers
   return OBF_OK;
 }
 
@@ -278,7 +295,7 @@ obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const v
                                 void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                 float* scores_out, float* delta_out, obf_diag_t* diag,
                                 void* ws, size_t ws_bytes, void* stream) {
-  return compress_relay_impl(0, Variant(), shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+  return compress_relay_impl(0, Variant(), nullptr, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
                              scores_out, delta_out, diag, ws, ws_bytes, stream);
 }
 
@@ -287,7 +304,7 @@ obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* 
                                           void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                           float* scores_out, float* delta_out, obf_diag_t* diag,
                                           void* ws, size_t ws_bytes, void* stream) {
-  return compress_relay_impl(1, Variant(), shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+  return compress_relay_impl(1, Variant(), nullptr, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
                              scores_out, delta_out, diag, ws, ws_bytes, stream);
 }
 
@@ -299,7 +316,7 @@ obf_status_t obf_compress_relay_variant(const obf_shape_t* shape, const void* K,
                                         void* ws, size_t ws_bytes, void* stream) {
   Variant var;
   OBF_TRY(make_variant(variant, &var));
-  return compress_relay_impl(layerwise != 0, var, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx,
+  return compress_relay_impl(layerwise != 0, var, nullptr, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx,
                              n_keep, scores_out, delta_out, diag, ws, ws_bytes, stream);
 }
 
@@ -318,6 +335,45 @@ obf_status_t obf_backfill_variant(const obf_shape_t* shape, const void* V, const
   OBF_TRY(check_ws(m, w, ws, ws_bytes));
   return launch_backfill(m, w, (char*)ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag,
                          (hipStream_t)stream, nullptr, false, -1, var);
+}
+
+obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_window_t* window,
+                                       const void* K, const void* V, const void* Qwin,
+                                       const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                       int32_t layerwise, const obf_variant_t* variant,
+                                       void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                       float* scores_out, float* delta_out, obf_diag_t* diag,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  Variant var;
+  OBF_TRY(make_variant(variant, &var));
+  return compress_relay_impl(layerwise != 0, var, window, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out,
+                             idx, n_keep, scores_out, delta_out, diag, ws, ws_bytes, stream);
+}
+
+obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype,
+                                const void* prev_K, const void* prev_V, const int32_t* prev_len, int32_t prev_len_all,
+                                int32_t prev_stride,
+                                const void* keep_K, const void* keep_V, const int32_t* n_keep, int32_t keep_stride,
+                                const void* gen_K, const void* gen_V, int32_t n_gen, int32_t gen_stride,
+                                void* msg_K, void* msg_V, int32_t* msg_len, int32_t msg_stride, void* stream) {
+  if (n_heads < 1 || n_heads > 65535) { set_error("n_heads must lie in [1, 65535]"); return OBF_ERR_INVALID_ARG; }
+  if (dtype != OBF_F32 && dtype != OBF_BF16) { set_error("unknown dtype %d", dtype); return OBF_ERR_INVALID_ARG; }
+  if (head_dim != 64 && head_dim != 128) { set_error("head_dim %d unsupported (64 or 128)", head_dim); return OBF_ERR_UNSUPPORTED; }
+  if (prev_stride < 0 || keep_stride < 0 || gen_stride < 0 || msg_stride < 1 || prev_len_all < 0 || n_gen < 0) {
+    set_error("strides and lengths must not be negative (msg_stride >= 1)");
+    return OBF_ERR_INVALID_ARG;
+  }
+  OBF_NONNULL(msg_K); OBF_NONNULL(msg_V); OBF_NONNULL(msg_len);
+  if ((prev_len || prev_len_all > 0) && (!prev_K || !prev_V)) { set_error("prev rows announced but prev_K / prev_V is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (n_keep && (!keep_K || !keep_V)) { set_error("n_keep given but keep_K / keep_V is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (n_gen > 0 && (!gen_K || !gen_V)) { set_error("n_gen > 0 but gen_K / gen_V is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (n_gen > gen_stride) { set_error("n_gen %d above gen_stride %d", n_gen, gen_stride); return OBF_ERR_INVALID_ARG; }
+  if (!prev_len && prev_len_all > prev_stride) { set_error("prev_len_all %d above prev_stride %d", prev_len_all, prev_stride); return OBF_ERR_INVALID_ARG; }
+  if (!prev_len && !n_keep && prev_len_all + n_gen > msg_stride) { set_error("message rows exceed msg_stride"); return OBF_ERR_INVALID_ARG; }
+  const int esize = (dtype == OBF_BF16) ? 2 : 4;
+  return launch_append_message(n_heads, head_dim * esize, prev_K, prev_V, prev_len, prev_len_all, prev_stride, keep_K, keep_V,
+                               n_keep, keep_stride, gen_K, gen_V, n_gen, gen_stride, msg_K, msg_V, msg_len, msg_stride,
+                               (hipStream_t)stream);
 }
 
 }  // extern "C"

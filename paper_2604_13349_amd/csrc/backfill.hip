@@ -203,7 +203,7 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
                                                               const int32_t* __restrict__ n_keep, int N, int d,
                                                               int max_budget, int rank, HeadState* __restrict__ state,
                                                               float* __restrict__ basis,
-                                                              const int32_t* __restrict__ decided) {
+                                                              const int32_t* __restrict__ decided, int scs, int kvs) {
   if (decided && decided[blockIdx.x]) return;        // settled by the fast full-rank test
   if (n_keep[blockIdx.x] <= d) return;               // heads of k_bf_keep_basis_small
   extern __shared__ double W[];            // [d][d] doubles (rows: vectors being orthonormalised / Gram)
@@ -215,9 +215,9 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
   const int head = blockIdx.x;
   const int n = n_keep[head];
   const int n_del = N - n;
-  const float* sc = scores + (size_t)head * N;
+  const float* sc = scores + (size_t)head * scs;
   const int32_t* id = idx + (size_t)head * max_budget;
-  const T* Vh = V + (size_t)head * N * d;
+  const T* Vh = V + (size_t)head * kvs * d;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // demand sums of Eq. 6, in double, fixed summation order
@@ -351,11 +351,11 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
 // demand sums of Eq. 6, r_keep = 0, and every head with retained and deleted rows is active.
 __global__ __launch_bounds__(KB_THREADS) void k_bf_plain_state(const float* __restrict__ scores, const int32_t* __restrict__ idx,
                                                                const int32_t* __restrict__ n_keep, int N, int max_budget,
-                                                               int rank, HeadState* __restrict__ state) {
+                                                               int rank, HeadState* __restrict__ state, int scs) {
   __shared__ double red[KB_WAVES];
   const int head = blockIdx.x;
   const int n = n_keep[head];
-  const float* sc = scores + (size_t)head * N;
+  const float* sc = scores + (size_t)head * scs;
   const int32_t* id = idx + (size_t)head * max_budget;
   double pk = 0.0, pt = 0.0;
   for (int i = threadIdx.x; i < n; i += KB_THREADS) pk += (double)sc[id[i]];
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
                                                              int max_budget, int nstat,
                                                              const HeadState* __restrict__ state,
                                                              const int32_t* __restrict__ n_keep /*non-null: do not read the head states*/,
-                                                             float* __restrict__ gram_part) {
+                                                             float* __restrict__ gram_part, int scs, int kvs) {
   const int head = blockIdx.y, chunk = blockIdx.x;
   const int n = n_keep ? n_keep[head] : state[head].n_keep;
   if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
@@ -390,8 +390,8 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
   __shared__ float wt[DS_TOK];               // score of the token (0 for rows that are not deleted)
   __shared__ int isdel[DS_TOK];              // 1: deleted row of this chunk
   const int32_t* id = idx + (size_t)head * max_budget;
-  const T* Vh = V + (size_t)head * N * d;
-  const float* sc = scores + (size_t)head * N;
+  const T* Vh = V + (size_t)head * kvs * d;
+  const float* sc = scores + (size_t)head * scs;
   const int t0 = chunk * kStatChunk, t1 = min(N, t0 + kStatChunk);
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int bs = d / 16;
@@ -466,7 +466,8 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
                                                             float* __restrict__ delta_out, obf_diag_t* __restrict__ diag,
                                                             T* __restrict__ V_out, int max_budget, int cls,
                                                             const float* __restrict__ scores,
-                                                            const int32_t* __restrict__ idx, int vflags, float evr_tau) {
+                                                            const int32_t* __restrict__ idx, int vflags, float evr_tau,
+                                                            int scs) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
@@ -910,7 +911,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     T* base = V_out + (size_t)head * max_budget * d;
     if (vflags & VF_ATTN_INJECT) {
       const float per_mass = (float)((double)st.n_keep / (st.a_keep + kEps));
-      const float* sc = scores + (size_t)head * N;
+      const float* sc = scores + (size_t)head * scs;
       const int32_t* id = idx + (size_t)head * max_budget;
       for (int e = tid; e < total; e += FN_THREADS) {
         T* p = base + e;
@@ -1013,7 +1014,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   if (var.skips_basis()) {
     if (basis_started) { set_error("backfill: a basis was started for a variant without one"); return OBF_ERR_INVALID_ARG; }
     ProfScope prof_(ST_KEEP_BASIS, st);
-    hipLaunchKernelGGL(k_bf_plain_state, dim3(m.heads), dim3(KB_THREADS), 0, st, scores, idx, n_keep, m.N, max_budget, rank, state);
+    hipLaunchKernelGGL(k_bf_plain_state, dim3(m.heads), dim3(KB_THREADS), 0, st, scores, idx, n_keep, m.N, max_budget, rank, state, m.scs);
     if (check_launch("backfill plain state") != OBF_OK) return OBF_ERR_HIP;
   } else if (!basis_started) {
     // the caller did not start the bases earlier: try here (beside the statistics pass only)
@@ -1033,7 +1034,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
         launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
     if (max_budget > m.d) {
       hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
-                         m.N, m.d, max_budget, rank, state, basis, decided);
+                         m.N, m.d, max_budget, rank, state, basis, decided, m.scs, m.kvs);
       if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
     }
   }
@@ -1043,7 +1044,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, nk_stats, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
   } else if (rank > 0) {
     { ProfScope prof_(ST_DEL_STATS, st); hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
-                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, nk_stats, gram_part); }
+                       (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, nk_stats, gram_part, m.scs, m.kvs); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
   if (basis_started) {
@@ -1057,7 +1058,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
       hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), one * (cls + 1), st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
-                         var.flags, var.evr_tau);
+                         var.flags, var.evr_tau, m.scs);
     }
   }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;

@@ -18,6 +18,8 @@ constexpr float kBandRel = 1.0e-4f;     // relative half-width of the refinement
 struct Dims {
   int heads;      // n_layers * n_kv_heads
   int L, H, g, d, N, W;
+  int kvs;        // tokens between consecutive heads of K and V (>= N; N for a dense cache)
+  int scs;        // floats between consecutive heads of the score array handed to selection and back-fill (>= N)
   int R;          // query rows per KV head = g * W
   int dtype;
   int esize;      // bytes per element of K/V/Q
@@ -26,6 +28,7 @@ struct Dims {
 inline Dims make_dims(const obf_shape_t* s) {
   Dims m;
   m.L = s->n_layers; m.H = s->n_kv_heads; m.g = s->group; m.d = s->head_dim; m.N = s->n_tokens; m.W = s->window;
+  m.kvs = m.N; m.scs = m.N;
   m.heads = m.L * m.H; m.R = m.g * m.W; m.dtype = s->dtype; m.esize = (s->dtype == OBF_BF16) ? 2 : 4;
   return m;
 }
@@ -198,6 +201,13 @@ struct Variant {
   float evr_tau = 0.f;
   bool skips_basis() const { return (flags & (VF_NO_PROJECTION | VF_NAIVE)) != 0; }
 };
+
+obf_status_t launch_append_message(int heads, int row_bytes, const void* prev_K, const void* prev_V, const int32_t* prev_len,
+                                   int prev_len_all, int prev_stride, const void* keep_K, const void* keep_V,
+                                   const int32_t* n_keep, int keep_stride, const void* gen_K, const void* gen_V, int n_gen,
+                                   int gen_stride, void* msg_K, void* msg_V, int32_t* msg_len, int msg_stride, hipStream_t st);
+// idx[i] += offset for every valid (non-negative) entry
+obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream_t st);
 
 // The library's second stream (one per host thread and device).  side_fork makes it wait for everything queued on st
 // so far and returns it (nullptr: none available, keep everything on st); side_join makes st wait for everything

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
                                                                      int max_budget, int nstat,
                                                                      const HeadState* __restrict__ state,
                                                                      const int32_t* __restrict__ n_keep /*non-null: the head states are still being written; every head with deleted rows is active*/,
-                                                                     float* __restrict__ gram_part) {
+                                                                     float* __restrict__ gram_part, int scs, int kvs) {
   const int head = blockIdx.y, chunk = blockIdx.x;
   const int n = n_keep ? n_keep[head] : state[head].n_keep;
   if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
@@ -45,8 +45,8 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 31, lh = lane >> 5;
   const int32_t* id = idx + (size_t)head * max_budget;
-  const uint16_t* Vh = V + (size_t)head * N * DM_D;
-  const float* sc = scores + (size_t)head * N;
+  const uint16_t* Vh = V + (size_t)head * kvs * DM_D;
+  const float* sc = scores + (size_t)head * scs;
   const int t0 = chunk * kStatChunk, t1 = min(N, t0 + kStatChunk);
   const int rows = t1 - t0;
 
@@ -214,7 +214,7 @@ obf_status_t launch_del_stats_mfma(const Dims& m, const Workspace& w, const void
                                    const int32_t* n_keep, float* gram_part, hipStream_t st) {
   { ProfScope prof_(ST_DEL_STATS, st);
     hipLaunchKernelGGL(k_bf_del_stats_mfma, dim3(w.nstat, m.heads), dim3(DM_THREADS), 0, st, (const uint16_t*)V, scores,
-                       idx, m.N, max_budget, w.nstat, state, n_keep, gram_part); }
+                       idx, m.N, max_budget, w.nstat, state, n_keep, gram_part, m.scs, m.kvs); }
   return check_launch("backfill del_stats (mfma)");
 }
 

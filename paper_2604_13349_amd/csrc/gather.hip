@@ -8,7 +8,7 @@ constexpr int GA_THREADS = 256;
 
 __global__ __launch_bounds__(GA_THREADS) void k_gather(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                        const int32_t* __restrict__ idx,
-                                                       const int32_t* __restrict__ n_keep, int N, int row_vec /*uint4 per row*/,
+                                                       const int32_t* __restrict__ n_keep, int kvs /*tokens per head in K, V*/, int row_vec /*uint4 per row*/,
                                                        int max_budget, uint4* __restrict__ K_out, uint4* __restrict__ V_out,
                                                        double* __restrict__ fro_part /*bf16 rows of 256 bytes only*/) {
   __shared__ float s_red[GA_THREADS / 64];
@@ -22,7 +22,7 @@ __global__ __launch_bounds__(GA_THREADS) void k_gather(const uint4* __restrict__
   uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
   if (r < n && r < max_budget) {
     const int j = idx[(size_t)head * max_budget + r];
-    const size_t s = ((size_t)head * N + j) * row_vec + c;
+    const size_t s = ((size_t)head * kvs + j) * row_vec + c;
     if (K_out) kv = K[s];
     if (V_out) vv = V[s];
   }
@@ -54,9 +54,21 @@ obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const in
   const int row_vec = m.d * m.esize / 16;            // 8, 16 or 32
   const int rows_per_block = GA_THREADS / row_vec;
   dim3 grid((max_budget + rows_per_block - 1) / rows_per_block, m.heads);
-  { ProfScope prof_(ST_GATHER, st); hipLaunchKernelGGL(k_gather, grid, dim3(GA_THREADS), 0, st, (const uint4*)K, (const uint4*)V, idx, n_keep, m.N, row_vec,
+  { ProfScope prof_(ST_GATHER, st); hipLaunchKernelGGL(k_gather, grid, dim3(GA_THREADS), 0, st, (const uint4*)K, (const uint4*)V, idx, n_keep, m.kvs, row_vec,
                      max_budget, (uint4*)K_out, (uint4*)V_out, fro_part); }
   return check_launch("gather");
+}
+
+// Index lists of a token window back in the head's own numbering: valid entries move by `offset`, the -1 padding stays.
+__global__ __launch_bounds__(GA_THREADS) void k_idx_offset(int32_t* __restrict__ idx, size_t n, int32_t offset) {
+  const size_t i = (size_t)blockIdx.x * GA_THREADS + threadIdx.x;
+  if (i < n) { const int32_t v = idx[i]; if (v >= 0) idx[i] = v + offset; }
+}
+
+obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream_t st) {
+  if (n == 0 || offset == 0) return OBF_OK;
+  hipLaunchKernelGGL(k_idx_offset, dim3((unsigned)((n + GA_THREADS - 1) / GA_THREADS)), dim3(GA_THREADS), 0, st, idx, n, offset);
+  return check_launch("idx offset");
 }
 
 }  // namespace obf

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
                                                                     const int32_t* __restrict__ idx,
                                                                     const int32_t* __restrict__ n_keep, int N, int d,
                                                                     int max_budget, int rank, HeadState* __restrict__ state,
-                                                                    float* __restrict__ basis) {
+                                                                    float* __restrict__ basis, int scs, int kvs) {
   const int head = blockIdx.x;
   const int n = n_keep[head];
   if (n > d) return;                         // heads of the general kernel
@@ -283,9 +283,9 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
   extern __shared__ double Cs[];             // [n][n] Gram matrix (first the staging area of its accumulation)
   __shared__ KsShared sh;
   const int n_del = N - n;
-  const float* sc = scores + (size_t)head * N;
+  const float* sc = scores + (size_t)head * scs;
   const int32_t* id = idx + (size_t)head * max_budget;
-  const T* Vh = V + (size_t)head * N * d;
+  const T* Vh = V + (size_t)head * kvs * d;
   const int tid = threadIdx.x;
 
   KS_STAMP(0);
@@ -341,11 +341,11 @@ static obf_status_t run_small(const Dims& m, const void* V, const float* scores,
   }
   const size_t nmax = (size_t)min(max_budget, m.d);
   hipLaunchKernelGGL((k_bf_keep_basis_small<T, false>), dim3(m.heads), dim3(KS_THREADS), ks_smem(min(nmax, (size_t)96), m.d), st,
-                     (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis);
+                     (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis, m.scs, m.kvs);
   if (check_launch("backfill keep_basis_small") != OBF_OK) return OBF_ERR_HIP;
   if (nmax > 96) {
     hipLaunchKernelGGL((k_bf_keep_basis_small<T, true>), dim3(m.heads), dim3(KS_THREADS), ks_smem(nmax, m.d), st,
-                       (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis);
+                       (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis, m.scs, m.kvs);
     if (check_launch("backfill keep_basis_small (wide)") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
                                                              int rank, HeadState* __restrict__ state,
                                                              int32_t* __restrict__ decided,
                                                              const double* __restrict__ fro_part /*optional: sums of squares of the retained rows, per gather block*/,
-                                                             int fro_blocks) {
+                                                             int fro_blocks, int scs, int kvs) {
   __shared__ uint32_t stage[2][(KC_TILE / 2) * KC_LDW];
   __shared__ __attribute__((aligned(16))) float panel[2][KC_D][4];
   __shared__ float4 ypan[KC_D], lpan[KC_D];
@@ -66,9 +66,9 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   const int lr = lane & 31, lh = lane >> 5;
   if (tid == 0) decided[head] = 0;
   if (!(rank > 0 && n > KC_D && n_del > 0)) return;
-  const float* sc = scores + (size_t)head * N;
+  const float* sc = scores + (size_t)head * scs;
   const int32_t* id = idx + (size_t)head * max_budget;
-  const uint16_t* Vh = Vsrc + (size_t)head * (via_idx ? N : max_budget) * KC_D;
+  const uint16_t* Vh = Vsrc + (size_t)head * (via_idx ? kvs : max_budget) * KC_D;
   auto row_of = [&](int r) -> size_t { return via_idx ? (size_t)id[r] : (size_t)r; };    // retained row r of the head
 
   KC_STAMP(0);
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   // The demand sums of Eq. 6 (diagnostics of a certified head) need sum(scores[idx]) and sum(scores): their first
   // batch of loads is issued here and consumed after the factorisation, so that its latency is hidden.
   int ej[8];
-  const bool vec_scores = (N & 3) == 0;
+  const bool vec_scores = (N & 3) == 0 && ((uintptr_t)sc & 15) == 0;
 #pragma unroll
   for (int u = 0; u < 8; ++u) { const int i = tid + u * KC_THREADS; ej[u] = (i < n) ? id[i] : -1; }
   // tile j is staged in stage[j % 2]; the loads run two tiles ahead in registers
@@ -367,10 +367,10 @@ obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, cons
   { ProfScope prof_(ST_KEEP_CERT, st);
     if (via_idx)
       hipLaunchKernelGGL(k_bf_keep_cert<true>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
-                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks);
+                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks, m.scs, m.kvs);
     else
       hipLaunchKernelGGL(k_bf_keep_cert<false>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
-                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks); }
+                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks, m.scs, m.kvs); }
   return check_launch("backfill keep_cert");
 }
 

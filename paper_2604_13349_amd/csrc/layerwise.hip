@@ -9,13 +9,13 @@ constexpr int LW_THREADS = 256;
 
 // layer_scores[l][j] = sum over the heads h of the layer (in head order) of scores[l][h][j]
 __global__ __launch_bounds__(LW_THREADS) void k_layer_sum(const float* __restrict__ scores, float* __restrict__ out,
-                                                          int H, int N) {
+                                                          int H, int N, int scs) {
   const int l = blockIdx.y;
   const int j = blockIdx.x * LW_THREADS + threadIdx.x;
   if (j >= N) return;
-  const float* p = scores + (size_t)l * H * N + j;
+  const float* p = scores + (size_t)l * H * scs + j;
   float s = 0.f;
-  for (int h = 0; h < H; ++h) s += p[(size_t)h * N];
+  for (int h = 0; h < H; ++h) s += p[(size_t)h * scs];
   out[(size_t)l * N + j] = s;
 }
 
@@ -40,11 +40,12 @@ obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws
   {
     ProfScope prof_(ST_SELECT, st);
     hipLaunchKernelGGL(k_layer_sum, dim3((m.N + LW_THREADS - 1) / LW_THREADS, m.L), dim3(LW_THREADS), 0, st, scores,
-                       layer_scores, m.H, m.N);
+                       layer_scores, m.H, m.N, m.scs);
   }
   if (check_launch("layer sum") != OBF_OK) return OBF_ERR_HIP;
   Dims ml = m;
   ml.heads = m.L;                                       // one selection per layer
+  ml.scs = m.N;                                         // the layer sums are dense
   if (launch_select(ml, layer_scores, budgets_host, budget, max_budget, idx_layer, nk_layer, st) != OBF_OK) return OBF_ERR_HIP;
   double* part = (double*)(ws + w.band);               // [heads][kBandCap] exact masses of the band tokens, per head
   if (launch_refine_layers(m, K, Q, layer_scores, row_lse, max_budget, idx_layer, nk_layer, part, st) != OBF_OK) return OBF_ERR_HIP;

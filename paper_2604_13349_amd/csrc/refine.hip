@@ -66,7 +66,7 @@ __device__ bool rf_find_band(RfShared<NT>& sh, const float* __restrict__ sc, con
   int seg = (N + NT - 1) / NT;
   seg = (seg + 3) & ~3;
   const int b0 = min(N, (int)threadIdx.x * seg), b1 = min(N, b0 + seg);
-  const bool vec = (N & 3) == 0;
+  const bool vec = (N & 3) == 0 && ((uintptr_t)sc & 15) == 0;
   int cnt = 0;
   if (vec) {
 #pragma unroll 8
@@ -134,17 +134,17 @@ __global__ __launch_bounds__(NT) void k_refine(const T* __restrict__ K, const T*
                                                 const float* __restrict__ scores,
                                                 const double* __restrict__ row_lse, int N, int d, int R,
                                                 int max_budget, int32_t* __restrict__ idx,
-                                                const int32_t* __restrict__ n_keep) {
+                                                const int32_t* __restrict__ n_keep, int scs, int kvs) {
   __shared__ RfShared<NT> sh;
   const int head = blockIdx.x;
   const int n = n_keep[head];
   if (n <= 0 || n >= N) return;
-  const float* sc = scores + (size_t)head * N;
+  const float* sc = scores + (size_t)head * scs;
   int32_t* out = idx + (size_t)head * max_budget;
   int nband, nkb, kb;
   if (!rf_find_band<NT>(sh, sc, out, n, N, nband, nkb, kb)) return;
   // 4. exact scores of the band tokens
-  rescore_band<T, NT / 64>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, sh.band,
+  rescore_band<T, NT / 64>(K + (size_t)head * kvs * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, sh.band,
                            nband, sh.band_score);
   __syncthreads();
   rf_apply<NT>(sh, out, N, nband, nkb, kb);
@@ -159,14 +159,14 @@ __global__ __launch_bounds__(NT) void k_refine_layer_part(const T* __restrict__ 
                                                           const double* __restrict__ row_lse, int N, int d, int R, int H,
                                                           int max_budget, const int32_t* __restrict__ idx_layer,
                                                           const int32_t* __restrict__ n_keep_layer,
-                                                          double* __restrict__ part /*[L*H][kBandCap]*/) {
+                                                          double* __restrict__ part /*[L*H][kBandCap]*/, int kvs) {
   __shared__ RfShared<NT> sh;
   const int head = blockIdx.x, l = head / H;
   const int n = n_keep_layer[l];
   if (n <= 0 || n >= N) return;
   int nband, nkb, kb;
   if (!rf_find_band<NT>(sh, layer_scores + (size_t)l * N, idx_layer + (size_t)l * max_budget, n, N, nband, nkb, kb)) return;
-  rescore_band<T, NT / 64>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, sh.band,
+  rescore_band<T, NT / 64>(K + (size_t)head * kvs * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R, sh.band,
                            nband, part + (size_t)head * kBandCap);
 }
 
@@ -200,10 +200,10 @@ obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const vo
   ProfScope prof_(ST_REFINE, st);
   if (m.dtype == OBF_BF16)
     hipLaunchKernelGGL((k_refine<uint16_t, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const uint16_t*)K,
-                       (const uint16_t*)Q, scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
+                       (const uint16_t*)Q, scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, m.scs, m.kvs);
   else
     hipLaunchKernelGGL((k_refine<float, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st, (const float*)K,
-                       (const float*)Q, scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep);
+                       (const float*)Q, scores, row_lse, m.N, m.d, m.R, max_budget, idx, n_keep, m.scs, m.kvs);
   return check_launch("refine");
 }
 
@@ -216,11 +216,11 @@ obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, c
   if (m.dtype == OBF_BF16)
     hipLaunchKernelGGL((k_refine_layer_part<uint16_t, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st,
                        (const uint16_t*)K, (const uint16_t*)Q, layer_scores, row_lse, m.N, m.d, m.R, m.H, max_budget,
-                       idx_layer, n_keep_layer, part);
+                       idx_layer, n_keep_layer, part, m.kvs);
   else
     hipLaunchKernelGGL((k_refine_layer_part<float, RF_THREADS>), dim3(m.heads), dim3(RF_THREADS), 0, st,
                        (const float*)K, (const float*)Q, layer_scores, row_lse, m.N, m.d, m.R, m.H, max_budget,
-                       idx_layer, n_keep_layer, part);
+                       idx_layer, n_keep_layer, part, m.kvs);
   if (check_launch("refine (layerwise, exact masses)") != OBF_OK) return OBF_ERR_HIP;
   hipLaunchKernelGGL((k_refine_layer_apply<RF_THREADS>), dim3(m.L), dim3(RF_THREADS), 0, st, layer_scores, m.N, m.H,
                      max_budget, idx_layer, n_keep_layer, part);

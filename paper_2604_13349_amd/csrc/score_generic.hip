@@ -23,7 +23,7 @@ __device__ __forceinline__ void load_tile(float* dst, int ld, const T* src, int 
 template <typename T>
 __global__ __launch_bounds__(GS_THREADS) void k_score_stats_generic(const T* __restrict__ K, const T* __restrict__ Q,
                                                                     double* __restrict__ stats_part, int N, int d, int R,
-                                                                    int nchunk, int chunk_tokens) {
+                                                                    int nchunk, int chunk_tokens, int kvs) {
   extern __shared__ float smem[];
   const int ld = d + 1;
   float* Qs = smem;                   // [GS_ROWS][ld]
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(GS_THREADS) void k_score_stats_generic(const T* __r
   const int head = blockIdx.y, chunk = blockIdx.x;
   const int t0 = chunk * chunk_tokens;
   const int t1 = min(N, t0 + chunk_tokens);
-  const T* Kh = K + (size_t)head * N * d;
+  const T* Kh = K + (size_t)head * kvs * d;
   const T* Qh = Q + (size_t)head * R * d;
   const int rr = threadIdx.x >> 3, tl = threadIdx.x & 7;
   const double scale = 1.0 / sqrt((double)d);
@@ -94,7 +94,7 @@ __global__ void k_score_lse(const double* __restrict__ stats_part, double* __res
 template <typename T>
 __global__ __launch_bounds__(GS_THREADS) void k_score_mass_generic(const T* __restrict__ K, const T* __restrict__ Q,
                                                                    const double* __restrict__ row_lse,
-                                                                   float* __restrict__ scores, int N, int d, int R, int chunk_tokens) {
+                                                                   float* __restrict__ scores, int N, int d, int R, int chunk_tokens, int kvs) {
   extern __shared__ float smem[];
   const int ld = d + 1;
   float* Qs = smem;
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(GS_THREADS) void k_score_mass_generic(const T* __re
   const int head = blockIdx.y, chunk = blockIdx.x;
   const int t0 = chunk * chunk_tokens;
   const int t1 = min(N, t0 + chunk_tokens);
-  const T* Kh = K + (size_t)head * N * d;
+  const T* Kh = K + (size_t)head * kvs * d;
   const T* Qh = Q + (size_t)head * R * d;
   const double* lse = row_lse + (size_t)head * R;
   const int rr = threadIdx.x >> 3, tl = threadIdx.x & 7;
@@ -153,14 +153,14 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   const size_t smemB = smemA + 8 + sizeof(double) * GS_ROWS * GS_TOK;
   dim3 grid(w.nchunk, m.heads);
   { ProfScope prof_(ST_SCORE_STATS, st); hipLaunchKernelGGL(k_score_stats_generic<T>, grid, dim3(GS_THREADS), smemA, st, (const T*)K, (const T*)Q, stats_part,
-                     m.N, m.d, m.R, w.nchunk, w.chunk_tokens); }
+                     m.N, m.d, m.R, w.nchunk, w.chunk_tokens, m.kvs); }
   if (check_launch("score stats (generic)") != OBF_OK) return OBF_ERR_HIP;
   const int total_rows = m.heads * m.R;
   { ProfScope prof_(ST_SCORE_LSE, st); hipLaunchKernelGGL(k_score_lse, dim3((total_rows + 255) / 256), dim3(256), 0, st, stats_part, row_lse, m.R, w.nchunk,
                      total_rows); }
   if (check_launch("score lse") != OBF_OK) return OBF_ERR_HIP;
   { ProfScope prof_(ST_SCORE_MASS, st); hipLaunchKernelGGL(k_score_mass_generic<T>, grid, dim3(GS_THREADS), smemB, st, (const T*)K, (const T*)Q, row_lse, scores,
-                     m.N, m.d, m.R, w.chunk_tokens); }
+                     m.N, m.d, m.R, w.chunk_tokens, m.kvs); }
   return check_launch("score mass (generic)");
 }
 

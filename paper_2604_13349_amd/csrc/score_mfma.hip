@@ -209,6 +209,7 @@ struct Part {
   int TH;        // 32-token tiles per head
   int T;         // tiles per workgroup range
   long TT;       // heads * TH
+  long kstride;  // elements between consecutive heads of K
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -238,7 +239,7 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
     const long se = min(ge, hs + pt.TH);
     const int ta = (int)(cur - hs) * SM_TILE, tb = min(N, (int)(se - hs) * SM_TILE);
     const int slot = range - (int)(hs / pt.T);
-    const uint16_t* Kh = K + (size_t)head * N * SM_D;
+    const uint16_t* Kh = K + (size_t)head * pt.kstride;
     const uint16_t* Qh = Q + (size_t)head * R * SM_D;
 
     Frag qf[SM_RB][SM_KK];
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
     const long hs = (long)head * pt.TH;
     const long cur = max(gs, hs);
     const int ta = (int)(cur - hs) * SM_TILE, tb = min(N, (int)(se - hs) * SM_TILE);
-    const uint16_t* Kh = K + (size_t)head * N * SM_D;
+    const uint16_t* Kh = K + (size_t)head * pt.kstride;
     const uint16_t* Qh = Q + (size_t)head * R * SM_D;
     float* dst = out + (size_t)rg * rg_stride + (size_t)head * N;
 
@@ -388,6 +389,7 @@ obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, cons
   float* part = (RG > 1) ? (float*)(ws + w.score_part) : scores;
   Part pt;
   pt.TH = w.tiles_per_head; pt.T = w.tiles_per_range; pt.TT = (long)m.heads * w.tiles_per_head;
+  pt.kstride = (long)m.kvs * SM_D;
   dim3 grid(((w.nranges + 7) / 8) * 8 * RG);
   { ProfScope prof_(ST_SCORE_STATS, st);
     hipLaunchKernelGGL(k_score_stats_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,

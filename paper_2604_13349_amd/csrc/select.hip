@@ -58,7 +58,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
                                                         int max_budget, int32_t* __restrict__ idx,
                                                         int32_t* __restrict__ n_keep, const ET* __restrict__ K,
                                                         const ET* __restrict__ Q, const double* __restrict__ row_lse,
-                                                        int d, int R) {
+                                                        int d, int R, int scs, int kvs) {
   constexpr int SEL_WAVES = SEL_THREADS / 64;
   __shared__ int band[REFINE ? kBandCap : 1];
   __shared__ double band_score[REFINE ? kBandCap : 1];
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   __shared__ int wcnt[2][SEL_WAVES];
   __shared__ int wsum[2 * SEL_WAVES];
   const int head = head0 + blockIdx.x;
-  const float* sc = scores + (size_t)head * N;
+  const float* sc = scores + (size_t)head * scs;
   int32_t* out = idx + (size_t)head * max_budget;
   int B = use_per_head ? per_head.b[blockIdx.x] : uniform_budget;
   if (B > N) B = N;
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   const int base = tid * SEG;
   uint32_t key[SEG];
   int nvalid = min(SEG, max(0, N - base));                     // tokens of this thread inside the head
-  if (nvalid == SEG && ((N & 3) == 0)) {
+  if (nvalid == SEG && (((uintptr_t)(sc + base) & 15) == 0)) {
 #pragma unroll
     for (int i = 0; i < SEG; i += 4) {
       const float4 v = *(const float4*)(sc + base + i);
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
       }
       __syncthreads();
       SEL_STAMP(4);
-      rescore_band<ET, SEL_WAVES>(K + (size_t)head * N * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R,
+      rescore_band<ET, SEL_WAVES>(K + (size_t)head * kvs * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R,
                                  band, nband, band_score);
       __syncthreads();
       int keep = 0, was = 0;
@@ -254,7 +254,7 @@ static obf_status_t launch_select_seg(const Dims& m, const float* scores, const 
   if (!budgets_host) {
     { ProfScope prof_(ST_SELECT, st);
       hipLaunchKernelGGL((k_select<SEG, SEL_THREADS, REFINE, T>), dim3(m.heads), dim3(SEL_THREADS), 0, st, scores, m.N, 0,
-                         budget, bb, 0, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R); }
+                         budget, bb, 0, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R, m.scs, m.kvs); }
     return check_launch("select");
   }
   for (int h0 = 0; h0 < m.heads; h0 += SEL_BATCH) {
@@ -262,7 +262,7 @@ static obf_status_t launch_select_seg(const Dims& m, const float* scores, const 
     for (int i = 0; i < nb; ++i) bb.b[i] = budgets_host[h0 + i];
     { ProfScope prof_(ST_SELECT, st);
       hipLaunchKernelGGL((k_select<SEG, SEL_THREADS, REFINE, T>), dim3(nb), dim3(SEL_THREADS), 0, st, scores, m.N, h0, 0, bb,
-                         1, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R); }
+                         1, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R, m.scs, m.kvs); }
     if (check_launch("select") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;

@@ -20,11 +20,11 @@ def to_host(t: torch.Tensor, dtype: str) -> np.ndarray:
     return t.cpu().numpy()
 
 
-def run_fused(cfg: si.RelayConfig, K, V, Q, budgets=None, budget=None, rank=None, max_budget=None, layerwise=False, variant=None):
+def run_fused(cfg: si.RelayConfig, K, V, Q, budgets=None, budget=None, rank=None, max_budget=None, layerwise=False, variant=None, n_tokens=None, sink=None):
     """K, V, Q numpy (I/O dtype).  Returns dict of numpy outputs."""
     Kd, Vd, Qd = to_dev(K, cfg.dtype), to_dev(V, cfg.dtype), to_dev(Q, cfg.dtype)
     rank = cfg.rank if rank is None else rank
-    kw = dict(rank=rank, want_scores=True, want_delta=True, want_diag=True, layerwise=layerwise, variant=variant)
+    kw = dict(rank=rank, want_scores=True, want_delta=True, want_diag=True, layerwise=layerwise, variant=variant, n_tokens=n_tokens, sink=sink)
     if budgets is not None:
         o = B.compress_relay(Kd, Vd, Qd, budgets=np.asarray(budgets).reshape(-1), max_budget=max_budget, **kw)
     else:

@@ -52,17 +52,18 @@ def gap_factor(diag) -> float:
 
 
 def check_head(tag, ref: O.HeadResult, K_io, V_io, dtype, budget, gpu_idx, gpu_n_keep, gpu_K, gpu_V,
-               gpu_diag=None, gpu_delta=None, gpu_scores=None, variant=None) -> HeadReport:
-    """variant: the oracle's Variant the reference was computed with (None: the method itself)."""
+               gpu_diag=None, gpu_delta=None, gpu_scores=None, variant=None, sink=0) -> HeadReport:
+    """variant: the oracle's Variant the reference was computed with (None: the method itself); sink: protected
+    leading tokens (the eligible set starts behind them)."""
     rep = HeadReport()
     N, d = K_io.shape
-    B = min(int(budget), N)
+    B = min(int(budget), N - sink)
     maxb = gpu_idx.shape[0]
     assert int(gpu_n_keep) == B, f"{tag}: n_keep {gpu_n_keep} != budget {B}"
     gi = np.asarray(gpu_idx[:B], dtype=np.int64)
     assert np.all(gpu_idx[B:] == -1), f"{tag}: idx tail is not -1"
     if B > 0:
-        assert gi.min() >= 0 and gi.max() < N, f"{tag}: idx out of range"
+        assert gi.min() >= sink and gi.max() < N, f"{tag}: idx out of range"
         assert np.all(np.diff(gi) > 0), f"{tag}: idx not strictly ascending"
     # gather is a bit copy of whatever the GPU selected
     assert np.array_equal(gpu_K[:B], K_io[gi]), f"{tag}: K_out is not a bit copy of K[idx]"

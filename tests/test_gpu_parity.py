@@ -478,6 +478,120 @@ def test_variant_argument_errors(gpu):
             gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, variant=bad)
 
 
+# --------------------------------------------------------------------------- relay assembly (Sec. 3.3, Sec. 4.3.2)
+def _check_window(gpu, cfg, sink, pad, seed=0, budget=None, rank=None, layerwise=False, variant=None):
+    """obf_compress_relay_window on right-padded storage (pad rows of junk behind every head) with a protected sink,
+    against the oracle on the real tokens."""
+    K, V, Q = si.make_cache(cfg, seed, threads=8)
+    L, H, N, d = K.shape
+    junk = np.random.default_rng(99)
+
+    def padded(a):
+        out = np.empty((L, H, N + pad, d), dtype=a.dtype)
+        out[:, :, :N] = a
+        if pad:
+            fill = junk.integers(0, 0x7F00, size=(L, H, pad, d)).astype(np.uint16)      # finite bf16 bit patterns
+            out[:, :, N:] = fill if a.dtype == np.uint16 else fill.astype(np.float32)
+        return out
+
+    budget = cfg.budget if budget is None else budget
+    rank = cfg.rank if rank is None else rank
+    out = gpu.run_fused(cfg, padded(K), padded(V), Q, budget=budget, rank=rank, max_budget=min(budget, N - sink),
+                        layerwise=layerwise, variant=None if variant is None else _gpu_variant(variant), n_tokens=N, sink=sink)
+    var = () if variant is None else (variant,)
+    active = 0
+    for l in range(L):
+        if layerwise:
+            idx, heads = O.compress_layer(K[l], V[l], Q[l], budget, rank, cfg.group, cfg.dtype, *(var or (O.Variant(),)), sink)
+        for h in range(H):
+            if layerwise:
+                ref = heads[h]
+                assert out["idx"][l, h, :len(idx)].tolist() == idx.tolist()
+            else:
+                ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], budget, rank, cfg.dtype,
+                                      *(var or (O.Variant(),)), sink)
+            rep = parity.check_head(f"{cfg.name}-win[{l},{h}]", ref, K[l, h], V[l, h], cfg.dtype, budget,
+                                    out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
+                                    gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h],
+                                    variant=variant, sink=sink)
+            active += int(rep.skipped == 0 and rep.v_checked)
+    return active
+
+
+@pytest.mark.parametrize("sink,pad", [(4, 0), (4, 37), (0, 64), (3, 5)])
+def test_window_paper_shape(gpu, sink, pad):
+    # sink_size = 4 is the paper's setting (App. A.1); 3 makes the score view misaligned for 16-byte loads
+    assert _check_window(gpu, si.shrink(si.CONFIGS["paper"], n_layers=2), sink, pad) > 0
+
+
+def test_window_mfma_score_path_ragged_length(gpu):
+    cfg = si.RelayConfig("win", 21, 1, 3, 4, 128, 2000 + 13, 32, 96, 4, "bf16", "structured", outlier_frac=0.01)
+    assert _check_window(gpu, cfg, sink=4, pad=51) > 0
+
+
+def test_window_budget_above_head_dim_and_fp32(gpu):
+    cfg = si.RelayConfig("win", 22, 1, 2, 4, 128, 1500, 32, 300, 4, "bf16", "structured")
+    _check_window(gpu, cfg, sink=4, pad=20)
+    cfg = si.RelayConfig("win", 23, 1, 2, 2, 64, 700, 8, 40, 2, "f32", "structured")
+    assert _check_window(gpu, cfg, sink=2, pad=9) > 0
+
+
+def test_window_layerwise_and_variant(gpu):
+    cfg = si.shrink(si.CONFIGS["2s"], n_layers=2)
+    assert _check_window(gpu, cfg, sink=4, pad=12, rank=4, layerwise=True) > 0
+    assert _check_window(gpu, si.shrink(si.CONFIGS["paper"], n_layers=1), sink=4, pad=3, variant=VARIANTS["no_projection"]) > 0
+
+
+def test_window_budget_above_eligible_count_and_errors(gpu):
+    cfg = si.RelayConfig("win", 24, 1, 2, 2, 64, 50, 8, 100, 2, "f32", "structured")
+    _check_window(gpu, cfg, sink=4, pad=6)                  # keeps tokens 4 .. 49
+    from paper_2604_13349_amd import binding as B
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    for bad in (dict(n_tokens=51), dict(sink=50), dict(sink=-1)):
+        with pytest.raises(B.ObfError):
+            gpu.run_fused(cfg, K, V, Q, budget=10, **bad)
+
+
+def test_append_message_matches_concatenation(gpu):
+    """obf_append_message against the oracle's row concatenation: ragged inherited lengths and retained counts per head,
+    one head that does not fit."""
+    import torch
+    from paper_2604_13349_amd import binding as B
+    r = np.random.default_rng(5)
+    heads, d = 6, 128
+    prev_stride, keep_stride, n_gen, msg_stride = 40, 32, 7, 70
+    prev_len = np.array([0, 40, 13, 25, 31, 40], dtype=np.int32)
+    n_keep = np.array([32, 20, 0, 32, 32, 32], dtype=np.int32)        # head 5: 40 + 32 + 7 > 70
+    mk = lambda rows: r.integers(0, 0x7F00, size=(heads, rows, d)).astype(np.uint16)
+    parts = {k: mk(rows) for k, rows in (("pK", prev_stride), ("pV", prev_stride), ("kK", keep_stride), ("kV", keep_stride),
+                                         ("gK", n_gen), ("gV", n_gen))}
+    dev = {k: gpu.to_dev(v, "bf16") for k, v in parts.items()}
+    mK, mV, mlen = B.append_message(dev["pK"], dev["pV"], torch.from_numpy(prev_len).cuda(), dev["kK"], dev["kV"],
+                                    torch.from_numpy(n_keep).cuda(), dev["gK"], dev["gV"], msg_stride)
+    torch.cuda.synchronize()
+    mK, mV, mlen = gpu.to_host(mK, "bf16"), gpu.to_host(mV, "bf16"), mlen.cpu().numpy()
+    for h in range(heads):
+        wantK = O.append_message(parts["pK"][h, :prev_len[h]], parts["kK"][h, :n_keep[h]], parts["gK"][h])
+        wantV = O.append_message(parts["pV"][h, :prev_len[h]], parts["kV"][h, :n_keep[h]], parts["gV"][h])
+        if wantK.shape[0] > msg_stride:
+            assert mlen[h] == -1 and not mK[h].any() and not mV[h].any()
+            continue
+        n = wantK.shape[0]
+        assert mlen[h] == n
+        assert np.array_equal(mK[h, :n], wantK) and np.array_equal(mV[h, :n], wantV)
+        assert not mK[h, n:].any() and not mV[h, n:].any()
+    # first agent: the inherited message is the sink, i.e. the first rows of the prompt cache itself (uniform length)
+    mK, mV, mlen = B.append_message(dev["pK"], dev["pV"], None, dev["kK"], dev["kV"], torch.from_numpy(n_keep).cuda(),
+                                    None, None, msg_stride, prev_len_all=4)
+    torch.cuda.synchronize()
+    mK, mlen = gpu.to_host(mK, "bf16"), mlen.cpu().numpy()
+    for h in range(heads):
+        want = O.append_message(parts["pK"][h, :4], parts["kK"][h, :n_keep[h]], parts["gK"][h, :0])
+        assert mlen[h] == want.shape[0] and np.array_equal(mK[h, :want.shape[0]], want)
+    with pytest.raises(B.ObfError):
+        B.append_message(dev["pK"], dev["pV"], None, dev["kK"], dev["kV"], None, None, None, msg_stride, prev_len_all=41)
+
+
 # --------------------------------------------------------------------------- HIP graph capture of the fused call
 @pytest.mark.parametrize("name,layerwise", [("2", False), ("2s", False), ("2s", True)])
 def test_graph_capture_replays_match_eager(gpu, name, layerwise):
