@@ -68,6 +68,13 @@ def main() -> int:
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the timed region (a kernel of known "
                          "traffic that calibrates the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--variant", default="none",
+                    choices=["none", "no_projection", "max_p", "no_scaling", "naive", "attn_inject", "evr"],
+                    help="ablation variant of App. D (not the headline path)")
+    ap.add_argument("--sink", type=int, default=-1,
+                    help="protect the first SINK tokens as the shared attention sink (the window entry point; -1: plain call)")
+    ap.add_argument("--message", type=int, default=0,
+                    help="also build the outgoing message [sink; retained rows; MESSAGE reasoning rows] in every step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -105,15 +112,32 @@ def main() -> int:
             c["bud"] = c["bud"].reshape(cfg.n_layers, cfg.n_kv_heads)[:, :1].copy()
     max_budget = int(max(int(min(c["bud"].max(), cfg.n_tokens)) for c in calls))
     outs = [None] * len(calls)
+    vflags = {"none": {}, "no_projection": {"no_projection": True}, "max_p": {"subspace": "all"}, "no_scaling": {"no_scaling": True},
+              "naive": {"naive_aggregation": True}, "attn_inject": {"attn_inject": True}, "evr": {"subspace": "evr", "evr_tau": 0.35}}
+    variant = B.make_variant(**vflags[args.variant]) if args.variant != "none" else None
+    sink = args.sink if args.sink >= 0 else None
+    if sink is not None:
+        max_budget = min(max_budget, cfg.n_tokens - sink)
+    gen_rows = None
+    if args.message > 0:                  # stand-in for the reasoning states G of Sec. 3.3 (bit copies: values do not matter)
+        gen_rows = [torch.zeros((cfg.n_layers, cfg.n_kv_heads, args.message, cfg.head_dim), dtype=calls[0]["K"].dtype,
+                                device="cuda") for _ in range(2)]
+    msg_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
 
     def step():
         for i, c in enumerate(calls):
             kw = dict(rank=cfg.rank, max_budget=max_budget, out=outs[i], ws=(outs[i] or {}).get("ws"),
-                      want_diag=True, layerwise=layerwise)
+                      want_diag=True, layerwise=layerwise, variant=variant, sink=sink)
             if uniform:
                 outs[i] = B.compress_relay(c["K"], c["V"], c["Q"], budget=int(c["bud"].flat[0]), **kw)
             else:
                 outs[i] = B.compress_relay(c["K"], c["V"], c["Q"], budgets=c["bud"].reshape(-1), **kw)
+            if gen_rows is not None:
+                msg_ev[0].record()
+                outs[i]["msg"] = B.append_message(c["K"], c["V"], None, outs[i]["K_out"], outs[i]["V_out"],
+                                                  outs[i]["n_keep"].reshape(-1), gen_rows[0], gen_rows[1],
+                                                  (sink or 0) + max_budget + args.message, prev_len_all=sink or 0)
+                msg_ev[1].record()
 
     if args.copy_mib > 0:
         src = torch.empty(args.copy_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -170,6 +194,16 @@ def main() -> int:
                 "path_frac": round(pbytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
                 "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
 
+    extra = {}
+    if gen_rows is not None:
+        row = cfg.head_dim * (2 if cfg.dtype == "bf16" else 4)
+        nk = int(outs[0]["n_keep"].sum().item())
+        copied = cfg.n_heads * ((sink or 0) + args.message) + nk                          # rows that carry data, per K or V
+        written = cfg.n_heads * ((sink or 0) + max_budget + args.message)                 # all rows of the message buffers
+        ms = msg_ev[0].elapsed_time(msg_ev[1])
+        extra["message"] = {"ms": round(ms, 4), "read_bytes": 2 * row * copied, "written_bytes": 2 * row * written,
+                            "GBps": round(2 * row * (copied + written) / (ms * 1e-3) / 1e9, 1)}
+    ovar, osink = None, (sink or 0)
     cpu = None
     if args.cpu_seconds > 0 and layerwise:
         from oracle import obf_oracle as O
@@ -183,7 +217,8 @@ def main() -> int:
         idx_host = outs[0]["idx"].cpu().numpy()
         done, mismatched, tc0 = 0, 0, time.perf_counter()
         for l in range(cfg.n_layers):
-            ref_idx, _ = O.compress_layer(Kh[l], Vh[l], Qh[l], int(bud[l, 0]), cfg.rank, cfg.group, cfg.dtype)
+            ovar = O.Variant(**{{"naive_aggregation": "naive"}.get(k, k): v for k, v in vflags[args.variant].items()})
+            ref_idx, _ = O.compress_layer(Kh[l], Vh[l], Qh[l], int(bud[l, 0]), cfg.rank, cfg.group, cfg.dtype, ovar, osink)
             done += 1
             mismatched += int(not np.array_equal(idx_host[l, 0, :len(ref_idx)], ref_idx))
             if time.perf_counter() - tc0 >= args.cpu_seconds:
@@ -206,7 +241,9 @@ def main() -> int:
         idx_host = outs[0]["idx"].cpu().numpy()
         mismatched = 0
         for (l, h) in order:
-            ref = O.compress_head(Kh[l, h], Vh[l, h], Qh[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), cfg.rank, cfg.dtype)
+            ovar = O.Variant(**{{"naive_aggregation": "naive"}.get(k, k): v for k, v in vflags[args.variant].items()})
+            ref = O.compress_head(Kh[l, h], Vh[l, h], Qh[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), cfg.rank, cfg.dtype,
+                                  ovar, osink)
             done += 1
             mismatched += int(not np.array_equal(idx_host[l, h, :len(ref.idx)], ref.idx))
             if time.perf_counter() - tc0 >= args.cpu_seconds:
@@ -223,9 +260,12 @@ def main() -> int:
         "config": {"workload": f"config {cfg.name}: {cfg.n_layers} layers x {cfg.n_kv_heads} KV heads, group {cfg.group}, "
                                f"head_dim {cfg.head_dim}, N={cfg.n_tokens}, window {cfg.window}, rank {cfg.rank}, "
                                f"budget {'per-head' if not uniform else cfg.budget}, {cfg.agents} call(s) per step"
-                               + (", layerwise selector" if layerwise else ""),
+                               + (", layerwise selector" if layerwise else "")
+                               + (f", variant {args.variant}" if variant is not None else "")
+                               + (f", sink {sink}" if sink is not None else "")
+                               + (f", message with {args.message} reasoning rows" if gen_rows is not None else ""),
                    "heads": cfg.n_heads, "active_obf_heads": active_heads, "input_gen_s": round(gen_s, 1)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, **extra,
     }
     print(json.dumps(line))
     return 0
