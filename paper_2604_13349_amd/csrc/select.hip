@@ -93,16 +93,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     for (int i = 0; i < SEG; ++i) key[i] = (i < nvalid) ? order_key(sc[base + i]) : 0u;
   }
 
-  const bool full = __builtin_amdgcn_readfirstlane(N) == SEG * SEL_THREADS;     // every thread owns SEG tokens
+  // tokens outside the head carry key 0 and every candidate is >= 1, so they never count
   auto count_ge = [&](uint32_t cand, int buf) -> int {
     int c = 0;
-    if (full) {
 #pragma unroll
-      for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(key[i] >= cand));
-    } else {
-#pragma unroll
-      for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(i < nvalid && key[i] >= cand));
-    }
+    for (int i = 0; i < SEG; ++i) c += __popcll(__ballot(key[i] >= cand));
     if (lane == 0) wcnt[buf][wave] = c;
     __syncthreads();
     int tot = 0;

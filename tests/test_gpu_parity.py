@@ -180,6 +180,14 @@ def test_fused_equals_staged_and_is_deterministic(gpu):
     assert torch.equal(K_out.view(torch.int16), a["K_out"].view(torch.int16))
     assert torch.equal(V_out.view(torch.int16), a["V_out"].view(torch.int16))
     assert torch.equal(delta, a["delta"])
+    # the same for the variant entry points: obf_backfill_variant on staged inputs == obf_compress_relay_variant
+    var = Bd.make_variant(no_scaling=True, attn_inject=True, subspace="evr", evr_tau=0.5)
+    c = Bd.compress_relay(Kd, Vd, Qd, budget=cfg.budget, rank=cfg.rank, want_delta=True, variant=var)
+    K_out, V_out = Bd.gather(sh, Kd, Vd, idx, n_keep)
+    Bd.backfill(sh, Vd, scores, idx, n_keep, cfg.rank, V_out, delta_out=delta, variant=var)
+    torch.cuda.synchronize()
+    assert torch.equal(V_out.view(torch.int16), c["V_out"].view(torch.int16)) and torch.equal(delta, c["delta"])
+    assert not torch.equal(c["V_out"].view(torch.int16), a["V_out"].view(torch.int16))
 
 
 def test_select_stage_is_exact_on_given_scores(gpu):
