@@ -494,7 +494,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     const int m0 = (st.active && !naive) ? d - st.r_keep : 0;
     const int mm0 = m0 + (m0 & 1);
     const int big = 2 * mm0 * (mm0 + 1) > d * ld;
-    if (big != cls) return;
+    if (cls >= 0 && big != cls) return;                        // cls < 0: one launch with the large LDS takes every head
   }
 
   BF_STAMP(1, 0);
@@ -1054,8 +1054,11 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   {
     ProfScope prof_(ST_FINALIZE, st);
     const size_t one = sizeof(float) * m.d * (m.d + 1);
-    for (int cls = 0; cls < 2; ++cls) {
-      hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), one * (cls + 1), st, m.N, m.d,
+    // every budget above head_dim: heads that need the finalisation are rare (the certificate settles the others), so one
+    // launch with the large LDS size serves both classes instead of two launches that mostly exit at once
+    const bool single = min_budget > m.d && m.N > m.d && !var.skips_basis();
+    for (int cls = single ? -1 : 0; cls < (single ? 0 : 2); ++cls) {
+      hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), one * (cls < 0 ? 2 : cls + 1), st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
                          var.flags, var.evr_tau, m.scs);
