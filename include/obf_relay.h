@@ -88,14 +88,14 @@ typedef struct {
  * Returns 0 if the shape is unsupported. */
 size_t obf_workspace_bytes(const obf_shape_t* shape, int32_t max_budget, int32_t rank);
 
-/* Eq. 1 / Alg. 2 line 1: scores[l][h][j] = sum over the group*window query rows of
+/* Eq. 1 (the scoring step of Alg. 2): scores[l][h][j] = sum over the group*window query rows of
  * softmax_j(q . k_j / sqrt(d)), softmax over the n_tokens keys of the head.
  * row_lse (nullable) receives log(sum_j exp(logit)) of every query row in double; the
  * boundary refinement needs it. */
 obf_status_t obf_score(const obf_shape_t* shape, const void* K, const void* Qwin, float* scores,
                        double* row_lse, void* ws, size_t ws_bytes, void* stream);
 
-/* TopK_B (Sec. 4.3.2, Alg. 2 line 3) on the float scores as given: the B largest, ties to the
+/* TopK_B (Sec. 4.3.2, the selection step of Alg. 2) on the float scores as given: the B largest, ties to the
  * lowest index, written ascending.  Pure integer/compare work on the fp32 bit patterns.
  * budgets_host (nullable, host memory, [n_layers*n_kv_heads]) gives per-head budgets;
  * otherwise `budget` is used for every head.  Budgets above n_tokens keep everything. */
@@ -111,12 +111,12 @@ obf_status_t obf_refine_boundary(const obf_shape_t* shape, const void* K, const 
                                  const double* row_lse, int32_t max_budget, int32_t* idx, const int32_t* n_keep,
                                  void* ws, size_t ws_bytes, void* stream);
 
-/* Alg. 2 line 7: K_out = K[idx], V_out = V[idx] as bit copies; rows >= n_keep are zeroed.
+/* The gather step of Alg. 2: K_out = K[idx], V_out = V[idx] as bit copies; rows >= n_keep are zeroed.
  * Either output may be NULL to skip it. */
 obf_status_t obf_gather(const obf_shape_t* shape, const void* K, const void* V, const int32_t* idx,
                         const int32_t* n_keep, int32_t max_budget, void* K_out, void* V_out, void* stream);
 
-/* Orthogonal BackFill (Eq. 2-7, Alg. 3 lines 3-10) on already gathered values: V_out holds
+/* Orthogonal BackFill (Eq. 2-7, Alg. 3) on already gathered values: V_out holds
  * V[idx] on entry and V[idx] + delta on exit (rounded to dtype); untouched where OBF is
  * skipped.  `rank` is pca_rank (0 = plain eviction).  delta_out, diag nullable. */
 obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* scores, const int32_t* idx,

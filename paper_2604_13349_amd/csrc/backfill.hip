@@ -1,4 +1,4 @@
-// Orthogonal BackFill (Sec. 4.4, Eq. 2-7; Alg. 3 lines 3-10) on one GPU.
+// Orthogonal BackFill (Sec. 4.4, Eq. 2-7; Alg. 3) on one GPU.
 //
 //   keep_basis : per head, demand sums (Eq. 6), dimension r and an orthonormal basis Q of the span of
 //                the retained values (Eq. 2).  r == d means the orthogonal complement is {0}: the

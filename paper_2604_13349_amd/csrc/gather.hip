@@ -1,4 +1,4 @@
-// Gather of the retained rows (Alg. 2 line 7): K_out = K[idx], V_out = V[idx], bit copies in
+// Gather of the retained rows (the gather step of Alg. 2): K_out = K[idx], V_out = V[idx], bit copies in
 // 16-byte pieces; rows past n_keep are zero-filled so the padded output is deterministic.
 #include "common.hpp"
 
