@@ -601,14 +601,15 @@ def test_append_message_matches_concatenation(gpu):
 
 
 # --------------------------------------------------------------------------- HIP graph capture of the fused call
-@pytest.mark.parametrize("name,layerwise", [("2", False), ("2s", False), ("2s", True)])
-def test_graph_capture_replays_match_eager(gpu, name, layerwise):
-    """The fused call is captured into a HIP graph (the small-budget shape forks and joins the library's second
-    stream inside the capture) and replayed several times with eager calls and synchronisations in between; every
-    replay must reproduce the eager outputs bit for bit."""
+@pytest.mark.parametrize("name,layerwise,layers", [("2", False, 3), ("2s", False, 3), ("2s", True, 3), ("3", False, 8)])
+def test_graph_capture_replays_match_eager(gpu, name, layerwise, layers):
+    """The fused call is captured into a HIP graph (the small-budget shape forks the library's second stream for the
+    bases, the 8-layer config-3 shape for the copy of the retained K rows, and both join inside the capture) and replayed
+    several times with eager calls and synchronisations in between; every replay must reproduce the eager outputs bit
+    for bit."""
     import torch
     from paper_2604_13349_amd import binding as Bd
-    cfg = si.shrink(si.CONFIGS[name], n_layers=3)
+    cfg = si.shrink(si.CONFIGS[name], n_layers=layers)
     K, V, Q = si.make_cache(cfg, 0, threads=8)
     Kd, Vd, Qd = gpu.to_dev(K, cfg.dtype), gpu.to_dev(V, cfg.dtype), gpu.to_dev(Q, cfg.dtype)
     out = None
