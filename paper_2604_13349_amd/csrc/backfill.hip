@@ -196,6 +196,68 @@ __device__ void gram_rows_f64(const T* __restrict__ Vh, const int32_t* __restric
 }
 
 // ------------------------------------------------------------------------------------------------
+// Heads of the general basis kernel (more than d retained rows, not settled by the certificate), numbered in head
+// order: the first kKeepGramSlots of them get their Gram matrix from partial matrices of kKeepGramChunks workgroups.
+__device__ __forceinline__ bool kg_general(const int32_t* __restrict__ decided, const int32_t* __restrict__ n_keep, int h, int N,
+                                           int d, int rank) {
+  const int n = n_keep[h];
+  return rank > 0 && n > d && N - n > 0 && !(decided && decided[h]);
+}
+
+// number of such heads below `head` (every thread gets it)
+__device__ int kg_rank_of(const int32_t* __restrict__ decided, const int32_t* __restrict__ n_keep, int head, int N, int d, int rank,
+                          double* red) {
+  double c = 0.0;
+  for (int h = threadIdx.x; h < head; h += KB_THREADS) c += kg_general(decided, n_keep, h, N, d, rank) ? 1.0 : 0.0;
+  return (int)block_sum(c, red);
+}
+
+// the head whose number is `target`, or -1 (every thread gets it); s_i has KB_WAVES + 1 entries
+__device__ int kg_head_of_rank(const int32_t* __restrict__ decided, const int32_t* __restrict__ n_keep, int heads, int N, int d,
+                               int rank, int target, int* s_i) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) s_i[KB_WAVES] = -1;
+  int base = 0;
+  for (int h0 = 0; h0 < heads; h0 += KB_THREADS) {
+    const int h = h0 + threadIdx.x;
+    const bool p = h < heads && kg_general(decided, n_keep, h, N, d, rank);
+    const uint64_t mask = __ballot(p);
+    __syncthreads();
+    if (lane == 0) s_i[wave] = __popcll(mask);
+    __syncthreads();
+    int before = base, tot = 0;
+    for (int w = 0; w < KB_WAVES; ++w) { if (w < wave) before += s_i[w]; tot += s_i[w]; }
+    if (p && before + __popcll(mask & ((1ull << lane) - 1ull)) == target) s_i[KB_WAVES] = h;
+    base += tot;
+    if (base > target) break;                        // uniform: found
+  }
+  __syncthreads();
+  return s_i[KB_WAVES];
+}
+
+// Partial Gram matrices: workgroup (c, s) sums chunk c of the retained rows of the s-th such head.
+template <typename T>
+__global__ __launch_bounds__(KB_THREADS) void k_bf_keep_gram_part(const T* __restrict__ V, const int32_t* __restrict__ idx,
+                                                                  const int32_t* __restrict__ n_keep,
+                                                                  const int32_t* __restrict__ decided, int heads, int N, int d,
+                                                                  int max_budget, int rank, int kvs,
+                                                                  double* __restrict__ gpart) {
+  extern __shared__ double W[];
+  __shared__ int s_i[KB_WAVES + 1];
+  const int head = kg_head_of_rank(decided, n_keep, heads, N, d, rank, blockIdx.y, s_i);
+  if (head < 0) return;
+  const int n = n_keep[head];
+  const int per = (n + kKeepGramChunks - 1) / kKeepGramChunks;
+  const int i0 = min(n, (int)blockIdx.x * per), i1 = min(n, i0 + per);
+  const int32_t* id = idx + (size_t)head * max_budget + i0;
+  const T* Vh = V + (size_t)head * kvs * d;
+  if (d == 128) gram_rows_f64<T, 8>(Vh, id, i1 - i0, W);
+  else gram_rows_f64<T, 4>(Vh, id, i1 - i0, W);
+  double* o = gpart + ((size_t)blockIdx.y * kKeepGramChunks + blockIdx.x) * d * d;
+  for (int e = threadIdx.x; e < d * d; e += KB_THREADS) o[e] = W[e];
+}
+
+// ------------------------------------------------------------------------------------------------
 // keep_basis
 template <typename T>
 __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restrict__ V, const float* __restrict__ scores,
@@ -203,7 +265,8 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
                                                               const int32_t* __restrict__ n_keep, int N, int d,
                                                               int max_budget, int rank, HeadState* __restrict__ state,
                                                               float* __restrict__ basis,
-                                                              const int32_t* __restrict__ decided, int scs, int kvs) {
+                                                              const int32_t* __restrict__ decided, int scs, int kvs,
+                                                              const double* __restrict__ gpart /*nullable*/) {
   if (decided && decided[blockIdx.x]) return;        // settled by the fast full-rank test
   if (n_keep[blockIdx.x] <= d) return;               // heads of k_bf_keep_basis_small
   extern __shared__ double W[];            // [d][d] doubles (rows: vectors being orthonormalised / Gram)
@@ -245,8 +308,21 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       KB_STAMP(0);
       // n > d: Gram matrix of the retained rows in double (inputs are exact, products exact),
       // diagonally pivoted Cholesky for the rank, then the rows of the factor span the row space.
-      if (d == 128) gram_rows_f64<T, 8>(Vh, id, n, W);
-      else gram_rows_f64<T, 4>(Vh, id, n, W);
+      const int slot = gpart ? kg_rank_of(decided, n_keep, head, N, d, rank, red) : kKeepGramSlots;
+      if (slot < kKeepGramSlots) {
+        // the chunk sums of k_bf_keep_gram_part, added in chunk order
+        const double* gp = gpart + (size_t)slot * kKeepGramChunks * d * d;
+        for (int e = threadIdx.x; e < d * d; e += KB_THREADS) {
+          double s = 0.0;
+          for (int c = 0; c < kKeepGramChunks; ++c) s += gp[(size_t)c * d * d + e];
+          W[e] = s;
+        }
+        __syncthreads();
+      } else if (d == 128) {
+        gram_rows_f64<T, 8>(Vh, id, n, W);
+      } else {
+        gram_rows_f64<T, 4>(Vh, id, n, W);
+      }
       KB_STAMP(1);
       // sigma_max^2 = lambda_max(G): power iteration on G
       for (int c = threadIdx.x; c < d; c += KB_THREADS) xv[c] = 1.0 / sqrt((double)d) * (1.0 + 0.01 * (c % 7));
@@ -1008,6 +1084,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
+    (void)hipFuncSetAttribute((const void*)k_bf_keep_gram_part<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     attr_done = true;
   }
@@ -1033,8 +1110,15 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     if (!(min_budget > m.d && m.N > m.d) &&
         launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, st) != OBF_OK) return OBF_ERR_HIP;
     if (max_budget > m.d) {
+      double* gpart = nullptr;
+      if (max_budget >= kKeepGramMinBudget) {
+        gpart = (double*)(ws + w.keep_gram);
+        hipLaunchKernelGGL(k_bf_keep_gram_part<T>, dim3(kKeepGramChunks, kKeepGramSlots), dim3(KB_THREADS), smem_kb, st,
+                           (const T*)V, idx, n_keep, decided, m.heads, m.N, m.d, max_budget, rank, m.kvs, gpart);
+        if (check_launch("backfill keep_gram_part") != OBF_OK) return OBF_ERR_HIP;
+      }
       hipLaunchKernelGGL(k_bf_keep_basis<T>, dim3(m.heads), dim3(KB_THREADS), smem_kb, st, (const T*)V, scores, idx, n_keep,
-                         m.N, m.d, max_budget, rank, state, basis, decided, m.scs, m.kvs);
+                         m.N, m.d, max_budget, rank, state, basis, decided, m.scs, m.kvs, gpart);
       if (check_launch("backfill keep_basis") != OBF_OK) return OBF_ERR_HIP;
     }
   }

@@ -33,6 +33,13 @@ inline Dims make_dims(const obf_shape_t* s) {
   return m;
 }
 
+// Heads with many retained rows that the full-rank certificate does not settle (rare): the double-precision Gram
+// matrix of their rows is summed from kKeepGramChunks partial matrices computed by as many workgroups, for at most
+// kKeepGramSlots such heads per call (further ones compute it in their own workgroup); used from kKeepGramMinBudget rows.
+constexpr int kKeepGramChunks = 16;
+constexpr int kKeepGramSlots = 8;
+constexpr int kKeepGramMinBudget = 2048;
+
 // Workspace carving.  Every region is 256-byte aligned; offsets are from the workspace base.
 struct Workspace {
   size_t stats_part;   // double2 [heads][nchunk][R]      partial (max, sum-exp) per score chunk
@@ -51,6 +58,7 @@ struct Workspace {
   size_t layer_scores; // float   [L][N]        attention mass summed over the heads of a layer (layerwise selector)
   size_t layer_idx;    // int32   [L][max_budget], then int32 [L]: the shared index lists and their lengths
   size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
+  size_t keep_gram;    // double  [kKeepGramSlots][kKeepGramChunks][d*d]  partial Gram matrices (max_budget >= kKeepGramMinBudget)
   size_t total;
   int nchunk;          // score chunks per head
   int chunk_tokens;    // tokens per score chunk
@@ -115,6 +123,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.layer_scores = take(sizeof(float) * (size_t)m.L * m.N);
   w.layer_idx = take(sizeof(int32_t) * ((size_t)m.L * (max_budget > 0 ? max_budget : 0) + m.L));
   w.fro_part = take(sizeof(double) * (size_t)m.heads * ((max_budget > 0 ? max_budget : 0) / kGatherRows + 1));
+  w.keep_gram = take(max_budget >= kKeepGramMinBudget ? sizeof(double) * kKeepGramSlots * kKeepGramChunks * (size_t)m.d * m.d : 0);
   w.total = off;
   return w;
 }

@@ -142,6 +142,26 @@ def test_rank_deficient_retained_rows(gpu, budget):
     assert all(r.r_keep < 128 for r in reps)
 
 
+def test_rank_deficient_large_budget_uses_partial_gram_sums(gpu):
+    """More than 2048 retained rows of rank-deficient values on ten heads (two plain ones among them): the certificate
+    cannot settle the eight-plus deficient heads, the first eight of them get their double-precision Gram matrix as
+    sixteen partial sums from as many workgroups, the others compute it alone; all must agree with the oracle."""
+    cfg = si.RelayConfig("rankdef-big", 13, 1, 10, 2, 128, 6000, 8, 2200, 4, "bf16", "structured")
+
+    def edit(K, V, Q):
+        N = V.shape[2]
+        free = np.arange(N) % 211 == 7
+        for h in range(V.shape[1]):
+            if h in (3, 6):
+                continue                                   # ordinary heads: full rank, certified
+            rep = V[0, h, :24 + h].copy()                  # rank 24 + h (+ the free rows' directions)
+            tiled = rep[np.arange(N) % (24 + h)]
+            V[0, h] = np.where(free[:, None], V[0, h], tiled)
+
+    reps = _check_cfg(gpu, cfg, edit=edit)
+    assert sum(r.r_keep < 128 for r in reps) == 8 and sum(r.r_keep == 128 for r in reps) == 2
+
+
 def test_budget_edges_and_rank_zero(gpu):
     cfg = si.RelayConfig("edge", 8, 1, 4, 2, 64, 300, 8, 0, 2, "bf16", "structured")
     _check_cfg(gpu, cfg, budgets=[0, 300, 1000, 17], max_budget=300)
