@@ -375,14 +375,19 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
           if (threadIdx.x == 0) { const int t = perm[k]; perm[k] = perm[p]; perm[p] = t; }
           __syncthreads();
         }
-        const double rkk = sqrt(piv);
-        for (int c = k + threadIdx.x; c < d; c += KB_THREADS) W[k * d + c] = W[k * d + c] / rkk;   // row k of the factor
+        const double rinv = 1.0 / sqrt(piv);
+        for (int c = k + threadIdx.x; c < d; c += KB_THREADS) W[k * d + c] *= rinv;                // row k of the factor
         __syncthreads();
-        // trailing update: G[i][j] -= R[k][i] R[k][j] for i, j > k
-        const int rem = d - k - 1;
-        for (int e = threadIdx.x; e < rem * rem; e += KB_THREADS) {
-          const int i = k + 1 + e / rem, j = k + 1 + e % rem;
-          W[i * d + j] -= W[k * d + i] * W[k * d + j];
+        // trailing update: G[i][j] -= R[k][i] R[k][j] for i, j > k; 8 x 32 threads, a thread walks rows i = k+1+ty+8a
+        // and columns j = k+1+tx+32b (no index arithmetic beyond additions; a wave touches two row segments of 256 bytes)
+        {
+          const int ty = threadIdx.x >> 5, tx = threadIdx.x & 31;
+          const double* rk = W + k * d;
+          for (int i = k + 1 + ty; i < d; i += 8) {
+            const double ri = rk[i];
+            double* wi = W + i * d;
+            for (int j = k + 1 + tx; j < d; j += 32) wi[j] = fma(-ri, rk[j], wi[j]);
+          }
         }
         __syncthreads();
         r = k + 1;
