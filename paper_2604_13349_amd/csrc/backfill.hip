@@ -195,6 +195,48 @@ __device__ void gram_rows_f64(const T* __restrict__ Vh, const int32_t* __restric
   __syncthreads();
 }
 
+// True iff G - shift I (G symmetric d x d in LDS, d = 16 BS, left untouched) is positive definite: LDL^T without
+// pivoting on a register copy, thread (ty, tx) of the 16 x 16 grid holding G[ty + 16a][tx + 16b].  Step k: the sixteen
+// owners of row k publish it (two row buffers alternate, so one barrier per step), every thread divides by the pivot
+// and updates its BS x BS entries.  Runs through iff every pivot is positive, i.e. iff lambda_min(G) > shift.
+template <int BS>
+__device__ bool shifted_ldl_positive(const double* W, double shift, double* row0, double* row1) {
+  constexpr int D = 16 * BS;
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  double g[BS][BS];
+#pragma unroll
+  for (int a = 0; a < BS; ++a)
+#pragma unroll
+    for (int b = 0; b < BS; ++b) g[a][b] = W[(ty + 16 * a) * D + tx + 16 * b] - ((ty + 16 * a == tx + 16 * b) ? shift : 0.0);
+  bool ok = true;
+  for (int k = 0; k < D; ++k) {
+    double* rb = (k & 1) ? row1 : row0;
+    if ((k & 15) == ty) {
+#pragma unroll
+      for (int a = 0; a < BS; ++a)
+        if (a == (k >> 4)) {
+#pragma unroll
+          for (int b = 0; b < BS; ++b) rb[tx + 16 * b] = g[a][b];
+        }
+    }
+    __syncthreads();
+    const double piv = rb[k];                                  // the same value in every thread
+    if (!(piv > 0.0)) { ok = false; break; }
+    const double ip = 1.0 / piv;
+    double ri[BS], rj[BS];
+#pragma unroll
+    for (int a = 0; a < BS; ++a) ri[a] = rb[ty + 16 * a] * ip;
+#pragma unroll
+    for (int b = 0; b < BS; ++b) rj[b] = rb[tx + 16 * b];
+#pragma unroll
+    for (int a = 0; a < BS; ++a)
+#pragma unroll
+      for (int b = 0; b < BS; ++b) g[a][b] = fma(-ri[a], rj[b], g[a][b]);
+  }
+  __syncthreads();
+  return ok;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Heads of the general basis kernel (more than d retained rows, not settled by the certificate), numbered in head
 // order: the first kKeepGramSlots of them get their Gram matrix from partial matrices of kKeepGramChunks workgroups.
@@ -309,20 +351,34 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       // n > d: Gram matrix of the retained rows in double (inputs are exact, products exact),
       // diagonally pivoted Cholesky for the rank, then the rows of the factor span the row space.
       const int slot = gpart ? kg_rank_of(decided, n_keep, head, N, d, rank, red) : kKeepGramSlots;
-      if (slot < kKeepGramSlots) {
-        // the chunk sums of k_bf_keep_gram_part, added in chunk order
-        const double* gp = gpart + (size_t)slot * kKeepGramChunks * d * d;
-        for (int e = threadIdx.x; e < d * d; e += KB_THREADS) {
-          double s = 0.0;
-          for (int c = 0; c < kKeepGramChunks; ++c) s += gp[(size_t)c * d * d + e];
-          W[e] = s;
+      auto form_gram = [&]() {
+        if (slot < kKeepGramSlots) {
+          // the chunk sums of k_bf_keep_gram_part, added in chunk order
+          const double* gp = gpart + (size_t)slot * kKeepGramChunks * d * d;
+          for (int e = threadIdx.x; e < d * d; e += KB_THREADS) {
+            double s = 0.0;
+            for (int c = 0; c < kKeepGramChunks; ++c) s += gp[(size_t)c * d * d + e];
+            W[e] = s;
+          }
+          __syncthreads();
+        } else if (d == 128) {
+          gram_rows_f64<T, 8>(Vh, id, n, W);
+        } else {
+          gram_rows_f64<T, 4>(Vh, id, n, W);
         }
-        __syncthreads();
-      } else if (d == 128) {
-        gram_rows_f64<T, 8>(Vh, id, n, W);
-      } else {
-        gram_rows_f64<T, 4>(Vh, id, n, W);
-      }
+      };
+      // G[i][j] -= R[k][i] R[k][j] for i, j > k with row k of the factor in place: 8 x 32 threads, a thread walks rows
+      // i = k+1+ty+8a and columns j = k+1+tx+32b (a wave touches two row segments of 256 bytes)
+      auto trailing_update = [&](int k) {
+        const int ty = threadIdx.x >> 5, tx = threadIdx.x & 31;
+        const double* rk = W + k * d;
+        for (int i = k + 1 + ty; i < d; i += 8) {
+          const double ri = rk[i];
+          double* wi = W + i * d;
+          for (int j = k + 1 + tx; j < d; j += 32) wi[j] = fma(-ri, rk[j], wi[j]);
+        }
+      };
+      form_gram();
       KB_STAMP(1);
       // sigma_max^2 = lambda_max(G): power iteration on G
       for (int c = threadIdx.x; c < d; c += KB_THREADS) xv[c] = 1.0 / sqrt((double)d) * (1.0 + 0.01 * (c % 7));
@@ -350,49 +406,45 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       const double smax = sqrt(lam);
       const double thr = smax * (double)max(n, d) * kRankEps;     // on singular values
       KB_STAMP(2);
-      // diagonally pivoted Cholesky, upper factor kept in the upper triangle (row k, columns >= k)
-      for (int c = threadIdx.x; c < d; c += KB_THREADS) perm[c] = c;
-      __syncthreads();
-      int r = 0;
-      for (int k = 0; k < d; ++k) {
-        if (threadIdx.x < 128) {                                   // largest remaining diagonal entry, lowest index first
-          const int i = threadIdx.x;
-          const double dv = (i >= k && i < d) ? W[i * d + i] : 0.0;
-          uint64_t key = (dv > 0.0) ? ((((uint64_t)__double_as_longlong(dv)) & ~0x7FULL) | (uint64_t)(127 - i)) : 0ULL;
-          key = wave_max_u64(key);
-          if ((threadIdx.x & 63) == 0) pkey[threadIdx.x >> 6] = key;
-        }
+      // Full-rank shortcut (what a head missed by the single-precision certificate usually is): G - thr^2 I is
+      // positive definite iff every eigenvalue of G exceeds thr^2, i.e. every singular value of V_keep exceeds thr.
+      const bool full = (d == 128) ? shifted_ldl_positive<8>(W, thr * thr, xv, yv) : shifted_ldl_positive<4>(W, thr * thr, xv, yv);
+      int r = d;
+      if (!full) {
+        // diagonally pivoted Cholesky, upper factor kept in the upper triangle (row k, columns >= k)
+        for (int c = threadIdx.x; c < d; c += KB_THREADS) perm[c] = c;
         __syncthreads();
-        const uint64_t key = pkey[0] > pkey[1] ? pkey[0] : pkey[1];
-        const int p = key ? 127 - (int)(key & 0x7F) : k;
-        const double piv = W[p * d + p];
-        __syncthreads();                                             // pkey is rewritten in the next step
-        if (!(piv > 0.0) || !(sqrt(piv) > thr)) break;
-        if (p != k) {   // symmetric swap of rows/columns p and k
-          for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[k * d + c]; W[k * d + c] = W[p * d + c]; W[p * d + c] = t; }
-          __syncthreads();
-          for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[c * d + k]; W[c * d + k] = W[c * d + p]; W[c * d + p] = t; }
-          if (threadIdx.x == 0) { const int t = perm[k]; perm[k] = perm[p]; perm[p] = t; }
-          __syncthreads();
-        }
-        const double rinv = 1.0 / sqrt(piv);
-        for (int c = k + threadIdx.x; c < d; c += KB_THREADS) W[k * d + c] *= rinv;                // row k of the factor
-        __syncthreads();
-        // trailing update: G[i][j] -= R[k][i] R[k][j] for i, j > k; 8 x 32 threads, a thread walks rows i = k+1+ty+8a
-        // and columns j = k+1+tx+32b (no index arithmetic beyond additions; a wave touches two row segments of 256 bytes)
-        {
-          const int ty = threadIdx.x >> 5, tx = threadIdx.x & 31;
-          const double* rk = W + k * d;
-          for (int i = k + 1 + ty; i < d; i += 8) {
-            const double ri = rk[i];
-            double* wi = W + i * d;
-            for (int j = k + 1 + tx; j < d; j += 32) wi[j] = fma(-ri, rk[j], wi[j]);
+        r = 0;
+        for (int k = 0; k < d; ++k) {
+          if (threadIdx.x < 128) {                                   // largest remaining diagonal entry, lowest index first
+            const int i = threadIdx.x;
+            const double dv = (i >= k && i < d) ? W[i * d + i] : 0.0;
+            uint64_t key = (dv > 0.0) ? ((((uint64_t)__double_as_longlong(dv)) & ~0x7FULL) | (uint64_t)(127 - i)) : 0ULL;
+            key = wave_max_u64(key);
+            if ((threadIdx.x & 63) == 0) pkey[threadIdx.x >> 6] = key;
           }
+          __syncthreads();
+          const uint64_t key = pkey[0] > pkey[1] ? pkey[0] : pkey[1];
+          const int p = key ? 127 - (int)(key & 0x7F) : k;
+          const double piv = W[p * d + p];
+          __syncthreads();                                             // pkey is rewritten in the next step
+          if (!(piv > 0.0) || !(sqrt(piv) > thr)) break;
+          if (p != k) {   // symmetric swap of rows/columns p and k
+            for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[k * d + c]; W[k * d + c] = W[p * d + c]; W[p * d + c] = t; }
+            __syncthreads();
+            for (int c = threadIdx.x; c < d; c += KB_THREADS) { const double t = W[c * d + k]; W[c * d + k] = W[c * d + p]; W[c * d + p] = t; }
+            if (threadIdx.x == 0) { const int t = perm[k]; perm[k] = perm[p]; perm[p] = t; }
+            __syncthreads();
+          }
+          const double rinv = 1.0 / sqrt(piv);
+          for (int c = k + threadIdx.x; c < d; c += KB_THREADS) W[k * d + c] *= rinv;                // row k of the factor
+          __syncthreads();
+          trailing_update(k);
+          __syncthreads();
+          r = k + 1;
         }
         __syncthreads();
-        r = k + 1;
       }
-      __syncthreads();
       r_keep = r;
       KB_STAMP(3);
       if (r_keep < d) {
