@@ -118,7 +118,8 @@ obf_status_t obf_gather(const obf_shape_t* shape, const void* K, const void* V, 
 
 /* Orthogonal BackFill (Eq. 2-7, Alg. 3) on already gathered values: V_out holds
  * V[idx] on entry and V[idx] + delta on exit (rounded to dtype); untouched where OBF is
- * skipped.  `rank` is pca_rank (0 = plain eviction).  delta_out, diag nullable. */
+ * skipped.  `rank` is pca_rank (0 = plain eviction).  delta_out, diag nullable; the diagnostics take an extra pass over
+ * the scores of every head, so a caller on the hot path leaves diag NULL. */
 obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* scores, const int32_t* idx,
                           const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
                           float* delta_out, obf_diag_t* diag, void* ws, size_t ws_bytes, void* stream);

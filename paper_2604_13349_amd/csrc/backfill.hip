@@ -1159,7 +1159,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     int32_t* decided = nullptr;
     if (keep_cert_supported(m)) {
       decided = (int32_t*)(ws + w.decided);
-      if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part) != OBF_OK)
+      if (launch_keep_cert(m, V_out, 0, scores, idx, n_keep, max_budget, rank, state, decided, st, fro_part, diag != nullptr) != OBF_OK)
         return OBF_ERR_HIP;
     }
     ProfScope prof_(ST_KEEP_BASIS, st);

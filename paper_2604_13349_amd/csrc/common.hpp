@@ -193,7 +193,7 @@ obf_status_t launch_del_stats_mfma(const Dims& m, const Workspace& w, const void
 bool keep_cert_supported(const Dims& m);
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
-                              int32_t* decided, hipStream_t st, const double* fro_part = nullptr);
+                              int32_t* decided, hipStream_t st, const double* fro_part = nullptr, bool want_sums = true);
 obf_status_t launch_refine_layers(const Dims& m, const void* K, const void* Q, const float* layer_scores,
                                   const double* row_lse, int32_t max_budget, int32_t* idx_layer,
                                   const int32_t* n_keep_layer, double* part /*[heads][kBandCap]*/, hipStream_t st);

@@ -52,7 +52,8 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
                                                              int rank, HeadState* __restrict__ state,
                                                              int32_t* __restrict__ decided,
                                                              const double* __restrict__ fro_part /*optional: sums of squares of the retained rows, per gather block*/,
-                                                             int fro_blocks, int scs, int kvs) {
+                                                             int fro_blocks, int scs, int kvs,
+                                                             int want_sums /*0: the demand sums of a certified head (diagnostics only) are left at zero*/) {
   __shared__ uint32_t stage[2][(KC_TILE / 2) * KC_LDW];
   __shared__ __attribute__((aligned(16))) float panel[2][KC_D][4];
   __shared__ float4 ypan[KC_D], lpan[KC_D];
@@ -148,8 +149,9 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   // batch of loads is issued here and consumed after the factorisation, so that its latency is hidden.
   int ej[8];
   const bool vec_scores = (N & 3) == 0 && ((uintptr_t)sc & 15) == 0;
+  const int ns = want_sums ? n : 0, Ns = want_sums ? N : 0;          // extents of the two sums
 #pragma unroll
-  for (int u = 0; u < 8; ++u) { const int i = tid + u * KC_THREADS; ej[u] = (i < n) ? id[i] : -1; }
+  for (int u = 0; u < 8; ++u) { const int i = tid + u * KC_THREADS; ej[u] = (i < ns) ? id[i] : -1; }
   // tile j is staged in stage[j % 2]; the loads run two tiles ahead in registers
   KC_STAMP(1);
   fetch(pre[0], 0);
@@ -320,10 +322,10 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   double pk = 0.0, ptot = 0.0;
 #pragma unroll
   for (int u = 0; u < 8; ++u) pk += (double)ev[u];
-  for (int i0 = tid + 8 * KC_THREADS; i0 < n; i0 += 8 * KC_THREADS) {       // further batches of index -> score loads
+  for (int i0 = tid + 8 * KC_THREADS; i0 < ns; i0 += 8 * KC_THREADS) {      // further batches of index -> score loads
     int j[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) { const int i = i0 + u * KC_THREADS; j[u] = (i < n) ? id[i] : -1; }
+    for (int u = 0; u < 8; ++u) { const int i = i0 + u * KC_THREADS; j[u] = (i < ns) ? id[i] : -1; }
     float v[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) v[u] = (j[u] >= 0) ? sc[j[u]] : 0.f;
@@ -332,7 +334,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   }
   if (vec_scores) {
     const float4* sc4 = (const float4*)sc;
-    const int n4 = N >> 2;
+    const int n4 = Ns >> 2;
     for (int i0 = tid; i0 < n4; i0 += 8 * KC_THREADS) {
       float4 v[8];
 #pragma unroll
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
       for (int u = 0; u < 8; ++u) ptot += ((double)v[u].x + (double)v[u].y) + ((double)v[u].z + (double)v[u].w);
     }
   } else {
-    for (int i = tid; i < N; i += KC_THREADS) ptot += (double)sc[i];
+    for (int i = tid; i < Ns; i += KC_THREADS) ptot += (double)sc[i];
   }
   for (int off = 32; off > 0; off >>= 1) { pk += __shfl_xor(pk, off); ptot += __shfl_xor(ptot, off); }
   if (lane == 0) { red[wave] = pk; red2[wave] = ptot; }
@@ -362,15 +364,15 @@ bool keep_cert_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == K
 
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,
-                              int32_t* decided, hipStream_t st, const double* fro_part) {
+                              int32_t* decided, hipStream_t st, const double* fro_part, bool want_sums) {
   const int fro_blocks = (max_budget + kGatherRows - 1) / kGatherRows;
   { ProfScope prof_(ST_KEEP_CERT, st);
     if (via_idx)
       hipLaunchKernelGGL(k_bf_keep_cert<true>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
-                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks, m.scs, m.kvs);
+                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks, m.scs, m.kvs, want_sums ? 1 : 0);
     else
       hipLaunchKernelGGL(k_bf_keep_cert<false>, dim3(m.heads), dim3(KC_THREADS), 0, st, (const uint16_t*)Vsrc, scores, idx,
-                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks, m.scs, m.kvs); }
+                         n_keep, m.N, max_budget, rank, state, decided, fro_part, fro_blocks, m.scs, m.kvs, want_sums ? 1 : 0); }
   return check_launch("backfill keep_cert");
 }
 
