@@ -1182,7 +1182,9 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   // while the bases are still being written on the second stream the statistics pass must not read the head states
   const int32_t* nk_stats = basis_started ? n_keep : nullptr;
   if (rank > 0 && del_stats_mfma_supported(m)) {
-    if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, nk_stats, gram_part, st) != OBF_OK) return OBF_ERR_HIP;
+    // every budget above head_dim: the certificate settles nearly every head, the few others are found on the device
+    const bool few_active = min_budget > m.d && m.N > m.d && !var.skips_basis();
+    if (launch_del_stats_mfma(m, w, V, scores, idx, max_budget, state, nk_stats, gram_part, st, few_active) != OBF_OK) return OBF_ERR_HIP;
   } else if (rank > 0) {
     { ProfScope prof_(ST_DEL_STATS, st); hipLaunchKernelGGL(k_bf_del_stats<T>, dim3(w.nstat, m.heads), dim3(DS_THREADS), sizeof(float) * DS_TOK * m.d, st,
                        (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, nk_stats, gram_part, m.scs, m.kvs); }

@@ -189,7 +189,7 @@ bool del_stats_mfma_supported(const Dims& m);
 obf_status_t launch_del_stats_mfma(const Dims& m, const Workspace& w, const void* V, const float* scores,
                                    const int32_t* idx, int32_t max_budget, const HeadState* state,
                                    const int32_t* n_keep /*non-null: do not read the head states*/, float* gram_part,
-                                   hipStream_t st);
+                                   hipStream_t st, bool few_active = false /*nearly every head is expected to be inactive*/);
 bool keep_cert_supported(const Dims& m);
 obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state,

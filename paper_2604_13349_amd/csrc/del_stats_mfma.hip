@@ -27,14 +27,11 @@ __device__ __forceinline__ void dm_wave_tiles(int wave, int (&rb)[3], int (&cb)[
   else { rb[0] = 3; cb[0] = 0; rb[1] = 2; cb[1] = 2; rb[2] = 0; cb[2] = 0; nt = 2; }
 }
 
-__global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint16_t* __restrict__ V,
-                                                                     const float* __restrict__ scores,
-                                                                     const int32_t* __restrict__ idx, int N,
-                                                                     int max_budget, int nstat,
-                                                                     const HeadState* __restrict__ state,
-                                                                     const int32_t* __restrict__ n_keep /*non-null: the head states are still being written; every head with deleted rows is active*/,
-                                                                     float* __restrict__ gram_part, int scs, int kvs) {
-  const int head = blockIdx.y, chunk = blockIdx.x;
+// One chunk of one head (the whole workgroup).
+__device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const float* __restrict__ scores,
+                                         const int32_t* __restrict__ idx, int N, int max_budget, int nstat,
+                                         const HeadState* __restrict__ state, const int32_t* __restrict__ n_keep,
+                                         float* __restrict__ gram_part, int scs, int kvs, int head, int chunk) {
   const int n = n_keep ? n_keep[head] : state[head].n_keep;
   if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
   __shared__ uint32_t stage[2][(DM_TILE / 2) * DM_LDW];
@@ -207,14 +204,63 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
   }
 }
 
+// The active head whose number (in head order) is `target`, or -1; every thread gets it.  s_i has 5 entries.
+__device__ int dm_active_head(const HeadState* __restrict__ state, int heads, int target, int* s_i) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (threadIdx.x == 0) s_i[4] = -1;
+  int base = 0;
+  for (int h0 = 0; h0 < heads; h0 += DM_THREADS) {
+    const int h = h0 + threadIdx.x;
+    const bool p = h < heads && state[h].active != 0;
+    const uint64_t mask = __ballot(p);
+    __syncthreads();
+    if (lane == 0) s_i[wave] = __popcll(mask);
+    __syncthreads();
+    int before = base, tot = 0;
+    for (int w = 0; w < DM_THREADS / 64; ++w) { if (w < wave) before += s_i[w]; tot += s_i[w]; }
+    if (p && before + __popcll(mask & ((1ull << lane) - 1ull)) == target) s_i[4] = h;
+    base += tot;
+    if (base > target) break;                        // uniform: found
+  }
+  __syncthreads();
+  return s_i[4];
+}
+
+// grid (chunks, heads): workgroup (c, h) takes chunk c of head h.  With compact != 0 the grid is (chunks, a few rows) and
+// row y takes the active heads number y, y + rows, ... (found by scanning the head states): for calls in which the
+// certificate settles nearly every head, so that a launch over all heads would consist of workgroups that exit at once.
+__global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint16_t* __restrict__ V,
+                                                                     const float* __restrict__ scores,
+                                                                     const int32_t* __restrict__ idx, int N,
+                                                                     int max_budget, int nstat,
+                                                                     const HeadState* __restrict__ state,
+                                                                     const int32_t* __restrict__ n_keep /*non-null: the head states are still being written; every head with deleted rows is active*/,
+                                                                     float* __restrict__ gram_part, int scs, int kvs,
+                                                                     int compact, int heads) {
+  if (!compact) {
+    dm_chunk(V, scores, idx, N, max_budget, nstat, state, n_keep, gram_part, scs, kvs, blockIdx.y, blockIdx.x);
+    return;
+  }
+  __shared__ int s_i[5];
+  for (int s = blockIdx.y;; s += gridDim.y) {
+    const int head = dm_active_head(state, heads, s, s_i);
+    if (head < 0) return;
+    dm_chunk(V, scores, idx, N, max_budget, nstat, state, n_keep, gram_part, scs, kvs, head, blockIdx.x);
+  }
+}
+
 bool del_stats_mfma_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == DM_D; }
 
 obf_status_t launch_del_stats_mfma(const Dims& m, const Workspace& w, const void* V, const float* scores,
                                    const int32_t* idx, int32_t max_budget, const HeadState* state,
-                                   const int32_t* n_keep, float* gram_part, hipStream_t st) {
+                                   const int32_t* n_keep, float* gram_part, hipStream_t st, bool few_active) {
+  // few_active: the head states are final (n_keep == nullptr) and nearly all heads are expected to be inactive
+  // (a launch of a few thousand workgroups that exit at once is still cheaper than the scan)
+  const int compact = (few_active && !n_keep && (long)w.nstat * m.heads >= 4096) ? 1 : 0;
   { ProfScope prof_(ST_DEL_STATS, st);
-    hipLaunchKernelGGL(k_bf_del_stats_mfma, dim3(w.nstat, m.heads), dim3(DM_THREADS), 0, st, (const uint16_t*)V, scores,
-                       idx, m.N, max_budget, w.nstat, state, n_keep, gram_part, m.scs, m.kvs); }
+    hipLaunchKernelGGL(k_bf_del_stats_mfma, dim3(w.nstat, compact ? 8 : m.heads), dim3(DM_THREADS), 0, st, (const uint16_t*)V,
+                       scores, idx, m.N, max_budget, w.nstat, state, n_keep, gram_part, m.scs, m.kvs, compact, m.heads); }
   return check_launch("backfill del_stats (mfma)");
 }
 

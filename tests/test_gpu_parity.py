@@ -162,6 +162,26 @@ def test_rank_deficient_large_budget_uses_partial_gram_sums(gpu):
     assert sum(r.r_keep < 128 for r in reps) == 8 and sum(r.r_keep == 128 for r in reps) == 2
 
 
+def test_few_active_heads_among_many_certified_ones(gpu):
+    """256 heads of 16K tokens with budgets above head_dim, twelve of them rank-deficient: the certificate settles the
+    other 244, and the statistics launch (whose full grid would be 4096 workgroups) finds the twelve on the device, in
+    eight rows of workgroups that take more than one head each."""
+    cfg = si.RelayConfig("few-active", 14, 32, 8, 1, 128, 16384, 8, 2100, 4, "bf16", "structured")
+    special = {5, 77, 130, 131, 200, 255, 16, 17, 18, 100, 180, 254}
+
+    def edit(K, V, Q):
+        N = V.shape[2]
+        free = np.arange(N) % 509 == 3
+        for hh in special:
+            l, h = divmod(hh, V.shape[1])
+            rep = V[l, h, :40].copy()
+            V[l, h] = np.where(free[:, None], V[l, h], rep[np.arange(N) % 40])
+
+    reps = _check_cfg(gpu, cfg, edit=edit)
+    low = [i for i, r in enumerate(reps) if r.r_keep is not None and r.r_keep < 128]
+    assert set(low) == special
+
+
 def test_budget_edges_and_rank_zero(gpu):
     cfg = si.RelayConfig("edge", 8, 1, 4, 2, 64, 300, 8, 0, 2, "bf16", "structured")
     _check_cfg(gpu, cfg, budgets=[0, 300, 1000, 17], max_budget=300)
