@@ -5,7 +5,7 @@
 
 namespace obf {
 
-constexpr int SEL_BATCH = 256;   // heads per launch when budgets differ per head
+constexpr int SEL_BATCH = 896;   // heads per launch when budgets differ per head (the budgets travel as a kernel argument: 3.5 KB of the 4 KB)
 
 struct BudgetBatch { int32_t b[SEL_BATCH]; };
 
