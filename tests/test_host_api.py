@@ -86,6 +86,42 @@ def test_argument_errors_are_reported_before_any_device_work(lib):
     assert lib.obf_profile_enable(999) == 1
 
 
+def test_variant_window_and_message_argument_errors(lib):
+    sh = B.make_shape(2, 2, 2, 64, 100, 4, "f32")
+    fake = C.c_void_p(256 * 7)          # never dereferenced
+    tail = (fake, fake, fake, fake, None, None, None, fake, 1 << 30, None)
+    for var, word in ((B.make_variant(subspace=5), "subspace"), (B.make_variant(subspace="evr", evr_tau=0.0), "evr_tau"),
+                      (B.make_variant(subspace="evr", evr_tau=1.01), "evr_tau")):
+        rc, msg = _status(lib, lib.obf_compress_relay_variant, C.byref(sh), fake, fake, fake, None, 5, 5, 1, 0, C.byref(var), *tail)
+        assert rc == 1 and word in msg
+        rc, msg = _status(lib, lib.obf_backfill_variant, C.byref(sh), fake, fake, fake, fake, 5, 1, C.byref(var), fake, None, None,
+                          fake, 1 << 30, None)
+        assert rc == 1 and word in msg
+    for win, word in ((B._Window(99, 0), "token_stride"), (B._Window(0, 100), "sink"), (B._Window(0, -1), "sink")):
+        rc, msg = _status(lib, lib.obf_compress_relay_window, C.byref(sh), C.byref(win), fake, fake, fake, None, 5, 5, 1, 0, None, *tail)
+        assert rc == 1 and word in msg
+    # a budget is counted in eligible tokens: 97 of them behind a sink of 3, so a budget of 98 keeps 97 > max_budget 96
+    rc, msg = _status(lib, lib.obf_compress_relay_window, C.byref(sh), C.byref(B._Window(0, 3)), fake, fake, fake, None, 98, 96, 1, 0,
+                      None, *tail)
+    assert rc == 1 and "max_budget" in msg
+    msg_args = dict(prev=(fake, fake, None, 4, 8), keep=(fake, fake, fake, 8), gen=(fake, fake, 2, 2))
+
+    def append(n_heads=4, d=64, dtype=B.OBF_F32, prev=msg_args["prev"], keep=msg_args["keep"], gen=msg_args["gen"], out=(fake, fake, fake, 32)):
+        return _status(lib, lib.obf_append_message, n_heads, d, dtype, *prev, *keep, *gen, *out, None)
+
+    assert append(n_heads=0)[0] == 1
+    assert append(d=96)[0] == 2
+    assert append(dtype=7)[0] == 1
+    rc, msg = append(prev=(fake, fake, None, 9, 8)); assert rc == 1 and "prev_len_all" in msg
+    rc, msg = append(prev=(None, fake, None, 4, 8)); assert rc == 1 and "prev" in msg
+    rc, msg = append(keep=(None, fake, fake, 8)); assert rc == 1 and "keep" in msg
+    rc, msg = append(gen=(fake, fake, 3, 2)); assert rc == 1 and "n_gen" in msg
+    rc, msg = append(gen=(None, fake, 2, 2)); assert rc == 1 and "gen" in msg
+    rc, msg = append(out=(fake, fake, None, 32)); assert rc == 1 and "msg_len" in msg
+    rc, msg = append(out=(fake, fake, fake, 0)); assert rc == 1
+    rc, msg = append(keep=(None, None, None, 0), out=(fake, fake, fake, 5)); assert rc == 1 and "msg_stride" in msg
+
+
 def test_binding_raises_without_library(monkeypatch, tmp_path):
     monkeypatch.setenv("OBF_RELAY_LIB", str(tmp_path / "missing.so"))
     monkeypatch.setattr(B, "_lib", None)
