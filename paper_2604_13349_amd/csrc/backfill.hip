@@ -881,6 +881,12 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           s = t * c;
         }
       };
+      // The work items of a rotation set - the half x half blocks of T (those with i <= j do the work) and the half x mm
+      // (rotation, row) pairs of W - are walked with a stride of FN_THREADS; their two indices advance by fixed steps,
+      // so the sets contain no division.
+      const int nb = half * half, nw = half * mm;
+      const int bi0 = tid / max(half, 1), bj0 = tid - bi0 * half, bdi = FN_THREADS / max(half, 1), bdj = FN_THREADS - bdi * half;
+      const int wi0 = tid / max(mm, 1), wk0 = tid - wi0 * mm, wdi = FN_THREADS / max(mm, 1), wdk = FN_THREADS - wdi * mm;
       for (int sweep = 0; sweep < FN_SWEEPS && mm > 1; ++sweep) {
         for (int round = 0; round < mm - 1; ++round) {
           if (tid < half) {
@@ -895,33 +901,32 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           __syncthreads();
           // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j, mirrored: the blocks are
           // disjoint, so one pass does both sides), and W <- W J by columns
-          const int nb = half * half;
-          for (int e = tid; e < nb + half * mm; e += FN_THREADS) {
-            if (e < nb) {
-              const int i = e / half, jb = e - i * half;
-              if (i <= jb) {
-                const int p = pp[i], q = qq[i], p2 = pp[jb], q2 = qq[jb];
-                const float ci = cs[i], si = sn[i], cj = cs[jb], sj = sn[jb];
-                const float a = M[p * lt + p2], b = M[p * lt + q2], c = M[q * lt + p2], dd = M[q * lt + q2];
-                const float a1 = cj * a - sj * b, b1 = sj * a + cj * b, c1 = cj * c - sj * dd, d1 = sj * c + cj * dd;
-                const float a2 = ci * a1 - si * c1, c2 = si * a1 + ci * c1, b2 = ci * b1 - si * d1, d2 = si * b1 + ci * d1;
-                if (i == jb) {
-                  const float od = 0.5f * (b2 + c2);
-                  M[p * lt + p] = a2; M[q * lt + q] = d2; M[p * lt + q] = od; M[q * lt + p] = od;
-                } else {
-                  M[p * lt + p2] = a2; M[p * lt + q2] = b2; M[q * lt + p2] = c2; M[q * lt + q2] = d2;
-                  M[p2 * lt + p] = a2; M[q2 * lt + p] = b2; M[p2 * lt + q] = c2; M[q2 * lt + q] = d2;
-                }
+          for (int e = tid, i = bi0, jb = bj0; e < nb; e += FN_THREADS) {
+            if (i <= jb) {
+              const int p = pp[i], q = qq[i], p2 = pp[jb], q2 = qq[jb];
+              const float ci = cs[i], si = sn[i], cj = cs[jb], sj = sn[jb];
+              const float a = M[p * lt + p2], b = M[p * lt + q2], c = M[q * lt + p2], dd = M[q * lt + q2];
+              const float a1 = cj * a - sj * b, b1 = sj * a + cj * b, c1 = cj * c - sj * dd, d1 = sj * c + cj * dd;
+              const float a2 = ci * a1 - si * c1, c2 = si * a1 + ci * c1, b2 = ci * b1 - si * d1, d2 = si * b1 + ci * d1;
+              if (i == jb) {
+                const float od = 0.5f * (b2 + c2);
+                M[p * lt + p] = a2; M[q * lt + q] = d2; M[p * lt + q] = od; M[q * lt + p] = od;
+              } else {
+                M[p * lt + p2] = a2; M[p * lt + q2] = b2; M[q * lt + p2] = c2; M[q * lt + q2] = d2;
+                M[p2 * lt + p] = a2; M[q2 * lt + p] = b2; M[p2 * lt + q] = c2; M[q2 * lt + q] = d2;
               }
-            } else {
-              const int e2 = e - nb;
-              const int i = e2 / mm, k = e2 - i * mm;
-              const int p = pp[i], q = qq[i];
-              const float c = cs[i], s = sn[i];
-              const float wp = U[k * lt + p], wq = U[k * lt + q];
-              U[k * lt + p] = c * wp - s * wq;
-              U[k * lt + q] = s * wp + c * wq;
             }
+            i += bdi; jb += bdj;
+            if (jb >= half) { jb -= half; ++i; }
+          }
+          for (int e = tid, i = wi0, k = wk0; e < nw; e += FN_THREADS) {
+            const int p = pp[i], q = qq[i];
+            const float c = cs[i], s = sn[i];
+            const float wp = U[k * lt + p], wq = U[k * lt + q];
+            U[k * lt + p] = c * wp - s * wq;
+            U[k * lt + q] = s * wp + c * wq;
+            i += wdi; k += wdk;
+            if (k >= mm) { k -= mm; ++i; }
           }
           __syncthreads();
         }
