@@ -589,6 +589,12 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
 constexpr int FN_THREADS = 1024;
 constexpr int FN_WAVES = FN_THREADS / 64;
 constexpr int FN_SWEEPS = 12;
+// Floats of dynamic LDS of the first finalisation launch: room for the d x (d+1) projector and for T and W of every
+// complement up to three quarters of d wide (74.5 KB at d = 128, so that two workgroups still share a CU).
+__host__ __device__ inline int fn_small_floats(int d) {
+  const int mq = 3 * d / 4, a = d * (d + 1), b = 2 * mq * (mq + 1);
+  return a > b ? a : b;
+}
 
 template <typename T>
 __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int nstat, int rank,
@@ -622,11 +628,11 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   const int tid = threadIdx.x;
   const bool naive = (vflags & VF_NAIVE) != 0;
   {
-    // Two launches share the heads: the first has LDS for one d x d matrix (two workgroups per CU) and takes
+    // Two launches share the heads: the first has fn_small_floats(d) floats of LDS (two workgroups per CU) and takes
     // every head whose complement is small enough for T and W to fit there, the second takes the rest.
     const int m0 = (st.active && !naive) ? d - st.r_keep : 0;
     const int mm0 = m0 + (m0 & 1);
-    const int big = 2 * mm0 * (mm0 + 1) > d * ld;
+    const int big = 2 * mm0 * (mm0 + 1) > fn_small_floats(d);
     if (cls >= 0 && big != cls) return;                        // cls < 0: one launch with the large LDS takes every head
   }
 
@@ -842,7 +848,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       }
     }
     __syncthreads();                                             // Z (in LDS) is dead from here on
-    U = (2 * mm * lt <= d * ld) ? sm + mm * lt : sm + d * ld;    // W next to T, or in the second buffer of the large launch
+    U = (2 * mm * lt <= fn_small_floats(d)) ? sm + mm * lt : sm + d * ld;   // W next to T, or in the second buffer of the large launch
     if (ttile) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -1206,7 +1212,8 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     // launch with the large LDS size serves both classes instead of two launches that mostly exit at once
     const bool single = min_budget > m.d && m.N > m.d && !var.skips_basis();
     for (int cls = single ? -1 : 0; cls < (single ? 0 : 2); ++cls) {
-      hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), one * (cls < 0 ? 2 : cls + 1), st, m.N, m.d,
+      const size_t lds = (cls == 0) ? sizeof(float) * (size_t)fn_small_floats(m.d) : 2 * one;
+      hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), lds, st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
                          var.flags, var.evr_tau, m.scs);
