@@ -10,7 +10,7 @@ namespace obf {
 constexpr int kMaxTokens = 32768;
 constexpr int kNumCU = 256;             // compute units of the target (MI355X)
 constexpr int kStatChunk = 1024;        // tokens per deleted-value statistics workgroup
-constexpr int kGatherRows = 16;         // rows per gather workgroup when a row is 256 bytes (bf16, head_dim 128)
+constexpr int kGatherRows = 64;         // rows per gather workgroup when a row is 256 bytes (bf16, head_dim 128)
 constexpr int kBandCap = 256;           // most boundary candidates re-scored per head
 constexpr double kEps = 1e-12;          // epsilon of Eq. 4 / Eq. 6
 constexpr float kBandRel = 1.0e-4f;     // relative half-width of the refinement band

@@ -5,6 +5,7 @@
 namespace obf {
 
 constexpr int GA_THREADS = 256;
+constexpr int GA_UNROLL = 4;             // rows per thread
 
 __global__ __launch_bounds__(GA_THREADS) void k_gather(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                        const int32_t* __restrict__ idx,
@@ -13,31 +14,47 @@ __global__ __launch_bounds__(GA_THREADS) void k_gather(const uint4* __restrict__
                                                        double* __restrict__ fro_part /*bf16 rows of 256 bytes only*/) {
   __shared__ float s_red[GA_THREADS / 64];
   const int head = blockIdx.y;
-  const int rows_per_block = GA_THREADS / row_vec;
-  const int r = blockIdx.x * rows_per_block + threadIdx.x / row_vec;
+  const int rows_per_pass = GA_THREADS / row_vec;
+  const int r0 = blockIdx.x * rows_per_pass * GA_UNROLL + threadIdx.x / row_vec;
   const int c = threadIdx.x % row_vec;
-  if (r >= max_budget && !fro_part) return;
   const int n = n_keep[head];
-  const size_t o = ((size_t)head * max_budget + r) * row_vec + c;
-  uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-  if (r < n && r < max_budget) {
-    const int j = idx[(size_t)head * max_budget + r];
-    const size_t s = ((size_t)head * kvs + j) * row_vec + c;
-    if (K_out) kv = K[s];
-    if (V_out) vv = V[s];
+  // GA_UNROLL rows per thread, all loads issued before the first store
+  int j[GA_UNROLL];
+#pragma unroll
+  for (int u = 0; u < GA_UNROLL; ++u) {
+    const int r = r0 + u * rows_per_pass;
+    j[u] = (r < n && r < max_budget) ? idx[(size_t)head * max_budget + r] : -1;
   }
-  if (r < max_budget) {
-    if (K_out) K_out[o] = kv;
-    if (V_out) V_out[o] = vv;
+  uint4 kv[GA_UNROLL], vv[GA_UNROLL];
+#pragma unroll
+  for (int u = 0; u < GA_UNROLL; ++u) {
+    kv[u] = make_uint4(0, 0, 0, 0); vv[u] = make_uint4(0, 0, 0, 0);
+    if (j[u] >= 0) {
+      const size_t s = ((size_t)head * kvs + j[u]) * row_vec + c;
+      if (K_out) kv[u] = K[s];
+      if (V_out) vv[u] = V[s];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < GA_UNROLL; ++u) {
+    const int r = r0 + u * rows_per_pass;
+    if (r < max_budget) {
+      const size_t o = ((size_t)head * max_budget + r) * row_vec + c;
+      if (K_out) K_out[o] = kv[u];
+      if (V_out) V_out[o] = vv[u];
+    }
   }
   if (fro_part) {
     // sum of squares of this workgroup's V rows (zero for the padding), in a fixed order
-    const uint32_t w4[4] = {vv.x, vv.y, vv.z, vv.w};
     float sq = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float a = __uint_as_float(w4[i] << 16), b = __uint_as_float(w4[i] & 0xffff0000u);
-      sq = fmaf(a, a, sq); sq = fmaf(b, b, sq);
+    for (int u = 0; u < GA_UNROLL; ++u) {
+      const uint32_t w4[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a = __uint_as_float(w4[i] << 16), b = __uint_as_float(w4[i] & 0xffff0000u);
+        sq = fmaf(a, a, sq); sq = fmaf(b, b, sq);
+      }
     }
     for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = sq;
@@ -52,7 +69,7 @@ obf_status_t launch_gather(const Dims& m, const void* K, const void* V, const in
   if (max_budget == 0 || (!K_out && !V_out)) return OBF_OK;
   if (!(m.dtype == OBF_BF16 && m.d * m.esize == 256 && V_out)) fro_part = nullptr;
   const int row_vec = m.d * m.esize / 16;            // 8, 16 or 32
-  const int rows_per_block = GA_THREADS / row_vec;
+  const int rows_per_block = GA_UNROLL * GA_THREADS / row_vec;
   dim3 grid((max_budget + rows_per_block - 1) / rows_per_block, m.heads);
   { ProfScope prof_(ST_GATHER, st); hipLaunchKernelGGL(k_gather, grid, dim3(GA_THREADS), 0, st, (const uint4*)K, (const uint4*)V, idx, n_keep, m.kvs, row_vec,
                      max_budget, (uint4*)K_out, (uint4*)V_out, fro_part); }
