@@ -588,7 +588,8 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
 // finalize: per head, everything after the streaming pass
 constexpr int FN_THREADS = 1024;
 constexpr int FN_WAVES = FN_THREADS / 64;
-constexpr int FN_SWEEPS = 12;
+constexpr int FN_SWEEPS = kJacobiSweeps;
+constexpr int FN_REPLAY_MIN = 64;        // complements at least this wide do not accumulate eigenvectors (see the Jacobi phase)
 // Floats of dynamic LDS of the first finalisation launch: room for the d x (d+1) projector and for T and W of every
 // complement up to three quarters of d wide (74.5 KB at d = 128, so that two workgroups still share a CU).
 __host__ __device__ inline int fn_small_floats(int d) {
@@ -606,7 +607,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
                                                             T* __restrict__ V_out, int max_budget, int cls,
                                                             const float* __restrict__ scores,
                                                             const int32_t* __restrict__ idx, int vflags, float evr_tau,
-                                                            int scs) {
+                                                            int scs, float* __restrict__ rot /*nullable*/) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
@@ -876,15 +877,32 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     if (!negligible) {
       // cyclic Jacobi with a round-robin ordering: mm/2 disjoint rotations per round
       const int half = mm / 2;
-      auto rot_of = [&](const float* A, const int p, const int q, float& c, float& s) {
+      // Wide complements: only W_k W_k^T y is needed of the eigenvectors (y = Z u, W_k the k_used leading ones), and
+      // W is the product of all rotations.  Instead of carrying the m x m matrix W through every rotation set (most
+      // of a set's work when m is large), the tangents are stored, y is rotated along (z = W^T y costs two entries
+      // per rotation), and afterwards the kept coordinates of z are taken back through the rotations in reverse order
+      // by one wave.  The result is the same product of the same rotations.
+      const bool replay = rot != nullptr && mm >= FN_REPLAY_MIN;
+      float* rot_h = rot ? rot + (size_t)head * FN_SWEEPS * (d - 1) * (d / 2) : nullptr;
+      int nsweeps = 0;
+      if (replay) {
+        if (tid < mm) {
+          float s = 0.f;
+          if (tid < m) for (int c = 0; c < d; ++c) s = fmaf(Zg[(size_t)tid * d + c], uvec[c], s);
+          rbar[tid] = s;                                       // y = Z u
+        }
+        __syncthreads();
+      }
+      auto rot_of = [&](const float* A, const int p, const int q, float& c, float& s, float& tt) {
         const float app = A[p * lt + p], aqq = A[q * lt + q], apq = A[p * lt + q];
-        c = 1.f; s = 0.f;
+        c = 1.f; s = 0.f; tt = 0.f;
         // single-instruction reciprocal / square roots (1 ulp): the rotation only has to be orthogonal to rounding
         if (fabsf(apq) > 1e-30f && fabsf(apq) > 1e-9f * __builtin_amdgcn_sqrtf(fabsf(app * aqq)) ) {
           const float tau = (aqq - app) * __builtin_amdgcn_rcpf(2.f * apq);
           const float t = copysignf(__builtin_amdgcn_rcpf(fabsf(tau) + __builtin_amdgcn_sqrtf(fmaf(tau, tau, 1.f))), tau);
           c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f));
           s = t * c;
+          tt = t;
         }
       };
       // The work items of a rotation set - the half x half blocks of T (those with i <= j do the work) and the half x mm
@@ -900,9 +918,15 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             if (tid == 0) { p = mm - 1; q = round; }
             else { p = (round + tid) % (mm - 1); q = (round - tid + (mm - 1)) % (mm - 1); }
             if (p > q) { const int t = p; p = q; q = t; }
-            float c, s;
-            rot_of(M, p, q, c, s);
+            float c, s, t;
+            rot_of(M, p, q, c, s, t);
             pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
+            if (replay) {
+              rot_h[((size_t)sweep * (mm - 1) + round) * half + tid] = t;
+              const float zp = rbar[p], zq = rbar[q];            // z <- J^T z
+              rbar[p] = c * zp - s * zq;
+              rbar[q] = s * zp + c * zq;
+            }
           }
           __syncthreads();
           // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j, mirrored: the blocks are
@@ -925,7 +949,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             i += bdi; jb += bdj;
             if (jb >= half) { jb -= half; ++i; }
           }
-          for (int e = tid, i = wi0, k = wk0; e < nw; e += FN_THREADS) {
+          for (int e = tid, i = wi0, k = wk0; e < nw && !replay; e += FN_THREADS) {
             const int p = pp[i], q = qq[i];
             const float c = cs[i], s = sn[i];
             const float wp = U[k * lt + p], wq = U[k * lt + q];
@@ -949,6 +973,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         __syncthreads();
         const float offn = s_off;
         __syncthreads();
+        nsweeps = sweep + 1;
         if (offn <= 1e-13f * res2 * res2) break;
       }
       BF_STAMP(1, 6);
@@ -991,6 +1016,46 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       revr = (k_used > 0) ? s_off : 0.f;
       __syncthreads();
       if (k_used > 0) {
+       if (replay) {
+        // x = W D z with D keeping the k_used leading coordinates: the rotations in reverse order, x <- J x, by wave 0
+        // (lane i owns rotation i of a set; the pairs of a set are disjoint and a wave's LDS accesses stay in order)
+        if (tid < mm) dvec[tid] = 0.f;
+        __syncthreads();
+        if (tid < k_used) dvec[order[tid]] = rbar[order[tid]];
+        __syncthreads();
+        if (tid < 64) {
+          const int nr = mm - 1;
+          for (int sw = nsweeps - 1; sw >= 0; --sw) {
+            // pair of lane i in set `round`: (mm-1, round) for i = 0, else ((round + i) mod nr, (round - i) mod nr); walked backwards
+            int p = (tid == 0) ? nr : (nr - 1 + tid) % nr, q = (tid == 0) ? nr - 1 : (2 * nr - 1 - tid) % nr;
+            for (int r0 = nr - 1; r0 >= 0; r0 -= 16) {
+              float tb[16];                                    // the tangents of sixteen sets are fetched together
+#pragma unroll
+              for (int u = 0; u < 16; ++u)
+                tb[u] = (r0 - u >= 0 && tid < half) ? rot_h[((size_t)sw * nr + (r0 - u)) * half + tid] : 0.f;
+#pragma unroll
+              for (int u = 0; u < 16; ++u) {
+                const int round = r0 - u;
+                if (round >= 0) {
+                  if (tid < half) {
+                    const float t = tb[u];
+                    const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f)), s = t * c;
+                    const int a = min(p, q), b = max(p, q);
+                    const float xa = dvec[a], xb = dvec[b];
+                    dvec[a] = c * xa + s * xb;
+                    dvec[b] = c * xb - s * xa;
+                  }
+                  if (tid == 0) q = round - 1; else { p = (p == 0) ? nr - 1 : p - 1; q = (q == 0) ? nr - 1 : q - 1; }
+                  __builtin_amdgcn_wave_barrier();             // the next set reads what other lanes have just written
+                }
+              }
+            }
+          }
+        }
+        __syncthreads();
+        if (tid < m) lamv[tid] = dvec[tid];                    // Delta in complement coordinates (times a_del + eps)
+        __syncthreads();
+       } else {
         // In complement coordinates: y = Z u, so that rbar = Z^T y / (a_del + eps)  (Eq. 4 with R_j = P v_j)
         if (tid < m) {
           float s = 0.f;
@@ -1012,6 +1077,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           lamv[tid] = s;                                   // Delta in complement coordinates (times a_del + eps)
         }
         __syncthreads();
+       }
         if (tid < d) {
           float s = 0.f;
           for (int t = 0; t < m; ++t) s = fmaf(Zg[(size_t)t * d + tid], lamv[t], s);
@@ -1216,7 +1282,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
       hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), lds, st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
-                         var.flags, var.evr_tau, m.scs);
+                         var.flags, var.evr_tau, m.scs, (max_budget < m.d && rank > 0) ? (float*)(ws + w.rot) : (float*)nullptr);
     }
   }
   if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;

@@ -36,6 +36,7 @@ inline Dims make_dims(const obf_shape_t* s) {
 // Heads with many retained rows that the full-rank certificate does not settle (rare): the double-precision Gram
 // matrix of their rows is summed from kKeepGramChunks partial matrices computed by as many workgroups, for at most
 // kKeepGramSlots such heads per call (further ones compute it in their own workgroup); used from kKeepGramMinBudget rows.
+constexpr int kJacobiSweeps = 12;       // cap of the cyclic Jacobi iteration of the finalisation
 constexpr int kKeepGramChunks = 16;
 constexpr int kKeepGramSlots = 8;
 constexpr int kKeepGramMinBudget = 2048;
@@ -58,6 +59,7 @@ struct Workspace {
   size_t layer_scores; // float   [L][N]        attention mass summed over the heads of a layer (layerwise selector)
   size_t layer_idx;    // int32   [L][max_budget], then int32 [L]: the shared index lists and their lengths
   size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
+  size_t rot;          // float   [heads][kJacobiSweeps][d-1][d/2]  rotation tangents of the Jacobi iteration (max_budget < d only)
   size_t keep_gram;    // double  [kKeepGramSlots][kKeepGramChunks][d*d]  partial Gram matrices (max_budget >= kKeepGramMinBudget)
   size_t total;
   int nchunk;          // score chunks per head
@@ -83,7 +85,6 @@ __host__ __device__ inline size_t gram_stride(int d) { return (size_t)d * d + 2 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 inline Workspace carve(const Dims& m, int max_budget, int rank) {
-  (void)rank;
   Workspace w;
   // reference-precision score path: fixed chunks of 512 tokens
   w.chunk_tokens = 512;
@@ -123,6 +124,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.layer_scores = take(sizeof(float) * (size_t)m.L * m.N);
   w.layer_idx = take(sizeof(int32_t) * ((size_t)m.L * (max_budget > 0 ? max_budget : 0) + m.L));
   w.fro_part = take(sizeof(double) * (size_t)m.heads * ((max_budget > 0 ? max_budget : 0) / kGatherRows + 1));
+  w.rot = take((max_budget < m.d && rank > 0) ? sizeof(float) * (size_t)m.heads * kJacobiSweeps * (m.d - 1) * (m.d / 2) : 0);
   w.keep_gram = take(max_budget >= kKeepGramMinBudget ? sizeof(double) * kKeepGramSlots * kKeepGramChunks * (size_t)m.d * m.d : 0);
   w.total = off;
   return w;
