@@ -41,6 +41,13 @@ constexpr int kKeepGramChunks = 16;
 constexpr int kKeepGramSlots = 8;
 constexpr int kKeepGramMinBudget = 2048;
 
+// Query rows per workgroup of the matrix-core score kernels: 128 (four 32-row blocks) or 160 (five), whichever pads the
+// g * W rows of a KV head less; ties go to 128, which has one more K buffer in flight.
+inline int score_rows_per_group(int R) {
+  const int g4 = (R + 127) / 128, g5 = (R + 159) / 160;
+  return (g5 * 160 - R < g4 * 128 - R) ? 160 : 128;
+}
+
 // Workspace carving.  Every region is 256-byte aligned; offsets are from the workspace base.
 struct Workspace {
   size_t stats_part;   // double2 [heads][nchunk][R]      partial (max, sum-exp) per score chunk
@@ -92,7 +99,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.nstat = (m.N + kStatChunk - 1) / kStatChunk;
   // matrix-core score path: the flattened (head, 32-token tile) space is cut into one range per
   // persistent workgroup; a head is covered by at most nslot ranges
-  w.rgroups = (m.R + 127) / 128;
+  w.rgroups = (m.R + score_rows_per_group(m.R) - 1) / score_rows_per_group(m.R);
   w.tiles_per_head = (m.N + 31) / 32;
   {
     const long TT = (long)m.heads * w.tiles_per_head;

@@ -22,8 +22,9 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int SM_THREADS = 256;
 constexpr int SM_WAVES = 4;
-constexpr int SM_RB = 4;                 // 32-row blocks per row group
-constexpr int SM_ROWS = SM_RB * 32;      // query rows per workgroup
+// The kernels are instantiated for (RB, KBUF) = (4, 3) and (5, 2): RB 32-row blocks of query rows per workgroup (RB * 32 = 128
+// or 160 rows, their Q operand in RB * 32 registers per lane) and KBUF rotating K fragment buffers.  RB * KBUF is even, so the
+// two accumulators keep alternating across the iterations of the tile loop.
 constexpr int SM_D = 128;
 constexpr int SM_KK = SM_D / 16;         // MFMA k-steps
 constexpr int SM_TILE = 32;              // tokens per MFMA tile
@@ -34,10 +35,11 @@ union Frag { uint4 u; bf16x8 v; };
 // Rows past R and tokens past t_end are clamped to the last valid one instead of being predicated: their
 // results are never used (padded rows get lse = +inf in pass B and are not written in pass A; tokens past the
 // end are masked by index), and branch-free loads keep the fragments in registers.
-__device__ __forceinline__ void load_q(Frag (&qf)[SM_RB][SM_KK], const uint16_t* __restrict__ Qh, int row0, int R, int lane) {
+template <int RB>
+__device__ __forceinline__ void load_q(Frag (&qf)[RB][SM_KK], const uint16_t* __restrict__ Qh, int row0, int R, int lane) {
   const int r = lane & 31, kh = (lane >> 5) * 8;
 #pragma unroll
-  for (int rb = 0; rb < SM_RB; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     const int row = min(row0 + rb * 32 + r, R - 1);
     const uint4* p = (const uint4*)(Qh + (size_t)row * SM_D + kh);
 #pragma unroll
@@ -75,9 +77,10 @@ __device__ __forceinline__ void block_mfma(f32x16& acc, const Frag (&kf)[SM_KK],
 // Pass A epilogue of one row block of a tile whose 32 tokens are all valid.  acc[i] is the raw dot product
 // of token tok + (i/4)*8 + (lane/32)*4 + (i%4) with query row row0 + rb*32 + lane%32.  m is the running
 // maximum in raw units, l the running sum of exp2((raw - m) a2) in double.
+template <int NRB>
 struct StatsEp {
-  float (&m)[SM_RB];
-  double (&l)[SM_RB];
+  float (&m)[NRB];
+  double (&l)[NRB];
   float a2;
   template <int RB>
   __device__ __forceinline__ void block(const f32x16& acc, int) {
@@ -135,8 +138,9 @@ __device__ __forceinline__ void stats_block_ragged(const f32x16& acc, float& m, 
 // Pass B epilogue: acc[i] is the raw dot product of query row row0 + rb*32 + (i/4)*8 + (lane/32)*4 + (i%4) with
 // token tok + lane%32; b2 holds lse[row] * log2(e) for the same (rb, i).  The column sum of a tile is
 // complete after its last row block.
+template <int NRB>
 struct MassEp {
-  const float (&b2)[SM_RB][16];
+  const float (&b2)[NRB][16];
   float a2;
   float* __restrict__ dst;
   int t_end, lane;
@@ -151,7 +155,7 @@ struct MassEp {
       c2 += fast_exp2(fmaf(acc[i + 2], a2, -b2[RB][i + 2]));
       c3 += fast_exp2(fmaf(acc[i + 3], a2, -b2[RB][i + 3]));
     }
-    if (RB == SM_RB - 1) {
+    if (RB == NRB - 1) {
       float col = (c0 + c1) + (c2 + c3);
       const float other = __shfl_xor(col, 32);
       col = (lane < 32) ? (col + other) : (other + col);
@@ -167,41 +171,46 @@ struct MassEp {
 // one wave a SIMD holds.  Two 16-register accumulators alternate; three K fragment buffers rotate, and the load
 // of tile t+3 is issued once the last chain of tile t has been issued (almost three tiles of work ahead of
 // its first use: the memory latency is covered by two tiles' worth of compute).
-constexpr int SM_KBUF = 3;
-
-template <bool TOKENS_BY_ROWS, int U, class Ep>
+template <bool TOKENS_BY_ROWS, int RB, int KBUF, int U, class Ep>
 __device__ __forceinline__ void micro_stage(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane, int i,
-                                            const Frag (&qf)[SM_RB][SM_KK], Frag (&kb)[SM_KBUF][SM_KK], f32x16 (&acc)[2], Ep& ep,
+                                            const Frag (&qf)[RB][SM_KK], Frag (&kb)[KBUF][SM_KK], f32x16 (&acc)[2], Ep& ep,
                                             bool guarded) {
-  constexpr int rb = U % 4, tl = U / 4;                 // current row block, tile offset within the group of SM_KBUF
-  constexpr int rbn = (U + 1) % 4, tln = (U + 1) / 4;   // next
+  constexpr int rb = U % RB, tl = U / RB;                 // current row block, tile offset within the group of KBUF
+  constexpr int rbn = (U + 1) % RB, tln = (U + 1) / RB;   // next
   const int tile = i + tl, tilen = i + tln;
   if (guarded && tile >= n) return;
-  if (!guarded || tilen < n) block_mfma<TOKENS_BY_ROWS>(acc[(U + 1) & 1], kb[tln % SM_KBUF], qf[rbn]);
+  if (!guarded || tilen < n) block_mfma<TOKENS_BY_ROWS>(acc[(U + 1) & 1], kb[tln % KBUF], qf[rbn]);
   ep.template block<rb>(acc[U & 1], first + tile * step);
-  if (rb == 3 && tile + SM_KBUF < n) load_k(kb[tl % SM_KBUF], Kh, first + (tile + SM_KBUF) * step, t_end, lane);
+  if (rb == RB - 1 && tile + KBUF < n) load_k(kb[tl % KBUF], Kh, first + (tile + KBUF) * step, t_end, lane);
   __builtin_amdgcn_sched_barrier(0);      // keep the scheduler from merging micro-stages (register pressure)
 }
 
-template <bool TOKENS_BY_ROWS, class Ep>
+// The RB * KBUF micro-stages of one iteration of the tile loop, in order.
+template <bool TOKENS_BY_ROWS, int RB, int KBUF, int U, class Ep>
+__device__ __forceinline__ void stage_sequence(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane,
+                                               int i, const Frag (&qf)[RB][SM_KK], Frag (&kb)[KBUF][SM_KK], f32x16 (&acc)[2],
+                                               Ep& ep, bool guarded) {
+  if constexpr (U < RB * KBUF) {
+    micro_stage<TOKENS_BY_ROWS, RB, KBUF, U>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, guarded);
+    stage_sequence<TOKENS_BY_ROWS, RB, KBUF, U + 1>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, guarded);
+  }
+}
+
+template <bool TOKENS_BY_ROWS, int RB, int KBUF, class Ep>
 __device__ __forceinline__ void run_tiles(const uint16_t* __restrict__ Kh, int first, int step, int n, int t_end, int lane,
-                                          const Frag (&qf)[SM_RB][SM_KK], Ep& ep) {
+                                          const Frag (&qf)[RB][SM_KK], Ep& ep) {
+  static_assert((RB * KBUF) % 2 == 0, "the accumulators alternate per micro-stage");
   if (n <= 0) return;
-  Frag kb[SM_KBUF][SM_KK];
+  Frag kb[KBUF][SM_KK];
   f32x16 acc[2];
-  load_k(kb[0], Kh, first, t_end, lane);
-  if (n > 1) load_k(kb[1], Kh, first + step, t_end, lane);
-  if (n > 2) load_k(kb[2], Kh, first + 2 * step, t_end, lane);
+#pragma unroll
+  for (int t = 0; t < KBUF; ++t)
+    if (t < n) load_k(kb[t], Kh, first + t * step, t_end, lane);
   block_mfma<TOKENS_BY_ROWS>(acc[0], kb[0], qf[0]);
   int i = 0;
-#define OBF_ST(U, G) micro_stage<TOKENS_BY_ROWS, U>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, G);
-#define OBF_STAGES(G)                                                                                      \
-  OBF_ST(0, G) OBF_ST(1, G) OBF_ST(2, G) OBF_ST(3, G) OBF_ST(4, G) OBF_ST(5, G)                            \
-  OBF_ST(6, G) OBF_ST(7, G) OBF_ST(8, G) OBF_ST(9, G) OBF_ST(10, G) OBF_ST(11, G)
-  for (; i + SM_KBUF < n; i += SM_KBUF) { OBF_STAGES(false) }   // three whole tiles and the first chain of the next exist
-  { OBF_STAGES(true) }
-#undef OBF_STAGES
-#undef OBF_ST
+  for (; i + KBUF < n; i += KBUF)                       // KBUF whole tiles and the first chain of the next exist
+    stage_sequence<TOKENS_BY_ROWS, RB, KBUF, 0>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, false);
+  stage_sequence<TOKENS_BY_ROWS, RB, KBUF, 0>(Kh, first, step, n, t_end, lane, i, qf, kb, acc, ep, true);
 }
 
 // Static partition of the flattened (head, tile) space over the persistent workgroups.
@@ -216,18 +225,19 @@ struct Part {
 // Pass A.  grid = G ranges x RG row groups, one workgroup per compute unit; a workgroup walks its range of
 // tiles segment by segment (a segment = the part of one head inside the range) and leaves one partial
 // (max, sum-exp) per query row and segment.
+template <int RB, int KBUF>
 __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16_t* __restrict__ K,
                                                                     const uint16_t* __restrict__ Q,
                                                                     double* __restrict__ stats_part, int N, int R,
                                                                     int RG, Part pt, int nslot) {
-  __shared__ double s_m[SM_WAVES][SM_ROWS], s_l[SM_WAVES][SM_ROWS];
+  __shared__ double s_m[SM_WAVES][(RB * 32)], s_l[SM_WAVES][(RB * 32)];
   // Workgroups are dealt to the 8 XCDs round-robin.  The RG workgroups that stream the same K range (one per row
   // group) get block indices 8 apart, so they run on one XCD side by side and share its L2.
   const int blk_group = blockIdx.x / (8 * RG), blk_in = blockIdx.x - blk_group * (8 * RG);
   const int range = blk_group * 8 + (blk_in & 7), rg = blk_in >> 3;
   if ((long)range * pt.T >= pt.TT) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row0 = rg * SM_ROWS;
+  const int row0 = rg * (RB * 32);
   const float a2 = kLog2e / sqrtf((float)SM_D);
   constexpr int STEP = SM_WAVES * SM_TILE;
   const long gs = (long)range * pt.T;
@@ -242,23 +252,23 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
     const uint16_t* Kh = K + (size_t)head * pt.kstride;
     const uint16_t* Qh = Q + (size_t)head * R * SM_D;
 
-    Frag qf[SM_RB][SM_KK];
+    Frag qf[RB][SM_KK];
     load_q(qf, Qh, row0, R, lane);
-    float m[SM_RB];
-    double l[SM_RB];
+    float m[RB];
+    double l[RB];
 #pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0; }
+    for (int rb = 0; rb < RB; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0; }
     const int first = ta + wave * SM_TILE;
     const int nfull = (tb - first >= SM_TILE) ? ((tb - first - SM_TILE) / STEP + 1) : 0;
-    StatsEp ep{m, l, a2};
-    run_tiles<true>(Kh, first, STEP, nfull, tb, lane, qf, ep);
+    StatsEp<RB> ep{m, l, a2};
+    run_tiles<true, RB, KBUF>(Kh, first, STEP, nfull, tb, lane, qf, ep);
     {
       const int tok = first + nfull * STEP;          // a ragged last tile, if any
       if (tok < tb) {
         Frag kr[SM_KK];
         load_k(kr, Kh, tok, tb, lane);
 #pragma unroll
-        for (int rb = 0; rb < SM_RB; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
           f32x16 accr;
           block_mfma<true>(accr, kr, qf[rb]);
           stats_block_ragged(accr, m[rb], l[rb], a2, tok, tb, lane);
@@ -267,7 +277,7 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
     }
     // fold the two lane halves (same query row, different tokens), then the four waves
 #pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
       const float mo = __shfl_xor(m[rb], 32);
       const double lo = __shfl_xor(l[rb], 32);
       const float mn = fmaxf(m[rb], mo);
@@ -277,7 +287,7 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
       if (lane < 32) { s_m[wave][rb * 32 + lane] = (double)mn * (double)a2; s_l[wave][rb * 32 + lane] = a + b; }
     }
     __syncthreads();
-    if (threadIdx.x < SM_ROWS) {
+    if (threadIdx.x < (RB * 32)) {
       const int row = row0 + threadIdx.x;
       if (row < R) {
         double M = -INFINITY;
@@ -299,20 +309,21 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
 // Pass B.  Same partition.  First folds the head's partials into log-sum-exp (every workgroup that touches
 // a head computes the same values; the one holding the head's first tile also writes row_lse), then
 // out = scores (RG == 1) or the row group's partial column sums.
+template <int RB, int KBUF>
 __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_t* __restrict__ K,
                                                                    const uint16_t* __restrict__ Q,
                                                                    const double* __restrict__ stats_part,
                                                                    double* __restrict__ row_lse,
                                                                    float* __restrict__ out, int N, int R, int RG,
                                                                    size_t rg_stride, Part pt, int nslot) {
-  __shared__ double s_lse[SM_ROWS];
+  __shared__ double s_lse[(RB * 32)];
   // Workgroups are dealt to the 8 XCDs round-robin.  The RG workgroups that stream the same K range (one per row
   // group) get block indices 8 apart, so they run on one XCD side by side and share its L2.
   const int blk_group = blockIdx.x / (8 * RG), blk_in = blockIdx.x - blk_group * (8 * RG);
   const int range = blk_group * 8 + (blk_in & 7), rg = blk_in >> 3;
   if ((long)range * pt.T >= pt.TT) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row0 = rg * SM_ROWS;
+  const int row0 = rg * (RB * 32);
   const float a2 = kLog2e / sqrtf((float)SM_D);
   constexpr int STEP = SM_WAVES * SM_TILE;
   const long gs = (long)range * pt.T;
@@ -330,7 +341,7 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
     float* dst = out + (size_t)rg * rg_stride + (size_t)head * N;
 
     __syncthreads();
-    if (threadIdx.x < SM_ROWS) {
+    if (threadIdx.x < (RB * 32)) {
       const int row = row0 + threadIdx.x;
       double lse = INFINITY;                                   // padded rows: exp2(-inf) = 0
       if (row < R) {
@@ -350,19 +361,19 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
     }
     __syncthreads();
 
-    Frag qf[SM_RB][SM_KK];
+    Frag qf[RB][SM_KK];
     load_q(qf, Qh, row0, R, lane);
-    float b2[SM_RB][16];
+    float b2[RB][16];
 #pragma unroll
-    for (int rb = 0; rb < SM_RB; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         b2[rb][i] = (float)(s_lse[rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3)] * 1.4426950408889634);
 
     const int first = ta + wave * SM_TILE;
     const int nt = (first < tb) ? ((tb - first - 1) / STEP + 1) : 0;      // tiles of this wave, the last may be ragged
-    MassEp ep{b2, a2, dst, tb, lane, 0.f, 0.f, 0.f, 0.f};
-    run_tiles<false>(Kh, first + (nt - 1) * STEP, -STEP, nt, tb, lane, qf, ep);
+    MassEp<RB> ep{b2, a2, dst, tb, lane, 0.f, 0.f, 0.f, 0.f};
+    run_tiles<false, RB, KBUF>(Kh, first + (nt - 1) * STEP, -STEP, nt, tb, lane, qf, ep);
     se = cur;
   }
 }
@@ -391,13 +402,22 @@ obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, cons
   pt.TH = w.tiles_per_head; pt.T = w.tiles_per_range; pt.TT = (long)m.heads * w.tiles_per_head;
   pt.kstride = (long)m.kvs * SM_D;
   dim3 grid(((w.nranges + 7) / 8) * 8 * RG);
+  const bool five = score_rows_per_group(m.R) == 160;     // five row blocks per workgroup, two K buffers (e.g. 320 rows = 2 x 160)
   { ProfScope prof_(ST_SCORE_STATS, st);
-    hipLaunchKernelGGL(k_score_stats_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       stats_part, m.N, m.R, RG, pt, w.nslot); }
+    if (five)
+      hipLaunchKernelGGL((k_score_stats_mfma<5, 2>), grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                         stats_part, m.N, m.R, RG, pt, w.nslot);
+    else
+      hipLaunchKernelGGL((k_score_stats_mfma<4, 3>), grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                         stats_part, m.N, m.R, RG, pt, w.nslot); }
   if (check_launch("score stats (mfma)") != OBF_OK) return OBF_ERR_HIP;
   { ProfScope prof_(ST_SCORE_MASS, st);
-    hipLaunchKernelGGL(k_score_mass_mfma, grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
-                       (const double*)stats_part, row_lse, part, m.N, m.R, RG, rg_stride, pt, w.nslot); }
+    if (five)
+      hipLaunchKernelGGL((k_score_mass_mfma<5, 2>), grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                         (const double*)stats_part, row_lse, part, m.N, m.R, RG, rg_stride, pt, w.nslot);
+    else
+      hipLaunchKernelGGL((k_score_mass_mfma<4, 3>), grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                         (const double*)stats_part, row_lse, part, m.N, m.R, RG, rg_stride, pt, w.nslot); }
   if (check_launch("score mass (mfma)") != OBF_OK) return OBF_ERR_HIP;
   if (RG > 1) {
     const size_t n = (size_t)m.heads * m.N;
