@@ -282,8 +282,9 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_stats_mfma(const uint16
       const double lo = __shfl_xor(l[rb], 32);
       const float mn = fmaxf(m[rb], mo);
       double a = 0.0, b = 0.0;
-      if (m[rb] > -INFINITY) a = l[rb] * exp2((double)((m[rb] - mn) * a2));
-      if (mo > -INFINITY) b = lo * exp2((double)((mo - mn) * a2));
+      // (the exponents are differences of two float maxima: a single-precision exp2 loses nothing they still carry)
+      if (m[rb] > -INFINITY) a = l[rb] * (double)fast_exp2((m[rb] - mn) * a2);
+      if (mo > -INFINITY) b = lo * (double)fast_exp2((mo - mn) * a2);
       if (lane < 32) { s_m[wave][rb * 32 + lane] = (double)mn * (double)a2; s_l[wave][rb * 32 + lane] = a + b; }
     }
     __syncthreads();
