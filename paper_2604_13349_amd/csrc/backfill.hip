@@ -613,8 +613,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   const int ld = d + 1;
   float* U = sm;                    // [d][ld]   projector P, then the rows of Z; later T and (if they both fit) W
   float* M = sm;                    // T = Z G Z^T and its diagonal form, set below
-  __shared__ float cs[64], sn[64];
-  __shared__ int pp[64], qq[64];
+  __shared__ __attribute__((aligned(16))) float4 rotp[64];       // (p, q, cos, sin) of each rotation of the current set; p and q as integer bits
   __shared__ float uvec[128], svec[128], rbar[128], dvec[128], lamv[128];
   __shared__ int order[128];
   __shared__ float fred[FN_WAVES];
@@ -905,11 +904,21 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           tt = t;
         }
       };
-      // The work items of a rotation set - the half x half blocks of T (those with i <= j do the work) and the half x mm
-      // (rotation, row) pairs of W - are walked with a stride of FN_THREADS; their two indices advance by fixed steps,
-      // so the sets contain no division.
-      const int nb = half * half, nw = half * mm;
-      const int bi0 = tid / max(half, 1), bj0 = tid - bi0 * half, bdi = FN_THREADS / max(half, 1), bdj = FN_THREADS - bdi * half;
+      // The work items of a rotation set: the 2 x 2 blocks (i, j), i <= j, of T - at most three per thread, found once
+      // (item e of the triangle walked by rows) - and the half x mm (rotation, row) pairs of W, walked with a stride of
+      // FN_THREADS by fixed index steps.  The sets contain no division.
+      const int nw = half * mm;
+      int items[3];
+#pragma unroll
+      for (int u = 0; u < 3; ++u) {
+        const int e = tid + u * FN_THREADS;
+        items[u] = -1;
+        if (e < half * (half + 1) / 2) {
+          int i = 0, rem = e;
+          while (rem >= half - i) { rem -= half - i; ++i; }
+          items[u] = i | ((i + rem) << 16);
+        }
+      }
       const int wi0 = tid / max(mm, 1), wk0 = tid - wi0 * mm, wdi = FN_THREADS / max(mm, 1), wdk = FN_THREADS - wdi * mm;
       for (int sweep = 0; sweep < FN_SWEEPS && mm > 1; ++sweep) {
         for (int round = 0; round < mm - 1; ++round) {
@@ -920,7 +929,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             if (p > q) { const int t = p; p = q; q = t; }
             float c, s, t;
             rot_of(M, p, q, c, s, t);
-            pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
+            rotp[tid] = make_float4(__int_as_float(p), __int_as_float(q), c, s);
             if (replay) {
               rot_h[((size_t)sweep * (mm - 1) + round) * half + tid] = t;
               const float zp = rbar[p], zq = rbar[q];            // z <- J^T z
@@ -929,29 +938,32 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             }
           }
           __syncthreads();
-          // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j, mirrored: the blocks are
-          // disjoint, so one pass does both sides), and W <- W J by columns
-          for (int e = tid, i = bi0, jb = bj0; e < nb; e += FN_THREADS) {
-            if (i <= jb) {
-              const int p = pp[i], q = qq[i], p2 = pp[jb], q2 = qq[jb];
-              const float ci = cs[i], si = sn[i], cj = cs[jb], sj = sn[jb];
-              const float a = M[p * lt + p2], b = M[p * lt + q2], c = M[q * lt + p2], dd = M[q * lt + q2];
+          // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j: the blocks are disjoint, so one
+          // pass does both sides), and W <- W J by columns
+#pragma unroll
+          for (int u = 0; u < 3; ++u) {
+            if (items[u] >= 0) {
+              const int i = items[u] & 0xffff, jb = items[u] >> 16;
+              const float4 ri = rotp[i], rj = rotp[jb];
+              const int p = __float_as_int(ri.x), q = __float_as_int(ri.y), p2 = __float_as_int(rj.x), q2 = __float_as_int(rj.y);
+              const float ci = ri.z, si = ri.w, cj = rj.z, sj = rj.w;
+              // only the upper triangle of T is kept current during the sweeps: entry (x, y) lives at (min, max)
+              const int e_a = min(p, p2) * lt + max(p, p2), e_b = min(p, q2) * lt + max(p, q2);
+              const int e_c = (i == jb) ? e_b : min(q, p2) * lt + max(q, p2), e_d = min(q, q2) * lt + max(q, q2);
+              const float a = M[e_a], b = M[e_b], c = M[e_c], dd = M[e_d];
               const float a1 = cj * a - sj * b, b1 = sj * a + cj * b, c1 = cj * c - sj * dd, d1 = sj * c + cj * dd;
               const float a2 = ci * a1 - si * c1, c2 = si * a1 + ci * c1, b2 = ci * b1 - si * d1, d2 = si * b1 + ci * d1;
               if (i == jb) {
-                const float od = 0.5f * (b2 + c2);
-                M[p * lt + p] = a2; M[q * lt + q] = d2; M[p * lt + q] = od; M[q * lt + p] = od;
+                M[e_a] = a2; M[e_d] = d2; M[e_b] = 0.5f * (b2 + c2);
               } else {
-                M[p * lt + p2] = a2; M[p * lt + q2] = b2; M[q * lt + p2] = c2; M[q * lt + q2] = d2;
-                M[p2 * lt + p] = a2; M[q2 * lt + p] = b2; M[p2 * lt + q] = c2; M[q2 * lt + q] = d2;
+                M[e_a] = a2; M[e_b] = b2; M[e_c] = c2; M[e_d] = d2;
               }
             }
-            i += bdi; jb += bdj;
-            if (jb >= half) { jb -= half; ++i; }
           }
           for (int e = tid, i = wi0, k = wk0; e < nw && !replay; e += FN_THREADS) {
-            const int p = pp[i], q = qq[i];
-            const float c = cs[i], s = sn[i];
+            const float4 ri = rotp[i];
+            const int p = __float_as_int(ri.x), q = __float_as_int(ri.y);
+            const float c = ri.z, s = ri.w;
             const float wp = U[k * lt + p], wq = U[k * lt + q];
             U[k * lt + p] = c * wp - s * wq;
             U[k * lt + q] = s * wp + c * wq;
@@ -964,7 +976,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         float off = 0.f;
         for (int e = tid; e < mm * mm; e += FN_THREADS) {
           const int a = e / mm, b = e - a * mm;
-          if (a != b) { const float v = M[a * lt + b]; off = fmaf(v, v, off); }
+          if (a < b) { const float v = M[a * lt + b]; off = fmaf(2.f * v, v, off); }
         }
         for (int o = 32; o > 0; o >>= 1) off += __shfl_xor(off, o);
         if ((tid & 63) == 0) fred[tid >> 6] = off;
