@@ -597,6 +597,39 @@ __host__ __device__ inline int fn_small_floats(int d) {
   return a > b ? a : b;
 }
 
+// Check after a Jacobi sweep, for a workgroup of FN_THREADS threads (all must call): have the rows of the `rank` largest
+// diagonal entries of the symmetric mm x mm matrix T (upper triangle current, row stride lt) separated from the rest?
+// True when each of those rows has off-diagonal energy of at most tol / 100 and every other row's Gershgorin bound is
+// under 0.99 times the smallest of those diagonal entries.  *total receives the off-diagonal energy of the whole of T.
+// The arrays are LDS scratch of mm floats.
+__device__ __forceinline__ bool jacobi_lead_rows_done(const float* T, int lt, int mm, int rank, float tol, float* dg,
+                                                   float* rowe, float* gers, float* lead_min, int* ok, float* total) {
+  const int tid = threadIdx.x;
+  if (tid < mm) {
+    float ro = 0.f, ga = 0.f;
+    for (int b = 0; b < mm; ++b) {
+      if (b != tid) { const float v = T[min(tid, b) * lt + max(tid, b)]; ro = fmaf(v, v, ro); ga += fabsf(v); }
+    }
+    const float dgv = T[tid * lt + tid];
+    dg[tid] = dgv; rowe[tid] = ro; gers[tid] = dgv + ga;
+  }
+  if (tid == 0) *ok = 1;
+  __syncthreads();
+  int rk = mm;
+  if (tid < mm) {
+    const float mine = dg[tid];
+    rk = 0;
+    for (int j = 0; j < mm; ++j) { const float o = dg[j]; rk += (o > mine) || (o == mine && j < tid); }
+    if (rk < rank && !(rowe[tid] <= 0.01f * tol)) *ok = 0;
+    if (rk == rank - 1) *lead_min = mine;
+  }
+  if (tid == 0) { float t = 0.f; for (int a = 0; a < mm; ++a) t += rowe[a]; *total = t; }
+  __syncthreads();
+  if (tid < mm && rk >= rank && !(gers[tid] < 0.99f * *lead_min)) *ok = 0;
+  __syncthreads();
+  return *ok != 0;
+}
+
 template <typename T>
 __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int nstat, int rank,
                                                             HeadState* __restrict__ state,
@@ -925,7 +958,10 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           if (tid < half) {
             int p, q;
             if (tid == 0) { p = mm - 1; q = round; }
-            else { p = (round + tid) % (mm - 1); q = (round - tid + (mm - 1)) % (mm - 1); }
+            else {                                                // (round + tid) mod (mm-1), (round - tid) mod (mm-1); tid < mm-1
+              p = round + tid; if (p >= mm - 1) p -= mm - 1;
+              q = round - tid; if (q < 0) q += mm - 1;
+            }
             if (p > q) { const int t = p; p = q; q = t; }
             float c, s, t;
             rot_of(M, p, q, c, s, t);
@@ -937,7 +973,9 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
               rbar[q] = s * zp + c * zq;
             }
           }
-          __syncthreads();
+          // the two barriers of a set wait for LDS traffic only: the tangent stores (read back by the same wave after
+          // the sweeps, behind full barriers) stay in flight
+          lds_barrier();
           // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j: the blocks are disjoint, so one
           // pass does both sides), and W <- W J by columns
 #pragma unroll
@@ -970,23 +1008,35 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             i += wdi; k += wdk;
             if (k >= mm) { k -= mm; ++i; }
           }
+          lds_barrier();
+        }
+        // The sweeps stop when the off-diagonal energy is below single-precision noise of the trace.  Where only a few
+        // leading eigenpairs are used (no Max-P / EVR rule, rank <= mm/8) they also stop as soon as the rows of the
+        // `rank` largest diagonal entries are each a hundred times further below that level and every other row's
+        // Gershgorin bound stays under the smallest of them by 1 %: those diagonal entries are then the leading
+        // eigenvalues and their rotations' columns the eigenvectors, to the same residual as at full convergence,
+        // whatever the rest of T still looks like.
+        const float tol = 1e-13f * res2 * res2;
+        const bool lead_only = !(vflags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR)) && 8 * rank <= mm;
+        bool lead_done = false;
+        if (lead_only) {
+          lead_done = jacobi_lead_rows_done(M, lt, mm, rank, tol, lamv, svec, dvec, &fred[1], &s_k, &s_off);
+        } else {
+          float off = 0.f;
+          for (int e = tid; e < mm * mm; e += FN_THREADS) {
+            const int a = e / mm, b = e - a * mm;
+            if (a < b) { const float v = M[a * lt + b]; off = fmaf(2.f * v, v, off); }
+          }
+          for (int o = 32; o > 0; o >>= 1) off += __shfl_xor(off, o);
+          if ((tid & 63) == 0) fred[tid >> 6] = off;
+          __syncthreads();
+          if (tid == 0) { float t = 0.f; for (int i = 0; i < FN_WAVES; ++i) t += fred[i]; s_off = t; }
           __syncthreads();
         }
-        // off-diagonal energy; stop when it is below single-precision noise of the trace
-        float off = 0.f;
-        for (int e = tid; e < mm * mm; e += FN_THREADS) {
-          const int a = e / mm, b = e - a * mm;
-          if (a < b) { const float v = M[a * lt + b]; off = fmaf(2.f * v, v, off); }
-        }
-        for (int o = 32; o > 0; o >>= 1) off += __shfl_xor(off, o);
-        if ((tid & 63) == 0) fred[tid >> 6] = off;
-        __syncthreads();
-        if (tid == 0) { float s = 0.f; for (int i = 0; i < FN_WAVES; ++i) s += fred[i]; s_off = s; }
-        __syncthreads();
         const float offn = s_off;
         __syncthreads();
         nsweeps = sweep + 1;
-        if (offn <= 1e-13f * res2 * res2) break;
+        if (offn <= tol || lead_done) break;
       }
       BF_STAMP(1, 6);
       // eigenvalues, descending order (ties: lower index first), numerical rank of R
