@@ -1079,17 +1079,20 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       __syncthreads();
       if (k_used > 0) {
        if (replay) {
-        // x = W D z with D keeping the k_used leading coordinates: the rotations in reverse order, x <- J x, by wave 0
-        // (lane i owns rotation i of a set; the pairs of a set are disjoint and a wave's LDS accesses stay in order)
+        // x = W D z with D keeping the k_used leading coordinates: the rotations in reverse order, x <- J x, by wave 0.
+        // x stays in registers: in set r lane i >= 1 holds x[(r + i) mod nr] and x[(r - i) mod nr] - the pair of its
+        // rotation - and lane 0 holds x[nr] and x[r]; stepping to set r - 1 moves the first entries one lane up and the
+        // second ones one lane down, with lane 0's second entry entering the first row at lane 1 and the first entry
+        // of the last lane entering the second row.
         if (tid < mm) dvec[tid] = 0.f;
         __syncthreads();
         if (tid < k_used) dvec[order[tid]] = rbar[order[tid]];
         __syncthreads();
         if (tid < 64) {
           const int nr = mm - 1;
+          int ia = (tid == 0) ? nr : (nr - 1 + tid) % nr, ib = (tid == 0) ? nr - 1 : (2 * nr - 1 - tid) % nr;   // at r = nr - 1
+          float xa = (tid < half) ? dvec[ia] : 0.f, xb = (tid < half) ? dvec[ib] : 0.f;
           for (int sw = nsweeps - 1; sw >= 0; --sw) {
-            // pair of lane i in set `round`: (mm-1, round) for i = 0, else ((round + i) mod nr, (round - i) mod nr); walked backwards
-            int p = (tid == 0) ? nr : (nr - 1 + tid) % nr, q = (tid == 0) ? nr - 1 : (2 * nr - 1 - tid) % nr;
             for (int r0 = nr - 1; r0 >= 0; r0 -= 16) {
               float tb[16];                                    // the tangents of sixteen sets are fetched together
 #pragma unroll
@@ -1097,22 +1100,21 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
                 tb[u] = (r0 - u >= 0 && tid < half) ? rot_h[((size_t)sw * nr + (r0 - u)) * half + tid] : 0.f;
 #pragma unroll
               for (int u = 0; u < 16; ++u) {
-                const int round = r0 - u;
-                if (round >= 0) {
-                  if (tid < half) {
-                    const float t = tb[u];
-                    const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f)), s = t * c;
-                    const int a = min(p, q), b = max(p, q);
-                    const float xa = dvec[a], xb = dvec[b];
-                    dvec[a] = c * xa + s * xb;
-                    dvec[b] = c * xb - s * xa;
-                  }
-                  if (tid == 0) q = round - 1; else { p = (p == 0) ? nr - 1 : p - 1; q = (q == 0) ? nr - 1 : q - 1; }
-                  __builtin_amdgcn_wave_barrier();             // the next set reads what other lanes have just written
+                if (r0 - u >= 0) {
+                  const float t = tb[u];
+                  const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f)), s0 = t * c;
+                  const float s = (ia < ib) ? s0 : -s0;          // the rotation is defined on the sorted pair
+                  const float na = fmaf(s, xb, c * xa), nb = fmaf(-s, xa, c * xb);
+                  const float ua = wave_from_below(na), ub = wave_from_below(nb), db = wave_from_above(nb);
+                  xa = (tid == 0) ? na : (tid == 1) ? ub : ua;
+                  xb = (tid == half - 1) ? na : db;
+                  if (tid != 0) ia = (ia == 0) ? nr - 1 : ia - 1;
+                  ib = (ib == 0) ? nr - 1 : ib - 1;
                 }
               }
             }
           }
+          if (tid < half) { dvec[ia] = xa; dvec[ib] = xb; }
         }
         __syncthreads();
         if (tid < m) lamv[tid] = dvec[tid];                    // Delta in complement coordinates (times a_del + eps)

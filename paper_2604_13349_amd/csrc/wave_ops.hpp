@@ -13,6 +13,11 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 #define OBF_DPP_MOV(x, ctrl) ((uint32_t)__builtin_amdgcn_update_dpp(0, (int)(x), (ctrl), 0xF, 0xF, false))
 
+// The value held by the next lower / next higher lane of the 64-lane wave (one DPP move each); lane 0 resp. lane 63
+// gets an unspecified value.
+__device__ __forceinline__ float wave_from_below(float v) { return __uint_as_float(OBF_DPP_MOV(__float_as_uint(v), 0x138)); }   // wave_shr:1
+__device__ __forceinline__ float wave_from_above(float v) { return __uint_as_float(OBF_DPP_MOV(__float_as_uint(v), 0x130)); }   // wave_shl:1
+
 // maximum over the wave, result in every lane
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   v = max(v, OBF_DPP_MOV(v, 0xB1));
