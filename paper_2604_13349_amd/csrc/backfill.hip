@@ -917,6 +917,9 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       const bool replay = rot != nullptr && mm >= FN_REPLAY_MIN;
       float* rot_h = rot ? rot + (size_t)head * FN_SWEEPS * (d - 1) * (d / 2) : nullptr;
       int nsweeps = 0;
+      // z = W^T y travels with the rotations in the registers of the lanes that compute them: in set r lane i >= 1
+      // holds z[(r + i) mod (mm-1)] and z[(r - i) mod (mm-1)], lane 0 holds z[mm-1] and z[r]
+      float za = 0.f, zb = 0.f;
       if (replay) {
         if (tid < mm) {
           float s = 0.f;
@@ -924,6 +927,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           rbar[tid] = s;                                       // y = Z u
         }
         __syncthreads();
+        if (tid < half) { za = rbar[tid == 0 ? mm - 1 : tid]; zb = rbar[tid == 0 ? 0 : mm - 1 - tid]; }
       }
       auto rot_of = [&](const float* A, const int p, const int q, float& c, float& s, float& tt) {
         const float app = A[p * lt + p], aqq = A[q * lt + q], apq = A[p * lt + q];
@@ -962,15 +966,21 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
               p = round + tid; if (p >= mm - 1) p -= mm - 1;
               q = round - tid; if (q < 0) q += mm - 1;
             }
-            if (p > q) { const int t = p; p = q; q = t; }
+            const bool swapped = p > q;
+            if (swapped) { const int t = p; p = q; q = t; }
             float c, s, t;
             rot_of(M, p, q, c, s, t);
             rotp[tid] = make_float4(__int_as_float(p), __int_as_float(q), c, s);
             if (replay) {
               rot_h[((size_t)sweep * (mm - 1) + round) * half + tid] = t;
-              const float zp = rbar[p], zq = rbar[q];            // z <- J^T z
-              rbar[p] = c * zp - s * zq;
-              rbar[q] = s * zp + c * zq;
+              // z <- J^T z on the pair this lane holds (the rotation is defined on the sorted pair), then the step to
+              // the next set: first entries one lane down, second entries one lane up, lane 1's first entry into
+              // lane 0's second, the last lane's second entry into its first
+              const float se = swapped ? -s : s;
+              const float na = fmaf(-se, zb, c * za), nb = fmaf(se, za, c * zb);
+              const float da = wave_from_above(na), ub = wave_from_below(nb);
+              za = (tid == 0) ? na : (tid == half - 1) ? nb : da;
+              zb = (tid == 0) ? da : ub;
             }
           }
           // the two barriers of a set wait for LDS traffic only: the tangent stores (read back by the same wave after
@@ -1039,6 +1049,10 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         if (offn <= tol || lead_done) break;
       }
       BF_STAMP(1, 6);
+      if (replay && tid < half) {                              // whole sweeps end in the layout of set 0
+        rbar[tid == 0 ? mm - 1 : tid] = za;
+        rbar[tid == 0 ? 0 : mm - 1 - tid] = zb;
+      }
       // eigenvalues, descending order (ties: lower index first), numerical rank of R
       if (tid < m) lamv[tid] = M[tid * lt + tid];
       __syncthreads();
