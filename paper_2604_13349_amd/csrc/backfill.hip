@@ -957,6 +957,29 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         }
       }
       const int wi0 = tid / max(mm, 1), wk0 = tid - wi0 * mm, wdi = FN_THREADS / max(mm, 1), wdk = FN_THREADS - wdi * mm;
+      // One 2 x 2 block of a rotation set.  Only the upper triangle of T is kept current during the sweeps: entry
+      // (x, y) lives at (min, max).
+      struct RotBlock { int e_a, e_b, e_c, e_d; float a, b, c, dd, ci, si, cj, sj; bool diag; };
+      auto block_load = [&](const int item, RotBlock& k) {
+        const int i = item & 0xffff, jb = item >> 16;
+        const float4 ri = rotp[i], rj = rotp[jb];
+        const int p = __float_as_int(ri.x), q = __float_as_int(ri.y), p2 = __float_as_int(rj.x), q2 = __float_as_int(rj.y);
+        k.ci = ri.z; k.si = ri.w; k.cj = rj.z; k.sj = rj.w;
+        k.diag = i == jb;
+        k.e_a = min(p, p2) * lt + max(p, p2); k.e_b = min(p, q2) * lt + max(p, q2);
+        k.e_c = k.diag ? k.e_b : min(q, p2) * lt + max(q, p2); k.e_d = min(q, q2) * lt + max(q, q2);
+        k.a = M[k.e_a]; k.b = M[k.e_b]; k.c = M[k.e_c]; k.dd = M[k.e_d];
+      };
+      auto block_store = [&](const RotBlock& k) {
+        const float a1 = k.cj * k.a - k.sj * k.b, b1 = k.sj * k.a + k.cj * k.b, c1 = k.cj * k.c - k.sj * k.dd, d1 = k.sj * k.c + k.cj * k.dd;
+        const float a2 = k.ci * a1 - k.si * c1, c2 = k.si * a1 + k.ci * c1, b2 = k.ci * b1 - k.si * d1, d2 = k.si * b1 + k.ci * d1;
+        if (k.diag) {
+          M[k.e_a] = a2; M[k.e_d] = d2; M[k.e_b] = 0.5f * (b2 + c2);
+        } else {
+          M[k.e_a] = a2; M[k.e_b] = b2; M[k.e_c] = c2; M[k.e_d] = d2;
+        }
+      };
+      const bool two_items = __builtin_amdgcn_ballot_w64(items[1] >= 0) != 0;      // wave-uniform
       for (int sweep = 0; sweep < FN_SWEEPS && mm > 1; ++sweep) {
         for (int round = 0; round < mm - 1; ++round) {
           if (tid < half) {
@@ -988,25 +1011,24 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
           lds_barrier();
           // T <- J^T T J by 2 x 2 blocks (rows {p_i, q_i} x columns {p_j, q_j}, i <= j: the blocks are disjoint, so one
           // pass does both sides), and W <- W J by columns
-#pragma unroll
-          for (int u = 0; u < 3; ++u) {
-            if (items[u] >= 0) {
-              const int i = items[u] & 0xffff, jb = items[u] >> 16;
-              const float4 ri = rotp[i], rj = rotp[jb];
-              const int p = __float_as_int(ri.x), q = __float_as_int(ri.y), p2 = __float_as_int(rj.x), q2 = __float_as_int(rj.y);
-              const float ci = ri.z, si = ri.w, cj = rj.z, sj = rj.w;
-              // only the upper triangle of T is kept current during the sweeps: entry (x, y) lives at (min, max)
-              const int e_a = min(p, p2) * lt + max(p, p2), e_b = min(p, q2) * lt + max(p, q2);
-              const int e_c = (i == jb) ? e_b : min(q, p2) * lt + max(q, p2), e_d = min(q, q2) * lt + max(q, q2);
-              const float a = M[e_a], b = M[e_b], c = M[e_c], dd = M[e_d];
-              const float a1 = cj * a - sj * b, b1 = sj * a + cj * b, c1 = cj * c - sj * dd, d1 = sj * c + cj * dd;
-              const float a2 = ci * a1 - si * c1, c2 = si * a1 + ci * c1, b2 = ci * b1 - si * d1, d2 = si * b1 + ci * d1;
-              if (i == jb) {
-                M[e_a] = a2; M[e_d] = d2; M[e_b] = 0.5f * (b2 + c2);
-              } else {
-                M[e_a] = a2; M[e_b] = b2; M[e_c] = c2; M[e_d] = d2;
-              }
-            }
+          if (two_items) {
+            // waves in which some thread has a second block: both blocks' loads are issued before the first one's
+            // arithmetic (a thread without a second block repeats the loads of its first and drops the result)
+            RotBlock k0, k1;
+            const bool v1 = items[1] >= 0;
+            block_load(items[0], k0);
+            block_load(v1 ? items[1] : items[0], k1);
+            block_store(k0);
+            if (v1) block_store(k1);
+          } else if (items[0] >= 0) {
+            RotBlock k0;
+            block_load(items[0], k0);
+            block_store(k0);
+          }
+          if (items[2] >= 0) {
+            RotBlock k2;
+            block_load(items[2], k2);
+            block_store(k2);
           }
           for (int e = tid, i = wi0, k = wk0; e < nw && !replay; e += FN_THREADS) {
             const float4 ri = rotp[i];
