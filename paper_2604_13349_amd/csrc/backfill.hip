@@ -1124,31 +1124,45 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         __syncthreads();
         if (tid < k_used) dvec[order[tid]] = rbar[order[tid]];
         __syncthreads();
-        if (tid < 64) {
-          const int nr = mm - 1;
+        // The tangents come back from global memory one sweep at a time through two LDS buffers (T's storage is free
+        // by now: its diagonal sits in lamv): while wave 0 replays a sweep, the other waves fetch the one before it.
+        {
+          const int nr = mm - 1, per = nr * half;
+          float* tbuf = sm;
+          for (int e = tid; e < per; e += FN_THREADS) tbuf[((nsweeps - 1) & 1) * per + e] = rot_h[(size_t)(nsweeps - 1) * per + e];
           int ia = (tid == 0) ? nr : (nr - 1 + tid) % nr, ib = (tid == 0) ? nr - 1 : (2 * nr - 1 - tid) % nr;   // at r = nr - 1
           float xa = (tid < half) ? dvec[ia] : 0.f, xb = (tid < half) ? dvec[ib] : 0.f;
+          __syncthreads();
           for (int sw = nsweeps - 1; sw >= 0; --sw) {
-            for (int r0 = nr - 1; r0 >= 0; r0 -= 16) {
-              float tb[16];                                    // the tangents of sixteen sets are fetched together
+            if (tid >= 64) {
+              if (sw > 0) {
+                float* dst = tbuf + ((sw - 1) & 1) * per;
+                const float* src = rot_h + (size_t)(sw - 1) * per;
+                for (int e = tid - 64; e < per; e += FN_THREADS - 64) dst[e] = src[e];
+              }
+            } else {
+              const float* tcur = tbuf + (sw & 1) * per;
+              for (int r0 = nr - 1; r0 >= 0; r0 -= 16) {
+                float tb[16];                                  // the tangents of sixteen sets are fetched together
 #pragma unroll
-              for (int u = 0; u < 16; ++u)
-                tb[u] = (r0 - u >= 0 && tid < half) ? rot_h[((size_t)sw * nr + (r0 - u)) * half + tid] : 0.f;
+                for (int u = 0; u < 16; ++u) tb[u] = (r0 - u >= 0 && tid < half) ? tcur[(r0 - u) * half + tid] : 0.f;
 #pragma unroll
-              for (int u = 0; u < 16; ++u) {
-                if (r0 - u >= 0) {
-                  const float t = tb[u];
-                  const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f)), s0 = t * c;
-                  const float s = (ia < ib) ? s0 : -s0;          // the rotation is defined on the sorted pair
-                  const float na = fmaf(s, xb, c * xa), nb = fmaf(-s, xa, c * xb);
-                  const float ua = wave_from_below(na), ub = wave_from_below(nb), db = wave_from_above(nb);
-                  xa = (tid == 0) ? na : (tid == 1) ? ub : ua;
-                  xb = (tid == half - 1) ? na : db;
-                  if (tid != 0) ia = (ia == 0) ? nr - 1 : ia - 1;
-                  ib = (ib == 0) ? nr - 1 : ib - 1;
+                for (int u = 0; u < 16; ++u) {
+                  if (r0 - u >= 0) {
+                    const float t = tb[u];
+                    const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f)), s0 = t * c;
+                    const float s = (ia < ib) ? s0 : -s0;        // the rotation is defined on the sorted pair
+                    const float na = fmaf(s, xb, c * xa), nb = fmaf(-s, xa, c * xb);
+                    const float ua = wave_from_below(na), ub = wave_from_below(nb), db = wave_from_above(nb);
+                    xa = (tid == 0) ? na : (tid == 1) ? ub : ua;
+                    xb = (tid == half - 1) ? na : db;
+                    if (tid != 0) ia = (ia == 0) ? nr - 1 : ia - 1;
+                    ib = (ib == 0) ? nr - 1 : ib - 1;
+                  }
                 }
               }
             }
+            __syncthreads();
           }
           if (tid < half) { dvec[ia] = xa; dvec[ib] = xb; }
         }
