@@ -100,6 +100,14 @@ def test_paper_shape(gpu):
     _check_cfg(gpu, si.shrink(si.CONFIGS["paper"], n_layers=2), expect_active=True)
 
 
+@pytest.mark.parametrize("seed,rank,budget", [(1, 2, 32), (3, 8, 32), (4, 4, 16), (5, 1, 24), (6, 12, 20)])
+def test_wide_complement_few_leading_directions(gpu, seed, rank, budget):
+    """Complements 96 to 112 wide with 1 to 12 back-fill directions: the regime in which the eigen-iteration may stop as
+    soon as the leading eigenpairs have separated from the rest (and the one in which it keeps no eigenvector matrix)."""
+    cfg = si.shrink(si.CONFIGS["paper"], n_layers=3, budget=budget, name=f"paper-r{rank}-b{budget}")
+    _check_cfg(gpu, cfg, seed=seed, rank=rank, expect_active=True)
+
+
 @pytest.mark.parametrize("N,d,dtype,g,W,B,rank", [
     (1000, 64, "bf16", 3, 8, 40, 3),        # ragged tail, odd group, d = 64
     (777, 128, "f32", 1, 5, 100, 2),        # fp32 at d = 128, rows not a multiple of anything
