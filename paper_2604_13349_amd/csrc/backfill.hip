@@ -930,7 +930,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         if (tid < half) { za = rbar[tid == 0 ? mm - 1 : tid]; zb = rbar[tid == 0 ? 0 : mm - 1 - tid]; }
       }
       auto rot_of = [&](const float* A, const int p, const int q, float& c, float& s, float& tt) {
-        const float app = A[p * lt + p], aqq = A[q * lt + q], apq = A[p * lt + q];
+        const float app = A[__mul24(p, lt) + p], aqq = A[__mul24(q, lt) + q], apq = A[__mul24(p, lt) + q];
         c = 1.f; s = 0.f; tt = 0.f;
         // single-instruction reciprocal / square roots (1 ulp): the rotation only has to be orthogonal to rounding
         if (fabsf(apq) > 1e-30f && fabsf(apq) > 1e-9f * __builtin_amdgcn_sqrtf(fabsf(app * aqq)) ) {
@@ -966,8 +966,9 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         const int p = __float_as_int(ri.x), q = __float_as_int(ri.y), p2 = __float_as_int(rj.x), q2 = __float_as_int(rj.y);
         k.ci = ri.z; k.si = ri.w; k.cj = rj.z; k.sj = rj.w;
         k.diag = i == jb;
-        k.e_a = min(p, p2) * lt + max(p, p2); k.e_b = min(p, q2) * lt + max(p, q2);
-        k.e_c = k.diag ? k.e_b : min(q, p2) * lt + max(q, p2); k.e_d = min(q, q2) * lt + max(q, q2);
+        // 24-bit multiplies (full rate; the indices are below 2^7)
+        k.e_a = __mul24(min(p, p2), lt) + max(p, p2); k.e_b = __mul24(min(p, q2), lt) + max(p, q2);
+        k.e_c = k.diag ? k.e_b : __mul24(min(q, p2), lt) + max(q, p2); k.e_d = __mul24(min(q, q2), lt) + max(q, q2);
         k.a = M[k.e_a]; k.b = M[k.e_b]; k.c = M[k.e_c]; k.dd = M[k.e_d];
       };
       auto block_store = [&](const RotBlock& k) {
@@ -1034,9 +1035,10 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
             const float4 ri = rotp[i];
             const int p = __float_as_int(ri.x), q = __float_as_int(ri.y);
             const float c = ri.z, s = ri.w;
-            const float wp = U[k * lt + p], wq = U[k * lt + q];
-            U[k * lt + p] = c * wp - s * wq;
-            U[k * lt + q] = s * wp + c * wq;
+            const int kr = __mul24(k, lt);
+            const float wp = U[kr + p], wq = U[kr + q];
+            U[kr + p] = c * wp - s * wq;
+            U[kr + q] = s * wp + c * wq;
             i += wdi; k += wdk;
             if (k >= mm) { k -= mm; ++i; }
           }
