@@ -5,9 +5,10 @@
 //
 //   G   = V_s^T V_s over a strided subset V_s of the retained rows (all rows up to 768), on the matrix
 //         cores: products of bf16 values are exact in fp32, accumulation is fp32;
-//   mu  = (max(n, d) 2^-23)^2 ||V_keep||_F^2  +  allowance for the fp32 error of G and of the
-//         factorisation;
-//   if the LDL^T factorisation of G - mu I runs through with positive pivots (G - mu I positive definite), then
+//   mu  = (max(n, d) 2^-23)^2 ||V_keep||_F^2;
+//   S   = D^-1/2 G D^-1/2 with D = diag(G): G - mu I is positive definite iff S - mu D^-1 is;
+//   if the LDL^T factorisation of S - mu D^-1 - eps I (eps: allowance for the fp32 error of G and of the
+//   factorisation, relative to trace(S) = d) runs through with positive pivots, then
 //   sigma_min(V_keep)^2 >= lambda_min(G) > (max(n, d) 2^-23)^2 sigma_max(V_keep)^2, i.e. every singular
 //   value is above the rank rule's threshold: r = d.
 #include "common.hpp"
@@ -22,7 +23,7 @@ constexpr int KC_D = 128;
 constexpr int KC_TILE = 64;              // rows staged per iteration
 constexpr int KC_LDW = 136;              // staging stride in 32-bit words per token PAIR (the two lane halves, 4 pairs apart, use different banks)
 constexpr int KC_MINROWS = 768;          // rows entering G: all up to 768, else about max(768, n/4) at a constant stride
-constexpr float kCertErr = 4.0e-6f;      // allowance for fp32 Gram + factorisation error, relative to trace(G)
+constexpr float kCertErr = 1.6e-5f;      // allowance for fp32 Gram + factorisation error, relative to the trace of the scaled Gram matrix (= d)
 
 union FragU { uint32_t w[4]; bf16x8 v; };
 
@@ -57,6 +58,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   __shared__ uint32_t stage[2][(KC_TILE / 2) * KC_LDW];
   __shared__ __attribute__((aligned(16))) float panel[2][KC_D][4];
   __shared__ float4 ypan[KC_D], lpan[KC_D];
+  __shared__ __attribute__((aligned(16))) float isd[KC_D];
   __shared__ int s_bad;
   __shared__ double red[KC_THREADS / 64], red2[KC_THREADS / 64];
   const int head = blockIdx.x;
@@ -231,13 +233,36 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     f2 = (red[0] + red[1]) + (red[2] + red[3]);
     __syncthreads();
   }
+  // Symmetric diagonal scaling S = D^-1/2 G D^-1/2 (unit diagonal): G - mu I is positive definite iff S - mu D^-1 is,
+  // and the scaled matrix no longer carries the spread of the channel magnitudes (a few outlier channels otherwise
+  // own the trace, and with it the rounding allowance, while lambda_min sits in the small ones).
   const double thr_rel = (double)max(n, KC_D) * 1.1920928955078125e-07;
-  const float mu = (float)(thr_rel * thr_rel * f2 + (double)kCertErr * tr);
+  const float mu = (float)(thr_rel * thr_rel * f2);
 #pragma unroll
   for (int t = 0; t < 3; ++t) {
     if (t < nt && trb[t] == tcb[t] && has_diag) {
+      float v = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) if (i == di) acc[t][i] -= mu;
+      for (int i = 0; i < 16; ++i) if (i == di) v = acc[t][i];
+      isd[tcb[t] * 32 + lr] = __builtin_amdgcn_rsqf(v);            // a zero column gives inf, then NaN pivots: not certified
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    if (t < nt) {
+      const float sc_col = isd[tcb[t] * 32 + lr];
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const float4 sr = *(const float4*)&isd[trb[t] * 32 + i4 * 8 + lh * 4];
+        acc[t][4 * i4 + 0] *= sr.x * sc_col; acc[t][4 * i4 + 1] *= sr.y * sc_col;
+        acc[t][4 * i4 + 2] *= sr.z * sc_col; acc[t][4 * i4 + 3] *= sr.w * sc_col;
+      }
+      if (trb[t] == tcb[t] && has_diag) {
+        const float shift = fmaf(mu, sc_col * sc_col, kCertErr * (float)KC_D);   // mu / G_jj + allowance relative to trace(S) = d
+#pragma unroll
+        for (int i = 0; i < 16; ++i) if (i == di) acc[t][i] -= shift;
+      }
     }
   }
 
