@@ -3,7 +3,7 @@
 // head_dim.  It is a sufficient test only: heads it cannot certify go to the reference-precision
 // basis kernel.
 //
-//   G   = V_s^T V_s over a strided subset V_s of the retained rows (all rows up to 768), on the matrix
+//   G   = V_s^T V_s over a strided subset V_s of the retained rows (all rows up to 512), on the matrix
 //         cores: products of bf16 values are exact in fp32, accumulation is fp32;
 //   mu  = (max(n, d) 2^-23)^2 ||V_keep||_F^2;
 //   S   = D^-1/2 G D^-1/2 with D = diag(G): G - mu I is positive definite iff S - mu D^-1 is;
@@ -22,7 +22,7 @@ constexpr int KC_THREADS = 256;
 constexpr int KC_D = 128;
 constexpr int KC_TILE = 64;              // rows staged per iteration
 constexpr int KC_LDW = 136;              // staging stride in 32-bit words per token PAIR (the two lane halves, 4 pairs apart, use different banks)
-constexpr int KC_MINROWS = 768;          // rows entering G: all up to 768, else about max(768, n/4) at a constant stride
+constexpr int KC_MINROWS = 512;          // rows entering G: all up to 512, else about max(512, n/4) at a constant stride
 constexpr float kCertErr = 1.6e-5f;      // allowance for fp32 Gram + factorisation error, relative to the trace of the scaled Gram matrix (= d)
 
 union FragU { uint32_t w[4]; bf16x8 v; };
