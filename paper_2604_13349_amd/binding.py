@@ -313,7 +313,7 @@ def append_message(prev_K, prev_V, prev_len, keep_K, keep_V, n_keep, gen_K, gen_
 
 
 def diag_to_numpy(diag: torch.Tensor) -> np.ndarray:
-    """Device diag bytes [L,H,32] -> structured numpy array [L,H]."""
+    """Device diag bytes [L,H,sizeof(obf_diag_t)] -> structured numpy array [L,H]."""
     a = diag.cpu().numpy()
     return a.view(DIAG_DTYPE).reshape(a.shape[0], a.shape[1])
 

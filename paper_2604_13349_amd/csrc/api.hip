@@ -50,7 +50,7 @@ ProfScope::~ProfScope() {
 }
 
 static const char* kStageNames[ST_COUNT] = {"score_stats", "score_lse", "score_mass", "select", "refine", "gather",
-                                            "keep_cert", "keep_basis", "del_stats", "finalize", "inject"};
+                                            "keep_cert", "keep_basis", "del_stats", "finalize"};
 
 static obf_status_t check_shape(const obf_shape_t* s) {
   if (!s) { set_error("shape is NULL"); return OBF_ERR_INVALID_ARG; }

@@ -29,16 +29,6 @@ constexpr double kRankEps = 1.1920928955078125e-07;   // 2^-23, the rank rule's 
 constexpr float kRcrSkip = 1.0e-6f;                   // "||R||_F negligible": ||R||^2 <= 1e-6 ||V_del||^2
 constexpr float kEigFloor = 1.0e-6f;                  // resolution of the fp32 residual Gram (relative)
 
-#ifdef BF_TRACE
-__device__ uint64_t g_bf_trace[512 * 12];
-#define BF_STAMP(w, k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_bf_trace[blockIdx.x * 12 + (k)] = wall_clock64(); } while (0)
-__device__ uint64_t g_kb_trace[512 * 12];
-#define KB_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_kb_trace[blockIdx.x * 12 + (k)] = wall_clock64(); } while (0)
-#else
-#define BF_STAMP(w, k) do { } while (0)
-#define KB_STAMP(k) do { } while (0)
-#endif
-
 // ------------------------------------------------------------------------------------------------
 // small block helpers (KB_THREADS threads)
 __device__ __forceinline__ double wave_sum(double v) {
@@ -347,7 +337,6 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       const double thr = smax * (double)max(n, d) * kRankEps;
       r_keep = pivoted_mgs(W, n, d, thr, red, ired);
     } else {
-      KB_STAMP(0);
       // n > d: Gram matrix of the retained rows in double (inputs are exact, products exact),
       // diagonally pivoted Cholesky for the rank, then the rows of the factor span the row space.
       const int slot = gpart ? kg_rank_of(decided, n_keep, head, N, d, rank, red) : kKeepGramSlots;
@@ -379,7 +368,6 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
         }
       };
       form_gram();
-      KB_STAMP(1);
       // sigma_max^2 = lambda_max(G): power iteration on G
       for (int c = threadIdx.x; c < d; c += KB_THREADS) xv[c] = 1.0 / sqrt((double)d) * (1.0 + 0.01 * (c % 7));
       __syncthreads();
@@ -405,7 +393,6 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
       }
       const double smax = sqrt(lam);
       const double thr = smax * (double)max(n, d) * kRankEps;     // on singular values
-      KB_STAMP(2);
       // Full-rank shortcut (what a head missed by the single-precision certificate usually is): G - thr^2 I is
       // positive definite iff every eigenvalue of G exceeds thr^2, i.e. every singular value of V_keep exceeds thr.
       const bool full = (d == 128) ? shifted_ldl_positive<8>(W, thr * thr, xv, yv) : shifted_ldl_positive<4>(W, thr * thr, xv, yv);
@@ -446,7 +433,6 @@ __global__ __launch_bounds__(KB_THREADS) void k_bf_keep_basis(const T* __restric
         __syncthreads();
       }
       r_keep = r;
-      KB_STAMP(3);
       if (r_keep < d) {
         // rows 0..r-1 of the factor (zero left of the diagonal), columns back in original order
         for (int e = threadIdx.x; e < d * d; e += KB_THREADS) {
@@ -669,7 +655,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     if (cls >= 0 && big != cls) return;                        // cls < 0: one launch with the large LDS takes every head
   }
 
-  BF_STAMP(1, 0);
   if (st.active && naive) {
     // Naive Aggregation (App. D): the plain mean of the deleted value rows, none of Eq. 3-6
     const size_t pstride = gram_stride(d);
@@ -727,7 +712,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     for (int c = 0; c < nstat; ++c) vd2 += gp[c * pstride + d * d + 2 * d];
 
     __syncthreads();                                           // G is in global scratch for every thread of the workgroup
-    BF_STAMP(1, 1);
     // P = I - Q^T Q (projector onto the complement of the retained span, Eq. 3) on the matrix cores: wave (rb, cb)
     // holds the 32 x 32 tile of P in 16 registers per lane, entry i of lane l being
     // P[rb*32 + (i/4)*8 + (l/32)*4 + i%4][cb*32 + l%32].
@@ -763,7 +747,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     }
     __syncthreads();
 
-    BF_STAMP(1, 2);
     // Diagonally pivoted Cholesky of P, right-looking on the register tiles: a projector of rank m factors as
     // P = Z^T Z with the m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  Step s takes
     // the column with the largest remaining diagonal, scales it into row s of Z (LDS) and deflates P by it.
@@ -826,7 +809,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       pc = (s2 > 0.f) ? sqrtf(fmaxf(s2 - z2, 0.f) / s2) : 0.f;
       __syncthreads();
     }
-    BF_STAMP(1, 3);
     // Z to global scratch (for the last phase), X = G Z^T (d x m) and T = Z X (m x m) on the matrix cores.
     // T is the residual Gram matrix R^T R = P G P restricted to the complement; its eigenpairs (lambda, w) give
     // those of P G P as (lambda, Z^T w).
@@ -856,7 +838,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       for (int i = 0; i < 16; ++i) Xg[(size_t)(cblk * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)) * MP + t] = xa[i];
     }
     __syncthreads();
-    BF_STAMP(1, 4);
     const int mm = m + (m & 1);
     const int lt = mm + 1;
     f32x16 ta;
@@ -905,7 +886,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     pcr = fmaxf(vd2 - res2, 0.f) / (vd2 + 1e-12f);
     const bool negligible = !(res2 > kRcrSkip * vd2) || m <= 0;
 
-    BF_STAMP(1, 5);
     if (!negligible) {
       // cyclic Jacobi with a round-robin ordering: mm/2 disjoint rotations per round
       const int half = mm / 2;
@@ -1072,7 +1052,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         nsweeps = sweep + 1;
         if (offn <= tol || lead_done) break;
       }
-      BF_STAMP(1, 6);
       if (replay && tid < half) {                              // whole sweeps end in the layout of set 0
         rbar[tid == 0 ? mm - 1 : tid] = za;
         rbar[tid == 0 ? 0 : mm - 1 - tid] = zb;
@@ -1208,7 +1187,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       }
     }
   }
-  BF_STAMP(1, 7);
   // outputs for every head
   if (tid < d) {
     const float v = skipped ? 0.f : uvec[tid];
@@ -1250,7 +1228,6 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       }
     }
   }
-  BF_STAMP(1, 8);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1415,12 +1392,3 @@ obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const 
 }
 
 }  // namespace obf
-
-#ifdef BF_TRACE
-extern "C" int obf_debug_copy_kb_trace(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_kb_trace), bytes, 0, hipMemcpyDeviceToHost);
-}
-extern "C" int obf_debug_copy_bf_trace(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_bf_trace), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif

@@ -52,10 +52,8 @@ inline int score_rows_per_group(int R) {
 struct Workspace {
   size_t stats_part;   // double2 [heads][nchunk][R]      partial (max, sum-exp) per score chunk
   size_t row_lse;      // double  [heads][R]
-  size_t lse_corr;     // int64   [heads][R]              fixed-point corrections of sum-exp (MFMA path)
   size_t scores;       // float   [heads][N]              (fused call without scores_out)
   size_t score_part;   // float   [RG][heads][N]          per-row-group column sums when group*window > 128
-  size_t budgets;      // unused placeholder kept for alignment
   size_t head_state;   // HeadState [heads]
   size_t decided;      // int32   [heads]                 1: the fast full-rank test settled the head
   size_t basis;        // float   [heads][d][d]           orthonormal basis of the retained span (columns)
@@ -117,10 +115,8 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   w.stats_part = take(sizeof(double) * 2 * (size_t)m.heads * (w.nchunk > w.nslot ? w.nchunk : w.nslot) * m.R);
   w.row_lse = take(sizeof(double) * (size_t)m.heads * m.R);
-  w.lse_corr = take(sizeof(int64_t) * (size_t)m.heads * m.R);
   w.scores = take(sizeof(float) * (size_t)m.heads * m.N);
   w.score_part = take(w.rgroups > 1 ? sizeof(float) * (size_t)w.rgroups * m.heads * m.N : 0);
-  w.budgets = take(256);
   w.head_state = take(sizeof(HeadState) * (size_t)m.heads);
   w.decided = take(sizeof(int32_t) * (size_t)m.heads);
   w.basis = take(sizeof(float) * (size_t)m.heads * m.d * m.d);
@@ -139,7 +135,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
 
 enum Stage {
   ST_SCORE_STATS = 0, ST_SCORE_LSE, ST_SCORE_MASS, ST_SELECT, ST_REFINE, ST_GATHER, ST_KEEP_CERT, ST_KEEP_BASIS, ST_DEL_STATS,
-  ST_FINALIZE, ST_INJECT, ST_COUNT
+  ST_FINALIZE, ST_COUNT
 };
 
 // Brackets one kernel launch with HIP events when profiling of that stage is enabled.

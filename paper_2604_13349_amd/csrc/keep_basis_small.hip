@@ -20,13 +20,6 @@ constexpr int KS_THREADS = 512;
 constexpr int KS_WAVES = KS_THREADS / 64;
 constexpr double kRankEpsKs = 1.1920928955078125e-07;   // 2^-23, the rank rule's epsilon
 
-#ifdef BF_TRACE
-__device__ uint64_t g_ks_trace[512 * 12];
-#define KS_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_ks_trace[blockIdx.x * 12 + (k)] = wall_clock64(); } while (0)
-#else
-#define KS_STAMP(k) do { } while (0)
-#endif
-
 __device__ __forceinline__ double ks_block_sum(double v, double* red /*[KS_WAVES]*/) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   __syncthreads();
@@ -142,7 +135,6 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
       }
     __syncthreads();
   }
-  KS_STAMP(2);
 
   // ---- sigma_max^2 = lambda_max(C): power iteration.  Each quarter of the workgroup (a wave pair) takes every
   // fourth row of C for all columns, the partial products meet in LDS.  The iterate is scaled by the first
@@ -178,7 +170,6 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
   }
   const double thr = sqrt(lam) * (double)max(n, d) * kRankEpsKs;
   const double thr2 = thr * thr;                               // pivots are squared distances
-  KS_STAMP(3);
 
   // ---- rows of A: thread (ty, tx) owns A[ty + 16a][tx*CW ..]
   double areg[TI][CW];
@@ -288,7 +279,6 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
   const T* Vh = V + (size_t)head * kvs * d;
   const int tid = threadIdx.x;
 
-  KS_STAMP(0);
   // demand sums of Eq. 6, in double, fixed summation order
   double pk = 0.0, pt = 0.0;
   for (int i = tid; i < n; i += KS_THREADS) pk += (double)sc[id[i]];
@@ -297,7 +287,6 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
   const double a_tot = ks_block_sum(pt, sh.red);
   double a_del = a_tot - a_keep;
   if (a_del < 0.0) a_del = 0.0;
-  KS_STAMP(1);
 
   int r_keep = 0, active = 0;
   if (rank > 0 && n > 0 && n_del > 0) {
@@ -314,7 +303,6 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
     }
     active = (r_keep < d) ? 1 : 0;
   }
-  KS_STAMP(4);
   if (tid == 0) {
     HeadState s;
     s.a_keep = a_keep; s.a_del = a_del; s.n_keep = n; s.n_del = n_del; s.r_keep = r_keep; s.active = active;
@@ -359,9 +347,3 @@ obf_status_t launch_keep_basis_small(const Dims& m, const void* V, const float* 
 }
 
 }  // namespace obf
-
-#ifdef BF_TRACE
-extern "C" int obf_debug_copy_ks_trace(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_ks_trace), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif

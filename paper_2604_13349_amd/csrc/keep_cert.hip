@@ -38,13 +38,6 @@ __device__ __forceinline__ void wave_tiles(int wave, int (&rb)[3], int (&cb)[3],
   else { rb[0] = 3; cb[0] = 0; rb[1] = 2; cb[1] = 2; rb[2] = 0; cb[2] = 0; nt = 2; }
 }
 
-#ifdef KC_TRACE
-__device__ uint64_t g_kc_trace[512 * 8];
-#define KC_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_kc_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define KC_STAMP(k) do { } while (0)
-#endif
-
 template <bool via_idx>
 __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* __restrict__ Vsrc /*via_idx ? V [heads][N][d] : gathered rows [heads][max_budget][d]*/,
                                                              const float* __restrict__ scores,
@@ -73,8 +66,6 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   const int32_t* id = idx + (size_t)head * max_budget;
   const uint16_t* Vh = Vsrc + (size_t)head * (via_idx ? kvs : max_budget) * KC_D;
   auto row_of = [&](int r) -> size_t { return via_idx ? (size_t)id[r] : (size_t)r; };    // retained row r of the head
-
-  KC_STAMP(0);
   const int cap = max(KC_MINROWS, n >> 2);
   const int stride = (n + cap - 1) / cap;
   const int rows = (n + stride - 1) / stride;
@@ -155,7 +146,6 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
 #pragma unroll
   for (int u = 0; u < 8; ++u) { const int i = tid + u * KC_THREADS; ej[u] = (i < ns) ? id[i] : -1; }
   // tile j is staged in stage[j % 2]; the loads run two tiles ahead in registers
-  KC_STAMP(1);
   fetch(pre[0], 0);
   fetch(pre[1], KC_TILE);
   put(pre[0], 0);
@@ -175,8 +165,6 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   float ev[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) ev[u] = (ej[u] >= 0) ? sc[ej[u]] : 0.f;
-
-  KC_STAMP(2);
   // ---- trace(G), ||V_keep||_F^2, shift
   // a lane holds a diagonal entry of a diagonal tile iff (lr % 8) / 4 == lh, at i = (lr / 8) * 4 + lr % 4
   const bool has_diag = ((lr & 7) >> 2) == lh;
@@ -286,7 +274,6 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
       }
     }
   };
-  KC_STAMP(3);
   if (tid == 0) s_bad = 0;
   publish(0);
   for (int k = 0; k < KC_D; k += 4) {
@@ -339,7 +326,6 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
       if (t < nt && tcb[t] != kbn && tcb[t] >= kb) update(t);
   }
   __syncthreads();
-  KC_STAMP(4);
   const bool ok = (s_bad == 0);
   if (!ok) return;
 
@@ -382,7 +368,6 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     state[head] = s;
     decided[head] = 1;
   }
-  KC_STAMP(5);
 }
 
 bool keep_cert_supported(const Dims& m) { return m.dtype == OBF_BF16 && m.d == KC_D; }
@@ -402,9 +387,3 @@ obf_status_t launch_keep_cert(const Dims& m, const void* Vsrc, int via_idx, cons
 }
 
 }  // namespace obf
-
-#ifdef KC_TRACE
-extern "C" int obf_debug_copy_kc_trace(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_kc_trace), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif

@@ -46,12 +46,6 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int& ea, int& eb, in
 // count(key >= T) >= B.  Counting is one ballot + population count per owned token and one workgroup sum per bit.
 // With REFINE the tokens whose score lies in the relative band around the threshold are re-decided in double from K, Q
 // and the row log-sum-exp before the list is written (same decisions as select followed by the refinement kernel).
-#ifdef SEL_TRACE
-__device__ uint64_t g_sel_trace[512 * 8];
-#define SEL_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x < 512) g_sel_trace[blockIdx.x * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define SEL_STAMP(k) do { } while (0)
-#endif
 template <int SEG, int SEL_THREADS, bool REFINE, typename ET>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict__ scores, int N, int head0,
                                                         int uniform_budget, BudgetBatch per_head, int use_per_head,
@@ -78,7 +72,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     if (tid == 0) n_keep[head] = B;
     return;
   }
-  SEL_STAMP(0);
   const int base = tid * SEG;
   uint32_t key[SEG];
   int nvalid = min(SEG, max(0, N - base));                     // tokens of this thread inside the head
@@ -111,10 +104,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   uint32_t T = 0u;
   int buf = 0;
   bool exact = false;
-#ifndef SEL_BITS
-#define SEL_BITS 32
-#endif
-  for (int bit = 31; bit >= 32 - SEL_BITS; --bit) {
+  for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = T | (1u << bit);
     const int c = count_ge(cand, buf);
     buf ^= 1;
@@ -139,19 +129,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   if (T != 0xffffffffu) n_gt = count_ge(T + 1u, buf);
   buf ^= 1;
   const int need_eq = B - n_gt;
-
-#ifdef SEL_SKIP_COMPACT
-  if (tid == 0) n_keep[head] = B + (int)T + need_eq;
-  return;
-#endif
-  SEL_STAMP(2);
   int cg = 0, ce = 0;
 #pragma unroll
   for (int i = 0; i < SEG; ++i) { if (i < nvalid) { cg += (key[i] > T); ce += (key[i] == T); } }
   int eg, ee, tg, te;
   block_exscan2<SEL_WAVES>(cg, ce, eg, ee, tg, te, wsum);
-
-  SEL_STAMP(3);
   bool refined = false;
   int bpos0 = 0;
   float lo = 0.f, hi = 0.f;
@@ -190,7 +172,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
         }
       }
       __syncthreads();
-      SEL_STAMP(4);
       rescore_band<ET, SEL_WAVES>(K + (size_t)head * kvs * d, Q + (size_t)head * R * d, row_lse + (size_t)head * R, d, R,
                                  band, nband, band_score);
       __syncthreads();
@@ -202,8 +183,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
       refined = s_changed != 0;
     }
   }
-
-  SEL_STAMP(5);
   if (!refined) {
 #pragma unroll
     for (int i = 0; i < SEG; ++i) {
@@ -238,7 +217,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
   }
   for (int i = B + tid; i < max_budget; i += SEL_THREADS) out[i] = -1;
   if (tid == 0) n_keep[head] = B;
-  SEL_STAMP(6);
 }
 
 template <int SEG, int SEL_THREADS, bool REFINE, typename T>
@@ -292,9 +270,3 @@ obf_status_t launch_select_refine(const Dims& m, const float* scores, const int3
 }
 
 }  // namespace obf
-
-#ifdef SEL_TRACE
-extern "C" int obf_debug_copy_sel_trace(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(obf::g_sel_trace), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif

@@ -46,6 +46,13 @@ def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, ma
                                     variant=variant)
             reps.append(rep)
     checked = [r for r in reps if r.v_checked]
+    swapped = sum(r.swaps > 0 for r in reps)
+    ambiguous = sum(r.ambiguous for r in reps)
+    print(f"[{cfg.name} seed {seed}] heads {len(reps)}: value-checked {len(checked)}, index swaps inside the 1e-6 allowance "
+          f"{swapped}, rank-ambiguous {ambiguous}")
+    # every head must reach the value check unless it is excused by name: a tolerated index swap or a singular value
+    # within a decade of a rank threshold
+    assert len(checked) == len(reps) - sum((r.swaps > 0) or r.ambiguous for r in reps), "a head skipped the value check unexcused"
     assert len(checked) >= max(1, len(reps) // 2), "too few heads reached the value check"
     if expect_active is True:
         assert any(r.skipped == 0 for r in checked), "no head exercised the back-fill"
@@ -286,12 +293,17 @@ def _full_size(gpu, name, seed, sample, expect_active):
     heads = [(int(l), int(h)) for l, h in zip(rng.integers(0, L, sample), rng.integers(0, H, sample))]
     heads += [(0, 0), (L - 1, H - 1)]
     active = 0
+    reps = []
     for (l, h) in heads:
         ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), cfg.rank, cfg.dtype)
         rep = parity.check_head(f"{name}[{l},{h}]", ref, K[l, h], V[l, h], cfg.dtype, int(bud[l, h]),
                                 out["idx"][l, h], out["n_keep"][l, h], out["K_out"][l, h], out["V_out"][l, h],
                                 gpu_diag=out["diag"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
         active += int(rep.skipped == 0)
+        reps.append(rep)
+    print(f"[{name} seed {seed}] oracle heads {len(reps)}: value-checked {sum(r.v_checked for r in reps)}, index swaps inside "
+          f"the 1e-6 allowance {sum(r.swaps > 0 for r in reps)}, rank-ambiguous {sum(r.ambiguous for r in reps)}")
+    assert sum(r.v_checked for r in reps) >= 2, "fewer than two heads reached the value check"
     if expect_active:
         assert active > 0
     else:
@@ -314,8 +326,10 @@ def test_full_config4(gpu):
     _full_size(gpu, "4", 0, 4, False)
 
 
-def test_full_config5_agent1(gpu):
-    _full_size(gpu, "5", 1, 3, False)
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_full_config5_every_handoff(gpu, seed):
+    """Config 5 is four hand-offs with per-agent seeds 0-3: each one at full size, with its own ragged budgets."""
+    _full_size(gpu, "5", seed, 2 if seed != 1 else 3, False)
 
 
 def test_full_paper_shape(gpu):
@@ -688,3 +702,44 @@ def test_graph_capture_replays_match_eager(gpu, name, layerwise, layers):
         torch.cuda.synchronize()
         for k in keys:
             assert torch.equal(out[k], ref[k]), f"eager call after replay {rep}: {k} differs"
+
+
+# --------------------------------------------------------------------------- the call a hot path makes: no optional output
+@pytest.mark.parametrize("name,heads,expect_active", [("3", 6, False), ("3s", 6, True)])
+def test_bare_call_without_optional_outputs(gpu, name, heads, expect_active):
+    """The fused call with scores_out, delta_out and diag all NULL (the configuration the benchmark times): the scores
+    stay in the workspace and the certificate skips its diagnostic sums; idx, K_out and V_out against the oracle."""
+    from paper_2604_13349_amd import binding as Bd
+    cfg = si.shrink(si.CONFIGS[name], n_layers=1, n_kv_heads=heads)
+    K, V, Q = si.make_cache(cfg, 2, threads=8)
+    o = Bd.compress_relay(gpu.to_dev(K, cfg.dtype), gpu.to_dev(V, cfg.dtype), gpu.to_dev(Q, cfg.dtype), budget=cfg.budget,
+                          rank=cfg.rank)
+    import torch
+    torch.cuda.synchronize()
+    assert "scores" not in o and "delta" not in o and "diag" not in o
+    idx, nk = o["idx"].cpu().numpy(), o["n_keep"].cpu().numpy()
+    Ko, Vo = gpu.to_host(o["K_out"], cfg.dtype), gpu.to_host(o["V_out"], cfg.dtype)
+    reps = []
+    for h in range(heads):
+        ref = O.compress_head(K[0, h], V[0, h], Q[0, h * cfg.group:(h + 1) * cfg.group], cfg.budget, cfg.rank, cfg.dtype)
+        reps.append(parity.check_head(f"bare {name}[{h}]", ref, K[0, h], V[0, h], cfg.dtype, cfg.budget, idx[0, h], nk[0, h],
+                                      Ko[0, h], Vo[0, h], gpu_diag=None, gpu_delta=None))
+    assert sum(r.v_checked for r in reps) >= heads - 1
+    assert any(r.skipped == 0 for r in reps) == expect_active
+
+
+@pytest.mark.parametrize("support,rank,k_want", [(44, 16, 4), (41, 8, 1), (40, 8, 0)])
+def test_residual_rank_below_requested_rank(gpu, support, rank, k_want):
+    """k = min(pca_rank, rank R) with rank R the smaller one (Sec. 4.4): the value rows live on the first `support`
+    coordinates, the 40 retained rows span 40 of those dimensions, so the residual has rank support - 40 exactly
+    (its further singular values are zero on both sides, far from either side's rank threshold); with support = 40
+    nothing is left to inject."""
+    cfg = si.RelayConfig("res-rank", 21, 1, 4, 2, 128, 900, 8, 40, rank, "bf16", "structured")
+
+    def edit(K, V, Q):
+        V[..., support:] = 0
+
+    reps = _check_cfg(gpu, cfg, edit=edit)
+    assert all(r.v_checked and not r.ambiguous for r in reps)
+    if k_want == 0:
+        assert all(r.skipped == 1 for r in reps)

@@ -663,3 +663,64 @@ def test_message_is_the_row_concatenation_in_the_order_of_sec_3_3():
     M = O.append_message(prev, keep, gen)
     assert M.tolist() == [[1, 1], [2, 2], [3, 3], [4, 4], [5, 5], [6, 6]]
     assert O.append_message(prev[:0], keep, gen[:0]).tolist() == [[3, 3]]
+
+
+# --------------------------------------------------------------------------- App. K.2: PC and DR by hand; threshold constants
+def test_projection_cosine_and_demand_ratio_by_hand():
+    # d = 4, retained rows e0 and 2 e1 (span = first two coordinates); deleted rows (1,2,3,4) and (2,0,-1,1).
+    # Column sums of the deleted rows: s = (3,2,2,5); of their projections onto the retained span: (3,2,0,0).
+    # PC = <s, Pi s> / (|s| |Pi s|) = 13 / (sqrt(42) sqrt(13)) = sqrt(13/42)              (App. K.2)
+    # DR = (0.25 + 0.5) / (2 + 1) = 0.25 up to the 1e-12 of the denominator               (App. K.2, Eq. 6)
+    V = np.array([[1.0, 0, 0, 0], [0, 2.0, 0, 0], [1.0, 2.0, 3.0, 4.0], [2.0, 0.0, -1.0, 1.0]])
+    A = np.array([2.0, 1.0, 0.25, 0.5])
+    _, dg = O.backfill(V, A, np.array([0, 1]), 1)
+    assert abs(dg.pc - math.sqrt(13.0 / 42.0)) < 1e-14
+    assert abs(dg.dr - 0.25) < 1e-12 and dg.dr < 0.25          # the epsilon sits in the denominator
+    assert abs(dg.a_keep - 3.0) < 1e-15 and abs(dg.a_del - 0.75) < 1e-15
+    # squared norms: deleted rows 30 + 6 = 36, their projections 5 + 4 = 9  =>  PCR = 1/4, RCR = 3/4
+    assert abs(dg.pcr - 0.25) < 1e-12 and abs(dg.rcr - 0.75) < 1e-12
+    # a sign flip of one deleted row's in-span part changes the cosine: rows (1,2,3,4), (-2,0,-1,1):
+    # s = (-1,2,2,5), Pi s = (-1,2,0,0): PC = 5 / (sqrt(34) sqrt(5)) = sqrt(5/34)
+    V2 = V.copy(); V2[3, 0] = -2.0
+    _, dg2 = O.backfill(V2, A, np.array([0, 1]), 1)
+    assert abs(dg2.pc - math.sqrt(5.0 / 34.0)) < 1e-14
+
+
+def test_demand_ratio_on_the_planted_case_is_the_eq6_factor():
+    # planted single direction (all deleted rows c_j e_{d-1}, c_j = 1): delta = DR * e_{d-1} exactly, so the
+    # diagnostic must equal the injected coordinate
+    d, B, nd = 16, 5, 9
+    Vk = np.zeros((B, d)); Vk[:, :B] = np.eye(B)
+    Vd = np.zeros((nd, d)); Vd[:, d - 1] = 1.0
+    A = np.concatenate([np.full(B, 3.0), np.full(nd, 0.5)])
+    Vs, dg = O.backfill(np.vstack([Vk, Vd]), A, np.arange(B), 2)
+    assert abs(dg.dr - 4.5 / 15.0) < 1e-12
+    assert abs((Vs - Vk)[0, d - 1] - dg.dr) < 1e-12 and abs(dg.ivn - dg.dr) < 1e-12
+
+
+def test_rank_rule_threshold_is_max_of_rows_and_cols_times_single_epsilon():
+    # singular values known by construction (scaled unit rows): {1, t}.  Threshold: max(rows, d) * 2^-23.
+    d = 4
+    def keep_rows(rows, t):
+        V = np.zeros((rows, d)); V[0, 0] = 1.0; V[1, 1] = t
+        return V
+    # 2 rows, d = 4: threshold 4 * 2^-23 = 2^-21
+    assert O.orth_rowspace(keep_rows(2, 1.01 * 2.0 ** -21))[0].shape[1] == 2
+    assert O.orth_rowspace(keep_rows(2, 0.99 * 2.0 ** -21))[0].shape[1] == 1
+    # 8 rows (six of them zero), d = 4: threshold 8 * 2^-23 = 2^-20 (with min(rows, d) it would still be 2^-21)
+    assert O.orth_rowspace(keep_rows(8, 1.5 * 2.0 ** -21))[0].shape[1] == 1
+    assert O.orth_rowspace(keep_rows(8, 1.01 * 2.0 ** -20))[0].shape[1] == 2
+    # the same rule decides rank(R) in k = min(pca_rank, rank R): residual rows (0,0,1,0) and (0,0,0,t), 2 deleted rows
+    for t, k_want in ((1.01 * 2.0 ** -21, 2), (0.99 * 2.0 ** -21, 1)):
+        V = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0, 0, 1.0, 0], [0, 0, 0, t]])
+        _, dg = O.backfill(V, np.array([2.0, 2.0, 0.5, 0.5]), np.array([0, 1]), 3)
+        assert dg.k_used == k_want
+
+
+def test_negligible_residual_threshold_is_one_millionth_of_the_deleted_energy():
+    # retained e0; one deleted row (1, t): ||R||^2 / ||V_del||^2 = t^2 / (1 + t^2)
+    for t, skipped in ((1.1e-3, 0), (0.9e-3, 1)):
+        V = np.array([[1.0, 0.0], [1.0, t]])
+        Vs, dg = O.backfill(V, np.array([2.0, 1.0]), np.array([0]), 1)
+        assert dg.skipped == skipped and abs(dg.rcr - t * t / (1 + t * t)) < 1e-17
+        assert (Vs[0, 1] != 0.0) == (skipped == 0)
