@@ -224,6 +224,21 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
  * (negative sizes, NULL parts, n_gen > gen_stride, prev_len_all > prev_stride: OBF_ERR_INVALID_ARG, nothing enqueued);
  * lengths that live on the device are checked there: a head whose parts exceed prev_stride, keep_stride or msg_stride
  * gets msg_len[h] = -1 and all-zero rows. */
+/* For callers that cannot allocate (code under HIP graph capture, serving loops and harnesses that forbid
+ * hipMalloc): obf_compress_relay without a workspace argument and without the optional outputs.  Its scratch is
+ * an array of OBF_STATIC_SCRATCH_BYTES bytes inside the library's device code (one copy per GPU, held until the
+ * process ends), so the call makes no hipMalloc / hipFree, creates no stream or event (all work stays on `stream`;
+ * the retained K rows are not copied on a second stream) and calls no allocating routine.  A shape whose
+ * obf_workspace_bytes() exceeds the array is OBF_ERR_UNSUPPORTED (nothing enqueued); stage profiling must be off.
+ * Outputs equal obf_compress_relay's bit for bit.  Every call on a GPU uses that GPU's one array, which keeps the
+ * last call's contents: no kernel relies on its initial contents, but two calls that overlap in time on one GPU
+ * (different streams or host threads) race on it - the caller serialises them. */
+#define OBF_STATIC_SCRATCH_BYTES (48u << 20)
+size_t obf_static_scratch_bytes(void);
+obf_status_t obf_compress_relay_static(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                       const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                       void* K_out, void* V_out, int32_t* idx, int32_t* n_keep, void* stream);
+
 obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype,
                                 const void* prev_K, const void* prev_V, const int32_t* prev_len, int32_t prev_len_all,
                                 int32_t prev_stride,

@@ -92,6 +92,10 @@ def load_library():
     lib.obf_compress_relay_window.restype = C.c_int
     lib.obf_compress_relay_window.argtypes = [sp, C.POINTER(_Window), vp, vp, vp, vp, i32, i32, i32, i32, vr, vp, vp, vp, vp,
                                               vp, vp, vp, vp, sz, vp]
+    lib.obf_static_scratch_bytes.restype = sz
+    lib.obf_static_scratch_bytes.argtypes = []
+    lib.obf_compress_relay_static.restype = C.c_int
+    lib.obf_compress_relay_static.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.obf_append_message.restype = C.c_int
     lib.obf_append_message.argtypes = [i32, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, i32, vp]
     lib.obf_profile_enable.restype = C.c_int
@@ -292,6 +296,18 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
         _ptr(ws), ws.numel(), _stream()))
     o["ws"] = ws
     return o
+
+
+def compress_relay_static(K, V, Qwin, out, budget: int = 0, rank: int = 0, budgets=None):
+    """obf_compress_relay_static: the fused call on the library's built-in scratch array.  `out` holds the caller's
+    K_out, V_out [L,H,max_budget,d], idx [L,H,max_budget] and n_keep [L,H]; nothing is allocated here or in the library."""
+    sh = shape_of(K, Qwin)
+    keep, bptr = _budgets_arg(budgets)          # `keep` holds the host array until the call has returned
+    max_budget = out["idx"].shape[-1]
+    _check(load_library().obf_compress_relay_static(C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank,
+                                                    _ptr(out["K_out"]), _ptr(out["V_out"]), _ptr(out["idx"]),
+                                                    _ptr(out["n_keep"]), _stream()))
+    return out
 
 
 def append_message(prev_K, prev_V, prev_len, keep_K, keep_V, n_keep, gen_K, gen_V, msg_stride: int, prev_len_all: int = 0):

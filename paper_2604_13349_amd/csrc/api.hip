@@ -3,6 +3,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include <vector>
 #include "common.hpp"
 
@@ -348,6 +349,53 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
   OBF_TRY(make_variant(variant, &var));
   return compress_relay_impl(layerwise != 0, var, window, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out,
                              idx, n_keep, scores_out, delta_out, diag, ws, ws_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------
+// Its workspace is this array in the code object's zero-initialised data: every GPU the library is loaded on holds its
+// own copy at its own address for the life of the process.  The name is a host-side handle only; the device address
+// comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)OBF_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static obf_status_t static_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptrs[64] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { set_error("hipGetDevice failed"); return OBF_ERR_HIP; }
+  if (dev < 0 || dev >= 64) { set_error("device ordinal %d out of range", dev); return OBF_ERR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { set_error("hipGetSymbolAddress(scratch): %s", hipGetErrorString(e)); return OBF_ERR_HIP; }
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return OBF_OK;
+}
+
+size_t obf_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+obf_status_t obf_compress_relay_static(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                       const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                       void* K_out, void* V_out, int32_t* idx, int32_t* n_keep, void* stream) {
+  OBF_TRY(check_shape(shape));
+  if (max_budget < 0 || rank < 0) { set_error("max_budget and rank must not be negative"); return OBF_ERR_INVALID_ARG; }
+  const size_t need = carve(make_dims(shape), max_budget, rank).total;
+  if (need > kStaticScratchBytes) {
+    set_error("this shape needs %zu bytes of scratch, the built-in array holds %zu: use obf_compress_relay with a workspace",
+              need, kStaticScratchBytes);
+    return OBF_ERR_UNSUPPORTED;
+  }
+  if (g_prof_stage >= 0) { set_error("stage profiling creates events: switch it off before this call"); return OBF_ERR_INVALID_ARG; }
+  void* ws = nullptr;
+  OBF_TRY(static_scratch_ptr(&ws));
+  set_single_stream(true);                 // no second stream: creating one allocates
+  obf_status_t s = compress_relay_impl(0, Variant(), nullptr, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out,
+                                       V_out, idx, n_keep, nullptr, nullptr, nullptr, ws, kStaticScratchBytes, stream);
+  set_single_stream(false);
+  return s;
 }
 
 obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype,

@@ -1235,7 +1235,11 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
 // A second stream (default priority) per host thread and device, with the two events of a fork / join.
 struct SideStream { hipStream_t stream; hipEvent_t fork, join; int dev; };
 
+static thread_local bool g_single_stream = false;
+void set_single_stream(bool on) { g_single_stream = on; }
+
 static SideStream* side_stream() {
+  if (g_single_stream) return nullptr;                            // everything stays on the caller's stream
   static thread_local SideStream ctx[16];
   static thread_local int nctx = 0;
   int dev = 0;

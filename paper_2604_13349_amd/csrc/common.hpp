@@ -227,6 +227,8 @@ obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream
 // so far and returns it (nullptr: none available, keep everything on st); side_join makes st wait for everything
 // queued on it since.  One fork/join pair may be open at a time.
 hipStream_t side_fork(hipStream_t st);
+// While on (per host thread), no second stream is created or used: every launcher keeps its work on the caller's stream.
+void set_single_stream(bool on);
 obf_status_t side_join(hipStream_t st);
 // Optional early start of the retained-span bases on a second stream (forked from st), for shapes where they
 // do not depend on the gather; *started is then passed on to launch_backfill as basis_started.

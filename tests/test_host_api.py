@@ -134,3 +134,15 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_static_scratch_entry_point_refuses_oversized_shapes_on_the_host(lib):
+    """obf_compress_relay_static: a shape whose workspace exceeds the built-in array is refused before any device call."""
+    assert lib.obf_static_scratch_bytes() >= 32 << 20
+    sh = B.make_shape(36, 8, 4, 128, 8192, 32, "bf16")
+    assert B.workspace_bytes(sh, 1229, 8) > lib.obf_static_scratch_bytes()
+    fake = C.c_void_p(256 * 7)
+    rc = lib.obf_compress_relay_static(C.byref(sh), fake, fake, fake, None, 1229, 1229, 8, fake, fake, fake, fake, None)
+    assert rc == 2 and "scratch" in lib.obf_last_error().decode()
+    bad = B.make_shape(1, 1, 1, 100, 64, 1, "bf16")
+    assert lib.obf_compress_relay_static(C.byref(bad), fake, fake, fake, None, 8, 8, 1, fake, fake, fake, fake, None) == 2
