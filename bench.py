@@ -73,6 +73,8 @@ def main() -> int:
                     help="ablation variant of App. D (not the headline path)")
     ap.add_argument("--sink", type=int, default=-1,
                     help="protect the first SINK tokens as the shared attention sink (the window entry point; -1: plain call)")
+    ap.add_argument("--no-full-path", dest="full_path", action="store_false",
+                    help="skip the extra timings of the full back-fill path (shadow config and paper shape) after the headline")
     ap.add_argument("--message", type=int, default=0,
                     help="also build the outgoing message [sink; retained rows; MESSAGE reasoning rows] in every step")
     args = ap.parse_args()
@@ -147,6 +149,38 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     stages = B.profile_stages()
+
+    def measure(step_fn, steps, warmup):
+        """Warm-up, a one-step-per-stage survey (HIP events inside the library, on the launch stream), then `steps` timed
+        steps: one wall-clock interval around all of them (the headline) and one HIP-event pair per step (the spread)."""
+        for _ in range(max(1, warmup)):
+            step_fn()
+        torch.cuda.synchronize()
+        stage_ms = {}
+        for sid, name in enumerate(stages):
+            B.profile_enable(sid)
+            step_fn()
+            ms, n = B.profile_read()
+            stage_ms[name] = ms
+        B.profile_enable(-1)
+        dominant = max(stage_ms, key=stage_ms.get)
+        B.profile_enable(stages.index(dominant))
+        B.profile_read()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            e0.record()
+            step_fn()
+            e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        dom_ms, dom_n = B.profile_read()
+        B.profile_enable(-1)
+        per = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return {"elapsed": t1 - t0, "stage_ms": stage_ms, "dominant": dominant, "dom_ms": dom_ms, "dom_n": dom_n,
+                "step_ms": {"median": round(per[len(per) // 2], 4), "min": round(per[0], 4), "max": round(per[-1], 4)}}
+
     # one untimed step with the per-head diagnostics (how many heads ran the back-fill); the timed steps leave them
     # out, as a caller on the hot path would (they cost a pass over every head's scores)
     want_diag = True
@@ -156,50 +190,71 @@ def main() -> int:
     active_heads = int((diag["skipped"] == 0).sum())
     outs = [None] * len(calls)
     want_diag = False
-    for _ in range(max(1, args.warmup)):
-        step()
-    torch.cuda.synchronize()
-    # survey: one untimed step per stage to find the dominant kernel
-    stage_ms = {}
-    for sid, name in enumerate(stages):
-        B.profile_enable(sid)
-        step()
-        ms, n = B.profile_read()
-        stage_ms[name] = ms
-    B.profile_enable(-1)
-    dominant = max(stage_ms, key=stage_ms.get)
-
-    B.profile_enable(stages.index(dominant))
-    B.profile_read()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    dom_ms, dom_n = B.profile_read()
-    B.profile_enable(-1)
-    elapsed = t1 - t0
+    r = measure(step, args.steps, args.warmup)
+    stage_ms, dominant, dom_ms, dom_n, elapsed = r["stage_ms"], r["dominant"], r["dom_ms"], r["dom_n"], r["elapsed"]
     ms_per_step = 1e3 * elapsed / args.steps
     head_tokens = cfg.n_heads * cfg.n_tokens * len(calls)
     value = head_tokens / (elapsed / args.steps)
 
-    launches_per_step = max(1, dom_n // max(1, args.steps))
-    dom_avg_ms = dom_ms / max(1, dom_n)
-    dom_bytes = sum(stage_bytes(dominant, cfg, c["bud"], active_heads) for c in calls) / launches_per_step
-    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_avg_ms > 0 else 0.0
-    pbytes = sum(path_bytes(cfg, c["bud"], active_heads) for c in calls)
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", f"traffic_config{cfg.name}.json")
-    if os.path.exists(tfile):
-        with open(tfile) as f:
-            traffic = json.load(f).get(dominant)
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "kernel_ms": round(dom_avg_ms, 4), "kernel_bytes": dom_bytes,
-                "path_bytes": pbytes, "path_GBps": round(pbytes / (elapsed / args.steps) / 1e9, 2),
-                "path_frac": round(pbytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
-                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
+    def roofline_of(r, cfg_, buds, active, steps, tname):
+        """The dominant kernel against the HBM roofline (its algorithmic bytes over its own average launch time) and, as a
+        separate object, the whole path (all algorithmic bytes of a step over the step time)."""
+        lps = max(1, r["dom_n"] // max(1, steps))
+        avg_ms = r["dom_ms"] / max(1, r["dom_n"])
+        kbytes = sum(stage_bytes(r["dominant"], cfg_, b, active) for b in buds) / lps
+        ach = kbytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+        pb = sum(path_bytes(cfg_, b, active) for b in buds)
+        step_s = r["elapsed"] / steps
+        traffic = None
+        tfile = os.path.join(ROOT, "profiles", f"traffic_config{tname}.json")
+        if os.path.exists(tfile):
+            with open(tfile) as f:
+                traffic = json.load(f).get(r["dominant"])
+        roof = {"bound": "hbm", "scope": "dominant kernel only (the whole path is the 'path' object)", "kernel": r["dominant"],
+                "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": traffic, "kernel_ms": round(avg_ms, 4), "kernel_bytes": kbytes,
+                "stage_ms": {k: round(v, 4) for k, v in r["stage_ms"].items()}}
+        path = {"bytes": pb, "GBps": round(pb / step_s / 1e9, 2), "frac": round(pb / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                "target_frac": 0.60, "unit": "GB/s of algorithmic bytes (K, Q once; retained rows read and written; V where the back-fill is active)"}
+        return roof, path
+
+    roofline, path = roofline_of(r, cfg, [c["bud"] for c in calls], active_heads, args.steps, cfg.name)
+    # kept for readers of earlier lines
+    roofline["path_bytes"], roofline["path_GBps"], roofline["path_frac"] = path["bytes"], path["GBps"], path["frac"]
+
+    # The full Orthogonal BackFill path (budget below head_dim, every head injects), measured in the same run: the
+    # same resident cache with budget 96 (shadow of this config) and the paper's own shape (N = 256, budget 32, rank 2).
+    full_path = []
+    plain = variant is None and sink is None and not layerwise and gen_rows is None and cfg.agents == 1
+    if args.full_path and plain and cfg.name in ("3", "2", "4"):
+        shadows = [(si.CONFIGS[cfg.name + "s"], calls[0])]
+        pc = si.CONFIGS["paper"]
+        if args.layers:
+            pc = si.shrink(pc, n_layers=args.layers, name=pc.name)
+        Kp, Vp, Qp = si.make_cache(pc, args.seed, threads=threads)
+        shadows.append((pc, {"K": dev(Kp), "V": dev(Vp), "Q": dev(Qp), "bud": si.budgets(pc, args.seed), "host": (Kp, Vp, Qp)}))
+        for scfg, c in shadows:
+            if args.layers and scfg.name != "paper":
+                scfg = si.shrink(scfg, n_layers=args.layers, name=scfg.name)
+            sb = si.budgets(scfg, args.seed)
+            holder = {"o": None}
+
+            def sstep(c=c, scfg=scfg, sb=sb, holder=holder, wd=False):
+                holder["o"] = B.compress_relay(c["K"], c["V"], c["Q"], budget=int(sb.flat[0]), rank=scfg.rank,
+                                               max_budget=int(sb.max()), out=holder["o"], ws=(holder["o"] or {}).get("ws"),
+                                               want_diag=wd)
+            sstep(wd=True)
+            torch.cuda.synchronize()
+            act = int((B.diag_to_numpy(holder["o"]["diag"])["skipped"] == 0).sum())
+            holder["o"] = None
+            rr = measure(sstep, args.steps, args.warmup)
+            roof_s, path_s = roofline_of(rr, scfg, [sb], act, args.steps, scfg.name)
+            full_path.append({"workload": f"config {scfg.name}: {scfg.n_layers} layers x {scfg.n_kv_heads} KV heads, N={scfg.n_tokens}, "
+                                          f"budget {int(sb.flat[0])}, rank {scfg.rank}", "active_obf_heads": act,
+                              "ms_per_step": round(1e3 * rr["elapsed"] / args.steps, 4), "step_ms": rr["step_ms"],
+                              "value": round(scfg.n_heads * scfg.n_tokens / (rr["elapsed"] / args.steps), 1), "unit": "head-tokens/s",
+                              "path": path_s, "roofline": roof_s})
+            c["shadow"] = (scfg, sb, holder["o"])
 
     extra = {}
     if gen_rows is not None:
@@ -236,29 +291,48 @@ def main() -> int:
                "layers_index_mismatch": mismatched}
     elif args.cpu_seconds > 0:
         from oracle import obf_oracle as O
+        from oracle import gram_baseline as G
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = 1
-        Kh, Vh, Qh = calls[0]["host"]
-        bud = calls[0]["bud"]
-        done, tc0 = 0, time.perf_counter()
-        order = [(l, h) for l in range(cfg.n_layers) for h in range(cfg.n_kv_heads)]
-        idx_host = outs[0]["idx"].cpu().numpy()
-        mismatched = 0
-        for (l, h) in order:
-            ovar = O.Variant(**{{"naive_aggregation": "naive"}.get(k, k): v for k, v in vflags[args.variant].items()})
-            ref = O.compress_head(Kh[l, h], Vh[l, h], Qh[l, h * cfg.group:(h + 1) * cfg.group], int(bud[l, h]), cfg.rank, cfg.dtype,
-                                  ovar, osink)
-            done += 1
-            mismatched += int(not np.array_equal(idx_host[l, h, :len(ref.idx)], ref.idx))
-            if time.perf_counter() - tc0 >= args.cpu_seconds:
+
+        def cpu_leg(kind, cfg_, host, bud_, idx_dev, seconds):
+            """The oracle (kind "oracle": float64, exact SVD) or the single-precision Gram route of App. H (kind "gram32")
+            on the first heads of a cache until `seconds` of CPU time are spent; also counts index sets that differ from
+            the GPU's."""
+            Kh, Vh, Qh = host
+            idx_host = idx_dev.cpu().numpy()
+            done, mismatched, tc0 = 0, 0, time.perf_counter()
+            for l in range(cfg_.n_layers):
+                for h in range(cfg_.n_kv_heads):
+                    Qg = Qh[l, h * cfg_.group:(h + 1) * cfg_.group]
+                    if kind == "oracle":
+                        ovar = O.Variant(**{{"naive_aggregation": "naive"}.get(k, k): v for k, v in vflags[args.variant].items()})
+                        ridx = O.compress_head(Kh[l, h], Vh[l, h], Qg, int(bud_[l, h]), cfg_.rank, cfg_.dtype, ovar, osink).idx
+                    else:
+                        ridx = G.compress_head_gram32(Kh[l, h], Vh[l, h], Qg, int(bud_[l, h]), cfg_.rank, cfg_.dtype)[0]
+                    done += 1
+                    mismatched += int(not np.array_equal(idx_host[l, h, :len(ridx)], ridx))
+                    if time.perf_counter() - tc0 >= seconds:
+                        break
+                else:
+                    continue
                 break
-        tc = time.perf_counter() - tc0
-        cpu = {"value": round(done * cfg.n_tokens / tc, 1), "unit": "head-tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"first {done} of {cfg.n_heads} heads of call 0, {tc:.1f} s, fp64 numpy with exact SVD",
-               "heads_index_mismatch": mismatched}
+            tc = time.perf_counter() - tc0
+            what = "fp64 numpy with exact SVD" if kind == "oracle" else "fp32 numpy, QR + Gram/eigh route of App. H"
+            return {"value": round(done * cfg_.n_tokens / tc, 1), "unit": "head-tokens/s", "cores": int(cores),
+                    "host_cpus": os.cpu_count(), "kind": kind,
+                    "sample": f"first {done} of {cfg_.n_heads} heads of config {cfg_.name}, {tc:.1f} s, {what}",
+                    "heads_index_mismatch": mismatched}
+
+        cpu = cpu_leg("oracle", cfg, calls[0]["host"], calls[0]["bud"], outs[0]["idx"], args.cpu_seconds)
+        if full_path and "shadow" in calls[0]:
+            # the same two CPU routes on the shadow workload, where the SVD of the residual actually runs
+            scfg, sb, so = calls[0]["shadow"]
+            extra["cpu_baseline_full_path"] = [cpu_leg("oracle", scfg, calls[0]["host"], sb, so["idx"], args.cpu_seconds / 2),
+                                               cpu_leg("gram32", scfg, calls[0]["host"], sb, so["idx"], args.cpu_seconds / 2)]
 
     line = {
         "metric": METRIC, "value": round(value, 1), "unit": "head-tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -272,7 +346,7 @@ def main() -> int:
                                + (f", sink {sink}" if sink is not None else "")
                                + (f", message with {args.message} reasoning rows" if gen_rows is not None else ""),
                    "heads": cfg.n_heads, "active_obf_heads": active_heads, "input_gen_s": round(gen_s, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, **extra,
+        "step_ms": r["step_ms"], "roofline": roofline, "path": path, "full_path": full_path or None, "cpu_baseline": cpu, **extra,
     }
     print(json.dumps(line))
     return 0

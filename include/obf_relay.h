@@ -224,6 +224,26 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
  * (negative sizes, NULL parts, n_gen > gen_stride, prev_len_all > prev_stride: OBF_ERR_INVALID_ARG, nothing enqueued);
  * lengths that live on the device are checked there: a head whose parts exceed prev_stride, keep_stride or msg_stride
  * gets msg_len[h] = -1 and all-zero rows. */
+/* The cache-merging comparison system of App. E ("Cache-merging implementation", steps ii and iii) on rows that were
+ * already selected and gathered: every deleted token j is routed to the retained slot t whose key has the highest
+ * cosine similarity with K_j (the first maximum wins; a key of zero norm has cosine 0 with every key), then
+ * V_out[t] = V[idx[t]] + sum over the j routed to t of scores[j] / (scores[idx[t]] + 1e-12) * V[j], added in ascending j
+ * and rounded once to dtype; slots that receive nothing keep the bit copy.  Keys are unchanged.
+ *   K, V      the head's full key / value rows; scores as from obf_score; idx / n_keep as from obf_select_topk
+ *   K_out     gathered keys (read only); V_out gathered values on entry, merged values on exit
+ *   route_out nullable, int32 [n_layers][n_kv_heads][n_tokens]: the slot of every deleted token, -1 for retained tokens
+ * Ownership, stream and error behaviour as obf_backfill. */
+obf_status_t obf_cache_merge(const obf_shape_t* shape, const void* K, const void* V, const float* scores, const int32_t* idx,
+                             const int32_t* n_keep, int32_t max_budget, const void* K_out, void* V_out, int32_t* route_out,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* The whole comparison system in one enqueue: (i) score, select and refine exactly as obf_compress_relay, gather,
+ * then obf_cache_merge.  scores_out, route_out nullable; other arguments as obf_compress_relay. */
+obf_status_t obf_compress_relay_merge(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                      const int32_t* budgets_host, int32_t budget, int32_t max_budget,
+                                      void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                      float* scores_out, int32_t* route_out, void* ws, size_t ws_bytes, void* stream);
+
 /* For callers that cannot allocate (code under HIP graph capture, serving loops and harnesses that forbid
  * hipMalloc): obf_compress_relay without a workspace argument and without the optional outputs.  Its scratch is
  * an array of OBF_STATIC_SCRATCH_BYTES bytes inside the library's device code (one copy per GPU, held until the

@@ -34,6 +34,9 @@ The ablations of App. D are the flags of Variant; readings taken there:
   * EVR-adaptive: k* = smallest k whose leading squared singular values of R
     reach the fraction tau of their total; never above rank R.
   The per-token variant is not stated precisely enough to restate and is absent.
+The cache-merging comparison system of App. E (select, route by key cosine, merge by
+attention mass) is merge_head; readings: the first maximum wins the routing, a key of
+zero norm has cosine 0 with everything, slots that receive nothing stay bit copies.
 Relay assembly (Sec. 3.2-3.3, Sec. 4.3.2): the eligible set Omega leaves out padding
 and the shared sink.  Readings: the arrays handed to this module hold real tokens
 only (right padding is a storage matter); the first `sink` tokens stay keys of the
@@ -358,6 +361,71 @@ def append_message(prev: np.ndarray, keep: np.ndarray, gen: np.ndarray) -> np.nd
     """M_i = [M_{i-1}; Phi(P; G); G] for one (layer, KV head) and one of K / V: rows of the inherited message,
     then the retained prompt rows, then the rows of the reasoning states, each [rows, d] in the I/O dtype."""
     return np.concatenate([prev, keep, gen], axis=0)
+
+
+# ----------------------------------------------------------------------------- cache-merging operator (App. E)
+def merge_routes(K: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """Step (ii) of App. E: every deleted position j is routed to the retained slot whose key has the highest
+    cosine similarity with K_j.  K [N, d] float64, idx ascending.  Returns route [N] int64: the slot number
+    (position in idx) for deleted tokens, -1 for retained ones.
+    Readings: the first maximum wins (lowest slot); a key of zero norm has cosine 0 with everything."""
+    N = K.shape[0]
+    idx = np.asarray(idx, dtype=np.int64)
+    route = np.full(N, -1, dtype=np.int64)
+    dele = complement(idx, N)
+    if dele.size == 0 or idx.size == 0:
+        return route
+    norms = np.sqrt((K * K).sum(axis=1))
+    inv = np.where(norms > 0, 1.0 / np.where(norms > 0, norms, 1.0), 0.0)
+    cos = (K[dele] @ K[idx].T) * inv[dele][:, None] * inv[idx][None, :]
+    route[dele] = np.argmax(cos, axis=1)
+    return route
+
+
+def merge_values(V: np.ndarray, A: np.ndarray, idx: np.ndarray, route: np.ndarray) -> np.ndarray:
+    """Step (iii) of App. E: V*_t = V_t + sum over the deleted j routed to t of A_j / (A_t + eps) V_j."""
+    idx = np.asarray(idx, dtype=np.int64)
+    V_star = V[idx].copy()
+    for j in np.nonzero(route >= 0)[0]:                     # ascending j; one term at a time
+        t = route[j]
+        V_star[t] += A[j] / (A[idx[t]] + EPS) * V[j]
+    return V_star
+
+
+@dataclass
+class MergeResult:
+    A: np.ndarray
+    idx: np.ndarray
+    route: np.ndarray         # [N]: retained slot of every deleted token, -1 for retained tokens
+    cos_gap: np.ndarray       # [N]: best minus second-best cosine of every deleted token (inf with one slot; checker's tie allowance)
+    K_keep: np.ndarray        # I/O dtype
+    V_out: np.ndarray         # I/O dtype (rounded V*; a bit copy where nothing was routed to the slot)
+    V_star: np.ndarray        # float64
+
+
+def merge_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int, dtype: str) -> MergeResult:
+    """The cache-merging comparison system of App. E for one (layer, KV head): (i) the same TopK_B selector,
+    (ii) routing by key cosine similarity, (iii) attention-weighted merge of the deleted values; keys unchanged."""
+    K = decode(K_io, dtype)
+    V = decode(V_io, dtype)
+    Qr = decode(Q_io, dtype).reshape(-1, K.shape[1])
+    A = attention_mass(K, Qr)
+    idx = select_topk(A, budget)
+    route = merge_routes(K, idx)
+    V_star = merge_values(V, A, idx, route)
+    gap = np.full(K.shape[0], np.inf)
+    dele = np.nonzero(route >= 0)[0]
+    if dele.size and idx.size > 1:
+        norms = np.sqrt((K * K).sum(axis=1))
+        inv = np.where(norms > 0, 1.0 / np.where(norms > 0, norms, 1.0), 0.0)
+        cos = (K[dele] @ K[idx].T) * inv[dele][:, None] * inv[idx][None, :]
+        top2 = np.partition(cos, -2, axis=1)[:, -2:]
+        gap[dele] = top2[:, 1] - top2[:, 0]
+    V_out = np.asarray(V_io)[idx].copy()
+    touched = np.zeros(idx.size, dtype=bool)
+    touched[route[dele]] = True
+    V_out[touched] = round_to_io(V_star[touched], dtype)
+    return MergeResult(A=A, idx=idx, route=route, cos_gap=gap, K_keep=np.asarray(K_io)[idx].copy(), V_out=V_out, V_star=V_star)
 
 
 # ----------------------------------------------------------------------------- App. H route (used by pins and as a second CPU timing)

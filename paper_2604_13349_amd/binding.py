@@ -92,6 +92,10 @@ def load_library():
     lib.obf_compress_relay_window.restype = C.c_int
     lib.obf_compress_relay_window.argtypes = [sp, C.POINTER(_Window), vp, vp, vp, vp, i32, i32, i32, i32, vr, vp, vp, vp, vp,
                                               vp, vp, vp, vp, sz, vp]
+    lib.obf_cache_merge.restype = C.c_int
+    lib.obf_cache_merge.argtypes = [sp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.obf_compress_relay_merge.restype = C.c_int
+    lib.obf_compress_relay_merge.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.obf_static_scratch_bytes.restype = sz
     lib.obf_static_scratch_bytes.argtypes = []
     lib.obf_compress_relay_static.restype = C.c_int
@@ -294,6 +298,40 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
         C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]),
         _ptr(o["idx"]), _ptr(o["n_keep"]), _ptr(o.get("scores")), _ptr(o.get("delta")), _ptr(o.get("diag")),
         _ptr(ws), ws.numel(), _stream()))
+    o["ws"] = ws
+    return o
+
+
+def cache_merge(shape: _Shape, K, V, scores, idx, n_keep, K_out, V_out, route=None, ws=None):
+    """obf_cache_merge on gathered rows; V_out is updated in place.  Returns the route tensor if one was passed."""
+    max_budget = idx.shape[-1]
+    ws = _ws(shape, max_budget, 0, ws, K.device)
+    _check(load_library().obf_cache_merge(C.byref(shape), _ptr(K), _ptr(V), _ptr(scores), _ptr(idx), _ptr(n_keep), max_budget,
+                                          _ptr(K_out), _ptr(V_out), _ptr(route), _ptr(ws), ws.numel(), _stream()))
+    return route
+
+
+def compress_relay_merge(K, V, Qwin, budget: int = 0, budgets=None, max_budget: Optional[int] = None, want_scores=False,
+                         want_route=False, ws=None):
+    """obf_compress_relay_merge: the cache-merging comparison system (App. E) end to end.  Returns a dict of device tensors."""
+    sh = shape_of(K, Qwin)
+    L, H, d, N = sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.n_tokens
+    keep, bptr = _budgets_arg(budgets)
+    if max_budget is None:
+        max_budget = int(min(N, max(keep) if keep is not None else budget))
+    dev = K.device
+    o = {"K_out": torch.empty((L, H, max_budget, d), dtype=K.dtype, device=dev),
+         "V_out": torch.empty((L, H, max_budget, d), dtype=K.dtype, device=dev),
+         "idx": torch.empty((L, H, max_budget), dtype=torch.int32, device=dev),
+         "n_keep": torch.empty((L, H), dtype=torch.int32, device=dev)}
+    if want_scores:
+        o["scores"] = torch.empty((L, H, N), dtype=torch.float32, device=dev)
+    if want_route:
+        o["route"] = torch.empty((L, H, N), dtype=torch.int32, device=dev)
+    ws = _ws(sh, max_budget, 0, ws, dev)
+    _check(load_library().obf_compress_relay_merge(C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget,
+                                                   _ptr(o["K_out"]), _ptr(o["V_out"]), _ptr(o["idx"]), _ptr(o["n_keep"]),
+                                                   _ptr(o.get("scores")), _ptr(o.get("route")), _ptr(ws), ws.numel(), _stream()))
     o["ws"] = ws
     return o
 

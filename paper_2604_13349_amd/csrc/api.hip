@@ -27,6 +27,42 @@ obf_status_t check_launch(const char* what) {
   return OBF_OK;
 }
 
+// ---- the library's own streams -------------------------------------------------------------------
+struct StreamPool { hipStream_t s[2]; hipEvent_t ev[EV_COUNT]; int dev; bool ok; };
+static thread_local bool g_single_stream = false;
+void set_single_stream(bool on) { g_single_stream = on; }
+
+static StreamPool* stream_pool() {
+  static thread_local StreamPool pools[16];
+  static thread_local int npools = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  for (int i = 0; i < npools; ++i) if (pools[i].dev == dev) return pools[i].ok ? &pools[i] : nullptr;
+  if (npools == 16) return nullptr;
+  StreamPool& p = pools[npools++];
+  p.dev = dev;
+  p.ok = true;
+  for (int i = 0; i < 2 && p.ok; ++i) p.ok = hipStreamCreateWithFlags(&p.s[i], hipStreamNonBlocking) == hipSuccess;
+  for (int i = 0; i < EV_COUNT && p.ok; ++i) p.ok = hipEventCreateWithFlags(&p.ev[i], hipEventDisableTiming) == hipSuccess;
+  if (!p.ok) (void)hipGetLastError();                             // no second stream on this device: not an error of the call
+  return p.ok ? &p : nullptr;
+}
+
+hipStream_t aux_stream(int which) {
+  if (g_single_stream || which < 0 || which > 1) return nullptr;
+  StreamPool* p = stream_pool();
+  return p ? p->s[which] : nullptr;
+}
+
+obf_status_t stream_after(hipStream_t waiter, hipStream_t signaller, int slot) {
+  StreamPool* p = (slot >= 0 && slot < EV_COUNT) ? stream_pool() : nullptr;
+  if (!p || hipEventRecord(p->ev[slot], signaller) != hipSuccess || hipStreamWaitEvent(waiter, p->ev[slot], 0) != hipSuccess) {
+    set_error("ordering two streams with an event failed");
+    return OBF_ERR_HIP;
+  }
+  return OBF_OK;
+}
+
 // ---- stage profiling ---------------------------------------------------------------------------
 struct ProfRec { hipEvent_t a, b; };
 static thread_local int g_prof_stage = -1;
@@ -199,7 +235,7 @@ obf_status_t obf_backfill(const obf_shape_t* shape, const void* V, const float* 
   Workspace w = carve(m, max_budget, rank);
   OBF_TRY(check_ws(m, w, ws, ws_bytes));
   return launch_backfill(m, w, (char*)ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag,
-                         (hipStream_t)stream);
+                         (hipStream_t)stream, aux_stream(0));
 }
 
 // obf_variant_t (nullable) checked and packed for the kernels.
@@ -269,24 +305,38 @@ static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_wi
   // the gather also leaves the sums of squares of the retained V rows for the full-rank certificate
   double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
   // small budgets: the bases of the retained spans start now on a second stream, beside the gather
+  hipStream_t aux = aux_stream(0);
   bool basis_started = false;
-  if (!var.skips_basis())
-    OBF_TRY(launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, &basis_started));
+  if (!var.skips_basis()) {
+    const obf_status_t bs = launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, aux, &basis_started);
+    if (bs != OBF_OK) {
+      if (basis_started) (void)stream_after(st, aux, EV_BASIS_JOIN);      // never leave the second stream un-joined
+      return bs;
+    }
+  }
   // Large budgets: nothing downstream reads K_out, so the retained K rows are copied on the second stream once the
   // V rows (which the certificate waits for) are through, beside the latency-bound per-head kernels.
-  hipStream_t kside = nullptr;
-  if (!basis_started && (size_t)max_budget * m.heads >= 65536) {
-    OBF_TRY(launch_gather(m, nullptr, V, idx, n_keep, max_budget, nullptr, V_out, st, fro_part));
-    kside = side_fork(st);
-    OBF_TRY(launch_gather(m, K, nullptr, idx, n_keep, max_budget, K_out, nullptr, kside ? kside : st, nullptr));
+  bool k_beside = false;
+  obf_status_t rs = OBF_OK;
+  if (!basis_started && aux && (size_t)max_budget * m.heads >= 65536) {
+    rs = launch_gather(m, nullptr, V, idx, n_keep, max_budget, nullptr, V_out, st, fro_part);
+    if (rs == OBF_OK) rs = stream_after(aux, st, EV_KROWS_FORK);
+    if (rs == OBF_OK) { k_beside = true; rs = launch_gather(m, K, nullptr, idx, n_keep, max_budget, K_out, nullptr, aux, nullptr); }
   } else {
-    OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part));
+    rs = launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part);
   }
   int32_t min_budget = budget;
   if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < mb.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
-  OBF_TRY(launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part,
-                          basis_started, min_budget, var));
-  if (kside) OBF_TRY(side_join(st));
+  // (launch_backfill joins the bases' stream itself, on every path; after an earlier error it is only called for that)
+  if (rs == OBF_OK || basis_started) {
+    const obf_status_t fs = (rs == OBF_OK)
+        ? launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, aux, fro_part,
+                          basis_started, min_budget, var)
+        : stream_after(st, aux, EV_BASIS_JOIN);
+    if (rs == OBF_OK) rs = fs;
+  }
+  if (k_beside) { const obf_status_t js = stream_after(st, aux, EV_KROWS_JOIN); if (rs == OBF_OK) rs = js; }
+  OBF_TRY(rs);
   OBF_TRY(launch_idx_offset(idx, (size_t)m.heads * max_budget, sink, st));   // back to the head's own token numbers
   return OBF_OK;
 }
@@ -335,7 +385,7 @@ obf_status_t obf_backfill_variant(const obf_shape_t* shape, const void* V, const
   Workspace w = carve(m, max_budget, rank);
   OBF_TRY(check_ws(m, w, ws, ws_bytes));
   return launch_backfill(m, w, (char*)ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag,
-                         (hipStream_t)stream, nullptr, false, -1, var);
+                         (hipStream_t)stream, aux_stream(0), nullptr, false, -1, var);
 }
 
 obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_window_t* window,
@@ -349,6 +399,38 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
   OBF_TRY(make_variant(variant, &var));
   return compress_relay_impl(layerwise != 0, var, window, shape, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out,
                              idx, n_keep, scores_out, delta_out, diag, ws, ws_bytes, stream);
+}
+
+obf_status_t obf_cache_merge(const obf_shape_t* shape, const void* K, const void* V, const float* scores, const int32_t* idx,
+                             const int32_t* n_keep, int32_t max_budget, const void* K_out, void* V_out, int32_t* route_out,
+                             void* ws, size_t ws_bytes, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(scores); OBF_NONNULL(idx); OBF_NONNULL(n_keep); OBF_NONNULL(K_out); OBF_NONNULL(V_out);
+  if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }
+  Dims m = make_dims(shape);
+  Workspace w = carve(m, max_budget, 0);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  return launch_cache_merge(m, w, (char*)ws, K, V, scores, idx, n_keep, max_budget, K_out, V_out, route_out, (hipStream_t)stream);
+}
+
+obf_status_t obf_compress_relay_merge(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
+                                      const int32_t* budgets_host, int32_t budget, int32_t max_budget,
+                                      void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                      float* scores_out, int32_t* route_out, void* ws, size_t ws_bytes, void* stream) {
+  OBF_TRY(check_shape(shape));
+  OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(Qwin); OBF_NONNULL(K_out); OBF_NONNULL(V_out); OBF_NONNULL(idx); OBF_NONNULL(n_keep);
+  Dims m = make_dims(shape);
+  OBF_TRY(check_budget(m, budgets_host, budget, max_budget));
+  Workspace w = carve(m, max_budget, 0);
+  OBF_TRY(check_ws(m, w, ws, ws_bytes));
+  char* base = (char*)ws;
+  hipStream_t st = (hipStream_t)stream;
+  float* scores = scores_out ? scores_out : (float*)(base + w.scores);
+  double* row_lse = (double*)(base + w.row_lse);
+  OBF_TRY(run_score(m, w, base, K, Qwin, scores, row_lse, st));                                   // (i) the same selector
+  OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+  OBF_TRY(launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, nullptr));
+  return launch_cache_merge(m, w, base, K, V, scores, idx, n_keep, max_budget, K_out, V_out, route_out, st);   // (ii), (iii)
 }
 
 // ---- the entry point that allocates nothing ------------------------------------------------------

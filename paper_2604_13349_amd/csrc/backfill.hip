@@ -1231,82 +1231,38 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
 }
 
 // ------------------------------------------------------------------------------------------------
-// inject: V_out[row] += delta for the retained rows of heads that were not skipped (Eq. 7)
-// A second stream (default priority) per host thread and device, with the two events of a fork / join.
-struct SideStream { hipStream_t stream; hipEvent_t fork, join; int dev; };
-
-static thread_local bool g_single_stream = false;
-void set_single_stream(bool on) { g_single_stream = on; }
-
-static SideStream* side_stream() {
-  if (g_single_stream) return nullptr;                            // everything stays on the caller's stream
-  static thread_local SideStream ctx[16];
-  static thread_local int nctx = 0;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-  for (int i = 0; i < nctx; ++i) if (ctx[i].dev == dev) return &ctx[i];
-  if (nctx == 16) return nullptr;
-  SideStream c;
-  c.dev = dev;
-  if (hipStreamCreateWithFlags(&c.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-  if (hipEventCreateWithFlags(&c.fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c.join, hipEventDisableTiming) != hipSuccess) return nullptr;
-  ctx[nctx] = c;
-  return &ctx[nctx++];
-}
-
-hipStream_t side_fork(hipStream_t st) {
-  SideStream* side = side_stream();
-  if (!side) return nullptr;
-  if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
-    (void)hipGetLastError();
-    return nullptr;
-  }
-  return side->stream;
-}
-
-obf_status_t side_join(hipStream_t st) {
-  SideStream* side = side_stream();
-  if (!side || hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess) {
-    set_error("joining the side stream failed");
-    return OBF_ERR_HIP;
-  }
-  return OBF_OK;
-}
-
+// host side
 // True when the basis of the retained span may be computed beside the gather and the statistics pass: with every
 // budget below the head dimension each head with deleted rows is active whatever its basis turns out to be.
 static bool basis_overlaps(const Dims& m, int32_t max_budget, int32_t rank) { return rank > 0 && max_budget < m.d; }
 
-// Forks a second stream off `st` and computes the bases there.  *started tells the caller to pass basis_started
-// to launch_backfill, which joins the second stream back before the finalisation.
+// Forks `aux` off `st` and computes the bases there.  *started tells the caller to pass basis_started
+// to launch_backfill, which joins `aux` back before the finalisation.
 obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                                    const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                                   hipStream_t st, bool* started) {
+                                   hipStream_t st, hipStream_t aux, bool* started) {
   *started = false;
-  if (!basis_overlaps(m, max_budget, rank)) return OBF_OK;
-  SideStream* side = side_stream();
-  if (!side) return OBF_OK;                                      // no second stream: the caller's stream does it all
+  if (!aux || aux == st || !basis_overlaps(m, max_budget, rank)) return OBF_OK;   // no second stream: `st` does it all
   HeadState* state = (HeadState*)(ws + w.head_state);
   float* basis = (float*)(ws + w.basis);
-  if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
-    set_error("backfill: forking the side stream failed");
-    return OBF_ERR_HIP;
-  }
-  {
-    ProfScope prof_(ST_KEEP_BASIS, side->stream);
-    if (launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, side->stream) != OBF_OK) return OBF_ERR_HIP;
-  }
-  if (hipEventRecord(side->join, side->stream) != hipSuccess) { set_error("backfill: side stream record failed"); return OBF_ERR_HIP; }
-  *started = true;
-  return OBF_OK;
+  if (stream_after(aux, st, EV_BASIS_FORK) != OBF_OK) return OBF_ERR_HIP;
+  *started = true;                                               // from here on `aux` must be joined, whatever happens
+  ProfScope prof_(ST_KEEP_BASIS, aux);
+  return launch_keep_basis_small(m, V, scores, idx, n_keep, max_budget, rank, state, basis, aux);
 }
 
 template <typename T>
 static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                         const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank, void* V_out,
-                        float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part, bool basis_started,
-                        int32_t min_budget, Variant var) {
+                        float* delta_out, obf_diag_t* diag, hipStream_t st, hipStream_t aux, const double* fro_part,
+                        bool basis_started, int32_t min_budget, Variant var) {
+  // Once the bases run on `aux`, every way out of this function joins it back into `st` first, errors included: the
+  // caller is promised that all work of the call is ordered on its stream.
+  struct Join {
+    hipStream_t st, aux; bool armed;
+    obf_status_t now() { if (!armed) return OBF_OK; armed = false; return stream_after(st, aux, EV_BASIS_JOIN); }
+    ~Join() { (void)now(); }
+  } join{st, aux, basis_started};
   HeadState* state = (HeadState*)(ws + w.head_state);
   float* basis = (float*)(ws + w.basis);
   float* gram_part = (float*)(ws + w.gram_part);
@@ -1326,7 +1282,9 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     if (check_launch("backfill plain state") != OBF_OK) return OBF_ERR_HIP;
   } else if (!basis_started) {
     // the caller did not start the bases earlier: try here (beside the statistics pass only)
-    if (launch_backfill_basis(m, w, ws, V, scores, idx, n_keep, max_budget, rank, st, &basis_started) != OBF_OK) return OBF_ERR_HIP;
+    const obf_status_t bs = launch_backfill_basis(m, w, ws, V, scores, idx, n_keep, max_budget, rank, st, aux, &basis_started);
+    join.armed = basis_started;
+    if (bs != OBF_OK) return OBF_ERR_HIP;
   }
   if (!basis_started && !var.skips_basis()) {
     const size_t smem_kb = sizeof(double) * (size_t)m.d * m.d;
@@ -1364,10 +1322,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
                        (const T*)V, scores, idx, m.N, m.d, max_budget, w.nstat, state, nk_stats, gram_part, m.scs, m.kvs); }
     if (check_launch("backfill del_stats") != OBF_OK) return OBF_ERR_HIP;
   }
-  if (basis_started) {
-    SideStream* side = side_stream();
-    if (!side || hipStreamWaitEvent(st, side->join, 0) != hipSuccess) { set_error("backfill: joining the side stream failed"); return OBF_ERR_HIP; }
-  }
+  if (join.now() != OBF_OK) return OBF_ERR_HIP;
   {
     ProfScope prof_(ST_FINALIZE, st);
     const size_t one = sizeof(float) * m.d * (m.d + 1);
@@ -1388,11 +1343,11 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
 
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, const double* fro_part,
-                             bool basis_started, int32_t min_budget, Variant var) {
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, hipStream_t aux,
+                             const double* fro_part, bool basis_started, int32_t min_budget, Variant var) {
   if (m.dtype == OBF_BF16)
-    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget, var);
-  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, fro_part, basis_started, min_budget, var);
+    return run<uint16_t>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, aux, fro_part, basis_started, min_budget, var);
+  return run<float>(m, w, ws, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, aux, fro_part, basis_started, min_budget, var);
 }
 
 }  // namespace obf

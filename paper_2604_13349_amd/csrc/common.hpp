@@ -66,6 +66,8 @@ struct Workspace {
   size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
   size_t rot;          // float   [heads][kJacobiSweeps][d-1][d/2]  rotation tangents of the Jacobi iteration (max_budget < d only)
   size_t keep_gram;    // double  [kKeepGramSlots][kKeepGramChunks][d*d]  partial Gram matrices (max_budget >= kKeepGramMinBudget)
+  size_t inv_norm;     // float   [heads][max_budget]     reciprocal norms of the retained keys (cache merging)
+  size_t route;        // int32   [heads][N]              retained slot of every deleted token (cache merging, when not an output)
   size_t total;
   int nchunk;          // score chunks per head
   int chunk_tokens;    // tokens per score chunk
@@ -129,6 +131,8 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.fro_part = take(sizeof(double) * (size_t)m.heads * ((max_budget > 0 ? max_budget : 0) / kGatherRows + 1));
   w.rot = take((max_budget < m.d && rank > 0) ? sizeof(float) * (size_t)m.heads * kJacobiSweeps * (m.d - 1) * (m.d / 2) : 0);
   w.keep_gram = take(max_budget >= kKeepGramMinBudget ? sizeof(double) * kKeepGramSlots * kKeepGramChunks * (size_t)m.d * m.d : 0);
+  w.inv_norm = take(sizeof(float) * (size_t)m.heads * (max_budget > 0 ? max_budget : 0));
+  w.route = take(sizeof(int32_t) * (size_t)m.heads * m.N);
   w.total = off;
   return w;
 }
@@ -220,24 +224,31 @@ obf_status_t launch_append_message(int heads, int row_bytes, const void* prev_K,
                                    int prev_len_all, int prev_stride, const void* keep_K, const void* keep_V,
                                    const int32_t* n_keep, int keep_stride, const void* gen_K, const void* gen_V, int n_gen,
                                    int gen_stride, void* msg_K, void* msg_V, int32_t* msg_len, int msg_stride, hipStream_t st);
+// Cache merging (App. E) on selected and gathered rows: routes (route_out nullable) and merged values in V_out.
+obf_status_t launch_cache_merge(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V, const float* scores,
+                                const int32_t* idx, const int32_t* n_keep, int32_t max_budget, const void* K_out,
+                                void* V_out, int32_t* route_out, hipStream_t st);
 // idx[i] += offset for every valid (non-negative) entry
 obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream_t st);
 
-// The library's second stream (one per host thread and device).  side_fork makes it wait for everything queued on st
-// so far and returns it (nullptr: none available, keep everything on st); side_join makes st wait for everything
-// queued on it since.  One fork/join pair may be open at a time.
-hipStream_t side_fork(hipStream_t st);
-// While on (per host thread), no second stream is created or used: every launcher keeps its work on the caller's stream.
+// The library's own streams: two per host thread and device, default priority, created on first use and kept.
+// aux_stream returns nullptr when none is available (creation failed, or the thread is in single-stream mode): the
+// launchers then keep everything on the caller's stream.
+hipStream_t aux_stream(int which /*0 or 1*/);
+// While on (per host thread), no stream or event is created or used by the library.
 void set_single_stream(bool on);
-obf_status_t side_join(hipStream_t st);
-// Optional early start of the retained-span bases on a second stream (forked from st), for shapes where they
-// do not depend on the gather; *started is then passed on to launch_backfill as basis_started.
+// Makes `waiter` wait for everything queued on `signaller` so far, through event `slot` of the calling thread's pool
+// (an event may be recorded again as soon as its wait has been enqueued).  Legal under stream capture.
+enum EventSlot { EV_SCORED = 0, EV_TAIL_JOIN, EV_BASIS_FORK, EV_BASIS_JOIN, EV_KROWS_FORK, EV_KROWS_JOIN, EV_COUNT };
+obf_status_t stream_after(hipStream_t waiter, hipStream_t signaller, int slot);
+// Optional early start of the retained-span bases on `aux` (forked from st), for shapes where they do not depend on
+// the gather; *started is then passed on to launch_backfill as basis_started, which joins `aux` back.
 obf_status_t launch_backfill_basis(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                                    const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                                   hipStream_t st, bool* started);
+                                   hipStream_t st, hipStream_t aux, bool* started);
 obf_status_t launch_backfill(const Dims& m, const Workspace& w, char* ws, const void* V, const float* scores,
                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, int32_t rank,
-                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st,
+                             void* V_out, float* delta_out, obf_diag_t* diag, hipStream_t st, hipStream_t aux /*nullable*/,
                              const double* fro_part = nullptr,
                              bool basis_started = false, int32_t min_budget = -1 /*smallest per-head budget if known*/,
                              Variant var = Variant());

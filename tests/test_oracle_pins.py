@@ -724,3 +724,92 @@ def test_negligible_residual_threshold_is_one_millionth_of_the_deleted_energy():
         Vs, dg = O.backfill(V, np.array([2.0, 1.0]), np.array([0]), 1)
         assert dg.skipped == skipped and abs(dg.rcr - t * t / (1 + t * t)) < 1e-17
         assert (Vs[0, 1] != 0.0) == (skipped == 0)
+
+
+# --------------------------------------------------------------------------- the benchmark's second CPU baseline (App. H route)
+def test_single_precision_gram_baseline_agrees_with_the_oracle():
+    import synth_inputs as si
+    from oracle import gram_baseline as G
+    cfg = si.shrink(si.CONFIGS["2s"], n_layers=1, n_kv_heads=2)
+    K, V, Q = si.make_cache(cfg, 4, threads=2)
+    for h in range(2):
+        Qh = Q[0, h * cfg.group:(h + 1) * cfg.group]
+        ref = O.compress_head(K[0, h], V[0, h], Qh, 40, 2, cfg.dtype)
+        idx, Vs, delta, skipped = G.compress_head_gram32(K[0, h], V[0, h], Qh, 40, 2, cfg.dtype)
+        assert skipped == 0 and ref.diag.skipped == 0
+        # float32 scores can swap tokens whose masses agree to ~1e-6; allow a couple
+        assert len(set(idx.tolist()) ^ set(ref.idx.tolist())) <= 2
+        if np.array_equal(idx, ref.idx):
+            err = np.linalg.norm(delta - ref.diag.delta) / np.linalg.norm(ref.diag.delta)
+            assert err < 2e-3 * max(1.0, 0.05 / max(1.0 - 1.0 / ref.diag.gap ** 2, 1e-12)), err
+    # full-rank retained span: identity, like the oracle
+    cfg3 = si.shrink(si.CONFIGS["2"], n_layers=1, n_kv_heads=1)
+    K, V, Q = si.make_cache(cfg3, 0, threads=2)
+    idx, Vs, delta, skipped = G.compress_head_gram32(K[0, 0], V[0, 0], Q[0, :cfg3.group], cfg3.budget, cfg3.rank, cfg3.dtype)
+    assert skipped == 1 and not delta.any() and idx.size == cfg3.budget
+
+
+# --------------------------------------------------------------------------- App. E: cache merging
+def test_merge_routing_brute_force_and_by_hand():
+    # by hand, d = 2: retained keys (1,0) [slot 0] and (0,2) [slot 1]; deleted keys (3,1): cos (0.949, 0.316) -> slot 0;
+    # (1,5): cos (0.196, 0.981) -> slot 1; (-1,-1): cos (-0.707, -0.707): a tie, the lowest slot wins; (0,0): all cosines
+    # are taken as 0, lowest slot
+    K = np.array([[1.0, 0], [3.0, 1.0], [0, 2.0], [1.0, 5.0], [-1.0, -1.0], [0.0, 0.0]])
+    route = O.merge_routes(K, np.array([0, 2]))
+    assert route.tolist() == [-1, 0, -1, 1, 0, 0]
+    # scale invariance of the cosine: rescaling any key changes no route (powers of two, so that the exact tie stays exact)
+    K2 = K * np.array([4.0, 0.125, 8.0, 2.0, 0.5, 1.0])[:, None]
+    assert O.merge_routes(K2, np.array([0, 2])).tolist() == route.tolist()
+    # brute force with an independent formulation (angles through arccos of normalised rows, python loops)
+    r = rng(40)
+    K = r.standard_normal((30, 8)); idx = np.sort(r.choice(30, 7, replace=False))
+    route = O.merge_routes(K, idx)
+    for j in range(30):
+        if j in idx:
+            assert route[j] == -1
+            continue
+        best, arg = None, None
+        for s, t in enumerate(idx):
+            ang = math.acos(max(-1.0, min(1.0, float(K[j] @ K[t]) / math.sqrt(float(K[j] @ K[j]) * float(K[t] @ K[t])))))
+            if best is None or ang < best - 1e-12:
+                best, arg = ang, s
+        assert route[j] == arg
+
+
+def test_merge_values_by_hand_and_mass_conservation():
+    # two retained slots (tokens 0 and 2), three deleted tokens: 1 -> slot 0, 3 -> slot 1, 4 -> slot 0
+    V = np.array([[1.0, 1.0], [2.0, 0.0], [0.0, 3.0], [4.0, 4.0], [0.0, -2.0]])
+    A = np.array([4.0, 1.0, 2.0, 0.5, 2.0])
+    idx = np.array([0, 2]); route = np.array([-1, 0, -1, 1, 0])
+    Vs = O.merge_values(V, A, idx, route)
+    # slot 0: (1,1) + 1/4 (2,0) + 2/4 (0,-2) = (1.5, 0);  slot 1: (0,3) + 0.5/2 (4,4) = (1, 4)
+    assert np.allclose(Vs, [[1.5, 0.0], [1.0, 4.0]], rtol=0, atol=1e-11)
+    # the epsilon sits in the denominator next to A_t: a retained mass of zero gives a finite (huge) weight, not inf
+    A0 = A.copy(); A0[2] = 0.0
+    assert np.isfinite(O.merge_values(V, A0, idx, route)).all()
+    # attention-mass weighted first moment is conserved: sum_t A_t V*_t = sum over all tokens A_j V_j (up to eps)
+    r = rng(41)
+    K = r.standard_normal((60, 16)); V = r.standard_normal((60, 16)); A = r.random(60) + 0.1
+    idx = O.select_topk(A, 9)
+    route = O.merge_routes(K, idx)
+    Vs = O.merge_values(V, A, idx, route)
+    assert np.allclose((A[idx][:, None] * Vs).sum(axis=0), (A[:, None] * V).sum(axis=0), rtol=1e-10)
+
+
+def test_merge_head_keeps_keys_and_index_set_and_leaves_untouched_slots_as_bit_copies():
+    import synth_inputs as si
+    cfg = si.RelayConfig("merge-pin", 50, 1, 1, 2, 64, 200, 4, 150, 0, "bf16", "structured")
+    K, V, Q = si.make_cache(cfg, 0)
+    ev = O.compress_head(K[0, 0], V[0, 0], Q[0, :2], 150, 0, "bf16")          # plain eviction: the same selector
+    mg = O.merge_head(K[0, 0], V[0, 0], Q[0, :2], 150, "bf16")
+    assert np.array_equal(mg.idx, ev.idx) and np.array_equal(mg.K_keep, ev.K_keep)
+    routed_to = set(mg.route[mg.route >= 0].tolist())
+    assert 0 < len(routed_to) < 150                                            # 50 deleted tokens cannot reach all 150 slots
+    for s in range(150):
+        same = np.array_equal(mg.V_out[s], V[0, 0][mg.idx[s]])
+        assert same == (s not in routed_to) or (s in routed_to and same)       # untouched slots are bit copies
+        if s not in routed_to:
+            assert same
+    # budget >= N: nothing deleted, nothing merged
+    full = O.merge_head(K[0, 0], V[0, 0], Q[0, :2], 500, "bf16")
+    assert np.array_equal(full.V_out, V[0, 0]) and (full.route == -1).all()
