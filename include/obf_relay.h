@@ -14,6 +14,9 @@
  *   - The caller owns all buffers.  The library never allocates, frees or keeps device
  *     memory; scratch space is the caller's workspace `ws` of at least
  *     obf_workspace_bytes() bytes, 256-byte aligned.  Its contents are undefined after a call.
+ *     Host-side resources the library does create, once per host thread and device and kept until the
+ *     process ends: two streams and a handful of events (first call that can use a second stream), and
+ *     pairs of timing events while stage profiling is on.  obf_compress_relay_static creates none.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*); nothing is
  *     synchronised.  Inputs are never modified.  obf_backfill and the fused calls may run part
  *     of their work on a second stream that the library creates once per host thread and device
@@ -35,8 +38,9 @@
  *       K_out,V_out [n_layers][n_kv_heads][max_budget][head_dim]        dtype, rows >= n_keep zero
  *       delta_out   [n_layers][n_kv_heads][head_dim]                    float (optional)
  *       diag        [n_layers][n_kv_heads]                              obf_diag_t (optional)
- *   - Limits: head_dim in {64, 128}; 1 <= n_tokens <= 32768; group*window >= 1;
- *     0 <= budget <= max_budget.  Anything else is OBF_ERR_UNSUPPORTED / OBF_ERR_INVALID_ARG.
+ *   - Limits: head_dim in {64, 128}; 1 <= n_tokens <= 32768; 1 <= group*window <= 4096;
+ *     n_layers*n_kv_heads <= 65535; budget >= 0 and min(budget, n_tokens) <= max_budget (a budget above
+ *     n_tokens keeps every token).  Anything else is OBF_ERR_UNSUPPORTED / OBF_ERR_INVALID_ARG.
  */
 #ifndef OBF_RELAY_H
 #define OBF_RELAY_H
@@ -224,6 +228,31 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
  * (negative sizes, NULL parts, n_gen > gen_stride, prev_len_all > prev_stride: OBF_ERR_INVALID_ARG, nothing enqueued);
  * lengths that live on the device are checked there: a head whose parts exceed prev_stride, keep_stride or msg_stride
  * gets msg_len[h] = -1 and all-zero rows. */
+obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype,
+                                const void* prev_K, const void* prev_V, const int32_t* prev_len, int32_t prev_len_all,
+                                int32_t prev_stride,
+                                const void* keep_K, const void* keep_V, const int32_t* n_keep, int32_t keep_stride,
+                                const void* gen_K, const void* gen_V, int32_t n_gen, int32_t gen_stride,
+                                void* msg_K, void* msg_V, int32_t* msg_len, int32_t msg_stride, void* stream);
+
+/* A batch of samples in one call (App. A.7: right padding, per-sample lengths).  Storage is right-padded:
+ *   K, V      [n_samples][n_layers][n_kv_heads][token_stride][head_dim], sample s holds n_tokens_host[s] real tokens per head
+ *   Qwin      [n_samples][n_layers][n_kv_heads*group][window][head_dim]
+ *   K_out, V_out, idx, n_keep, diag: the layouts of obf_compress_relay with a leading [n_samples] dimension
+ * shape describes one sample (shape.n_tokens is ignored; every n_tokens_host[s] must lie in [1, token_stride] and obey the
+ * library's token limit).  n_tokens_host and budgets_host are HOST arrays of n_samples entries (budgets_host nullable:
+ * `budget` for every sample); a sample's budget applies to each of its heads and counts eligible tokens; `sink` as in
+ * obf_window_t (0 <= sink < every n_tokens_host[s]).  Each sample is compressed exactly as obf_compress_relay_window would
+ * compress it alone (the samples are enqueued one after the other on `stream`); the workspace must hold
+ * obf_workspace_bytes_batch() bytes.  diag nullable.  Errors as obf_compress_relay; nothing is enqueued on a host-side error. */
+size_t obf_workspace_bytes_batch(const obf_shape_t* shape, int32_t n_samples, int32_t token_stride, int32_t max_budget, int32_t rank);
+obf_status_t obf_compress_relay_batch(const obf_shape_t* shape, int32_t n_samples, const int32_t* n_tokens_host,
+                                      int32_t token_stride, int32_t sink,
+                                      const void* K, const void* V, const void* Qwin,
+                                      const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                      void* K_out, void* V_out, int32_t* idx, int32_t* n_keep, obf_diag_t* diag,
+                                      void* ws, size_t ws_bytes, void* stream);
+
 /* The cache-merging comparison system of App. E ("Cache-merging implementation", steps ii and iii) on rows that were
  * already selected and gathered: every deleted token j is routed to the retained slot t whose key has the highest
  * cosine similarity with K_j (the first maximum wins; a key of zero norm has cosine 0 with every key), then
@@ -258,13 +287,6 @@ size_t obf_static_scratch_bytes(void);
 obf_status_t obf_compress_relay_static(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
                                        const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
                                        void* K_out, void* V_out, int32_t* idx, int32_t* n_keep, void* stream);
-
-obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype,
-                                const void* prev_K, const void* prev_V, const int32_t* prev_len, int32_t prev_len_all,
-                                int32_t prev_stride,
-                                const void* keep_K, const void* keep_V, const int32_t* n_keep, int32_t keep_stride,
-                                const void* gen_K, const void* gen_V, int32_t n_gen, int32_t gen_stride,
-                                void* msg_K, void* msg_V, int32_t* msg_len, int32_t msg_stride, void* stream);
 
 /* Profiling aid (tracing of the path's own kernels with HIP events on the caller's stream).
  * obf_profile_enable(stage) makes every later call on this thread bracket the launch of that

@@ -92,6 +92,10 @@ def load_library():
     lib.obf_compress_relay_window.restype = C.c_int
     lib.obf_compress_relay_window.argtypes = [sp, C.POINTER(_Window), vp, vp, vp, vp, i32, i32, i32, i32, vr, vp, vp, vp, vp,
                                               vp, vp, vp, vp, sz, vp]
+    lib.obf_workspace_bytes_batch.restype = sz
+    lib.obf_workspace_bytes_batch.argtypes = [sp, i32, i32, i32, i32]
+    lib.obf_compress_relay_batch.restype = C.c_int
+    lib.obf_compress_relay_batch.argtypes = [sp, i32, vp, i32, i32, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.obf_cache_merge.restype = C.c_int
     lib.obf_cache_merge.argtypes = [sp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.obf_compress_relay_merge.restype = C.c_int
@@ -298,6 +302,34 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
         C.byref(sh), _ptr(K), _ptr(V), _ptr(Qwin), bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]),
         _ptr(o["idx"]), _ptr(o["n_keep"]), _ptr(o.get("scores")), _ptr(o.get("delta")), _ptr(o.get("diag")),
         _ptr(ws), ws.numel(), _stream()))
+    o["ws"] = ws
+    return o
+
+
+def compress_relay_batch(K, V, Qwin, n_tokens, budget: int = 0, budgets=None, rank: int = 0, sink: int = 0,
+                         max_budget: Optional[int] = None, want_diag=False):
+    """obf_compress_relay_batch: K, V [S,L,H,stride,d] right-padded, Qwin [S,L,H*g,W,d], n_tokens the real length of each
+    sample (host sequence), budgets one per sample.  Returns a dict of device tensors with a leading sample dimension."""
+    S, L, H, stride, d = K.shape
+    sh = shape_of(K[0], Qwin[0])
+    lens = np.ascontiguousarray(np.asarray(n_tokens, dtype=np.int32).reshape(-1))
+    keep, bptr = _budgets_arg(budgets)
+    if max_budget is None:
+        per = keep if keep is not None else np.full(S, budget)
+        max_budget = int(max(min(int(b), int(n) - sink) for b, n in zip(per, lens)))
+    dev = K.device
+    o = {"K_out": torch.empty((S, L, H, max_budget, d), dtype=K.dtype, device=dev),
+         "V_out": torch.empty((S, L, H, max_budget, d), dtype=K.dtype, device=dev),
+         "idx": torch.empty((S, L, H, max_budget), dtype=torch.int32, device=dev),
+         "n_keep": torch.empty((S, L, H), dtype=torch.int32, device=dev)}
+    if want_diag:
+        o["diag"] = torch.empty((S, L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
+    lib = load_library()
+    nbytes = lib.obf_workspace_bytes_batch(C.byref(sh), S, stride, max_budget, rank)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    _check(lib.obf_compress_relay_batch(C.byref(sh), S, lens.ctypes.data_as(C.c_void_p), stride, sink, _ptr(K), _ptr(V), _ptr(Qwin),
+                                        bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]), _ptr(o["idx"]),
+                                        _ptr(o["n_keep"]), _ptr(o.get("diag")), _ptr(ws), ws.numel(), _stream()))
     o["ws"] = ws
     return o
 

@@ -401,6 +401,73 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
                              idx, n_keep, scores_out, delta_out, diag, ws, ws_bytes, stream);
 }
 
+// ---- a batch of right-padded samples (App. A.7) ---------------------------------------------------
+static size_t batch_slot_bytes(const obf_shape_t* shape, int32_t token_stride, int32_t max_budget, int32_t rank) {
+  // the samples run one after the other on the caller's stream and share one workspace: the largest any length needs
+  obf_shape_t s = *shape;
+  size_t need = 0;
+  for (int32_t n = 1; n <= token_stride; ++n) {
+    s.n_tokens = n;
+    const size_t t = carve(make_dims(&s), max_budget, rank).total;
+    need = t > need ? t : need;
+  }
+  return need;
+}
+
+size_t obf_workspace_bytes_batch(const obf_shape_t* shape, int32_t n_samples, int32_t token_stride, int32_t max_budget, int32_t rank) {
+  if (!shape || n_samples < 1 || token_stride < 1 || token_stride > kMaxTokens || max_budget < 0 || rank < 0) return 0;
+  obf_shape_t s = *shape;
+  s.n_tokens = token_stride;
+  if (check_shape(&s) != OBF_OK) return 0;
+  return batch_slot_bytes(shape, token_stride, max_budget, rank);
+}
+
+obf_status_t obf_compress_relay_batch(const obf_shape_t* shape, int32_t n_samples, const int32_t* n_tokens_host,
+                                      int32_t token_stride, int32_t sink,
+                                      const void* K, const void* V, const void* Qwin,
+                                      const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                      void* K_out, void* V_out, int32_t* idx, int32_t* n_keep, obf_diag_t* diag,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  if (!shape) { set_error("shape is NULL"); return OBF_ERR_INVALID_ARG; }
+  OBF_NONNULL(n_tokens_host); OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(Qwin); OBF_NONNULL(K_out); OBF_NONNULL(V_out);
+  OBF_NONNULL(idx); OBF_NONNULL(n_keep);
+  if (n_samples < 1) { set_error("n_samples < 1"); return OBF_ERR_INVALID_ARG; }
+  if (token_stride < 1 || token_stride > kMaxTokens) { set_error("token_stride outside [1, %d]", kMaxTokens); return OBF_ERR_INVALID_ARG; }
+  if (max_budget < 0 || rank < 0 || sink < 0) { set_error("max_budget, rank and sink must not be negative"); return OBF_ERR_INVALID_ARG; }
+  // everything the host can check, for every sample, before the first kernel is enqueued
+  size_t need = 0;
+  for (int32_t i = 0; i < n_samples; ++i) {
+    obf_shape_t s = *shape;
+    s.n_tokens = n_tokens_host[i];
+    if (s.n_tokens < 1 || s.n_tokens > token_stride) { set_error("n_tokens_host[%d] = %d outside [1, token_stride]", i, s.n_tokens); return OBF_ERR_INVALID_ARG; }
+    if (sink >= s.n_tokens) { set_error("sink %d leaves sample %d (%d tokens) without eligible tokens", sink, i, s.n_tokens); return OBF_ERR_INVALID_ARG; }
+    OBF_TRY(check_shape(&s));
+    Dims m = make_dims(&s);
+    const int32_t b = budgets_host ? budgets_host[i] : budget;
+    if (b < 0) { set_error("budget of sample %d is negative", i); return OBF_ERR_INVALID_ARG; }
+    const int32_t eligible = m.N - sink;
+    if ((b < eligible ? b : eligible) > max_budget) { set_error("budget of sample %d exceeds max_budget %d", i, max_budget); return OBF_ERR_INVALID_ARG; }
+    const size_t t = carve(m, max_budget, rank).total;
+    need = t > need ? t : need;
+  }
+  if (!ws) { set_error("workspace is NULL"); return OBF_ERR_INVALID_ARG; }
+  if (ws_bytes < need) { set_error("workspace too small: %zu bytes given, %zu needed", ws_bytes, need); return OBF_ERR_WORKSPACE_TOO_SMALL; }
+  Dims m0 = make_dims(shape);
+  const size_t heads = (size_t)m0.heads, row = (size_t)m0.d * m0.esize;
+  const obf_window_t win = {token_stride, sink};
+  for (int32_t i = 0; i < n_samples; ++i) {
+    obf_shape_t s = *shape;
+    s.n_tokens = n_tokens_host[i];
+    const size_t kv_off = (size_t)i * heads * token_stride * row, q_off = (size_t)i * heads * m0.R * row;
+    const size_t out_rows = (size_t)i * heads * max_budget;
+    OBF_TRY(compress_relay_impl(0, Variant(), &win, &s, (const char*)K + kv_off, (const char*)V + kv_off, (const char*)Qwin + q_off,
+                                nullptr, budgets_host ? budgets_host[i] : budget, max_budget, rank,
+                                (char*)K_out + out_rows * row, (char*)V_out + out_rows * row, idx + out_rows, n_keep + (size_t)i * heads,
+                                nullptr, nullptr, diag ? diag + (size_t)i * heads : nullptr, ws, ws_bytes, stream));
+  }
+  return OBF_OK;
+}
+
 obf_status_t obf_cache_merge(const obf_shape_t* shape, const void* K, const void* V, const float* scores, const int32_t* idx,
                              const int32_t* n_keep, int32_t max_budget, const void* K_out, void* V_out, int32_t* route_out,
                              void* ws, size_t ws_bytes, void* stream) {

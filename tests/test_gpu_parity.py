@@ -817,3 +817,37 @@ def test_cache_merging_fp32_and_head_dim_64(gpu):
 def test_cache_merging_ragged_token_count_on_the_matrix_cores(gpu):
     cfg = si.RelayConfig("merge-tail", 24, 1, 3, 2, 128, 4099, 16, 0, 0, "bf16", "structured", outlier_frac=0.01)
     assert _check_merge(gpu, cfg, 3, [130, 1, 615]) > 600
+
+
+# --------------------------------------------------------------------------- batch of right-padded samples (App. A.7)
+@pytest.mark.parametrize("sink", [0, 4])
+def test_batch_of_right_padded_samples_with_mixed_lengths(gpu, sink):
+    """Four samples of different lengths in one right-padded buffer, one budget per sample (below and above head_dim),
+    one call: every (sample, layer, head) must equal what the oracle computes for that sample alone."""
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    lens, buds, stride = [340, 165, 512, 97], [32, 32, 200, 500], 512
+    cfg = si.RelayConfig("batch", 61, 2, 2, 2, 128, stride, 8, 0, 2, "bf16", "structured", outlier_frac=0.01)
+    Ks, Vs, Qs = [], [], []
+    for s in range(len(lens)):
+        K, V, Q = si.make_cache(cfg, 100 + s, threads=4)
+        K[:, :, lens[s]:] = 0x7FC0                        # padding rows hold NaNs: they must never be read
+        V[:, :, lens[s]:] = 0x7FC0
+        Ks.append(K); Vs.append(V); Qs.append(Q)
+    Kb, Vb, Qb = (np.stack(x) for x in (Ks, Vs, Qs))
+    o = Bd.compress_relay_batch(gpu.to_dev(Kb, "bf16"), gpu.to_dev(Vb, "bf16"), gpu.to_dev(Qb, "bf16"), lens, budgets=buds,
+                                rank=cfg.rank, sink=sink, want_diag=True)
+    torch.cuda.synchronize()
+    idx, nk = o["idx"].cpu().numpy(), o["n_keep"].cpu().numpy()
+    Ko, Vo = gpu.to_host(o["K_out"], "bf16"), gpu.to_host(o["V_out"], "bf16")
+    diag = o["diag"].cpu().numpy().view(Bd.DIAG_DTYPE).reshape(len(lens), cfg.n_layers, cfg.n_kv_heads)
+    checked = active = 0
+    for s, n in enumerate(lens):
+        for l in range(cfg.n_layers):
+            for h in range(cfg.n_kv_heads):
+                ref = O.compress_head(Kb[s, l, h, :n], Vb[s, l, h, :n], Qb[s, l, h * cfg.group:(h + 1) * cfg.group], buds[s],
+                                      cfg.rank, "bf16", O.Variant(), sink)
+                rep = parity.check_head(f"batch[{s},{l},{h}]", ref, Kb[s, l, h, :n], Vb[s, l, h, :n], "bf16", buds[s], idx[s, l, h],
+                                        nk[s, l, h], Ko[s, l, h], Vo[s, l, h], gpu_diag=diag[s, l, h], sink=sink)
+                checked += int(rep.v_checked); active += int(rep.skipped == 0)
+    assert checked >= 14 and active >= 6

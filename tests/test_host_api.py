@@ -146,3 +146,21 @@ def test_static_scratch_entry_point_refuses_oversized_shapes_on_the_host(lib):
     assert rc == 2 and "scratch" in lib.obf_last_error().decode()
     bad = B.make_shape(1, 1, 1, 100, 64, 1, "bf16")
     assert lib.obf_compress_relay_static(C.byref(bad), fake, fake, fake, None, 8, 8, 1, fake, fake, fake, fake, None) == 2
+
+
+def test_batch_entry_point_checks_every_sample_on_the_host(lib):
+    sh = B.make_shape(2, 2, 2, 128, 1, 8, "bf16")
+    fake = C.c_void_p(256 * 9)
+    lens = (C.c_int32 * 3)(100, 0, 50)
+    call = lambda lens_, stride, sink, buds, budget, maxb, ws_bytes: lib.obf_compress_relay_batch(
+        C.byref(sh), 3, lens_, stride, sink, fake, fake, fake, buds, budget, maxb, 2, fake, fake, fake, fake, None, fake, ws_bytes, None)
+    assert call(lens, 128, 0, None, 16, 16, 1 << 30) == 1 and "n_tokens_host[1]" in lib.obf_last_error().decode()
+    lens = (C.c_int32 * 3)(100, 200, 50)
+    assert call(lens, 128, 0, None, 16, 16, 1 << 30) == 1                       # 200 tokens in a stride of 128
+    lens = (C.c_int32 * 3)(100, 128, 50)
+    assert call(lens, 128, 50, None, 16, 16, 1 << 30) == 1 and "eligible" in lib.obf_last_error().decode()
+    buds = (C.c_int32 * 3)(16, 40, 16)
+    assert call(lens, 128, 0, buds, 0, 16, 1 << 30) == 1 and "sample 1" in lib.obf_last_error().decode()
+    need = lib.obf_workspace_bytes_batch(C.byref(sh), 3, 128, 40, 2)
+    assert need > 0 and call(lens, 128, 0, buds, 0, 40, need - 1) == 3          # OBF_ERR_WORKSPACE_TOO_SMALL
+    assert lib.obf_workspace_bytes_batch(C.byref(sh), 3, 40000, 40, 2) == 0
