@@ -273,6 +273,20 @@ obf_status_t obf_compress_relay_merge(const obf_shape_t* shape, const void* K, c
                                       void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                       float* scores_out, int32_t* route_out, void* ws, size_t ws_bytes, void* stream);
 
+/* Stacked int8 / int4 relay (the "+ int8" / "+ int4" rows of App. E's comparison table) on rows of the compressed cache
+ * (K_out, V_out of the calls above, or any [n_rows][head_dim] array of `dtype`).  The paper names no scheme; this one
+ * reproduces its ratios (16 d / (8 d + 32) = 1.94 and 16 d / (4 d + 32) = 3.76 at head_dim 128): per row,
+ *   zero = fp16(min x), scale = fp16((max x - min x) / L), L = 2^bits - 1, q_c = clamp(rint((x_c - zero) / scale), 0, L)
+ * (all codes 0 when scale is 0), the decision taken in single precision with individually rounded operations.
+ *   codes      uint8 [n_rows][head_dim] for bits = 8; [n_rows][head_dim / 2] for bits = 4 (even column in the low half)
+ *   scale_f16, zero_f16   half-precision bit patterns, [n_rows] each
+ * obf_dequantize_rows writes x_hat = zero + scale * q, rounded once to single precision and then to `dtype`.
+ * Values must lie in the half-precision range.  bits other than 4 or 8: OBF_ERR_INVALID_ARG. */
+obf_status_t obf_quantize_rows(const void* X, int64_t n_rows, int32_t head_dim, int32_t dtype, int32_t bits,
+                               uint8_t* codes, uint16_t* scale_f16, uint16_t* zero_f16, void* stream);
+obf_status_t obf_dequantize_rows(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* zero_f16, int64_t n_rows,
+                                 int32_t head_dim, int32_t dtype, int32_t bits, void* X_out, void* stream);
+
 /* For callers that cannot allocate (code under HIP graph capture, serving loops and harnesses that forbid
  * hipMalloc): obf_compress_relay without a workspace argument and without the optional outputs.  Its scratch is
  * an array of OBF_STATIC_SCRATCH_BYTES bytes inside the library's device code (one copy per GPU, held until the

@@ -428,6 +428,36 @@ def merge_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: int
     return MergeResult(A=A, idx=idx, route=route, cos_gap=gap, K_keep=np.asarray(K_io)[idx].copy(), V_out=V_out, V_star=V_star)
 
 
+# ----------------------------------------------------------------------------- stacked int8 / int4 relay (App. E)
+def quantize_rows(X_io: np.ndarray, dtype: str, bits: int):
+    """Post-hoc quantisation of relay rows (App. E stacks int8 on the compressed relay; the paper fixes no scheme).
+    Reading, chosen because it reproduces the table's ratios (16 d / (8 d + 32) = 1.94 and 16 d / (4 d + 32) = 3.76 at
+    d = 128): every row gets its own asymmetric code with two half-precision numbers,
+        zero = fp16(min x), scale = fp16((max x - min x) / L), L = 2^bits - 1,
+        q_c = clamp(rint((x_c - zero) / scale), 0, L)   (0 when scale is 0),
+    the arithmetic that decides the integer codes being single precision (subtract, divide, round to nearest even), the
+    precision the device takes the same decision in.  X_io [rows, d] in the I/O dtype.
+    Returns (codes uint8 [rows, d], scale float16 [rows], zero float16 [rows]); parity of the scheme itself is unpinned
+    by the paper."""
+    if bits not in (4, 8):
+        raise ValueError(bits)
+    L = np.float32(2 ** bits - 1)
+    X = decode(X_io, dtype).astype(np.float32)              # exact: bf16 and fp32 values are fp32 values
+    lo, hi = X.min(axis=1), X.max(axis=1)
+    zero = lo.astype(np.float16)
+    scale = ((hi - lo) / L).astype(np.float16)
+    z32, s32 = zero.astype(np.float32), scale.astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q = np.rint((X - z32[:, None]) / s32[:, None])
+    q = np.where(s32[:, None] > 0, np.clip(q, 0, L), 0)
+    return q.astype(np.uint8), scale, zero
+
+
+def dequantize_rows(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """x_hat = zero + scale * q in float64 (exact for these operand widths up to one rounding)."""
+    return zero.astype(np.float64)[:, None] + scale.astype(np.float64)[:, None] * codes.astype(np.float64)
+
+
 # ----------------------------------------------------------------------------- App. H route (used by pins and as a second CPU timing)
 def top_subspace_gram(R: np.ndarray, k: int) -> np.ndarray:
     """Top-k right singular vectors of R from the d x d Gram matrix R^T R (App. H)."""

@@ -96,6 +96,10 @@ def load_library():
     lib.obf_workspace_bytes_batch.argtypes = [sp, i32, i32, i32, i32]
     lib.obf_compress_relay_batch.restype = C.c_int
     lib.obf_compress_relay_batch.argtypes = [sp, i32, vp, i32, i32, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.obf_quantize_rows.restype = C.c_int
+    lib.obf_quantize_rows.argtypes = [vp, C.c_int64, i32, i32, i32, vp, vp, vp, vp]
+    lib.obf_dequantize_rows.restype = C.c_int
+    lib.obf_dequantize_rows.argtypes = [vp, vp, vp, C.c_int64, i32, i32, i32, vp, vp]
     lib.obf_cache_merge.restype = C.c_int
     lib.obf_cache_merge.argtypes = [sp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.obf_compress_relay_merge.restype = C.c_int
@@ -332,6 +336,26 @@ def compress_relay_batch(K, V, Qwin, n_tokens, budget: int = 0, budgets=None, ra
                                         _ptr(o["n_keep"]), _ptr(o.get("diag")), _ptr(ws), ws.numel(), _stream()))
     o["ws"] = ws
     return o
+
+
+def quantize_rows(X: torch.Tensor, bits: int = 8):
+    """obf_quantize_rows on X [..., d]: returns (codes uint8, scale, zero) with scale / zero as float16 tensors."""
+    d = X.shape[-1]
+    rows = X.numel() // d
+    dt = OBF_BF16 if X.dtype == torch.bfloat16 else OBF_F32
+    codes = torch.empty((rows, d if bits == 8 else d // 2), dtype=torch.uint8, device=X.device)
+    scale = torch.empty((rows,), dtype=torch.float16, device=X.device)
+    zero = torch.empty((rows,), dtype=torch.float16, device=X.device)
+    _check(load_library().obf_quantize_rows(_ptr(X), rows, d, dt, bits, _ptr(codes), _ptr(scale), _ptr(zero), _stream()))
+    return codes, scale, zero
+
+
+def dequantize_rows(codes, scale, zero, d: int, dtype: torch.dtype, bits: int = 8):
+    rows = scale.numel()
+    X = torch.empty((rows, d), dtype=dtype, device=codes.device)
+    dt = OBF_BF16 if dtype == torch.bfloat16 else OBF_F32
+    _check(load_library().obf_dequantize_rows(_ptr(codes), _ptr(scale), _ptr(zero), rows, d, dt, bits, _ptr(X), _stream()))
+    return X
 
 
 def cache_merge(shape: _Shape, K, V, scores, idx, n_keep, K_out, V_out, route=None, ws=None):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libobf_relay.so")
-SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "select.hip", "refine.hip", "layerwise.hip", "gather.hip", "message.hip", "merge.hip", "keep_cert.hip", "del_stats_mfma.hip", "keep_basis_small.hip", "backfill.hip"]
+SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "select.hip", "refine.hip", "layerwise.hip", "gather.hip", "message.hip", "merge.hip", "quant.hip", "keep_cert.hip", "del_stats_mfma.hip", "keep_basis_small.hip", "backfill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

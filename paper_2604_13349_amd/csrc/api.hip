@@ -500,6 +500,28 @@ obf_status_t obf_compress_relay_merge(const obf_shape_t* shape, const void* K, c
   return launch_cache_merge(m, w, base, K, V, scores, idx, n_keep, max_budget, K_out, V_out, route_out, st);   // (ii), (iii)
 }
 
+static obf_status_t check_quant(int64_t n_rows, int32_t head_dim, int32_t dtype, int32_t bits) {
+  if (n_rows < 0 || n_rows > ((int64_t)1 << 40)) { set_error("n_rows out of range"); return OBF_ERR_INVALID_ARG; }
+  if (head_dim != 64 && head_dim != 128) { set_error("head_dim %d unsupported (64 or 128)", head_dim); return OBF_ERR_UNSUPPORTED; }
+  if (dtype != OBF_F32 && dtype != OBF_BF16) { set_error("unknown dtype %d", dtype); return OBF_ERR_INVALID_ARG; }
+  if (bits != 4 && bits != 8) { set_error("bits must be 4 or 8"); return OBF_ERR_INVALID_ARG; }
+  return OBF_OK;
+}
+
+obf_status_t obf_quantize_rows(const void* X, int64_t n_rows, int32_t head_dim, int32_t dtype, int32_t bits,
+                               uint8_t* codes, uint16_t* scale_f16, uint16_t* zero_f16, void* stream) {
+  OBF_TRY(check_quant(n_rows, head_dim, dtype, bits));
+  OBF_NONNULL(X); OBF_NONNULL(codes); OBF_NONNULL(scale_f16); OBF_NONNULL(zero_f16);
+  return launch_quant_rows(X, (long)n_rows, head_dim, dtype, bits, codes, scale_f16, zero_f16, (hipStream_t)stream);
+}
+
+obf_status_t obf_dequantize_rows(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* zero_f16, int64_t n_rows,
+                                 int32_t head_dim, int32_t dtype, int32_t bits, void* X_out, void* stream) {
+  OBF_TRY(check_quant(n_rows, head_dim, dtype, bits));
+  OBF_NONNULL(X_out); OBF_NONNULL(codes); OBF_NONNULL(scale_f16); OBF_NONNULL(zero_f16);
+  return launch_dequant_rows(codes, scale_f16, zero_f16, (long)n_rows, head_dim, dtype, bits, X_out, (hipStream_t)stream);
+}
+
 // ---- the entry point that allocates nothing ------------------------------------------------------
 // Its workspace is this array in the code object's zero-initialised data: every GPU the library is loaded on holds its
 // own copy at its own address for the life of the process.  The name is a host-side handle only; the device address

@@ -18,6 +18,7 @@
 // The basis kernels may run on a second stream beside the gather and the statistics pass (small budgets).
 #include "common.hpp"
 #include "wave_ops.hpp"
+#include "tri_eigs.hpp"
 
 namespace obf {
 
@@ -575,6 +576,7 @@ __global__ __launch_bounds__(DS_THREADS) void k_bf_del_stats(const T* __restrict
 constexpr int FN_THREADS = 1024;
 constexpr int FN_WAVES = FN_THREADS / 64;
 constexpr int FN_SWEEPS = kJacobiSweeps;
+constexpr int FN_DIRECT_MIN = 20;         // complements at least this wide take the direct leading-eigenpair route when it applies
 constexpr int FN_REPLAY_MIN = 64;        // complements at least this wide do not accumulate eigenvectors (see the Jacobi phase)
 // Floats of dynamic LDS of the first finalisation launch: room for the d x (d+1) projector and for T and W of every
 // complement up to three quarters of d wide (74.5 KB at d = 128, so that two workgroups still share a CU).
@@ -616,6 +618,58 @@ __device__ __forceinline__ bool jacobi_lead_rows_done(const float* T, int lt, in
   return *ok != 0;
 }
 
+// Outputs of one head, shared by the two kernels that can finish it: delta, the head state, the diagnostics, and Eq. 7 on
+// the retained rows.  uvec (LDS) holds delta when the head is not skipped.  NT threads, all must call.
+template <typename T, int NT>
+__device__ __forceinline__ void fn_emit(const int head, const int d, const int rank, HeadState st, const int skipped,
+                                        const int k_used, const float rcr, const float ivn, const float pcr, const float pc,
+                                        const float revr, const float* uvec, HeadState* __restrict__ state,
+                                        float* __restrict__ delta, float* __restrict__ delta_out, obf_diag_t* __restrict__ diag,
+                                        T* __restrict__ V_out, const int max_budget, const float* __restrict__ scores,
+                                        const int32_t* __restrict__ idx, const int vflags, const int scs) {
+  const int tid = threadIdx.x;
+  if (tid < d) {
+    const float v = skipped ? 0.f : uvec[tid];
+    delta[(size_t)head * d + tid] = v;
+    if (delta_out) delta_out[(size_t)head * d + tid] = v;
+  }
+  if (tid == 0) {
+    st.active = skipped ? 0 : 1;
+    st.k_used = k_used; st.rcr = rcr; st.ivn = ivn;
+    state[head] = st;
+    if (diag) {
+      obf_diag_t dg;
+      dg.n_keep = st.n_keep; dg.r_keep = st.r_keep; dg.k_used = k_used; dg.skipped = skipped;
+      dg.a_keep = (float)st.a_keep; dg.a_del = (float)st.a_del; dg.rcr = rcr; dg.ivn = ivn;
+      // a head whose retained span is all of R^d has its deleted values entirely inside it
+      dg.pcr = (rank > 0 && st.n_keep > 0 && st.n_del > 0 && st.r_keep >= d) ? 1.f : pcr;
+      dg.pc = pc; dg.revr = revr;
+      dg.dr = (float)(st.a_del / (st.a_keep + kEps));
+      diag[head] = dg;
+    }
+  }
+  // Eq. 7: the one offset is added to every retained value row (rounded once to the storage type); under Attn-inject
+  // (App. D) row t receives n_keep A_t / (a_keep + eps) times the offset instead
+  if (!skipped && V_out) {
+    const int total = st.n_keep * d;
+    T* base = V_out + (size_t)head * max_budget * d;
+    if (vflags & VF_ATTN_INJECT) {
+      const float per_mass = (float)((double)st.n_keep / (st.a_keep + kEps));
+      const float* sc = scores + (size_t)head * scs;
+      const int32_t* id = idx + (size_t)head * max_budget;
+      for (int e = tid; e < total; e += NT) {
+        T* p = base + e;
+        Elem<T>::store(p, fmaf(per_mass * sc[id[e / d]], uvec[e % d], Elem<T>::load(p)));
+      }
+    } else {
+      for (int e = tid; e < total; e += NT) {
+        T* p = base + e;
+        Elem<T>::store(p, Elem<T>::load(p) + uvec[e % d]);
+      }
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int nstat, int rank,
                                                             HeadState* __restrict__ state,
@@ -626,7 +680,9 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
                                                             T* __restrict__ V_out, int max_budget, int cls,
                                                             const float* __restrict__ scores,
                                                             const int32_t* __restrict__ idx, int vflags, float evr_tau,
-                                                            int scs, float* __restrict__ rot /*nullable*/) {
+                                                            int scs, float* __restrict__ rot /*nullable*/,
+                                                            LeadJob* __restrict__ lead /*nullable: no leading-eigenpair kernel follows*/,
+                                                            int m_direct_max) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
@@ -654,6 +710,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     const int big = 2 * mm0 * (mm0 + 1) > fn_small_floats(d);
     if (cls >= 0 && big != cls) return;                        // cls < 0: one launch with the large LDS takes every head
   }
+  if (lead && tid == 0) lead[head].pending = 0;
 
   if (st.active && naive) {
     // Naive Aggregation (App. D): the plain mean of the deleted value rows, none of Eq. 3-6
@@ -886,7 +943,24 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     pcr = fmaxf(vd2 - res2, 0.f) / (vd2 + 1e-12f);
     const bool negligible = !(res2 > kRcrSkip * vd2) || m <= 0;
 
-    if (!negligible) {
+    // Only a few leading eigenpairs wanted (the method itself: k = pca_rank, no Max-P / EVR rule) from a wide enough
+    // complement: the head is handed to the leading-eigenpair kernel (tridiagonalisation + bisection + inverse iteration,
+    // with a register budget of its own) instead of diagonalising all of T here.
+    const int kq = min(rank, m);
+    const bool direct = lead != nullptr && !negligible && !(vflags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR)) && kq >= 1 &&
+                        kq <= TE_MAXK && m >= FN_DIRECT_MIN && m <= m_direct_max;
+    if (direct) {
+      float* Tg = Gg;                                            // G itself is no longer needed
+      for (int e = tid; e < m * m; e += FN_THREADS) { const int a = e / m; Tg[e] = M[a * lt + (e - a * m)]; }
+      if (tid < d) delta[(size_t)head * d + tid] = uvec[tid];    // u = sum_j A_j v_j; the other kernel replaces it by delta
+      if (tid == 0) {
+        LeadJob jb;
+        jb.pending = 1; jb.m = m; jb.res2 = res2; jb.vd2 = vd2; jb.pc = pc; jb.pcr = pcr; jb.rcr = rcr; jb.pad = 0;
+        lead[head] = jb;
+      }
+      return;
+    }
+    if (!negligible && !direct) {
       // cyclic Jacobi with a round-robin ordering: mm/2 disjoint rotations per round
       const int half = mm / 2;
       // Wide complements: only W_k W_k^T y is needed of the eigenvectors (y = Z u, W_k the k_used leading ones), and
@@ -1173,61 +1247,111 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         }
         __syncthreads();
        }
-        if (tid < d) {
-          float s = 0.f;
-          for (int t = 0; t < m; ++t) s = fmaf(Zg[(size_t)t * d + tid], lamv[t], s);
-          const double alpha = (vflags & VF_NO_SCALING) ? 1.0 : st.a_del / (st.a_keep + kEps);          // Eq. 6
-          uvec[tid] = (float)(alpha * ((double)s / (st.a_del + kEps)));
-        }
-        __syncthreads();
-        if (tid == 0) { double s = 0.0; for (int c = 0; c < d; ++c) s += (double)uvec[c] * uvec[c]; s_off = (float)sqrt(s); }
-        __syncthreads();
-        ivn = s_off;
-        skipped = 0;
       }
     }
+    if (!negligible && k_used > 0) {
+      if (tid < d) {
+        float s = 0.f;
+        for (int t = 0; t < m; ++t) s = fmaf(Zg[(size_t)t * d + tid], lamv[t], s);
+        const double alpha = (vflags & VF_NO_SCALING) ? 1.0 : st.a_del / (st.a_keep + kEps);          // Eq. 6
+        uvec[tid] = (float)(alpha * ((double)s / (st.a_del + kEps)));
+      }
+      __syncthreads();
+      if (tid == 0) { double s = 0.0; for (int c = 0; c < d; ++c) s += (double)uvec[c] * uvec[c]; s_off = (float)sqrt(s); }
+      __syncthreads();
+      ivn = s_off;
+      skipped = 0;
+    }
   }
-  // outputs for every head
-  if (tid < d) {
-    const float v = skipped ? 0.f : uvec[tid];
-    delta[(size_t)head * d + tid] = v;
-    if (delta_out) delta_out[(size_t)head * d + tid] = v;
-  }
+  fn_emit<T, FN_THREADS>(head, d, rank, st, skipped, k_used, rcr, ivn, pcr, pc, revr, uvec, state, delta, delta_out, diag, V_out,
+                         max_budget, scores, idx, vflags, scs);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The heads the finalisation handed over: leading eigenpairs of T by the direct route, then Eq. 4-7 as there.
+template <typename T>
+__global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, HeadState* __restrict__ state, float* __restrict__ mats,
+                                                          float* __restrict__ delta, float* __restrict__ delta_out,
+                                                          obf_diag_t* __restrict__ diag, T* __restrict__ V_out, int max_budget,
+                                                          const float* __restrict__ scores, const int32_t* __restrict__ idx,
+                                                          int vflags, int scs, const LeadJob* __restrict__ lead) {
+  extern __shared__ float sm[];
+  __shared__ float uvec[128], rbar[128], dvec[16], dcomp[128];
+  __shared__ int s_k;
+  __shared__ float s_off;
+  const int head = blockIdx.x;
+  const LeadJob jb = lead[head];
+  if (!jb.pending) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const HeadState st = state[head];
+  const int m = jb.m, r = st.r_keep;
+  const int lt = m | 1;                                        // odd row stride: column accesses without bank conflicts
+  const float* Zg = mats + (size_t)head * 3 * d * d;           // [m][d] basis of the complement
+  const float* Tg = Zg + 2 * (size_t)d * d;                    // [m][m]
+  float* Rf = sm;
+  float* work = sm + ((m * lt + 3) & ~3);                      // 16-byte aligned
+  const int kq = min(rank, m);
+  if (tid < d) uvec[tid] = delta[(size_t)head * d + tid];      // u
+  const float* th;
+  const float* Wk;
+  if (kq <= 4) tri_top_eigs<4>(Tg, m, Rf, lt, m, kq, work, &th, &Wk);
+  else tri_top_eigs<8>(Tg, m, Rf, lt, m, kq, work, &th, &Wk);
   if (tid == 0) {
-    st.active = skipped ? 0 : 1;
-    st.k_used = k_used; st.rcr = rcr; st.ivn = ivn;
-    state[head] = st;
-    if (diag) {
-      obf_diag_t dg;
-      dg.n_keep = st.n_keep; dg.r_keep = st.r_keep; dg.k_used = k_used; dg.skipped = skipped;
-      dg.a_keep = (float)st.a_keep; dg.a_del = (float)st.a_del; dg.rcr = rcr; dg.ivn = ivn;
-      // a head whose retained span is all of R^d has its deleted values entirely inside it
-      dg.pcr = (rank > 0 && st.n_keep > 0 && st.n_del > 0 && st.r_keep >= d) ? 1.f : pcr;
-      dg.pc = pc; dg.revr = revr;
-      dg.dr = (float)(st.a_del / (st.a_keep + kEps));
-      diag[head] = dg;
-    }
+    const float lmax = th[0];
+    const float srel = (float)max(st.n_del, d) * (float)kRankEps;
+    const float floor_rel = fmaxf(srel * srel, kEigFloor);
+    int rankR = 0;
+    for (int j = 0; j < kq; ++j) if (th[j] > lmax * floor_rel) ++rankR;      // descending: the count is a prefix
+    rankR = min(rankR, min(min(st.n_del, d - r), d));
+    s_k = min(rank, rankR);
+    double top = 0.0;
+    for (int j = 0; j < s_k; ++j) top += (double)th[j];
+    s_off = (float)(top / ((double)jb.res2 + 1e-12));
   }
-  // Eq. 7: the one offset is added to every retained value row (rounded once to the storage type); under Attn-inject
-  // (App. D) row t receives n_keep A_t / (a_keep + eps) times the offset instead
-  if (!skipped && V_out) {
-    const int total = st.n_keep * d;
-    T* base = V_out + (size_t)head * max_budget * d;
-    if (vflags & VF_ATTN_INJECT) {
-      const float per_mass = (float)((double)st.n_keep / (st.a_keep + kEps));
-      const float* sc = scores + (size_t)head * scs;
-      const int32_t* id = idx + (size_t)head * max_budget;
-      for (int e = tid; e < total; e += FN_THREADS) {
-        T* p = base + e;
-        Elem<T>::store(p, fmaf(per_mass * sc[id[e / d]], uvec[e % d], Elem<T>::load(p)));
-      }
-    } else {
-      for (int e = tid; e < total; e += FN_THREADS) {
-        T* p = base + e;
-        Elem<T>::store(p, Elem<T>::load(p) + uvec[e % d]);
-      }
+  __syncthreads();
+  const int k_used = s_k;
+  const float revr = (k_used > 0) ? s_off : 0.f;
+  int skipped = 1;
+  float ivn = 0.f;
+  __syncthreads();
+  if (k_used > 0) {
+    if (tid < m) {                                             // y = Z u (Eq. 4 in complement coordinates)
+      float sy = 0.f;
+      for (int c = 0; c < d; ++c) sy = fmaf(Zg[(size_t)tid * d + c], uvec[c], sy);
+      rbar[tid] = sy;
     }
+    __syncthreads();
+    if (wave < k_used) {                                       // coefficient of eigenvector `wave` (Eq. 5)
+      float sc = (lane < m) ? rbar[lane] * Wk[wave * m + lane] : 0.f;
+      if (lane + 64 < m) sc = fmaf(rbar[lane + 64], Wk[wave * m + lane + 64], sc);
+      sc = te_wave_sum(sc);
+      if (lane == 0) dvec[wave] = sc;
+    }
+    __syncthreads();
+    if (tid < m) {
+      float sd = 0.f;
+      for (int i = 0; i < k_used; ++i) sd = fmaf(dvec[i], Wk[i * m + tid], sd);
+      dcomp[tid] = sd;                                         // Delta in complement coordinates (times a_del + eps)
+    }
+    __syncthreads();
+    float dl = 0.f;
+    if (tid < d) {
+      float s = 0.f;
+      for (int t = 0; t < m; ++t) s = fmaf(Zg[(size_t)t * d + tid], dcomp[t], s);
+      const double alpha = (vflags & VF_NO_SCALING) ? 1.0 : st.a_del / (st.a_keep + kEps);          // Eq. 6
+      dl = (float)(alpha * ((double)s / (st.a_del + kEps)));
+    }
+    __syncthreads();                                           // every thread has read u
+    if (tid < d) uvec[tid] = dl;
+    __syncthreads();
+    if (tid == 0) { double s = 0.0; for (int c = 0; c < d; ++c) s += (double)uvec[c] * uvec[c]; s_off = (float)sqrt(s); }
+    __syncthreads();
+    ivn = s_off;
+    skipped = 0;
   }
+  fn_emit<T, TE_THREADS>(head, d, rank, st, skipped, k_used, jb.rcr, ivn, jb.pcr, jb.pc, revr, uvec, state, delta, delta_out, diag, V_out,
+                         max_budget, scores, idx, vflags, scs);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1273,6 +1397,8 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_keep_gram_part<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
+    (void)hipFuncSetAttribute((const void*)k_bf_lead<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)sizeof(float) * (128 * 129 + 4 + tri_work_floats(128, TE_MAXK)));
     attr_done = true;
   }
   if (var.skips_basis()) {
@@ -1326,6 +1452,13 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   {
     ProfScope prof_(ST_FINALIZE, st);
     const size_t one = sizeof(float) * m.d * (m.d + 1);
+    // Heads that only need a few leading eigenpairs of a wide enough complement go to k_bf_lead after the finalisation
+    // (not under the Max-P / EVR rules, which need the whole spectrum).  Its LDS is sized for complements up to 3d/4 wide
+    // (two workgroups per CU); without the projection every complement is all of R^d, and it is sized for that.
+    const bool lead_ok = rank > 0 && rank <= TE_MAXK && !(var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR | VF_NAIVE)) &&
+                         !(min_budget > m.d && m.N > m.d && !var.skips_basis());
+    LeadJob* lead = lead_ok ? (LeadJob*)(ws + w.lead_job) : (LeadJob*)nullptr;
+    const int m_direct_max = (var.flags & VF_NO_PROJECTION) ? m.d : 3 * m.d / 4;
     // every budget above head_dim: heads that need the finalisation are rare (the certificate settles the others), so one
     // launch with the large LDS size serves both classes instead of two launches that mostly exit at once
     const bool single = min_budget > m.d && m.N > m.d && !var.skips_basis();
@@ -1334,10 +1467,19 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
       hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), lds, st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
-                         var.flags, var.evr_tau, m.scs, (max_budget < m.d && rank > 0) ? (float*)(ws + w.rot) : (float*)nullptr);
+                         var.flags, var.evr_tau, m.scs, (max_budget < m.d && rank > 0) ? (float*)(ws + w.rot) : (float*)nullptr,
+                         lead, m_direct_max);
+    }
+    if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
+    if (lead) {
+      const int kq = rank < TE_MAXK ? rank : TE_MAXK;
+      const size_t lds = sizeof(float) * ((size_t)m_direct_max * (m_direct_max | 1) + 4 + tri_work_floats(m_direct_max, kq));
+      hipLaunchKernelGGL(k_bf_lead<T>, dim3(m.heads), dim3(TE_THREADS), lds, st, m.d, rank, state, mats, delta, delta_out, diag,
+                         (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, scores, idx, var.flags, m.scs,
+                         (const LeadJob*)lead);
+      if (check_launch("backfill leading eigenpairs") != OBF_OK) return OBF_ERR_HIP;
     }
   }
-  if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
   return OBF_OK;
 }
 

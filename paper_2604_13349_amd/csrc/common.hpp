@@ -66,6 +66,7 @@ struct Workspace {
   size_t fro_part;     // double  [heads][ceil(max_budget/16)]   per-gather-block sums of squares of the retained V rows
   size_t rot;          // float   [heads][kJacobiSweeps][d-1][d/2]  rotation tangents of the Jacobi iteration (max_budget < d only)
   size_t keep_gram;    // double  [kKeepGramSlots][kKeepGramChunks][d*d]  partial Gram matrices (max_budget >= kKeepGramMinBudget)
+  size_t lead_job;     // LeadJob [heads]                 hand-over from the finalisation to the leading-eigenpair kernel
   size_t inv_norm;     // float   [heads][max_budget]     reciprocal norms of the retained keys (cache merging)
   size_t route;        // int32   [heads][N]              retained slot of every deleted token (cache merging, when not an output)
   size_t total;
@@ -83,6 +84,14 @@ struct HeadState {
   int32_t k_used;
   int32_t pad;
   float rcr, ivn;
+};
+
+// What the finalisation hands to the leading-eigenpair kernel for a head it does not diagonalise itself.
+struct LeadJob {
+  int32_t pending;      // 1: the residual Gram matrix T (m x m, complement coordinates) waits in the head's scratch
+  int32_t m;
+  float res2, vd2, pc, pcr, rcr;
+  int32_t pad;
 };
 
 // One chunk's statistics of the deleted values: G [d][d] (tiles on and below the diagonal), u = sum_j A_j v_j [d],
@@ -131,6 +140,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.fro_part = take(sizeof(double) * (size_t)m.heads * ((max_budget > 0 ? max_budget : 0) / kGatherRows + 1));
   w.rot = take((max_budget < m.d && rank > 0) ? sizeof(float) * (size_t)m.heads * kJacobiSweeps * (m.d - 1) * (m.d / 2) : 0);
   w.keep_gram = take(max_budget >= kKeepGramMinBudget ? sizeof(double) * kKeepGramSlots * kKeepGramChunks * (size_t)m.d * m.d : 0);
+  w.lead_job = take(sizeof(LeadJob) * (size_t)m.heads);
   w.inv_norm = take(sizeof(float) * (size_t)m.heads * (max_budget > 0 ? max_budget : 0));
   w.route = take(sizeof(int32_t) * (size_t)m.heads * m.N);
   w.total = off;
@@ -228,6 +238,11 @@ obf_status_t launch_append_message(int heads, int row_bytes, const void* prev_K,
 obf_status_t launch_cache_merge(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V, const float* scores,
                                 const int32_t* idx, const int32_t* n_keep, int32_t max_budget, const void* K_out,
                                 void* V_out, int32_t* route_out, hipStream_t st);
+// Per-row int8 / int4 codes of relay rows and back (App. E's stacked quantisation, the reading stated in quant.hip).
+obf_status_t launch_quant_rows(const void* X, long n_rows, int d, int dtype, int bits, uint8_t* codes, uint16_t* scale,
+                               uint16_t* zero, hipStream_t st);
+obf_status_t launch_dequant_rows(const uint8_t* codes, const uint16_t* scale, const uint16_t* zero, long n_rows, int d, int dtype,
+                                 int bits, void* X, hipStream_t st);
 // idx[i] += offset for every valid (non-negative) entry
 obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream_t st);
 

@@ -851,3 +851,26 @@ def test_batch_of_right_padded_samples_with_mixed_lengths(gpu, sink):
                                         nk[s, l, h], Ko[s, l, h], Vo[s, l, h], gpu_diag=diag[s, l, h], sink=sink)
                 checked += int(rep.v_checked); active += int(rep.skipped == 0)
     assert checked >= 14 and active >= 6
+
+
+# --------------------------------------------------------------------------- stacked int8 / int4 relay codes (App. E, a reading)
+@pytest.mark.parametrize("dtype,d,bits", [("bf16", 128, 8), ("bf16", 128, 4), ("f32", 64, 8), ("bf16", 64, 4)])
+def test_relay_row_codes_are_bit_exact(gpu, dtype, d, bits):
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    r = np.random.default_rng(70 + bits + d)
+    X = (r.standard_normal((1500, d)) * np.exp(r.standard_normal((1500, 1)))).astype(np.float32)
+    X[7] = 0.0; X[8] = 2.5; X[9, 1:] = X[9, 0]                  # all-zero, constant and almost constant rows
+    X_io = O.round_to_io(X, dtype)
+    q_ref, s_ref, z_ref = O.quantize_rows(X_io, dtype, bits)
+    Xd = gpu.to_dev(X_io, dtype)
+    codes, scale, zero = Bd.quantize_rows(Xd, bits)
+    back = Bd.dequantize_rows(codes, scale, zero, d, Xd.dtype, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(scale.cpu().numpy().view(np.uint16), s_ref.view(np.uint16))
+    assert np.array_equal(zero.cpu().numpy().view(np.uint16), z_ref.view(np.uint16))
+    got = codes.cpu().numpy()
+    want = q_ref if bits == 8 else (q_ref[:, 0::2] | (q_ref[:, 1::2] << 4)).astype(np.uint8)
+    assert np.array_equal(got, want), f"{int((got != want).sum())} codes differ"
+    ref_back = O.round_to_io(O.dequantize_rows(q_ref, s_ref, z_ref), dtype)
+    assert np.array_equal(gpu.to_host(back, dtype), ref_back)

@@ -813,3 +813,33 @@ def test_merge_head_keeps_keys_and_index_set_and_leaves_untouched_slots_as_bit_c
     # budget >= N: nothing deleted, nothing merged
     full = O.merge_head(K[0, 0], V[0, 0], Q[0, :2], 500, "bf16")
     assert np.array_equal(full.V_out, V[0, 0]) and (full.route == -1).all()
+
+
+# --------------------------------------------------------------------------- App. E: stacked int8 / int4 relay (a reading; unpinned by the paper)
+def test_row_quantisation_by_hand_roundtrip_bound_and_ratio():
+    # by hand: x = 0, 0.5, ..., 127.5: zero = 0, scale = 127.5 / 255 = 0.5 exactly, code of entry i is i
+    x = (np.arange(256, dtype=np.float32) * 0.5)[None, :]
+    q, s, z = O.quantize_rows(x, "f32", 8)
+    assert float(z[0]) == 0.0 and float(s[0]) == 0.5 and q[0].tolist() == list(range(256))
+    # int4: x = -3 + 0.4 i, i = 0..15: zero = fp16(-3), scale = fp16(0.4), codes 0..15
+    x4 = (-3.0 + 0.4 * np.arange(16, dtype=np.float32))[None, :].astype(np.float32)
+    q4, s4, z4 = O.quantize_rows(x4, "f32", 4)
+    assert q4[0].tolist() == list(range(16)) and float(z4[0]) == -3.0 and abs(float(s4[0]) - 0.4) < 2e-4
+    # a constant row: scale 0, codes 0, the value comes back as fp16(x)
+    qc, sc, zc = O.quantize_rows(np.full((1, 64), 1.5, dtype=np.float32), "f32", 8)
+    assert not qc.any() and float(sc[0]) == 0.0 and np.all(O.dequantize_rows(qc, sc, zc) == 1.5)
+    # round trip on random bf16 rows: |x - x_hat| <= scale / 2 + the rounding of zero and scale to half precision
+    r = rng(60)
+    X = O.round_to_io(r.standard_normal((50, 128)) * np.exp(r.standard_normal((50, 1))), "bf16")
+    for bits in (8, 4):
+        q, s, z = O.quantize_rows(X, "bf16", bits)
+        assert q.max() <= 2 ** bits - 1
+        x = O.decode(X, "bf16")
+        err = np.abs(O.dequantize_rows(q, s, z) - x)
+        span = x.max(axis=1) - x.min(axis=1)
+        bound = 0.5 * s.astype(np.float64) + 2.0 ** -10 * (np.abs(x).max(axis=1) + span)      # fp16 keeps 11 significant bits
+        assert np.all(err <= bound[:, None] * 1.01 + 1e-12)
+        # every row uses its range: the smallest entry gets code 0 or 1, the largest the top code or one below
+        assert np.all(q[np.arange(50), x.argmin(axis=1)] <= 1) and np.all(q[np.arange(50), x.argmax(axis=1)] >= 2 ** bits - 2)
+    # the sizes behind the paper's ratios at head_dim 128: 16-bit rows against codes plus two half-precision numbers
+    assert abs(16 * 128 / (8 * 128 + 32) - 1.94) < 0.01 and abs(16 * 128 / (4 * 128 + 32) - 3.76) < 0.01
