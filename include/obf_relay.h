@@ -86,6 +86,9 @@ typedef struct {
   float pc;         /* projection cosine between the column sums of V_del and of V_par; 0 when not computed */
   float revr;       /* residual explained variance ratio of the k_used directions; 0 when none is used */
   float dr;         /* demand ratio a_del / (a_keep + eps) */
+  float fast_err;   /* with obf_variant_t.subspace_iters > 0: ||Delta_fast - Delta_svd|| / ||Delta_svd|| of the head
+                       (App. H), 0 if Delta_svd = 0; -1 when not computed (any other call, and heads without an injection
+                       decision by Eq. 5) */
 } obf_diag_t;
 
 /* Bytes of workspace any entry point needs for this shape (host function, no device work).
@@ -163,6 +166,14 @@ obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* 
  *   naive_aggregation  "Naive Aggregation": delta = unweighted mean of the deleted value rows (no Eq. 3-6).
  *   attn_inject        "Attn-inject": row t of V_out receives n_keep * A_t / (sum of A over the retained rows + eps)
  *                      times delta instead of delta (Eq. 7 replaced); delta_out is still delta.
+ *   subspace_iters     0: the exact top-`rank` directions.  t > 0 (at most 64): the fast path of App. H, t steps of
+ *                      C <- orth(C G), G = R^T R, from the first k = min(rank, d - r_keep, |P_del|) rows of the
+ *                      orthonormal cosine basis C_0[i][c] = sqrt(2/d) cos(pi (i + 1/2)(c + 1/2) / d) (the paper asks
+ *                      only for orthonormal rows and runs t = 3); orth is Gram-Schmidt over the rows in order, a row
+ *                      left with at most 1e-5 of the first row's norm is dropped (k_used counts the rows kept, revr is
+ *                      their share of the trace).  Needs subspace = OBF_SUBSPACE_RANK, rank <= 8 and head_dim <= 128,
+ *                      else OBF_ERR_UNSUPPORTED.  With diag != NULL the exact directions are computed too and
+ *                      diag.fast_err reports the distance between the two (this costs the exact route's time).
  * `rank` = 0 is plain eviction under every variant.  The per-token alternative of App. D is not provided. */
 #define OBF_SUBSPACE_RANK 0
 #define OBF_SUBSPACE_ALL 1
@@ -174,6 +185,7 @@ typedef struct obf_variant_t {
   int32_t no_scaling;
   int32_t naive_aggregation;
   int32_t attn_inject;
+  int32_t subspace_iters;
 } obf_variant_t;
 
 /* obf_backfill with an ablation variant (App. D); variant == NULL is obf_backfill itself.  Arguments, layouts,

@@ -33,6 +33,10 @@ The ablations of App. D are the flags of Variant; readings taken there:
     delta the Eq. 6 vector ("alpha delta" in Alg. 3's naming).
   * EVR-adaptive: k* = smallest k whose leading squared singular values of R
     reach the fraction tau of their total; never above rank R.
+  * Fast SVD alternative (Sec. 4.4, App. H): subspace_iters > 0 replaces the SVD by that many steps of
+    C <- orth(C G) on G = R^T R from a fixed orthonormal start (start_rows), with
+    k = min(pca_rank, d - r, |P_del|) rows of which dependent ones are dropped; fast_err reports
+    the distance of the resulting Delta from the SVD's.
   The per-token variant is not stated precisely enough to restate and is absent.
 The cache-merging comparison system of App. E (select, route by key cosine, merge by
 attention mass) is merge_head; readings: the first maximum wins the routing, a key of
@@ -148,6 +152,7 @@ class Variant:
     no_scaling: bool = False         # component ablation "No Scaling"
     naive: bool = False              # component ablation "Naive Aggregation"
     attn_inject: bool = False        # alternative design "Attn-inject"
+    subspace_iters: int = 0          # > 0: the Gram subspace iteration of App. H with this many steps (the paper runs 3) instead of the SVD
 
 
 @dataclass
@@ -163,6 +168,8 @@ class HeadDiag:
     pc: float = 0.0              # projection cosine                 (App. K.2)
     revr: float = 0.0            # residual explained variance ratio (App. K.2)
     dr: float = 0.0              # demand ratio                      (App. K.2)
+    fast_cond: float = 1.0       # subspace iteration only: worst first-norm / remaining-norm ratio met by the orth steps (test tolerances)
+    fast_err: float = -1.0       # subspace iteration only: ||delta - delta_svd|| / ||delta_svd|| (App. H quotes ~1e-4)
     ivn: float = 0.0             # ||delta||                         (App. K.2)
     gap: float = np.inf          # sigma_k / sigma_{k+1} of R (subspace conditioning)
     keep_sigma_margin: float = np.inf   # min over sigma of |log10(sigma / rank threshold)|
@@ -265,11 +272,68 @@ def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int, variant: 
     w = A[dele] / (diag.a_del + EPS)                       # Eq. 4
     rbar = w @ R
     Delta = (rbar @ C.T) @ C                               # Eq. 5
+    if variant.subspace_iters > 0:
+        # App. H: the same Delta from C_{t+1} = orth(C_t G), G = R^T R, instead of the SVD; the exact one above is
+        # kept for the error report only
+        info = {}
+        Cf = subspace_iteration(R.T @ R, min(int(rank), d - diag.r_keep, dele.size), variant.subspace_iters, info)
+        diag.fast_cond = info.get("cond", 1.0)
+        Delta_f = (rbar @ Cf.T) @ Cf
+        nd = float(np.linalg.norm(Delta))
+        diag.fast_err = float(np.linalg.norm(Delta_f - Delta)) / nd if nd > 0 else 0.0
+        Delta = Delta_f
+        diag.k_used = Cf.shape[0]
+        tr = float(np.trace(R.T @ R))
+        diag.revr = float(sum(c @ (R.T @ (R @ c)) for c in Cf) / (tr + EPS))
+        if diag.k_used == 0:
+            diag.k_used, diag.revr = 0, 0.0
+            return V_keep.copy(), diag
     delta = Delta if variant.no_scaling else diag.a_del / (diag.a_keep + EPS) * Delta       # Eq. 6
     diag.delta = delta
     diag.ivn = float(np.linalg.norm(delta))
     diag.skipped = 0
     return inject(V_keep, A[idx], diag.a_keep, delta, variant), diag                         # Eq. 7
+
+
+# ----------------------------------------------------------------------------- App. H: Gram subspace iteration
+def start_rows(k: int, d: int) -> np.ndarray:
+    """C_0 of App. H, which only asks for orthonormal rows.  Reading: the first k rows of the orthonormal cosine
+    basis C_0[i, c] = sqrt(2/d) cos(pi/d (i + 1/2)(c + 1/2)) - fixed, dense, the same on every side."""
+    i = np.arange(k, dtype=np.float64)[:, None] + 0.5
+    c = np.arange(d, dtype=np.float64)[None, :] + 0.5
+    return np.sqrt(2.0 / d) * np.cos(np.pi / d * i * c)
+
+
+def orth_rows(Y: np.ndarray, info: dict = None) -> np.ndarray:
+    """Thin QR of Y^T written as Gram-Schmidt on the rows (two passes); a row that is left with at most 1e-5 of the
+    first row's norm depends on the rows before it and is dropped (reading: the QR of App. H is of full rank in the
+    paper's setting; this keeps the rule k <= rank R of Sec. 4.4)."""
+    rows = []
+    first = None
+    for y in Y:
+        v = y.astype(np.float64).copy()
+        for _ in range(2):
+            for q in rows:
+                v = v - (v @ q) * q
+        n = float(np.linalg.norm(v))
+        if first is None:
+            first = n
+        if first <= 0.0 or n <= 1e-5 * first:
+            continue
+        rows.append(v / n)
+        if info is not None:     # how far the kept rows were from dependent: largest ratio first norm / norm left
+            info["cond"] = max(info.get("cond", 1.0), first / n)
+    return np.array(rows).reshape(len(rows), Y.shape[1])
+
+
+def subspace_iteration(G: np.ndarray, k: int, iters: int, info: dict = None) -> np.ndarray:
+    """C_{t+1} = orth(C_t G), t = 0 .. iters - 1, from C_0 = start_rows (App. H).  Returns C [k' <= k, d]."""
+    C = start_rows(k, G.shape[0])
+    for _ in range(iters):
+        C = orth_rows(C @ G, info)
+        if C.shape[0] == 0:
+            break
+    return C
 
 
 # ----------------------------------------------------------------------------- one head, whole relay

@@ -17,7 +17,8 @@ _STATUS = {1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP
 
 DIAG_DTYPE = np.dtype([("n_keep", "<i4"), ("r_keep", "<i4"), ("k_used", "<i4"), ("skipped", "<i4"),
                        ("a_keep", "<f4"), ("a_del", "<f4"), ("rcr", "<f4"), ("ivn", "<f4"),
-                       ("pcr", "<f4"), ("pc", "<f4"), ("revr", "<f4"), ("dr", "<f4")])
+                       ("pcr", "<f4"), ("pc", "<f4"), ("revr", "<f4"), ("dr", "<f4"),
+                       ("fast_err", "<f4")])
 
 
 class ObfError(RuntimeError):
@@ -34,7 +35,8 @@ class _Shape(C.Structure):
 class _Variant(C.Structure):
     """obf_variant_t."""
     _fields_ = [("no_projection", C.c_int32), ("subspace", C.c_int32), ("evr_tau", C.c_float),
-                ("no_scaling", C.c_int32), ("naive_aggregation", C.c_int32), ("attn_inject", C.c_int32)]
+                ("no_scaling", C.c_int32), ("naive_aggregation", C.c_int32), ("attn_inject", C.c_int32),
+                ("subspace_iters", C.c_int32)]
 
 
 class _Window(C.Structure):
@@ -46,10 +48,11 @@ SUBSPACE = {"rank": 0, "all": 1, "evr": 2}
 
 
 def make_variant(no_projection=False, subspace="rank", evr_tau=0.35, no_scaling=False, naive_aggregation=False,
-                 attn_inject=False) -> _Variant:
+                 attn_inject=False, subspace_iters=0) -> _Variant:
     """obf_variant_t from keywords (subspace by its name or its number)."""
     code = SUBSPACE[subspace] if isinstance(subspace, str) else int(subspace)
-    return _Variant(int(no_projection), code, float(evr_tau), int(no_scaling), int(naive_aggregation), int(attn_inject))
+    return _Variant(int(no_projection), code, float(evr_tau), int(no_scaling), int(naive_aggregation), int(attn_inject),
+                    int(subspace_iters))
 
 
 def lib_path() -> str:

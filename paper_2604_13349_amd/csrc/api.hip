@@ -250,6 +250,11 @@ static obf_status_t make_variant(const obf_variant_t* v, Variant* out) {
     set_error("variant: evr_tau must lie in (0, 1]");
     return OBF_ERR_INVALID_ARG;
   }
+  if (v->subspace_iters < 0 || v->subspace_iters > 64) {
+    set_error("variant: subspace_iters must lie in [0, 64]");
+    return OBF_ERR_INVALID_ARG;
+  }
+  out->subspace_iters = v->subspace_iters;
   if (v->no_projection) out->flags |= VF_NO_PROJECTION;
   if (v->subspace == OBF_SUBSPACE_ALL) out->flags |= VF_SUBSPACE_ALL;
   if (v->subspace == OBF_SUBSPACE_EVR) { out->flags |= VF_SUBSPACE_EVR; out->evr_tau = v->evr_tau; }
@@ -257,6 +262,72 @@ static obf_status_t make_variant(const obf_variant_t* v, Variant* out) {
   if (v->naive_aggregation) out->flags |= VF_NAIVE;
   if (v->attn_inject) out->flags |= VF_ATTN_INJECT;
   return OBF_OK;
+}
+
+// The heads of one call: scores on `score_st`, everything after them on `st` (which waits for the scores when it is
+// another stream), side work of that part on `aux` (nullable).
+static obf_status_t compress_heads(int layerwise, Variant var, const Dims& mf, int sink,
+                                   const void* K, const void* V, const void* Qwin,
+                                   const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
+                                   void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
+                                   float* scores_out, float* delta_out, obf_diag_t* diag,
+                                   char* base, hipStream_t score_st, hipStream_t st, hipStream_t aux) {
+  // the eligible tokens (Sec. 4.3.2): a view behind the sink, same strides; selection, gather and back-fill run on it
+  Dims m = mf;
+  m.N = mf.N - sink;
+  m.scs = mf.N;
+  Dims mb = m;                                          // the units that own a budget: heads, or layers
+  if (layerwise) mb.heads = m.L;
+  Workspace w = carve(mf, max_budget, rank);
+  float* scores = scores_out ? scores_out : (float*)(base + w.scores);
+  double* row_lse = (double*)(base + w.row_lse);
+  OBF_TRY(run_score(mf, w, base, K, Qwin, scores, row_lse, score_st));
+  if (st != score_st) OBF_TRY(stream_after(st, score_st, EV_SCORED));
+  w.nstat = (m.N + kStatChunk - 1) / kStatChunk;        // statistics chunks of the view
+  K = (const char*)K + (size_t)sink * m.d * m.esize;
+  V = (const char*)V + (size_t)sink * m.d * m.esize;
+  scores += sink;
+  if (layerwise) {
+    OBF_TRY(launch_select_layerwise(m, w, base, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+  } else {
+    // selection and boundary refinement in one kernel (same decisions as the two stage calls)
+    OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+  }
+  // the gather also leaves the sums of squares of the retained V rows for the full-rank certificate
+  double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
+  // small budgets: the bases of the retained spans start now on a second stream, beside the gather
+  bool basis_started = false;
+  if (!var.skips_basis()) {
+    const obf_status_t bs = launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, aux, &basis_started);
+    if (bs != OBF_OK) {
+      if (basis_started) (void)stream_after(st, aux, EV_BASIS_JOIN);      // never leave the second stream un-joined
+      return bs;
+    }
+  }
+  // Large budgets: nothing downstream reads K_out, so the retained K rows are copied on the second stream once the
+  // V rows (which the certificate waits for) are through, beside the latency-bound per-head kernels.
+  bool k_beside = false;
+  obf_status_t rs = OBF_OK;
+  if (!basis_started && aux && aux != st && (size_t)max_budget * m.heads >= 65536) {
+    rs = launch_gather(m, nullptr, V, idx, n_keep, max_budget, nullptr, V_out, st, fro_part);
+    if (rs == OBF_OK) rs = stream_after(aux, st, EV_KROWS_FORK);
+    if (rs == OBF_OK) { k_beside = true; rs = launch_gather(m, K, nullptr, idx, n_keep, max_budget, K_out, nullptr, aux, nullptr); }
+  } else {
+    rs = launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part);
+  }
+  int32_t min_budget = budget;
+  if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < mb.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
+  // (launch_backfill joins the bases' stream itself, on every path; after an earlier error it is only called for that)
+  if (rs == OBF_OK || basis_started) {
+    const obf_status_t fs = (rs == OBF_OK)
+        ? launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, aux, fro_part,
+                          basis_started, min_budget, var)
+        : stream_after(st, aux, EV_BASIS_JOIN);
+    if (rs == OBF_OK) rs = fs;
+  }
+  if (k_beside) { const obf_status_t js = stream_after(st, aux, EV_KROWS_JOIN); if (rs == OBF_OK) rs = js; }
+  OBF_TRY(rs);
+  return launch_idx_offset(idx, (size_t)m.heads * max_budget, sink, st);   // back to the head's own token numbers
 }
 
 // Shared body of the fused calls; layerwise != 0 selects the per-layer retention rule.
@@ -278,67 +349,15 @@ static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_wi
     if (window->token_stride) mf.kvs = window->token_stride;
     sink = window->sink;
   }
-  // the eligible tokens (Sec. 4.3.2): a view behind the sink, same strides; selection, gather and back-fill run on it
-  Dims m = mf;
-  m.N = mf.N - sink;
-  m.scs = mf.N;
-  Dims mb = m;                                          // the units that own a budget: heads, or layers
-  if (layerwise) mb.heads = m.L;
+  Dims mb = mf;
+  mb.N = mf.N - sink;
+  if (layerwise) mb.heads = mf.L;
   OBF_TRY(check_budget(mb, budgets_host, budget, max_budget));
   Workspace w = carve(mf, max_budget, rank);
   OBF_TRY(check_ws(mf, w, ws, ws_bytes));
-  char* base = (char*)ws;
   hipStream_t st = (hipStream_t)stream;
-  float* scores = scores_out ? scores_out : (float*)(base + w.scores);
-  double* row_lse = (double*)(base + w.row_lse);
-  OBF_TRY(run_score(mf, w, base, K, Qwin, scores, row_lse, st));
-  w.nstat = (m.N + kStatChunk - 1) / kStatChunk;        // statistics chunks of the view
-  K = (const char*)K + (size_t)sink * m.d * m.esize;
-  V = (const char*)V + (size_t)sink * m.d * m.esize;
-  scores += sink;
-  if (layerwise) {
-    OBF_TRY(launch_select_layerwise(m, w, base, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
-  } else {
-    // selection and boundary refinement in one kernel (same decisions as the two stage calls)
-    OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
-  }
-  // the gather also leaves the sums of squares of the retained V rows for the full-rank certificate
-  double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
-  // small budgets: the bases of the retained spans start now on a second stream, beside the gather
-  hipStream_t aux = aux_stream(0);
-  bool basis_started = false;
-  if (!var.skips_basis()) {
-    const obf_status_t bs = launch_backfill_basis(m, w, base, V, scores, idx, n_keep, max_budget, rank, st, aux, &basis_started);
-    if (bs != OBF_OK) {
-      if (basis_started) (void)stream_after(st, aux, EV_BASIS_JOIN);      // never leave the second stream un-joined
-      return bs;
-    }
-  }
-  // Large budgets: nothing downstream reads K_out, so the retained K rows are copied on the second stream once the
-  // V rows (which the certificate waits for) are through, beside the latency-bound per-head kernels.
-  bool k_beside = false;
-  obf_status_t rs = OBF_OK;
-  if (!basis_started && aux && (size_t)max_budget * m.heads >= 65536) {
-    rs = launch_gather(m, nullptr, V, idx, n_keep, max_budget, nullptr, V_out, st, fro_part);
-    if (rs == OBF_OK) rs = stream_after(aux, st, EV_KROWS_FORK);
-    if (rs == OBF_OK) { k_beside = true; rs = launch_gather(m, K, nullptr, idx, n_keep, max_budget, K_out, nullptr, aux, nullptr); }
-  } else {
-    rs = launch_gather(m, K, V, idx, n_keep, max_budget, K_out, V_out, st, fro_part);
-  }
-  int32_t min_budget = budget;
-  if (budgets_host) { min_budget = budgets_host[0]; for (int h = 1; h < mb.heads; ++h) min_budget = budgets_host[h] < min_budget ? budgets_host[h] : min_budget; }
-  // (launch_backfill joins the bases' stream itself, on every path; after an earlier error it is only called for that)
-  if (rs == OBF_OK || basis_started) {
-    const obf_status_t fs = (rs == OBF_OK)
-        ? launch_backfill(m, w, base, V, scores, idx, n_keep, max_budget, rank, V_out, delta_out, diag, st, aux, fro_part,
-                          basis_started, min_budget, var)
-        : stream_after(st, aux, EV_BASIS_JOIN);
-    if (rs == OBF_OK) rs = fs;
-  }
-  if (k_beside) { const obf_status_t js = stream_after(st, aux, EV_KROWS_JOIN); if (rs == OBF_OK) rs = js; }
-  OBF_TRY(rs);
-  OBF_TRY(launch_idx_offset(idx, (size_t)m.heads * max_budget, sink, st));   // back to the head's own token numbers
-  return OBF_OK;
+  return compress_heads(layerwise, var, mf, sink, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
+                        scores_out, delta_out, diag, (char*)ws, st, st, aux_stream(0));
 }
 
 obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,

@@ -623,7 +623,8 @@ __device__ __forceinline__ bool jacobi_lead_rows_done(const float* T, int lt, in
 template <typename T, int NT>
 __device__ __forceinline__ void fn_emit(const int head, const int d, const int rank, HeadState st, const int skipped,
                                         const int k_used, const float rcr, const float ivn, const float pcr, const float pc,
-                                        const float revr, const float* uvec, HeadState* __restrict__ state,
+                                        const float revr, const float fast_err, const float* uvec,
+                                        HeadState* __restrict__ state,
                                         float* __restrict__ delta, float* __restrict__ delta_out, obf_diag_t* __restrict__ diag,
                                         T* __restrict__ V_out, const int max_budget, const float* __restrict__ scores,
                                         const int32_t* __restrict__ idx, const int vflags, const int scs) {
@@ -645,6 +646,7 @@ __device__ __forceinline__ void fn_emit(const int head, const int d, const int r
       dg.pcr = (rank > 0 && st.n_keep > 0 && st.n_del > 0 && st.r_keep >= d) ? 1.f : pcr;
       dg.pc = pc; dg.revr = revr;
       dg.dr = (float)(st.a_del / (st.a_keep + kEps));
+      dg.fast_err = fast_err;
       diag[head] = dg;
     }
   }
@@ -682,7 +684,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
                                                             const int32_t* __restrict__ idx, int vflags, float evr_tau,
                                                             int scs, float* __restrict__ rot /*nullable*/,
                                                             LeadJob* __restrict__ lead /*nullable: no leading-eigenpair kernel follows*/,
-                                                            int m_direct_max) {
+                                                            int m_direct_min, int m_direct_max) {
   extern __shared__ float sm[];
   const int head = blockIdx.x;
   const int ld = d + 1;
@@ -948,7 +950,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     // with a register budget of its own) instead of diagonalising all of T here.
     const int kq = min(rank, m);
     const bool direct = lead != nullptr && !negligible && !(vflags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR)) && kq >= 1 &&
-                        kq <= TE_MAXK && m >= FN_DIRECT_MIN && m <= m_direct_max;
+                        kq <= TE_MAXK && m >= m_direct_min && m <= m_direct_max;
     if (direct) {
       float* Tg = Gg;                                            // G itself is no longer needed
       for (int e = tid; e < m * m; e += FN_THREADS) { const int a = e / m; Tg[e] = M[a * lt + (e - a * m)]; }
@@ -1263,20 +1265,24 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       skipped = 0;
     }
   }
-  fn_emit<T, FN_THREADS>(head, d, rank, st, skipped, k_used, rcr, ivn, pcr, pc, revr, uvec, state, delta, delta_out, diag, V_out,
+  fn_emit<T, FN_THREADS>(head, d, rank, st, skipped, k_used, rcr, ivn, pcr, pc, revr, -1.f, uvec, state, delta, delta_out, diag, V_out,
                          max_budget, scores, idx, vflags, scs);
 }
 
 // ------------------------------------------------------------------------------------------------
 // The heads the finalisation handed over: leading eigenpairs of T by the direct route, then Eq. 4-7 as there.
+// iters > 0 selects the fast path of App. H instead: `iters` steps of C <- orth(C G) from a fixed orthonormal start,
+// carried out in complement coordinates (G = Z^T T Z, so a row c of C is followed as its coordinates c Z^T and
+// C G becomes Y T); the direct route then runs only when diagnostics are wanted, to report how far the fast path's
+// Delta is from it.
 template <typename T>
 __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, HeadState* __restrict__ state, float* __restrict__ mats,
                                                           float* __restrict__ delta, float* __restrict__ delta_out,
                                                           obf_diag_t* __restrict__ diag, T* __restrict__ V_out, int max_budget,
                                                           const float* __restrict__ scores, const int32_t* __restrict__ idx,
-                                                          int vflags, int scs, const LeadJob* __restrict__ lead) {
+                                                          int vflags, int scs, const LeadJob* __restrict__ lead, int iters) {
   extern __shared__ float sm[];
-  __shared__ float uvec[128], rbar[128], dvec[16], dcomp[128];
+  __shared__ float uvec[128], rbar[128], dvec[16], dcomp[128], dex[128];
   __shared__ int s_k;
   __shared__ float s_off;
   const int head = blockIdx.x;
@@ -1293,48 +1299,160 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
   float* work = sm + ((m * lt + 3) & ~3);                      // 16-byte aligned
   const int kq = min(rank, m);
   if (tid < d) uvec[tid] = delta[(size_t)head * d + tid];      // u
-  const float* th;
-  const float* Wk;
-  if (kq <= 4) tri_top_eigs<4>(Tg, m, Rf, lt, m, kq, work, &th, &Wk);
-  else tri_top_eigs<8>(Tg, m, Rf, lt, m, kq, work, &th, &Wk);
-  if (tid == 0) {
-    const float lmax = th[0];
-    const float srel = (float)max(st.n_del, d) * (float)kRankEps;
-    const float floor_rel = fmaxf(srel * srel, kEigFloor);
-    int rankR = 0;
-    for (int j = 0; j < kq; ++j) if (th[j] > lmax * floor_rel) ++rankR;      // descending: the count is a prefix
-    rankR = min(rankR, min(min(st.n_del, d - r), d));
-    s_k = min(rank, rankR);
-    double top = 0.0;
-    for (int j = 0; j < s_k; ++j) top += (double)th[j];
-    s_off = (float)(top / ((double)jb.res2 + 1e-12));
+  __syncthreads();
+  if (tid < m) {                                               // y = Z u (Eq. 4 in complement coordinates)
+    float sy = 0.f;
+    for (int c = 0; c < d; ++c) sy = fmaf(Zg[(size_t)tid * d + c], uvec[c], sy);
+    rbar[tid] = sy;
   }
-  __syncthreads();
-  const int k_used = s_k;
-  const float revr = (k_used > 0) ? s_off : 0.f;
-  int skipped = 1;
-  float ivn = 0.f;
-  __syncthreads();
-  if (k_used > 0) {
-    if (tid < m) {                                             // y = Z u (Eq. 4 in complement coordinates)
-      float sy = 0.f;
-      for (int c = 0; c < d; ++c) sy = fmaf(Zg[(size_t)tid * d + c], uvec[c], sy);
-      rbar[tid] = sy;
-    }
-    __syncthreads();
-    if (wave < k_used) {                                       // coefficient of eigenvector `wave` (Eq. 5)
-      float sc = (lane < m) ? rbar[lane] * Wk[wave * m + lane] : 0.f;
-      if (lane + 64 < m) sc = fmaf(rbar[lane + 64], Wk[wave * m + lane + 64], sc);
+  // Delta in complement coordinates (times a_del + eps) from kk orthonormal rows Cb [kk][m]: Eq. 5
+  auto project = [&](const float* Cb, const int kk) {
+    if (wave < kk) {
+      float sc = (lane < m) ? rbar[lane] * Cb[wave * m + lane] : 0.f;
+      if (lane + 64 < m) sc = fmaf(rbar[lane + 64], Cb[wave * m + lane + 64], sc);
       sc = te_wave_sum(sc);
       if (lane == 0) dvec[wave] = sc;
     }
     __syncthreads();
     if (tid < m) {
       float sd = 0.f;
-      for (int i = 0; i < k_used; ++i) sd = fmaf(dvec[i], Wk[i * m + tid], sd);
-      dcomp[tid] = sd;                                         // Delta in complement coordinates (times a_del + eps)
+      for (int i = 0; i < kk; ++i) sd = fmaf(dvec[i], Cb[i * m + tid], sd);
+      dcomp[tid] = sd;
     }
     __syncthreads();
+  };
+  int k_used = 0;
+  float revr = 0.f, fast_err = -1.f;
+  if (iters <= 0 || diag != nullptr) {
+    const float* th;
+    const float* Wk;
+    if (kq <= 4) tri_top_eigs<4>(Tg, m, Rf, lt, m, kq, work, &th, &Wk);
+    else tri_top_eigs<8>(Tg, m, Rf, lt, m, kq, work, &th, &Wk);
+    if (tid == 0) {
+      const float lmax = th[0];
+      const float srel = (float)max(st.n_del, d) * (float)kRankEps;
+      const float floor_rel = fmaxf(srel * srel, kEigFloor);
+      int rankR = 0;
+      for (int j = 0; j < kq; ++j) if (th[j] > lmax * floor_rel) ++rankR;      // descending: the count is a prefix
+      rankR = min(rankR, min(min(st.n_del, d - r), d));
+      s_k = min(rank, rankR);
+      double top = 0.0;
+      for (int j = 0; j < s_k; ++j) top += (double)th[j];
+      s_off = (float)(top / ((double)jb.res2 + 1e-12));
+    }
+    __syncthreads();
+    k_used = s_k;
+    revr = (k_used > 0) ? s_off : 0.f;
+    __syncthreads();
+    project(Wk, k_used);
+  }
+  if (iters > 0) {
+    if (diag != nullptr && tid < m) dex[tid] = dcomp[tid];     // the direct route's Delta, for the error report
+    __syncthreads();                                           // the direct route's LDS is free
+    float* Tl = sm;                                            // [m][lt]
+    float* Ya = work;                                          // [TE_MAXK][m] the current rows
+    float* Yb = Ya + TE_MAXK * m;                              // [TE_MAXK][m] their images under T
+    float* c0 = work + tri_work_floats(m, kq);                 // [k][d] start rows (the host sized the LDS for them)
+    const int k0 = min(min(rank, m), st.n_del);
+    for (int e = tid; e < m * m; e += TE_THREADS) { const int a = e / m; Tl[a * lt + (e - a * m)] = Tg[e]; }
+    // C_0: the first rows of the orthonormal cosine basis, C_0[i][c] = sqrt(2/d) cos(pi (i + 1/2)(c + 1/2) / d)
+    for (int e = tid; e < k0 * d; e += TE_THREADS) {
+      const int i = e / d, c = e - i * d;
+      c0[e] = sqrtf(2.f / (float)d) * cospif((float)((2 * i + 1) * (2 * c + 1)) / (float)(4 * d));
+    }
+    __syncthreads();
+    if (wave < k0) {
+      for (int t = lane; t < m; t += 64) {
+        float sy = 0.f;
+        for (int c = 0; c < d; ++c) sy = fmaf(c0[wave * d + c], Zg[(size_t)t * d + c], sy);
+        Ya[wave * m + t] = sy;
+      }
+    }
+    if (tid == 0) s_k = k0;
+    __syncthreads();
+    auto times_T = [&](const int kk) {                         // Yb = Ya T (T is symmetric: row s is read as column s)
+      if (wave < kk) {
+        float a0 = 0.f, a1 = 0.f;
+        for (int s = 0; s < m; ++s) {
+          const float ys = Ya[wave * m + s];
+          a0 = fmaf(ys, (lane < m) ? Tl[s * lt + lane] : 0.f, a0);
+          a1 = fmaf(ys, (lane + 64 < m) ? Tl[s * lt + lane + 64] : 0.f, a1);
+        }
+        if (lane < m) Yb[wave * m + lane] = a0;
+        if (lane + 64 < m) Yb[wave * m + lane + 64] = a1;
+      }
+      __syncthreads();
+    };
+    for (int it = 0; it < iters; ++it) {
+      const int kk = s_k;
+      __syncthreads();
+      if (kk == 0) break;                                      // uniform
+      times_T(kk);
+      if (wave == 0) {
+        // orth: Gram-Schmidt over the rows in order, two passes each; a row left with at most 1e-5 of the first row's
+        // norm depends on the rows before it and is dropped
+        int nk = 0;
+        float first = -1.f;
+        for (int i = 0; i < kk; ++i) {
+          float x0 = (lane < m) ? Yb[i * m + lane] : 0.f, x1 = (lane + 64 < m) ? Yb[i * m + lane + 64] : 0.f;
+          for (int pass = 0; pass < 2; ++pass) {
+            for (int j = 0; j < nk; ++j) {
+              const float y0 = (lane < m) ? Ya[j * m + lane] : 0.f, y1 = (lane + 64 < m) ? Ya[j * m + lane + 64] : 0.f;
+              const float dt = te_wave_sum(fmaf(x0, y0, x1 * y1));
+              x0 = fmaf(-dt, y0, x0); x1 = fmaf(-dt, y1, x1);
+            }
+          }
+          const float nn = sqrtf(te_wave_sum(fmaf(x0, x0, x1 * x1)));
+          if (first < 0.f) first = nn;
+          if (!(first > 0.f) || !(nn > 1e-5f * first)) continue;
+          const float rn = 1.f / nn;
+          if (lane < m) Ya[nk * m + lane] = x0 * rn;
+          if (lane + 64 < m) Ya[nk * m + lane + 64] = x1 * rn;
+          ++nk;
+        }
+        if (lane == 0) s_k = nk;
+      }
+      __syncthreads();
+    }
+    k_used = s_k;
+    __syncthreads();
+    revr = 0.f;
+    if (k_used > 0) {
+      times_T(k_used);                                         // explained share: sum_i c_i T c_i^T over the trace
+      if (wave < k_used) {
+        float sc = (lane < m) ? Ya[wave * m + lane] * Yb[wave * m + lane] : 0.f;
+        if (lane + 64 < m) sc = fmaf(Ya[wave * m + lane + 64], Yb[wave * m + lane + 64], sc);
+        sc = te_wave_sum(sc);
+        if (lane == 0) dvec[wave] = sc;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        double top = 0.0;
+        for (int i = 0; i < k_used; ++i) top += (double)dvec[i];
+        s_off = (float)(top / ((double)jb.res2 + 1e-12));
+      }
+      __syncthreads();
+      revr = s_off;
+      __syncthreads();
+      project(Ya, k_used);
+    } else {
+      if (tid < m) dcomp[tid] = 0.f;
+      __syncthreads();
+    }
+    if (diag != nullptr) {
+      if (tid == 0) {
+        double num = 0.0, den = 0.0;
+        for (int t = 0; t < m; ++t) { const double e = (double)dcomp[t] - dex[t]; num += e * e; den += (double)dex[t] * dex[t]; }
+        s_off = (den > 0.0) ? (float)sqrt(num / den) : 0.f;
+      }
+      __syncthreads();
+      fast_err = s_off;
+      __syncthreads();
+    }
+  }
+  int skipped = 1;
+  float ivn = 0.f;
+  if (k_used > 0) {
     float dl = 0.f;
     if (tid < d) {
       float s = 0.f;
@@ -1350,8 +1468,8 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
     ivn = s_off;
     skipped = 0;
   }
-  fn_emit<T, TE_THREADS>(head, d, rank, st, skipped, k_used, jb.rcr, ivn, jb.pcr, jb.pc, revr, uvec, state, delta, delta_out, diag, V_out,
-                         max_budget, scores, idx, vflags, scs);
+  fn_emit<T, TE_THREADS>(head, d, rank, st, skipped, k_used, jb.rcr, ivn, jb.pcr, jb.pc, revr, fast_err, uvec, state, delta, delta_out,
+                         diag, V_out, max_budget, scores, idx, vflags, scs);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1398,8 +1516,13 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     (void)hipFuncSetAttribute((const void*)k_bf_keep_gram_part<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     (void)hipFuncSetAttribute((const void*)k_bf_lead<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)sizeof(float) * (128 * 129 + 4 + tri_work_floats(128, TE_MAXK)));
+                              (int)sizeof(float) * (128 * 129 + 4 + tri_work_floats(128, TE_MAXK) + TE_MAXK * 128));
     attr_done = true;
+  }
+  if (var.subspace_iters > 0 && !(var.flags & VF_NAIVE) &&
+      (rank > TE_MAXK || (var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR)) || m.d > 128)) {
+    set_error("backfill: the subspace iteration takes the rank rule with pca_rank <= 8 and head_dim <= 128");
+    return OBF_ERR_UNSUPPORTED;
   }
   if (var.skips_basis()) {
     if (basis_started) { set_error("backfill: a basis was started for a variant without one"); return OBF_ERR_INVALID_ARG; }
@@ -1455,10 +1578,13 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     // Heads that only need a few leading eigenpairs of a wide enough complement go to k_bf_lead after the finalisation
     // (not under the Max-P / EVR rules, which need the whole spectrum).  Its LDS is sized for complements up to 3d/4 wide
     // (two workgroups per CU); without the projection every complement is all of R^d, and it is sized for that.
+    // The fast path of App. H lives in that kernel too and then takes every head that reaches Eq. 4.
+    const int iters = (var.flags & VF_NAIVE) ? 0 : var.subspace_iters;
     const bool lead_ok = rank > 0 && rank <= TE_MAXK && !(var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR | VF_NAIVE)) &&
-                         !(min_budget > m.d && m.N > m.d && !var.skips_basis());
+                         (iters > 0 || !(min_budget > m.d && m.N > m.d && !var.skips_basis()));
     LeadJob* lead = lead_ok ? (LeadJob*)(ws + w.lead_job) : (LeadJob*)nullptr;
-    const int m_direct_max = (var.flags & VF_NO_PROJECTION) ? m.d : 3 * m.d / 4;
+    const int m_direct_max = ((var.flags & VF_NO_PROJECTION) || iters > 0) ? m.d : 3 * m.d / 4;
+    const int m_direct_min = iters > 0 ? 1 : FN_DIRECT_MIN;
     // every budget above head_dim: heads that need the finalisation are rare (the certificate settles the others), so one
     // launch with the large LDS size serves both classes instead of two launches that mostly exit at once
     const bool single = min_budget > m.d && m.N > m.d && !var.skips_basis();
@@ -1468,15 +1594,16 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
                          var.flags, var.evr_tau, m.scs, (max_budget < m.d && rank > 0) ? (float*)(ws + w.rot) : (float*)nullptr,
-                         lead, m_direct_max);
+                         lead, m_direct_min, m_direct_max);
     }
     if (check_launch("backfill finalize") != OBF_OK) return OBF_ERR_HIP;
     if (lead) {
       const int kq = rank < TE_MAXK ? rank : TE_MAXK;
-      const size_t lds = sizeof(float) * ((size_t)m_direct_max * (m_direct_max | 1) + 4 + tri_work_floats(m_direct_max, kq));
+      const size_t lds = sizeof(float) * ((size_t)m_direct_max * (m_direct_max | 1) + 4 + tri_work_floats(m_direct_max, kq) +
+                                          (iters > 0 ? (size_t)kq * m.d : 0));
       hipLaunchKernelGGL(k_bf_lead<T>, dim3(m.heads), dim3(TE_THREADS), lds, st, m.d, rank, state, mats, delta, delta_out, diag,
                          (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, scores, idx, var.flags, m.scs,
-                         (const LeadJob*)lead);
+                         (const LeadJob*)lead, iters);
       if (check_launch("backfill leading eigenpairs") != OBF_OK) return OBF_ERR_HIP;
     }
   }

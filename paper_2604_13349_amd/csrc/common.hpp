@@ -227,6 +227,7 @@ enum : int { VF_NO_PROJECTION = 1, VF_SUBSPACE_ALL = 2, VF_SUBSPACE_EVR = 4, VF_
 struct Variant {
   int flags = 0;
   float evr_tau = 0.f;
+  int subspace_iters = 0;          // > 0: App. H's Gram subspace iteration with this many steps instead of the eigen-decomposition
   bool skips_basis() const { return (flags & (VF_NO_PROJECTION | VF_NAIVE)) != 0; }
 };
 
@@ -254,7 +255,7 @@ hipStream_t aux_stream(int which /*0 or 1*/);
 void set_single_stream(bool on);
 // Makes `waiter` wait for everything queued on `signaller` so far, through event `slot` of the calling thread's pool
 // (an event may be recorded again as soon as its wait has been enqueued).  Legal under stream capture.
-enum EventSlot { EV_SCORED = 0, EV_TAIL_JOIN, EV_BASIS_FORK, EV_BASIS_JOIN, EV_KROWS_FORK, EV_KROWS_JOIN, EV_COUNT };
+enum EventSlot { EV_SCORED = 0, EV_BASIS_FORK, EV_BASIS_JOIN, EV_KROWS_FORK, EV_KROWS_JOIN, EV_COUNT };
 obf_status_t stream_after(hipStream_t waiter, hipStream_t signaller, int slot);
 // Optional early start of the retained-span bases on `aux` (forked from st), for shapes where they do not depend on
 // the gather; *started is then passed on to launch_backfill as basis_started, which joins `aux` back.

@@ -43,7 +43,17 @@ class HeadReport:
         self.r_keep = None
 
 
+def _exact_gap_factor(diag) -> float:
+    if not np.isfinite(diag.gap) or diag.gap <= 0:
+        return 1.0
+    return max(1.0, 0.05 / max(1.0 - 1.0 / (diag.gap * diag.gap), 1e-12))
+
+
 def gap_factor(diag) -> float:
+    if diag.fast_err >= 0.0:
+        # the subspace iteration (App. H) does not resolve single directions: what amplifies rounding there is how close
+        # to dependent the rows were that its orth steps had to separate
+        return max(1.0, diag.fast_cond / 50.0)
     if not np.isfinite(diag.gap) or diag.gap <= 0:
         return 1.0
     ratio2 = 1.0 / (diag.gap * diag.gap)
@@ -116,6 +126,14 @@ def check_head(tag, ref: O.HeadResult, K_io, V_io, dtype, budget, gpu_idx, gpu_n
                 assert abs(float(gpu_diag["rcr"]) - dg.rcr) <= 2e-4, f"{tag}: RCR {gpu_diag['rcr']} vs {dg.rcr}"
                 assert abs(float(gpu_diag["pc"]) - abs(dg.pc)) <= 1e-3, f"{tag}: PC {gpu_diag['pc']} vs {dg.pc}"
                 assert abs(float(gpu_diag["revr"]) - dg.revr) <= 1e-3, f"{tag}: REVR {gpu_diag['revr']} vs {dg.revr}"
+                if "fast_err" in gpu_diag.dtype.names:
+                    fe = float(gpu_diag["fast_err"])
+                    if dg.fast_err < 0:
+                        assert fe == -1.0, f"{tag}: fast_err {fe} on a head without the fast path"
+                    else:
+                        # both directions' single-precision errors, relative to the exact Delta
+                        tol = 2e-3 * (gap_factor(dg) + _exact_gap_factor(dg)) * (1.0 + dg.fast_err)
+                        assert abs(fe - dg.fast_err) <= tol, f"{tag}: fast_err {fe} vs {dg.fast_err}"
                 assert abs(float(gpu_diag["ivn"]) - dg.ivn) <= 2e-3 * gap_factor(dg) * dg.ivn + 1e-6 * max(dg.ivn, 1e-3), (
                     f"{tag}: IVN {gpu_diag['ivn']} vs {dg.ivn}")
     if dg.skipped and not rep.ambiguous:
@@ -139,7 +157,11 @@ def check_head(tag, ref: O.HeadResult, K_io, V_io, dtype, budget, gpu_idx, gpu_n
         assert rep.v_err <= 1.0, f"{tag}: V_out off by {rep.v_err:.3f} x (half ulp + delta tolerance)"
         diff = gpu_V[:B] != ref.V_out
         frac = float(diff.mean())
-        assert frac < 5e-3, f"{tag}: {frac:.2%} of V_out elements round differently from the oracle"
+        # an element rounds differently when the two sums straddle a bf16 boundary: a share of about (error of delta) /
+        # (spacing of the sum) of them, which only matters where delta dominates the sum
+        derr = 0.0 if gpu_delta is None else float(np.abs(gpu_delta.astype(np.float64) - dg.delta).max())
+        crowd = float(np.mean(derr * inj / np.maximum(2.0 * half_ulp, 1e-300)))
+        assert frac < 5e-3 + 4.0 * crowd, f"{tag}: {frac:.2%} of V_out elements round differently from the oracle"
         if diff.any():
             step = np.abs(got - O.decode(ref.V_out, dtype))
             assert np.all(step <= 2.0 * half_ulp * (1.0 + 1e-6) + 2e-3 * g * inj * np.abs(dg.delta).max()), (

@@ -24,7 +24,7 @@ def _gpu_variant(v):
     """The binding's obf_variant_t for an oracle Variant (field by field, no arithmetic)."""
     from paper_2604_13349_amd import binding as B
     return B.make_variant(no_projection=v.no_projection, subspace=v.subspace, evr_tau=v.evr_tau, no_scaling=v.no_scaling,
-                          naive_aggregation=v.naive, attn_inject=v.attn_inject)
+                          naive_aggregation=v.naive, attn_inject=v.attn_inject, subspace_iters=v.subspace_iters)
 
 
 def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None, edit=None, variant=None):
@@ -243,6 +243,36 @@ def test_fused_equals_staged_and_is_deterministic(gpu):
     torch.cuda.synchronize()
     assert torch.equal(V_out.view(torch.int16), c["V_out"].view(torch.int16)) and torch.equal(delta, c["delta"])
     assert not torch.equal(c["V_out"].view(torch.int16), a["V_out"].view(torch.int16))
+
+
+def test_large_fused_call_equals_the_stage_calls(gpu):
+    """72 heads of 16K tokens (288 MiB of keys) with a budget below head_dim: the fused call is bit-identical to the stage
+    calls in sequence, and a head from each end of the cache matches the oracle."""
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    cfg = si.RelayConfig("large", 71, 9, 8, 4, 128, 16384, 8, 96, 4, "bf16", "structured", outlier_frac=0.01)   # 72 heads, 288 MiB of K
+    K, V, Q = si.make_cache(cfg, 1, threads=8)
+    Kd, Vd, Qd = (gpu.to_dev(x, cfg.dtype) for x in (K, V, Q))
+    a = Bd.compress_relay(Kd, Vd, Qd, budget=cfg.budget, rank=cfg.rank, want_scores=True, want_delta=True)
+    sh = Bd.shape_of(Kd, Qd)
+    scores, lse = Bd.score(Kd, Qd)
+    idx, n_keep = Bd.select_topk(sh, scores, budget=cfg.budget)
+    Bd.refine_boundary(Kd, Qd, scores, lse, idx, n_keep)
+    K_out, V_out = Bd.gather(sh, Kd, Vd, idx, n_keep)
+    delta = torch.empty((cfg.n_layers, cfg.n_kv_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+    Bd.backfill(sh, Vd, scores, idx, n_keep, cfg.rank, V_out, delta_out=delta)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, a["scores"]) and torch.equal(idx, a["idx"]) and torch.equal(n_keep, a["n_keep"])
+    assert torch.equal(K_out.view(torch.int16), a["K_out"].view(torch.int16))
+    assert torch.equal(V_out.view(torch.int16), a["V_out"].view(torch.int16)) and torch.equal(delta, a["delta"])
+    assert bool(delta.abs().sum() > 0)
+    # and against the oracle on a head of each chunk
+    out = {k: (gpu.to_host(a[k], cfg.dtype) if k in ("K_out", "V_out") else a[k].cpu().numpy()) for k in ("K_out", "V_out", "idx", "n_keep", "scores", "delta")}
+    for (l, h) in ((0, 3), (8, 7)):
+        ref = O.compress_head(K[l, h], V[l, h], Q[l, h * cfg.group:(h + 1) * cfg.group], cfg.budget, cfg.rank, cfg.dtype)
+        rep = parity.check_head(f"large[{l},{h}]", ref, K[l, h], V[l, h], cfg.dtype, cfg.budget, out["idx"][l, h], out["n_keep"][l, h],
+                                out["K_out"][l, h], out["V_out"][l, h], gpu_delta=out["delta"][l, h], gpu_scores=out["scores"][l, h])
+        assert rep.v_checked or rep.swaps or rep.ambiguous
 
 
 def test_select_stage_is_exact_on_given_scores(gpu):
@@ -501,6 +531,9 @@ VARIANTS = {
     "evr_0.35": O.Variant(subspace="evr", evr_tau=0.35),
     "evr_0.8": O.Variant(subspace="evr", evr_tau=0.8),
     "no_projection+no_scaling+attn_inject": O.Variant(no_projection=True, no_scaling=True, attn_inject=True),
+    "fast_path_3": O.Variant(subspace_iters=3),
+    "fast_path_1+no_projection": O.Variant(subspace_iters=1, no_projection=True),
+    "fast_path_6+attn_inject": O.Variant(subspace_iters=6, attn_inject=True),
 }
 
 
@@ -663,10 +696,12 @@ def test_append_message_matches_concatenation(gpu):
 
 
 # --------------------------------------------------------------------------- HIP graph capture of the fused call
-@pytest.mark.parametrize("name,layerwise,layers", [("2", False, 3), ("2s", False, 3), ("2s", True, 3), ("3", False, 8)])
+@pytest.mark.parametrize("name,layerwise,layers", [("2", False, 3), ("2s", False, 3), ("2s", True, 3), ("3", False, 8), ("3", False, 18),
+                                                   ("3s", False, 18)])
 def test_graph_capture_replays_match_eager(gpu, name, layerwise, layers):
     """The fused call is captured into a HIP graph (the small-budget shape forks the library's second stream for the
-    bases, the 8-layer config-3 shape for the copy of the retained K rows, and both join inside the capture) and replayed
+    bases, the config-3 shapes for the copy of the retained K rows, and both join inside the capture; the 18-layer shapes
+    hold 300 MB of keys) and replayed
     several times with eager calls and synchronisations in between; every replay must reproduce the eager outputs bit
     for bit."""
     import torch
@@ -743,6 +778,65 @@ def test_residual_rank_below_requested_rank(gpu, support, rank, k_want):
     assert all(r.v_checked and not r.ambiguous for r in reps)
     if k_want == 0:
         assert all(r.skipped == 1 for r in reps)
+
+
+@pytest.mark.parametrize("dtype,d,rank", [("bf16", 128, 4), ("f32", 64, 2), ("bf16", 128, 8)])
+def test_fast_path_is_close_to_the_svd_on_a_steep_residual_spectrum(gpu, dtype, d, rank):
+    """App. H quotes a relative error near 1e-4 for three steps: that needs a gap behind the k-th singular value of R.
+    Values = `rank` strong directions + weak noise give one; the device's fast path then matches the oracle's fast path to
+    the usual tolerance, both report the same small distance from the SVD route, and the plain call (the SVD route on
+    the device) lands that close to it too."""
+    cfg = si.RelayConfig("steep", 31, 1, 4, 2, d, 1500, 8, 24, rank, dtype, "structured")
+
+    def edit(K, V, Q):
+        r = np.random.default_rng(5)
+        L, H, N, _ = V.shape
+        dirs = np.linalg.qr(r.standard_normal((d, rank)))[0].T * np.linspace(6.0, 4.0, rank)[:, None]
+        X = r.standard_normal((L, H, N, rank)) @ dirs + 0.05 * r.standard_normal((L, H, N, d))
+        for h in range(H):
+            # the retained rows (decided by K and Q alone) carry only the noise, so the strong directions stay in R
+            keep = O.compress_head(K[0, h], V[0, h], Q[0, h * cfg.group:(h + 1) * cfg.group], cfg.budget, 0, dtype).idx
+            X[0, h, keep] = 0.05 * r.standard_normal((keep.size, d))
+        V[...] = O.round_to_io(X, dtype)
+
+    var = O.Variant(subspace_iters=3)
+    reps = _check_cfg(gpu, cfg, edit=edit, variant=var, expect_active=True)
+    assert all(r.v_checked for r in reps)
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    edit(K, V, Q)
+    fast = gpu.run_fused(cfg, K, V, Q, budgets=si.budgets(cfg, 0), rank=rank, variant=_gpu_variant(var))
+    plain = gpu.run_fused(cfg, K, V, Q, budgets=si.budgets(cfg, 0), rank=rank)
+    fe = fast["diag"]["fast_err"]
+    assert np.all((fe >= 0) & (fe < 5e-3)), fe
+    assert np.all(plain["diag"]["fast_err"] == -1.0)
+    for h in range(cfg.n_kv_heads):
+        a, b = fast["delta"][0, h].astype(np.float64), plain["delta"][0, h].astype(np.float64)
+        assert abs(np.linalg.norm(a - b) / np.linalg.norm(b) - fe[0, h]) < 1e-3
+
+
+@pytest.mark.parametrize("support,k_want", [(43, 3), (41, 1), (40, 0)])
+def test_fast_path_drops_dependent_rows_when_the_residual_rank_is_smaller(gpu, support, k_want):
+    """The iteration starts from min(pca_rank, d - r, |P_del|) rows; a residual of lower rank leaves fewer independent ones."""
+    cfg = si.RelayConfig("fast-rank", 22, 1, 4, 2, 128, 900, 8, 40, 8, "bf16", "structured")
+
+    def edit(K, V, Q):
+        V[..., support:] = 0
+
+    reps = _check_cfg(gpu, cfg, edit=edit, variant=O.Variant(subspace_iters=3))
+    assert all(r.v_checked and not r.ambiguous for r in reps)
+    assert all(r.skipped == (1 if k_want == 0 else 0) for r in reps)
+
+
+def test_fast_path_argument_errors(gpu):
+    cfg = si.shrink(si.CONFIGS["1s"], n_layers=1)
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    from paper_2604_13349_amd import binding as B
+    for bad, rank in ((B.make_variant(subspace_iters=-1), 2), (B.make_variant(subspace_iters=65), 2),
+                      (B.make_variant(subspace_iters=3), 9), (B.make_variant(subspace_iters=3, subspace="all"), 2)):
+        with pytest.raises(B.ObfError):
+            gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, rank=rank, variant=bad)
+    # the aggregate of the deleted rows has no subspace: the field is ignored there
+    gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, rank=2, variant=B.make_variant(subspace_iters=3, naive_aggregation=True))
 
 
 # --------------------------------------------------------------------------- cache-merging comparison system (App. E)

@@ -843,3 +843,45 @@ def test_row_quantisation_by_hand_roundtrip_bound_and_ratio():
         assert np.all(q[np.arange(50), x.argmin(axis=1)] <= 1) and np.all(q[np.arange(50), x.argmax(axis=1)] >= 2 ** bits - 2)
     # the sizes behind the paper's ratios at head_dim 128: 16-bit rows against codes plus two half-precision numbers
     assert abs(16 * 128 / (8 * 128 + 32) - 1.94) < 0.01 and abs(16 * 128 / (4 * 128 + 32) - 3.76) < 0.01
+
+
+# --------------------------------------------------------------------------- App. H: the literal Gram subspace iteration
+def test_subspace_iteration_start_is_orthonormal_and_converges_to_the_svd_subspace():
+    C0 = O.start_rows(8, 64)
+    assert np.allclose(C0 @ C0.T, np.eye(8), atol=1e-13)
+    # a residual with a clear gap after the third singular value: three steps already agree with the SVD to ~1e-4
+    # (the accuracy App. H quotes), many steps to rounding
+    r = rng(80)
+    U = np.linalg.qr(r.standard_normal((400, 64)))[0]; Vt = np.linalg.qr(r.standard_normal((64, 64)))[0]
+    sv = np.concatenate([[10.0, 9.0, 8.0], 0.4 * r.random(61)])
+    R = (U * sv) @ Vt
+    exact = Vt[:3]
+    P = exact.T @ exact
+    C3 = O.subspace_iteration(R.T @ R, 3, 3)
+    C60 = O.subspace_iteration(R.T @ R, 3, 60)
+    assert C3.shape == (3, 64) and np.allclose(C3 @ C3.T, np.eye(3), atol=1e-12)
+    assert np.linalg.norm(C3.T @ C3 - P) < 5e-4 and np.linalg.norm(C60.T @ C60 - P) < 1e-10
+    # one step from C_0 is literally orth(C_0 G): its rows span the rows of C_0 G
+    C1 = O.subspace_iteration(R.T @ R, 3, 1)
+    Y = O.start_rows(3, 64) @ (R.T @ R)
+    assert np.linalg.matrix_rank(np.vstack([C1, Y]), tol=1e-8 * np.linalg.norm(Y)) == 3
+    # dependent rows are dropped: a residual of rank 2 leaves two rows whatever k asks for
+    R2 = (U[:, :2] * np.array([3.0, 1.0])) @ Vt[:2]
+    assert O.subspace_iteration(R2.T @ R2, 5, 3).shape[0] == 2
+
+
+def test_fast_path_variant_reports_its_distance_from_the_svd_and_injects_its_own_direction():
+    r = rng(81)
+    V = r.standard_normal((300, 64)) * np.exp(-0.05 * np.arange(64)); A = r.random(300)
+    idx = O.select_topk(A, 20)
+    Vs, dg = O.backfill(V, A, idx, 2)
+    Vf, df = O.backfill(V, A, idx, 2, O.Variant(subspace_iters=3))
+    V50, d50 = O.backfill(V, A, idx, 2, O.Variant(subspace_iters=200))
+    assert df.k_used == 2 and df.skipped == 0 and dg.fast_err == -1.0
+    # the reported error is the relative distance of the two injected vectors (same scaling on both)
+    assert abs(df.fast_err - np.linalg.norm(df.delta - dg.delta) / np.linalg.norm(dg.delta)) < 1e-12
+    assert df.fast_err > 1e-8                      # three steps are an approximation on a flat spectrum ...
+    assert d50.fast_err < 1e-6 * max(1.0, 0.05 / max(1 - 1 / dg.gap ** 2, 1e-12)) + 1e-9   # ... many steps are not
+    assert np.allclose(Vf - V[idx], df.delta[None, :], atol=1e-13)
+    # still orthogonal to the retained values: every iterate stays in the row space of R
+    assert np.abs(V[idx] @ df.delta).max() < 1e-10 * np.linalg.norm(V[idx], axis=1).max() * np.linalg.norm(df.delta)
