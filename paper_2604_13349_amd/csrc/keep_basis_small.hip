@@ -3,12 +3,14 @@
 //
 // Per head (one workgroup of 16 x 32 threads), everything in double precision:
 //   C = A A^T, the n x n Gram matrix of the retained rows A (entries of A are exact in float; products and
-//       sums are taken in double), kept in LDS;
+//       sums are taken in double), kept in registers (thread (ty, tx) owns C[ty + 16a][tx + 32b]; a single-precision
+//       copy in LDS serves the power iteration only);
 //   sigma_max^2 = lambda_max(C) by power iteration (the rank rule's threshold);
 //   pivoted Gram-Schmidt on the rows of A, which live in registers (thread (ty, tx) owns A[ty + 16a][tx*CW ..]):
 //       the pivot is the row with the largest remaining squared norm, read off the diagonal of C; the
 //       projection coefficients of all rows onto the new direction are row j of C over sqrt(C[j][j]), so a
-//       step is one rank-1 update of C and one of A (no inner products, two barriers);
+//       step is one rank-1 update of C and one of A, both in registers (no inner products; the owners of row j publish
+//       it, two barriers);
 //   rows whose remaining norm is at or below sigma_max * max(n, d) * 2^-23 end the loop: r = number of steps.
 // Row s of the basis is written as soon as it is final.
 #include "common.hpp"
@@ -60,8 +62,9 @@ template <> struct RowLoad<float, 2> {
 
 struct KsShared {
   double red[KS_WAVES];
-  double xv[128], yp[4][128];        // power iteration: iterate, partial products
+  float xv[128], yp[4][128];         // power iteration: iterate, partial products
   double qrow[128];                  // row j of A at a step (unscaled)
+  double crow[128];                  // row j of C at a step (before the loop: the diagonal of C)
   uint32_t wkey[2][2];
 };
 
@@ -95,11 +98,12 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
   constexpr int NP = 16 * TI;
   const int tid = threadIdx.x, lane = tid & 63;
   const int ty = tid >> 5, tx = tid & 31;
-  float* stg = (float*)C;                                      // Gram staging [n][d + 1], before C is stored
+  float* stg = (float*)C;                                      // Gram staging [n][d + 1], before the copy of C is stored
+  float* Cf = (float*)C;                                       // [NP][NP]
 
   // ---- Gram matrix: thread (ty, tx) accumulates C[ty + 16a][tx + 32b]
+  double creg[TI][TJ];
   {
-    double creg[TI][TJ];
 #pragma unroll
     for (int a = 0; a < TI; ++a)
 #pragma unroll
@@ -131,39 +135,44 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
 #pragma unroll
       for (int b = 0; b < TJ; ++b) {
         const int i = ty + 16 * a, jj = tx + 32 * b;
-        C[i * NP + jj] = (i < n && jj < n) ? creg[a][b] : 0.0;   // rows past n were clamped reads
+        if (!(i < n && jj < n)) creg[a][b] = 0.0;                // rows past n were clamped reads
+        Cf[i * NP + jj] = (float)creg[a][b];                     // single-precision copy for the power iteration
+        if (i == jj) sh.crow[i] = creg[a][b];
       }
     __syncthreads();
   }
 
-  // ---- sigma_max^2 = lambda_max(C): power iteration.  Each quarter of the workgroup (a wave pair) takes every
-  // fourth row of C for all columns, the partial products meet in LDS.  The iterate is scaled by the first
-  // step's estimate only; the last step takes the true ratio.
-  if (tid < 128) sh.xv[tid] = (tid < n) ? 1.0 / sqrt((double)n) * (1.0 + 0.01 * (tid % 7)) : 0.0;
+  // ---- sigma_max^2 = lambda_max(C): power iteration in single precision (the estimate only sets the rank rule's
+  // threshold, where a percent is immaterial).  Each quarter of the workgroup (a wave pair) takes every fourth row of
+  // C for all columns, the partial products meet in LDS.  The iterate is scaled by the first step's estimate only;
+  // the last step takes the true ratio.
+  if (tid < 128) sh.xv[tid] = (tid < n) ? (float)(1.0 / sqrt((double)n)) * (1.f + 0.01f * (float)(tid % 7)) : 0.f;
   __syncthreads();
-  double lam = 0.0, scale = 1.0;
+  double lam = 0.0;
+  float scale = 1.f;
   const int prow = tid & 127, ppart = tid >> 7;                // ppart is uniform over a wave
   const bool pact = prow < NP;
-  const double* cp = C + ppart * NP + (pact ? prow : 0);       // C symmetric: column reads are row reads
-  const double* xp = sh.xv + ppart;
-  for (int it = 0; it < 24; ++it) {
-    double y0 = 0.0, y1 = 0.0;
+  const float* cp = Cf + ppart * NP + (pact ? prow : 0);       // C symmetric: column reads are row reads
+  const float* xp = sh.xv + ppart;
+  constexpr int kPowerIters = 12;
+  for (int it = 0; it < kPowerIters; ++it) {
+    float y0 = 0.f, y1 = 0.f;
 #pragma unroll
     for (int u = 0; u < NP / 4; u += 2) {
-      y0 = fma(cp[(4 * u) * NP], xp[4 * u], y0);
-      y1 = fma(cp[(4 * u + 4) * NP], xp[4 * u + 4], y1);
+      y0 = fmaf(cp[(4 * u) * NP], xp[4 * u], y0);
+      y1 = fmaf(cp[(4 * u + 4) * NP], xp[4 * u + 4], y1);
     }
-    sh.yp[ppart][prow] = pact ? y0 + y1 : 0.0;
+    sh.yp[ppart][prow] = pact ? y0 + y1 : 0.f;
     lds_barrier();
-    double y = 0.0;
+    float y = 0.f;
     if (tid < 128) y = (sh.yp[0][tid] + sh.yp[1][tid]) + (sh.yp[2][tid] + sh.yp[3][tid]);
-    if (it == 0 || it == 23) {
-      const double x0 = (tid < 128) ? sh.xv[tid] : 0.0;
-      const double n2 = ks_block_sum(y * y, sh.red);
-      const double d2 = ks_block_sum(x0 * x0, sh.red);
+    if (it == 0 || it == kPowerIters - 1) {
+      const float x0 = (tid < 128) ? sh.xv[tid] : 0.f;
+      const double n2 = ks_block_sum((double)y * y, sh.red);
+      const double d2 = ks_block_sum((double)x0 * x0, sh.red);
       lam = sqrt(n2 / fmax(d2, 1e-300));
       if (!(lam > 0.0)) break;
-      scale = 1.0 / lam;
+      scale = (float)(1.0 / lam);
     }
     if (tid < 128) sh.xv[tid] = y * scale;
     lds_barrier();
@@ -188,7 +197,7 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
   }
 
   // ---- pivoted Gram-Schmidt driven by C
-  double dg = (tid < n) ? C[tid * NP + tid] : -1.0;            // threads < n: remaining squared norm of row tid
+  double dg = (tid < n) ? sh.crow[tid] : -1.0;                 // threads < n: remaining squared norm of row tid
   bool used = false;
   // Pivot search key: the high word of the (positive) double, low 7 bits replaced by 127 - row, so that the
   // maximum over the keys is the largest remaining norm (to 13 mantissa bits), lowest row first among equals.
@@ -201,33 +210,27 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
   };
   publish(0);
   __syncthreads();
-  double* cown = C + ty * NP + tx;                             // element (a, b) of this thread: cown[16a * NP + 32b]
   int r = 0;
   for (int s = 0; s < n; ++s) {
     const uint32_t key = max(sh.wkey[s & 1][0], sh.wkey[s & 1][1]);
     if (key == 0u) break;
     const int j = 127 - (int)(key & 0x7Fu);
-    // row j of C (= column j) straight into registers: final since the last barrier, and every thread has its
-    // values before the next barrier lets anyone update them
-    const double* crow = C + j * NP;
-    const double xjj = crow[j];
-    double la[TI], lb[TJ];
-#pragma unroll
-    for (int a = 0; a < TI; ++a) la[a] = crow[ty + 16 * a];
-#pragma unroll
-    for (int b = 0; b < TJ; ++b) lb[b] = crow[tx + 32 * b];
-    const double lmine = crow[min(tid, NP - 1)];             // threads < 128: their own row's coefficient
-    if (ty == (j & 15)) {                                      // row j of A sits in these threads, register j / 16
+    if (ty == (j & 15)) {                                      // row j of C and of A sit in these threads, register j / 16
       double* qr = sh.qrow + tx * CW;
-#define KS_ROW(k) case k: if constexpr (k < TI) { _Pragma("unroll") for (int c = 0; c < CW; ++c) qr[c] = areg[k][c]; } break;
+      double* cr = sh.crow + tx;
+#define KS_ROW(k) case k: if constexpr (k < TI) { \
+        _Pragma("unroll") for (int c = 0; c < CW; ++c) qr[c] = areg[k][c]; \
+        _Pragma("unroll") for (int b = 0; b < TJ; ++b) cr[32 * b] = creg[k][b]; } break;
       switch (j >> 4) { KS_ROW(0) KS_ROW(1) KS_ROW(2) KS_ROW(3) KS_ROW(4) KS_ROW(5) KS_ROW(6) KS_ROW(7) default: break; }
 #undef KS_ROW
     }
-    if (!(xjj > thr2)) break;                                  // the largest remaining norm is at the rank threshold
     lds_barrier();
+    const double xjj = sh.crow[j];
+    if (!(xjj > thr2)) break;                                  // the largest remaining norm is at the rank threshold (uniform)
     const double inv = rsqrt(xjj);                             // 1 / remaining norm of row j
+    double la[TI];
 #pragma unroll
-    for (int a = 0; a < TI; ++a) la[a] *= inv;                 // <row, new direction>
+    for (int a = 0; a < TI; ++a) la[a] = sh.crow[ty + 16 * a] * inv;     // <row, new direction>
     {
       double q[CW];
 #pragma unroll
@@ -244,12 +247,12 @@ __device__ __forceinline__ int ks_head(const T* __restrict__ Vh, const int32_t* 
     }
 #pragma unroll
     for (int b = 0; b < TJ; ++b) {
-      const double lbs = lb[b] * inv;
+      const double lbs = sh.crow[tx + 32 * b] * inv;
 #pragma unroll
-      for (int a = 0; a < TI; ++a) cown[16 * a * NP + 32 * b] = fma(-la[a], lbs, cown[16 * a * NP + 32 * b]);
+      for (int a = 0; a < TI; ++a) creg[a][b] = fma(-la[a], lbs, creg[a][b]);
     }
     if (tid < 128) {
-      const double l = lmine * inv;
+      const double l = sh.crow[min(tid, NP - 1)] * inv;        // this thread's own row's coefficient
       if (tid == j) used = true;
       if (!used) dg -= l * l;
     }
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
   const int n = n_keep[head];
   if (n > d) return;                         // heads of the general kernel
   if ((n > 96) != BIG) return;               // n > 96: larger LDS buffer and register budget, a launch of its own
-  extern __shared__ double Cs[];             // [n][n] Gram matrix (first the staging area of its accumulation)
+  extern __shared__ double Cs[];             // staging area of the Gram accumulation, then the single-precision copy of C
   __shared__ KsShared sh;
   const int n_del = N - n;
   const float* sc = scores + (size_t)head * scs;
@@ -314,7 +317,7 @@ __global__ __launch_bounds__(KS_THREADS, BIG ? 2 : 4) void k_bf_keep_basis_small
 // dynamic LDS of a launch whose heads keep at most nmax rows: the padded Gram matrix or the row staging
 static size_t ks_smem(size_t nmax, int d) {
   const size_t np = (nmax + 31) / 32 * 32;
-  return max(np * np * sizeof(double), nmax * (size_t)(d + 1) * sizeof(float));
+  return max(np * np * sizeof(float), nmax * (size_t)(d + 1) * sizeof(float));
 }
 
 template <typename T>
@@ -324,7 +327,7 @@ static obf_status_t run_small(const Dims& m, const void* V, const float* scores,
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 129 * 4);
-    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
+    (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 129 * 4);
     attr_done = true;
   }
   const size_t nmax = (size_t)min(max_budget, m.d);

@@ -137,23 +137,27 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
   float* zz = lu + 6 * m * KS;        // [m][KS] iteration vectors
 
   // ---- 1. tridiagonalisation.  The matrix lives in registers: thread (a, g) = (tid % 128, tid / 128) owns row a, columns
-  // 32 g .. 32 g + 31 (absolute numbering throughout; vv and pv are zero in front of the trailing block, so no column
-  // needs masking).  Per reflector: wave 0 forms v from the column the owners published, all threads form their
-  // share of T v, the rows add the four shares, and the symmetric rank-two update stays in registers.
-  // LDS carries only vectors and receives the reflectors.
-  const int ra = tid & 127, rg = tid >> 7;
+  // g, g + 4, ..., g + 124 (absolute numbering throughout; vv and pv are zero in front of the trailing block, so no
+  // column needs masking).  The cyclic deal keeps the four column groups equally busy while the trailing block shrinks:
+  // a group's columns come in four blocks of eight, and a block that lies in front of the trailing block (or past the
+  // matrix) is skipped by the whole wave, as is a wave all of whose 64 rows do.  Per reflector: wave 0 forms v from the
+  // column the owners published, all threads form their share of T v, the rows add the four shares, and the symmetric
+  // rank-two update stays in registers.  LDS carries only vectors and receives the reflectors.
+  const int ra = tid & 127;
+  const int rg = __builtin_amdgcn_readfirstlane(tid >> 7);
+  const int row_lo = (wave & 1) * 64;                          // the rows of this wave: row_lo .. row_lo + 63
   float* part = (float*)cnt;                                   // [4][128] shares of T v (the counts come later)
   float* xcol = e2;                                            // the published column (e2 is free until the form is complete)
   float tr[TE_CPT];
 #pragma unroll
-  for (int c = 0; c < TE_CPT; ++c) tr[c] = (ra < m && rg * TE_CPT + c < m) ? Tsrc[(size_t)ra * ls + rg * TE_CPT + c] : 0.f;
+  for (int c = 0; c < TE_CPT; ++c) tr[c] = (ra < m && rg + 4 * c < m) ? Tsrc[(size_t)ra * ls + rg + 4 * c] : 0.f;
   if (tid < 128) { vv[tid] = 0.f; pv[tid] = 0.f; }
   if (rg == 0 && ra < m) xcol[ra] = tr[0];                     // column 0
   if (tid == 0) dv[0] = tr[0];
   __syncthreads();
   // A wave's threads share their 32 columns (rg is the same for all of them): each lane fetches one entry of v and of
   // p, and the others' entries arrive as scalar operands through lane reads - no LDS broadcast traffic.
-  const int cmine = rg * TE_CPT + (lane & 31);
+  const int cmine = rg + 4 * (lane & 31);
   auto lane_val = [](const float x, const int l) -> float {
     return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), l));
   };
@@ -177,14 +181,20 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
     }
     __syncthreads();
     const float beta = bet[j];
+    const bool rows_live = row_lo + 63 > j && row_lo < m;      // uniform over the wave
     if (beta != 0.f) {                                         // uniform
       const float vmine = vv[cmine];
-      {
+      if (rows_live) {
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;           // four independent chains
 #pragma unroll
-        for (int c = 0; c < TE_CPT; c += 4) {
-          s0 = fmaf(tr[c], lane_val(vmine, c), s0); s1 = fmaf(tr[c + 1], lane_val(vmine, c + 1), s1);
-          s2 = fmaf(tr[c + 2], lane_val(vmine, c + 2), s2); s3 = fmaf(tr[c + 3], lane_val(vmine, c + 3), s3);
+        for (int b = 0; b < TE_CPT / 8; ++b) {
+          if (rg + 32 * b + 28 > j && rg + 32 * b < m) {        // uniform: the block reaches into the trailing block
+#pragma unroll
+            for (int c = 8 * b; c < 8 * b + 8; c += 4) {
+              s0 = fmaf(tr[c], lane_val(vmine, c), s0); s1 = fmaf(tr[c + 1], lane_val(vmine, c + 1), s1);
+              s2 = fmaf(tr[c + 2], lane_val(vmine, c + 2), s2); s3 = fmaf(tr[c + 3], lane_val(vmine, c + 3), s3);
+            }
+          }
         }
         if (ra > j && ra < m) part[rg * 128 + ra] = (s0 + s1) + (s2 + s3);
       }
@@ -192,19 +202,24 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
       if (tid > j && tid < m) pv[tid] = beta * ((part[tid] + part[128 + tid]) + (part[256 + tid] + part[384 + tid]));
       __syncthreads();
       const float K = 0.5f * beta * te_wave_sum(fmaf(pv[lane], vv[lane], pv[lane + 64] * vv[lane + 64]));   // the same in every wave
-      {
+      if (rows_live) {
         // rows outside the trailing block (and past the matrix) have v = p = 0: their registers do not change
-        const float va = (ra < 128) ? vv[ra] : 0.f, wa = fmaf(-K, va, pv[ra]);
-        const float wmine = fmaf(-K, vmine, pv[cmine]);        // w = p - K v of this lane's column
+        const float va = vv[ra], wa = fmaf(-K, va, pv[ra]);
+        const float wmine = fmaf(-K, vmine, pv[cmine]);      // w = p - K v of this lane's column
 #pragma unroll
-        for (int c = 0; c < TE_CPT; ++c) tr[c] -= fmaf(va, lane_val(wmine, c), wa * lane_val(vmine, c));
+        for (int b = 0; b < TE_CPT / 8; ++b) {
+          if (rg + 32 * b + 28 > j && rg + 32 * b < m) {
+#pragma unroll
+            for (int c = 8 * b; c < 8 * b + 8; ++c) tr[c] -= fmaf(va, lane_val(wmine, c), wa * lane_val(vmine, c));
+          }
+        }
       }
     }
     // the owners publish column j + 1 of the updated block (and its diagonal entry, final from here on); the column's
     // position in the register array is the same for the whole workgroup: a jump, not a chain of selects
-    if (rg == (j + 1) / TE_CPT && ra > j && ra < m) {
+    if (rg == ((j + 1) & 3) && ra > j && ra < m) {
       float xv = 0.f;
-      switch ((j + 1) % TE_CPT) {
+      switch ((j + 1) >> 2) {
 #define OBF_TE_CASE(q) case q: xv = tr[q]; break;
         OBF_TE_CASE(0) OBF_TE_CASE(1) OBF_TE_CASE(2) OBF_TE_CASE(3) OBF_TE_CASE(4) OBF_TE_CASE(5) OBF_TE_CASE(6) OBF_TE_CASE(7)
         OBF_TE_CASE(8) OBF_TE_CASE(9) OBF_TE_CASE(10) OBF_TE_CASE(11) OBF_TE_CASE(12) OBF_TE_CASE(13) OBF_TE_CASE(14) OBF_TE_CASE(15)
@@ -220,16 +235,16 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
   }
   // the last 2 x 2 block: its diagonal entries and the sub-diagonal entry between them
   if (m >= 2) {
-    if (rg == (m - 1) / TE_CPT && ra == m - 1) {
+    if (rg == ((m - 1) & 3) && ra == m - 1) {
       float xv = 0.f;
 #pragma unroll
-      for (int c = 0; c < TE_CPT; ++c) if (c == (m - 1) % TE_CPT) xv = tr[c];
+      for (int c = 0; c < TE_CPT; ++c) if (c == (m - 1) >> 2) xv = tr[c];
       dv[m - 1] = xv;
     }
-    if (rg == (m - 2) / TE_CPT && ra == m - 1) {
+    if (rg == ((m - 2) & 3) && ra == m - 1) {
       float xv = 0.f;
 #pragma unroll
-      for (int c = 0; c < TE_CPT; ++c) if (c == (m - 2) % TE_CPT) xv = tr[c];
+      for (int c = 0; c < TE_CPT; ++c) if (c == (m - 2) >> 2) xv = tr[c];
       ev[m - 2] = xv;
     }
   }
