@@ -1,9 +1,13 @@
 // Statistics of the deleted value rows of a head, for the residual of Eq. 3 - 4, on the matrix cores (bf16 caches,
 // head_dim 128): per chunk of 1024 tokens the partial Gram V_del^T V_del (products of bf16 values are exact in fp32,
-// accumulation is fp32), the weighted sum  sum_j A_j v_j  and  sum_j ||v_j||^2  over the deleted rows of the chunk.
-// Retained rows enter as zeros.  Output format and meaning are those of the reference-precision kernel it replaces:
-// gram_part[head][chunk] = { G [d][d], u [d], ||V_del||^2, pad[3] }.
+// accumulation is fp32), the weighted sum  sum_j A_j v_j,  the plain sum  sum_j v_j  and  sum_j ||v_j||^2  over the
+// deleted rows of the chunk.  Retained rows enter as zeros.  The two sums are matrix products as well: the weight of
+// a token, split into three bf16 parts that add up to it exactly, and the constant one are four more "columns" next
+// to the 128 value columns, and the squared norm is the trace of the Gram matrix - the vector ALU only moves data.
+// Output format and meaning are those of the reference-precision kernel it replaces:
+// gram_part[head][chunk] = { G [d][d], u [d], s [d], ||V_del||^2, pad[3] }.
 #include "common.hpp"
+#include "wave_ops.hpp"
 
 namespace obf {
 
@@ -14,18 +18,21 @@ constexpr int DM_THREADS = 256;
 constexpr int DM_D = 128;
 constexpr int DM_TILE = 64;              // rows staged per iteration
 constexpr int DM_LDW = 136;              // staging stride in 32-bit words per token PAIR
+constexpr int DM_WQ = kStatChunk + 8;    // stride of the weight-part arrays (bf16 entries)
 static_assert(kStatChunk % DM_TILE == 0, "a chunk is a whole number of tiles");
 
-union DmFrag { uint32_t w[4]; dm_bf16x8 v; };
+union DmFrag { uint32_t w[4]; uint4 q; dm_bf16x8 v; };
 
-// The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb), three or two per wave; entry i of
-// lane l of a tile is G[rb*32 + (i/4)*8 + (l/32)*4 + (i%4)][cb*32 + l%32].
-__device__ __forceinline__ void dm_wave_tiles(int wave, int (&rb)[3], int (&cb)[3], int& nt) {
-  if (wave == 0) { rb[0] = 0; cb[0] = 0; rb[1] = 1; cb[1] = 1; rb[2] = 3; cb[2] = 2; nt = 3; }
-  else if (wave == 1) { rb[0] = 1; cb[0] = 0; rb[1] = 2; cb[1] = 1; rb[2] = 3; cb[2] = 3; nt = 3; }
-  else if (wave == 2) { rb[0] = 2; cb[0] = 0; rb[1] = 3; cb[1] = 1; rb[2] = 0; cb[2] = 0; nt = 2; }
-  else { rb[0] = 3; cb[0] = 0; rb[1] = 2; cb[1] = 2; rb[2] = 0; cb[2] = 0; nt = 2; }
-}
+// The lower triangle of G is ten 32x32 tiles, and the two sums take four more tile products (one per 32-column
+// block; such a tile has the weight parts in rows 0 - 2 and the plain sum in row 3, i.e. entries 0 - 3 of lanes
+// 0 - 31).  Wave w takes the k-steps 2h, 2h + 1 of every staged tile (h = w / 2: the two wave pairs split the tokens,
+// their accumulators meet in LDS at the end) and seven products per step, the same instruction stream in all waves:
+// with g[i] the operand fragment of column block (i + s) mod 4, s = w % 2,
+//   g0 g0, g2 g2, g1 g0, g3 g2, g2 g0   and   e g0, e g2          (e: the sums' operand)
+// which are the Gram tiles (0,0) (2,2) (1,0) (3,2) (2,0) for s = 0 and (1,1) (3,3) (2,1) (0,3) (3,1) for s = 1 - all ten,
+// (0,3) being the mirror image of (3,0) - and the sums of blocks s and s + 2.  Every wave reads each staged fragment
+// once.  Entry i of lane l of a product of row block R and column block C is G[R*32 + (i/4)*8 + (l/32)*4 + (i%4)][C*32 + l%32].
+constexpr int DM_NACC = 7;
 
 // One chunk of one head (the whole workgroup).
 __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const float* __restrict__ scores,
@@ -34,10 +41,10 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
                                          float* __restrict__ gram_part, int scs, int kvs, int head, int chunk) {
   const int n = n_keep ? n_keep[head] : state[head].n_keep;
   if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
-  __shared__ uint32_t stage[2][(DM_TILE / 2) * DM_LDW];
-  __shared__ float wt[kStatChunk];                     // score of a deleted token of the chunk, 0 for a retained one
+  __shared__ __attribute__((aligned(16))) uint32_t stage[2][(DM_TILE / 2) * DM_LDW];
+  __shared__ __attribute__((aligned(16))) uint16_t wq[4][DM_WQ];   // bf16: three parts of a deleted token's score, and one; 0 for a retained token
   __shared__ uint32_t kept[kStatChunk / 32];           // bitmap of the retained tokens of the chunk
-  __shared__ float red[8][DM_D + 1];                   // cross-thread reduction of u and ||.||^2
+  __shared__ float red[4];                             // the waves' shares of the trace
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 31, lh = lane >> 5;
@@ -48,6 +55,7 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
   const int rows = t1 - t0;
 
   // which tokens of the chunk are retained; weights
+  __syncthreads();                                     // a workgroup that takes several heads in turn: the last one is done
   for (int i = tid; i < kStatChunk / 32; i += DM_THREADS) kept[i] = 0u;
   __syncthreads();
   for (int i = tid; i < n; i += DM_THREADS) {
@@ -57,151 +65,158 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
   __syncthreads();
   for (int i = tid; i < kStatChunk; i += DM_THREADS) {
     const bool del = i < rows && !((kept[i >> 5] >> (i & 31)) & 1u);
-    wt[i] = del ? sc[t0 + i] : 0.f;
+    const float w = del ? sc[t0 + i] : 0.f;
+    // w = w1 + w2 + w3 with every part a bf16 value (truncations: each takes the next eight significant bits)
+    const uint32_t b1 = __float_as_uint(w) & 0xffff0000u;
+    const float r1 = w - __uint_as_float(b1);
+    const uint32_t b2 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(b2);
+    wq[0][i] = (uint16_t)(b1 >> 16);
+    wq[1][i] = (uint16_t)(b2 >> 16);
+    wq[2][i] = (uint16_t)(__float_as_uint(r2) >> 16);
+    wq[3][i] = del ? (uint16_t)0x3f80 : (uint16_t)0;
   }
   // (visible to everyone after the first barrier of the pipeline below)
 
-  int trb[3], tcb[3], nt;
-  dm_wave_tiles(wave, trb, tcb, nt);
-  dm_f32x16 acc[3];
+  dm_f32x16 acc[DM_NACC];
 #pragma unroll
-  for (int t = 0; t < 3; ++t)
+  for (int t = 0; t < DM_NACC; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-  float u4[4] = {0.f, 0.f, 0.f, 0.f};                  // weighted sums of this thread's four columns 4*(tid%32) ..
-  float s4[4] = {0.f, 0.f, 0.f, 0.f};                  // plain sums of the same columns (deleted rows only)
-  float nn = 0.f;                                      // squared norms of the deleted entries this thread has seen
 
-  uint2 pre[2][8];
-  auto fetch = [&](uint2 (&dst)[8], int r0) {
+  // A thread moves 16-byte pieces: piece `pc` (eight columns) of token r0 + 4 (wave + 4 q) + tl, q = 0 .. 3.  Lanes l and
+  // l + 32 hold the two tokens of a pair (tl = 0, 2 in the lower half of the wave, 1, 3 in the upper half).
+  const int pc = lane & 15, tl = ((lane >> 4) & 1) * 2 + lh;
+  uint4 pre[2][4];
+  auto fetch = [&](uint4 (&dst)[4], int r0) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int e = tid + q * DM_THREADS;
-      const int r = r0 + (e >> 5), c = e & 31;
-      dst[q] = make_uint2(0u, 0u);
-      if (r < rows) dst[q] = *(const uint2*)(Vh + (size_t)(t0 + r) * DM_D + c * 4);
+    for (int q = 0; q < 4; ++q) {
+      const int r = min(r0 + 4 * (wave + 4 * q) + tl, rows - 1);         // clamped: rows past the end are zeroed in put
+      dst[q] = *(const uint4*)(Vh + (size_t)(t0 + r) * DM_D + pc * 8);
     }
   };
   // Staging layout: word [p][j] holds column j of tokens 2p and 2p+1 (low / high half), so that an operand fragment
-  // (8 tokens of one column) is four 32-bit reads.  Lanes l and l+32 of a wave hold rows 2p and 2p+1 of the same four
-  // columns; the lower lane writes the words of the first two, the upper lane of the last two.  Retained rows are
-  // zeroed here, and the weighted sum and the squared norm are taken from the same registers.
-  auto put = [&](const uint2 (&src)[8], int buf, int r0) {
+  // (8 tokens of one column) is four 32-bit reads.  One lane swap per word pair brings the partner token's words for
+  // four of the eight columns to each lane (the lower lane ends up with the piece's columns 0 - 3 of both tokens, the
+  // upper lane with columns 4 - 7), two byte permutes interleave them.  Retained rows and rows past the end are zeroed.
+  auto put = [&](const uint4 (&src)[4], int buf, int r0) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int e = tid + q * DM_THREADS;
-      const int r = r0 + (e >> 5);
-      const int pr = e >> 6, c = e & 31;
-      const float w = (r < rows) ? wt[r] : 0.f;
-      const bool del = (r < rows) && !((kept[r >> 5] >> (r & 31)) & 1u);
-      const uint32_t sx = del ? src[q].x : 0u, sy = del ? src[q].y : 0u;
-      {
-        const float v0 = __uint_as_float(sx << 16), v1 = __uint_as_float(sx & 0xffff0000u);
-        const float v2 = __uint_as_float(sy << 16), v3 = __uint_as_float(sy & 0xffff0000u);
-        u4[0] = fmaf(w, v0, u4[0]); u4[1] = fmaf(w, v1, u4[1]); u4[2] = fmaf(w, v2, u4[2]); u4[3] = fmaf(w, v3, u4[3]);
-        s4[0] += v0; s4[1] += v1; s4[2] += v2; s4[3] += v3;
-        nn = fmaf(v0, v0, nn); nn = fmaf(v1, v1, nn); nn = fmaf(v2, v2, nn); nn = fmaf(v3, v3, nn);
-      }
-      const uint32_t mine = lh ? sy : sx;
-      const uint32_t other = lh ? sx : sy;
-      const auto sw = __builtin_amdgcn_permlane32_swap(other, other, false, false);
-      const uint32_t theirs = lh ? sw[0] : sw[1];
-      const uint32_t even = lh ? theirs : mine, odd = lh ? mine : theirs;     // rows 2p and 2p+1
-      uint2 wv;
-      wv.x = (even & 0xffffu) | (odd << 16);
-      wv.y = (even >> 16) | (odd & 0xffff0000u);
-      *(uint2*)(&stage[buf][pr * DM_LDW + c * 4 + lh * 2]) = wv;
+    for (int q = 0; q < 4; ++q) {
+      const int rl = 4 * (wave + 4 * q) + tl;                            // row within the tile
+      const int r = r0 + rl;
+      const uint32_t kbit = (kept[(r >> 5) & (kStatChunk / 32 - 1)] >> (r & 31)) & 1u;
+      const uint32_t mk = (r < rows ? 1u : 0u) & (kbit ^ 1u) ? 0xffffffffu : 0u;
+      const auto s0 = __builtin_amdgcn_permlane32_swap(src[q].x & mk, src[q].z & mk, false, false);   // [0]: even token, [1]: odd token
+      const auto s1 = __builtin_amdgcn_permlane32_swap(src[q].y & mk, src[q].w & mk, false, false);
+      uint4 wv;
+      wv.x = __builtin_amdgcn_perm(s0[1], s0[0], 0x05040100u);
+      wv.y = __builtin_amdgcn_perm(s0[1], s0[0], 0x07060302u);
+      wv.z = __builtin_amdgcn_perm(s1[1], s1[0], 0x05040100u);
+      wv.w = __builtin_amdgcn_perm(s1[1], s1[0], 0x07060302u);
+      *(uint4*)(&stage[buf][(rl >> 1) * DM_LDW + pc * 8 + lh * 4]) = wv;
     }
   };
-  auto compute = [&](const uint32_t* st) {
+  const int ws = wave & 1, wh = wave >> 1;
+  const int og0 = ws * 32, og1 = ((1 + ws) & 3) * 32, og2 = (2 + ws) * 32, og3 = ((3 + ws) & 3) * 32;   // operand column blocks (words)
+  auto compute = [&](const uint32_t* st, int r0) {
 #pragma unroll
-    for (int ks = 0; ks < DM_TILE / 16; ++ks) {
-      DmFrag f[4];
+    for (int kk = 0; kk < 2; ++kk) {
+      const int ks = 2 * wh + kk;
+      const uint32_t* p = st + (ks * 8 + lh * 4) * DM_LDW + lr;
+      DmFrag g0, g1, g2, g3, e;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t* p = st + (ks * 8 + lh * 4) * DM_LDW + c * 32 + lr;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[c].w[i] = p[i * DM_LDW];
+      for (int i = 0; i < 4; ++i) {
+        g0.w[i] = p[i * DM_LDW + og0]; g1.w[i] = p[i * DM_LDW + og1];
+        g2.w[i] = p[i * DM_LDW + og2]; g3.w[i] = p[i * DM_LDW + og3];
       }
-      if (wave == 0) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[1].v, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[2].v, acc[2], 0, 0, 0);
-      } else if (wave == 1) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[1].v, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[3].v, acc[2], 0, 0, 0);
-      } else if (wave == 2) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[1].v, acc[1], 0, 0, 0);
-      } else {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[2].v, acc[1], 0, 0, 0);
-      }
+      // the sums' operand: row lr < 4 of it holds eight tokens' entries of weight part lr (or of the ones); the address is
+      // clamped so that every lane loads, the other rows are cleared
+      e.q = *(const uint4*)(&wq[lr & 3][r0 + ks * 16 + lh * 8]);
+      if (lr >= 4) e.q = make_uint4(0u, 0u, 0u, 0u);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g0.v, g0.v, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g2.v, g2.v, acc[1], 0, 0, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g1.v, g0.v, acc[2], 0, 0, 0);
+      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g3.v, g2.v, acc[3], 0, 0, 0);
+      acc[4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g2.v, g0.v, acc[4], 0, 0, 0);
+      acc[5] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.v, g0.v, acc[5], 0, 0, 0);
+      acc[6] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.v, g2.v, acc[6], 0, 0, 0);
     }
   };
   fetch(pre[0], 0);
   fetch(pre[1], DM_TILE);
-  __syncthreads();                       // wt and kept complete
+  __syncthreads();                       // wq and kept complete
   put(pre[0], 0, 0);
   fetch(pre[0], 2 * DM_TILE);
-  __syncthreads();
+  lds_barrier();
+#pragma unroll 1
   for (int r0 = 0; r0 < rows; r0 += 2 * DM_TILE) {
     // even tile: in stage[0]; pre[1] holds tile r0+64, pre[0] holds tile r0+128
-    compute(stage[0]);
+    compute(stage[0], r0);
     put(pre[1], 1, r0 + DM_TILE);
     fetch(pre[1], r0 + 3 * DM_TILE);
-    __syncthreads();
-    if (r0 + DM_TILE < rows) compute(stage[1]);
+    lds_barrier();                      // LDS only: the loads just issued stay in flight across the barrier
+    if (r0 + DM_TILE < rows) compute(stage[1], r0 + DM_TILE);
     put(pre[0], 0, r0 + 2 * DM_TILE);
     fetch(pre[0], r0 + 4 * DM_TILE);
-    __syncthreads();
+    lds_barrier();
   }
 
-  // ---- results: the 32 x 32 tiles of the Gram matrix on and below the diagonal (row-major in the d x d partial, so
-  // the stores are row segments; the tiles above the diagonal are left unwritten, the reader mirrors)
-  float* out = gram_part + ((size_t)head * nstat + chunk) * gram_stride(DM_D);
+  // ---- the two wave pairs' accumulators meet: waves 2 and 3 hand theirs over through LDS (the staging buffers are free
+  // after the loop's last barrier), four products first, then three; waves 0 and 1 add them to their own
+  {
+    float* xch = (float*)&stage[0][0];                 // [2 (s)][4][16][64] floats = 32 KB
 #pragma unroll
-  for (int t = 0; t < 3; ++t) {
-    if (t < nt) {
+    for (int round = 0; round < 2; ++round) {
+      const int tb = round * 4, tn = round ? 3 : 4;
+      if (round) __syncthreads();
+      if (wh == 1) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = trb[t] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3), col = tcb[t] * 32 + lr;
-        out[row * DM_D + col] = acc[t][i];
+        for (int t = 0; t < 4; ++t)
+          if (t < tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) xch[((ws * 4 + t) * 16 + i) * 64 + lane] = acc[tb + t][i];
+      }
+      __syncthreads();
+      if (wh == 0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          if (t < tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tb + t][i] += xch[((ws * 4 + t) * 16 + i) * 64 + lane];
       }
     }
   }
-  // ---- weighted sum and squared norm: the eight threads with the same tid % 32 own the same four columns
-  {
-    const int c = tid & 31, part = tid >> 5;
+  // ---- results (waves 0 and 1): the 32 x 32 tiles of the Gram matrix on and below the diagonal (row-major in the
+  // d x d partial; the tiles above the diagonal are left unwritten, the reader mirrors; the one product that came
+  // out as an upper tile is stored as its mirror image)
+  float* out = gram_part + ((size_t)head * nstat + chunk) * gram_stride(DM_D);
+  float tr = 0.f;                                      // this lane's share of the trace (the squared norms)
+  if (wh == 0) {
+    const int trb[5] = {ws, 2 + ws, 1 + ws, (3 + ws) & 3, 2 + ws}, tcb[5] = {ws, 2 + ws, ws, 2 + ws, ws};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) red[part][c * 4 + k] = u4[k];
-    // squared norms: wave-level sum first (fixed order), then the four waves
-    float s = nn;
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-    if (lane == 0) red[wave][DM_D] = s;
+    for (int t = 0; t < 5; ++t) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int rw = (i >> 2) * 8 + lh * 4 + (i & 3);
+        const int gr = trb[t] * 32 + rw, gc = tcb[t] * 32 + lr;
+        if (trb[t] >= tcb[t]) out[gr * DM_D + gc] = acc[t][i]; else out[gc * DM_D + gr] = acc[t][i];
+        if (t < 2 && rw == lr) tr += acc[t][i];
+      }
+    }
+    // ---- weighted sum and plain sum: rows 0 - 3 of the sums tiles
+    if (lane < 32) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int col = (2 * t + ws) * 32 + lane;
+        out[DM_D * DM_D + col] = (acc[5 + t][0] + acc[5 + t][1]) + acc[5 + t][2];
+        out[DM_D * DM_D + DM_D + col] = acc[5 + t][3];
+      }
+    }
   }
+  for (int off = 32; off > 0; off >>= 1) tr += __shfl_xor(tr, off);
+  if (lane == 0) red[wave] = tr;
   __syncthreads();
-  if (tid < DM_D) {
-    float s = 0.f;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) s += red[p][tid];
-    out[DM_D * DM_D + tid] = s;
-  }
-  if (tid == 0) out[DM_D * DM_D + 2 * DM_D] = (red[0][DM_D] + red[1][DM_D]) + (red[2][DM_D] + red[3][DM_D]);
-  __syncthreads();
-  {
-    const int c = tid & 31, part = tid >> 5;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) red[part][c * 4 + k] = s4[k];
-  }
-  __syncthreads();
-  if (tid < DM_D) {
-    float s = 0.f;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) s += red[p][tid];
-    out[DM_D * DM_D + DM_D + tid] = s;
-  }
+  if (tid == 0) out[DM_D * DM_D + 2 * DM_D] = red[0] + red[1];
 }
 
 // The active head whose number (in head order) is `target`, or -1; every thread gets it.  s_i has 5 entries.
