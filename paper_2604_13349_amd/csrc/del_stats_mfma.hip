@@ -14,7 +14,8 @@ namespace obf {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 dm_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float dm_f32x16;
 
-constexpr int DM_THREADS = 256;
+constexpr int DM_THREADS = 512;
+constexpr int DM_WAVES = DM_THREADS / 64;
 constexpr int DM_D = 128;
 constexpr int DM_TILE = 64;              // rows staged per iteration
 constexpr int DM_LDW = 136;              // staging stride in 32-bit words per token PAIR
@@ -23,16 +24,25 @@ static_assert(kStatChunk % DM_TILE == 0, "a chunk is a whole number of tiles");
 
 union DmFrag { uint32_t w[4]; uint4 q; dm_bf16x8 v; };
 
-// The lower triangle of G is ten 32x32 tiles, and the two sums take four more tile products (one per 32-column
-// block; such a tile has the weight parts in rows 0 - 2 and the plain sum in row 3, i.e. entries 0 - 3 of lanes
-// 0 - 31).  Wave w takes the k-steps 2h, 2h + 1 of every staged tile (h = w / 2: the two wave pairs split the tokens,
-// their accumulators meet in LDS at the end) and seven products per step, the same instruction stream in all waves:
-// with g[i] the operand fragment of column block (i + s) mod 4, s = w % 2,
-//   g0 g0, g2 g2, g1 g0, g3 g2, g2 g0   and   e g0, e g2          (e: the sums' operand)
-// which are the Gram tiles (0,0) (2,2) (1,0) (3,2) (2,0) for s = 0 and (1,1) (3,3) (2,1) (0,3) (3,1) for s = 1 - all ten,
-// (0,3) being the mirror image of (3,0) - and the sums of blocks s and s + 2.  Every wave reads each staged fragment
-// once.  Entry i of lane l of a product of row block R and column block C is G[R*32 + (i/4)*8 + (l/32)*4 + (i%4)][C*32 + l%32].
-constexpr int DM_NACC = 7;
+// The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb), and the two sums take four more tile
+// products (one per 32-column block; such a tile has the weight parts in rows 0 - 2 and the plain sum in row 3, i.e.
+// entries 0 - 3 of lanes 0 - 31).  Entry i of lane l of a tile is G[rb*32 + (i/4)*8 + (l/32)*4 + (i%4)][cb*32 + l%32].
+// Eight waves, one instruction stream: wave w takes the k-steps 2h, 2h + 1 of every staged tile (h = w / 4: the two
+// halves of the workgroup split the tokens, their accumulators meet in LDS at the end) and, with j = w % 4, four
+// products per step, the operands picked by LDS address, not by branch:
+//   tile (j, 0),  tiles (a, b) and (c, b),  sums of columns 32 j .. 32 j + 31
+//   j = 0: (1,1) (2,1)    j = 1: (3,1)    j = 2: (2,2) (3,2)    j = 3: (3,3)
+// (j = 1 and j = 3 have one tile less: their third product repeats the second and is dropped).
+struct DmTiles { int a, c, b, third; };
+__device__ __forceinline__ DmTiles dm_wave_tiles(int j) {
+  DmTiles t;
+  t.a = (j == 0) ? 1 : (j == 2) ? 2 : 3;
+  t.c = (j == 0) ? 2 : 3;
+  t.b = (j < 2) ? 1 : j;
+  t.third = (j == 0 || j == 2) ? 1 : 0;
+  return t;
+}
+constexpr int DM_NACC = 4;
 
 // One chunk of one head (the whole workgroup).
 __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const float* __restrict__ scores,
@@ -44,7 +54,7 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
   __shared__ __attribute__((aligned(16))) uint32_t stage[2][(DM_TILE / 2) * DM_LDW];
   __shared__ __attribute__((aligned(16))) uint16_t wq[4][DM_WQ];   // bf16: three parts of a deleted token's score, and one; 0 for a retained token
   __shared__ uint32_t kept[kStatChunk / 32];           // bitmap of the retained tokens of the chunk
-  __shared__ float red[4];                             // the waves' shares of the trace
+  __shared__ float red[DM_WAVES];                      // the waves' shares of the trace
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 31, lh = lane >> 5;
@@ -84,14 +94,14 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-  // A thread moves 16-byte pieces: piece `pc` (eight columns) of token r0 + 4 (wave + 4 q) + tl, q = 0 .. 3.  Lanes l and
+  // A thread moves 16-byte pieces: piece `pc` (eight columns) of token r0 + 4 (wave + 8 q) + tl, q = 0, 1.  Lanes l and
   // l + 32 hold the two tokens of a pair (tl = 0, 2 in the lower half of the wave, 1, 3 in the upper half).
   const int pc = lane & 15, tl = ((lane >> 4) & 1) * 2 + lh;
-  uint4 pre[2][4];
-  auto fetch = [&](uint4 (&dst)[4], int r0) {
+  uint4 pre[2][2];
+  auto fetch = [&](uint4 (&dst)[2], int r0) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = min(r0 + 4 * (wave + 4 * q) + tl, rows - 1);         // clamped: rows past the end are zeroed in put
+    for (int q = 0; q < 2; ++q) {
+      const int r = min(r0 + 4 * (wave + 8 * q) + tl, rows - 1);         // clamped: rows past the end are zeroed in put
       dst[q] = *(const uint4*)(Vh + (size_t)(t0 + r) * DM_D + pc * 8);
     }
   };
@@ -99,10 +109,10 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
   // (8 tokens of one column) is four 32-bit reads.  One lane swap per word pair brings the partner token's words for
   // four of the eight columns to each lane (the lower lane ends up with the piece's columns 0 - 3 of both tokens, the
   // upper lane with columns 4 - 7), two byte permutes interleave them.  Retained rows and rows past the end are zeroed.
-  auto put = [&](const uint4 (&src)[4], int buf, int r0) {
+  auto put = [&](const uint4 (&src)[2], int buf, int r0) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int rl = 4 * (wave + 4 * q) + tl;                            // row within the tile
+    for (int q = 0; q < 2; ++q) {
+      const int rl = 4 * (wave + 8 * q) + tl;                            // row within the tile
       const int r = r0 + rl;
       const uint32_t kbit = (kept[(r >> 5) & (kStatChunk / 32 - 1)] >> (r & 31)) & 1u;
       const uint32_t mk = (r < rows ? 1u : 0u) & (kbit ^ 1u) ? 0xffffffffu : 0u;
@@ -116,30 +126,28 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
       *(uint4*)(&stage[buf][(rl >> 1) * DM_LDW + pc * 8 + lh * 4]) = wv;
     }
   };
-  const int ws = wave & 1, wh = wave >> 1;
-  const int og0 = ws * 32, og1 = ((1 + ws) & 3) * 32, og2 = (2 + ws) * 32, og3 = ((3 + ws) & 3) * 32;   // operand column blocks (words)
+  const int wj = wave & 3, wh = wave >> 2;
+  const DmTiles tl3 = dm_wave_tiles(wj);
+  const int oW = wj * 32, oA = tl3.a * 32, oB = tl3.b * 32, oC = tl3.c * 32;      // operand column blocks (words)
   auto compute = [&](const uint32_t* st, int r0) {
-#pragma unroll
+#pragma unroll 1
     for (int kk = 0; kk < 2; ++kk) {
       const int ks = 2 * wh + kk;
       const uint32_t* p = st + (ks * 8 + lh * 4) * DM_LDW + lr;
-      DmFrag g0, g1, g2, g3, e;
+      DmFrag fW, f0, fA, fB, fC, e;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        g0.w[i] = p[i * DM_LDW + og0]; g1.w[i] = p[i * DM_LDW + og1];
-        g2.w[i] = p[i * DM_LDW + og2]; g3.w[i] = p[i * DM_LDW + og3];
+        fW.w[i] = p[i * DM_LDW + oW]; f0.w[i] = p[i * DM_LDW];
+        fA.w[i] = p[i * DM_LDW + oA]; fB.w[i] = p[i * DM_LDW + oB]; fC.w[i] = p[i * DM_LDW + oC];
       }
       // the sums' operand: row lr < 4 of it holds eight tokens' entries of weight part lr (or of the ones); the address is
       // clamped so that every lane loads, the other rows are cleared
       e.q = *(const uint4*)(&wq[lr & 3][r0 + ks * 16 + lh * 8]);
       if (lr >= 4) e.q = make_uint4(0u, 0u, 0u, 0u);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g0.v, g0.v, acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g2.v, g2.v, acc[1], 0, 0, 0);
-      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g1.v, g0.v, acc[2], 0, 0, 0);
-      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g3.v, g2.v, acc[3], 0, 0, 0);
-      acc[4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g2.v, g0.v, acc[4], 0, 0, 0);
-      acc[5] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.v, g0.v, acc[5], 0, 0, 0);
-      acc[6] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.v, g2.v, acc[6], 0, 0, 0);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fW.v, f0.v, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fA.v, fB.v, acc[1], 0, 0, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fC.v, fB.v, acc[2], 0, 0, 0);
+      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.v, fW.v, acc[3], 0, 0, 0);
     }
   };
   fetch(pre[0], 0);
@@ -161,69 +169,63 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
     lds_barrier();
   }
 
-  // ---- the two wave pairs' accumulators meet: waves 2 and 3 hand theirs over through LDS (the staging buffers are free
-  // after the loop's last barrier), four products first, then three; waves 0 and 1 add them to their own
+  // ---- the two halves' accumulators meet: waves 4 - 7 hand theirs over through LDS (the staging buffers are free after
+  // the loop's last barrier), two products at a time; waves 0 - 3 add them to their own
   {
-    float* xch = (float*)&stage[0][0];                 // [2 (s)][4][16][64] floats = 32 KB
+    float* xch = (float*)&stage[0][0];                 // [4 (j)][2][16][64] floats = 32 KB
 #pragma unroll
     for (int round = 0; round < 2; ++round) {
-      const int tb = round * 4, tn = round ? 3 : 4;
       if (round) __syncthreads();
       if (wh == 1) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          if (t < tn)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) xch[((ws * 4 + t) * 16 + i) * 64 + lane] = acc[tb + t][i];
+          for (int i = 0; i < 16; ++i) xch[((wj * 2 + t) * 16 + i) * 64 + lane] = acc[round * 2 + t][i];
       }
       __syncthreads();
       if (wh == 0) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          if (t < tn)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tb + t][i] += xch[((ws * 4 + t) * 16 + i) * 64 + lane];
+          for (int i = 0; i < 16; ++i) acc[round * 2 + t][i] += xch[((wj * 2 + t) * 16 + i) * 64 + lane];
       }
     }
   }
-  // ---- results (waves 0 and 1): the 32 x 32 tiles of the Gram matrix on and below the diagonal (row-major in the
-  // d x d partial; the tiles above the diagonal are left unwritten, the reader mirrors; the one product that came
-  // out as an upper tile is stored as its mirror image)
+  // ---- results (waves 0 - 3): the 32 x 32 tiles of the Gram matrix on and below the diagonal (row-major in the d x d
+  // partial, so the stores are row segments; the tiles above the diagonal are left unwritten, the reader mirrors)
   float* out = gram_part + ((size_t)head * nstat + chunk) * gram_stride(DM_D);
   float tr = 0.f;                                      // this lane's share of the trace (the squared norms)
   if (wh == 0) {
-    const int trb[5] = {ws, 2 + ws, 1 + ws, (3 + ws) & 3, 2 + ws}, tcb[5] = {ws, 2 + ws, ws, 2 + ws, ws};
+    const int trb[3] = {wj, tl3.a, tl3.c}, tcb[3] = {0, tl3.b, tl3.b};
 #pragma unroll
-    for (int t = 0; t < 5; ++t) {
+    for (int t = 0; t < 3; ++t) {
+      if (t < 2 || tl3.third) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int rw = (i >> 2) * 8 + lh * 4 + (i & 3);
-        const int gr = trb[t] * 32 + rw, gc = tcb[t] * 32 + lr;
-        if (trb[t] >= tcb[t]) out[gr * DM_D + gc] = acc[t][i]; else out[gc * DM_D + gr] = acc[t][i];
-        if (t < 2 && rw == lr) tr += acc[t][i];
+        for (int i = 0; i < 16; ++i) {
+          const int rw = (i >> 2) * 8 + lh * 4 + (i & 3);
+          out[(trb[t] * 32 + rw) * DM_D + tcb[t] * 32 + lr] = acc[t][i];
+          if (trb[t] == tcb[t] && rw == lr) tr += acc[t][i];
+        }
       }
     }
-    // ---- weighted sum and plain sum: rows 0 - 3 of the sums tiles
+    // ---- weighted sum and plain sum: rows 0 - 3 of the sums tile
     if (lane < 32) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int col = (2 * t + ws) * 32 + lane;
-        out[DM_D * DM_D + col] = (acc[5 + t][0] + acc[5 + t][1]) + acc[5 + t][2];
-        out[DM_D * DM_D + DM_D + col] = acc[5 + t][3];
-      }
+      const int col = wj * 32 + lane;
+      out[DM_D * DM_D + col] = (acc[3][0] + acc[3][1]) + acc[3][2];
+      out[DM_D * DM_D + DM_D + col] = acc[3][3];
     }
   }
   for (int off = 32; off > 0; off >>= 1) tr += __shfl_xor(tr, off);
   if (lane == 0) red[wave] = tr;
   __syncthreads();
-  if (tid == 0) out[DM_D * DM_D + 2 * DM_D] = red[0] + red[1];
+  if (tid == 0) out[DM_D * DM_D + 2 * DM_D] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// The active head whose number (in head order) is `target`, or -1; every thread gets it.  s_i has 5 entries.
+// The active head whose number (in head order) is `target`, or -1; every thread gets it.  s_i has DM_WAVES + 1 entries.
 __device__ int dm_active_head(const HeadState* __restrict__ state, int heads, int target, int* s_i) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __syncthreads();
-  if (threadIdx.x == 0) s_i[4] = -1;
+  if (threadIdx.x == 0) s_i[DM_WAVES] = -1;
   int base = 0;
   for (int h0 = 0; h0 < heads; h0 += DM_THREADS) {
     const int h = h0 + threadIdx.x;
@@ -234,18 +236,18 @@ __device__ int dm_active_head(const HeadState* __restrict__ state, int heads, in
     __syncthreads();
     int before = base, tot = 0;
     for (int w = 0; w < DM_THREADS / 64; ++w) { if (w < wave) before += s_i[w]; tot += s_i[w]; }
-    if (p && before + __popcll(mask & ((1ull << lane) - 1ull)) == target) s_i[4] = h;
+    if (p && before + __popcll(mask & ((1ull << lane) - 1ull)) == target) s_i[DM_WAVES] = h;
     base += tot;
     if (base > target) break;                        // uniform: found
   }
   __syncthreads();
-  return s_i[4];
+  return s_i[DM_WAVES];
 }
 
 // grid (chunks, heads): workgroup (c, h) takes chunk c of head h.  With compact != 0 the grid is (chunks, a few rows) and
 // row y takes the active heads number y, y + rows, ... (found by scanning the head states): for calls in which the
 // certificate settles nearly every head, so that a launch over all heads would consist of workgroups that exit at once.
-__global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint16_t* __restrict__ V,
+__global__ __launch_bounds__(DM_THREADS, 4) void k_bf_del_stats_mfma(const uint16_t* __restrict__ V,
                                                                      const float* __restrict__ scores,
                                                                      const int32_t* __restrict__ idx, int N,
                                                                      int max_budget, int nstat,
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(DM_THREADS, 2) void k_bf_del_stats_mfma(const uint1
     dm_chunk(V, scores, idx, N, max_budget, nstat, state, n_keep, gram_part, scs, kvs, blockIdx.y, blockIdx.x);
     return;
   }
-  __shared__ int s_i[5];
+  __shared__ int s_i[DM_WAVES + 1];
   for (int s = blockIdx.y;; s += gridDim.y) {
     const int head = dm_active_head(state, heads, s, s_i);
     if (head < 0) return;
