@@ -7,22 +7,21 @@
 // Output format and meaning are those of the reference-precision kernel it replaces:
 // gram_part[head][chunk] = { G [d][d], u [d], s [d], ||V_del||^2, pad[3] }.
 #include "common.hpp"
+#include "gram_stage.hpp"
 #include "wave_ops.hpp"
 
 namespace obf {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 dm_bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float dm_f32x16;
+typedef gs_f32x16 dm_f32x16;
 
 constexpr int DM_THREADS = 512;
 constexpr int DM_WAVES = DM_THREADS / 64;
-constexpr int DM_D = 128;
-constexpr int DM_TILE = 64;              // rows staged per iteration
-constexpr int DM_LDW = 136;              // staging stride in 32-bit words per token PAIR
+constexpr int DM_D = GS_D;
+constexpr int DM_TILE = GS_TILE;         // rows staged per iteration
 constexpr int DM_WQ = kStatChunk + 8;    // stride of the weight-part arrays (bf16 entries)
 static_assert(kStatChunk % DM_TILE == 0, "a chunk is a whole number of tiles");
 
-union DmFrag { uint32_t w[4]; uint4 q; dm_bf16x8 v; };
+typedef GsFrag DmFrag;
 
 // The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb), and the two sums take four more tile
 // products (one per 32-column block; such a tile has the weight parts in rows 0 - 2 and the plain sum in row 3, i.e.
@@ -51,7 +50,7 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
                                          float* __restrict__ gram_part, int scs, int kvs, int head, int chunk) {
   const int n = n_keep ? n_keep[head] : state[head].n_keep;
   if (n_keep ? !(n > 0 && n < N) : !state[head].active) return;
-  __shared__ __attribute__((aligned(16))) uint32_t stage[2][(DM_TILE / 2) * DM_LDW];
+  __shared__ __attribute__((aligned(16))) uint32_t stage[2][GS_STAGE_WORDS];
   __shared__ __attribute__((aligned(16))) uint16_t wq[4][DM_WQ];   // bf16: three parts of a deleted token's score, and one; 0 for a retained token
   __shared__ uint32_t kept[kStatChunk / 32];           // bitmap of the retained tokens of the chunk
   __shared__ float red[DM_WAVES];                      // the waves' shares of the trace
@@ -94,36 +93,24 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-  // A thread moves 16-byte pieces: piece `pc` (eight columns) of token r0 + 4 (wave + 8 q) + tl, q = 0, 1.  Lanes l and
-  // l + 32 hold the two tokens of a pair (tl = 0, 2 in the lower half of the wave, 1, 3 in the upper half).
-  const int pc = lane & 15, tl = ((lane >> 4) & 1) * 2 + lh;
+  // 16-byte pieces through registers (two per thread and tile), two tiles ahead of the products
+  const int pc = lane & 15;
   uint4 pre[2][2];
   auto fetch = [&](uint4 (&dst)[2], int r0) {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int r = min(r0 + 4 * (wave + 8 * q) + tl, rows - 1);         // clamped: rows past the end are zeroed in put
+      const int r = min(r0 + gs_row<DM_WAVES>(wave, lane, q), rows - 1);      // clamped: rows past the end are zeroed in put
       dst[q] = *(const uint4*)(Vh + (size_t)(t0 + r) * DM_D + pc * 8);
     }
   };
-  // Staging layout: word [p][j] holds column j of tokens 2p and 2p+1 (low / high half), so that an operand fragment
-  // (8 tokens of one column) is four 32-bit reads.  One lane swap per word pair brings the partner token's words for
-  // four of the eight columns to each lane (the lower lane ends up with the piece's columns 0 - 3 of both tokens, the
-  // upper lane with columns 4 - 7), two byte permutes interleave them.  Retained rows and rows past the end are zeroed.
+  // retained rows and rows past the end are staged as zeros
   auto put = [&](const uint4 (&src)[2], int buf, int r0) {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int rl = 4 * (wave + 8 * q) + tl;                            // row within the tile
+      const int rl = gs_row<DM_WAVES>(wave, lane, q);
       const int r = r0 + rl;
       const uint32_t kbit = (kept[(r >> 5) & (kStatChunk / 32 - 1)] >> (r & 31)) & 1u;
-      const uint32_t mk = (r < rows ? 1u : 0u) & (kbit ^ 1u) ? 0xffffffffu : 0u;
-      const auto s0 = __builtin_amdgcn_permlane32_swap(src[q].x & mk, src[q].z & mk, false, false);   // [0]: even token, [1]: odd token
-      const auto s1 = __builtin_amdgcn_permlane32_swap(src[q].y & mk, src[q].w & mk, false, false);
-      uint4 wv;
-      wv.x = __builtin_amdgcn_perm(s0[1], s0[0], 0x05040100u);
-      wv.y = __builtin_amdgcn_perm(s0[1], s0[0], 0x07060302u);
-      wv.z = __builtin_amdgcn_perm(s1[1], s1[0], 0x05040100u);
-      wv.w = __builtin_amdgcn_perm(s1[1], s1[0], 0x07060302u);
-      *(uint4*)(&stage[buf][(rl >> 1) * DM_LDW + pc * 8 + lh * 4]) = wv;
+      gs_put(stage[buf], rl, lane, src[q], (r < rows) && !kbit);
     }
   };
   const int wj = wave & 3, wh = wave >> 2;
@@ -133,13 +120,9 @@ __device__ __forceinline__ void dm_chunk(const uint16_t* __restrict__ V, const f
 #pragma unroll 1
     for (int kk = 0; kk < 2; ++kk) {
       const int ks = 2 * wh + kk;
-      const uint32_t* p = st + (ks * 8 + lh * 4) * DM_LDW + lr;
       DmFrag fW, f0, fA, fB, fC, e;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fW.w[i] = p[i * DM_LDW + oW]; f0.w[i] = p[i * DM_LDW];
-        fA.w[i] = p[i * DM_LDW + oA]; fB.w[i] = p[i * DM_LDW + oB]; fC.w[i] = p[i * DM_LDW + oC];
-      }
+      gs_frag(fW, st, ks, lane, oW); gs_frag(f0, st, ks, lane, 0);
+      gs_frag(fA, st, ks, lane, oA); gs_frag(fB, st, ks, lane, oB); gs_frag(fC, st, ks, lane, oC);
       // the sums' operand: row lr < 4 of it holds eight tokens' entries of weight part lr (or of the ones); the address is
       // clamped so that every lane loads, the other rows are cleared
       e.q = *(const uint4*)(&wq[lr & 3][r0 + ks * 16 + lh * 8]);

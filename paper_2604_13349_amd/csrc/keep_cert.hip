@@ -12,20 +12,20 @@
 //   sigma_min(V_keep)^2 >= lambda_min(G) > (max(n, d) 2^-23)^2 sigma_max(V_keep)^2, i.e. every singular
 //   value is above the rank rule's threshold: r = d.
 #include "common.hpp"
+#include "gram_stage.hpp"
+#include "wave_ops.hpp"
 
 namespace obf {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef gs_f32x16 f32x16;
 
 constexpr int KC_THREADS = 256;
-constexpr int KC_D = 128;
-constexpr int KC_TILE = 64;              // rows staged per iteration
-constexpr int KC_LDW = 136;              // staging stride in 32-bit words per token PAIR (the two lane halves, 4 pairs apart, use different banks)
+constexpr int KC_WAVES = KC_THREADS / 64;
+constexpr int KC_D = GS_D;
+constexpr int KC_TILE = GS_TILE;         // rows staged per iteration
 constexpr int KC_MINROWS = 512;          // rows entering G: all up to 512, else about max(512, n/4) at a constant stride
 constexpr float kCertErr = 1.6e-5f;      // allowance for fp32 Gram + factorisation error, relative to the trace of the scaled Gram matrix (= d)
 
-union FragU { uint32_t w[4]; bf16x8 v; };
 
 // The lower triangle of G is ten 32x32 tiles (row block rb >= column block cb).  Each tile lives in one wave's
 // registers from the Gram phase to the end of the factorisation: entry i of lane l is
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
                                                              const double* __restrict__ fro_part /*optional: sums of squares of the retained rows, per gather block*/,
                                                              int fro_blocks, int scs, int kvs,
                                                              int want_sums /*0: the demand sums of a certified head (diagnostics only) are left at zero*/) {
-  __shared__ uint32_t stage[2][(KC_TILE / 2) * KC_LDW];
+  __shared__ __attribute__((aligned(16))) uint32_t stage[2][GS_STAGE_WORDS];
   __shared__ __attribute__((aligned(16))) float panel[2][KC_D][4];
   __shared__ float4 ypan[KC_D], lpan[KC_D];
   __shared__ __attribute__((aligned(16))) float isd[KC_D];
@@ -79,63 +79,37 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
   // ---- Gram phase: rows staged 64 at a time through LDS (double buffered); the loads run two tiles ahead in
-  // registers so that their latency is covered by the MFMAs and the transposing LDS reads of two tiles
-  uint2 pre[2][8];
-  auto fetch = [&](uint2 (&dst)[8], int r0) {
+  // registers so that their latency is covered by the products of two tiles.  All waves run one instruction stream:
+  // the operands of a wave's tiles are picked by LDS address (a wave with two tiles repeats its second product into an
+  // accumulator nobody reads).
+  const int pc = lane & 15;
+  uint4 pre[2][4];
+  auto fetch = [&](uint4 (&dst)[4], int r0) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int e = tid + q * KC_THREADS;
-      const int r = e >> 5, c = e & 31;
-      dst[q] = make_uint2(0u, 0u);
-      if (r0 + r < rows) dst[q] = *(const uint2*)(Vh + row_of((r0 + r) * stride) * KC_D + c * 4);
+    for (int q = 0; q < 4; ++q) {
+      const int r = min(r0 + gs_row<KC_WAVES>(wave, lane, q), rows - 1);      // clamped: rows past the end are zeroed in put
+      dst[q] = *(const uint4*)(Vh + row_of(r * stride) * KC_D + pc * 8);
     }
   };
-  // Staging layout: word [p][j] holds column j of tokens 2p and 2p+1 (low / high half), so that an operand
-  // fragment (8 tokens of one column) is four 32-bit reads; the order of the tokens inside a fragment does not
-  // matter for V^T V as long as both operands use the same one.  Lanes l and l+32 of a wave hold rows 2p and 2p+1
-  // of the same four columns; the lower lane writes the words of the first two, the upper lane of the last two.
-  auto put = [&](const uint2 (&src)[8], int buf) {
+  auto put = [&](const uint4 (&src)[4], int buf, int r0) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int e = tid + q * KC_THREADS;
-      const int pr = e >> 6, c = e & 31;
-      const uint32_t mine = lh ? src[q].y : src[q].x;            // the dword this lane combines: columns 4c+2*lh, +1
-      const uint32_t other = lh ? src[q].x : src[q].y;           // the dword the partner lane combines
-      // partner's copy of "my" dword: it is the partner's "other" seen from its side
-      const auto sw = __builtin_amdgcn_permlane32_swap(other, other, false, false);
-      const uint32_t theirs = lh ? sw[0] : sw[1];                // lower lanes get the upper half's value and vice versa
-      const uint32_t even = lh ? theirs : mine, odd = lh ? mine : theirs;     // rows 2p and 2p+1
-      uint2 w;
-      w.x = (even & 0xffffu) | (odd << 16);
-      w.y = (even >> 16) | (odd & 0xffff0000u);
-      *(uint2*)(&stage[buf][pr * KC_LDW + c * 4 + lh * 2]) = w;
+    for (int q = 0; q < 4; ++q) {
+      const int rl = gs_row<KC_WAVES>(wave, lane, q);
+      gs_put(stage[buf], rl, lane, src[q], r0 + rl < rows);
     }
   };
+  const int oA0 = trb[0] * 32, oB0 = tcb[0] * 32, oA1 = trb[1] * 32, oB1 = tcb[1] * 32;
+  const int oA2 = (nt > 2 ? trb[2] : trb[1]) * 32, oB2 = (nt > 2 ? tcb[2] : tcb[1]) * 32;
   auto compute = [&](const uint32_t* st) {
 #pragma unroll
     for (int ks = 0; ks < KC_TILE / 16; ++ks) {
-      FragU f[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t* p = st + (ks * 8 + lh * 4) * KC_LDW + c * 32 + lr;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[c].w[i] = p[i * KC_LDW];
-      }
-      if (wave == 0) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[1].v, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[2].v, acc[2], 0, 0, 0);
-      } else if (wave == 1) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[1].v, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[3].v, acc[2], 0, 0, 0);
-      } else if (wave == 2) {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[1].v, acc[1], 0, 0, 0);
-      } else {
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3].v, f[0].v, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2].v, f[2].v, acc[1], 0, 0, 0);
-      }
+      GsFrag a0, b0, a1, b1, a2, b2;
+      gs_frag(a0, st, ks, lane, oA0); gs_frag(b0, st, ks, lane, oB0);
+      gs_frag(a1, st, ks, lane, oA1); gs_frag(b1, st, ks, lane, oB1);
+      gs_frag(a2, st, ks, lane, oA2); gs_frag(b2, st, ks, lane, oB2);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b0.v, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, b1.v, acc[1], 0, 0, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2.v, b2.v, acc[2], 0, 0, 0);
     }
   };
   // The demand sums of Eq. 6 (diagnostics of a certified head) need sum(scores[idx]) and sum(scores): their first
@@ -148,19 +122,20 @@ __global__ __launch_bounds__(KC_THREADS, 2) void k_bf_keep_cert(const uint16_t* 
   // tile j is staged in stage[j % 2]; the loads run two tiles ahead in registers
   fetch(pre[0], 0);
   fetch(pre[1], KC_TILE);
-  put(pre[0], 0);
+  put(pre[0], 0, 0);
   fetch(pre[0], 2 * KC_TILE);
-  __syncthreads();
+  lds_barrier();
+#pragma unroll 1
   for (int r0 = 0; r0 < rows; r0 += 2 * KC_TILE) {
     // even tile: in stage[0]; pre[1] holds tile r0+64, pre[0] holds tile r0+128
     compute(stage[0]);
-    put(pre[1], 1);
+    put(pre[1], 1, r0 + KC_TILE);
     fetch(pre[1], r0 + 3 * KC_TILE);
-    __syncthreads();
+    lds_barrier();                      // LDS only: the loads just issued stay in flight across the barrier
     if (r0 + KC_TILE < rows) compute(stage[1]);
-    put(pre[0], 0);
+    put(pre[0], 0, r0 + 2 * KC_TILE);
     fetch(pre[0], r0 + 4 * KC_TILE);
-    __syncthreads();
+    lds_barrier();
   }
   float ev[8];
 #pragma unroll
