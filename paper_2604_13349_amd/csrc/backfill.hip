@@ -1300,10 +1300,11 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
   const int kq = min(rank, m);
   if (tid < d) uvec[tid] = delta[(size_t)head * d + tid];      // u
   __syncthreads();
-  if (tid < m) {                                               // y = Z u (Eq. 4 in complement coordinates)
-    float sy = 0.f;
-    for (int c = 0; c < d; ++c) sy = fmaf(Zg[(size_t)tid * d + c], uvec[c], sy);
-    rbar[tid] = sy;
+  for (int t = wave; t < m; t += TE_WAVES) {                   // y = Z u (Eq. 4 in complement coordinates), a wave per row
+    float sy = (lane < d) ? Zg[(size_t)t * d + lane] * uvec[lane] : 0.f;
+    if (lane + 64 < d) sy = fmaf(Zg[(size_t)t * d + lane + 64], uvec[lane + 64], sy);
+    sy = te_wave_sum(sy);
+    if (lane == 0) rbar[t] = sy;
   }
   // Delta in complement coordinates (times a_del + eps) from kk orthonormal rows Cb [kk][m]: Eq. 5
   auto project = [&](const float* Cb, const int kk) {

@@ -61,15 +61,15 @@ __device__ __forceinline__ void te_factor(const float* __restrict__ dv, const fl
   a1[(m - 1) * KS] = 0.f; a2[(m - 1) * KS] = 0.f;
 }
 
-// the row operations of the elimination applied to the right-hand side: in -> out
+// the row operations of the elimination applied to the right-hand side: scale * in -> out
 template <int KS>
 __device__ __forceinline__ void te_forward(const float* __restrict__ f, const int m, const float* __restrict__ in,
-                                           float* __restrict__ out) {
+                                           float* __restrict__ out, const float scale) {
   const float* mu = f + 3 * m * KS; const float* sw = mu + m * KS;
-  float carry = in[0];
+  float carry = in[0] * scale;
 #pragma unroll 4
   for (int j = 0; j + 1 < m; ++j) {
-    const float nx = in[(j + 1) * KS], g = mu[j * KS];
+    const float nx = in[(j + 1) * KS] * scale, g = mu[j * KS];
     const bool swap = sw[j * KS] != 0.f;
     const float bj = swap ? nx : carry, bn = swap ? carry : nx;
     out[j * KS] = bj;
@@ -331,14 +331,17 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
       const uint32_t h = ((uint32_t)j * 2654435761u + (uint32_t)lane * 40503u + 12345u) >> 8;
       za[j * KS] = (float)(h & 0xffffu) * (1.f / 65536.f) - 0.5f;
     }
+    // Three solves.  Between them the iterate is only rescaled by its largest magnitude (folded into the next solve's
+    // first pass: the squares of the last normalisation cannot overflow, and nothing else depends on the length).
+    float big = 1.f;
     for (int it = 0; it < 3; ++it) {
-      te_forward<KS>(lu + lane, m, za, zb);
-      const float big = te_backward<KS>(lu + lane, m, zb, za);
-      // the last pass also clears what is left of the start vector in blocks that S decouples from this eigenvalue
-      // (an exactly zero sub-diagonal entry): some twenty orders of magnitude down, exact zeros in exact arithmetic
-      te_normalise<KS>(m, za, zb, big, it == 2);
-      float* t = za; za = zb; zb = t;
+      te_forward<KS>(lu + lane, m, za, zb, (big > 0.f && big < INFINITY) ? 1.f / big : 1.f);
+      big = te_backward<KS>(lu + lane, m, zb, za);
     }
+    // unit length; this pass also clears what is left of the start vector in blocks that S decouples from this eigenvalue
+    // (an exactly zero sub-diagonal entry): some twenty orders of magnitude down, exact zeros in exact arithmetic
+    te_normalise<KS>(m, za, zb, big, true);
+    { float* t = za; za = zb; zb = t; }
     if (za != zz + lane) for (int j = 0; j < m; ++j) zz[j * KS + lane] = za[j * KS];
   }
   __syncthreads();
