@@ -72,6 +72,13 @@ typedef struct {
   int32_t dtype;      /* obf_dtype_t of K, V, Qwin, K_out, V_out */
 } obf_shape_t;
 
+/* Bits of obf_diag_t.select_flags.
+ *   OBF_SELECT_BAND_OVERFLOW  more than 256 tokens have single-precision scores within 1e-4 (relative) of the head's threshold
+ *                             score and they straddle it: the double-precision re-decision at the threshold was not run
+ *                             for this head, its index list follows the single-precision scores (ties to the lowest
+ *                             index); exact for all-equal scores, otherwise within the single-precision error of Eq. 1. */
+#define OBF_SELECT_BAND_OVERFLOW 1
+
 /* Per-head diagnostics: the quantities of App. K.2 (PCR, RCR, PC, REVR, DR, IVN) and the decisions taken. */
 typedef struct {
   int32_t n_keep;   /* retained tokens */
@@ -86,6 +93,7 @@ typedef struct {
   float pc;         /* projection cosine between the column sums of V_del and of V_par; 0 when not computed */
   float revr;       /* residual explained variance ratio of the k_used directions; 0 when none is used */
   float dr;         /* demand ratio a_del / (a_keep + eps) */
+  int32_t select_flags; /* OBF_SELECT_* bits of the head's selection; set by the fused headwise calls only (0 elsewhere) */
   float fast_err;   /* with obf_variant_t.subspace_iters > 0: ||Delta_fast - Delta_svd|| / ||Delta_svd|| of the head
                        (App. H), 0 if Delta_svd = 0; -1 when not computed (any other call, and heads without an injection
                        decision by Eq. 5) */

@@ -18,7 +18,7 @@ _STATUS = {1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP
 DIAG_DTYPE = np.dtype([("n_keep", "<i4"), ("r_keep", "<i4"), ("k_used", "<i4"), ("skipped", "<i4"),
                        ("a_keep", "<f4"), ("a_del", "<f4"), ("rcr", "<f4"), ("ivn", "<f4"),
                        ("pcr", "<f4"), ("pc", "<f4"), ("revr", "<f4"), ("dr", "<f4"),
-                       ("fast_err", "<f4")])
+                       ("select_flags", "<i4"), ("fast_err", "<f4")])
 
 
 class ObfError(RuntimeError):
@@ -45,6 +45,7 @@ class _Window(C.Structure):
 
 
 SUBSPACE = {"rank": 0, "all": 1, "evr": 2}
+OBF_SELECT_BAND_OVERFLOW = 1
 
 
 def make_variant(no_projection=False, subspace="rank", evr_tau=0.35, no_scaling=False, naive_aggregation=False,

@@ -291,7 +291,8 @@ static obf_status_t compress_heads(int layerwise, Variant var, const Dims& mf, i
     OBF_TRY(launch_select_layerwise(m, w, base, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
   } else {
     // selection and boundary refinement in one kernel (same decisions as the two stage calls)
-    OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st));
+    OBF_TRY(launch_select_refine(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Qwin, row_lse, st,
+                                 (int32_t*)(base + w.sel_flags)));
   }
   // the gather also leaves the sums of squares of the retained V rows for the full-rank certificate
   double* fro_part = (m.dtype == OBF_BF16 && m.d == 128) ? (double*)(base + w.fro_part) : nullptr;
@@ -327,6 +328,7 @@ static obf_status_t compress_heads(int layerwise, Variant var, const Dims& mf, i
   }
   if (k_beside) { const obf_status_t js = stream_after(st, aux, EV_KROWS_JOIN); if (rs == OBF_OK) rs = js; }
   OBF_TRY(rs);
+  if (diag && !layerwise) OBF_TRY(launch_diag_flags(diag, (const int32_t*)(base + w.sel_flags), m.heads, st));
   return launch_idx_offset(idx, (size_t)m.heads * max_budget, sink, st);   // back to the head's own token numbers
 }
 

@@ -647,6 +647,7 @@ __device__ __forceinline__ void fn_emit(const int head, const int d, const int r
       dg.pc = pc; dg.revr = revr;
       dg.dr = (float)(st.a_del / (st.a_keep + kEps));
       dg.fast_err = fast_err;
+      dg.select_flags = 0;                                     // the fused call fills it in afterwards
       diag[head] = dg;
     }
   }

@@ -60,6 +60,7 @@ struct Workspace {
   size_t gram_part;    // float   [heads][nstat][gram_stride(d)] partial Gram / weighted sum / plain sum / norm of V_del
   size_t mats;         // float   [heads][3][d*d]         scratch matrices of the per-head finalisation
   size_t delta;        // float   [heads][d]
+  size_t sel_flags;    // int32   [heads]: OBF_SELECT_* bits of the fused selection (read into obf_diag_t when diagnostics are asked for)
   size_t band;         // 16 bytes [heads][kBandCap]: scratch of the threshold re-decision (layerwise: exact per-head masses of the band)
   size_t layer_scores; // float   [L][N]        attention mass summed over the heads of a layer (layerwise selector)
   size_t layer_idx;    // int32   [L][max_budget], then int32 [L]: the shared index lists and their lengths
@@ -134,6 +135,7 @@ inline Workspace carve(const Dims& m, int max_budget, int rank) {
   w.gram_part = take(sizeof(float) * (size_t)m.heads * w.nstat * gram_stride(m.d));
   w.mats = take(sizeof(float) * (size_t)m.heads * 3 * m.d * m.d);
   w.delta = take(sizeof(float) * (size_t)m.heads * m.d);
+  w.sel_flags = take(sizeof(int32_t) * (size_t)m.heads);
   w.band = take(16 * (size_t)m.heads * kBandCap);
   w.layer_scores = take(sizeof(float) * (size_t)m.L * m.N);
   w.layer_idx = take(sizeof(int32_t) * ((size_t)m.L * (max_budget > 0 ? max_budget : 0) + m.L));
@@ -194,7 +196,9 @@ obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* bu
                            int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st);
 obf_status_t launch_select_refine(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                                   int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
-                                  const double* row_lse, hipStream_t st);
+                                  const double* row_lse, hipStream_t st, int32_t* sel_flags = nullptr /*[heads], nullable*/);
+// diag[h].select_flags = sel_flags[h] for every head (diagnostics only)
+obf_status_t launch_diag_flags(obf_diag_t* diag, const int32_t* sel_flags, int heads, hipStream_t st);
 obf_status_t launch_refine(const Dims& m, const Workspace& w, char* ws, const void* K, const void* Q,
                            const float* scores, const double* row_lse, int32_t max_budget, int32_t* idx,
                            const int32_t* n_keep, hipStream_t st);

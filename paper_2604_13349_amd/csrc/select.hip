@@ -52,7 +52,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
                                                         int max_budget, int32_t* __restrict__ idx,
                                                         int32_t* __restrict__ n_keep, const ET* __restrict__ K,
                                                         const ET* __restrict__ Q, const double* __restrict__ row_lse,
-                                                        int d, int R, int scs, int kvs) {
+                                                        int d, int R, int scs, int kvs,
+                                                        int32_t* __restrict__ sel_flags /*nullable; written with REFINE only*/) {
   constexpr int SEL_WAVES = SEL_THREADS / 64;
   __shared__ int band[REFINE ? kBandCap : 1];
   __shared__ double band_score[REFINE ? kBandCap : 1];
@@ -159,6 +160,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
     int ebk, nband, nkb;
     block_exscan2<SEL_WAVES>(cb, ckb, bpos0, ebk, nband, nkb, wsum);
     if (tid == 0) s_changed = 0;
+    // a band that straddles the threshold but is too large to re-score keeps the single-precision order: say so
+    if (sel_flags && tid == 0) sel_flags[head] = (nband > kBandCap && nkb > 0 && nkb < nband) ? OBF_SELECT_BAND_OVERFLOW : 0;
     if (nband > 1 && nband <= kBandCap && nkb > 0 && nkb < nband) {       // uniform
       int bp = bpos0, er = ee;
 #pragma unroll
@@ -222,12 +225,12 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const float* __restrict_
 template <int SEG, int SEL_THREADS, bool REFINE, typename T>
 static obf_status_t launch_select_seg(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                                       int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
-                                      const double* row_lse, hipStream_t st) {
+                                      const double* row_lse, hipStream_t st, int32_t* sel_flags) {
   BudgetBatch bb;
   if (!budgets_host) {
     { ProfScope prof_(ST_SELECT, st);
       hipLaunchKernelGGL((k_select<SEG, SEL_THREADS, REFINE, T>), dim3(m.heads), dim3(SEL_THREADS), 0, st, scores, m.N, 0,
-                         budget, bb, 0, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R, m.scs, m.kvs); }
+                         budget, bb, 0, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R, m.scs, m.kvs, sel_flags); }
     return check_launch("select");
   }
   for (int h0 = 0; h0 < m.heads; h0 += SEL_BATCH) {
@@ -235,7 +238,7 @@ static obf_status_t launch_select_seg(const Dims& m, const float* scores, const 
     for (int i = 0; i < nb; ++i) bb.b[i] = budgets_host[h0 + i];
     { ProfScope prof_(ST_SELECT, st);
       hipLaunchKernelGGL((k_select<SEG, SEL_THREADS, REFINE, T>), dim3(nb), dim3(SEL_THREADS), 0, st, scores, m.N, h0, 0, bb,
-                         1, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R, m.scs, m.kvs); }
+                         1, max_budget, idx, n_keep, (const T*)K, (const T*)Q, row_lse, m.d, m.R, m.scs, m.kvs, sel_flags); }
     if (check_launch("select") != OBF_OK) return OBF_ERR_HIP;
   }
   return OBF_OK;
@@ -244,9 +247,9 @@ static obf_status_t launch_select_seg(const Dims& m, const float* scores, const 
 template <bool REFINE, typename T>
 static obf_status_t dispatch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                                     int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
-                                    const double* row_lse, hipStream_t st) {
+                                    const double* row_lse, hipStream_t st, int32_t* sel_flags) {
   // per bit every wave counts its keys and the workgroup adds the counts: 16 keys per thread up to 8192 tokens, 32 above
-#define OBF_SEL(SEG, THR) launch_select_seg<SEG, THR, REFINE, T>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st)
+#define OBF_SEL(SEG, THR) launch_select_seg<SEG, THR, REFINE, T>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st, sel_flags)
   if (m.N <= 4 * 256) return OBF_SEL(4, 256);
   if (m.N <= 8 * 256) return OBF_SEL(8, 256);
   if (m.N <= 16 * 256) return OBF_SEL(16, 256);
@@ -258,15 +261,26 @@ static obf_status_t dispatch_select(const Dims& m, const float* scores, const in
 
 obf_status_t launch_select(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                            int32_t max_budget, int32_t* idx, int32_t* n_keep, hipStream_t st) {
-  return dispatch_select<false, float>(m, scores, budgets_host, budget, max_budget, idx, n_keep, nullptr, nullptr, nullptr, st);
+  return dispatch_select<false, float>(m, scores, budgets_host, budget, max_budget, idx, n_keep, nullptr, nullptr, nullptr, st, nullptr);
 }
 
 obf_status_t launch_select_refine(const Dims& m, const float* scores, const int32_t* budgets_host, int32_t budget,
                                   int32_t max_budget, int32_t* idx, int32_t* n_keep, const void* K, const void* Q,
-                                  const double* row_lse, hipStream_t st) {
+                                  const double* row_lse, hipStream_t st, int32_t* sel_flags) {
   if (m.dtype == OBF_BF16)
-    return dispatch_select<true, uint16_t>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st);
-  return dispatch_select<true, float>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st);
+    return dispatch_select<true, uint16_t>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st, sel_flags);
+  return dispatch_select<true, float>(m, scores, budgets_host, budget, max_budget, idx, n_keep, K, Q, row_lse, st, sel_flags);
+}
+
+__global__ void k_diag_flags(obf_diag_t* __restrict__ diag, const int32_t* __restrict__ sel_flags, int heads) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h < heads) diag[h].select_flags = sel_flags[h];
+}
+
+obf_status_t launch_diag_flags(obf_diag_t* diag, const int32_t* sel_flags, int heads, hipStream_t st) {
+  if (!diag || !sel_flags || heads <= 0) return OBF_OK;
+  hipLaunchKernelGGL(k_diag_flags, dim3((heads + 255) / 256), dim3(256), 0, st, diag, sel_flags, heads);
+  return check_launch("diag flags");
 }
 
 }  // namespace obf

@@ -211,6 +211,12 @@ def test_all_ties_keep_lowest_indices(gpu):
     out = gpu.run_fused(cfg, K, V, Q, budget=50)
     for h in range(2):
         assert out["idx"][0, h].tolist() == list(range(50))
+    # 640 equal scores straddle the threshold: more than the re-decision takes, and the call says so per head
+    from paper_2604_13349_amd import binding as Bd
+    assert np.all(out["diag"]["select_flags"] == Bd.OBF_SELECT_BAND_OVERFLOW)
+    cfg2 = si.shrink(si.CONFIGS["2s"], n_layers=1)
+    K2, V2, Q2 = si.make_cache(cfg2, 0, threads=8)
+    assert np.all(gpu.run_fused(cfg2, K2, V2, Q2, budget=cfg2.budget)["diag"]["select_flags"] == 0)
 
 
 def test_fused_equals_staged_and_is_deterministic(gpu):
