@@ -214,6 +214,9 @@ def main() -> int:
                 "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "kernel_ms": round(avg_ms, 4), "kernel_bytes": kbytes,
                 "stage_ms": {k: round(v, 4) for k, v in r["stage_ms"].items()}}
+        if r["dominant"] in ("keep_basis", "finalize", "select", "keep_cert"):
+            roof["note"] = ("a per-head sequential factorisation / bisection: bound by the latency of its dependent steps, "
+                            "the HBM fraction only says how far from streaming it is")
         path = {"bytes": pb, "GBps": round(pb / step_s / 1e9, 2), "frac": round(pb / step_s / 1e9 / HBM_PEAK_GBS, 4),
                 "target_frac": 0.60, "unit": "GB/s of algorithmic bytes (K, Q once; retained rows read and written; V where the back-fill is active)"}
         return roof, path
