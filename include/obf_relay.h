@@ -179,7 +179,7 @@ obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* 
  *                      orthonormal cosine basis C_0[i][c] = sqrt(2/d) cos(pi (i + 1/2)(c + 1/2) / d) (the paper asks
  *                      only for orthonormal rows and runs t = 3); orth is Gram-Schmidt over the rows in order, a row
  *                      left with at most 1e-5 of the first row's norm is dropped (k_used counts the rows kept, revr is
- *                      their share of the trace).  Needs subspace = OBF_SUBSPACE_RANK, rank <= 8 and head_dim <= 128,
+ *                      their share of the trace).  Needs subspace = OBF_SUBSPACE_RANK, rank <= 16 and head_dim <= 128,
  *                      else OBF_ERR_UNSUPPORTED.  With diag != NULL the exact directions are computed too and
  *                      diag.fast_err reports the distance between the two (this costs the exact route's time).
  * `rank` = 0 is plain eviction under every variant.  The per-token alternative of App. D is not provided. */

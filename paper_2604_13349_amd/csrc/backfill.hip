@@ -1309,11 +1309,11 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
   }
   // Delta in complement coordinates (times a_del + eps) from kk orthonormal rows Cb [kk][m]: Eq. 5
   auto project = [&](const float* Cb, const int kk) {
-    if (wave < kk) {
-      float sc = (lane < m) ? rbar[lane] * Cb[wave * m + lane] : 0.f;
-      if (lane + 64 < m) sc = fmaf(rbar[lane + 64], Cb[wave * m + lane + 64], sc);
+    for (int v = wave; v < kk; v += TE_WAVES) {
+      float sc = (lane < m) ? rbar[lane] * Cb[v * m + lane] : 0.f;
+      if (lane + 64 < m) sc = fmaf(rbar[lane + 64], Cb[v * m + lane + 64], sc);
       sc = te_wave_sum(sc);
-      if (lane == 0) dvec[wave] = sc;
+      if (lane == 0) dvec[v] = sc;
     }
     __syncthreads();
     if (tid < m) {
@@ -1363,25 +1363,25 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
       c0[e] = sqrtf(2.f / (float)d) * cospif((float)((2 * i + 1) * (2 * c + 1)) / (float)(4 * d));
     }
     __syncthreads();
-    if (wave < k0) {
+    for (int v = wave; v < k0; v += TE_WAVES) {
       for (int t = lane; t < m; t += 64) {
         float sy = 0.f;
-        for (int c = 0; c < d; ++c) sy = fmaf(c0[wave * d + c], Zg[(size_t)t * d + c], sy);
-        Ya[wave * m + t] = sy;
+        for (int c = 0; c < d; ++c) sy = fmaf(c0[v * d + c], Zg[(size_t)t * d + c], sy);
+        Ya[v * m + t] = sy;
       }
     }
     if (tid == 0) s_k = k0;
     __syncthreads();
     auto times_T = [&](const int kk) {                         // Yb = Ya T (T is symmetric: row s is read as column s)
-      if (wave < kk) {
+      for (int v = wave; v < kk; v += TE_WAVES) {
         float a0 = 0.f, a1 = 0.f;
         for (int s = 0; s < m; ++s) {
-          const float ys = Ya[wave * m + s];
+          const float ys = Ya[v * m + s];
           a0 = fmaf(ys, (lane < m) ? Tl[s * lt + lane] : 0.f, a0);
           a1 = fmaf(ys, (lane + 64 < m) ? Tl[s * lt + lane + 64] : 0.f, a1);
         }
-        if (lane < m) Yb[wave * m + lane] = a0;
-        if (lane + 64 < m) Yb[wave * m + lane + 64] = a1;
+        if (lane < m) Yb[v * m + lane] = a0;
+        if (lane + 64 < m) Yb[v * m + lane + 64] = a1;
       }
       __syncthreads();
     };
@@ -1421,11 +1421,11 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
     revr = 0.f;
     if (k_used > 0) {
       times_T(k_used);                                         // explained share: sum_i c_i T c_i^T over the trace
-      if (wave < k_used) {
-        float sc = (lane < m) ? Ya[wave * m + lane] * Yb[wave * m + lane] : 0.f;
-        if (lane + 64 < m) sc = fmaf(Ya[wave * m + lane + 64], Yb[wave * m + lane + 64], sc);
+      for (int v = wave; v < k_used; v += TE_WAVES) {
+        float sc = (lane < m) ? Ya[v * m + lane] * Yb[v * m + lane] : 0.f;
+        if (lane + 64 < m) sc = fmaf(Ya[v * m + lane + 64], Yb[v * m + lane + 64], sc);
         sc = te_wave_sum(sc);
-        if (lane == 0) dvec[wave] = sc;
+        if (lane == 0) dvec[v] = sc;
       }
       __syncthreads();
       if (tid == 0) {
@@ -1523,7 +1523,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   }
   if (var.subspace_iters > 0 && !(var.flags & VF_NAIVE) &&
       (rank > TE_MAXK || (var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR)) || m.d > 128)) {
-    set_error("backfill: the subspace iteration takes the rank rule with pca_rank <= 8 and head_dim <= 128");
+    set_error("backfill: the subspace iteration takes the rank rule with pca_rank <= 16 and head_dim <= 128");
     return OBF_ERR_UNSUPPORTED;
   }
   if (var.skips_basis()) {

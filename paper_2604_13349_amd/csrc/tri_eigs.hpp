@@ -5,7 +5,7 @@
 //   2. the k largest eigenvalues of the tridiagonal S by multisection on Sturm counts (every thread evaluates one
 //      shift per round; four rounds shrink an eigenvalue's bracket below single-precision resolution);
 //   3. their eigenvectors by inverse iteration on S - theta I (tridiagonal elimination with row exchanges, one lane
-//      per eigenvector, three solves from a fixed pseudo-random start);
+//      per eigenvector, three solves from a fixed pseudo-random start), eight at a time;
 //   4. back-transformation through the reflectors (one wave per eigenvector) and a final Gram-Schmidt pass over the
 //      k vectors (eigenvalues that agree to rounding give vectors that only span the right subspace together).
 // All arithmetic is single precision; nothing here depends on convergence of an iteration.
@@ -17,12 +17,15 @@ namespace obf {
 
 constexpr int TE_THREADS = 512;
 constexpr int TE_WAVES = TE_THREADS / 64;
-constexpr int TE_MAXK = 8;               // one wave per eigenvector in the back-transformation
+constexpr int TE_MAXK = 16;              // most eigenpairs
+constexpr int TE_BATCH = 8;              // eigenvectors per pass of the inverse iteration and the back-transformation (one wave each)
 constexpr int TE_CPT = 32;               // columns per thread of the register-resident matrix (128 rows x 4 groups)
 
 // floats of LDS scratch tri_top_eigs needs for an m x m matrix and k eigenpairs
 __host__ __device__ inline int tri_lane_stride(int k) { return k <= 4 ? 4 : 8; }
-__host__ __device__ inline int tri_work_floats(int m, int k) { return 4 * m + 256 + TE_THREADS + 96 + 7 * tri_lane_stride(k) * m; }
+__host__ __device__ inline int tri_work_floats(int m, int k) {
+  return 4 * m + 256 + TE_THREADS + 96 + 7 * tri_lane_stride(k) * m + (k > TE_BATCH ? k * m : 0);
+}
 
 // sum over the 64 lanes, the result in every lane: four in-row DPP steps, then the rows and the halves meet through
 // lane swaps (no LDS traffic, a fixed order of additions)
@@ -114,6 +117,8 @@ __device__ __forceinline__ void te_normalise(const int m, const float* __restric
 // Tsrc: the m x m symmetric matrix (row stride ls; global or LDS, read once).  Rf: LDS, m rows of stride lt (odd), receives
 // the reflectors (column j below the sub-diagonal).  m <= 128.
 // work: LDS scratch of tri_work_floats(m, k) floats, 16-byte aligned.  1 <= k <= min(m, TE_MAXK); KS = tri_lane_stride(k).
+// More than TE_BATCH eigenpairs are found in passes of TE_BATCH (the eigenvalues' multisection, the inverse iteration and
+// the back-transformation each run once per pass on the same scratch).
 // On return (after its own final barrier) *theta points at the k eigenvalues, largest first, and *W at the k unit
 // eigenvectors, W[i * m + t].  Every thread of the workgroup must call.
 template <int KS>
@@ -291,9 +296,10 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
     }
     __syncthreads();
   }
-  {
+  for (int g0 = 0; g0 < k; g0 += TE_BATCH) {                   // eigenvalues g0 .. g0 + kb - 1 (from the top)
+    const int kb = min(TE_BATCH, k - g0);
     int kp = 1;
-    while (kp < k) kp <<= 1;
+    while (kp < kb) kp <<= 1;
     const int S = TE_THREADS / kp;                             // shifts per eigenvalue and round (a multiple of 64)
     const int g = tid / S, s = tid - g * S;
     // round one left a bracket of 1/513 of the spectrum's extent; each further round divides it by S + 1
@@ -301,72 +307,74 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
     for (int round = 0; round < rounds; ++round) {
       bool below = false;
       float a = 0.f, b = 0.f;
-      if (g < k) {
-        a = br_a[g]; b = br_b[g];
-        below = sturm(a + (b - a) * ((float)(s + 1) / (float)(S + 1))) <= m - 1 - g;
+      if (g < kb) {
+        a = br_a[g0 + g]; b = br_b[g0 + g];
+        below = sturm(a + (b - a) * ((float)(s + 1) / (float)(S + 1))) <= m - 1 - (g0 + g);
       }
       const int c = __popcll(__ballot(below));
       if (lane == 0) wc[wave] = c;
       __syncthreads();
-      if (tid < k) {
-        const float a2 = br_a[tid], b2 = br_b[tid];
+      if (tid < kb) {
+        const float a2 = br_a[g0 + tid], b2 = br_b[g0 + tid];
         int p = 0;
         for (int w = 0; w < S / 64; ++w) p += wc[tid * (S / 64) + w];
         // counts are monotone in the shift: the first p shifts are at or below the eigenvalue
-        if (p > 0) br_a[tid] = a2 + (b2 - a2) * ((float)p / (float)(S + 1));
-        if (p < S) br_b[tid] = a2 + (b2 - a2) * ((float)(p + 1) / (float)(S + 1));
+        if (p > 0) br_a[g0 + tid] = a2 + (b2 - a2) * ((float)p / (float)(S + 1));
+        if (p < S) br_b[g0 + tid] = a2 + (b2 - a2) * ((float)(p + 1) / (float)(S + 1));
       }
       __syncthreads();
     }
-    if (tid < k) th[tid] = 0.5f * (br_a[tid] + br_b[tid]);
+    if (tid < kb) th[g0 + tid] = 0.5f * (br_a[g0 + tid] + br_b[g0 + tid]);
     __syncthreads();
   }
 
-  // ---- 3. eigenvectors of S: inverse iteration, lane i of wave 0 owns eigenvector i
-  if (wave == 0 && lane < k) {
-    float* za = zz + lane;
-    float* zb = lu + 5 * m * KS + lane;                        // second vector buffer (behind the factors)
-    te_factor<KS>(dv, ev, m, th[lane], scal[3], lu + lane);
-    for (int j = 0; j < m; ++j) {
-      const uint32_t h = ((uint32_t)j * 2654435761u + (uint32_t)lane * 40503u + 12345u) >> 8;
-      za[j * KS] = (float)(h & 0xffffu) * (1.f / 65536.f) - 0.5f;
+  // ---- 3. eigenvectors of S: inverse iteration, lane i of wave 0 owns eigenvector b0 + i; 4. back-transformation
+  // w = H_0 H_1 ... H_{m-3} z, one wave per eigenvector, lane l holds entries l and l + 64
+  float* Wv = (k > TE_BATCH) ? zz + m * KS : lu;               // [k][m]; a single pass leaves it where the factors were
+  for (int b0 = 0; b0 < k; b0 += TE_BATCH) {
+    const int kb = min(TE_BATCH, k - b0);
+    if (wave == 0 && lane < kb) {
+      float* za = zz + lane;
+      float* zb = lu + 5 * m * KS + lane;                      // second vector buffer (behind the factors)
+      te_factor<KS>(dv, ev, m, th[b0 + lane], scal[3], lu + lane);
+      for (int j = 0; j < m; ++j) {
+        const uint32_t h = ((uint32_t)j * 2654435761u + (uint32_t)(b0 + lane) * 40503u + 12345u) >> 8;
+        za[j * KS] = (float)(h & 0xffffu) * (1.f / 65536.f) - 0.5f;
+      }
+      // Three solves.  Between them the iterate is only rescaled by its largest magnitude (folded into the next solve's
+      // first pass: the squares of the last normalisation cannot overflow, and nothing else depends on the length).
+      float big = 1.f;
+      for (int it = 0; it < 3; ++it) {
+        te_forward<KS>(lu + lane, m, za, zb, (big > 0.f && big < INFINITY) ? 1.f / big : 1.f);
+        big = te_backward<KS>(lu + lane, m, zb, za);
+      }
+      // unit length; this pass also clears what is left of the start vector in blocks that S decouples from this
+      // eigenvalue (an exactly zero sub-diagonal entry): some twenty orders of magnitude down, exact zeros in exact arithmetic
+      te_normalise<KS>(m, za, zb, big, true);
+      { float* t = za; za = zb; zb = t; }
+      if (za != zz + lane) for (int j = 0; j < m; ++j) zz[j * KS + lane] = za[j * KS];
     }
-    // Three solves.  Between them the iterate is only rescaled by its largest magnitude (folded into the next solve's
-    // first pass: the squares of the last normalisation cannot overflow, and nothing else depends on the length).
-    float big = 1.f;
-    for (int it = 0; it < 3; ++it) {
-      te_forward<KS>(lu + lane, m, za, zb, (big > 0.f && big < INFINITY) ? 1.f / big : 1.f);
-      big = te_backward<KS>(lu + lane, m, zb, za);
+    __syncthreads();
+    float w0 = 0.f, w1 = 0.f;
+    if (wave < kb) {
+      w0 = (lane < m) ? zz[lane * KS + wave] : 0.f;
+      w1 = (lane + 64 < m) ? zz[(lane + 64) * KS + wave] : 0.f;
+      for (int j = m - 3; j >= 0; --j) {
+        const float beta = bet[j];
+        if (beta == 0.f) continue;
+        const float v0 = (lane > j && lane < m) ? Rf[lane * lt + j] : 0.f;
+        const float v1 = (lane + 64 > j && lane + 64 < m) ? Rf[(lane + 64) * lt + j] : 0.f;
+        const float s = beta * te_wave_sum(fmaf(v0, w0, v1 * w1));
+        w0 = fmaf(-s, v0, w0); w1 = fmaf(-s, v1, w1);
+      }
     }
-    // unit length; this pass also clears what is left of the start vector in blocks that S decouples from this eigenvalue
-    // (an exactly zero sub-diagonal entry): some twenty orders of magnitude down, exact zeros in exact arithmetic
-    te_normalise<KS>(m, za, zb, big, true);
-    { float* t = za; za = zb; zb = t; }
-    if (za != zz + lane) for (int j = 0; j < m; ++j) zz[j * KS + lane] = za[j * KS];
-  }
-  __syncthreads();
-
-  // ---- 4. back-transformation w = H_0 H_1 ... H_{m-3} z, one wave per eigenvector; lane l holds entries l and l + 64
-  float* Wv = lu;                                              // the factors are dead
-  float w0 = 0.f, w1 = 0.f;
-  if (wave < k) {
-    w0 = (lane < m) ? zz[lane * KS + wave] : 0.f;
-    w1 = (lane + 64 < m) ? zz[(lane + 64) * KS + wave] : 0.f;
-    for (int j = m - 3; j >= 0; --j) {
-      const float beta = bet[j];
-      if (beta == 0.f) continue;
-      const float v0 = (lane > j && lane < m) ? Rf[lane * lt + j] : 0.f;
-      const float v1 = (lane + 64 > j && lane + 64 < m) ? Rf[(lane + 64) * lt + j] : 0.f;
-      const float s = beta * te_wave_sum(fmaf(v0, w0, v1 * w1));
-      w0 = fmaf(-s, v0, w0); w1 = fmaf(-s, v1, w1);
+    __syncthreads();                                           // every wave has read its column of zz / lu is free
+    if (wave < kb) {
+      if (lane < m) Wv[(b0 + wave) * m + lane] = w0;
+      if (lane + 64 < m) Wv[(b0 + wave) * m + lane + 64] = w1;
     }
+    __syncthreads();
   }
-  __syncthreads();                                             // every wave has read its column of zz / lu is free
-  if (wave < k) {
-    if (lane < m) Wv[wave * m + lane] = w0;
-    if (lane + 64 < m) Wv[wave * m + lane + 64] = w1;
-  }
-  __syncthreads();
   if (wave == 0) {                                             // Gram-Schmidt over the k vectors, in order
     for (int i = 0; i < k; ++i) {
       float x0 = (lane < m) ? Wv[i * m + lane] : 0.f, x1 = (lane + 64 < m) ? Wv[i * m + lane + 64] : 0.f;

@@ -786,7 +786,7 @@ def test_residual_rank_below_requested_rank(gpu, support, rank, k_want):
         assert all(r.skipped == 1 for r in reps)
 
 
-@pytest.mark.parametrize("dtype,d,rank", [("bf16", 128, 4), ("f32", 64, 2), ("bf16", 128, 8)])
+@pytest.mark.parametrize("dtype,d,rank", [("bf16", 128, 4), ("f32", 64, 2), ("bf16", 128, 8), ("bf16", 128, 12)])
 def test_fast_path_is_close_to_the_svd_on_a_steep_residual_spectrum(gpu, dtype, d, rank):
     """App. H quotes a relative error near 1e-4 for three steps: that needs a gap behind the k-th singular value of R.
     Values = `rank` strong directions + weak noise give one; the device's fast path then matches the oracle's fast path to
@@ -838,7 +838,7 @@ def test_fast_path_argument_errors(gpu):
     K, V, Q = si.make_cache(cfg, 0, threads=8)
     from paper_2604_13349_amd import binding as B
     for bad, rank in ((B.make_variant(subspace_iters=-1), 2), (B.make_variant(subspace_iters=65), 2),
-                      (B.make_variant(subspace_iters=3), 9), (B.make_variant(subspace_iters=3, subspace="all"), 2)):
+                      (B.make_variant(subspace_iters=3), 17), (B.make_variant(subspace_iters=3, subspace="all"), 2)):
         with pytest.raises(B.ObfError):
             gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, rank=rank, variant=bad)
     # the aggregate of the deleted rows has no subspace: the field is ignored there
