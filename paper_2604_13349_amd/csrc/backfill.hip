@@ -1512,15 +1512,15 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
   float* gram_part = (float*)(ws + w.gram_part);
   float* mats = (float*)(ws + w.mats);
   float* delta = (float*)(ws + w.delta);
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::mutex attr_mu;
+  static uint64_t attr_seen = 0;
+  once_per_device(attr_mu, attr_seen, [] {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_keep_gram_part<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 128 * 8);
     (void)hipFuncSetAttribute((const void*)k_bf_finalize<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 129 * 4);
     (void)hipFuncSetAttribute((const void*)k_bf_lead<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)sizeof(float) * (128 * 129 + 4 + tri_work_floats(128, TE_MAXK) + TE_MAXK * 128));
-    attr_done = true;
-  }
+  });
   if (var.subspace_iters > 0 && !(var.flags & VF_NAIVE) &&
       (rank > TE_MAXK || (var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR)) || m.d > 128)) {
     set_error("backfill: the subspace iteration takes the rank rule with pca_rank <= 16 and head_dim <= 128");

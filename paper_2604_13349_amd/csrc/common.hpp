@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <mutex>
 #include "obf_relay.h"
 
 namespace obf {
@@ -248,6 +249,19 @@ obf_status_t launch_quant_rows(const void* X, long n_rows, int d, int dtype, int
                                uint16_t* zero, hipStream_t st);
 obf_status_t launch_dequant_rows(const uint8_t* codes, const uint16_t* scale, const uint16_t* zero, long n_rows, int d, int dtype,
                                  int bits, void* X, hipStream_t st);
+// Runs `set` (hipFuncSetAttribute calls) once per device: kernel attributes belong to the device that is current when they
+// are set.  `seen` and `mu` are the caller's function-local statics; the device's bit is set only after `set` has returned,
+// so a second host thread either waits for the mutex or finds the attributes in place.
+template <class F>
+inline void once_per_device(std::mutex& mu, uint64_t& seen, F set) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { set(); return; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (seen & (1ull << dev)) return;
+  set();
+  seen |= 1ull << dev;
+}
+
 // idx[i] += offset for every valid (non-negative) entry
 obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream_t st);
 

@@ -324,12 +324,12 @@ template <typename T>
 static obf_status_t run_small(const Dims& m, const void* V, const float* scores, const int32_t* idx,
                               const int32_t* n_keep, int32_t max_budget, int32_t rank, HeadState* state, float* basis,
                               hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::mutex attr_mu;
+  static uint64_t attr_seen = 0;
+  once_per_device(attr_mu, attr_seen, [] {
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 129 * 4);
     (void)hipFuncSetAttribute((const void*)k_bf_keep_basis_small<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 129 * 4);
-    attr_done = true;
-  }
+  });
   const size_t nmax = (size_t)min(max_budget, m.d);
   hipLaunchKernelGGL((k_bf_keep_basis_small<T, false>), dim3(m.heads), dim3(KS_THREADS), ks_smem(min(nmax, (size_t)96), m.d), st,
                      (const T*)V, scores, idx, n_keep, m.N, m.d, max_budget, rank, state, basis, m.scs, m.kvs);
