@@ -182,7 +182,15 @@ obf_status_t obf_compress_relay_layerwise(const obf_shape_t* shape, const void* 
  *                      their share of the trace).  Needs subspace = OBF_SUBSPACE_RANK, rank <= 16 and head_dim <= 128,
  *                      else OBF_ERR_UNSUPPORTED.  With diag != NULL the exact directions are computed too and
  *                      diag.fast_err reports the distance between the two (this costs the exact route's time).
- * `rank` = 0 is plain eviction under every variant.  The per-token alternative of App. D is not provided. */
+ *   per_token          "Per-token" (App. D names it without a formula; this is a stated reading): the deleted tokens are
+ *                      shared out among the retained slots by key cosine similarity (the routing of obf_cache_merge),
+ *                      slot t receives delta_t = n_keep * a_del / (a_keep + eps) * Proj_C(sum over its tokens of
+ *                      A_j R_j / (a_del + eps)) instead of delta (C: the subspace of Eq. 5), so that the mean over the
+ *                      slots is Eq. 6's delta - which is what delta_out and diag still report.  A slot no token is routed
+ *                      to keeps its value.  Fused calls only (the routing reads the keys): obf_backfill_variant returns
+ *                      OBF_ERR_UNSUPPORTED for it.  Combines with no_projection, no_scaling and subspace_iters; needs
+ *                      subspace = OBF_SUBSPACE_RANK, rank <= 16, head_dim <= 128, no naive_aggregation, no attn_inject.
+ * `rank` = 0 is plain eviction under every variant. */
 #define OBF_SUBSPACE_RANK 0
 #define OBF_SUBSPACE_ALL 1
 #define OBF_SUBSPACE_EVR 2
@@ -194,6 +202,7 @@ typedef struct obf_variant_t {
   int32_t naive_aggregation;
   int32_t attn_inject;
   int32_t subspace_iters;
+  int32_t per_token;
 } obf_variant_t;
 
 /* obf_backfill with an ablation variant (App. D); variant == NULL is obf_backfill itself.  Arguments, layouts,

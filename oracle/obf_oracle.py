@@ -37,7 +37,8 @@ The ablations of App. D are the flags of Variant; readings taken there:
     C <- orth(C G) on G = R^T R from a fixed orthonormal start (start_rows), with
     k = min(pca_rank, d - r, |P_del|) rows of which dependent ones are dropped; fast_err reports
     the distance of the resulting Delta from the SVD's.
-  The per-token variant is not stated precisely enough to restate and is absent.
+  * Per-token (App. D): not stated precisely enough to restate; per_token_offsets is a stated reading, unpinned
+    against the paper, pinned by the properties the reading itself fixes.
 The cache-merging comparison system of App. E (select, route by key cosine, merge by
 attention mass) is merge_head; readings: the first maximum wins the routing, a key of
 zero norm has cosine 0 with everything, slots that receive nothing stay bit copies.
@@ -152,6 +153,7 @@ class Variant:
     no_scaling: bool = False         # component ablation "No Scaling"
     naive: bool = False              # component ablation "Naive Aggregation"
     attn_inject: bool = False        # alternative design "Attn-inject"
+    per_token: bool = False          # alternative design "Per-token" (App. D), the reading stated at per_token_offsets
     subspace_iters: int = 0          # > 0: the Gram subspace iteration of App. H with this many steps (the paper runs 3) instead of the SVD
 
 
@@ -199,8 +201,28 @@ def inject(V_keep: np.ndarray, A_keep: np.ndarray, a_keep: float, delta: np.ndar
     return V_keep + delta[None, :]
 
 
-def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int, variant: Variant = Variant()):
-    """OBF for one head (Eq. 2-7, Alg. 3).  V [N, d] float64, A [N], idx ascending.
+def per_token_offsets(R: np.ndarray, w: np.ndarray, C: np.ndarray, route_del: np.ndarray, B: int, scale: float) -> np.ndarray:
+    """The "Per-token" alternative of App. D: one direction delta_t per retained slot t, "analogous to Eq. 6 but with per-t
+    residual weighting".  The paper gives no formula; this is a READING (parity against the paper unpinned), built only
+    from pieces the paper does define:
+      * the deleted tokens are shared out among the retained slots by the routing rule of App. E (key cosine, first
+        maximum): route_del[i] is the slot of deleted token i;
+      * slot t's residual mean keeps Eq. 4's weights but only over its own tokens:  rbar_t = sum_{pi(j) = t} w_j R_j;
+      * Eq. 5's projection onto the same subspace C and Eq. 6's demand ratio;
+      * the factor B = |P_keep| that App. D's Attn-inject uses for its per-slot shares, so that the mean over the slots
+        of delta_t is exactly the method's single delta (sum_t rbar_t = rbar).
+    R [n_del, d] residuals, w [n_del] Eq. 4 weights, C [k, d], scale = a_del / (a_keep + eps) (1 under No Scaling).
+    Returns delta [B, d]; a slot nothing was routed to gets zero."""
+    d = R.shape[1]
+    out = np.zeros((B, d))
+    for i in range(R.shape[0]):                            # ascending token order; one term at a time
+        out[route_del[i]] += w[i] * R[i]
+    return B * scale * ((out @ C.T) @ C)
+
+
+def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int, variant: Variant = Variant(), K: np.ndarray = None):
+    """OBF for one head (Eq. 2-7, Alg. 3).  V [N, d] float64, A [N], idx ascending.  K [N, d] float64: only the Per-token
+    alternative reads the keys (its routing).
 
     Returns (V_star [B, d] float64 before output rounding, HeadDiag).
     """
@@ -292,6 +314,15 @@ def backfill(V: np.ndarray, A: np.ndarray, idx: np.ndarray, rank: int, variant: 
     diag.delta = delta
     diag.ivn = float(np.linalg.norm(delta))
     diag.skipped = 0
+    if variant.per_token:
+        if K is None:
+            raise ValueError("the Per-token alternative routes by the keys")
+        if variant.attn_inject or variant.subspace != "rank":
+            raise ValueError("Per-token combines with No Projection, No Scaling and the fast path only")
+        Cu = Cf if variant.subspace_iters > 0 else C
+        route = merge_routes(K, idx)
+        scale = 1.0 if variant.no_scaling else diag.a_del / (diag.a_keep + EPS)
+        return V_keep + per_token_offsets(R, w, Cu, route[dele], idx.size, scale), diag    # delta (above) is their mean
     return inject(V_keep, A[idx], diag.a_keep, delta, variant), diag                         # Eq. 7
 
 
@@ -359,7 +390,7 @@ def compress_head(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget: 
     Qr = decode(Q_io, dtype).reshape(-1, K.shape[1])
     A = attention_mass(K, Qr)                               # the sink tokens are keys like any other
     idx = sink + select_topk(A[sink:], budget)              # TopK_B over Omega
-    V_star, diag = backfill(V[sink:], A[sink:], idx - sink, rank, variant)
+    V_star, diag = backfill(V[sink:], A[sink:], idx - sink, rank, variant, K[sink:] if variant.per_token else None)
     if diag.skipped:
         V_out = np.asarray(V_io)[idx].copy()               # identity: a bit copy, not a re-rounding
     else:
@@ -410,7 +441,8 @@ def compress_layer(K_io: np.ndarray, V_io: np.ndarray, Q_io: np.ndarray, budget:
     heads = []
     for h in range(H):
         V = decode(V_io[h], dtype)
-        V_star, diag = backfill(V[sink:], masses[h][sink:], idx - sink, rank, variant)
+        V_star, diag = backfill(V[sink:], masses[h][sink:], idx - sink, rank, variant,
+                                decode(K_io[h], dtype)[sink:] if variant.per_token else None)
         if diag.skipped:
             V_out = np.asarray(V_io[h])[idx].copy()
         else:

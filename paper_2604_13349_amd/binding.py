@@ -36,7 +36,7 @@ class _Variant(C.Structure):
     """obf_variant_t."""
     _fields_ = [("no_projection", C.c_int32), ("subspace", C.c_int32), ("evr_tau", C.c_float),
                 ("no_scaling", C.c_int32), ("naive_aggregation", C.c_int32), ("attn_inject", C.c_int32),
-                ("subspace_iters", C.c_int32)]
+                ("subspace_iters", C.c_int32), ("per_token", C.c_int32)]
 
 
 class _Window(C.Structure):
@@ -49,11 +49,11 @@ OBF_SELECT_BAND_OVERFLOW = 1
 
 
 def make_variant(no_projection=False, subspace="rank", evr_tau=0.35, no_scaling=False, naive_aggregation=False,
-                 attn_inject=False, subspace_iters=0) -> _Variant:
+                 attn_inject=False, subspace_iters=0, per_token=False) -> _Variant:
     """obf_variant_t from keywords (subspace by its name or its number)."""
     code = SUBSPACE[subspace] if isinstance(subspace, str) else int(subspace)
     return _Variant(int(no_projection), code, float(evr_tau), int(no_scaling), int(naive_aggregation), int(attn_inject),
-                    int(subspace_iters))
+                    int(subspace_iters), int(per_token))
 
 
 def lib_path() -> str:

@@ -261,6 +261,7 @@ static obf_status_t make_variant(const obf_variant_t* v, Variant* out) {
   if (v->no_scaling) out->flags |= VF_NO_SCALING;
   if (v->naive_aggregation) out->flags |= VF_NAIVE;
   if (v->attn_inject) out->flags |= VF_ATTN_INJECT;
+  if (v->per_token) out->flags |= VF_PER_TOKEN;
   return OBF_OK;
 }
 
@@ -328,6 +329,9 @@ static obf_status_t compress_heads(int layerwise, Variant var, const Dims& mf, i
   }
   if (k_beside) { const obf_status_t js = stream_after(st, aux, EV_KROWS_JOIN); if (rs == OBF_OK) rs = js; }
   OBF_TRY(rs);
+  if ((var.flags & VF_PER_TOKEN) && rank > 0)                    // needs the gathered keys: after the join above
+    OBF_TRY(launch_per_token_inject(m, w, base, K, V, scores, idx, n_keep, max_budget, K_out, V_out,
+                                    (var.flags & VF_NO_SCALING) ? 1 : 0, st));
   if (diag && !layerwise) OBF_TRY(launch_diag_flags(diag, (const int32_t*)(base + w.sel_flags), m.heads, st));
   return launch_idx_offset(idx, (size_t)m.heads * max_budget, sink, st);   // back to the head's own token numbers
 }
@@ -398,6 +402,7 @@ obf_status_t obf_backfill_variant(const obf_shape_t* shape, const void* V, const
                                   void* ws, size_t ws_bytes, void* stream) {
   Variant var;
   OBF_TRY(make_variant(variant, &var));
+  if (var.flags & VF_PER_TOKEN) { set_error("the per-token variant routes by the keys: use a fused call"); return OBF_ERR_UNSUPPORTED; }
   OBF_TRY(check_shape(shape));
   OBF_NONNULL(V); OBF_NONNULL(scores); OBF_NONNULL(idx); OBF_NONNULL(n_keep); OBF_NONNULL(V_out);
   if (max_budget < 0) { set_error("max_budget < 0"); return OBF_ERR_INVALID_ARG; }

@@ -1323,6 +1323,18 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
     }
     __syncthreads();
   };
+  // Per-token alternative (App. D): the subspace goes to the head's second scratch matrix in head_dim coordinates
+  // (row i: sum_t Cb[i][t] Z[t][:]) for the kernel that forms the per-slot directions.
+  auto export_basis = [&](const float* Cb, const int kk) {
+    if (!(vflags & VF_PER_TOKEN)) return;
+    float* Cg = mats + ((size_t)head * 3 + 1) * d * d;
+    for (int e = tid; e < kk * d; e += TE_THREADS) {
+      const int i = e / d, c = e - i * d;
+      float s = 0.f;
+      for (int t = 0; t < m; ++t) s = fmaf(Cb[i * m + t], Zg[(size_t)t * d + c], s);
+      Cg[e] = s;
+    }
+  };
   int k_used = 0;
   float revr = 0.f, fast_err = -1.f;
   if (iters <= 0 || diag != nullptr) {
@@ -1347,6 +1359,7 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
     revr = (k_used > 0) ? s_off : 0.f;
     __syncthreads();
     project(Wk, k_used);
+    if (iters <= 0) export_basis(Wk, k_used);
   }
   if (iters > 0) {
     if (diag != nullptr && tid < m) dex[tid] = dcomp[tid];     // the direct route's Delta, for the error report
@@ -1437,6 +1450,7 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
       revr = s_off;
       __syncthreads();
       project(Ya, k_used);
+      export_basis(Ya, k_used);
     } else {
       if (tid < m) dcomp[tid] = 0.f;
       __syncthreads();
@@ -1526,6 +1540,12 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     set_error("backfill: the subspace iteration takes the rank rule with pca_rank <= 16 and head_dim <= 128");
     return OBF_ERR_UNSUPPORTED;
   }
+  if ((var.flags & VF_PER_TOKEN) &&
+      (rank > TE_MAXK || (var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR | VF_NAIVE | VF_ATTN_INJECT)) || m.d > 128)) {
+    set_error("backfill: the per-token variant takes the rank rule with pca_rank <= 16 and head_dim <= 128, without Naive Aggregation or Attn-inject");
+    return OBF_ERR_UNSUPPORTED;
+  }
+  void* V_inject = (var.flags & VF_PER_TOKEN) ? nullptr : V_out;   // Per-token: the per-slot directions are added by a later kernel
   if (var.skips_basis()) {
     if (basis_started) { set_error("backfill: a basis was started for a variant without one"); return OBF_ERR_INVALID_ARG; }
     ProfScope prof_(ST_KEEP_BASIS, st);
@@ -1581,12 +1601,14 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
     // (not under the Max-P / EVR rules, which need the whole spectrum).  Its LDS is sized for complements up to 3d/4 wide
     // (two workgroups per CU); without the projection every complement is all of R^d, and it is sized for that.
     // The fast path of App. H lives in that kernel too and then takes every head that reaches Eq. 4.
+    // So does the Per-token alternative (it needs the subspace itself, which only that kernel exports).
     const int iters = (var.flags & VF_NAIVE) ? 0 : var.subspace_iters;
+    const bool all_lead = iters > 0 || (var.flags & VF_PER_TOKEN);
     const bool lead_ok = rank > 0 && rank <= TE_MAXK && !(var.flags & (VF_SUBSPACE_ALL | VF_SUBSPACE_EVR | VF_NAIVE)) &&
-                         (iters > 0 || !(min_budget > m.d && m.N > m.d && !var.skips_basis()));
+                         (all_lead || !(min_budget > m.d && m.N > m.d && !var.skips_basis()));
     LeadJob* lead = lead_ok ? (LeadJob*)(ws + w.lead_job) : (LeadJob*)nullptr;
-    const int m_direct_max = ((var.flags & VF_NO_PROJECTION) || iters > 0) ? m.d : 3 * m.d / 4;
-    const int m_direct_min = iters > 0 ? 1 : FN_DIRECT_MIN;
+    const int m_direct_max = ((var.flags & VF_NO_PROJECTION) || all_lead) ? m.d : 3 * m.d / 4;
+    const int m_direct_min = all_lead ? 1 : FN_DIRECT_MIN;
     // every budget above head_dim: heads that need the finalisation are rare (the certificate settles the others), so one
     // launch with the large LDS size serves both classes instead of two launches that mostly exit at once
     const bool single = min_budget > m.d && m.N > m.d && !var.skips_basis();
@@ -1594,7 +1616,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
       const size_t lds = (cls == 0) ? sizeof(float) * (size_t)fn_small_floats(m.d) : 2 * one;
       hipLaunchKernelGGL(k_bf_finalize<T>, dim3(m.heads), dim3(FN_THREADS), lds, st, m.N, m.d,
                          w.nstat, rank, state, basis, gram_part, mats, delta, delta_out, diag,
-                         (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, cls, scores, idx,
+                         (rank > 0 && max_budget > 0) ? (T*)V_inject : (T*)nullptr, max_budget, cls, scores, idx,
                          var.flags, var.evr_tau, m.scs, (max_budget < m.d && rank > 0) ? (float*)(ws + w.rot) : (float*)nullptr,
                          lead, m_direct_min, m_direct_max);
     }
@@ -1604,7 +1626,7 @@ static obf_status_t run(const Dims& m, const Workspace& w, char* ws, const void*
       const size_t lds = sizeof(float) * ((size_t)m_direct_max * (m_direct_max | 1) + 4 + tri_work_floats(m_direct_max, kq) +
                                           (iters > 0 ? (size_t)kq * m.d : 0));
       hipLaunchKernelGGL(k_bf_lead<T>, dim3(m.heads), dim3(TE_THREADS), lds, st, m.d, rank, state, mats, delta, delta_out, diag,
-                         (rank > 0 && max_budget > 0) ? (T*)V_out : (T*)nullptr, max_budget, scores, idx, var.flags, m.scs,
+                         (rank > 0 && max_budget > 0) ? (T*)V_inject : (T*)nullptr, max_budget, scores, idx, var.flags, m.scs,
                          (const LeadJob*)lead, iters);
       if (check_launch("backfill leading eigenpairs") != OBF_OK) return OBF_ERR_HIP;
     }

@@ -228,7 +228,7 @@ obf_status_t launch_select_layerwise(const Dims& m, const Workspace& w, char* ws
                                      int32_t* n_keep, const void* K, const void* Q, const double* row_lse,
                                      hipStream_t st);
 // Ablation variants of App. D as the kernels see them (obf_variant_t checked and packed).
-enum : int { VF_NO_PROJECTION = 1, VF_SUBSPACE_ALL = 2, VF_SUBSPACE_EVR = 4, VF_NO_SCALING = 8, VF_NAIVE = 16, VF_ATTN_INJECT = 32 };
+enum : int { VF_NO_PROJECTION = 1, VF_SUBSPACE_ALL = 2, VF_SUBSPACE_EVR = 4, VF_NO_SCALING = 8, VF_NAIVE = 16, VF_ATTN_INJECT = 32, VF_PER_TOKEN = 64 };
 struct Variant {
   int flags = 0;
   float evr_tau = 0.f;
@@ -244,6 +244,11 @@ obf_status_t launch_append_message(int heads, int row_bytes, const void* prev_K,
 obf_status_t launch_cache_merge(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V, const float* scores,
                                 const int32_t* idx, const int32_t* n_keep, int32_t max_budget, const void* K_out,
                                 void* V_out, int32_t* route_out, hipStream_t st);
+// The Per-token alternative of App. D after a back-fill that left its subspace in the workspace (flag VF_PER_TOKEN) and
+// did not inject: routes as in the cache merging, then one direction per retained slot added to V_out.
+obf_status_t launch_per_token_inject(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V,
+                                     const float* scores, const int32_t* idx, const int32_t* n_keep, int32_t max_budget,
+                                     const void* K_out, void* V_out, int no_scaling, hipStream_t st);
 // Per-row int8 / int4 codes of relay rows and back (App. E's stacked quantisation, the reading stated in quant.hip).
 obf_status_t launch_quant_rows(const void* X, long n_rows, int d, int dtype, int bits, uint8_t* codes, uint16_t* scale,
                                uint16_t* zero, hipStream_t st);

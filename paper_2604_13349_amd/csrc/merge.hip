@@ -146,21 +146,43 @@ __global__ __launch_bounds__(MG_THREADS) void k_mg_unroute_kept(const int32_t* _
   if (t < n_keep[head] && t < max_budget) route[(size_t)head * N + idx[(size_t)head * max_budget + t]] = -1;
 }
 
+// The same per-slot sums serve the Per-token alternative of App. D (PER_TOKEN; the reading: the deleted tokens are shared
+// out among the slots by the routing above, slot t's direction is B a_del / (a_keep + eps) times the projection of
+// sum_{pi(j) = t} A_j v_j / (a_del + eps) onto the residual subspace C of Eq. 5 - C's rows lie in the complement of
+// the retained span, so projecting the values is projecting their residuals; the mean over the slots is Eq. 6's delta).
+// There the weights are the attention masses themselves, the sums are projected with the k_used rows of C that the
+// back-fill kernel left in the head's scratch, and the result is added to the slot's value.
+//
 // Merge.  A workgroup owns 32 consecutive retained slots, a wave eight of them.  Every wave scans the head's route list
 // 64 tokens at a time and, for each token routed to one of its slots, in ascending token order, adds the weighted value
 // row into that slot's running sum (LDS, one lane per pair of columns): the order of the additions is fixed, so the
 // result is the same on every run.  Slots that received nothing are left as the bit copies the gather wrote.
-template <typename T>
+template <typename T, bool PER_TOKEN>
 __global__ __launch_bounds__(MG_THREADS) void k_mg_merge(const T* __restrict__ V, const float* __restrict__ scores,
                                                          const int32_t* __restrict__ idx, const int32_t* __restrict__ n_keep,
                                                          const int32_t* __restrict__ route, int N, int d, int kvs, int scs,
-                                                         int max_budget, T* __restrict__ V_out) {
+                                                         int max_budget, T* __restrict__ V_out,
+                                                         const HeadState* __restrict__ state /*PER_TOKEN*/,
+                                                         const float* __restrict__ mats /*PER_TOKEN: [heads][3][d*d], C in the second matrix*/,
+                                                         int no_scaling) {
   __shared__ float acc[4][MG_SLOTS_PER_WAVE][MG_D];
   __shared__ float a_slot[4][MG_SLOTS_PER_WAVE];
   __shared__ int cnt[4][MG_SLOTS_PER_WAVE];
+  __shared__ float cb[PER_TOKEN ? 16 : 1][MG_D];               // the rows of C
   const int head = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nk = min(n_keep[head], max_budget);
+  int kc = 0;
+  float pt_scale = 0.f;
+  if (PER_TOKEN) {
+    const HeadState hs = state[head];
+    if (!hs.active || hs.k_used <= 0) return;                  // no injection for this head (uniform over the workgroup)
+    kc = min(hs.k_used, 16);
+    const float* Cg = mats + ((size_t)head * 3 + 1) * d * d;
+    for (int e = threadIdx.x; e < kc * d; e += MG_THREADS) cb[e / d][e % d] = Cg[e];
+    pt_scale = (float)((double)hs.n_keep * (no_scaling ? 1.0 : hs.a_del / (hs.a_keep + kEps)) / (hs.a_del + kEps));
+    __syncthreads();
+  }
   const int slot0 = blockIdx.x * MG_SLOTS_PER_WG + wave * MG_SLOTS_PER_WAVE;
   if (slot0 >= nk) return;                                     // whole wave: nothing to own (no barrier below)
   const float* sc = scores + (size_t)head * scs;
@@ -182,7 +204,7 @@ __global__ __launch_bounds__(MG_THREADS) void k_mg_merge(const T* __restrict__ V
       mask &= mask - 1;
       const int sl = __shfl((int)local, l);
       const int jj = base + l;
-      const float w = (float)((double)sc[jj] / ((double)a_slot[wave][sl] + kEps));
+      const float w = PER_TOKEN ? sc[jj] : (float)((double)sc[jj] / ((double)a_slot[wave][sl] + kEps));
       const T* vr = Vh + (size_t)jj * d;
       for (int c = lane; c < d; c += 64) acc[wave][sl][c] = fmaf(w, Elem<T>::load(vr + c), acc[wave][sl][c]);
       if (lane == 0) cnt[wave][sl] += 1;
@@ -192,13 +214,30 @@ __global__ __launch_bounds__(MG_THREADS) void k_mg_merge(const T* __restrict__ V
   for (int sl = 0; sl < MG_SLOTS_PER_WAVE; ++sl) {
     if (slot0 + sl >= nk || cnt[wave][sl] == 0) continue;
     T* o = V_out + ((size_t)head * max_budget + slot0 + sl) * d;
-    for (int c = lane; c < d; c += 64) Elem<T>::store(o + c, Elem<T>::load(o + c) + acc[wave][sl][c]);
+    if (PER_TOKEN) {
+      // lane l holds columns l and l + 64 of the slot's sum; its coefficient on every row of C, then the combination
+      const float u0 = (lane < d) ? acc[wave][sl][lane] : 0.f, u1 = (lane + 64 < d) ? acc[wave][sl][lane + 64] : 0.f;
+      float d0 = 0.f, d1 = 0.f;
+      for (int i = 0; i < kc; ++i) {
+        const float c0 = (lane < d) ? cb[i][lane] : 0.f, c1 = (lane + 64 < d) ? cb[i][lane + 64] : 0.f;
+        float g = fmaf(u0, c0, u1 * c1);
+        for (int off = 32; off > 0; off >>= 1) g += __shfl_xor(g, off);
+        d0 = fmaf(g, c0, d0); d1 = fmaf(g, c1, d1);
+      }
+      if (lane < d) Elem<T>::store(o + lane, fmaf(pt_scale, d0, Elem<T>::load(o + lane)));
+      if (lane + 64 < d) Elem<T>::store(o + lane + 64, fmaf(pt_scale, d1, Elem<T>::load(o + lane + 64)));
+    } else {
+      for (int c = lane; c < d; c += 64) Elem<T>::store(o + c, Elem<T>::load(o + c) + acc[wave][sl][c]);
+    }
   }
 }
 
-obf_status_t launch_cache_merge(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V, const float* scores,
-                                const int32_t* idx, const int32_t* n_keep, int32_t max_budget, const void* K_out,
-                                void* V_out, int32_t* route_out, hipStream_t st) {
+// steps (ii) and (iii); per_token: the per-slot directions of App. D's Per-token alternative instead of the merge
+static obf_status_t run_merge(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V, const float* scores,
+                              const int32_t* idx, const int32_t* n_keep, int32_t max_budget, const void* K_out,
+                              void* V_out, int32_t* route_out, hipStream_t st, bool per_token, int no_scaling) {
+  const HeadState* state = (const HeadState*)(ws + w.head_state);
+  const float* mats = (const float*)(ws + w.mats);
   if (max_budget == 0) {                                         // nothing retained: nothing to route to
     if (route_out) {
       const size_t n = (size_t)m.heads * m.N;
@@ -229,11 +268,27 @@ obf_status_t launch_cache_merge(const Dims& m, const Workspace& w, char* ws, con
                      n_keep, m.N, max_budget, route);
   if (check_launch("merge unroute") != OBF_OK) return OBF_ERR_HIP;
   dim3 gm((max_budget + MG_SLOTS_PER_WG - 1) / MG_SLOTS_PER_WG, m.heads);
-  if (bf) hipLaunchKernelGGL(k_mg_merge<uint16_t>, gm, dim3(MG_THREADS), 0, st, (const uint16_t*)V, scores, idx, n_keep, route, m.N,
-                             m.d, m.kvs, m.scs, max_budget, (uint16_t*)V_out);
-  else hipLaunchKernelGGL(k_mg_merge<float>, gm, dim3(MG_THREADS), 0, st, (const float*)V, scores, idx, n_keep, route, m.N, m.d,
-                          m.kvs, m.scs, max_budget, (float*)V_out);
+#define OBF_MG_LAUNCH(T, PT) hipLaunchKernelGGL((k_mg_merge<T, PT>), gm, dim3(MG_THREADS), 0, st, (const T*)V, scores, idx, n_keep, \
+                                               route, m.N, m.d, m.kvs, m.scs, max_budget, (T*)V_out, state, mats, no_scaling)
+  if (bf && per_token) OBF_MG_LAUNCH(uint16_t, true);
+  else if (bf) OBF_MG_LAUNCH(uint16_t, false);
+  else if (per_token) OBF_MG_LAUNCH(float, true);
+  else OBF_MG_LAUNCH(float, false);
+#undef OBF_MG_LAUNCH
   return check_launch("merge values");
+}
+
+obf_status_t launch_cache_merge(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V, const float* scores,
+                                const int32_t* idx, const int32_t* n_keep, int32_t max_budget, const void* K_out,
+                                void* V_out, int32_t* route_out, hipStream_t st) {
+  return run_merge(m, w, ws, K, V, scores, idx, n_keep, max_budget, K_out, V_out, route_out, st, false, 0);
+}
+
+obf_status_t launch_per_token_inject(const Dims& m, const Workspace& w, char* ws, const void* K, const void* V,
+                                     const float* scores, const int32_t* idx, const int32_t* n_keep, int32_t max_budget,
+                                     const void* K_out, void* V_out, int no_scaling, hipStream_t st) {
+  if (m.d > MG_D) { set_error("per-token variant: head_dim above 128"); return OBF_ERR_UNSUPPORTED; }
+  return run_merge(m, w, ws, K, V, scores, idx, n_keep, max_budget, K_out, V_out, nullptr, st, true, no_scaling);
 }
 
 }  // namespace obf

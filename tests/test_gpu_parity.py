@@ -24,7 +24,8 @@ def _gpu_variant(v):
     """The binding's obf_variant_t for an oracle Variant (field by field, no arithmetic)."""
     from paper_2604_13349_amd import binding as B
     return B.make_variant(no_projection=v.no_projection, subspace=v.subspace, evr_tau=v.evr_tau, no_scaling=v.no_scaling,
-                          naive_aggregation=v.naive, attn_inject=v.attn_inject, subspace_iters=v.subspace_iters)
+                          naive_aggregation=v.naive, attn_inject=v.attn_inject, subspace_iters=v.subspace_iters,
+                          per_token=v.per_token)
 
 
 def _check_cfg(gpu, cfg, seed=0, budgets=None, rank=None, expect_active=None, max_budget=None, edit=None, variant=None):
@@ -920,6 +921,81 @@ def test_cache_merging_ragged_token_count_on_the_matrix_cores(gpu):
 
 
 # --------------------------------------------------------------------------- batch of right-padded samples (App. A.7)
+# --------------------------------------------------------------------------- the Per-token alternative (App. D; a stated reading)
+PER_TOKEN = {
+    "plain": O.Variant(per_token=True),
+    "no_scaling": O.Variant(per_token=True, no_scaling=True),
+    "fast_path_3": O.Variant(per_token=True, subspace_iters=3),
+    "no_projection": O.Variant(per_token=True, no_projection=True),
+}
+
+
+@pytest.mark.parametrize("name,cfgname", [("plain", "paper"), ("no_scaling", "paper"), ("fast_path_3", "paper"),
+                                          ("no_projection", "paper"), ("plain", "1s"), ("plain", "2s")])
+def test_per_token_alternative(gpu, name, cfgname):
+    """One direction per retained slot (the reading stated at the oracle's per_token_offsets): the fused variant call against
+    the oracle, slot by slot.  The routing is the cache-merging one; a route may differ from the oracle's only where the
+    oracle's two best cosines agree to COS_TIE, and the slots such a token touches are left out of the value check."""
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    var = PER_TOKEN[name]
+    cfg = si.shrink(si.CONFIGS[cfgname], n_layers=1)
+    K, V, Q = si.make_cache(cfg, 3, threads=8)
+    out = gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, variant=_gpu_variant(var))
+    mo = Bd.compress_relay_merge(gpu.to_dev(K, cfg.dtype), gpu.to_dev(V, cfg.dtype), gpu.to_dev(Q, cfg.dtype),
+                                 budget=cfg.budget, want_route=True)
+    torch.cuda.synchronize()
+    route = mo["route"].cpu().numpy()
+    checked = untouched = 0
+    for h in range(cfg.n_kv_heads):
+        tag = f"per-token {cfgname}/{name}[{h}]"
+        Qh = Q[0, h * cfg.group:(h + 1) * cfg.group]
+        ref = O.compress_head(K[0, h], V[0, h], Qh, cfg.budget, cfg.rank, cfg.dtype, var)
+        mref = O.merge_head(K[0, h], V[0, h], Qh, cfg.budget, cfg.dtype)
+        B = ref.idx.size
+        if not np.array_equal(out["idx"][0, h][:B], ref.idx):
+            continue                                         # a tolerated swap at the threshold (checked elsewhere)
+        assert np.array_equal(out["K_out"][0, h][:B], K[0, h][ref.idx])
+        dg = ref.diag
+        assert int(out["diag"][0, h]["skipped"]) == dg.skipped == 0 and int(out["diag"][0, h]["k_used"]) == dg.k_used
+        # delta_out is the slots' mean, i.e. Eq. 6's vector
+        g = parity.gap_factor(dg)
+        dn = np.linalg.norm(dg.delta)
+        assert np.linalg.norm(out["delta"][0, h].astype(np.float64) - dg.delta) <= 2e-3 * g * dn, f"{tag}: delta"
+        diff = np.nonzero(route[0, h] != mref.route)[0]
+        assert np.all(mref.cos_gap[diff] < COS_TIE), f"{tag}: routes differ beyond the cosine tie allowance"
+        tainted = set(route[0, h][diff].tolist()) | set(mref.route[diff].tolist())
+        touched = set(mref.route[mref.route >= 0].tolist())
+        Vk = O.decode(V[0, h][ref.idx], cfg.dtype)
+        got = O.decode(out["V_out"][0, h][:B], cfg.dtype)
+        for s_ in range(B):
+            if s_ in tainted:
+                continue
+            if s_ not in touched:
+                assert np.array_equal(out["V_out"][0, h][s_], V[0, h][ref.idx[s_]]), f"{tag}: slot {s_} must stay a bit copy"
+                untouched += 1
+                continue
+            want = ref.V_star[s_]
+            off = np.abs(want - Vk[s_]).max()
+            mag = np.maximum(np.abs(want), np.abs(got[s_]))
+            half_ulp = np.where(mag > 0, 2.0 ** (np.floor(np.log2(np.maximum(mag, 1e-300))) - 8.0), 0.0) if cfg.dtype == "bf16" else 0.0
+            bound = half_ulp * (1 + 1e-6) + 2e-3 * g * off + 1e-6 * np.abs(want).max()
+            assert np.all(np.abs(got[s_] - want) <= bound), f"{tag}: slot {s_} off by {np.abs(got[s_] - want).max():.3e} (offset {off:.3e})"
+            checked += 1
+    print(f"[per-token {cfgname}/{name}] slots value-checked {checked}, untouched bit copies {untouched}")
+    assert checked >= 4 * cfg.n_kv_heads
+
+
+def test_per_token_argument_errors(gpu):
+    cfg = si.shrink(si.CONFIGS["1s"], n_layers=1)
+    K, V, Q = si.make_cache(cfg, 0, threads=8)
+    from paper_2604_13349_amd import binding as B
+    for bad, rank in ((B.make_variant(per_token=True, attn_inject=True), 2), (B.make_variant(per_token=True, subspace="all"), 2),
+                      (B.make_variant(per_token=True, naive_aggregation=True), 2), (B.make_variant(per_token=True), 17)):
+        with pytest.raises(B.ObfError):
+            gpu.run_fused(cfg, K, V, Q, budget=cfg.budget, rank=rank, variant=bad)
+
+
 @pytest.mark.parametrize("sink", [0, 4])
 def test_batch_of_right_padded_samples_with_mixed_lengths(gpu, sink):
     """Four samples of different lengths in one right-padded buffer, one budget per sample (below and above head_dim),

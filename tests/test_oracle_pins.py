@@ -885,3 +885,67 @@ def test_fast_path_variant_reports_its_distance_from_the_svd_and_injects_its_own
     assert np.allclose(Vf - V[idx], df.delta[None, :], atol=1e-13)
     # still orthogonal to the retained values: every iterate stays in the row space of R
     assert np.abs(V[idx] @ df.delta).max() < 1e-10 * np.linalg.norm(V[idx], axis=1).max() * np.linalg.norm(df.delta)
+
+
+# --------------------------------------------------------------------------- App. D: the Per-token alternative (a stated reading)
+def test_per_token_offsets_average_to_the_methods_delta_and_stay_orthogonal():
+    r = rng(90)
+    N, d, B, k = 260, 32, 12, 3
+    K = r.standard_normal((N, d)); V = r.standard_normal((N, d)) * np.exp(-0.08 * np.arange(d)); A = r.random(N)
+    idx = O.select_topk(A, B)
+    Vm, dm = O.backfill(V, A, idx, k)                                        # the method itself
+    Vp, dp = O.backfill(V, A, idx, k, O.Variant(per_token=True), K)
+    off = Vp - V[idx]
+    # the reading's defining property: the slots' directions average to Eq. 6's single delta, which is also what is reported
+    assert np.allclose(off.mean(axis=0), dm.delta, rtol=0, atol=1e-12 * np.abs(dm.delta).max())
+    assert np.allclose(dp.delta, dm.delta, rtol=0, atol=1e-15) and dp.k_used == dm.k_used and dp.skipped == 0
+    # every slot's direction lies in the residual subspace: orthogonal to every retained value (Eq. 3)
+    assert np.abs(V[idx] @ off.T).max() < 1e-10 * np.linalg.norm(V[idx], axis=1).max() * np.linalg.norm(off, axis=1).max()
+    # a slot that no deleted token is routed to keeps its value exactly
+    route = O.merge_routes(K, idx)
+    empty = sorted(set(range(B)) - set(route[route >= 0].tolist()))
+    for t in empty:
+        assert np.array_equal(Vp[t], V[idx][t])
+    # No Scaling leaves Eq. 6's ratio out of every slot alike
+    Vn, dn = O.backfill(V, A, idx, k, O.Variant(per_token=True, no_scaling=True), K)
+    ratio = dm.a_del / (dm.a_keep + O.EPS)
+    assert np.allclose((Vn - V[idx]) * ratio, off, rtol=1e-12, atol=1e-15)
+
+
+def test_per_token_with_every_deleted_token_on_one_slot_gives_that_slot_everything():
+    r = rng(91)
+    N, d, B, k = 120, 16, 5, 2
+    K = 0.01 * r.standard_normal((N, d)); V = r.standard_normal((N, d)); A = r.random(N) + 0.1
+    idx = np.array([3, 40, 41, 77, 100])
+    # keys: every deleted token points along e_0 like slot 2 (token 41); the other slots point elsewhere
+    K[:, 0] += 1.0
+    for s, t in enumerate(idx):
+        if s != 2:
+            K[t] = 0.0; K[t, 1 + s] = 1.0
+    route = O.merge_routes(K, idx)
+    assert set(route[route >= 0].tolist()) == {2}
+    Vm, dm = O.backfill(V, A, idx, k)
+    Vp, dp = O.backfill(V, A, idx, k, O.Variant(per_token=True), K)
+    off = Vp - V[idx]
+    assert np.allclose(off[2], B * dm.delta, rtol=1e-12, atol=1e-15)         # B times the method's share, so that the mean is delta
+    assert not off[[0, 1, 3, 4]].any()
+    # with a single retained slot the alternative IS the method
+    i1 = np.array([41])
+    V1, d1 = O.backfill(V, A, i1, k)
+    P1, _ = O.backfill(V, A, i1, k, O.Variant(per_token=True), K)
+    assert np.allclose(P1, V1, rtol=1e-13, atol=1e-15)
+
+
+def test_per_token_needs_keys_and_refuses_the_combinations_it_has_no_reading_for():
+    r = rng(92)
+    V = r.standard_normal((50, 8)); A = r.random(50); K = r.standard_normal((50, 8))
+    idx = O.select_topk(A, 4)
+    with pytest.raises(ValueError):
+        O.backfill(V, A, idx, 2, O.Variant(per_token=True))
+    for bad in (O.Variant(per_token=True, attn_inject=True), O.Variant(per_token=True, subspace="all")):
+        with pytest.raises(ValueError):
+            O.backfill(V, A, idx, 2, bad, K)
+    # the fast path's subspace is used when both are asked for
+    Vf, df = O.backfill(V, A, idx, 2, O.Variant(per_token=True, subspace_iters=3), K)
+    Vg, dg = O.backfill(V, A, idx, 2, O.Variant(subspace_iters=3))
+    assert np.allclose((Vf - V[idx]).mean(axis=0), dg.delta, rtol=0, atol=1e-12 * np.abs(dg.delta).max())
