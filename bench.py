@@ -258,6 +258,30 @@ def main() -> int:
                               "value": round(scfg.n_heads * scfg.n_tokens / (rr["elapsed"] / args.steps), 1), "unit": "head-tokens/s",
                               "path": path_s, "roofline": roof_s})
             c["shadow"] = (scfg, sb, holder["o"])
+        # a batch of paper-shape samples through the batch entry point (three samples in flight on streams of the library)
+        nb = 12
+        if not args.layers:
+            trip = [si.make_cache(pc, args.seed + 100 + j, threads=threads) for j in range(nb)]
+            Kb, Vb, Qb = (dev(np.stack([t[j] for t in trip])) for j in range(3))
+            del trip
+            pb_ = int(si.budgets(pc, args.seed).flat[0])
+            bo = {"o": None}
+
+            def bstep():
+                bo["o"] = B.compress_relay_batch(Kb, Vb, Qb, [pc.n_tokens] * nb, budget=pb_, rank=pc.rank, out=bo["o"])
+            for _ in range(max(1, args.warmup)):
+                bstep()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                bstep()
+            torch.cuda.synchronize()
+            bt = (time.perf_counter() - t0) / args.steps
+            full_path.append({"workload": f"batch of {nb} samples of config {pc.name} (N={pc.n_tokens}, budget {pb_}, rank {pc.rank}) in one "
+                                          "call of the batch entry point", "ms_per_step": round(1e3 * bt, 4),
+                              "ms_per_sample": round(1e3 * bt / nb, 4),
+                              "value": round(nb * pc.n_heads * pc.n_tokens / bt, 1), "unit": "head-tokens/s"})
+            del Kb, Vb, Qb
 
     extra = {}
     if gen_rows is not None:

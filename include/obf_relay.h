@@ -272,8 +272,13 @@ obf_status_t obf_append_message(int32_t n_heads, int32_t head_dim, int32_t dtype
  * library's token limit).  n_tokens_host and budgets_host are HOST arrays of n_samples entries (budgets_host nullable:
  * `budget` for every sample); a sample's budget applies to each of its heads and counts eligible tokens; `sink` as in
  * obf_window_t (0 <= sink < every n_tokens_host[s]).  Each sample is compressed exactly as obf_compress_relay_window would
- * compress it alone (the samples are enqueued one after the other on `stream`); the workspace must hold
- * obf_workspace_bytes_batch() bytes.  diag nullable.  Errors as obf_compress_relay; nothing is enqueued on a host-side error. */
+ * compress it alone.  obf_workspace_bytes_batch() returns room for up to three samples in flight (one slot each; with
+ * n_samples = 1 it returns the size of one slot): sample s then runs in lane s mod 3, lane 0 being `stream` and the others
+ * streams of the library's own (forked off `stream` and joined back before the call returns, so that all work is ordered
+ * on `stream` for the caller); a workspace of one or two slots is accepted too and gives that many lanes, and under stream
+ * capture or stage profiling the samples are simply enqueued one after the other on `stream`.  Results do not depend on
+ * the number of lanes.  diag nullable.  Errors as
+ * obf_compress_relay; nothing is enqueued on a host-side error. */
 size_t obf_workspace_bytes_batch(const obf_shape_t* shape, int32_t n_samples, int32_t token_stride, int32_t max_budget, int32_t rank);
 obf_status_t obf_compress_relay_batch(const obf_shape_t* shape, int32_t n_samples, const int32_t* n_tokens_host,
                                       int32_t token_stride, int32_t sink,

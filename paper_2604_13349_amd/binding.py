@@ -315,9 +315,11 @@ def compress_relay(K, V, Qwin, budget: int = 0, rank: int = 0, budgets=None, max
 
 
 def compress_relay_batch(K, V, Qwin, n_tokens, budget: int = 0, budgets=None, rank: int = 0, sink: int = 0,
-                         max_budget: Optional[int] = None, want_diag=False):
+                         max_budget: Optional[int] = None, want_diag=False, out=None, lanes=None):
     """obf_compress_relay_batch: K, V [S,L,H,stride,d] right-padded, Qwin [S,L,H*g,W,d], n_tokens the real length of each
-    sample (host sequence), budgets one per sample.  Returns a dict of device tensors with a leading sample dimension."""
+    sample (host sequence), budgets one per sample.  Returns a dict of device tensors with a leading sample dimension.
+    out: a dict returned by an earlier call of the same shape (its buffers and workspace are reused); lanes: hand over a
+    workspace for that many samples in flight instead of what obf_workspace_bytes_batch() asks for."""
     S, L, H, stride, d = K.shape
     sh = shape_of(K[0], Qwin[0])
     lens = np.ascontiguousarray(np.asarray(n_tokens, dtype=np.int32).reshape(-1))
@@ -326,15 +328,20 @@ def compress_relay_batch(K, V, Qwin, n_tokens, budget: int = 0, budgets=None, ra
         per = keep if keep is not None else np.full(S, budget)
         max_budget = int(max(min(int(b), int(n) - sink) for b, n in zip(per, lens)))
     dev = K.device
-    o = {"K_out": torch.empty((S, L, H, max_budget, d), dtype=K.dtype, device=dev),
-         "V_out": torch.empty((S, L, H, max_budget, d), dtype=K.dtype, device=dev),
-         "idx": torch.empty((S, L, H, max_budget), dtype=torch.int32, device=dev),
-         "n_keep": torch.empty((S, L, H), dtype=torch.int32, device=dev)}
-    if want_diag:
-        o["diag"] = torch.empty((S, L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
     lib = load_library()
-    nbytes = lib.obf_workspace_bytes_batch(C.byref(sh), S, stride, max_budget, rank)
-    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    if out is not None:
+        o, ws = out, out["ws"]
+    else:
+        o = {"K_out": torch.empty((S, L, H, max_budget, d), dtype=K.dtype, device=dev),
+             "V_out": torch.empty((S, L, H, max_budget, d), dtype=K.dtype, device=dev),
+             "idx": torch.empty((S, L, H, max_budget), dtype=torch.int32, device=dev),
+             "n_keep": torch.empty((S, L, H), dtype=torch.int32, device=dev)}
+        if want_diag:
+            o["diag"] = torch.empty((S, L, H, DIAG_DTYPE.itemsize), dtype=torch.uint8, device=dev)
+        nbytes = lib.obf_workspace_bytes_batch(C.byref(sh), S, stride, max_budget, rank)
+        if lanes is not None:
+            nbytes = min(nbytes, int(lanes) * lib.obf_workspace_bytes_batch(C.byref(sh), 1, stride, max_budget, rank))
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
     _check(lib.obf_compress_relay_batch(C.byref(sh), S, lens.ctypes.data_as(C.c_void_p), stride, sink, _ptr(K), _ptr(V), _ptr(Qwin),
                                         bptr, budget, max_budget, rank, _ptr(o["K_out"]), _ptr(o["V_out"]), _ptr(o["idx"]),
                                         _ptr(o["n_keep"]), _ptr(o.get("diag")), _ptr(ws), ws.numel(), _stream()))

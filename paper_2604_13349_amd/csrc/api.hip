@@ -28,7 +28,7 @@ obf_status_t check_launch(const char* what) {
 }
 
 // ---- the library's own streams -------------------------------------------------------------------
-struct StreamPool { hipStream_t s[2]; hipEvent_t ev[EV_COUNT]; int dev; bool ok; };
+struct StreamPool { hipStream_t s[kAuxStreams]; hipEvent_t ev[EV_COUNT]; int dev; bool ok; };
 static thread_local bool g_single_stream = false;
 void set_single_stream(bool on) { g_single_stream = on; }
 
@@ -42,14 +42,14 @@ static StreamPool* stream_pool() {
   StreamPool& p = pools[npools++];
   p.dev = dev;
   p.ok = true;
-  for (int i = 0; i < 2 && p.ok; ++i) p.ok = hipStreamCreateWithFlags(&p.s[i], hipStreamNonBlocking) == hipSuccess;
+  for (int i = 0; i < kAuxStreams && p.ok; ++i) p.ok = hipStreamCreateWithFlags(&p.s[i], hipStreamNonBlocking) == hipSuccess;
   for (int i = 0; i < EV_COUNT && p.ok; ++i) p.ok = hipEventCreateWithFlags(&p.ev[i], hipEventDisableTiming) == hipSuccess;
   if (!p.ok) (void)hipGetLastError();                             // no second stream on this device: not an error of the call
   return p.ok ? &p : nullptr;
 }
 
 hipStream_t aux_stream(int which) {
-  if (g_single_stream || which < 0 || which > 1) return nullptr;
+  if (g_single_stream || which < 0 || which >= kAuxStreams) return nullptr;
   StreamPool* p = stream_pool();
   return p ? p->s[which] : nullptr;
 }
@@ -342,7 +342,8 @@ static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_wi
                                         const int32_t* budgets_host, int32_t budget, int32_t max_budget, int32_t rank,
                                         void* K_out, void* V_out, int32_t* idx, int32_t* n_keep,
                                         float* scores_out, float* delta_out, obf_diag_t* diag,
-                                        void* ws, size_t ws_bytes, void* stream) {
+                                        void* ws, size_t ws_bytes, void* stream,
+                                        bool own_side_stream = true /*false: the call forks nothing (its stream is a side stream itself)*/) {
   OBF_TRY(check_shape(shape));
   OBF_NONNULL(K); OBF_NONNULL(V); OBF_NONNULL(Qwin); OBF_NONNULL(K_out); OBF_NONNULL(V_out);
   OBF_NONNULL(idx); OBF_NONNULL(n_keep);
@@ -363,7 +364,7 @@ static obf_status_t compress_relay_impl(int layerwise, Variant var, const obf_wi
   OBF_TRY(check_ws(mf, w, ws, ws_bytes));
   hipStream_t st = (hipStream_t)stream;
   return compress_heads(layerwise, var, mf, sink, K, V, Qwin, budgets_host, budget, max_budget, rank, K_out, V_out, idx, n_keep,
-                        scores_out, delta_out, diag, (char*)ws, st, st, aux_stream(0));
+                        scores_out, delta_out, diag, (char*)ws, st, st, own_side_stream ? aux_stream(0) : (hipStream_t)nullptr);
 }
 
 obf_status_t obf_compress_relay(const obf_shape_t* shape, const void* K, const void* V, const void* Qwin,
@@ -428,8 +429,10 @@ obf_status_t obf_compress_relay_window(const obf_shape_t* shape, const obf_windo
 }
 
 // ---- a batch of right-padded samples (App. A.7) ---------------------------------------------------
+static size_t batch_align(size_t n) { return (n + 255) & ~(size_t)255; }
+
 static size_t batch_slot_bytes(const obf_shape_t* shape, int32_t token_stride, int32_t max_budget, int32_t rank) {
-  // the samples run one after the other on the caller's stream and share one workspace: the largest any length needs
+  // one workspace slot serves every sample that runs on it: the largest any length needs
   obf_shape_t s = *shape;
   size_t need = 0;
   for (int32_t n = 1; n <= token_stride; ++n) {
@@ -445,7 +448,9 @@ size_t obf_workspace_bytes_batch(const obf_shape_t* shape, int32_t n_samples, in
   obf_shape_t s = *shape;
   s.n_tokens = token_stride;
   if (check_shape(&s) != OBF_OK) return 0;
-  return batch_slot_bytes(shape, token_stride, max_budget, rank);
+  // one slot per sample in flight: the samples take turns on the caller's stream and on the library's own
+  const size_t slot = batch_align(batch_slot_bytes(shape, token_stride, max_budget, rank));
+  return (size_t)(n_samples < kBatchLanes ? n_samples : kBatchLanes) * slot;
 }
 
 obf_status_t obf_compress_relay_batch(const obf_shape_t* shape, int32_t n_samples, const int32_t* n_tokens_host,
@@ -481,17 +486,41 @@ obf_status_t obf_compress_relay_batch(const obf_shape_t* shape, int32_t n_sample
   Dims m0 = make_dims(shape);
   const size_t heads = (size_t)m0.heads, row = (size_t)m0.d * m0.esize;
   const obf_window_t win = {token_stride, sink};
-  for (int32_t i = 0; i < n_samples; ++i) {
+  // Samples share nothing, and a short sample's per-head kernels leave most of the chip idle: with room for several
+  // workspace slots, sample i runs in lane i mod lanes; lane 0 is the caller's stream (with the library's first stream for
+  // the forks inside a sample), every further lane one of the library's other streams, forked off the caller's before the
+  // first sample and joined back after the last, on every way out.  Not under stream capture (the captured graph stays a
+  // chain per sample) and not while stage timing is on.
+  hipStream_t st = (hipStream_t)stream, lane_st[kBatchLanes] = {st};
+  const size_t slot = batch_align(need);
+  int lanes = 1;
+  if (n_samples >= 2 && ws_bytes >= 2 * slot && g_prof_stage < 0) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs == hipStreamCaptureStatusNone) {
+      const size_t fit = ws_bytes / slot;
+      const int want = (int)(fit < (size_t)kBatchLanes ? fit : (size_t)kBatchLanes);
+      while (lanes < want && lanes < n_samples) {
+        hipStream_t s2 = aux_stream(lanes);
+        if (!s2 || stream_after(s2, st, EV_BATCH_FORK) != OBF_OK) break;
+        lane_st[lanes++] = s2;
+      }
+    } else (void)hipGetLastError();
+  }
+  obf_status_t rs = OBF_OK;
+  for (int32_t i = 0; i < n_samples && rs == OBF_OK; ++i) {
     obf_shape_t s = *shape;
     s.n_tokens = n_tokens_host[i];
     const size_t kv_off = (size_t)i * heads * token_stride * row, q_off = (size_t)i * heads * m0.R * row;
     const size_t out_rows = (size_t)i * heads * max_budget;
-    OBF_TRY(compress_relay_impl(0, Variant(), &win, &s, (const char*)K + kv_off, (const char*)V + kv_off, (const char*)Qwin + q_off,
-                                nullptr, budgets_host ? budgets_host[i] : budget, max_budget, rank,
-                                (char*)K_out + out_rows * row, (char*)V_out + out_rows * row, idx + out_rows, n_keep + (size_t)i * heads,
-                                nullptr, nullptr, diag ? diag + (size_t)i * heads : nullptr, ws, ws_bytes, stream));
+    const int lane = lanes > 1 ? i % lanes : 0;
+    rs = compress_relay_impl(0, Variant(), &win, &s, (const char*)K + kv_off, (const char*)V + kv_off, (const char*)Qwin + q_off,
+                             nullptr, budgets_host ? budgets_host[i] : budget, max_budget, rank,
+                             (char*)K_out + out_rows * row, (char*)V_out + out_rows * row, idx + out_rows, n_keep + (size_t)i * heads,
+                             nullptr, nullptr, diag ? diag + (size_t)i * heads : nullptr,
+                             (char*)ws + (size_t)lane * slot, lanes > 1 ? slot : ws_bytes, (void*)lane_st[lane], lane == 0);
   }
-  return OBF_OK;
+  for (int l = 1; l < lanes; ++l) { const obf_status_t js = stream_after(st, lane_st[l], EV_BATCH_JOIN); if (rs == OBF_OK) rs = js; }
+  return rs;
 }
 
 obf_status_t obf_cache_merge(const obf_shape_t* shape, const void* K, const void* V, const float* scores, const int32_t* idx,

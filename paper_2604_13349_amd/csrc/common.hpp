@@ -270,15 +270,18 @@ inline void once_per_device(std::mutex& mu, uint64_t& seen, F set) {
 // idx[i] += offset for every valid (non-negative) entry
 obf_status_t launch_idx_offset(int32_t* idx, size_t n, int32_t offset, hipStream_t st);
 
-// The library's own streams: two per host thread and device, default priority, created on first use and kept.
+// The library's own streams: kAuxStreams per host thread and device, default priority, created on first use and kept.
 // aux_stream returns nullptr when none is available (creation failed, or the thread is in single-stream mode): the
 // launchers then keep everything on the caller's stream.
-hipStream_t aux_stream(int which /*0 or 1*/);
+constexpr int kBatchLanes = 3;                                   // samples of a batch in flight at a time: with lane 0's
+                                                                  // inner fork that makes four streams, one per hardware queue
+constexpr int kAuxStreams = kBatchLanes;                          // the library's own streams per device and thread
+hipStream_t aux_stream(int which /*0 .. kAuxStreams-1*/);
 // While on (per host thread), no stream or event is created or used by the library.
 void set_single_stream(bool on);
 // Makes `waiter` wait for everything queued on `signaller` so far, through event `slot` of the calling thread's pool
 // (an event may be recorded again as soon as its wait has been enqueued).  Legal under stream capture.
-enum EventSlot { EV_SCORED = 0, EV_BASIS_FORK, EV_BASIS_JOIN, EV_KROWS_FORK, EV_KROWS_JOIN, EV_COUNT };
+enum EventSlot { EV_SCORED = 0, EV_BASIS_FORK, EV_BASIS_JOIN, EV_KROWS_FORK, EV_KROWS_JOIN, EV_BATCH_FORK, EV_BATCH_JOIN, EV_COUNT };
 obf_status_t stream_after(hipStream_t waiter, hipStream_t signaller, int slot);
 // Optional early start of the retained-span bases on `aux` (forked from st), for shapes where they do not depend on
 // the gather; *started is then passed on to launch_backfill as basis_started, which joins `aux` back.

@@ -1030,6 +1030,36 @@ def test_batch_of_right_padded_samples_with_mixed_lengths(gpu, sink):
 
 
 # --------------------------------------------------------------------------- stacked int8 / int4 relay codes (App. E, a reading)
+def test_batch_with_two_samples_in_flight_equals_one_at_a_time(gpu):
+    """With room for several workspace slots the samples take turns on the caller's stream and the library's own; the
+    outputs are those of the same batch run one sample after the other (one slot), bit for bit, also when the call is
+    repeated on the same buffers."""
+    import torch
+    from paper_2604_13349_amd import binding as Bd
+    cfg = si.shrink(si.CONFIGS["paper"], n_layers=2)
+    lens = [256, 201, 256, 77, 130]
+    stride = 256
+    S = len(lens)
+    r = np.random.default_rng(11)
+    Ks, Vs, Qs = [], [], []
+    for s_ in range(S):
+        K, V, Q = si.make_cache(cfg, 20 + s_, threads=8)
+        Ks.append(K); Vs.append(V); Qs.append(Q)
+    Kb, Vb, Qb = (gpu.to_dev(np.stack(x), cfg.dtype) for x in (Ks, Vs, Qs))
+    buds = [32, 20, 48, 16, 32]
+    two = Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True)
+    one = Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True, lanes=1)
+    torch.cuda.synchronize()
+    keep = {k: two[k].clone() for k in ("K_out", "V_out", "idx", "n_keep", "diag")}
+    for k in keep:
+        assert torch.equal(two[k], one[k]), k
+    for _ in range(3):
+        Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True, out=two)
+    torch.cuda.synchronize()
+    for k in keep:
+        assert torch.equal(two[k], keep[k]), f"{k} changed on a repeated call"
+
+
 @pytest.mark.parametrize("dtype,d,bits", [("bf16", 128, 8), ("bf16", 128, 4), ("f32", 64, 8), ("bf16", 64, 4)])
 def test_relay_row_codes_are_bit_exact(gpu, dtype, d, bits):
     import torch

@@ -162,5 +162,9 @@ def test_batch_entry_point_checks_every_sample_on_the_host(lib):
     buds = (C.c_int32 * 3)(16, 40, 16)
     assert call(lens, 128, 0, buds, 0, 16, 1 << 30) == 1 and "sample 1" in lib.obf_last_error().decode()
     need = lib.obf_workspace_bytes_batch(C.byref(sh), 3, 128, 40, 2)
-    assert need > 0 and call(lens, 128, 0, buds, 0, 40, need - 1) == 3          # OBF_ERR_WORKSPACE_TOO_SMALL
+    one = lib.obf_workspace_bytes_batch(C.byref(sh), 1, 128, 40, 2)
+    assert one > 0 and one % 256 == 0 and need == 3 * one                       # a slot per sample in flight, three at most
+    assert lib.obf_workspace_bytes_batch(C.byref(sh), 2, 128, 40, 2) == 2 * one
+    assert lib.obf_workspace_bytes_batch(C.byref(sh), 9, 128, 40, 2) == 3 * one
+    assert call(lens, 128, 0, buds, 0, 40, one // 2) == 3                       # OBF_ERR_WORKSPACE_TOO_SMALL
     assert lib.obf_workspace_bytes_batch(C.byref(sh), 3, 40000, 40, 2) == 0
