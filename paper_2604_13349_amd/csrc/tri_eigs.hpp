@@ -1,9 +1,9 @@
 // Leading eigenpairs of a small symmetric matrix, for a workgroup of 512 threads: the direct route for
 // the case "a few leading right singular vectors of the residual" (Sec. 4.4: k = pca_rank is small against the
 // width of the complement), in place of a full Jacobi diagonalisation:
-//   1. Householder tridiagonalisation T = H S H^T (m - 2 reflectors, three barriers each);
+//   1. Householder tridiagonalisation T = H S H^T (m - 2 reflectors, four barriers each);
 //   2. the k largest eigenvalues of the tridiagonal S by multisection on Sturm counts (every thread evaluates one
-//      shift per round; four rounds shrink an eigenvalue's bracket below single-precision resolution);
+//      shift per round; three or four rounds shrink an eigenvalue's bracket below single-precision resolution);
 //   3. their eigenvectors by inverse iteration on S - theta I (tridiagonal elimination with row exchanges, one lane
 //      per eigenvector, three solves from a fixed pseudo-random start), eight at a time;
 //   4. back-transformation through the reflectors (one wave per eigenvector) and a final Gram-Schmidt pass over the
@@ -55,7 +55,8 @@ __device__ __forceinline__ void te_factor(const float* __restrict__ dv, const fl
     const bool swap = fabsf(n0) > fabsf(r0);
     if (swap) { float t; t = r0; r0 = n0; n0 = t; t = r1; r1 = n1; n1 = t; t = r2; r2 = n2; n2 = t; }
     if (r0 == 0.f) r0 = tiny;
-    const float inv = 1.f / r0;
+    float inv = __builtin_amdgcn_rcpf(r0);                      // one Newton step on the hardware reciprocal: the pivots only
+    inv = fmaf(fmaf(-r0, inv, 1.f), inv, inv);                  // steer an iteration that converges whatever their last bit
     const float g = n0 * inv;
     i0[j * KS] = inv; a1[j * KS] = r1; a2[j * KS] = r2; mu[j * KS] = g; sw[j * KS] = swap ? 1.f : 0.f;
     r0 = fmaf(-g, r1, n1); r1 = fmaf(-g, r2, n2); r2 = 0.f;
@@ -95,23 +96,6 @@ __device__ __forceinline__ float te_backward(const float* __restrict__ f, const 
     big = fmaxf(big, fabsf(v));
   }
   return big;
-}
-
-// in / ||in||_2 -> out (scaled by the largest magnitude first, so that the squares cannot overflow)
-template <int KS>
-__device__ __forceinline__ void te_normalise(const int m, const float* __restrict__ in, float* __restrict__ out,
-                                             const float big, const bool flush) {
-  const float sc = (big > 0.f && big < INFINITY) ? 1.f / big : 1.f;
-  float nn = 0.f;
-#pragma unroll 4
-  for (int j = 0; j < m; ++j) { const float v = in[j * KS] * sc; nn = fmaf(v, v, nn); }
-  const float rn = (nn > 0.f) ? sc * rsqrtf(nn) : 0.f;
-#pragma unroll 4
-  for (int j = 0; j < m; ++j) {
-    float v = in[j * KS] * rn;
-    if (flush && fabsf(v) < 1e-12f) v = 0.f;
-    out[j * KS] = v;
-  }
 }
 
 // Tsrc: the m x m symmetric matrix (row stride ls; global or LDS, read once).  Rf: LDS, m rows of stride lt (odd), receives
@@ -254,19 +238,30 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
     }
   }
   __syncthreads();
-  if (tid < m) e2[tid] = (tid + 1 < m) ? ev[tid] * ev[tid] : 0.f;
-  if (tid == 0) {
+  if (wave == 0) {
+    // Gershgorin interval of S and its largest squared sub-diagonal entry: lane l looks at rows l and l + 64
     float lo = INFINITY, hi = -INFINITY, me2 = 0.f;
-    for (int i = 0; i < m; ++i) {
-      const float r = ((i > 0) ? fabsf(ev[i - 1]) : 0.f) + ((i + 1 < m) ? fabsf(ev[i]) : 0.f);
-      lo = fminf(lo, dv[i] - r); hi = fmaxf(hi, dv[i] + r);
-      if (i + 1 < m) me2 = fmaxf(me2, ev[i] * ev[i]);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int i = lane + 64 * h;
+      if (i < m) {
+        const float below = (i + 1 < m) ? ev[i] : 0.f, above = (i > 0) ? ev[i - 1] : 0.f;
+        const float r = fabsf(above) + fabsf(below);
+        lo = fminf(lo, dv[i] - r); hi = fmaxf(hi, dv[i] + r);
+        me2 = fmaxf(me2, below * below);
+        e2[i] = below * below;
+      }
     }
-    const float span = hi - lo;
-    scal[0] = lo - (1e-3f * span + 1e-30f);
-    scal[1] = hi + (1e-3f * span + 1e-30f);
-    scal[2] = 1e-30f * fmaxf(1.f, me2);                        // smallest pivot magnitude of the Sturm recurrence
-    scal[3] = 1.2e-7f * fmaxf(fabsf(lo), fabsf(hi));           // pivot perturbation of the inverse iteration
+    for (int off = 32; off > 0; off >>= 1) {
+      lo = fminf(lo, __shfl_xor(lo, off)); hi = fmaxf(hi, __shfl_xor(hi, off)); me2 = fmaxf(me2, __shfl_xor(me2, off));
+    }
+    if (lane == 0) {
+      const float span = hi - lo;
+      scal[0] = lo - (1e-3f * span + 1e-30f);
+      scal[1] = hi + (1e-3f * span + 1e-30f);
+      scal[2] = 1e-30f * fmaxf(1.f, me2);                        // smallest pivot magnitude of the Sturm recurrence
+      scal[3] = 1.2e-7f * fmaxf(fabsf(lo), fabsf(hi));           // pivot perturbation of the inverse iteration
+    }
   }
   __syncthreads();
 
@@ -302,8 +297,9 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
     while (kp < kb) kp <<= 1;
     const int S = TE_THREADS / kp;                             // shifts per eigenvalue and round (a multiple of 64)
     const int g = tid / S, s = tid - g * S;
-    // round one left a bracket of 1/513 of the spectrum's extent; each further round divides it by S + 1
-    const int rounds = (S >= TE_THREADS) ? 2 : 3;
+    // round one left a bracket of 1/513 of the spectrum's extent; each further round divides it by S + 1: two rounds of
+    // 257 reach 3e-8 of the extent, half a unit in the last place of the largest eigenvalue
+    const int rounds = (2 * S >= TE_THREADS) ? 2 : 3;
     for (int round = 0; round < rounds; ++round) {
       bool below = false;
       float a = 0.f, b = 0.f;
@@ -348,23 +344,36 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
         te_forward<KS>(lu + lane, m, za, zb, (big > 0.f && big < INFINITY) ? 1.f / big : 1.f);
         big = te_backward<KS>(lu + lane, m, zb, za);
       }
-      // unit length; this pass also clears what is left of the start vector in blocks that S decouples from this
-      // eigenvalue (an exactly zero sub-diagonal entry): some twenty orders of magnitude down, exact zeros in exact arithmetic
-      te_normalise<KS>(m, za, zb, big, true);
-      { float* t = za; za = zb; zb = t; }
-      if (za != zz + lane) for (int j = 0; j < m; ++j) zz[j * KS + lane] = za[j * KS];
+      scal[8 + lane] = big;                                    // the waves of the back-transformation bring it to unit length
     }
     __syncthreads();
     float w0 = 0.f, w1 = 0.f;
     if (wave < kb) {
       w0 = (lane < m) ? zz[lane * KS + wave] : 0.f;
       w1 = (lane + 64 < m) ? zz[(lane + 64) * KS + wave] : 0.f;
+      {
+        // unit length (scaled by the largest magnitude first, so that the squares cannot overflow); this also clears what
+        // is left of the start vector in blocks that S decouples from this eigenvalue (an exactly zero sub-diagonal
+        // entry): some twenty orders of magnitude down, exact zeros in exact arithmetic
+        const float big = scal[8 + wave];
+        const float sc = (big > 0.f && big < INFINITY) ? 1.f / big : 1.f;
+        w0 *= sc; w1 *= sc;
+        const float nn = te_wave_sum(fmaf(w0, w0, w1 * w1));
+        const float rn = (nn > 0.f) ? rsqrtf(nn) : 0.f;
+        w0 *= rn; w1 *= rn;
+        if (fabsf(w0) < 1e-12f) w0 = 0.f;
+        if (fabsf(w1) < 1e-12f) w1 = 0.f;
+      }
+      // reflector j - 1 is fetched while reflector j is applied (the chain through w is all that is sequential)
+      const float* r0p = Rf + min(lane, m - 1) * lt;
+      const float* r1p = Rf + min(lane + 64, m - 1) * lt;
+      float nb = (m >= 3) ? bet[m - 3] : 0.f, n0 = (m >= 3) ? r0p[m - 3] : 0.f, n1 = (m >= 3) ? r1p[m - 3] : 0.f;
       for (int j = m - 3; j >= 0; --j) {
-        const float beta = bet[j];
-        if (beta == 0.f) continue;
-        const float v0 = (lane > j && lane < m) ? Rf[lane * lt + j] : 0.f;
-        const float v1 = (lane + 64 > j && lane + 64 < m) ? Rf[(lane + 64) * lt + j] : 0.f;
-        const float s = beta * te_wave_sum(fmaf(v0, w0, v1 * w1));
+        const float beta = nb;
+        const float v0 = (lane > j && lane < m) ? n0 : 0.f;
+        const float v1 = (lane + 64 > j && lane + 64 < m) ? n1 : 0.f;
+        if (j > 0) { nb = bet[j - 1]; n0 = r0p[j - 1]; n1 = r1p[j - 1]; }
+        const float s = beta * te_wave_sum(fmaf(v0, w0, v1 * w1));   // beta = 0: an identity reflector
         w0 = fmaf(-s, v0, w0); w1 = fmaf(-s, v1, w1);
       }
     }
