@@ -697,8 +697,8 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
   __shared__ float fred[FN_WAVES];
   __shared__ int s_k;
   __shared__ float s_off;
-  __shared__ __attribute__((aligned(16))) float xcol[128];
-  __shared__ uint32_t wkey[2][2];
+  __shared__ __attribute__((aligned(16))) float xcol[128], xcol2[128];
+  __shared__ uint32_t wkey[2][4];
   HeadState st = state[head];
   int skipped = 1;
   float rcr = 0.f, ivn = 0.f, pcr = 0.f, pc = 0.f, revr = 0.f;
@@ -808,51 +808,98 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     __syncthreads();
 
     // Diagonally pivoted Cholesky of P, right-looking on the register tiles: a projector of rank m factors as
-    // P = Z^T Z with the m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  Step s takes
-    // the column with the largest remaining diagonal, scales it into row s of Z (LDS) and deflates P by it.
+    // P = Z^T Z with the m rows of Z orthonormal, i.e. Z is an orthonormal basis of the complement.  A step takes the
+    // two columns with the largest remaining diagonals, factors their 2 x 2 block, scales the pair into two rows of Z
+    // (LDS) and deflates P by both (one pair of barriers for two rows); when the second column loses most of its
+    // diagonal to the first, the step takes the first alone and the choice is made again.
     float dg = (tid < d) ? xcol[tid] : -1.f;
     bool used = false;
-    auto publish = [&](int buf) {                              // wave maxima of (remaining diagonal, lowest index first)
+    auto publish = [&](int buf) {                              // per wave: its two largest (remaining diagonal, lowest index first)
       if (tid < 128) {
-        uint32_t key = (!used && dg > 0.f) ? ((__float_as_uint(dg) & ~0x7Fu) | (uint32_t)(127 - tid)) : 0u;
-        key = wave_max_u32(key);
-        if (lane == 0) wkey[buf][tid >> 6] = key;
+        const uint32_t key = (!used && dg > 0.f) ? ((__float_as_uint(dg) & ~0x7Fu) | (uint32_t)(127 - tid)) : 0u;
+        const uint32_t k1 = wave_max_u32(key);
+        const uint32_t k2 = wave_max_u32(key == k1 ? 0u : key);  // non-zero keys are distinct: they carry the index
+        if (lane == 0) { wkey[buf][2 * (tid >> 6)] = k1; wkey[buf][2 * (tid >> 6) + 1] = k2; }
       }
     };
     __syncthreads();
     publish(0);
     __syncthreads();
-    for (int s = 0; s < m; ++s) {
-      const uint32_t key = max(wkey[s & 1][0], wkey[s & 1][1]);
-      if (key == 0u) { m = s; break; }
-      const int j = 127 - (int)(key & 0x7Fu);
-      if (ptile && cb == (j >> 5) && l31 == (j & 31)) {         // column j of P sits in these lanes
+    {
+      int s = 0, buf = 0;
+      while (s < m) {
+        const uint32_t a1 = wkey[buf][0], a2 = wkey[buf][1], b1 = wkey[buf][2], b2 = wkey[buf][3];
+        const uint32_t key1 = max(a1, b1);
+        uint32_t key2 = (a1 > b1) ? max(a2, b1) : max(a1, b2);
+        if (key1 == 0u) { m = s; break; }
+        if (s + 1 >= m) key2 = 0u;                                // one row left to find
+        const int j1 = 127 - (int)(key1 & 0x7Fu), j2 = key2 ? 127 - (int)(key2 & 0x7Fu) : -1;
+        if (ptile && cb == (j1 >> 5) && l31 == (j1 & 31)) {       // column j1 of P sits in these lanes
 #pragma unroll
-        for (int i = 0; i < 16; ++i) xcol[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
-      }
-      lds_barrier();
-      const float xjj = xcol[j];
-      if (!(xjj > 1e-5f)) { m = s; break; }                      // cannot happen for an exact projector of rank m
-      const float inv = rsqrtf(xjj);
-      if (ptile) {
-        const float lc = xcol[cb * 32 + l31] * inv;
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const float4 lr = *(const float4*)&xcol[rb * 32 + i4 * 8 + lh * 4];
-          acc[4 * i4 + 0] = fmaf(-lr.x * inv, lc, acc[4 * i4 + 0]);
-          acc[4 * i4 + 1] = fmaf(-lr.y * inv, lc, acc[4 * i4 + 1]);
-          acc[4 * i4 + 2] = fmaf(-lr.z * inv, lc, acc[4 * i4 + 2]);
-          acc[4 * i4 + 3] = fmaf(-lr.w * inv, lc, acc[4 * i4 + 3]);
+          for (int i = 0; i < 16; ++i) xcol[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
         }
+        if (j2 >= 0 && ptile && cb == (j2 >> 5) && l31 == (j2 & 31)) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) xcol2[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
+        }
+        lds_barrier();
+        const float p11 = xcol[j1];
+        if (!(p11 > 1e-5f)) { m = s; break; }                     // cannot happen for an exact projector of rank m
+        const float i1 = rsqrtf(p11);
+        float l21 = 0.f, i2 = 0.f;
+        bool two = false;
+        if (j2 >= 0) {
+          const float p22 = xcol2[j2];
+          l21 = xcol[j2] * i1;
+          const float sc = fmaf(-l21, l21, p22);                  // what the first column leaves of the second diagonal
+          two = sc > 1e-5f && sc > 0.25f * p22;
+          if (two) i2 = rsqrtf(sc);
+        }
+        if (ptile) {
+          // z1 = x1 i1 and z2 = (x2 - g x1) i2 with g = l21 i1: the deflation z1 z1^T + z2 z2^T of this tile, written
+          // on the raw columns so that an entry costs two multiply-adds: x1_r e1_c + x2_r e2_c
+          const float x1c = xcol[cb * 32 + l31];
+          if (two) {                                              // uniform
+            const float g = l21 * i1;
+            const float e2 = -(i2 * i2) * fmaf(-g, x1c, xcol2[cb * 32 + l31]);
+            const float e1 = fmaf(-(i1 * i1), x1c, -g * e2);
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const float4 x1 = *(const float4*)&xcol[rb * 32 + i4 * 8 + lh * 4];
+              const float4 x2 = *(const float4*)&xcol2[rb * 32 + i4 * 8 + lh * 4];
+              acc[4 * i4 + 0] = fmaf(x1.x, e1, fmaf(x2.x, e2, acc[4 * i4 + 0]));
+              acc[4 * i4 + 1] = fmaf(x1.y, e1, fmaf(x2.y, e2, acc[4 * i4 + 1]));
+              acc[4 * i4 + 2] = fmaf(x1.z, e1, fmaf(x2.z, e2, acc[4 * i4 + 2]));
+              acc[4 * i4 + 3] = fmaf(x1.w, e1, fmaf(x2.w, e2, acc[4 * i4 + 3]));
+            }
+          } else {
+            const float e1 = -(i1 * i1) * x1c;
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const float4 x1 = *(const float4*)&xcol[rb * 32 + i4 * 8 + lh * 4];
+              acc[4 * i4 + 0] = fmaf(x1.x, e1, acc[4 * i4 + 0]);
+              acc[4 * i4 + 1] = fmaf(x1.y, e1, acc[4 * i4 + 1]);
+              acc[4 * i4 + 2] = fmaf(x1.z, e1, acc[4 * i4 + 2]);
+              acc[4 * i4 + 3] = fmaf(x1.w, e1, acc[4 * i4 + 3]);
+            }
+          }
+        }
+        if (tid < d) {
+          const float z1 = used ? 0.f : xcol[tid] * i1;           // rows already taken are zero in exact arithmetic
+          U[s * ld + tid] = z1;                                   // row s of Z
+          float z2 = 0.f;
+          if (two) {
+            z2 = (used || tid == j1) ? 0.f : (xcol2[tid] - l21 * z1) * i2;
+            U[(s + 1) * ld + tid] = z2;
+          }
+          if (tid == j1 || (two && tid == j2)) used = true;
+          if (!used) dg -= fmaf(z1, z1, z2 * z2);
+        }
+        s += two ? 2 : 1;
+        buf ^= 1;
+        publish(buf);
+        lds_barrier();
       }
-      if (tid < d) {
-        const float l = used ? 0.f : xcol[tid] * inv;            // rows already taken are zero in exact arithmetic
-        U[s * ld + tid] = l;                                     // row s of Z
-        if (tid == j) used = true;
-        if (!used) dg -= l * l;
-      }
-      publish((s + 1) & 1);
-      lds_barrier();
     }
     __syncthreads();
 
