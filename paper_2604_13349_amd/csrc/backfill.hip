@@ -986,7 +986,12 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
       U[a * lt + b] = (a == b) ? 1.f : 0.f;
     }
     __syncthreads();
-    if (tid == 0) { double tr = 0.0; for (int a = 0; a < m; ++a) tr += (double)M[a * lt + a]; s_off = (float)tr; }
+    if (wave == 0) {                                             // trace(T) = ||R||_F^2, summed in double
+      double tr = (lane < m) ? (double)M[lane * lt + lane] : 0.0;
+      if (lane + 64 < m) tr += (double)M[(lane + 64) * lt + lane + 64];
+      for (int o = 32; o > 0; o >>= 1) tr += __shfl_xor(tr, o);
+      if (lane == 0) s_off = (float)tr;
+    }
     __syncthreads();
     const float res2 = s_off;
     rcr = res2 / (vd2 + 1e-12f);
@@ -1348,11 +1353,20 @@ __global__ __launch_bounds__(TE_THREADS, 4) void k_bf_lead(int d, int rank, Head
   const int kq = min(rank, m);
   if (tid < d) uvec[tid] = delta[(size_t)head * d + tid];      // u
   __syncthreads();
-  for (int t = wave; t < m; t += TE_WAVES) {                   // y = Z u (Eq. 4 in complement coordinates), a wave per row
-    float sy = (lane < d) ? Zg[(size_t)t * d + lane] * uvec[lane] : 0.f;
-    if (lane + 64 < d) sy = fmaf(Zg[(size_t)t * d + lane + 64], uvec[lane + 64], sy);
-    sy = te_wave_sum(sy);
-    if (lane == 0) rbar[t] = sy;
+  for (int t0 = wave; t0 < m; t0 += 4 * TE_WAVES) {            // y = Z u (Eq. 4 in complement coordinates), a wave per row,
+    float z0[4], z1[4];                                        // four rows' loads in flight
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int t = min(t0 + q * TE_WAVES, m - 1);
+      z0[q] = (lane < d) ? Zg[(size_t)t * d + lane] : 0.f;
+      z1[q] = (lane + 64 < d) ? Zg[(size_t)t * d + lane + 64] : 0.f;
+    }
+    const float u0 = (lane < d) ? uvec[lane] : 0.f, u1 = (lane + 64 < d) ? uvec[lane + 64] : 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float sy = te_wave_sum(fmaf(z1[q], u1, z0[q] * u0));
+      if (lane == 0 && t0 + q * TE_WAVES < m) rbar[t0 + q * TE_WAVES] = sy;
+    }
   }
   // Delta in complement coordinates (times a_del + eps) from kk orthonormal rows Cb [kk][m]: Eq. 5
   auto project = [&](const float* Cb, const int kk) {

@@ -139,7 +139,8 @@ __device__ __forceinline__ void tri_top_eigs(const float* __restrict__ Tsrc, con
   float* xcol = e2;                                            // the published column (e2 is free until the form is complete)
   float tr[TE_CPT];
 #pragma unroll
-  for (int c = 0; c < TE_CPT; ++c) tr[c] = (ra < m && rg + 4 * c < m) ? Tsrc[(size_t)ra * ls + rg + 4 * c] : 0.f;
+  for (int c = 0; c < TE_CPT; ++c)                              // symmetric: entry (ra, col) is read as (col, ra), lanes along a row
+    tr[c] = (ra < m && rg + 4 * c < m) ? Tsrc[(size_t)(rg + 4 * c) * ls + ra] : 0.f;
   if (tid < 128) { vv[tid] = 0.f; pv[tid] = 0.f; }
   if (rg == 0 && ra < m) xcol[ra] = tr[0];                     // column 0
   if (tid == 0) dv[0] = tr[0];

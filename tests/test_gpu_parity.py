@@ -787,6 +787,25 @@ def test_residual_rank_below_requested_rank(gpu, support, rank, k_want):
         assert all(r.skipped == 1 for r in reps)
 
 
+def test_complement_projector_with_coinciding_columns(gpu):
+    """Every seventh token carries a multiple of e_0 - e_1 as its value row and no other row touches those two
+    coordinates: e_0 - e_1 lies in the retained span, e_0 + e_1 in its complement, so columns 0 and 1 of the projector
+    onto the complement coincide and carry its largest diagonal entries (1/2 against about (d - r)/d).  A factorisation
+    that takes the two leading columns in one step meets them as a pair, and the first leaves nothing of the second."""
+    cfg = si.RelayConfig("twin-cols", 23, 1, 4, 2, 64, 600, 8, 58, 2, "f32", "structured")
+
+    def edit(K, V, Q):
+        twin = np.arange(V.shape[2]) % 7 == 3
+        amp = V[..., twin, 0].copy()
+        V[..., twin, :] = 0
+        V[..., twin, 0] = amp
+        V[..., twin, 1] = -amp
+        V[..., ~twin, 0:2] = 0
+
+    reps = _check_cfg(gpu, cfg, edit=edit, expect_active=True)
+    assert all(r.v_checked for r in reps)
+
+
 @pytest.mark.parametrize("dtype,d,rank", [("bf16", 128, 4), ("f32", 64, 2), ("bf16", 128, 8), ("bf16", 128, 12)])
 def test_fast_path_is_close_to_the_svd_on_a_steep_residual_spectrum(gpu, dtype, d, rank):
     """App. H quotes a relative error near 1e-4 for three steps: that needs a gap behind the k-th singular value of R.
