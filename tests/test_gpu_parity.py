@@ -1077,6 +1077,19 @@ def test_batch_with_two_samples_in_flight_equals_one_at_a_time(gpu):
     torch.cuda.synchronize()
     for k in keep:
         assert torch.equal(two[k], keep[k]), f"{k} changed on a repeated call"
+    # under stream capture the samples are enqueued one after the other on the capturing stream: same bits on every replay
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True, out=two)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for k in keep:
+            two[k].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in keep:
+            assert torch.equal(two[k], keep[k]), f"graph replay {rep}: {k} differs from the eager call"
 
 
 @pytest.mark.parametrize("dtype,d,bits", [("bf16", 128, 8), ("bf16", 128, 4), ("f32", 64, 8), ("bf16", 64, 4)])
