@@ -1068,10 +1068,12 @@ def test_batch_with_two_samples_in_flight_equals_one_at_a_time(gpu):
     buds = [32, 20, 48, 16, 32]
     two = Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True)
     one = Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True, lanes=1)
+    pair = Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True, lanes=2)
     torch.cuda.synchronize()
     keep = {k: two[k].clone() for k in ("K_out", "V_out", "idx", "n_keep", "diag")}
     for k in keep:
         assert torch.equal(two[k], one[k]), k
+        assert torch.equal(pair[k], one[k]), f"{k} with a workspace of two slots"
     for _ in range(3):
         Bd.compress_relay_batch(Kb, Vb, Qb, lens, budgets=buds, rank=2, want_diag=True, out=two)
     torch.cuda.synchronize()
