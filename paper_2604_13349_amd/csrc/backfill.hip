@@ -778,7 +778,10 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     const int lane = tid & 63, l31 = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int TD = d >> 5;
-    const bool ptile = wave < TD * TD;
+    // P is symmetric: only the tiles on and below the diagonal are formed and deflated (10 of 16 at d = 128; the waves
+    // of the others stay out of the way), and a column's entries above the diagonal block are read off as the row of
+    // the mirrored tile
+    const bool ptile = wave < TD * TD && wave / TD >= wave % TD;
     const int rb = wave / TD, cb = wave % TD;
     f32x16 acc;
 #pragma unroll
@@ -825,6 +828,28 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     __syncthreads();
     publish(0);
     __syncthreads();
+    // column j of P to LDS: the tiles of block column j / 32 hold its entries from the diagonal block down in the lanes
+    // of that column; the tiles of block row j / 32 left of the diagonal hold the others as row j (one register of the
+    // half-wave that owns the row, the same register in every such tile: a jump, not a chain of selects)
+    auto put_column = [&](const int j, float* dst) {
+      if (!ptile) return;
+      const int J = j >> 5, jr = j & 31;
+      if (cb == J && l31 == jr) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dst[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
+      }
+      if (rb == J && cb < J && lh == ((jr >> 2) & 1)) {
+        float v = 0.f;
+        switch ((jr >> 3) * 4 + (jr & 3)) {
+#define OBF_FN_CASE(q) case q: v = acc[q]; break;
+          OBF_FN_CASE(0) OBF_FN_CASE(1) OBF_FN_CASE(2) OBF_FN_CASE(3) OBF_FN_CASE(4) OBF_FN_CASE(5) OBF_FN_CASE(6) OBF_FN_CASE(7)
+          OBF_FN_CASE(8) OBF_FN_CASE(9) OBF_FN_CASE(10) OBF_FN_CASE(11) OBF_FN_CASE(12) OBF_FN_CASE(13) OBF_FN_CASE(14) OBF_FN_CASE(15)
+#undef OBF_FN_CASE
+          default: break;
+        }
+        dst[cb * 32 + l31] = v;
+      }
+    };
     {
       int s = 0, buf = 0;
       while (s < m) {
@@ -834,14 +859,8 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
         if (key1 == 0u) { m = s; break; }
         if (s + 1 >= m) key2 = 0u;                                // one row left to find
         const int j1 = 127 - (int)(key1 & 0x7Fu), j2 = key2 ? 127 - (int)(key2 & 0x7Fu) : -1;
-        if (ptile && cb == (j1 >> 5) && l31 == (j1 & 31)) {       // column j1 of P sits in these lanes
-#pragma unroll
-          for (int i = 0; i < 16; ++i) xcol[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
-        }
-        if (j2 >= 0 && ptile && cb == (j2 >> 5) && l31 == (j2 & 31)) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) xcol2[rb * 32 + (i >> 2) * 8 + lh * 4 + (i & 3)] = acc[i];
-        }
+        put_column(j1, xcol);
+        if (j2 >= 0) put_column(j2, xcol2);
         lds_barrier();
         const float p11 = xcol[j1];
         if (!(p11 > 1e-5f)) { m = s; break; }                     // cannot happen for an exact projector of rank m
