@@ -969,8 +969,8 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     f32x16 ta;
 #pragma unroll
     for (int i = 0; i < 16; ++i) ta[i] = 0.f;
-    const bool ttile = wave < MB * MB;
     const int sblk = wave / max(MB, 1), tblk2 = wave % max(MB, 1);
+    const bool ttile = wave < MB * MB && sblk >= tblk2;          // T is symmetric: the tiles on and below the diagonal
     if (ttile) {
       const int srow = sblk * 32 + l31;
       const float* za = U + min(srow, m - 1) * ld;
@@ -1001,7 +1001,7 @@ __global__ __launch_bounds__(FN_THREADS, 8) void k_bf_finalize(int N, int d, int
     // symmetrise, W = I, trace
     for (int e = tid; e < mm * mm; e += FN_THREADS) {
       const int a = e / mm, b = e - a * mm;
-      if (a < b) { const float v = 0.5f * (M[a * lt + b] + M[b * lt + a]); M[a * lt + b] = v; M[b * lt + a] = v; }
+      if (a < b) M[a * lt + b] = M[b * lt + a];                  // the upper triangle mirrors the computed lower one
       U[a * lt + b] = (a == b) ? 1.f : 0.f;
     }
     __syncthreads();
