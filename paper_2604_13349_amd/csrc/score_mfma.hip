@@ -29,6 +29,7 @@ constexpr int SM_D = 128;
 constexpr int SM_KK = SM_D / 16;         // MFMA k-steps
 constexpr int SM_TILE = 32;              // tokens per MFMA tile
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kScoreOneLaunchTokens = 768;   // prompts up to this length take both score passes in one launch (a tie with two launches near 1024)
 
 union Frag { uint4 u; bf16x8 v; };
 
@@ -379,6 +380,88 @@ __global__ __launch_bounds__(SM_THREADS, 1) void k_score_mass_mfma(const uint16_
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Both passes in one launch, for short prompts (a head's tiles are few and one row group covers the query rows): one
+// workgroup per head keeps Q in registers, takes the row maxima and sums over the head's tokens, forms the row
+// log-sum-exp in LDS and walks the same tokens again, backwards, for the masses.  Same arithmetic, in the same order, as
+// the two launches make of a head that lies inside one range.
+template <int RB, int KBUF>
+__global__ __launch_bounds__(SM_THREADS, 1) void k_score_head_mfma(const uint16_t* __restrict__ K,
+                                                                   const uint16_t* __restrict__ Q,
+                                                                   double* __restrict__ row_lse, float* __restrict__ out,
+                                                                   int N, int R, long kstride) {
+  __shared__ double s_m[SM_WAVES][(RB * 32)], s_l[SM_WAVES][(RB * 32)];
+  __shared__ double s_lse[(RB * 32)];
+  const int head = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float a2 = kLog2e / sqrtf((float)SM_D);
+  constexpr int STEP = SM_WAVES * SM_TILE;
+  const uint16_t* Kh = K + (size_t)head * kstride;
+  const uint16_t* Qh = Q + (size_t)head * R * SM_D;
+  float* dst = out + (size_t)head * N;
+  const int first = wave * SM_TILE;
+
+  Frag qf[RB][SM_KK];
+  load_q(qf, Qh, 0, R, lane);
+  {
+    float m[RB];
+    double l[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0; }
+    const int nfull = (N - first >= SM_TILE) ? ((N - first - SM_TILE) / STEP + 1) : 0;
+    StatsEp<RB> ep{m, l, a2};
+    run_tiles<true, RB, KBUF>(Kh, first, STEP, nfull, N, lane, qf, ep);
+    {
+      const int tok = first + nfull * STEP;          // a ragged last tile, if any
+      if (tok < N) {
+        Frag kr[SM_KK];
+        load_k(kr, Kh, tok, N, lane);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          f32x16 accr;
+          block_mfma<true>(accr, kr, qf[rb]);
+          stats_block_ragged(accr, m[rb], l[rb], a2, tok, N, lane);
+        }
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {                // the two lane halves, then (below) the four waves
+      const float mo = __shfl_xor(m[rb], 32);
+      const double lo = __shfl_xor(l[rb], 32);
+      const float mn = fmaxf(m[rb], mo);
+      double a = 0.0, b = 0.0;
+      if (m[rb] > -INFINITY) a = l[rb] * (double)fast_exp2((m[rb] - mn) * a2);
+      if (mo > -INFINITY) b = lo * (double)fast_exp2((mo - mn) * a2);
+      if (lane < 32) { s_m[wave][rb * 32 + lane] = (double)mn * (double)a2; s_l[wave][rb * 32 + lane] = a + b; }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < (RB * 32)) {
+    const int row = threadIdx.x;
+    double lse = INFINITY;                                     // padded rows: exp2(-inf) = 0
+    if (row < R) {
+      double M = -INFINITY;
+      for (int w = 0; w < SM_WAVES; ++w) M = fmax(M, s_m[w][row]);
+      double L = 0.0;
+      for (int w = 0; w < SM_WAVES; ++w)
+        if (s_m[w][row] > -INFINITY) L += s_l[w][row] * exp2(s_m[w][row] - M);
+      lse = M * 0.6931471805599453 + log(L);                   // log2 units -> natural log
+      row_lse[(size_t)head * R + row] = lse;
+    }
+    s_lse[row] = lse;
+  }
+  __syncthreads();
+  float b2[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      b2[rb][i] = (float)(s_lse[rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3)] * 1.4426950408889634);
+  const int nt = (first < N) ? ((N - first - 1) / STEP + 1) : 0;          // tiles of this wave, the last may be ragged
+  MassEp<RB> ep{b2, a2, dst, N, lane, 0.f, 0.f, 0.f, 0.f};
+  run_tiles<false, RB, KBUF>(Kh, first + (nt - 1) * STEP, -STEP, nt, N, lane, qf, ep);
+}
+
 // scores = sum of the row groups' partial column sums (fixed order)
 __global__ void k_score_sum_groups(const float* __restrict__ part, float* __restrict__ scores, size_t n, int RG,
                                    size_t rg_stride) {
@@ -404,6 +487,12 @@ obf_status_t launch_score_mfma(const Dims& m, const Workspace& w, char* ws, cons
   pt.kstride = (long)m.kvs * SM_D;
   dim3 grid(((w.nranges + 7) / 8) * 8 * RG);
   const bool five = score_rows_per_group(m.R) == 160;     // five row blocks per workgroup, two K buffers (e.g. 320 rows = 2 x 160)
+  if (RG == 1 && !five && m.N <= kScoreOneLaunchTokens) {  // short prompts: both passes in one launch, a workgroup per head
+    ProfScope prof_(ST_SCORE_STATS, st);
+    hipLaunchKernelGGL((k_score_head_mfma<4, 3>), dim3(m.heads), dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,
+                       row_lse, scores, m.N, m.R, pt.kstride);
+    return check_launch("score, one launch per call (mfma)");
+  }
   { ProfScope prof_(ST_SCORE_STATS, st);
     if (five)
       hipLaunchKernelGGL((k_score_stats_mfma<5, 2>), grid, dim3(SM_THREADS), 0, st, (const uint16_t*)K, (const uint16_t*)Q,

@@ -122,6 +122,10 @@ def test_wide_complement_few_leading_directions(gpu, seed, rank, budget):
     (1, 64, "f32", 1, 1, 1, 2),             # a single token
     (513, 128, "bf16", 2, 16, 20, 40),      # rank above the complement's dimension is capped
     (4099, 128, "bf16", 4, 32, 130, 4),     # budget just above head_dim
+    (31, 128, "bf16", 4, 32, 8, 2),         # less than one 32-token tile: three of the four score waves have nothing to do
+    (97, 128, "bf16", 4, 32, 20, 2),        # one-launch score kernel, ragged fourth tile
+    (768, 128, "bf16", 4, 32, 50, 2),       # the longest prompt of the one-launch score kernel
+    (769, 128, "bf16", 4, 32, 50, 2),       # the shortest of the two-launch one
 ])
 def test_ragged_shapes(gpu, N, d, dtype, g, W, B, rank):
     cfg = si.RelayConfig("ragged", 7, 1, 2, g, d, N, W, B, rank, dtype, "structured", outlier_frac=0.01)
