@@ -151,7 +151,7 @@ def main() -> int:
     stages = B.profile_stages()
 
     def measure(step_fn, steps, warmup):
-        """Warm-up, a one-step-per-stage survey (HIP events inside the library, on the launch stream), then `steps` timed
+        """Warm-up, one step per stage with that stage's timing on (HIP events inside the library, on the launch stream), then `steps` timed
         steps: one wall-clock interval around all of them (the headline) and one HIP-event pair per step (the spread)."""
         for _ in range(max(1, warmup)):
             step_fn()
